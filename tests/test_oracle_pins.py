@@ -1,0 +1,398 @@
+"""Pins for the CPU oracle: values the paper prints, closed forms, invariants,
+textbook special cases and brute force on tiny inputs.  No GPU involved."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import lightkv_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_values.txt")
+
+
+def _golden():
+    out = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if "=" in line:
+                k, v = line.split("=")
+                out[k.strip()] = [float(t) for t in v.split()]
+    return out
+
+
+# ---------------------------------------------------------------- Sec. 3.3 / appendix tables
+def test_token_fraction_matches_printed_example():
+    g = _golden()
+    frac = O.token_fraction(40, [10, 20, 30], [0.5, 0.5, 0.5])
+    assert frac == pytest.approx(0.46875, abs=1e-15)            # (10 + 5 + 2.5 + 1.25) / 40
+    assert round(100 * frac, 1) == g["token_fraction_example_percent"][0]
+
+
+def test_token_fraction_terms():
+    # no compression at all; one stage; a ratio of zero changes nothing
+    assert O.token_fraction(10, [10], [0.9]) == pytest.approx(1.0)
+    assert O.token_fraction(10, [4], [0.5]) == pytest.approx((4 + 6 * 0.5) / 10)
+    assert O.token_fraction(32, [12, 18, 24], [0.0, 0.0, 0.0]) == pytest.approx(1.0)
+    # the schedules the paper's tables use, rho = .5 each: the "55 %" retention
+    assert O.token_fraction(40, [15, 23, 31], [0.5] * 3) == pytest.approx(0.553125)
+    assert O.token_fraction(32, [12, 18, 24], [0.5] * 3) == pytest.approx(0.546875)
+    # stages are not interchangeable: order of ratios matters
+    assert O.token_fraction(40, [10, 20, 30], [0.5, 0.0, 0.0]) != pytest.approx(
+        O.token_fraction(40, [10, 20, 30], [0.0, 0.0, 0.5]))
+
+
+def test_flops_convention_matches_appendix_table():
+    g = _golden()
+    for v, bi, full in zip(g["flops_tokens"], g["flops_bipartite"], g["flops_full"]):
+        v = int(v)
+        assert O.fd_flops(v, 1024, True) / 1e9 == pytest.approx(bi, rel=3e-3)
+        assert O.fd_flops(v, 1024, False) / 1e9 == pytest.approx(full, rel=3e-3)
+        assert O.fd_flops(v, 1024, False) == 4 * O.fd_flops(v, 1024, True)
+    assert O.fd_flops(5, 3, True) == 2 * 3 * 2 * 3              # |A|=3, |B|=2
+
+
+# ---------------------------------------------------------------- windows
+def test_windows_equal_sized_and_spatial():
+    gh = gw = 24
+    pos = np.arange(gh * gw, dtype=np.int32)
+    cu = np.array([0, gh * gw], dtype=np.int32)
+    for w, per in ((4, 36), (6, 16), (2, 144), (1, 576)):
+        offs, toks = O.build_windows(pos, cu, 1, gh, gw, w)
+        assert len(offs) == w * w + 1
+        assert np.all(np.diff(offs) == per)                     # "each containing an equal number of tokens"
+        assert sorted(toks.tolist()) == list(range(gh * gw))    # a partition
+        for k in range(w * w):
+            t = toks[offs[k]:offs[k + 1]]
+            assert np.all(np.diff(t) > 0)                       # ascending inside a window
+            rows, cols = t // gw, t % gw
+            side = gh // w
+            assert np.all(rows // side == k // w) and np.all(cols // side == k % w)
+
+
+def test_windows_tiles_sequences_and_holes():
+    gh = gw = 4
+    # two sequences, two tiles each; the second sequence lost some tokens at an earlier stage
+    pos_full = np.arange(2 * gh * gw, dtype=np.int32)
+    kept2 = np.array([0, 3, 5, 6, 9, 17, 18, 30, 31], dtype=np.int32)
+    pos = np.concatenate([pos_full, kept2])
+    cu = np.array([0, 32, 32 + len(kept2)], dtype=np.int32)
+    offs, toks = O.build_windows(pos, cu, 2, gh, gw, 2)
+    assert len(offs) - 1 == 2 * 2 * 4
+    assert offs[-1] == len(pos)
+    # windows never mix sequences or tiles
+    for k in range(len(offs) - 1):
+        t = toks[offs[k]:offs[k + 1]]
+        seq = k // 8
+        assert np.all((t >= cu[seq]) & (t < cu[seq + 1]))
+        assert np.all(pos[t] // (gh * gw) == (k % 8) // 4)
+    # token with original cell (tile 1, row 3, col 2) = pos 30 sits in window tile1/(1,1) of sequence 1
+    k = 8 + 4 + 3
+    assert 32 + 7 in toks[offs[k]:offs[k + 1]].tolist()
+    # w = 0: one window per sequence
+    offs0, toks0 = O.build_windows(pos, cu, 2, gh, gw, 0)
+    assert offs0.tolist() == [0, 32, 41] and toks0.tolist() == list(range(41))
+
+
+def test_windows_grid_not_divisible():
+    gh, gw, w = 5, 7, 2
+    pos = np.arange(gh * gw, dtype=np.int32)
+    offs, toks = O.build_windows(pos, np.array([0, gh * gw], dtype=np.int32), 1, gh, gw, w)
+    assert offs[-1] == gh * gw and len(offs) == 5
+    for k in range(4):
+        t = toks[offs[k]:offs[k + 1]]
+        assert np.all((t // gw) * w // gh == k // w) and np.all((t % gw) * w // gw == k % w)
+
+
+def test_split_first_token_goes_to_A():
+    A, B = O.split_window(np.array([3, 4, 9, 11, 20]))
+    assert A.tolist() == [3, 9, 20] and B.tolist() == [4, 11]    # near-equal halves, |A| = ceil(v/2)
+
+
+# ---------------------------------------------------------------- FD
+def test_fd_closed_forms():
+    XA = np.array([[1.0, 0, 0], [2.0, 0, 0], [0, 3.0, 0], [-1.0, 0, 0], [1.0, 1.0, 0]])
+    XB = np.array([[5.0, 0, 0], [0, 0, 7.0]])
+    fd = O.feature_divergence(XA, XB)
+    assert fd.shape == (5, 2)
+    np.testing.assert_allclose(fd[:, 0], [0, 0, 1, 2, 1 - math.sqrt(0.5)], atol=1e-15)   # same, scaled, orthogonal, opposite, 45 deg
+    np.testing.assert_allclose(fd[:, 1], [1, 1, 1, 1, 1], atol=1e-15)
+    # zero vector: cosine taken as 0
+    np.testing.assert_allclose(O.feature_divergence(np.zeros((1, 3)), XB), [[1, 1]])
+
+
+def test_fd_against_library_and_scaling():
+    rng = np.random.default_rng(0)
+    XA, XB = rng.standard_normal((7, 33)), rng.standard_normal((5, 33))
+    from scipy.spatial.distance import cdist
+    ref = cdist(XA, XB, metric="cosine")                         # 1 - cos, independent implementation
+    np.testing.assert_allclose(O.feature_divergence(XA, XB), ref, atol=1e-13)
+    sa, sb = rng.uniform(0.1, 9, (7, 1)), rng.uniform(0.1, 9, (5, 1))
+    np.testing.assert_allclose(O.feature_divergence(XA * sa, XB * sb), ref, atol=1e-13)
+    # rows index A, columns index B (a transposed operand would change the shape or the values)
+    np.testing.assert_allclose(O.feature_divergence(XB, XA), ref.T, atol=1e-13)
+
+
+# ---------------------------------------------------------------- selection
+def _explicit_fd(X, a, b):
+    xa, xb = X[a], X[b]
+    dot = sum(float(p) * float(q) for p, q in zip(xa, xb))
+    return 1.0 - dot / (math.sqrt(sum(float(p) ** 2 for p in xa)) * math.sqrt(sum(float(q) ** 2 for q in xb)))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_selection_is_the_brute_force_minimiser(seed):
+    """Among all ways of choosing r nodes of A and one B partner for each, the
+    selected edge set has the smallest total FD."""
+    rng = np.random.default_rng(seed)
+    v = int(rng.integers(4, 10))
+    d = 6
+    X = rng.standard_normal((v + 3, d))
+    toks = np.sort(rng.choice(v + 3, size=v, replace=False)).astype(np.int32)
+    offs = np.array([0, v], dtype=np.int32)
+    A, B = toks[0::2], toks[1::2]
+    r = int(rng.integers(1, min(3, len(A)) + 1))
+    bf, bd = O.best_edges(X, offs, toks)
+    dst = O.select(bf, bd, offs, toks, np.array([r]))
+    got = sorted((int(a), int(dst[a])) for a in range(len(dst)) if dst[a] >= 0)
+    assert len(got) == r
+    best, best_cost = None, float("inf")
+    for S in itertools.combinations(A.tolist(), r):
+        for g in itertools.product(B.tolist(), repeat=r):
+            cost = sum(_explicit_fd(X, a, b) for a, b in zip(S, g))
+            if cost < best_cost - 1e-14:
+                best, best_cost = sorted(zip(S, g)), cost
+    assert got == best
+    # every endpoint is in the right set, and only A tokens leave
+    assert all(a in A.tolist() and b in B.tolist() for a, b in got)
+
+
+def test_edge_topk_is_the_brute_force_minimiser_over_edge_sets():
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((7, 4))
+    toks = np.arange(7, dtype=np.int32)
+    offs = np.array([0, 7], dtype=np.int32)
+    A, B = toks[0::2], toks[1::2]
+    k = 3
+    got = sorted(O.select_edge_topk(X, offs, toks, np.array([k])))
+    all_edges = [(int(a), int(b)) for a in A for b in B]
+    best = min(itertools.combinations(all_edges, k), key=lambda es: sum(_explicit_fd(X, a, b) for a, b in es))
+    assert got == sorted(best)
+
+
+def test_selection_ties_and_hub():
+    # three identical A tokens, one B equal to them, one far B: all FD ties at 0 -> lowest positions win
+    X = np.array([[1.0, 0], [1.0, 0], [1.0, 0], [0, 1.0], [1.0, 0], [0, -1.0]])
+    toks = np.arange(6, dtype=np.int32)      # A = 0,2,4   B = 1,3,5
+    offs = np.array([0, 6], dtype=np.int32)
+    bf, bd = O.best_edges(X, offs, toks)
+    assert bd[[0, 2, 4]].tolist() == [1, 1, 1]                  # several A share one B (hub)
+    assert np.all(bf[[0, 2, 4]] == 0) and np.all(np.isinf(bf[[1, 3, 5]]))
+    dst = O.select(bf, bd, offs, toks, np.array([2]))
+    assert dst.tolist() == [1, -1, 1, -1, -1, -1]
+    # two equal B candidates: the earlier one is taken
+    X2 = np.array([[3.0, 4.0], [6.0, 8.0], [5.0, 0], [30.0, 40.0]])   # norms 5, 10, 50: exact in binary
+    bf2, bd2 = O.best_edges(X2, np.array([0, 4], dtype=np.int32), np.arange(4, dtype=np.int32))
+    assert bd2[0] == 1
+
+
+def test_selection_counts_and_limits():
+    rng = np.random.default_rng(3)
+    n = 40
+    X = rng.standard_normal((n, 8))
+    offs = np.array([0, 13, 13, 14, 40], dtype=np.int32)        # sizes 13, 0, 1, 26
+    toks = np.arange(n, dtype=np.int32)
+    bf, bd = O.best_edges(X, offs, toks)
+    rem = np.array([7, 0, 0, 5], dtype=np.int32)                 # 7 = |A| of the first window: all of A leaves
+    dst = O.select(bf, bd, offs, toks, rem)
+    assert int((dst >= 0).sum()) == 12
+    kept = np.nonzero(dst < 0)[0]
+    assert len(kept) + int((dst >= 0).sum()) == n               # kept + merged = N
+    assert [i for i in kept if i < 13] == list(range(1, 13, 2))  # r = |A|  =>  exactly B stays
+    assert dst[13] == -1                                         # single-token window untouched
+    with pytest.raises(ValueError):
+        O.select(bf, bd, offs, toks, np.array([8, 0, 0, 0]))    # more than half cannot leave
+    ni = O.kept_index(dst)
+    assert ni[kept].tolist() == list(range(len(kept))) and np.all(ni[dst >= 0] == -1)
+    go, gs = O.groups_csr(dst)
+    assert go[-1] == 12 and sorted(gs.tolist()) == sorted(np.nonzero(dst >= 0)[0].tolist())
+    for b in range(n):
+        s = gs[go[b]:go[b + 1]]
+        assert np.all(dst[s] == b) and np.all(np.diff(s) > 0)
+    # positive rescaling of the embeddings does not change the choice
+    bf2, bd2 = O.best_edges(X * rng.uniform(0.5, 2, (n, 1)), offs, toks)
+    np.testing.assert_array_equal(O.select(bf2, bd2, offs, toks, rem), dst)
+
+
+def test_ratio_counts_reproduce_the_printed_halving():
+    g = _golden()
+    n_in, n_out = int(g["halving_stage1_in"][0]), int(g["halving_stage1_out"][0])
+    pos = np.arange(n_in, dtype=np.int32)
+    offs, toks = O.build_windows(pos, np.array([0, n_in], dtype=np.int32), 1, 24, 24, 4)
+    rem = O.removal_counts_ratio(offs, 0.5)
+    assert n_in - int(rem.sum()) == n_out
+    assert np.all(rem == (np.diff(offs) + 1) // 2)               # = |A|: the 50 % ceiling of one step
+    assert np.all(O.removal_counts_ratio(offs, 0.9) == rem)      # capped by that ceiling
+    assert rem.sum() / n_in == g["max_step_removal_fraction"][0]
+    ev = O.removal_counts_even(104, 16)
+    assert ev.sum() == 104 and ev.tolist() == [7] * 8 + [6] * 8
+
+
+# ---------------------------------------------------------------- xi
+def test_xi_closed_form_softmax():
+    H, dh, N, T = 3, 4, 6, 5
+    # head h: q = e_0 (all text tokens), k_i = log(w_hi) * sqrt(dh) * e_0  ->  softmax_i = w_hi / sum_i w_hi
+    w = np.array([[1, 2, 3, 4, 5, 6], [1, 1, 1, 1, 1, 1], [6, 1, 1, 1, 1, 10]], dtype=float)
+    Q = np.zeros((T, H * dh)); K = np.zeros((N, H * dh))
+    for h in range(H):
+        Q[:, h * dh] = 1.0
+        K[:, h * dh] = np.log(w[h]) * math.sqrt(dh)
+        K[:, h * dh + 1] = 7.0                                   # orthogonal to q: must not matter
+    xi = O.xi_text_query(Q, K, [0, N], [0, T], H, dh)
+    expect = T * (w / w.sum(axis=1, keepdims=True)).sum(axis=0)
+    np.testing.assert_allclose(xi, expect, rtol=1e-13)
+    assert xi.sum() == pytest.approx(H * T)
+    # explicit scale overrides 1/sqrt(dh)
+    xi1 = O.xi_text_query(Q, K / math.sqrt(dh), [0, N], [0, T], H, dh, scale=1.0)
+    np.testing.assert_allclose(xi1, expect, rtol=1e-13)
+
+
+def test_xi_equal_keys_ragged_batch_and_given_lse():
+    rng = np.random.default_rng(1)
+    H, dh = 2, 8
+    cu_vis, cu_txt = [0, 5, 12], [0, 3, 7]
+    Q = rng.standard_normal((7, H * dh))
+    K = np.tile(rng.standard_normal((1, H * dh)), (12, 1))
+    xi = O.xi_text_query(Q, K, cu_vis, cu_txt, H, dh)
+    np.testing.assert_allclose(xi[:5], H * 3 / 5, rtol=1e-13)
+    np.testing.assert_allclose(xi[5:], H * 4 / 7, rtol=1e-13)
+    # random keys: mass per sequence is H*T_b, and a handed-in lse gives the same result
+    K = rng.standard_normal((12, H * dh))
+    xi = O.xi_text_query(Q, K, cu_vis, cu_txt, H, dh)
+    assert xi[:5].sum() == pytest.approx(H * 3) and xi[5:].sum() == pytest.approx(H * 4)
+    lse = np.zeros((H, 7))
+    for b in range(2):
+        for h in range(H):
+            l = Q[cu_txt[b]:cu_txt[b + 1], h * dh:(h + 1) * dh] @ K[cu_vis[b]:cu_vis[b + 1], h * dh:(h + 1) * dh].T
+            l = l / math.sqrt(dh)
+            lse[h, cu_txt[b]:cu_txt[b + 1]] = np.log(np.exp(l).sum(axis=1))
+    np.testing.assert_allclose(O.xi_text_query(Q, K, cu_vis, cu_txt, H, dh, lse=lse), xi, rtol=1e-12)
+    # a larger normaliser (keys outside the vision span took part of the mass) scales xi down
+    np.testing.assert_allclose(O.xi_text_query(Q, K, cu_vis, cu_txt, H, dh, lse=lse + math.log(2)), xi / 2, rtol=1e-12)
+    # matches scipy's softmax, head by head
+    from scipy.special import softmax
+    ref = np.zeros(12)
+    for b in range(2):
+        for h in range(H):
+            l = Q[cu_txt[b]:cu_txt[b + 1], h * dh:(h + 1) * dh] @ K[cu_vis[b]:cu_vis[b + 1], h * dh:(h + 1) * dh].T
+            ref[cu_vis[b]:cu_vis[b + 1]] += softmax(l / math.sqrt(dh), axis=1).sum(axis=0)
+    np.testing.assert_allclose(xi, ref, rtol=1e-12)
+
+
+def test_xi_vision_query_degenerate_and_direction():
+    rng = np.random.default_rng(2)
+    H, dh, N, T = 2, 4, 6, 3
+    Qv, Kt = rng.standard_normal((N, H * dh)), rng.standard_normal((T, H * dh))
+    lse = np.zeros((H, N))
+    for h in range(H):
+        l = Qv[:, h * dh:(h + 1) * dh] @ Kt[:, h * dh:(h + 1) * dh].T / math.sqrt(dh)
+        lse[h] = np.log(np.exp(l).sum(axis=1))
+    # row normalised over the prompt keys only: every vision query spends all its mass there
+    np.testing.assert_allclose(O.xi_vision_query(Qv, Kt, lse, [0, N], [0, T], H, dh), H, rtol=1e-13)
+    # one extra key of logit 0 in every row: mass on the prompt is S/(S+1)
+    lse2 = np.log(np.exp(lse) + 1.0)
+    expect = (np.exp(lse) / (np.exp(lse) + 1.0)).sum(axis=0)
+    np.testing.assert_allclose(O.xi_vision_query(Qv, Kt, lse2, [0, N], [0, T], H, dh), expect, rtol=1e-13)
+
+
+def test_xi_floor():
+    Q = np.array([[100.0]]); K = np.array([[10.0], [-10.0]])
+    xi = O.xi_text_query(Q, K, [0, 2], [0, 1], 1, 1)
+    assert xi[0] == pytest.approx(1.0) and xi[1] == O.XI_FLOOR      # exp(-2000) underflows
+
+
+# ---------------------------------------------------------------- message passing, compaction
+def test_message_passing_worked_examples():
+    Y = np.array([[0.0, 8.0], [4.0, 0.0], [1.0, 1.0], [2.0, 6.0], [9.0, 9.0]])
+    xi = np.array([1.0, 3.0, 2.0, 1.0, 5.0])
+    dst = np.array([1, -1, 3, -1, 3], dtype=np.int32)             # 0 -> 1 ; 2 and 4 -> 3 (hub)
+    out = O.message_passing(Y, xi, dst)
+    np.testing.assert_allclose(out[1], [(3 * 4 + 1 * 0) / 4, (3 * 0 + 1 * 8) / 4])
+    np.testing.assert_allclose(out[3], [(1 * 2 + 2 * 1 + 5 * 9) / 8, (1 * 6 + 2 * 1 + 5 * 9) / 8])
+    np.testing.assert_array_equal(out[[0, 2, 4]], Y[[0, 2, 4]])   # A rows are not written
+    np.testing.assert_array_equal(O.compact(out, dst), out[[1, 3]])
+
+
+def test_message_passing_invariants():
+    rng = np.random.default_rng(4)
+    n, d = 30, 5
+    Y = rng.standard_normal((n, d)); xi = rng.uniform(0.01, 3, n)
+    dst = np.full(n, -1, dtype=np.int32)
+    for a in range(0, n, 2):
+        if rng.random() < 0.7:
+            dst[a] = int(rng.choice(np.arange(1, n, 2)))
+    out = O.message_passing(Y, xi, dst)
+    # scale invariance in xi
+    np.testing.assert_allclose(O.message_passing(Y, 37.5 * xi, dst), out, rtol=1e-13)
+    # uniform xi -> arithmetic mean of the group
+    outu = O.message_passing(Y, np.ones(n), dst)
+    go, gs = O.groups_csr(dst)
+    for b in range(n):
+        src = gs[go[b]:go[b + 1]]
+        if len(src):
+            np.testing.assert_allclose(outu[b], np.mean(np.vstack([Y[b:b + 1], Y[src]]), axis=0), rtol=1e-13)
+            grp = np.vstack([Y[b:b + 1], Y[src]])
+            assert np.all(out[b] <= grp.max(axis=0) + 1e-12) and np.all(out[b] >= grp.min(axis=0) - 1e-12)  # convex
+        else:
+            np.testing.assert_array_equal(out[b], Y[b])
+    # xi-weighted mass is conserved by merge + delete
+    xi_out = xi.copy()
+    for a in np.nonzero(dst >= 0)[0]:
+        xi_out[dst[a]] += xi[a]
+    keep = dst < 0
+    np.testing.assert_allclose((xi[:, None] * Y).sum(axis=0), (xi_out[keep, None] * out[keep]).sum(axis=0), rtol=1e-12)
+    # identical tokens merge without loss
+    Y2 = Y.copy(); Y2[dst >= 0] = Y2[dst[dst >= 0]]
+    out2 = O.message_passing(Y2, xi, dst)
+    np.testing.assert_allclose(out2[keep], Y2[keep], rtol=1e-15, atol=0)
+    # r = 0: identity
+    np.testing.assert_array_equal(O.message_passing(Y, xi, np.full(n, -1, dtype=np.int32)), Y)
+
+
+# ---------------------------------------------------------------- storage casts
+def test_storage_roundtrip():
+    x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, -2.5, 3.140625, 1e-3])
+    b = O.round_to_storage(x, "bf16")
+    back = O.widen(b, "bf16")
+    assert back[0] == 1.0 and back[1] == 1.0 and back[2] == 1.0 + 2 ** -6   # ties to even
+    assert back[3] == -2.5 and back[4] == 3.140625
+    assert abs(back[5] - 1e-3) <= 1e-3 * 2 ** -8
+    torch = pytest.importorskip("torch")
+    r = np.random.default_rng(0).standard_normal(1000).astype(np.float32)
+    tb = torch.from_numpy(r).to(torch.bfloat16)
+    np.testing.assert_array_equal(O.widen(O.round_to_storage(r, "bf16"), "bf16"), tb.to(torch.float64).numpy())
+
+
+# ---------------------------------------------------------------- whole step on the tiny configuration
+def test_whole_schedule_tiny_config():
+    from workloads import make_workload
+    wl = make_workload(1)
+    res = O.compress_schedule(wl)
+    assert len(res) == 1
+    r = res[0]
+    assert r.X.shape == (36, 128) and r.K.shape == (36, 128) and r.pos.shape == (36,)
+    assert int((r.dst >= 0).sum()) == 28 and r.cu_vis.tolist() == [0, 36]
+    assert np.all(np.diff(r.pos) > 0)
+    assert r.xi.sum() == pytest.approx(4 * 16)
+    # merged pairs come from the same window and opposite halves
+    wo, wt = O.build_windows(wl.pos, wl.cu_vis, 1, 8, 8, 2)
+    win_of = np.empty(64, dtype=int); half = np.empty(64, dtype=int)
+    for k in range(4):
+        t = wt[wo[k]:wo[k + 1]]
+        win_of[t] = k; half[t] = np.arange(len(t)) % 2
+    for a in np.nonzero(r.dst >= 0)[0]:
+        assert win_of[a] == win_of[r.dst[a]] and half[a] == 0 and half[r.dst[a]] == 1
+    # with mixture data the merged pairs overwhelmingly share a centre: their FD is far below the median FD
+    assert np.median(r.best_fd[r.dst >= 0]) < 0.05
