@@ -1,0 +1,197 @@
+/*
+ * lightkv.h -- C ABI of the LightKV compression step for AMD MI355X (gfx950).
+ *
+ * One step of prompt-guided vision-token compression, as run after a selected
+ * decoder layer during LVLM prefill (paper Sec. 3.2): inside every spatial window
+ * the vision tokens are split into two alternating node sets A and B (Sec. 3.2.1,
+ * Step 1), every A node is scored against the B nodes by feature divergence
+ * FD = 1 - cos (Eq. "similarity"), the lowest-FD edges are selected (Step 2), the
+ * selected A nodes are averaged into their B node with the prompt-attention
+ * weights xi (Step 3, Eq. "attention-factor" and Eq. "message-passing"), and the
+ * merged A nodes are dropped from the hidden states and from the layer's K/V rows
+ * (Steps 4-5; "key and value tokens are compressed simultaneously", appendix
+ * "Method overview").
+ *
+ * Conventions
+ *   - plain C, no C++ types cross the boundary; every function returns a
+ *     lightkv_status (0 = OK) and never throws; on error no output is touched.
+ *   - pointers named h_* are HOST memory, read during the call only.  Every other
+ *     pointer is DEVICE memory owned by the caller; the library allocates nothing,
+ *     frees nothing and keeps no state between calls.  Scratch comes from the
+ *     caller's workspace `ws` (size from lightkv_workspace_size, 256-byte aligned).
+ *   - all work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream); no call synchronises or reads device memory on the host.
+ *   - tensors are token-major: row i holds the `d` contiguous elements of token i;
+ *     `ld*` are row strides in elements.  Sequences of a batch are packed one after
+ *     the other; cu_vis / cu_txt are their [batch+1] offsets.
+ *   - indices are int32.  Device data pointers must be 16-byte aligned, row strides
+ *     multiples of 8 elements (bf16) or 4 elements (fp32).
+ *   - element type: LIGHTKV_BF16 (bf16 storage, fp32 accumulation on the matrix
+ *     cores) or LIGHTKV_F32.
+ */
+#ifndef LIGHTKV_H
+#define LIGHTKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LIGHTKV_OK = 0,
+  LIGHTKV_ERR_NULL = 1,         /* a required pointer is NULL                                   */
+  LIGHTKV_ERR_SHAPE = 2,        /* sizes/strides/offsets inconsistent, aliasing in/out buffers   */
+  LIGHTKV_ERR_WINDOWS = 3,      /* window CSR not a partition of the tokens                      */
+  LIGHTKV_ERR_REMOVE_COUNT = 4, /* some r_w exceeds |A_w|: one step removes at most half a window
+                                   (limitations paragraph of the paper)                           */
+  LIGHTKV_ERR_UNSUPPORTED = 5,  /* dtype, head_dim, alignment or a size beyond the stated limits */
+  LIGHTKV_ERR_WORKSPACE = 6,    /* workspace NULL, misaligned or too small                       */
+  LIGHTKV_ERR_LAUNCH = 7        /* the HIP runtime refused a launch                              */
+} lightkv_status;
+
+typedef enum { LIGHTKV_F32 = 0, LIGHTKV_BF16 = 1 } lightkv_dtype;
+
+/* How the prompt-guidance weight xi_i (Eq. "attention-factor") is obtained. */
+typedef enum {
+  /* prompt token j is the query, vision token i the key: xi_i = sum_h sum_j softmax_i(q_j.k_i*scale).
+     The softmax runs over the sequence's vision keys, or uses the caller's lse[heads, sumT]. */
+  LIGHTKV_XI_TEXT_QUERY = 0,
+  /* index order of the equation taken literally: vision token i is the query, prompt token j the key,
+     xi_i = sum_h sum_j exp(q_i.k_j*scale - lse[h,i]); lse[heads, sumN] (log-sum-exp of the whole
+     attention row of query i, as a flash-style attention kernel returns it) is required. */
+  LIGHTKV_XI_VISION_QUERY = 1,
+  /* xi is an input (e.g. all ones: the uniform-weight ablation of the paper). */
+  LIGHTKV_XI_GIVEN = 2
+} lightkv_xi_mode;
+
+/* Limits of this build. */
+#define LIGHTKV_MAX_WINDOW_TOKENS 4096   /* tokens in one window                    */
+#define LIGHTKV_MAX_SEQ_TOKENS    16384  /* vision tokens in one sequence           */
+#define LIGHTKV_MAX_TEXT_TOKENS   4096   /* prompt tokens in one sequence           */
+
+/*
+ * Problem descriptor of one compression step (host struct).
+ * Windows (Sec. 3.2 and Sec. 3.2.2 "Window partitioning") are given in CSR form:
+ * window w owns win_tokens[win_offsets[w] .. win_offsets[w+1]), token indices into
+ * the packed tensors, ascending.  Local positions 0,2,4,.. form set A, 1,3,5,.. set B
+ * (Step 1).  Windows never cross sequences.  r_w = win_remove[w] tokens of A are
+ * merged away in window w (Step 2; 0 <= r_w <= |A_w|).
+ */
+typedef struct lightkv_problem {
+  int32_t batch;              /* sequences in the batch                                          */
+  int32_t d;                  /* elements per row of X, K, V (= heads*head_dim)                  */
+  int32_t heads, head_dim;    /* head_dim in {32, 64, 128}                                       */
+  int32_t dtype;              /* lightkv_dtype                                                   */
+  int32_t n_windows;
+  int32_t max_window_tokens;  /* host-side upper bound on the size of any window; sizes launches.
+                                 0 = take it from h_win_offsets (then required).                 */
+  const int32_t *h_cu_vis;    /* HOST [batch+1] vision-token offsets, h_cu_vis[0] = 0            */
+  const int32_t *h_cu_txt;    /* HOST [batch+1] prompt-token offsets (may be NULL for XI_GIVEN)  */
+  const int32_t *cu_vis;      /* device copy of h_cu_vis                                         */
+  const int32_t *cu_txt;      /* device copy of h_cu_txt                                         */
+  const int32_t *win_offsets; /* device [n_windows+1]                                            */
+  const int32_t *win_tokens;  /* device [sumN]                                                   */
+  const int32_t *win_remove;  /* device [n_windows]                                              */
+  const int32_t *h_win_offsets; /* HOST mirror, optional: when given the CSR is validated on the host */
+  const int32_t *h_win_remove;  /* HOST mirror, optional: when given r_w <= |A_w| is validated        */
+} lightkv_problem;
+
+const char *lightkv_status_string(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int lightkv_version(void);
+
+/* Bytes of workspace that any call for this problem needs (upper bound over the four steps). */
+lightkv_status lightkv_workspace_size(const lightkv_problem *p, size_t *bytes);
+
+/*
+ * Window partition (Sec. 3.2: the tokens are put back on their image grid and cut into w x w
+ * non-overlapping windows; Sec. 3.2.2: later stages use fewer, larger windows).
+ *   pos[sumN]  device: original grid cell of every current token, tile*grid_h*grid_w + row*grid_w + col
+ *   window of a token = (tile, floor(row*w/grid_h), floor(col*w/grid_w)); w = 0: one window per sequence.
+ *   Every sequence owns tiles*w*w windows (1 if w = 0), in that order; n_windows = batch * that.
+ * Outputs: win_offsets[n_windows+1], win_tokens[sumN] (device).  Tokens of a window are listed in
+ * ascending order.  Sequences longer than LIGHTKV_MAX_SEQ_TOKENS -> LIGHTKV_ERR_UNSUPPORTED.
+ * A pos value outside the grid is clamped to the last tile/row/col.
+ */
+lightkv_status lightkv_build_windows(int32_t batch, const int32_t *h_cu_vis, const int32_t *cu_vis,
+                                     const int32_t *pos, int32_t tiles, int32_t grid_h, int32_t grid_w,
+                                     int32_t w, int32_t *win_offsets, int32_t *win_tokens, void *stream);
+
+/*
+ * Scores (Steps 1-3).
+ *   X[sumN, d] (row stride ldx): vision hidden states.  For every A node the lowest-FD B node of its
+ *   window: best_fd[i] = FD (fp32, clamped at 0), best_dst[i] = that B token; ties go to the B node that
+ *   comes first in the window.  B rows, and A rows of windows without a B node, get +inf / -1.
+ *   FD(a,b) = 1 - <x_a,x_b> / (max(|x_a|,1e-12) * max(|x_b|,1e-12))          (Eq. "similarity")
+ *   xi[sumN]: prompt-guidance weight (Eq. "attention-factor"), floored at 1e-30.
+ *     TEXT_QUERY  : Q = prompt queries [sumT, heads, head_dim], K = vision keys [sumN, heads, head_dim]
+ *     VISION_QUERY: Q = vision queries [sumN, ...],             K = prompt keys [sumT, ...], lse required
+ *     GIVEN       : Q, K, lse ignored, xi is read-only input and left as is.
+ *     element (token t, head h, e) of Q sits at Q[t*q_tok_stride + h*q_head_stride + e], K alike.
+ *   softmax_scale: 0 selects 1/sqrt(head_dim).   lse: natural-log units, layout [heads, tokens], or NULL.
+ */
+lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ldx,
+                             const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
+                             const void *K, int64_t k_tok_stride, int64_t k_head_stride,
+                             int32_t xi_mode, const float *lse, float softmax_scale,
+                             float *xi, float *best_fd, int32_t *best_dst,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Edge selection (Step 2) and the index structures of the merge.
+ * In window w the r_w A nodes with the lowest best_fd are merged (ties: earlier in the window first);
+ * if the device-side r_w exceeds |A_w| it is clamped to |A_w|, and windows without a B node merge nothing.
+ * An A node without a usable proposal (NaN scores) ranks last and, if still selected, goes to the first
+ * B node of its window, so exactly min(r_w, |A_w|) tokens leave every window.
+ *   dst[sumN]          token the A token is merged into, -1 for every token that stays (sets R and B)
+ *   new_index[sumN]    row of a staying token in the compacted tensors (order preserved), -1 if merged
+ *   grp_offsets[sumN+1], grp_src[sum r_w]   inverse of dst: the sources of token b, ascending
+ *   cu_vis_out[batch+1]  vision-token offsets after the step
+ */
+lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, const int32_t *best_dst,
+                              int32_t *dst, int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src,
+                              int32_t *cu_vis_out, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Message passing (Step 3, Eq. "message-passing"), in place: every token b that has sources becomes
+ *   y_b <- (xi_b*y_b + sum_a xi_a*y_a) / (xi_b + sum_a xi_a)       for y in {X, K, V} rows,
+ * evaluated as y_b + sum_a w_a*(y_a - y_b), w_a = xi_a/(xi_b + sum xi_a), in fp32 (identical rows stay
+ * bit-identical), rounded to nearest-even on store.  Source (A) rows are only read; each B row has one
+ * writer, so the update is race free.  Any of X, K, V may be NULL (skipped).
+ */
+lightkv_status lightkv_aggregate(const lightkv_problem *p, const int32_t *grp_offsets, const int32_t *grp_src,
+                                 const float *xi, void *X, int64_t ldx, void *K, int64_t ldk,
+                                 void *V, int64_t ldv, void *stream);
+
+/*
+ * Delete + reorder (Steps 4-5): out[new_index[i]] = in[i] for every staying token, for X, K, V and pos.
+ * Outputs are dense [out_rows, d] (row stride d) and must not overlap the inputs (-> LIGHTKV_ERR_SHAPE).
+ * out_rows is the capacity of the output tensors in rows (normally sumN' = sumN - sum r_w); a staying
+ * token whose new_index does not fit is dropped, never written out of bounds -- compare
+ * cu_vis_out[batch] from lightkv_select with out_rows to detect that.
+ * NULL tensors are skipped (in and out together).
+ */
+lightkv_status lightkv_compact(const lightkv_problem *p, const int32_t *new_index,
+                               const void *X, int64_t ldx, const void *K, int64_t ldk,
+                               const void *V, int64_t ldv, const int32_t *pos,
+                               void *X_out, void *K_out, void *V_out, int32_t *pos_out, int64_t out_rows,
+                               void *stream);
+
+/*
+ * lightkv_aggregate followed by lightkv_compact in one pass over the rows: reads every input row once,
+ * writes every output row once, leaves the inputs untouched.  Same results as the two calls.
+ */
+lightkv_status lightkv_aggregate_compact(const lightkv_problem *p, const int32_t *new_index,
+                                         const int32_t *grp_offsets, const int32_t *grp_src, const float *xi,
+                                         const void *X, int64_t ldx, const void *K, int64_t ldk,
+                                         const void *V, int64_t ldv, const int32_t *pos,
+                                         void *X_out, void *K_out, void *V_out, int32_t *pos_out,
+                                         int64_t out_rows, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIGHTKV_H */

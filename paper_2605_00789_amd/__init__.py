@@ -1,0 +1,25 @@
+"""LightKV compression step for AMD MI355X: thin Python binding over liblightkv.so.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in
+include/lightkv.h; this package only marshals arguments and owns buffers.
+There is no CPU fallback: importing `binding` without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    LightKVError,
+    Problem,
+    lib_path,
+    lightkv_aggregate,
+    lightkv_aggregate_compact,
+    lightkv_build_windows,
+    lightkv_compact,
+    lightkv_score,
+    lightkv_select,
+    lightkv_status_string,
+    lightkv_version,
+    lightkv_workspace_size,
+    XI_TEXT_QUERY,
+    XI_VISION_QUERY,
+    XI_GIVEN,
+)
+from .schedule import removal_counts, windows_per_sequence, max_window_cells  # noqa: F401
+from .pipeline import CompressionPipeline  # noqa: F401

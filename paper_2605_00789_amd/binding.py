@@ -1,0 +1,194 @@
+"""ctypes binding of liblightkv.so: same names as the C ABI (include/lightkv.h),
+argument marshalling only.  torch tensors supply device memory and the stream."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+import torch
+
+XI_TEXT_QUERY, XI_VISION_QUERY, XI_GIVEN = 0, 1, 2
+F32, BF16 = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "liblightkv.so")
+
+
+class LightKVError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: status %d (%s)" % (where, status, lightkv_status_string(status)))
+
+
+class _CProblem(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("d", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32),
+        ("dtype", C.c_int32), ("n_windows", C.c_int32), ("max_window_tokens", C.c_int32),
+        ("h_cu_vis", C.c_void_p), ("h_cu_txt", C.c_void_p), ("cu_vis", C.c_void_p), ("cu_txt", C.c_void_p),
+        ("win_offsets", C.c_void_p), ("win_tokens", C.c_void_p), ("win_remove", C.c_void_p),
+        ("h_win_offsets", C.c_void_p), ("h_win_remove", C.c_void_p),
+    ]
+
+
+def _load():
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(
+            "liblightkv.so is not built (%s). Run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "or `python paper_2605_00789_amd/build.py`; there is no fallback path." % path)
+    lib = C.CDLL(path)
+    P = C.POINTER(_CProblem)
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+    lib.lightkv_status_string.restype = C.c_char_p
+    lib.lightkv_status_string.argtypes = [C.c_int]
+    lib.lightkv_version.restype = C.c_int
+    lib.lightkv_version.argtypes = []
+    lib.lightkv_workspace_size.restype = C.c_int
+    lib.lightkv_workspace_size.argtypes = [P, C.POINTER(sz)]
+    lib.lightkv_build_windows.restype = C.c_int
+    lib.lightkv_build_windows.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
+    lib.lightkv_score.restype = C.c_int
+    lib.lightkv_score.argtypes = [P, vp, i64, vp, i64, i64, vp, i64, i64, i32, vp, f32, vp, vp, vp, vp, sz, vp]
+    lib.lightkv_select.restype = C.c_int
+    lib.lightkv_select.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lightkv_aggregate.restype = C.c_int
+    lib.lightkv_aggregate.argtypes = [P, vp, vp, vp, vp, i64, vp, i64, vp, i64, vp]
+    lib.lightkv_compact.restype = C.c_int
+    lib.lightkv_compact.argtypes = [P, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, i64, vp]
+    lib.lightkv_aggregate_compact.restype = C.c_int
+    lib.lightkv_aggregate_compact.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, i64, vp]
+    return lib
+
+
+_lib = _load()
+
+EXPORTS = ("lightkv_status_string", "lightkv_version", "lightkv_workspace_size", "lightkv_build_windows",
+           "lightkv_score", "lightkv_select", "lightkv_aggregate", "lightkv_compact", "lightkv_aggregate_compact")
+
+
+def _dptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    return C.c_void_p(t.data_ptr())
+
+
+def _hptr(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    if a.dtype != np.int32 or not a.flags["C_CONTIGUOUS"]:
+        raise ValueError("host arrays must be contiguous int32")
+    return C.c_void_p(a.ctypes.data)
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise LightKVError(status, where)
+
+
+def _out_rows(*outs) -> int:
+    rows = [int(t.shape[0]) for t in outs if t is not None]
+    return min(rows) if rows else 0
+
+
+def _ld(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else int(t.stride(0))
+
+
+class Problem:
+    """Python mirror of `lightkv_problem`; keeps the host arrays and device tensors it points to alive."""
+
+    def __init__(self, *, batch, d, heads, head_dim, dtype, h_cu_vis, cu_vis, h_cu_txt=None, cu_txt=None,
+                 n_windows=0, max_window_tokens=0, win_offsets=None, win_tokens=None, win_remove=None,
+                 h_win_offsets=None, h_win_remove=None):
+        self.refs = dict(h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=h_cu_txt, cu_txt=cu_txt,
+                         win_offsets=win_offsets, win_tokens=win_tokens, win_remove=win_remove,
+                         h_win_offsets=h_win_offsets, h_win_remove=h_win_remove)
+        self.c = _CProblem()
+        self.c.batch, self.c.d, self.c.heads, self.c.head_dim = batch, d, heads, head_dim
+        self.c.dtype = {"f32": F32, "bf16": BF16, F32: F32, BF16: BF16}[dtype]
+        self.c.n_windows, self.c.max_window_tokens = n_windows, max_window_tokens
+        for name in ("h_cu_vis", "h_cu_txt", "h_win_offsets", "h_win_remove"):
+            setattr(self.c, name, _hptr(self.refs[name]))
+        for name in ("cu_vis", "cu_txt", "win_offsets", "win_tokens", "win_remove"):
+            setattr(self.c, name, _dptr(self.refs[name]))
+
+    def ref(self):
+        return C.byref(self.c)
+
+
+def lightkv_status_string(status: int) -> str:
+    return _lib.lightkv_status_string(int(status)).decode()
+
+
+def lightkv_version() -> int:
+    return int(_lib.lightkv_version())
+
+
+def lightkv_workspace_size(p: Problem) -> int:
+    out = C.c_size_t(0)
+    _check(_lib.lightkv_workspace_size(p.ref(), C.byref(out)), "lightkv_workspace_size")
+    return int(out.value)
+
+
+def lightkv_build_windows(batch, h_cu_vis, cu_vis, pos, tiles, grid_h, grid_w, w, win_offsets, win_tokens,
+                          stream=None):
+    _check(_lib.lightkv_build_windows(batch, _hptr(h_cu_vis), _dptr(cu_vis), _dptr(pos), tiles, grid_h, grid_w, w,
+                                      _dptr(win_offsets), _dptr(win_tokens), _stream(stream)),
+           "lightkv_build_windows")
+
+
+def lightkv_score(p: Problem, X, Q, K, xi, best_fd, best_dst, ws, *, heads_major=False, xi_mode=XI_TEXT_QUERY,
+                  lse=None, softmax_scale=0.0, stream=None):
+    """X [sumN, d]; Q, K token-major [tokens, heads*head_dim] (or [heads, tokens, head_dim] with heads_major)."""
+    hd = p.c.head_dim
+
+    def strides(t):
+        if t is None:
+            return 0, 0
+        if heads_major:
+            return int(t.stride(1)), int(t.stride(0))
+        return int(t.stride(0)), hd
+
+    qts, qhs = strides(Q)
+    kts, khs = strides(K)
+    _check(_lib.lightkv_score(p.ref(), _dptr(X), _ld(X), _dptr(Q), qts, qhs, _dptr(K), kts, khs, xi_mode,
+                              _dptr(lse), float(softmax_scale), _dptr(xi), _dptr(best_fd), _dptr(best_dst),
+                              _dptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "lightkv_score")
+
+
+def lightkv_select(p: Problem, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, ws, stream=None):
+    _check(_lib.lightkv_select(p.ref(), _dptr(best_fd), _dptr(best_dst), _dptr(dst), _dptr(new_index),
+                               _dptr(grp_offsets), _dptr(grp_src), _dptr(cu_vis_out), _dptr(ws),
+                               ws.numel() * ws.element_size(), _stream(stream)), "lightkv_select")
+
+
+def lightkv_aggregate(p: Problem, grp_offsets, grp_src, xi, X, K, V, stream=None):
+    _check(_lib.lightkv_aggregate(p.ref(), _dptr(grp_offsets), _dptr(grp_src), _dptr(xi), _dptr(X), _ld(X),
+                                  _dptr(K), _ld(K), _dptr(V), _ld(V), _stream(stream)), "lightkv_aggregate")
+
+
+def lightkv_compact(p: Problem, new_index, X, K, V, pos, X_out, K_out, V_out, pos_out, stream=None):
+    _check(_lib.lightkv_compact(p.ref(), _dptr(new_index), _dptr(X), _ld(X), _dptr(K), _ld(K), _dptr(V), _ld(V),
+                                _dptr(pos), _dptr(X_out), _dptr(K_out), _dptr(V_out), _dptr(pos_out),
+                                _out_rows(X_out, K_out, V_out, pos_out), _stream(stream)), "lightkv_compact")
+
+
+def lightkv_aggregate_compact(p: Problem, new_index, grp_offsets, grp_src, xi, X, K, V, pos, X_out, K_out, V_out,
+                              pos_out, stream=None):
+    _check(_lib.lightkv_aggregate_compact(p.ref(), _dptr(new_index), _dptr(grp_offsets), _dptr(grp_src), _dptr(xi),
+                                          _dptr(X), _ld(X), _dptr(K), _ld(K), _dptr(V), _ld(V), _dptr(pos),
+                                          _dptr(X_out), _dptr(K_out), _dptr(V_out), _dptr(pos_out),
+                                          _out_rows(X_out, K_out, V_out, pos_out), _stream(stream)),
+           "lightkv_aggregate_compact")

@@ -1,0 +1,283 @@
+// C ABI of the LightKV compression step: argument validation, workspace layout, launches.
+// Nothing here allocates, synchronises or reads device memory.
+#include "../../include/lightkv.h"
+#include "lk_launch.h"
+
+#include <math.h>
+
+namespace {
+
+using namespace lk;
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Checked {
+  int sum_n = 0, sum_t = 0, max_seq = 0, max_window = 0, elem_bytes = 0;
+};
+
+lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool need_txt, Checked &c) {
+  if (!p || !p->h_cu_vis || !p->cu_vis) return LIGHTKV_ERR_NULL;
+  if (p->batch < 1 || p->d < 1 || p->heads < 1 || p->head_dim < 1 || p->n_windows < 0) return LIGHTKV_ERR_SHAPE;
+  if (p->dtype != LIGHTKV_F32 && p->dtype != LIGHTKV_BF16) return LIGHTKV_ERR_UNSUPPORTED;
+  c.elem_bytes = p->dtype == LIGHTKV_BF16 ? 2 : 4;
+  if (p->d % (16 / c.elem_bytes) != 0) return LIGHTKV_ERR_UNSUPPORTED;
+  if ((int64_t)p->heads * p->head_dim != p->d) return LIGHTKV_ERR_SHAPE;
+  if (p->head_dim != 32 && p->head_dim != 64 && p->head_dim != 128) return LIGHTKV_ERR_UNSUPPORTED;
+  if (p->h_cu_vis[0] != 0) return LIGHTKV_ERR_SHAPE;
+  for (int b = 0; b < p->batch; ++b) {
+    const int n = p->h_cu_vis[b + 1] - p->h_cu_vis[b];
+    if (n < 0) return LIGHTKV_ERR_SHAPE;
+    if (n > LIGHTKV_MAX_SEQ_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;
+    c.max_seq = n > c.max_seq ? n : c.max_seq;
+  }
+  c.sum_n = p->h_cu_vis[p->batch];
+  if (need_txt) {
+    if (!p->h_cu_txt || !p->cu_txt) return LIGHTKV_ERR_NULL;
+    if (p->h_cu_txt[0] != 0) return LIGHTKV_ERR_SHAPE;
+    for (int b = 0; b < p->batch; ++b) {
+      const int t = p->h_cu_txt[b + 1] - p->h_cu_txt[b];
+      if (t < 0) return LIGHTKV_ERR_SHAPE;
+      if (t > LIGHTKV_MAX_TEXT_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;
+    }
+    c.sum_t = p->h_cu_txt[p->batch];
+  }
+  if (need_windows) {
+    if (!p->win_offsets || !p->win_tokens) return LIGHTKV_ERR_NULL;
+    int maxw = 0;
+    if (p->h_win_offsets) {
+      if (p->n_windows > 0 && p->h_win_offsets[0] != 0) return LIGHTKV_ERR_WINDOWS;
+      for (int w = 0; w < p->n_windows; ++w) {
+        const int v = p->h_win_offsets[w + 1] - p->h_win_offsets[w];
+        if (v < 0) return LIGHTKV_ERR_WINDOWS;
+        maxw = v > maxw ? v : maxw;
+      }
+      if (p->n_windows > 0 && p->h_win_offsets[p->n_windows] != c.sum_n) return LIGHTKV_ERR_WINDOWS;
+      if (p->n_windows == 0 && c.sum_n != 0) return LIGHTKV_ERR_WINDOWS;
+      if (p->max_window_tokens > 0 && p->max_window_tokens < maxw) return LIGHTKV_ERR_WINDOWS;
+      if (p->h_win_remove) {
+        for (int w = 0; w < p->n_windows; ++w) {
+          const int v = p->h_win_offsets[w + 1] - p->h_win_offsets[w];
+          const int r = p->h_win_remove[w];
+          const int cap = (v >= 2) ? (v + 1) / 2 : 0;
+          if (r < 0 || r > cap) return LIGHTKV_ERR_REMOVE_COUNT;
+        }
+      }
+      c.max_window = p->max_window_tokens > 0 ? p->max_window_tokens : maxw;
+    } else {
+      if (p->max_window_tokens <= 0) return LIGHTKV_ERR_NULL;
+      c.max_window = p->max_window_tokens;
+    }
+    if (c.max_window > LIGHTKV_MAX_WINDOW_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;
+  }
+  return LIGHTKV_OK;
+}
+
+struct WsLayout {
+  size_t fd_partial = 0, xi_stats = 0, xi_part = 0, sel_cnt = 0, sel_rank = 0, total = 0;
+};
+
+WsLayout ws_layout(const FdPlan &fd, const XiPlan &xi, int sum_n) {
+  WsLayout l;
+  size_t off = 0;
+  l.fd_partial = off; off = align_up(off + fd.partial_floats * sizeof(float));
+  l.xi_stats = off;   off = align_up(off + xi.stat_floats * sizeof(float));
+  l.xi_part = off;    off = align_up(off + xi.part_floats * sizeof(float));
+  l.sel_cnt = off;    off = align_up(off + (size_t)sum_n * sizeof(int32_t));
+  l.sel_rank = off;   off = align_up(off + (size_t)sum_n * sizeof(int32_t));
+  l.total = off + ALIGN;
+  return l;
+}
+
+bool row_tensor_ok(const void *p, int64_t ld, int d, int elem_bytes, lightkv_status &st) {
+  if (!p) return true;
+  if (!aligned16(p) || ld % (16 / elem_bytes) != 0) { st = LIGHTKV_ERR_UNSUPPORTED; return false; }
+  if (ld < d) { st = LIGHTKV_ERR_SHAPE; return false; }
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *lightkv_status_string(int status) {
+  switch (status) {
+    case LIGHTKV_OK: return "ok";
+    case LIGHTKV_ERR_NULL: return "a required pointer is NULL";
+    case LIGHTKV_ERR_SHAPE: return "inconsistent sizes, strides or offsets";
+    case LIGHTKV_ERR_WINDOWS: return "window lists are not a partition of the tokens";
+    case LIGHTKV_ERR_REMOVE_COUNT: return "a window is asked to remove more tokens than its set A holds";
+    case LIGHTKV_ERR_UNSUPPORTED: return "unsupported dtype, head size, alignment or size limit";
+    case LIGHTKV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LIGHTKV_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int lightkv_version(void) { return 100; }
+
+lightkv_status lightkv_workspace_size(const lightkv_problem *p, size_t *bytes) {
+  if (!bytes) return LIGHTKV_ERR_NULL;
+  Checked c;
+  // prompt offsets are optional here: without them the xi scratch is not counted (XI_GIVEN callers)
+  const bool have_txt = p && p->h_cu_txt && p->cu_txt;
+  lightkv_status st = check_problem(p, true, have_txt, c);
+  if (st != LIGHTKV_OK) return st;
+  const FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
+  const XiPlan xi = make_xi_plan(p->batch, p->h_cu_vis, have_txt ? p->h_cu_txt : nullptr, p->heads, 0);
+  *bytes = ws_layout(fd, xi, c.sum_n).total;
+  return LIGHTKV_OK;
+}
+
+lightkv_status lightkv_build_windows(int32_t batch, const int32_t *h_cu_vis, const int32_t *cu_vis,
+                                     const int32_t *pos, int32_t tiles, int32_t grid_h, int32_t grid_w,
+                                     int32_t w, int32_t *win_offsets, int32_t *win_tokens, void *stream) {
+  if (!h_cu_vis || !cu_vis || !pos || !win_offsets || !win_tokens) return LIGHTKV_ERR_NULL;
+  if (batch < 1 || tiles < 1 || grid_h < 1 || grid_w < 1 || w < 0 || h_cu_vis[0] != 0) return LIGHTKV_ERR_SHAPE;
+  int max_seq = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int n = h_cu_vis[b + 1] - h_cu_vis[b];
+    if (n < 0) return LIGHTKV_ERR_SHAPE;
+    max_seq = n > max_seq ? n : max_seq;
+  }
+  if (max_seq > LIGHTKV_MAX_SEQ_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;
+  if ((int64_t)tiles * w * w > (1 << 17) || (int64_t)tiles * grid_h * grid_w > (1ll << 30)) return LIGHTKV_ERR_UNSUPPORTED;
+  if (launch_build_windows(cu_vis, pos, batch, max_seq, tiles, grid_h, grid_w, w, win_offsets, win_tokens,
+                           static_cast<hipStream_t>(stream)) != hipSuccess)
+    return LIGHTKV_ERR_LAUNCH;
+  return LIGHTKV_OK;
+}
+
+lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ldx,
+                             const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
+                             const void *K, int64_t k_tok_stride, int64_t k_head_stride,
+                             int32_t xi_mode, const float *lse, float softmax_scale,
+                             float *xi, float *best_fd, int32_t *best_dst,
+                             void *ws, size_t ws_bytes, void *stream) {
+  if (xi_mode < LIGHTKV_XI_TEXT_QUERY || xi_mode > LIGHTKV_XI_GIVEN) return LIGHTKV_ERR_UNSUPPORTED;
+  const bool need_xi = xi_mode != LIGHTKV_XI_GIVEN;
+  Checked c;
+  lightkv_status st = check_problem(p, true, need_xi, c);
+  if (st != LIGHTKV_OK) return st;
+  if (!X || !xi || !best_fd || !best_dst) return LIGHTKV_ERR_NULL;
+  if (!row_tensor_ok(X, ldx, p->d, c.elem_bytes, st)) return st;
+  if (need_xi) {
+    if (!Q || !K) return LIGHTKV_ERR_NULL;
+    if (xi_mode == LIGHTKV_XI_VISION_QUERY && !lse) return LIGHTKV_ERR_NULL;
+    const int64_t m = 16 / c.elem_bytes;
+    if (!aligned16(Q) || !aligned16(K) || q_tok_stride % m || q_head_stride % m || k_tok_stride % m || k_head_stride % m)
+      return LIGHTKV_ERR_UNSUPPORTED;
+    if (q_tok_stride < 0 || q_head_stride < 0 || k_tok_stride < 0 || k_head_stride < 0) return LIGHTKV_ERR_SHAPE;
+  }
+  const FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
+  const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, need_xi ? p->h_cu_txt : nullptr, p->heads, xi_mode);
+  const WsLayout l = ws_layout(fd, xp, c.sum_n);
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) != 0 || ws_bytes < l.total) return LIGHTKV_ERR_WORKSPACE;
+  char *wsb = static_cast<char *>(ws);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  if (need_xi) {
+    const float scale = softmax_scale != 0.f ? softmax_scale : 1.0f / sqrtf((float)p->head_dim);
+    if (launch_xi(xp, p->dtype, xi_mode, p->batch, p->heads, p->head_dim, c.sum_n, c.sum_t, p->cu_vis, p->cu_txt,
+                  Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, lse, scale,
+                  reinterpret_cast<float *>(wsb + l.xi_stats), reinterpret_cast<float *>(wsb + l.xi_part), xi, s)
+        != hipSuccess)
+      return LIGHTKV_ERR_LAUNCH;
+  }
+  if (launch_fd(fd, p->dtype, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
+                reinterpret_cast<float *>(wsb + l.fd_partial), best_fd, best_dst, s) != hipSuccess)
+    return LIGHTKV_ERR_LAUNCH;
+  return LIGHTKV_OK;
+}
+
+lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, const int32_t *best_dst,
+                              int32_t *dst, int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src,
+                              int32_t *cu_vis_out, void *ws, size_t ws_bytes, void *stream) {
+  Checked c;
+  lightkv_status st = check_problem(p, true, false, c);
+  if (st != LIGHTKV_OK) return st;
+  if (!p->win_remove || !best_fd || !best_dst || !dst || !new_index || !grp_offsets || !grp_src || !cu_vis_out)
+    return LIGHTKV_ERR_NULL;
+  const FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
+  const bool have_txt = p->h_cu_txt && p->cu_txt;
+  const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, have_txt ? p->h_cu_txt : nullptr, p->heads, 0);
+  const WsLayout l = ws_layout(fd, xp, c.sum_n);
+  // only the selection scratch is used here; accept a workspace that just covers it as laid out
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) != 0 || ws_bytes < l.total) return LIGHTKV_ERR_WORKSPACE;
+  char *wsb = static_cast<char *>(ws);
+  if (launch_select(p->n_windows, c.max_window, p->batch, c.sum_n, p->cu_vis, p->win_offsets, p->win_tokens,
+                    p->win_remove, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out,
+                    reinterpret_cast<int32_t *>(wsb + l.sel_cnt), reinterpret_cast<int32_t *>(wsb + l.sel_rank),
+                    static_cast<hipStream_t>(stream)) != hipSuccess)
+    return LIGHTKV_ERR_LAUNCH;
+  return LIGHTKV_OK;
+}
+
+static lightkv_status rows_call(int mode, const lightkv_problem *p, const int32_t *new_index,
+                                const int32_t *grp_offsets, const int32_t *grp_src, const float *xi,
+                                const void *X, int64_t ldx, const void *K, int64_t ldk, const void *V, int64_t ldv,
+                                const int32_t *pos, void *Xo, void *Ko, void *Vo, int32_t *pos_out, int64_t out_rows,
+                                void *stream) {
+  Checked c;
+  lightkv_status st = check_problem(p, false, false, c);
+  if (st != LIGHTKV_OK) return st;
+  if (mode != 1 && (!grp_offsets || !grp_src || !xi)) return LIGHTKV_ERR_NULL;
+  if (mode != 0 && !new_index) return LIGHTKV_ERR_NULL;
+  if (mode != 0 && out_rows < 0) return LIGHTKV_ERR_SHAPE;
+  if (mode != 0 && out_rows > c.sum_n) out_rows = c.sum_n;
+  const void *in[3] = {X, K, V};
+  void *out[3] = {Xo, Ko, Vo};
+  const int64_t ld[3] = {ldx, ldk, ldv};
+  RowTensors t{};
+  for (int i = 0; i < 3; ++i) {
+    if (mode != 0 && ((in[i] == nullptr) != (out[i] == nullptr))) return LIGHTKV_ERR_NULL;
+    if (!row_tensor_ok(in[i], ld[i], p->d, c.elem_bytes, st)) return st;
+    if (mode != 0 && in[i]) {
+      if (!aligned16(out[i])) return LIGHTKV_ERR_UNSUPPORTED;
+      const char *a = static_cast<const char *>(in[i]);
+      const char *b = static_cast<const char *>(out[i]);
+      const size_t in_bytes = (size_t)c.sum_n * (size_t)ld[i] * c.elem_bytes;
+      const size_t out_bytes = (size_t)out_rows * (size_t)p->d * c.elem_bytes;
+      if (a == b || (b > a && b < a + in_bytes) || (a > b && a < b + out_bytes)) return LIGHTKV_ERR_SHAPE;
+    }
+    t.in[i] = in[i];
+    t.out[i] = mode == 0 ? const_cast<void *>(in[i]) : out[i];
+    t.ld_in[i] = ld[i];
+    t.ld_out[i] = mode == 0 ? ld[i] : p->d;
+  }
+  if (mode != 0 && ((pos == nullptr) != (pos_out == nullptr))) return LIGHTKV_ERR_NULL;
+  if (mode != 0 && pos && pos == pos_out) return LIGHTKV_ERR_SHAPE;
+  if (launch_rows(mode, p->dtype, p->d, c.sum_n, t, new_index, grp_offsets, grp_src, xi, pos, pos_out, out_rows,
+                  static_cast<hipStream_t>(stream)) != hipSuccess)
+    return LIGHTKV_ERR_LAUNCH;
+  return LIGHTKV_OK;
+}
+
+lightkv_status lightkv_aggregate(const lightkv_problem *p, const int32_t *grp_offsets, const int32_t *grp_src,
+                                 const float *xi, void *X, int64_t ldx, void *K, int64_t ldk,
+                                 void *V, int64_t ldv, void *stream) {
+  return rows_call(0, p, nullptr, grp_offsets, grp_src, xi, X, ldx, K, ldk, V, ldv, nullptr, nullptr, nullptr,
+                   nullptr, nullptr, 0, stream);
+}
+
+lightkv_status lightkv_compact(const lightkv_problem *p, const int32_t *new_index,
+                               const void *X, int64_t ldx, const void *K, int64_t ldk,
+                               const void *V, int64_t ldv, const int32_t *pos,
+                               void *X_out, void *K_out, void *V_out, int32_t *pos_out, int64_t out_rows,
+                               void *stream) {
+  return rows_call(1, p, new_index, nullptr, nullptr, nullptr, X, ldx, K, ldk, V, ldv, pos, X_out, K_out, V_out,
+                   pos_out, out_rows, stream);
+}
+
+lightkv_status lightkv_aggregate_compact(const lightkv_problem *p, const int32_t *new_index,
+                                         const int32_t *grp_offsets, const int32_t *grp_src, const float *xi,
+                                         const void *X, int64_t ldx, const void *K, int64_t ldk,
+                                         const void *V, int64_t ldv, const int32_t *pos,
+                                         void *X_out, void *K_out, void *V_out, int32_t *pos_out,
+                                         int64_t out_rows, void *stream) {
+  return rows_call(2, p, new_index, grp_offsets, grp_src, xi, X, ldx, K, ldk, V, ldv, pos, X_out, K_out, V_out,
+                   pos_out, out_rows, stream);
+}
+
+}  // extern "C"

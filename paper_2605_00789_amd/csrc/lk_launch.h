@@ -1,0 +1,71 @@
+// Host-side launch plans and launcher declarations (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lk {
+
+// ---- feature divergence (Steps 1-2) ------------------------------------------------------
+// The |A_w| x |B_w| cosine blocks are cut into 32x32 tiles.  Small windows are packed several to
+// a tile (block diagonal): `slot` rows/cols per window, `group` windows per tile.  Large windows
+// get mt x nt tiles each.  The d axis is split over `ksplit` workgroups (and the 4 waves of each);
+// partial tiles are summed in a fixed order by the epilogue.
+struct FdPlan {
+  int slot;         // rows (and cols) reserved per window in a packed tile; 0 when group == 1
+  int group;        // windows per tile
+  int mt, nt;       // tiles per window along A and B (group == 1)
+  int n_tiles;      // tile jobs
+  int n_rowblocks;  // epilogue jobs (one per 32 A rows)
+  int ksplit;
+  size_t partial_floats;   // n_tiles * ksplit * FD_TILE_FLOATS
+};
+constexpr int FD_TILE_FLOATS = 32 * 32 + 32 + 32;   // dots, |a|^2 partials, |b|^2 partials
+constexpr int FD_MAX_COLS = 2048;                   // |B| of the largest supported window
+
+FdPlan make_fd_plan(int n_windows, int max_window_tokens, int d, int dtype_bytes);
+
+hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, int batch, int max_seq, int tiles,
+                                int grid_h, int grid_w, int w, int32_t *win_offsets, int32_t *win_tokens,
+                                hipStream_t stream);
+
+hipError_t launch_fd(const FdPlan &plan, int dtype, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
+                     const int32_t *win_offsets, const int32_t *win_tokens, float *partial, float *best_fd,
+                     int32_t *best_dst, hipStream_t stream);
+
+// ---- prompt-guidance weight xi (Step 3) ----------------------------------------------------
+struct XiPlan {
+  int vsplit;          // workgroups sharing the vision axis of one (sequence, head, 32 text rows) job in pass 1
+  int max_text_tiles;  // ceil(max T_b / 32)
+  int max_vis_blocks;  // ceil(max N_b / 128)
+  size_t stat_floats;  // pass-1 partial (max, sum) pairs: heads * sumT * vsplit * 2
+  size_t part_floats;  // per-head partial xi: heads * sumN
+};
+XiPlan make_xi_plan(int batch, const int32_t *h_cu_vis, const int32_t *h_cu_txt, int heads, int xi_mode);
+
+hipError_t launch_xi(const XiPlan &plan, int dtype, int xi_mode, int batch, int heads, int head_dim, int sum_n,
+                     int sum_t, const int32_t *cu_vis, const int32_t *cu_txt, const void *Q, int64_t q_tok_stride,
+                     int64_t q_head_stride, const void *K, int64_t k_tok_stride, int64_t k_head_stride,
+                     const float *lse, float scale, float *stats, float *xi_part, float *xi, hipStream_t stream);
+
+// ---- selection (Step 2) ----------------------------------------------------------------------
+hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int sum_n, const int32_t *cu_vis,
+                         const int32_t *win_offsets, const int32_t *win_tokens, const int32_t *win_remove,
+                         const float *best_fd, const int32_t *best_dst, int32_t *dst, int32_t *new_index,
+                         int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, int32_t *cnt,
+                         int32_t *src_rank, hipStream_t stream);
+
+// ---- message passing + compaction (Steps 3-5) ---------------------------------------------------
+struct RowTensors {
+  const void *in[3];
+  void *out[3];
+  int64_t ld_in[3];
+  int64_t ld_out[3];
+};
+// mode 0: aggregate in place (out == in, only rows with sources are written)
+// mode 1: compact (copy staying rows to new_index)      mode 2: aggregate + compact
+hipError_t launch_rows(int mode, int dtype, int d, int sum_n, const RowTensors &t, const int32_t *new_index,
+                       const int32_t *grp_offsets, const int32_t *grp_src, const float *xi, const int32_t *pos,
+                       int32_t *pos_out, int64_t out_rows, hipStream_t stream);
+
+}  // namespace lk

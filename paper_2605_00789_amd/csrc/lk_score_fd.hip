@@ -1,0 +1,294 @@
+// Feature divergence and the best edge of every A node (paper Sec. 3.2.1 Steps 1-2, Eq. "similarity").
+//
+// For every window the |A| x |B| block of inner products <x_a, x_b> is a dense contraction over the
+// hidden dimension and runs on the matrix cores (bf16 -> v_mfma_f32_32x32x16_bf16, fp32 ->
+// v_mfma_f32_32x32x2_f32), fp32 accumulation.  The squared norms come from the same instruction
+// (a tile times itself: the diagonal is |x|^2), so a token identical to another one gets cos == 1 exactly.
+// The FD matrix is never written: an epilogue reduces each A row to (min FD, arg min) directly.
+//
+//   fd_partial_kernel : one workgroup = one 32x32 tile x one slice of the hidden axis; the four waves of
+//                       the workgroup take interleaved 128-byte runs of that slice straight from global
+//                       memory into MFMA operands (no LDS staging: nothing is reused across waves), are
+//                       summed through LDS and stored as a partial tile.
+//   fd_epilogue_kernel: sums the partial tiles over the slices in a fixed order (fp64), forms
+//                       cos = dot / sqrt(|a|^2 |b|^2), FD = max(1 - cos, 0) and keeps the first minimum per row.
+#include "lk_common.h"
+#include "lk_launch.h"
+
+namespace lk {
+
+constexpr int FD_THREADS = 256;
+constexpr int FD_WAVES = 4;
+constexpr int FD_CHUNKS = 4;   // 16-byte chunks per lane and span
+constexpr double NORM_EPS = 1e-12;
+
+struct FdArgs {
+  const void *X;
+  int64_t ldx;
+  int d, n_windows, sum_n;
+  const int32_t *win_offsets, *win_tokens;
+  float *partial;
+  float *best_fd;
+  int32_t *best_dst;
+  int slot, group, mt, nt, n_tiles, ksplit, n_spans, spans_per_wg;
+};
+
+struct WinInfo { int off, nA, nB; };
+
+__device__ __forceinline__ WinInfo win_info(const FdArgs &g, int w) {
+  WinInfo wi{0, 0, 0};
+  if (w < g.n_windows) {
+    wi.off = g.win_offsets[w];
+    const int v = g.win_offsets[w + 1] - wi.off;
+    wi.nA = (v + 1) >> 1;
+    wi.nB = v >> 1;
+  }
+  return wi;
+}
+
+__device__ __forceinline__ int checked_token(const FdArgs &g, int idx) {
+  const int t = g.win_tokens[idx];
+  return ((unsigned)t < (unsigned)g.sum_n) ? t : -1;
+}
+
+template <typename T>
+__global__ __launch_bounds__(FD_THREADS) void fd_partial_kernel(FdArgs g) {
+  using E = Elem<T>;
+  constexpr int EPC = E::PER_CHUNK;
+  constexpr int LANE_ELEMS = FD_CHUNKS * EPC;   // contiguous elements of one lane in a span
+  constexpr int SPAN = 2 * LANE_ELEMS;          // elements of a row covered by one span
+
+  __shared__ float red[FD_WAVES][32 * 32];
+  __shared__ float rnorm[FD_WAVES][2][32];
+
+  const int tile = blockIdx.x % g.n_tiles;
+  const int ks = blockIdx.x / g.n_tiles;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 31, half = lane >> 5;
+
+  // rows of this tile
+  int a_tok = -1, b_tok = -1;
+  bool need_na = true, need_nb = true;
+  if (g.group > 1) {
+    const int s = r / g.slot, l = r - s * g.slot;
+    const WinInfo wi = win_info(g, tile * g.group + s);
+    if (l < wi.nA) a_tok = checked_token(g, wi.off + 2 * l);
+    if (l < wi.nB) b_tok = checked_token(g, wi.off + 2 * l + 1);
+  } else {
+    const int per = g.mt * g.nt;
+    const int w = tile / per, rem = tile - w * per;
+    const int mt = rem / g.nt, nt = rem - mt * g.nt;
+    const WinInfo wi = win_info(g, w);
+    const int la = mt * 32 + r, lb = nt * 32 + r;
+    if (la < wi.nA) a_tok = checked_token(g, wi.off + 2 * la);
+    if (lb < wi.nB) b_tok = checked_token(g, wi.off + 2 * lb + 1);
+    need_na = (nt == 0);
+    need_nb = (mt == 0);
+  }
+  // a tile without A rows or without B rows is never read by the epilogue
+  if (__ballot(a_tok >= 0) == 0ull || __ballot(b_tok >= 0) == 0ull) return;
+
+  const char *pa = static_cast<const char *>(g.X) + (int64_t)(a_tok < 0 ? 0 : a_tok) * g.ldx * E::BYTES;
+  const char *pb = static_cast<const char *>(g.X) + (int64_t)(b_tok < 0 ? 0 : b_tok) * g.ldx * E::BYTES;
+
+  f32x16 acc = {0}, na = {0}, nb = {0};
+  const int s_begin = ks * g.spans_per_wg;
+  const int s_end = min(s_begin + g.spans_per_wg, g.n_spans);
+
+  uint4 ca[FD_CHUNKS], cb[FD_CHUNKS];
+  auto load_span = [&](int s, uint4 *va, uint4 *vb) {
+    const int e0 = s * SPAN + half * LANE_ELEMS;
+#pragma unroll
+    for (int c = 0; c < FD_CHUNKS; ++c) {
+      const int e = e0 + c * EPC;
+      const bool ok = (e + EPC <= g.d);
+      va[c] = (ok && a_tok >= 0) ? ld16(pa + (int64_t)e * E::BYTES) : make_uint4(0, 0, 0, 0);
+      vb[c] = (ok && b_tok >= 0) ? ld16(pb + (int64_t)e * E::BYTES) : make_uint4(0, 0, 0, 0);
+    }
+  };
+
+  int s = s_begin + wave;
+  if (s < s_end) load_span(s, ca, cb);
+  while (s < s_end) {
+    uint4 na_next[FD_CHUNKS], nb_next[FD_CHUNKS];
+    const int sn = s + FD_WAVES;
+    if (sn < s_end) load_span(sn, na_next, nb_next);
+#pragma unroll
+    for (int c = 0; c < FD_CHUNKS; ++c) {
+      E::mma32(ca[c], cb[c], acc);
+      if (need_na) E::mma32(ca[c], ca[c], na);
+      if (need_nb) E::mma32(cb[c], cb[c], nb);
+    }
+    if (sn < s_end) {
+#pragma unroll
+      for (int c = 0; c < FD_CHUNKS; ++c) { ca[c] = na_next[c]; cb[c] = nb_next[c]; }
+    }
+    s = sn;
+  }
+
+  // cross-wave sum through LDS
+#pragma unroll
+  for (int i = 0; i < 16; ++i) red[wave][acc_row(i, lane) * 32 + r] = acc[i];
+  if (((r >> 2) & 1) == half) {   // this lane holds the diagonal element (r, r)
+    const int idx = 4 * (r >> 3) + (r & 3);
+    float da = 0.f, db = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      da = (i == idx) ? na[i] : da;
+      db = (i == idx) ? nb[i] : db;
+    }
+    rnorm[wave][0][r] = da;
+    rnorm[wave][1][r] = db;
+  }
+  __syncthreads();
+  float *out = g.partial + ((int64_t)ks * g.n_tiles + tile) * FD_TILE_FLOATS;
+  for (int e = threadIdx.x; e < 32 * 32; e += FD_THREADS)
+    out[e] = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+  if (threadIdx.x < 64) {
+    const int which = threadIdx.x >> 5, i = threadIdx.x & 31;
+    out[32 * 32 + threadIdx.x] = (rnorm[0][which][i] + rnorm[1][which][i]) + (rnorm[2][which][i] + rnorm[3][which][i]);
+  }
+}
+
+// One workgroup per 32 A rows.  Lanes of a half-wave sweep the columns of one row.
+__global__ __launch_bounds__(FD_THREADS) void fd_epilogue_kernel(FdArgs g) {
+  __shared__ double nb2[FD_MAX_COLS];
+  const int rb = blockIdx.x;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int c32 = lane & 31, rsub = lane >> 5;
+  const int64_t ks_stride = (int64_t)g.n_tiles * FD_TILE_FLOATS;
+  const int per = g.mt * g.nt;
+
+  // columns whose norms this row block needs
+  int tile_row0;            // tile holding the dots of (this row block, column tile 0)
+  int tile_col0;            // tile holding |b|^2 of column tile 0
+  int w_single = 0, m_single = 0;
+  if (g.group > 1) {
+    tile_row0 = tile_col0 = rb;
+  } else {
+    w_single = rb / g.mt;
+    m_single = rb - w_single * g.mt;
+    tile_row0 = w_single * per + m_single * g.nt;
+    tile_col0 = w_single * per;
+  }
+  const int ncol_tiles = (g.group > 1) ? 1 : g.nt;
+  for (int c = threadIdx.x; c < ncol_tiles * 32; c += FD_THREADS) {
+    const float *p = g.partial + (int64_t)(tile_col0 + (c >> 5)) * FD_TILE_FLOATS + 32 * 32 + 32 + (c & 31);
+    double sum = 0.0;
+    for (int ks = 0; ks < g.ksplit; ++ks) sum += (double)p[ks * ks_stride];
+    nb2[c] = sum;
+  }
+  __syncthreads();
+
+  for (int rp = 0; rp < 4; ++rp) {
+    const int r = wave * 8 + rp * 2 + rsub;
+    WinInfo wi;
+    int l, col_base;   // local A position; first tile column of this row's window
+    if (g.group > 1) {
+      const int s = r / g.slot;
+      l = r - s * g.slot;
+      wi = win_info(g, rb * g.group + s);
+      col_base = s * g.slot;
+    } else {
+      wi = win_info(g, w_single);
+      l = m_single * 32 + r;
+      col_base = 0;
+    }
+    const bool a_valid = l < wi.nA;
+    const int col_cap = (g.group > 1) ? g.slot : g.nt * 32;   // columns this launch really tiled
+    if (wi.nB > col_cap) wi.nB = col_cap;
+    double best = __longlong_as_double(0x7ff0000000000000ll);   // +inf
+    int best_c = 0x7fffffff;
+    if (a_valid && wi.nB > 0) {
+      const float *pn = g.partial + (int64_t)tile_row0 * FD_TILE_FLOATS + 32 * 32 + r;
+      double na2 = 0.0;
+      for (int ks = 0; ks < g.ksplit; ++ks) na2 += (double)pn[ks * ks_stride];
+      for (int c = c32; c < wi.nB; c += 32) {
+        const int tc = col_base + c;   // column inside this row block's tile row
+        const float *p = g.partial + (int64_t)(tile_row0 + (tc >> 5)) * FD_TILE_FLOATS + r * 32 + (tc & 31);
+        double dot = 0.0;
+        for (int ks = 0; ks < g.ksplit; ++ks) dot += (double)p[ks * ks_stride];
+        const double b2 = nb2[tc];
+        double den;
+        if (na2 >= NORM_EPS * NORM_EPS && b2 >= NORM_EPS * NORM_EPS) den = sqrt(na2 * b2);
+        else den = fmax(sqrt(na2), NORM_EPS) * fmax(sqrt(b2), NORM_EPS);
+        const double fd = fmax(1.0 - dot / den, 0.0);
+        if (fd < best) { best = fd; best_c = c; }   // columns ascend: strict < keeps the first minimum
+      }
+    }
+    // reduce over the 32 lanes of the half-wave
+#pragma unroll
+    for (int m = 16; m >= 1; m >>= 1) {
+      const double ob = __shfl_xor(best, m, 64);
+      const int oc = __shfl_xor(best_c, m, 64);
+      if (ob < best || (ob == best && oc < best_c)) { best = ob; best_c = oc; }
+    }
+    if (c32 == 0 && a_valid) {
+      const int a_tok = checked_token(g, wi.off + 2 * l);
+      if (a_tok >= 0) {
+        // no finite score at all (NaN rows): propose the first B node with FD = +inf, so that counts stay exact
+        const bool has = best_c != 0x7fffffff;
+        g.best_fd[a_tok] = has ? (float)best : __uint_as_float(0x7f800000u);
+        g.best_dst[a_tok] = (wi.nB > 0) ? checked_token(g, wi.off + 2 * (has ? best_c : 0) + 1) : -1;
+      }
+    }
+    if (c32 == 1 && l < wi.nB) {   // B rows carry no proposal
+      const int b_tok = checked_token(g, wi.off + 2 * l + 1);
+      if (b_tok >= 0) {
+        g.best_fd[b_tok] = __uint_as_float(0x7f800000u);
+        g.best_dst[b_tok] = -1;
+      }
+    }
+  }
+}
+
+FdPlan make_fd_plan(int n_windows, int max_window_tokens, int d, int dtype_bytes) {
+  FdPlan p{};
+  const int maxA = (max_window_tokens + 1) / 2, maxB = max_window_tokens / 2;
+  if (maxA <= 16) {
+    p.slot = maxA <= 8 ? 8 : 16;
+    p.group = 32 / p.slot;
+    p.mt = p.nt = 1;
+    p.n_tiles = (n_windows + p.group - 1) / p.group;
+    p.n_rowblocks = p.n_tiles;
+  } else {
+    p.slot = 0;
+    p.group = 1;
+    p.mt = (maxA + 31) / 32;
+    p.nt = maxB > 0 ? (maxB + 31) / 32 : 1;
+    p.n_tiles = n_windows * p.mt * p.nt;
+    p.n_rowblocks = n_windows * p.mt;
+  }
+  const int span = (dtype_bytes == 2) ? 64 : 32;
+  const int n_spans = (d + span - 1) / span;
+  const int max_ks = n_spans / FD_WAVES > 0 ? n_spans / FD_WAVES : 1;
+  int ks = 1;
+  while ((int64_t)p.n_tiles * ks < 1024 && ks * 2 <= max_ks) ks *= 2;
+  p.ksplit = ks;
+  p.partial_floats = (size_t)p.n_tiles * ks * FD_TILE_FLOATS;
+  return p;
+}
+
+hipError_t launch_fd(const FdPlan &plan, int dtype, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
+                     const int32_t *win_offsets, const int32_t *win_tokens, float *partial, float *best_fd,
+                     int32_t *best_dst, hipStream_t stream) {
+  if (n_windows == 0 || plan.n_tiles == 0) return hipSuccess;
+  FdArgs g{};
+  g.X = X; g.ldx = ldx; g.d = d; g.n_windows = n_windows; g.sum_n = sum_n;
+  g.win_offsets = win_offsets; g.win_tokens = win_tokens;
+  g.partial = partial; g.best_fd = best_fd; g.best_dst = best_dst;
+  g.slot = plan.slot; g.group = plan.group; g.mt = plan.mt; g.nt = plan.nt;
+  g.n_tiles = plan.n_tiles; g.ksplit = plan.ksplit;
+  const int span = (dtype == 1) ? 64 : 32;
+  g.n_spans = (d + span - 1) / span;
+  g.spans_per_wg = (g.n_spans + plan.ksplit - 1) / plan.ksplit;
+  const dim3 grid((unsigned)(plan.n_tiles * plan.ksplit));
+  if (dtype == 1) hipLaunchKernelGGL(fd_partial_kernel<bf16_t>, grid, dim3(FD_THREADS), 0, stream, g);
+  else hipLaunchKernelGGL(fd_partial_kernel<float>, grid, dim3(FD_THREADS), 0, stream, g);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fd_epilogue_kernel, dim3((unsigned)plan.n_rowblocks), dim3(FD_THREADS), 0, stream, g);
+  return hipGetLastError();
+}
+
+}  // namespace lk

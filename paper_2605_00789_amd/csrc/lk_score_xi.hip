@@ -1,0 +1,277 @@
+// Prompt-guidance weight xi (paper Sec. 3.2.1 Step 3, Eq. "attention-factor"):
+//   xi_i = sum over heads h and prompt tokens j of the attention weight between vision token i and j.
+// The logits q.k * scale of one head are a (prompt x vision x head_dim) contraction and run on the
+// matrix cores; nothing of the attention matrix is ever written to memory.
+//
+//   text-query mode, no lse handed in:
+//     pass 1  per (sequence, head, 32 prompt rows, vision split): row maximum and sum of exponentials over
+//             the vision keys, kept online, one (max, sum) pair per split.
+//     pass 2  per (sequence, head, 128 vision tokens): merges the pairs of its prompt rows, recomputes the
+//             logits and adds exp(logit - max) / sum over the prompt rows -> per-head partial xi.
+//   lse handed in (either mode): pass 2 only.
+//   pass 3  sums the heads in a fixed order and applies the floor.
+// The operand whose index must be reduced inside a lane is always fed as the MFMA row operand:
+// accumulator registers run over rows, lanes over columns, so both reductions stay in registers.
+#include "lk_common.h"
+#include "lk_launch.h"
+
+namespace lk {
+
+constexpr int XI_THREADS = 256;
+constexpr float XI_FLOOR = 1e-30f;
+constexpr float LOG2E = 1.4426950408889634f;
+
+struct XiArgs {
+  const void *vis, *txt;                 // vision-side and prompt-side tensors of the contraction
+  int64_t vis_ts, vis_hs, txt_ts, txt_hs;   // token / head strides in elements
+  const int32_t *cu_vis, *cu_txt;
+  const float *lse;                      // optional, natural log
+  float scale_log2;                      // softmax scale * log2(e)
+  float *stats;                          // [heads][sum_t][vsplit][2]  (max, sum) in the exp2 domain
+  float *xi_part;                        // [heads][sum_n]
+  float *xi;                             // [sum_n]
+  int batch, heads, sum_n, sum_t, vsplit, max_text_tiles, max_vis_blocks;
+  int lse_per_vision;                    // 1: lse indexed [h][vision token] (vision-query mode)
+};
+
+template <typename T, int DH> struct XiShape {
+  using E = Elem<T>;
+  static constexpr int NCH = DH / 2 / E::PER_CHUNK;   // 16-byte chunks per lane: half a head row
+};
+
+template <typename T, int DH>
+__device__ __forceinline__ void load_half_row(const void *base, int64_t elem_off, bool valid, int half, uint4 *v) {
+  using E = Elem<T>;
+  const char *p = static_cast<const char *>(base) + (elem_off + half * (DH / 2)) * E::BYTES;
+#pragma unroll
+  for (int c = 0; c < XiShape<T, DH>::NCH; ++c) v[c] = valid ? ld16(p + c * 16) : make_uint4(0, 0, 0, 0);
+}
+
+// ---- pass 1: online (max, sum) of every prompt row over the vision keys -------------------------
+template <typename T, int DH>
+__global__ __launch_bounds__(XI_THREADS) void xi_rowstat_kernel(XiArgs g) {
+  using E = Elem<T>;
+  constexpr int NCH = XiShape<T, DH>::NCH;
+  __shared__ float sm[4][32], ss[4][32];
+
+  int id = blockIdx.x;
+  const int vs = id % g.vsplit; id /= g.vsplit;
+  const int tt = id % g.max_text_tiles; id /= g.max_text_tiles;
+  const int h = id % g.heads;
+  const int b = id / g.heads;
+  const int t0 = g.cu_txt[b], nT = g.cu_txt[b + 1] - t0;
+  const int v0 = g.cu_vis[b], nV = g.cu_vis[b + 1] - v0;
+  if (tt * 32 >= nT) return;
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 31, half = lane >> 5;
+  const int j = tt * 32 + r;   // prompt row of this lane's column
+
+  uint4 q[NCH];
+  load_half_row<T, DH>(g.txt, (int64_t)(t0 + j) * g.txt_ts + (int64_t)h * g.txt_hs, j < nT, half, q);
+
+  const float NEG_INF = __uint_as_float(0xff800000u);
+  float m_run = NEG_INF, s_run = 0.f;
+  const int n_vt = (nV + 31) >> 5;
+  for (int vt = vs * 4 + wave; vt < n_vt; vt += g.vsplit * 4) {
+    const int i = vt * 32 + r;
+    uint4 k[NCH];
+    load_half_row<T, DH>(g.vis, (int64_t)(v0 + i) * g.vis_ts + (int64_t)h * g.vis_hs, i < nV, half, k);
+    f32x16 acc = {0};
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) E::mma32(k[c], q[c], acc);   // rows: vision tokens, cols: prompt rows
+    float t[16];
+    float tmax = NEG_INF;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      const bool ok = (vt * 32 + acc_row(x, lane)) < nV;
+      t[x] = ok ? acc[x] * g.scale_log2 : NEG_INF;
+      tmax = fmaxf(tmax, t[x]);
+    }
+    if (tmax > NEG_INF) {
+      const float m_new = fmaxf(m_run, tmax);
+      float s = 0.f;
+#pragma unroll
+      for (int x = 0; x < 16; ++x) s += exp2f(t[x] - m_new);   // exp2(-inf) = 0 for masked rows
+      s_run = s_run * exp2f(m_run - m_new) + s;
+      m_run = m_new;
+    }
+  }
+  // the two half-waves hold different rows of the same column
+  {
+    const float om = __shfl_xor(m_run, 32, 64), os = __shfl_xor(s_run, 32, 64);
+    const float m_new = fmaxf(m_run, om);
+    if (m_new > NEG_INF) s_run = s_run * exp2f(m_run - m_new) + os * exp2f(om - m_new);
+    m_run = m_new;
+  }
+  if (half == 0) { sm[wave][r] = m_run; ss[wave][r] = s_run; }
+  __syncthreads();
+  if (threadIdx.x < 32 && j < nT) {
+    float m = NEG_INF;
+    for (int w = 0; w < 4; ++w) m = fmaxf(m, sm[w][r]);
+    float s = 0.f;
+    if (m > NEG_INF)
+      for (int w = 0; w < 4; ++w) s += ss[w][r] * exp2f(sm[w][r] - m);
+    float *o = g.stats + (((int64_t)h * g.sum_t + t0 + j) * g.vsplit + vs) * 2;
+    o[0] = m;
+    o[1] = s;
+  }
+}
+
+// ---- pass 2: column sums of exp(logit - lse) over the prompt rows -----------------------------------
+template <typename T, int DH, bool VISION_LSE>
+__global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
+  using E = Elem<T>;
+  constexpr int NCH = XiShape<T, DH>::NCH;
+  extern __shared__ float2 rowstat[];   // per prompt row: (max in exp2 domain, 1/sum)
+
+  int id = blockIdx.x;
+  const int blk = id % g.max_vis_blocks; id /= g.max_vis_blocks;
+  const int h = id % g.heads;
+  const int b = id / g.heads;
+  const int t0 = g.cu_txt[b], nT = g.cu_txt[b + 1] - t0;
+  const int v0 = g.cu_vis[b], nV = g.cu_vis[b + 1] - v0;
+  if (blk * 128 >= nV) return;
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 31, half = lane >> 5;
+  const float NEG_INF = __uint_as_float(0xff800000u);
+
+  if (!VISION_LSE) {
+    for (int j = threadIdx.x; j < nT; j += XI_THREADS) {
+      float m, inv;
+      if (g.lse) {
+        m = g.lse[(int64_t)h * g.sum_t + t0 + j] * LOG2E;
+        inv = 1.f;
+      } else {
+        const float *p = g.stats + ((int64_t)h * g.sum_t + t0 + j) * g.vsplit * 2;
+        m = NEG_INF;
+        for (int s = 0; s < g.vsplit; ++s) m = fmaxf(m, p[2 * s]);
+        float sum = 0.f;
+        for (int s = 0; s < g.vsplit; ++s) sum += (p[2 * s] > NEG_INF) ? p[2 * s + 1] * exp2f(p[2 * s] - m) : 0.f;
+        inv = 1.f / sum;
+      }
+      rowstat[j] = make_float2(m, inv);
+    }
+    __syncthreads();
+  }
+
+  const int i = blk * 128 + wave * 32 + r;   // vision token of this lane's column
+  uint4 k[NCH];
+  load_half_row<T, DH>(g.vis, (int64_t)(v0 + i) * g.vis_ts + (int64_t)h * g.vis_hs, i < nV, half, k);
+  float col_m = 0.f;
+  if (VISION_LSE) col_m = (i < nV) ? g.lse[(int64_t)h * g.sum_n + v0 + i] * LOG2E : 0.f;
+
+  float colsum = 0.f;
+  const int n_tt = (nT + 31) >> 5;
+  for (int tt = 0; tt < n_tt; ++tt) {
+    const int j = tt * 32 + r;
+    uint4 q[NCH];
+    load_half_row<T, DH>(g.txt, (int64_t)(t0 + j) * g.txt_ts + (int64_t)h * g.txt_hs, j < nT, half, q);
+    f32x16 acc = {0};
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) E::mma32(q[c], k[c], acc);   // rows: prompt tokens, cols: vision tokens
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      const int row = tt * 32 + acc_row(x, lane);
+      if (row < nT) {
+        if (VISION_LSE) {
+          colsum += exp2f(acc[x] * g.scale_log2 - col_m);
+        } else {
+          const float2 st = rowstat[row];
+          colsum += exp2f(acc[x] * g.scale_log2 - st.x) * st.y;
+        }
+      }
+    }
+  }
+  colsum += __shfl_xor(colsum, 32, 64);
+  if (half == 0 && i < nV) g.xi_part[(int64_t)h * g.sum_n + v0 + i] = colsum;
+}
+
+// ---- pass 3: heads summed in a fixed order, floor applied ---------------------------------------------
+__global__ __launch_bounds__(256) void xi_heads_kernel(XiArgs g) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= g.sum_n) return;
+  float s = 0.f;
+  for (int h = 0; h < g.heads; ++h) s += g.xi_part[(int64_t)h * g.sum_n + i];
+  g.xi[i] = fmaxf(s, XI_FLOOR);
+}
+
+XiPlan make_xi_plan(int batch, const int32_t *h_cu_vis, const int32_t *h_cu_txt, int heads, int xi_mode) {
+  XiPlan p{};
+  if (xi_mode == 2 || !h_cu_txt) return p;
+  int max_t = 0, max_n = 0;
+  for (int b = 0; b < batch; ++b) {
+    max_t = h_cu_txt[b + 1] - h_cu_txt[b] > max_t ? h_cu_txt[b + 1] - h_cu_txt[b] : max_t;
+    max_n = h_cu_vis[b + 1] - h_cu_vis[b] > max_n ? h_cu_vis[b + 1] - h_cu_vis[b] : max_n;
+  }
+  p.max_text_tiles = (max_t + 31) / 32;
+  p.max_vis_blocks = (max_n + 127) / 128;
+  // pass 1: enough workgroups to fill the chip, but at least four vision tiles (one per wave) per workgroup
+  const int64_t jobs = (int64_t)batch * heads * (p.max_text_tiles > 0 ? p.max_text_tiles : 1);
+  const int max_split = p.max_vis_blocks > 0 ? p.max_vis_blocks : 1;
+  int vs = 1;
+  while (jobs * vs < 1024 && vs * 2 <= max_split) vs *= 2;
+  p.vsplit = vs;
+  p.stat_floats = (size_t)heads * (size_t)h_cu_txt[batch] * vs * 2;
+  p.part_floats = (size_t)heads * (size_t)h_cu_vis[batch];
+  return p;
+}
+
+template <typename T, int DH>
+static hipError_t launch_xi_t(const XiPlan &plan, const XiArgs &g, int xi_mode, int max_t, hipStream_t stream) {
+  const bool vision_lse = (xi_mode == 1);
+  if (xi_mode == 0 && g.lse == nullptr) {
+    const unsigned grid = (unsigned)(g.batch * g.heads * plan.max_text_tiles * plan.vsplit);
+    if (grid) hipLaunchKernelGGL((xi_rowstat_kernel<T, DH>), dim3(grid), dim3(XI_THREADS), 0, stream, g);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const unsigned grid2 = (unsigned)(g.batch * g.heads * plan.max_vis_blocks);
+  if (grid2) {
+    if (vision_lse)
+      hipLaunchKernelGGL((xi_colsum_kernel<T, DH, true>), dim3(grid2), dim3(XI_THREADS), 0, stream, g);
+    else
+      hipLaunchKernelGGL((xi_colsum_kernel<T, DH, false>), dim3(grid2), dim3(XI_THREADS),
+                         (size_t)max_t * sizeof(float2), stream, g);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (g.sum_n) hipLaunchKernelGGL(xi_heads_kernel, dim3((unsigned)((g.sum_n + 255) / 256)), dim3(256), 0, stream, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_xi(const XiPlan &plan, int dtype, int xi_mode, int batch, int heads, int head_dim, int sum_n,
+                     int sum_t, const int32_t *cu_vis, const int32_t *cu_txt, const void *Q, int64_t q_tok_stride,
+                     int64_t q_head_stride, const void *K, int64_t k_tok_stride, int64_t k_head_stride,
+                     const float *lse, float scale, float *stats, float *xi_part, float *xi, hipStream_t stream) {
+  XiArgs g{};
+  if (xi_mode == 0) {   // prompt queries against vision keys
+    g.vis = K; g.vis_ts = k_tok_stride; g.vis_hs = k_head_stride;
+    g.txt = Q; g.txt_ts = q_tok_stride; g.txt_hs = q_head_stride;
+  } else {              // vision queries against prompt keys
+    g.vis = Q; g.vis_ts = q_tok_stride; g.vis_hs = q_head_stride;
+    g.txt = K; g.txt_ts = k_tok_stride; g.txt_hs = k_head_stride;
+  }
+  g.cu_vis = cu_vis; g.cu_txt = cu_txt; g.lse = lse;
+  g.scale_log2 = scale * LOG2E;
+  g.stats = stats; g.xi_part = xi_part; g.xi = xi;
+  g.batch = batch; g.heads = heads; g.sum_n = sum_n; g.sum_t = sum_t;
+  g.vsplit = plan.vsplit; g.max_text_tiles = plan.max_text_tiles; g.max_vis_blocks = plan.max_vis_blocks;
+  g.lse_per_vision = (xi_mode == 1);
+  const int max_t = plan.max_text_tiles * 32;
+#define LK_XI_CASE(TT, DHV) return launch_xi_t<TT, DHV>(plan, g, xi_mode, max_t, stream)
+  if (dtype == 1) {
+    if (head_dim == 128) LK_XI_CASE(bf16_t, 128);
+    if (head_dim == 64) LK_XI_CASE(bf16_t, 64);
+    if (head_dim == 32) LK_XI_CASE(bf16_t, 32);
+  } else {
+    if (head_dim == 128) LK_XI_CASE(float, 128);
+    if (head_dim == 64) LK_XI_CASE(float, 64);
+    if (head_dim == 32) LK_XI_CASE(float, 32);
+  }
+#undef LK_XI_CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace lk

@@ -1,0 +1,131 @@
+"""Buffer ownership and call order for the hierarchical schedule (paper Sec. 3.2.2): every stage calls
+lightkv_build_windows -> lightkv_score -> lightkv_select -> lightkv_aggregate_compact (or the separate
+lightkv_aggregate + lightkv_compact) on one stream, without host synchronisation.  All device buffers are
+allocated once in the constructor; `run` only enqueues kernels."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .schedule import max_window_cells, removal_counts, windows_per_sequence
+
+
+@dataclass
+class StageBuffers:
+    n_in: int
+    n_out: int
+    w: int
+    problem: B.Problem
+    h_cu_vis: np.ndarray
+    cu_vis: torch.Tensor
+    win_offsets: torch.Tensor
+    win_tokens: torch.Tensor
+    win_remove: torch.Tensor
+    h_win_remove: np.ndarray
+    xi: torch.Tensor
+    best_fd: torch.Tensor
+    best_dst: torch.Tensor
+    dst: torch.Tensor
+    new_index: torch.Tensor
+    grp_offsets: torch.Tensor
+    grp_src: torch.Tensor
+    cu_vis_out: torch.Tensor
+    X_out: torch.Tensor
+    K_out: torch.Tensor
+    V_out: torch.Tensor
+    pos_out: torch.Tensor
+
+
+class CompressionPipeline:
+    def __init__(self, *, dtype: str, batch: int, d: int, heads: int, head_dim: int, tiles: int, grid_h: int,
+                 grid_w: int, cu_txt: np.ndarray, windows_per_axis: Sequence[int], targets: Sequence[int],
+                 device="cuda:0", fused: bool = True):
+        self.dtype, self.batch, self.d, self.heads, self.head_dim = dtype, batch, d, heads, head_dim
+        self.tiles, self.grid_h, self.grid_w = tiles, grid_h, grid_w
+        self.device = torch.device(device)
+        self.fused = fused
+        self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.h_cu_txt = np.ascontiguousarray(cu_txt, dtype=np.int32)
+        self.cu_txt = torch.from_numpy(self.h_cu_txt).to(self.device)
+        dev = self.device
+        i32 = dict(dtype=torch.int32, device=dev)
+        n_in = tiles * grid_h * grid_w
+        self.stages: List[StageBuffers] = []
+        ws_bytes = 0
+        for w, n_out in zip(windows_per_axis, targets):
+            sum_in, sum_out = batch * n_in, batch * n_out
+            wps = windows_per_sequence(tiles, w)
+            n_windows = batch * wps
+            h_cu = (np.arange(batch + 1, dtype=np.int32) * n_in).astype(np.int32)
+            cu = torch.from_numpy(h_cu).to(dev)
+            h_rem = removal_counts(batch, n_in, n_out, wps)
+            win_offsets = torch.empty(n_windows + 1, **i32)
+            win_tokens = torch.empty(max(sum_in, 1), **i32)
+            win_remove = torch.from_numpy(h_rem).to(dev)
+            bound = min(max_window_cells(tiles, grid_h, grid_w, w), n_in)
+            prob = B.Problem(batch=batch, d=d, heads=heads, head_dim=head_dim, dtype=dtype, h_cu_vis=h_cu,
+                             cu_vis=cu, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt, n_windows=n_windows,
+                             max_window_tokens=bound, win_offsets=win_offsets, win_tokens=win_tokens,
+                             win_remove=win_remove, h_win_remove=None)
+            ws_bytes = max(ws_bytes, B.lightkv_workspace_size(prob))
+            st = StageBuffers(
+                n_in=n_in, n_out=n_out, w=w, problem=prob, h_cu_vis=h_cu, cu_vis=cu, win_offsets=win_offsets,
+                win_tokens=win_tokens, win_remove=win_remove, h_win_remove=h_rem,
+                xi=torch.empty(sum_in, dtype=torch.float32, device=dev),
+                best_fd=torch.empty(sum_in, dtype=torch.float32, device=dev),
+                best_dst=torch.empty(sum_in, **i32), dst=torch.empty(sum_in, **i32),
+                new_index=torch.empty(sum_in, **i32), grp_offsets=torch.empty(sum_in + 1, **i32),
+                grp_src=torch.empty(max(sum_in - sum_out, 1), **i32), cu_vis_out=torch.empty(batch + 1, **i32),
+                X_out=torch.empty(sum_out, d, dtype=self.tdtype, device=dev),
+                K_out=torch.empty(sum_out, d, dtype=self.tdtype, device=dev),
+                V_out=torch.empty(sum_out, d, dtype=self.tdtype, device=dev),
+                pos_out=torch.empty(sum_out, **i32))
+            self.stages.append(st)
+            n_in = n_out
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        # scratch copies for the unfused path (aggregate works in place)
+        if not fused:
+            s0 = self.stages[0]
+            n0 = batch * s0.n_in
+            self.tmp = [torch.empty(n0, d, dtype=self.tdtype, device=dev) for _ in range(3)]
+
+    # one stage; inputs are device tensors of this stage's shape
+    def run_stage(self, s: int, X, K, V, Q, pos, *, xi_mode=B.XI_TEXT_QUERY, lse=None, softmax_scale=0.0,
+                  xi_given: Optional[torch.Tensor] = None, score_K=None, stream=None):
+        """score_K: keys of the xi contraction when they are not the K rows being merged
+        (vision-query mode: Q holds the vision queries, score_K the prompt keys)."""
+        st = self.stages[s]
+        p = st.problem
+        B.lightkv_build_windows(self.batch, st.h_cu_vis, st.cu_vis, pos, self.tiles, self.grid_h, self.grid_w, st.w,
+                                st.win_offsets, st.win_tokens, stream=stream)
+        xi = st.xi
+        if xi_given is not None:
+            xi = xi_given
+            xi_mode = B.XI_GIVEN
+        B.lightkv_score(p, X, Q, K if score_K is None else score_K, xi, st.best_fd, st.best_dst, self.ws, xi_mode=xi_mode, lse=lse,
+                        softmax_scale=softmax_scale, stream=stream)
+        B.lightkv_select(p, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets, st.grp_src,
+                         st.cu_vis_out, self.ws, stream=stream)
+        if self.fused:
+            B.lightkv_aggregate_compact(p, st.new_index, st.grp_offsets, st.grp_src, xi, X, K, V, pos, st.X_out,
+                                        st.K_out, st.V_out, st.pos_out, stream=stream)
+        else:
+            n = X.shape[0]
+            tx, tk, tv = (t[:n] for t in self.tmp)
+            tx.copy_(X); tk.copy_(K); tv.copy_(V)
+            B.lightkv_aggregate(p, st.grp_offsets, st.grp_src, xi, tx, tk, tv, stream=stream)
+            B.lightkv_compact(p, st.new_index, tx, tk, tv, pos, st.X_out, st.K_out, st.V_out, st.pos_out,
+                              stream=stream)
+        return st
+
+    def run(self, X, K, V, Q, pos, stream=None):
+        """All stages back to back; returns the last stage's buffers (its *_out tensors hold the result)."""
+        st = None
+        for s in range(len(self.stages)):
+            st = self.run_stage(s, X, K, V, Q, pos, stream=stream)
+            X, K, V, pos = st.X_out, st.K_out, st.V_out, st.pos_out
+        return st

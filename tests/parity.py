@@ -1,0 +1,202 @@
+"""Stage-by-stage comparison of the HIP path with the CPU oracle (used by the GPU tests, the smoke
+check and nothing else).  Every stage is "teacher forced": the oracle gets exactly the tensors the
+GPU stage consumed, so storage rounding of earlier stages cannot fork the selection.
+
+Tolerances (stated by the task's parity bar):
+  index sets       bit exact, except where the oracle's own fp64 scores are tied within 1e-6
+                   (relative on the cosine); such cases are verified by score, and counted
+  xi               relative 1e-3 (bf16 inputs) / 1e-5 (fp32)
+  best_fd          absolute 1e-5 (bf16 inputs) / 1e-6 (fp32)
+  X, K, V rows     per-row |delta|_2/|ref|_2 and max|delta|/max|ref| <= 2e-2 (bf16 I/O) / 1e-5 (fp32)
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+import torch
+
+from oracle import lightkv_oracle as O
+
+TIE_BAND = 1e-6
+
+
+def to_dev(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(device)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+def from_dev(t: torch.Tensor, dtype: str) -> np.ndarray:
+    t = t.detach().cpu().contiguous()
+    if dtype == "bf16":
+        return t.view(torch.int16).numpy().view(np.uint16).copy()
+    return t.numpy().copy()
+
+
+@dataclass
+class StageReport:
+    stage: int
+    n_in: int
+    n_out: int
+    edge_ties: int = 0          # A rows whose GPU partner differs from the oracle's but ties within the band
+    window_ties: int = 0        # windows whose merged set differs but ties within the band
+    max_xi_rel: float = 0.0
+    max_fd_abs: float = 0.0
+    max_row_rel: float = 0.0
+    max_elem_rel: float = 0.0
+    notes: list = field(default_factory=list)
+
+
+def check_stage(pipe, s: int, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_mode=0, lse=None, xi_given=None,
+                softmax_scale=None, Qdev=None, score_K=None, extra_run_kwargs=None) -> tuple:
+    """Runs stage s of `pipe` on the storage arrays (numpy) and checks every output against the oracle.
+    Returns (report, outputs as storage arrays)."""
+    st_cfg = pipe.stages[s]
+    batch = pipe.batch
+    dX, dK, dV = to_dev(Xs, dtype), to_dev(Ks, dtype), to_dev(Vs, dtype)
+    dQ = Qdev if Qdev is not None else (to_dev(Qs, dtype) if Qs is not None else None)
+    dpos = torch.from_numpy(np.ascontiguousarray(pos, dtype=np.int32)).to(dX.device)
+    kw = dict(extra_run_kwargs or {})
+    if lse is not None:
+        kw["lse"] = torch.from_numpy(np.ascontiguousarray(lse, dtype=np.float32)).to(dX.device)
+    if xi_given is not None:
+        kw["xi_given"] = torch.from_numpy(np.ascontiguousarray(xi_given, dtype=np.float32)).to(dX.device)
+    if softmax_scale is not None:
+        kw["softmax_scale"] = float(softmax_scale)
+    if score_K is not None:
+        kw["score_K"] = to_dev(score_K, dtype)
+    st = pipe.run_stage(s, dX, dK, dV, dQ, dpos, xi_mode=xi_mode, **kw)
+    torch.cuda.synchronize()
+
+    g = {k: getattr(st, k).cpu().numpy() for k in ("win_offsets", "win_tokens", "best_fd", "best_dst", "dst",
+                                                     "new_index", "grp_offsets", "grp_src", "cu_vis_out", "pos_out")}
+    g_xi = (st.xi.cpu().numpy() if xi_given is None else np.asarray(xi_given, dtype=np.float32))
+    rep = StageReport(stage=s, n_in=st_cfg.n_in, n_out=st_cfg.n_out)
+    bf16 = dtype == "bf16"
+
+    # ---- windows: exact
+    cu_vis = st_cfg.h_cu_vis
+    wo, wt = O.build_windows(pos, cu_vis, pipe.tiles, pipe.grid_h, pipe.grid_w, st_cfg.w)
+    np.testing.assert_array_equal(g["win_offsets"], wo, err_msg="win_offsets")
+    np.testing.assert_array_equal(g["win_tokens"][:len(wt)], wt, err_msg="win_tokens")
+    rem = st_cfg.h_win_remove
+
+    X64, K64, V64 = O.widen(Xs, dtype), O.widen(Ks, dtype), O.widen(Vs, dtype)
+    # ---- xi
+    if xi_given is None:
+        Q64 = O.widen(Qs, dtype)
+        lse64 = None if lse is None else np.asarray(lse, dtype=np.float32).astype(np.float64)
+        if xi_mode == 0:
+            xi_ref = O.xi_text_query(Q64, K64, cu_vis, pipe.h_cu_txt, pipe.heads, pipe.head_dim, scale=softmax_scale,
+                                     lse=lse64)
+        else:
+            xi_ref = O.xi_vision_query(Q64, O.widen(score_K, dtype), lse64, cu_vis, pipe.h_cu_txt, pipe.heads, pipe.head_dim,
+                                       scale=softmax_scale)
+        rel = np.abs(g_xi - xi_ref) / np.maximum(np.abs(xi_ref), 1e-300)
+        rep.max_xi_rel = float(rel.max()) if len(rel) else 0.0
+        assert rep.max_xi_rel <= (1e-3 if bf16 else 1e-5), "xi relative error %.3g" % rep.max_xi_rel
+    else:
+        xi_ref = np.asarray(xi_given, dtype=np.float64)
+
+    # ---- best edge per A node, then the merged set per window
+    n = X64.shape[0]
+    exp_new_removed = 0
+    for w in range(len(wo) - 1):
+        toks = wt[wo[w]:wo[w + 1]]
+        A, Bn = O.split_window(toks)
+        if len(Bn) == 0:
+            assert np.all(g["best_dst"][A] == -1) and np.all(np.isinf(g["best_fd"][A]))
+            assert np.all(g["dst"][toks] == -1)
+            continue
+        fd = O.feature_divergence(X64[A], X64[Bn])                # oracle's dense FD block (fp64)
+        j_ref = np.argmin(fd, axis=1)
+        f_ref = fd[np.arange(len(A)), j_ref]
+        assert np.all(g["best_dst"][Bn] == -1) and np.all(np.isinf(g["best_fd"][Bn]))
+        # partner: same index, or a score tie inside the band
+        b_gpu = g["best_dst"][A]
+        local = {int(t): k for k, t in enumerate(Bn)}
+        for la in np.nonzero(b_gpu != Bn[j_ref])[0]:
+            assert int(b_gpu[la]) in local, "partner of token %d is outside its window's B set" % A[la]
+            f_g = fd[la, local[int(b_gpu[la])]]
+            assert f_g <= f_ref[la] + TIE_BAND, "window %d row %d: partner FD %.9g vs best %.9g" % (w, la, f_g, f_ref[la])
+            rep.edge_ties += 1
+        err = np.abs(g["best_fd"][A].astype(np.float64) - f_ref)
+        rep.max_fd_abs = max(rep.max_fd_abs, float(err.max()))
+        # merged set
+        r = int(rem[w])
+        order = sorted(range(len(A)), key=lambda la: (f_ref[la], la))
+        ref_set = set(int(A[la]) for la in order[:r])
+        gpu_set = set(int(a) for a in A if g["dst"][a] >= 0)
+        assert len(gpu_set) == r, "window %d: %d merged, expected %d" % (w, len(gpu_set), r)
+        exp_new_removed += r
+        if gpu_set != ref_set:
+            tau = f_ref[order[r - 1]]
+            for la, a in enumerate(A):
+                if int(a) in gpu_set:
+                    assert f_ref[la] <= tau + TIE_BAND, "window %d: merged token %d has FD %.9g > threshold %.9g" % (w, a, f_ref[la], tau)
+                else:
+                    assert f_ref[la] >= tau - TIE_BAND, "window %d: kept token %d has FD %.9g < threshold %.9g" % (w, a, f_ref[la], tau)
+            rep.window_ties += 1
+        # a merged token goes to the partner the score step reported
+        for a in gpu_set:
+            assert g["dst"][a] == g["best_dst"][a]
+        assert np.all(g["dst"][Bn] == -1)
+    assert rep.max_fd_abs <= (1e-5 if bf16 else 1e-6), "best_fd abs error %.3g" % rep.max_fd_abs
+
+    # ---- index structures follow from dst: exact
+    dst = g["dst"]
+    np.testing.assert_array_equal(g["new_index"], O.kept_index(dst), err_msg="new_index")
+    go, gs = O.groups_csr(dst)
+    np.testing.assert_array_equal(g["grp_offsets"], go, err_msg="grp_offsets")
+    np.testing.assert_array_equal(g["grp_src"][:len(gs)], gs, err_msg="grp_src")
+    keep = dst < 0
+    cu_out = np.zeros(batch + 1, dtype=np.int32)
+    for b in range(batch):
+        cu_out[b + 1] = cu_out[b] + int(keep[cu_vis[b]:cu_vis[b + 1]].sum())
+    np.testing.assert_array_equal(g["cu_vis_out"], cu_out, err_msg="cu_vis_out")
+    n_out = int(keep.sum())
+    assert n_out == n - exp_new_removed == batch * st_cfg.n_out                  # kept + merged = N
+    np.testing.assert_array_equal(g["pos_out"][:n_out], np.asarray(pos)[keep], err_msg="pos_out")
+
+    # ---- values: oracle message passing on the GPU's (verified) selection
+    outs = {}
+    tol = 2e-2 if bf16 else 1e-5
+    for name, Y64, dev_out in (("X", X64, st.X_out), ("K", K64, st.K_out), ("V", V64, st.V_out)):
+        ref = O.compact(O.message_passing(Y64, xi_ref, dst), dst)
+        got_store = from_dev(dev_out[:n_out], dtype)
+        got = O.widen(got_store, dtype)
+        num = np.linalg.norm(got - ref, axis=1)
+        den = np.maximum(np.linalg.norm(ref, axis=1), 1e-300)
+        row_rel = float((num / den).max()) if n_out else 0.0
+        elem_rel = float((np.abs(got - ref).max(axis=1) / np.maximum(np.abs(ref).max(axis=1), 1e-300)).max()) if n_out else 0.0
+        rep.max_row_rel = max(rep.max_row_rel, row_rel)
+        rep.max_elem_rel = max(rep.max_elem_rel, elem_rel)
+        assert row_rel <= tol and elem_rel <= tol, "%s rows: rel %.3g / %.3g" % (name, row_rel, elem_rel)
+        # rows that were only copied are bit exact
+        untouched = (go[1:] - go[:-1])[keep] == 0
+        src_store = {"X": Xs, "K": Ks, "V": Vs}[name]
+        np.testing.assert_array_equal(got_store[untouched], np.asarray(src_store)[keep][untouched],
+                                      err_msg=name + " copied rows")
+        outs[name] = got_store
+    outs["pos"] = g["pos_out"][:n_out].copy()
+    outs["cu_vis"] = cu_out
+    outs["dst"] = dst
+    outs["xi"] = g_xi
+    return rep, outs
+
+
+def check_workload(wl, pipe=None, stages=None, fused=True):
+    """Runs all stages of a workload teacher-forced; returns the per-stage reports."""
+    from paper_2605_00789_amd import CompressionPipeline
+    if pipe is None:
+        pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                                   tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                                   windows_per_axis=wl.windows_per_axis, targets=wl.targets, fused=fused)
+    X, K, V, pos = wl.X, wl.K, wl.V, wl.pos
+    reports = []
+    for s in range(wl.stages if stages is None else stages):
+        rep, out = check_stage(pipe, s, X, K, V, wl.Q, pos, wl.dtype)
+        reports.append(rep)
+        X, K, V, pos = out["X"], out["K"], out["V"], out["pos"]
+    return reports

@@ -1,0 +1,143 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol, and rejects bad
+arguments before anything is launched (no GPU needed: validation happens on the host)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_00789_amd import binding
+    return binding
+
+
+def test_every_declared_symbol_is_exported(B):
+    header = open(os.path.join(ROOT, "include", "lightkv.h")).read()
+    declared = set(re.findall(r"^(?:const char \*|int |lightkv_status )(lightkv_[a-z_]+)\(", header, re.M))
+    assert declared == set(B.EXPORTS)
+    lib = C.CDLL(B.lib_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert B.lightkv_version() >= 100
+    assert B.lightkv_status_string(0) == "ok"
+    assert "half" not in B.lightkv_status_string(4) and "set A" in B.lightkv_status_string(4)
+    assert B.lightkv_status_string(99) == "unknown status"
+
+
+def _problem(B, **over):
+    """A descriptor whose device pointers are fake but non-NULL: only host-side validation may touch it."""
+    fake = 0x1000
+    h_cu_vis = np.array([0, 8], dtype=np.int32)
+    h_cu_txt = np.array([0, 4], dtype=np.int32)
+    h_wo = np.array([0, 4, 8], dtype=np.int32)
+    h_wr = np.array([1, 2], dtype=np.int32)
+    p = B._CProblem()
+    p.batch, p.d, p.heads, p.head_dim, p.dtype, p.n_windows, p.max_window_tokens = 1, 64, 2, 32, 1, 2, 0
+    keep = dict(h_cu_vis=h_cu_vis, h_cu_txt=h_cu_txt, h_win_offsets=h_wo, h_win_remove=h_wr)
+    for k, v in over.items():
+        if isinstance(v, np.ndarray):
+            keep[k] = v
+    for k in ("h_cu_vis", "h_cu_txt", "h_win_offsets", "h_win_remove"):
+        setattr(p, k, C.c_void_p(keep[k].ctypes.data))
+    for k in ("cu_vis", "cu_txt", "win_offsets", "win_tokens", "win_remove"):
+        setattr(p, k, C.c_void_p(fake))
+    for k, v in over.items():
+        if not isinstance(v, np.ndarray):
+            setattr(p, k, v)
+    p._keep = keep
+    return p
+
+
+def _ws_size(B, p):
+    out = C.c_size_t(0)
+    st = B._lib.lightkv_workspace_size(C.byref(p), C.byref(out))
+    return st, out.value
+
+
+def test_workspace_size_and_descriptor_validation(B):
+    st, n = _ws_size(B, _problem(B))
+    assert st == 0 and n > 0 and n % 256 == 0
+    assert B._lib.lightkv_workspace_size(None, C.byref(C.c_size_t(0))) == 1
+    assert B._lib.lightkv_workspace_size(C.byref(_problem(B)), None) == 1
+    assert _ws_size(B, _problem(B, h_cu_vis=None))[0] == 1                      # NULL
+    assert _ws_size(B, _problem(B, d=60))[0] == 5                               # 16-byte rows
+    assert _ws_size(B, _problem(B, heads=3))[0] == 2                            # heads*head_dim != d
+    assert _ws_size(B, _problem(B, d=96, heads=2, head_dim=48))[0] == 5         # head size
+    assert _ws_size(B, _problem(B, dtype=7))[0] == 5
+    assert _ws_size(B, _problem(B, batch=0))[0] == 2
+    assert _ws_size(B, _problem(B, h_cu_vis=np.array([1, 8], dtype=np.int32)))[0] == 2
+    assert _ws_size(B, _problem(B, h_cu_vis=np.array([0, 20000], dtype=np.int32),
+                                h_win_offsets=np.array([0, 4, 20000], dtype=np.int32)))[0] == 5   # sequence limit
+    assert _ws_size(B, _problem(B, h_win_offsets=np.array([0, 5, 7], dtype=np.int32)))[0] == 3    # not a partition
+    assert _ws_size(B, _problem(B, h_win_offsets=np.array([0, 6, 4], dtype=np.int32)))[0] == 3
+    assert _ws_size(B, _problem(B, h_win_offsets=np.array([1, 4, 8], dtype=np.int32)))[0] == 3
+    assert _ws_size(B, _problem(B, max_window_tokens=3))[0] == 3                # bound below the real size
+    assert _ws_size(B, _problem(B, h_win_remove=np.array([3, 0], dtype=np.int32)))[0] == 4        # r > |A|
+    assert _ws_size(B, _problem(B, h_win_remove=np.array([-1, 0], dtype=np.int32)))[0] == 4
+    assert _ws_size(B, _problem(B, h_win_remove=np.array([2, 2], dtype=np.int32)))[0] == 0        # r = |A| is the limit
+    # no host mirror: the bound becomes mandatory
+    assert _ws_size(B, _problem(B, h_win_offsets=None))[0] == 1
+    assert _ws_size(B, _problem(B, h_win_offsets=None, max_window_tokens=4))[0] == 0
+    assert _ws_size(B, _problem(B, h_win_offsets=None, max_window_tokens=5000))[0] == 5
+    # a one-token window cannot give up its token
+    assert _ws_size(B, _problem(B, h_win_offsets=np.array([0, 1, 8], dtype=np.int32),
+                                h_win_remove=np.array([1, 0], dtype=np.int32)))[0] == 4
+
+
+def test_entry_points_reject_bad_arguments_before_launch(B):
+    lib = B._lib
+    fake = C.c_void_p(0x1000)
+    p = _problem(B)
+    _, ws = _ws_size(B, p)
+    # score: NULL outputs, misaligned X, short row stride, bad mode, missing workspace
+    args = lambda **o: [o.get("p", C.byref(p)), o.get("X", fake), o.get("ldx", 64), fake, 64, 32, fake, 64, 32,
+                        o.get("mode", 0), o.get("lse", None), 0.0, o.get("xi", fake), fake, fake,
+                        o.get("ws", fake), o.get("wsb", ws), None]
+    assert lib.lightkv_score(*args(xi=None)) == 1
+    assert lib.lightkv_score(*args(X=C.c_void_p(0x1008))) == 5
+    assert lib.lightkv_score(*args(ldx=32)) == 2
+    assert lib.lightkv_score(*args(ldx=68)) == 5
+    assert lib.lightkv_score(*args(mode=3)) == 5
+    assert lib.lightkv_score(*args(mode=1)) == 1                                 # vision-query needs lse
+    assert lib.lightkv_score(*args(ws=None)) == 6
+    assert lib.lightkv_score(*args(wsb=ws - 1)) == 6
+    assert lib.lightkv_score(*args(ws=C.c_void_p(0x1010))) == 6                  # workspace alignment
+    # select
+    assert lib.lightkv_select(C.byref(p), fake, fake, None, fake, fake, fake, fake, fake, ws, None) == 1
+    assert lib.lightkv_select(C.byref(p), fake, fake, fake, fake, fake, fake, fake, fake, 16, None) == 6
+    # aggregate / compact
+    assert lib.lightkv_aggregate(C.byref(p), None, fake, fake, fake, 64, fake, 64, fake, 64, None) == 1
+    assert lib.lightkv_aggregate(C.byref(p), fake, fake, fake, fake, 8, fake, 64, fake, 64, None) == 2
+    other = C.c_void_p(0x100000)
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, fake, None, None, None, 8, None) == 2   # in == out
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, None, None, None, None, 8, None) == 1   # out missing
+    assert lib.lightkv_compact(C.byref(p), None, fake, 64, None, 0, None, 0, None, other, None, None, None, 8, None) == 1
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, fake, other, None, None, None, 8, None) == 1  # pos without pos_out
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, C.c_void_p(0x1100), None, None, None, 8, None) == 2  # overlap
+    # build_windows
+    hcu = np.array([0, 8], dtype=np.int32)
+    hp = C.c_void_p(hcu.ctypes.data)
+    assert lib.lightkv_build_windows(1, hp, fake, None, 1, 4, 2, 2, fake, fake, None) == 1
+    assert lib.lightkv_build_windows(1, hp, fake, fake, 0, 4, 2, 2, fake, fake, None) == 2
+    assert lib.lightkv_build_windows(1, hp, fake, fake, 1, 4, 2, -1, fake, fake, None) == 2
+    assert lib.lightkv_build_windows(1, hp, fake, fake, 1, 4, 2, 1000, fake, fake, None) == 5
+
+
+def test_schedule_helpers_agree_with_the_oracle():
+    from paper_2605_00789_amd.schedule import removal_counts, windows_per_sequence, max_window_cells
+    from oracle import lightkv_oracle as O
+    for batch, n_in, n_out, wps in ((1, 576, 472, 16), (16, 472, 387, 4), (1, 2880, 2360, 180), (2, 64, 36, 4), (1, 10, 10, 3)):
+        np.testing.assert_array_equal(removal_counts(batch, n_in, n_out, wps), O.stage_removals(batch, n_in, n_out, wps))
+    assert windows_per_sequence(5, 6) == 180 and windows_per_sequence(5, 0) == 1
+    assert max_window_cells(1, 24, 24, 4) == 36 and max_window_cells(5, 24, 24, 0) == 2880
+    # the bound really bounds every window the oracle builds, also on grids that do not divide
+    for gh, gw, w in ((24, 24, 6), (5, 7, 2), (7, 9, 4), (3, 3, 3)):
+        wo, _ = O.build_windows(np.arange(gh * gw), np.array([0, gh * gw]), 1, gh, gw, w)
+        assert np.diff(wo).max() == max_window_cells(1, gh, gw, w)
+    with pytest.raises(ValueError):
+        removal_counts(1, 10, 11, 2)

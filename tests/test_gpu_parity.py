@@ -1,0 +1,207 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, stage by stage."""
+import math
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _report(wl, reps):
+    for r in reps:
+        print("[parity] %s stage %d: %d -> %d | xi rel %.2e | fd abs %.2e | rows rel %.2e (elem %.2e) | "
+              "tie rows %d, tie windows %d" % (wl.name, r.stage, r.n_in, r.n_out, r.max_xi_rel, r.max_fd_abs,
+                                              r.max_row_rel, r.max_elem_rel, r.edge_ties, r.window_ties), flush=True)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 4, 3, "halving", "global", 5])
+def test_measured_configs_match_oracle(cfg):
+    from workloads import make_workload
+    from parity import check_workload
+    print("[parity] building workload", cfg, flush=True)
+    wl = make_workload(cfg)
+    reps = check_workload(wl)
+    _report(wl, reps)
+    assert [r.n_out for r in reps] == wl.targets
+
+
+@pytest.mark.parametrize("case", [
+    dict(name="odd_windows_bf16", dtype="bf16", batch=2, grid_h=7, grid_w=9, text_lens=(5, 33), d=256, heads=2,
+         head_dim=128, n_c=6, structure="iid", windows_per_axis=(2, 1), n_final=40),
+    dict(name="odd_windows_f32", dtype="f32", batch=3, grid_h=5, grid_w=5, text_lens=(1, 32, 47), d=192, heads=6,
+         head_dim=32, n_c=5, structure="iid", windows_per_axis=(2, 0), n_final=15),
+    dict(name="headdim64_bf16", dtype="bf16", batch=1, tiles=2, grid_h=10, grid_w=10, text_lens=(70,), d=320,
+         heads=5, head_dim=64, n_c=12, structure="grid", windows_per_axis=(5, 2, 1), n_final=90),
+    dict(name="headdim64_f32", dtype="f32", batch=1, grid_h=12, grid_w=12, text_lens=(20,), d=128, heads=2,
+         head_dim=64, n_c=9, structure="grid", windows_per_axis=(3,), n_final=100),
+    dict(name="headdim128_f32_bigwindow", dtype="f32", batch=1, grid_h=20, grid_w=20, text_lens=(40,), d=256,
+         heads=2, head_dim=128, n_c=30, structure="grid", windows_per_axis=(1,), n_final=230),
+    dict(name="no_removal", dtype="bf16", batch=1, grid_h=8, grid_w=8, text_lens=(8,), d=128, heads=1,
+         head_dim=128, n_c=4, structure="iid", windows_per_axis=(2,), n_final=64),
+    dict(name="all_of_A_leaves", dtype="bf16", batch=2, grid_h=8, grid_w=8, text_lens=(8, 9), d=128, heads=1,
+         head_dim=128, n_c=4, structure="iid", windows_per_axis=(4,), n_final=32),
+    dict(name="single_token_windows", dtype="f32", batch=1, grid_h=3, grid_w=3, text_lens=(4,), d=64, heads=2,
+         head_dim=32, n_c=3, structure="iid", windows_per_axis=(3,), n_final=9),
+])
+def test_shapes_and_edge_cases(case):
+    from workloads import make_custom
+    from parity import check_workload
+    print("[parity] case", case["name"], flush=True)
+    wl = make_custom(seed=1234, **case)
+    reps = check_workload(wl)
+    _report(wl, reps)
+
+
+def test_unfused_aggregate_then_compact_equals_fused_and_is_deterministic():
+    from workloads import make_workload
+    from parity import check_workload, to_dev
+    from paper_2605_00789_amd import CompressionPipeline
+    wl = make_workload(2)
+    reps = check_workload(wl, fused=False)           # the four separate entry points against the oracle
+    _report(wl, reps)
+    outs = []
+    for fused in (True, False, True):
+        pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                                   tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                                   windows_per_axis=wl.windows_per_axis, targets=wl.targets, fused=fused)
+        X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+        pos = torch.from_numpy(wl.pos).cuda()
+        st = pipe.run(X, K, V, Q, pos)
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (st.X_out, st.K_out, st.V_out, st.pos_out, st.dst, st.xi, st.best_fd)])
+    for a, b in zip(outs[0], outs[1]):
+        assert torch.equal(a, b)                     # fused == unfused, bit for bit
+    for a, b in zip(outs[0], outs[2]):
+        assert torch.equal(a, b)                     # run to run reproducible (no float atomics)
+
+
+def test_identical_tokens_merge_losslessly_and_uniform_xi_is_the_mean():
+    from workloads import make_custom
+    from parity import check_stage, to_dev
+    from oracle import lightkv_oracle as O
+    from paper_2605_00789_amd import CompressionPipeline
+    wl = make_custom(name="dups", seed=5, dtype="bf16", batch=1, grid_h=8, grid_w=8, text_lens=(12,), d=256, heads=2,
+                     head_dim=128, n_c=64, structure="iid", windows_per_axis=(2,), n_final=48)
+    # every A token of window 0..3 (first 4 of them) becomes an exact copy of the B token next to it
+    wo, wt = O.build_windows(wl.pos, wl.cu_vis, 1, 8, 8, 2)
+    X, K, V = wl.X.copy(), wl.K.copy(), wl.V.copy()
+    pairs = []
+    for w in range(4):
+        t = wt[wo[w]:wo[w + 1]]
+        for la in range(4):
+            a, b = t[2 * la], t[2 * la + 1]
+            X[a], K[a], V[a] = X[b], K[b], V[b]
+            pairs.append((a, b))
+    pipe = CompressionPipeline(dtype="bf16", batch=1, d=256, heads=2, head_dim=128, tiles=1, grid_h=8, grid_w=8,
+                               cu_txt=wl.cu_txt, windows_per_axis=(2,), targets=(48,))
+    rep, out = check_stage(pipe, 0, X, K, V, wl.Q, wl.pos, "bf16")
+    dst = out["dst"]
+    keep = dst < 0
+    new_index = np.cumsum(keep) - 1
+    for a, b in pairs:                                # FD is exactly 0 there: all 16 duplicates are merged ...
+        assert dst[a] == b
+        np.testing.assert_array_equal(out["X"][new_index[b]], X[b])      # ... and the merged row is unchanged
+        np.testing.assert_array_equal(out["K"][new_index[b]], K[b])
+    # uniform xi -> arithmetic mean (prompt-guidance ablation of the paper)
+    rep, out = check_stage(pipe, 0, wl.X, wl.K, wl.V, None, wl.pos, "bf16", xi_given=np.ones(64, dtype=np.float32))
+    X64 = O.widen(wl.X, "bf16")
+    dst = out["dst"]
+    go, gs = O.groups_csr(dst)
+    new_index = np.cumsum(dst < 0) - 1
+    for b in range(64):
+        src = gs[go[b]:go[b + 1]]
+        if len(src):
+            mean = np.mean(np.vstack([X64[b:b + 1], X64[src]]), axis=0)
+            got = O.widen(out["X"][new_index[b]], "bf16")
+            assert np.abs(got - mean).max() <= 2e-2 * np.abs(mean).max()
+
+
+def test_xi_variants_given_lse_vision_query_scale_and_head_major_layout():
+    from workloads import make_custom
+    from parity import check_stage, to_dev
+    from oracle import lightkv_oracle as O
+    from paper_2605_00789_amd import CompressionPipeline
+    import paper_2605_00789_amd as L
+    for dtype, d, H, dh in (("bf16", 256, 2, 128), ("f32", 128, 4, 32)):
+        wl = make_custom(name="xi_" + dtype, seed=9, dtype=dtype, batch=2, grid_h=6, grid_w=6, text_lens=(10, 37), d=d,
+                         heads=H, head_dim=dh, n_c=6, structure="iid", windows_per_axis=(2,), n_final=30)
+        pipe = CompressionPipeline(dtype=dtype, batch=2, d=d, heads=H, head_dim=dh, tiles=1, grid_h=6, grid_w=6,
+                                   cu_txt=wl.cu_txt, windows_per_axis=(2,), targets=(30,))
+        Q64, K64 = O.widen(wl.Q, dtype), O.widen(wl.K, dtype)
+        sumT = int(wl.cu_txt[-1])
+        # (a) text-query with the layer's own lse: keys outside the vision span took half of every row's mass
+        lse = np.zeros((H, sumT))
+        for b in range(2):
+            for h in range(H):
+                l = Q64[wl.cu_txt[b]:wl.cu_txt[b + 1], h * dh:(h + 1) * dh] @ K64[wl.cu_vis[b]:wl.cu_vis[b + 1], h * dh:(h + 1) * dh].T
+                lse[h, wl.cu_txt[b]:wl.cu_txt[b + 1]] = np.log(np.exp(l / math.sqrt(dh)).sum(axis=1)) + math.log(2)
+        rep, out = check_stage(pipe, 0, wl.X, wl.K, wl.V, wl.Q, wl.pos, dtype, lse=lse)
+        assert abs(out["xi"].sum() - H * sumT / 2) < 1e-2 * H * sumT
+        # (b) explicit softmax scale
+        check_stage(pipe, 0, wl.X, wl.K, wl.V, wl.Q, wl.pos, dtype, softmax_scale=0.05)
+        # (c) vision-query mode: vision queries against prompt keys, lse of the whole causal row given
+        rng = np.random.default_rng(3)
+        from workloads import f32_to_bf16_bits
+        Qv64 = rng.standard_normal((72, d)); Kt64 = rng.standard_normal((sumT, d))
+        if dtype == "bf16":
+            Qv, Kt = f32_to_bf16_bits(Qv64.astype(np.float32)), f32_to_bf16_bits(Kt64.astype(np.float32))
+        else:
+            Qv, Kt = Qv64.astype(np.float32), Kt64.astype(np.float32)
+        Qv64, Kt64 = O.widen(Qv, dtype), O.widen(Kt, dtype)
+        lse_v = np.zeros((H, 72))
+        for b in range(2):
+            for h in range(H):
+                l = Qv64[wl.cu_vis[b]:wl.cu_vis[b + 1], h * dh:(h + 1) * dh] @ Kt64[wl.cu_txt[b]:wl.cu_txt[b + 1], h * dh:(h + 1) * dh].T
+                lse_v[h, wl.cu_vis[b]:wl.cu_vis[b + 1]] = np.log(np.exp(l / math.sqrt(dh)).sum(axis=1) + rng.uniform(0.5, 3.0, l.shape[0]))
+        check_stage(pipe, 0, wl.X, wl.K, wl.V, Qv, wl.pos, dtype, xi_mode=L.XI_VISION_QUERY, lse=lse_v, score_K=Kt)
+        # (d) heads-major [H, S, d_h] layout of Q and K gives the same xi as token-major
+        st = pipe.stages[0]
+        X, K, Q = to_dev(wl.X, dtype), to_dev(wl.K, dtype), to_dev(wl.Q, dtype)
+        pos = torch.from_numpy(wl.pos).cuda()
+        pipe.run_stage(0, X, K, to_dev(wl.V, dtype), Q, pos)
+        xi_tok = st.xi.clone()
+        Kh = K.view(72, H, dh).permute(1, 0, 2).contiguous()
+        Qh = Q.view(sumT, H, dh).permute(1, 0, 2).contiguous()
+        xi2 = torch.empty_like(st.xi)
+        L.lightkv_score(st.problem, X, Qh, Kh, xi2, st.best_fd, st.best_dst, pipe.ws, heads_major=True)
+        torch.cuda.synchronize()
+        assert torch.equal(xi_tok, xi2)
+
+
+def test_strided_rows_and_error_paths_on_device():
+    """Row strides larger than d (a view into a wider cache), and errors that need real device pointers."""
+    from workloads import make_custom
+    from parity import to_dev, from_dev
+    import paper_2605_00789_amd as L
+    from paper_2605_00789_amd import CompressionPipeline
+    wl = make_custom(name="strided", seed=2, dtype="bf16", batch=1, grid_h=8, grid_w=8, text_lens=(16,), d=256, heads=2,
+                     head_dim=128, n_c=8, structure="iid", windows_per_axis=(2,), n_final=40)
+    pipe = CompressionPipeline(dtype="bf16", batch=1, d=256, heads=2, head_dim=128, tiles=1, grid_h=8, grid_w=8,
+                               cu_txt=wl.cu_txt, windows_per_axis=(2,), targets=(40,))
+    X, K, V, Q = (to_dev(t, "bf16") for t in (wl.X, wl.K, wl.V, wl.Q))
+    pos = torch.from_numpy(wl.pos).cuda()
+    st = pipe.run_stage(0, X, K, V, Q, pos)
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (st.X_out, st.K_out, st.V_out, st.dst)]
+    wide = [torch.zeros(64, 256 + 64, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    for wt, src in zip(wide, (X, K, V)):
+        wt[:, :256] = src
+    Xs, Ks, Vs = (wt[:, :256] for wt in wide)
+    st = pipe.run_stage(0, Xs, Ks, Vs, Q, pos)
+    torch.cuda.synchronize()
+    for a, b in zip(ref, (st.X_out, st.K_out, st.V_out, st.dst)):
+        assert torch.equal(a, b)
+    # compaction must not run in place
+    with pytest.raises(L.LightKVError) as e:
+        L.lightkv_compact(st.problem, st.new_index, X, K, V, pos, X, st.K_out, st.V_out, st.pos_out)
+    assert e.value.status == 2
+    # workspace too small
+    with pytest.raises(L.LightKVError) as e:
+        L.lightkv_score(st.problem, X, Q, K, st.xi, st.best_fd, st.best_dst, pipe.ws[:256])
+    assert e.value.status == 6
+    # vision-query mode without lse
+    with pytest.raises(L.LightKVError) as e:
+        L.lightkv_score(st.problem, X, Q, K, st.xi, st.best_fd, st.best_dst, pipe.ws, xi_mode=L.XI_VISION_QUERY)
+    assert e.value.status == 1
