@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the LightKV compression step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: every stage of the
+workload's hierarchical schedule, each stage = window partition -> scores (FD + xi) -> selection ->
+message passing + compaction.  All inputs are resident in HBM before the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 3] [--mode graph|eager]
+
+Prints ONE JSON line: metric "vision tokens compressed/sec per layer" (tokens entering the compression
+stages of one step / time of the step), the roofline of the dominant kernel and the CPU oracle timed
+on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def _parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="3", help="1..5, halving, global (default 3: the N=2880 LLaVA-NeXT-shaped layer)")
+    ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-repeats", type=int, default=3)
+    return ap.parse_args()
+
+
+def _elem_bytes(dtype):
+    return 2 if dtype == "bf16" else 4
+
+
+def rows_bytes(wl, n_in, n_out):
+    """Algorithmic HBM bytes of message passing + compaction for one stage: X, K, V rows read once
+    (batch * n_in rows) and written once (batch * n_out rows)."""
+    return 3 * _elem_bytes(wl.dtype) * wl.d * wl.batch * (n_in + n_out)
+
+
+def main():
+    args = _parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the step has no cross-GPU part); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    from workloads import make_workload
+    from paper_2605_00789_amd import CompressionPipeline
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import to_dev
+
+    cfg = int(args.workload) if args.workload.isdigit() else args.workload
+    wl = make_workload(cfg)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                               tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                               windows_per_axis=wl.windows_per_axis, targets=wl.targets, fused=True)
+    X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+    pos = torch.from_numpy(wl.pos).to(dev)
+    n_ins = [wl.n_per_seq] + list(wl.targets[:-1])
+    tokens_per_step = wl.batch * sum(n_ins)
+
+    stream = torch.cuda.Stream()
+    graph = None
+    with torch.cuda.stream(stream):
+        for _ in range(max(args.warmup, 1)):
+            pipe.run(X, K, V, Q, pos)
+        stream.synchronize()
+        if args.mode == "graph":
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                pipe.run(X, K, V, Q, pos)
+            for _ in range(3):
+                graph.replay()
+            stream.synchronize()
+
+        def step():
+            if graph is not None:
+                graph.replay()
+            else:
+                pipe.run(X, K, V, Q, pos)
+
+        # ---- timed region: exactly K steps, synchronised on both sides
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+        # ---- per-call durations with HIP events on the launch stream.  A sleep kernel in front lets the
+        # host enqueue the whole step before the GPU starts it, so event intervals hold GPU time only.
+        names = ("build_windows", "score", "select", "aggregate_compact")
+        n_inst = max(5, min(args.steps, 50))
+        acc = {(s, n): 0.0 for s in range(wl.stages) for n in names}
+        from paper_2605_00789_amd import binding as B
+        for it in range(n_inst):
+            evs = []
+            torch.cuda._sleep(2_000_000)
+            Xi, Ki, Vi, pi = X, K, V, pos
+            for s in range(wl.stages):
+                st = pipe.stages[s]
+                p = st.problem
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+                e[0].record(stream)
+                B.lightkv_build_windows(pipe.batch, st.h_cu_vis, st.cu_vis, pi, pipe.tiles, pipe.grid_h, pipe.grid_w,
+                                        st.w, st.win_offsets, st.win_tokens)
+                e[1].record(stream)
+                B.lightkv_score(p, Xi, Q, Ki, st.xi, st.best_fd, st.best_dst, pipe.ws)
+                e[2].record(stream)
+                B.lightkv_select(p, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets, st.grp_src,
+                                 st.cu_vis_out, pipe.ws)
+                e[3].record(stream)
+                B.lightkv_aggregate_compact(p, st.new_index, st.grp_offsets, st.grp_src, st.xi, Xi, Ki, Vi, pi,
+                                            st.X_out, st.K_out, st.V_out, st.pos_out)
+                e[4].record(stream)
+                evs.append(e)
+                Xi, Ki, Vi, pi = st.X_out, st.K_out, st.V_out, st.pos_out
+            stream.synchronize()
+            for s, e in enumerate(evs):
+                for k, n in enumerate(names):
+                    acc[(s, n)] += e[k].elapsed_time(e[k + 1]) * 1e3 / n_inst   # microseconds
+    calls_us = {"stage%d.%s" % (s + 1, n): round(acc[(s, n)], 2) for s in range(wl.stages) for n in names}
+
+    # ---- roofline of the dominant kernel: message passing + compaction (one kernel per stage, HBM bound)
+    rows_us = sum(acc[(s, "aggregate_compact")] for s in range(wl.stages))
+    rows_b = sum(rows_bytes(wl, n_ins[s], wl.targets[s]) for s in range(wl.stages))
+    achieved = rows_b / (rows_us * 1e-6) / 1e9 if rows_us > 0 else 0.0
+    roofline = {"kernel": "rows_kernel (lightkv_aggregate_compact)", "bound": "hbm",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "launches_per_step": wl.stages,
+                "avg_launch_us": round(rows_us / wl.stages, 2),
+                "algorithmic_bytes_per_launch": int(rows_b / wl.stages)}
+
+    value = tokens_per_step / (ms_per_step * 1e-3)
+    out = {
+        "metric": "vision tokens compressed/sec per layer",
+        "value": round(value, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": wl.name, "description": wl.notes, "batch": wl.batch, "stages": wl.stages,
+                   "tokens_in_per_stage": [wl.batch * n for n in n_ins], "windows_per_axis": wl.windows_per_axis,
+                   "launch": args.mode},
+        "roofline": roofline,
+        "calls_us": calls_us,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import lightkv_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        t0 = time.perf_counter()
+        for _ in range(args.cpu_repeats):
+            O.compress_schedule(wl)
+        dt = (time.perf_counter() - t0) / args.cpu_repeats
+        out["cpu_baseline"] = {"value": round(tokens_per_step / dt, 1), "unit": "tokens/s", "cores": int(cores),
+                               "kind": "oracle",
+                               "sample": "%d full steps of the same workload (all %d stages), numpy fp64, %.2f s each"
+                                         % (args.cpu_repeats, wl.stages, dt)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
