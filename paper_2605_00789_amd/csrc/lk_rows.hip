@@ -1,5 +1,5 @@
 // Message passing (paper Sec. 3.2.1 Step 3, Eq. "message-passing") and delete + reorder (Steps 4-5)
-// on the row tensors X, K, V.  Pure HBM streaming: one workgroup per (token, tensor) row, 16-byte
+// on the row tensors X, K, V.  Pure HBM streaming: one wave per (token, tensor) row, 16-byte
 // loads and stores, fp32 arithmetic, round-to-nearest-even on store.
 //
 // A token b with sources a_1..a_m becomes  y_b + sum_a w_a (y_a - y_b),  w_a = xi_a / (xi_b + sum xi_a),
@@ -49,57 +49,106 @@ template <> struct RowIO<float> {
   }
 };
 
-template <typename T>
+// One wave = one row of one tensor (4 rows per workgroup).  Index loads go out together, then the whole row
+// (8 x 16 bytes per lane for an 8 KB row) is in flight before anything is consumed; all loads are
+// unconditional (clamped addresses) so that the compiler never has to wait inside a branch.
+constexpr int ROWS_PER_WG = ROW_THREADS / WAVE;
+constexpr int ROW_UNROLL = 8;   // 16-byte chunks per lane and pass
+
+// MODE 0: aggregate in place   1: compact   2: aggregate + compact
+template <typename T, int MODE>
 __global__ __launch_bounds__(ROW_THREADS) void rows_kernel(RowArgs g) {
   using IO = RowIO<T>;
   constexpr int N = IO::N;
   constexpr int BYTES = Elem<T>::BYTES;
-  const int b = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int b = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 6);
   const int which = blockIdx.y;
+  if (b >= g.sum_n) return;
   const char *in = static_cast<const char *>(g.t.in[which]);
   char *out = static_cast<char *>(g.t.out[which]);
 
-  int out_row = b;
-  if (g.mode != 0) {
-    out_row = g.new_index[b];
-    if (out_row < 0 || out_row >= g.out_rows) return;   // merged away (or no room: the caller under-sized the output)
-    if (which == 0 && threadIdx.x == 0 && g.pos && g.pos_out) g.pos_out[out_row] = g.pos[b];
-  }
-  if (in == nullptr) return;
-  int s0 = 0, s1 = 0;
-  if (g.mode != 1) { s0 = g.grp_offsets[b]; s1 = g.grp_offsets[b + 1]; }
+  int out_row = b, s0 = 0, s1 = 0;
+  if (MODE != 0) out_row = g.new_index[b];
+  if (MODE != 1) { s0 = g.grp_offsets[b]; s1 = g.grp_offsets[b + 1]; }
   const int m = s1 - s0;
-  if (g.mode == 0 && m == 0) return;   // in place: rows without sources are left alone
+  if (MODE != 0 && (out_row < 0 || out_row >= g.out_rows)) return;   // merged away, or no room in the output
+  if (MODE == 0 && m == 0) return;                                    // in place: nothing to do for this row
+  if (MODE != 0 && which == 0 && lane == 0 && g.pos && g.pos_out) g.pos_out[out_row] = g.pos[b];
+  if (in == nullptr) return;
 
   const char *row_in = in + (int64_t)b * g.t.ld_in[which] * BYTES;
   char *row_out = out + (int64_t)out_row * g.t.ld_out[which] * BYTES;
+  const int64_t ld_in = g.t.ld_in[which] * BYTES;
   const int n_chunks = g.d / N;
 
-  if (m == 0) {
-    for (int c = threadIdx.x; c < n_chunks; c += ROW_THREADS)
-      *reinterpret_cast<uint4 *>(row_out + (int64_t)c * 16) = ld16(row_in + (int64_t)c * 16);
-    return;
+  // sources and weights: lane s holds source s (groups beyond 64 sources take the slow loop below)
+  int a_l = b;
+  float w_l = 0.f;
+  if (MODE != 1 && m > 0) {
+    const int mm = m < WAVE ? m : WAVE;
+    a_l = g.grp_src[s0 + (lane < mm ? lane : mm - 1)];
+    float x_l = g.xi[a_l];
+    x_l = lane < mm ? x_l : 0.f;
+    float den = x_l;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) den += __shfl_xor(den, o, 64);   // fixed butterfly: reproducible
+    den += g.xi[b];
+    for (int s = s0 + WAVE; s < s1; ++s) den += g.xi[g.grp_src[s]];
+    w_l = x_l / den;
+    if (m > WAVE) w_l = 1.f / den;   // slow path keeps 1/den instead
   }
 
-  // weights
-  float den = g.xi[b];
-  for (int s = s0; s < s1; ++s) den += g.xi[g.grp_src[s]];
-  const float inv = 1.f / den;
-
-  for (int c = threadIdx.x; c < n_chunks; c += ROW_THREADS) {
-    float yb[N], acc[N];
-    IO::unpack(ld16(row_in + (int64_t)c * 16), yb);
+  for (int c0 = 0; c0 < n_chunks; c0 += WAVE * ROW_UNROLL) {
+    uint4 v[ROW_UNROLL];
 #pragma unroll
-    for (int e = 0; e < N; ++e) acc[e] = yb[e];
-    for (int s = s0; s < s1; ++s) {
-      const int a = g.grp_src[s];
-      const float w = g.xi[a] * inv;
-      float ya[N];
-      IO::unpack(ld16(in + (int64_t)a * g.t.ld_in[which] * BYTES + (int64_t)c * 16), ya);
-#pragma unroll
-      for (int e = 0; e < N; ++e) acc[e] = fmaf(w, ya[e] - yb[e], acc[e]);
+    for (int u = 0; u < ROW_UNROLL; ++u) {
+      const int c = c0 + u * WAVE + lane;
+      v[u] = ld16(row_in + (int64_t)(c < n_chunks ? c : n_chunks - 1) * 16);
     }
-    *reinterpret_cast<uint4 *>(row_out + (int64_t)c * 16) = IO::pack(acc);
+    if (MODE != 1 && m > 0) {
+      // two halves of the pass, to keep the accumulators at 4 chunks (register budget -> occupancy)
+#pragma unroll
+      for (int hb = 0; hb < ROW_UNROLL; hb += ROW_UNROLL / 2) {
+        constexpr int HU = ROW_UNROLL / 2;
+        float acc[HU][N];   // y_b stays packed in v[] and is unpacked where it is used
+#pragma unroll
+        for (int u = 0; u < HU; ++u) IO::unpack(v[hb + u], acc[u]);
+        for (int s = 0; s < m; ++s) {
+          int a;
+          float w;
+          if (m <= WAVE) {
+            a = __shfl(a_l, s, 64);
+            w = __shfl(w_l, s, 64);
+          } else {
+            a = g.grp_src[s0 + s];
+            w = g.xi[a] * __shfl(w_l, 0, 64);
+          }
+          const char *row_a = in + (int64_t)a * ld_in;
+          uint4 va[HU];
+#pragma unroll
+          for (int u = 0; u < HU; ++u) {
+            const int c = c0 + (hb + u) * WAVE + lane;
+            va[u] = ld16(row_a + (int64_t)(c < n_chunks ? c : n_chunks - 1) * 16);
+          }
+#pragma unroll
+          for (int u = 0; u < HU; ++u) {
+            float ya[N], yb[N];
+            IO::unpack(va[u], ya);
+            IO::unpack(v[hb + u], yb);
+#pragma unroll
+            for (int e = 0; e < N; ++e) acc[u][e] = fmaf(w, ya[e] - yb[e], acc[u][e]);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < HU; ++u) v[hb + u] = IO::pack(acc[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < ROW_UNROLL; ++u) {
+      const int c = c0 + u * WAVE + lane;
+      if (c < n_chunks) *reinterpret_cast<uint4 *>(row_out + (int64_t)c * 16) = v[u];
+    }
   }
 }
 
@@ -110,9 +159,16 @@ hipError_t launch_rows(int mode, int dtype, int d, int sum_n, const RowTensors &
   RowArgs g{};
   g.t = t; g.new_index = new_index; g.grp_offsets = grp_offsets; g.grp_src = grp_src; g.pos = pos;
   g.pos_out = pos_out; g.xi = xi; g.d = d; g.sum_n = sum_n; g.mode = mode; g.out_rows = out_rows;
-  const dim3 grid((unsigned)sum_n, 3);
-  if (dtype == 1) hipLaunchKernelGGL(rows_kernel<bf16_t>, grid, dim3(ROW_THREADS), 0, stream, g);
-  else hipLaunchKernelGGL(rows_kernel<float>, grid, dim3(ROW_THREADS), 0, stream, g);
+  const dim3 grid((unsigned)((sum_n + ROWS_PER_WG - 1) / ROWS_PER_WG), 3);
+#define LK_ROWS(TT)                                                                                       \
+  do {                                                                                                    \
+    if (mode == 0) hipLaunchKernelGGL((rows_kernel<TT, 0>), grid, dim3(ROW_THREADS), 0, stream, g);      \
+    else if (mode == 1) hipLaunchKernelGGL((rows_kernel<TT, 1>), grid, dim3(ROW_THREADS), 0, stream, g); \
+    else hipLaunchKernelGGL((rows_kernel<TT, 2>), grid, dim3(ROW_THREADS), 0, stream, g);                \
+  } while (0)
+  if (dtype == 1) LK_ROWS(bf16_t);
+  else LK_ROWS(float);
+#undef LK_ROWS
   return hipGetLastError();
 }
 

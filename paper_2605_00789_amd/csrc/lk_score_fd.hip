@@ -88,6 +88,7 @@ __global__ __launch_bounds__(FD_THREADS) void fd_partial_kernel(FdArgs g) {
   // a tile without A rows or without B rows is never read by the epilogue
   if (__ballot(a_tok >= 0) == 0ull || __ballot(b_tok >= 0) == 0ull) return;
 
+  // padding rows of the tile read token 0: their products land in rows/columns nobody reads
   const char *pa = static_cast<const char *>(g.X) + (int64_t)(a_tok < 0 ? 0 : a_tok) * g.ldx * E::BYTES;
   const char *pb = static_cast<const char *>(g.X) + (int64_t)(b_tok < 0 ? 0 : b_tok) * g.ldx * E::BYTES;
 
@@ -102,8 +103,10 @@ __global__ __launch_bounds__(FD_THREADS) void fd_partial_kernel(FdArgs g) {
     for (int c = 0; c < FD_CHUNKS; ++c) {
       const int e = e0 + c * EPC;
       const bool ok = (e + EPC <= g.d);
-      va[c] = (ok && a_tok >= 0) ? ld16(pa + (int64_t)e * E::BYTES) : make_uint4(0, 0, 0, 0);
-      vb[c] = (ok && b_tok >= 0) ? ld16(pb + (int64_t)e * E::BYTES) : make_uint4(0, 0, 0, 0);
+      const int ec = ok ? e : g.d - EPC;   // unconditional load from a clamped address, zeroed below
+      const uint4 ta = ld16(pa + (int64_t)ec * E::BYTES), tb = ld16(pb + (int64_t)ec * E::BYTES);
+      va[c] = ok ? ta : make_uint4(0, 0, 0, 0);
+      vb[c] = ok ? tb : make_uint4(0, 0, 0, 0);
     }
   };
 
@@ -150,16 +153,33 @@ __global__ __launch_bounds__(FD_THREADS) void fd_partial_kernel(FdArgs g) {
   }
 }
 
-// One workgroup per 32 A rows.  Lanes of a half-wave sweep the columns of one row.
+// One workgroup per 32 A rows.  Phase 1: squared norms of the block's rows and of its window's columns
+// into LDS.  Phase 2: thread (row group t/32, column lane t%32) sweeps 4 rows x the column tiles; all
+// loads of the partial slices are issued together (the slice loop is unrolled), the sum order is fixed.
+constexpr int FD_MAX_KSPLIT = 16;
+
+__device__ __forceinline__ double sum_slices(const float *p, int64_t ks_stride, int ksplit) {
+  // every load is unconditional (surplus slices re-read the last one and are dropped afterwards): the
+  // compiler then issues all of them before the first wait instead of one load per branch
+  float v[FD_MAX_KSPLIT];
+#pragma unroll
+  for (int ks = 0; ks < FD_MAX_KSPLIT; ++ks) v[ks] = p[(ks < ksplit ? ks : ksplit - 1) * ks_stride];
+#pragma unroll
+  for (int ks = 0; ks < FD_MAX_KSPLIT; ++ks) v[ks] = (ks < ksplit) ? v[ks] : 0.f;
+  double s = 0.0;
+#pragma unroll
+  for (int ks = 0; ks < FD_MAX_KSPLIT; ++ks) s += (double)v[ks];
+  return s;
+}
+
 __global__ __launch_bounds__(FD_THREADS) void fd_epilogue_kernel(FdArgs g) {
   __shared__ double nb2[FD_MAX_COLS];
+  __shared__ double na2[32];
   const int rb = blockIdx.x;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int c32 = lane & 31, rsub = lane >> 5;
+  const int c32 = threadIdx.x & 31, rgrp = threadIdx.x >> 5;   // 8 row groups
   const int64_t ks_stride = (int64_t)g.n_tiles * FD_TILE_FLOATS;
   const int per = g.mt * g.nt;
 
-  // columns whose norms this row block needs
   int tile_row0;            // tile holding the dots of (this row block, column tile 0)
   int tile_col0;            // tile holding |b|^2 of column tile 0
   int w_single = 0, m_single = 0;
@@ -172,16 +192,20 @@ __global__ __launch_bounds__(FD_THREADS) void fd_epilogue_kernel(FdArgs g) {
     tile_col0 = w_single * per;
   }
   const int ncol_tiles = (g.group > 1) ? 1 : g.nt;
-  for (int c = threadIdx.x; c < ncol_tiles * 32; c += FD_THREADS) {
-    const float *p = g.partial + (int64_t)(tile_col0 + (c >> 5)) * FD_TILE_FLOATS + 32 * 32 + 32 + (c & 31);
-    double sum = 0.0;
-    for (int ks = 0; ks < g.ksplit; ++ks) sum += (double)p[ks * ks_stride];
-    nb2[c] = sum;
+  for (int c = threadIdx.x; c < ncol_tiles * 32 + 32; c += FD_THREADS) {
+    if (c < ncol_tiles * 32)
+      nb2[c] = sum_slices(g.partial + (int64_t)(tile_col0 + (c >> 5)) * FD_TILE_FLOATS + 32 * 32 + 32 + (c & 31),
+                          ks_stride, g.ksplit);
+    else
+      na2[c - ncol_tiles * 32] = sum_slices(g.partial + (int64_t)tile_row0 * FD_TILE_FLOATS + 32 * 32 + (c - ncol_tiles * 32),
+                                            ks_stride, g.ksplit);
   }
   __syncthreads();
 
+  const int col_cap = (g.group > 1) ? g.slot : g.nt * 32;   // columns this launch really tiled
+#pragma unroll
   for (int rp = 0; rp < 4; ++rp) {
-    const int r = wave * 8 + rp * 2 + rsub;
+    const int r = rp * 8 + rgrp;
     WinInfo wi;
     int l, col_base;   // local A position; first tile column of this row's window
     if (g.group > 1) {
@@ -195,28 +219,24 @@ __global__ __launch_bounds__(FD_THREADS) void fd_epilogue_kernel(FdArgs g) {
       col_base = 0;
     }
     const bool a_valid = l < wi.nA;
-    const int col_cap = (g.group > 1) ? g.slot : g.nt * 32;   // columns this launch really tiled
     if (wi.nB > col_cap) wi.nB = col_cap;
     double best = __longlong_as_double(0x7ff0000000000000ll);   // +inf
     int best_c = 0x7fffffff;
     if (a_valid && wi.nB > 0) {
-      const float *pn = g.partial + (int64_t)tile_row0 * FD_TILE_FLOATS + 32 * 32 + r;
-      double na2 = 0.0;
-      for (int ks = 0; ks < g.ksplit; ++ks) na2 += (double)pn[ks * ks_stride];
+      const double a2 = na2[r];
       for (int c = c32; c < wi.nB; c += 32) {
         const int tc = col_base + c;   // column inside this row block's tile row
-        const float *p = g.partial + (int64_t)(tile_row0 + (tc >> 5)) * FD_TILE_FLOATS + r * 32 + (tc & 31);
-        double dot = 0.0;
-        for (int ks = 0; ks < g.ksplit; ++ks) dot += (double)p[ks * ks_stride];
+        const double dot = sum_slices(g.partial + (int64_t)(tile_row0 + (tc >> 5)) * FD_TILE_FLOATS + r * 32 + (tc & 31),
+                                      ks_stride, g.ksplit);
         const double b2 = nb2[tc];
         double den;
-        if (na2 >= NORM_EPS * NORM_EPS && b2 >= NORM_EPS * NORM_EPS) den = sqrt(na2 * b2);
-        else den = fmax(sqrt(na2), NORM_EPS) * fmax(sqrt(b2), NORM_EPS);
+        if (a2 >= NORM_EPS * NORM_EPS && b2 >= NORM_EPS * NORM_EPS) den = sqrt(a2 * b2);
+        else den = fmax(sqrt(a2), NORM_EPS) * fmax(sqrt(b2), NORM_EPS);
         const double fd = fmax(1.0 - dot / den, 0.0);
         if (fd < best) { best = fd; best_c = c; }   // columns ascend: strict < keeps the first minimum
       }
     }
-    // reduce over the 32 lanes of the half-wave
+    // reduce over the 32 lanes of the half-wave that share this row
 #pragma unroll
     for (int m = 16; m >= 1; m >>= 1) {
       const double ob = __shfl_xor(best, m, 64);
@@ -263,7 +283,7 @@ FdPlan make_fd_plan(int n_windows, int max_window_tokens, int d, int dtype_bytes
   const int n_spans = (d + span - 1) / span;
   const int max_ks = n_spans / FD_WAVES > 0 ? n_spans / FD_WAVES : 1;
   int ks = 1;
-  while ((int64_t)p.n_tiles * ks < 1024 && ks * 2 <= max_ks) ks *= 2;
+  while ((int64_t)p.n_tiles * ks < 1024 && ks * 2 <= max_ks && ks * 2 <= 16) ks *= 2;   // 16 = FD_MAX_KSPLIT
   p.ksplit = ks;
   p.partial_floats = (size_t)p.n_tiles * ks * FD_TILE_FLOATS;
   return p;

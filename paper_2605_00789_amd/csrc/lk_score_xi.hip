@@ -4,8 +4,8 @@
 // matrix cores; nothing of the attention matrix is ever written to memory.
 //
 //   text-query mode, no lse handed in:
-//     pass 1  per (sequence, head, 32 prompt rows, vision split): row maximum and sum of exponentials over
-//             the vision keys, kept online, one (max, sum) pair per split.
+//     pass 1  per (sequence, head, 128 vision tokens): for every prompt row the maximum and the sum of
+//             exponentials over those vision keys, one (max, sum) pair per block.
 //     pass 2  per (sequence, head, 128 vision tokens): merges the pairs of its prompt rows, recomputes the
 //             logits and adds exp(logit - max) / sum over the prompt rows -> per-head partial xi.
 //   lse handed in (either mode): pass 2 only.
@@ -39,86 +39,100 @@ template <typename T, int DH> struct XiShape {
   static constexpr int NCH = DH / 2 / E::PER_CHUNK;   // 16-byte chunks per lane: half a head row
 };
 
+// Loads half a head row of token (first + min(idx, count - 1)): always a valid address, never a branch, so
+// the loads of a whole tile are in flight together.  Rows past `count` repeat the last one; callers mask them.
 template <typename T, int DH>
-__device__ __forceinline__ void load_half_row(const void *base, int64_t elem_off, bool valid, int half, uint4 *v) {
+__device__ __forceinline__ void load_half_row(const void *base, int first, int idx, int count, int64_t tok_stride,
+                                              int64_t head_off, int half, uint4 *v) {
   using E = Elem<T>;
-  const char *p = static_cast<const char *>(base) + (elem_off + half * (DH / 2)) * E::BYTES;
+  const int tok = first + (idx < count ? idx : count - 1);
+  const char *p = static_cast<const char *>(base) + ((int64_t)tok * tok_stride + head_off + half * (DH / 2)) * E::BYTES;
 #pragma unroll
-  for (int c = 0; c < XiShape<T, DH>::NCH; ++c) v[c] = valid ? ld16(p + c * 16) : make_uint4(0, 0, 0, 0);
+  for (int c = 0; c < XiShape<T, DH>::NCH; ++c) v[c] = ld16(p + c * 16);
 }
 
-// ---- pass 1: online (max, sum) of every prompt row over the vision keys -------------------------
+// ---- pass 1: (max, sum of exponentials) of every prompt row over one block of 128 vision keys ----------
+// Workgroup = (sequence, head, vision block); wave w owns the 32 vision tokens blk*128 + w*32 .. +32 and keeps
+// their key rows in registers as the MFMA row operand; the prompt rows stream through as the column operand.
+constexpr int XI_TT_CHUNK = 8;   // prompt tiles merged per LDS round
+
 template <typename T, int DH>
 __global__ __launch_bounds__(XI_THREADS) void xi_rowstat_kernel(XiArgs g) {
   using E = Elem<T>;
   constexpr int NCH = XiShape<T, DH>::NCH;
-  __shared__ float sm[4][32], ss[4][32];
+  __shared__ float2 part[4][XI_TT_CHUNK * 32];
 
   int id = blockIdx.x;
-  const int vs = id % g.vsplit; id /= g.vsplit;
-  const int tt = id % g.max_text_tiles; id /= g.max_text_tiles;
+  const int blk = id % g.max_vis_blocks; id /= g.max_vis_blocks;
   const int h = id % g.heads;
   const int b = id / g.heads;
   const int t0 = g.cu_txt[b], nT = g.cu_txt[b + 1] - t0;
   const int v0 = g.cu_vis[b], nV = g.cu_vis[b + 1] - v0;
-  if (tt * 32 >= nT) return;
+  if (blk * 128 >= nV || nT == 0) return;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = lane & 31, half = lane >> 5;
-  const int j = tt * 32 + r;   // prompt row of this lane's column
-
-  uint4 q[NCH];
-  load_half_row<T, DH>(g.txt, (int64_t)(t0 + j) * g.txt_ts + (int64_t)h * g.txt_hs, j < nT, half, q);
-
   const float NEG_INF = __uint_as_float(0xff800000u);
-  float m_run = NEG_INF, s_run = 0.f;
-  const int n_vt = (nV + 31) >> 5;
-  for (int vt = vs * 4 + wave; vt < n_vt; vt += g.vsplit * 4) {
-    const int i = vt * 32 + r;
-    uint4 k[NCH];
-    load_half_row<T, DH>(g.vis, (int64_t)(v0 + i) * g.vis_ts + (int64_t)h * g.vis_hs, i < nV, half, k);
-    f32x16 acc = {0};
+  const int vt = blk * 4 + wave;
+  const int i = vt * 32 + r;
+  const int64_t vis_ho = (int64_t)h * g.vis_hs, txt_ho = (int64_t)h * g.txt_hs;
+
+  uint4 k[NCH];
+  load_half_row<T, DH>(g.vis, v0, i, nV, g.vis_ts, vis_ho, half, k);
+  bool row_ok[16];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) E::mma32(k[c], q[c], acc);   // rows: vision tokens, cols: prompt rows
-    float t[16];
-    float tmax = NEG_INF;
+  for (int x = 0; x < 16; ++x) row_ok[x] = (vt * 32 + acc_row(x, lane)) < nV;
+
+  const int n_tt = (nT + 31) >> 5;
+  uint4 q[NCH], qn[NCH];
+  load_half_row<T, DH>(g.txt, t0, r, nT, g.txt_ts, txt_ho, half, q);
+  for (int tc = 0; tc < n_tt; tc += XI_TT_CHUNK) {
+    const int tt_end = min(tc + XI_TT_CHUNK, n_tt);
+    for (int tt = tc; tt < tt_end; ++tt) {
+      load_half_row<T, DH>(g.txt, t0, (tt + 1) * 32 + r, nT, g.txt_ts, txt_ho, half, qn);   // next tile in flight
+      f32x16 acc = {0};
 #pragma unroll
-    for (int x = 0; x < 16; ++x) {
-      const bool ok = (vt * 32 + acc_row(x, lane)) < nV;
-      t[x] = ok ? acc[x] * g.scale_log2 : NEG_INF;
-      tmax = fmaxf(tmax, t[x]);
-    }
-    if (tmax > NEG_INF) {
-      const float m_new = fmaxf(m_run, tmax);
+      for (int c = 0; c < NCH; ++c) E::mma32(k[c], q[c], acc);   // rows: vision tokens, cols: prompt rows
+      float t[16];
+      float m = NEG_INF;
+#pragma unroll
+      for (int x = 0; x < 16; ++x) {
+        t[x] = row_ok[x] ? acc[x] * g.scale_log2 : NEG_INF;
+        m = fmaxf(m, t[x]);
+      }
+      m = fmaxf(m, __shfl_xor(m, 32, 64));   // both half-waves hold rows of the same column
       float s = 0.f;
+      if (m > NEG_INF) {
 #pragma unroll
-      for (int x = 0; x < 16; ++x) s += exp2f(t[x] - m_new);   // exp2(-inf) = 0 for masked rows
-      s_run = s_run * exp2f(m_run - m_new) + s;
-      m_run = m_new;
+        for (int x = 0; x < 16; ++x) s += exp2f(t[x] - m);   // exp2(-inf) = 0 on masked rows
+      }
+      s += __shfl_xor(s, 32, 64);
+      if (half == 0) part[wave][(tt - tc) * 32 + r] = make_float2(m, s);
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) q[c] = qn[c];
     }
-  }
-  // the two half-waves hold different rows of the same column
-  {
-    const float om = __shfl_xor(m_run, 32, 64), os = __shfl_xor(s_run, 32, 64);
-    const float m_new = fmaxf(m_run, om);
-    if (m_new > NEG_INF) s_run = s_run * exp2f(m_run - m_new) + os * exp2f(om - m_new);
-    m_run = m_new;
-  }
-  if (half == 0) { sm[wave][r] = m_run; ss[wave][r] = s_run; }
-  __syncthreads();
-  if (threadIdx.x < 32 && j < nT) {
-    float m = NEG_INF;
-    for (int w = 0; w < 4; ++w) m = fmaxf(m, sm[w][r]);
-    float s = 0.f;
-    if (m > NEG_INF)
-      for (int w = 0; w < 4; ++w) s += ss[w][r] * exp2f(sm[w][r] - m);
-    float *o = g.stats + (((int64_t)h * g.sum_t + t0 + j) * g.vsplit + vs) * 2;
-    o[0] = m;
-    o[1] = s;
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < (tt_end - tc) * 32; idx += XI_THREADS) {
+      const int j = tc * 32 + idx;
+      if (j < nT) {
+        float m = NEG_INF;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) m = fmaxf(m, part[w][idx].x);
+        float s = 0.f;
+        if (m > NEG_INF) {
+#pragma unroll
+          for (int w = 0; w < 4; ++w) s += part[w][idx].y * exp2f(part[w][idx].x - m);
+        }
+        reinterpret_cast<float2 *>(g.stats)[((int64_t)h * g.sum_t + t0 + j) * g.max_vis_blocks + blk] = make_float2(m, s);
+      }
+    }
+    __syncthreads();
   }
 }
 
 // ---- pass 2: column sums of exp(logit - lse) over the prompt rows -----------------------------------
+// Same decomposition; the key rows of the wave's 32 vision tokens are now the MFMA column operand, so the sum
+// over prompt rows runs over accumulator registers.
 template <typename T, int DH, bool VISION_LSE>
 __global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
   using E = Elem<T>;
@@ -137,37 +151,55 @@ __global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
   const int r = lane & 31, half = lane >> 5;
   const float NEG_INF = __uint_as_float(0xff800000u);
 
+  const int i = blk * 128 + wave * 32 + r;   // vision token of this lane's column
+  if (nT == 0) {   // no prompt tokens: xi is zero before the floor
+    if (half == 0 && i < nV) g.xi_part[(int64_t)h * g.sum_n + v0 + i] = 0.f;
+    return;
+  }
+  const int64_t vis_ho = (int64_t)h * g.vis_hs, txt_ho = (int64_t)h * g.txt_hs;
+  uint4 k[NCH];
+  load_half_row<T, DH>(g.vis, v0, i, nV, g.vis_ts, vis_ho, half, k);
+  uint4 q[NCH], qn[NCH];
+  load_half_row<T, DH>(g.txt, t0, r, nT, g.txt_ts, txt_ho, half, q);
+
   if (!VISION_LSE) {
+    const int nblk = (nV + 127) >> 7;
     for (int j = threadIdx.x; j < nT; j += XI_THREADS) {
       float m, inv;
       if (g.lse) {
         m = g.lse[(int64_t)h * g.sum_t + t0 + j] * LOG2E;
         inv = 1.f;
       } else {
-        const float *p = g.stats + ((int64_t)h * g.sum_t + t0 + j) * g.vsplit * 2;
+        const float2 *p = reinterpret_cast<const float2 *>(g.stats) + ((int64_t)h * g.sum_t + t0 + j) * g.max_vis_blocks;
         m = NEG_INF;
-        for (int s = 0; s < g.vsplit; ++s) m = fmaxf(m, p[2 * s]);
         float sum = 0.f;
-        for (int s = 0; s < g.vsplit; ++s) sum += (p[2 * s] > NEG_INF) ? p[2 * s + 1] * exp2f(p[2 * s] - m) : 0.f;
+        int s = 0;
+        for (; s + 4 <= nblk; s += 4) {   // four partials in flight; merged in index order
+          const float2 a0 = p[s], a1 = p[s + 1], a2 = p[s + 2], a3 = p[s + 3];
+          const float mn = fmaxf(fmaxf(m, fmaxf(a0.x, a1.x)), fmaxf(a2.x, a3.x));
+          sum = sum * exp2f(m - mn) + a0.y * exp2f(a0.x - mn) + a1.y * exp2f(a1.x - mn) + a2.y * exp2f(a2.x - mn) +
+                a3.y * exp2f(a3.x - mn);
+          m = mn;
+        }
+        for (; s < nblk; ++s) {
+          const float2 a = p[s];
+          const float mn = fmaxf(m, a.x);
+          sum = sum * exp2f(m - mn) + a.y * exp2f(a.x - mn);
+          m = mn;
+        }
         inv = 1.f / sum;
       }
       rowstat[j] = make_float2(m, inv);
     }
     __syncthreads();
   }
-
-  const int i = blk * 128 + wave * 32 + r;   // vision token of this lane's column
-  uint4 k[NCH];
-  load_half_row<T, DH>(g.vis, (int64_t)(v0 + i) * g.vis_ts + (int64_t)h * g.vis_hs, i < nV, half, k);
   float col_m = 0.f;
   if (VISION_LSE) col_m = (i < nV) ? g.lse[(int64_t)h * g.sum_n + v0 + i] * LOG2E : 0.f;
 
   float colsum = 0.f;
   const int n_tt = (nT + 31) >> 5;
   for (int tt = 0; tt < n_tt; ++tt) {
-    const int j = tt * 32 + r;
-    uint4 q[NCH];
-    load_half_row<T, DH>(g.txt, (int64_t)(t0 + j) * g.txt_ts + (int64_t)h * g.txt_hs, j < nT, half, q);
+    load_half_row<T, DH>(g.txt, t0, (tt + 1) * 32 + r, nT, g.txt_ts, txt_ho, half, qn);   // next tile in flight
     f32x16 acc = {0};
 #pragma unroll
     for (int c = 0; c < NCH; ++c) E::mma32(q[c], k[c], acc);   // rows: prompt tokens, cols: vision tokens
@@ -183,17 +215,27 @@ __global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
         }
       }
     }
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) q[c] = qn[c];
   }
   colsum += __shfl_xor(colsum, 32, 64);
   if (half == 0 && i < nV) g.xi_part[(int64_t)h * g.sum_n + v0 + i] = colsum;
 }
 
 // ---- pass 3: heads summed in a fixed order, floor applied ---------------------------------------------
-__global__ __launch_bounds__(256) void xi_heads_kernel(XiArgs g) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(64) void xi_heads_kernel(XiArgs g) {
+  const int i = blockIdx.x * 64 + threadIdx.x;
   if (i >= g.sum_n) return;
   float s = 0.f;
-  for (int h = 0; h < g.heads; ++h) s += g.xi_part[(int64_t)h * g.sum_n + i];
+  int h = 0;
+  for (; h + 8 <= g.heads; h += 8) {   // eight loads in flight, summed in head order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = g.xi_part[(int64_t)(h + u) * g.sum_n + i];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; h < g.heads; ++h) s += g.xi_part[(int64_t)h * g.sum_n + i];
   g.xi[i] = fmaxf(s, XI_FLOOR);
 }
 
@@ -207,13 +249,8 @@ XiPlan make_xi_plan(int batch, const int32_t *h_cu_vis, const int32_t *h_cu_txt,
   }
   p.max_text_tiles = (max_t + 31) / 32;
   p.max_vis_blocks = (max_n + 127) / 128;
-  // pass 1: enough workgroups to fill the chip, but at least four vision tiles (one per wave) per workgroup
-  const int64_t jobs = (int64_t)batch * heads * (p.max_text_tiles > 0 ? p.max_text_tiles : 1);
-  const int max_split = p.max_vis_blocks > 0 ? p.max_vis_blocks : 1;
-  int vs = 1;
-  while (jobs * vs < 1024 && vs * 2 <= max_split) vs *= 2;
-  p.vsplit = vs;
-  p.stat_floats = (size_t)heads * (size_t)h_cu_txt[batch] * vs * 2;
+  p.vsplit = p.max_vis_blocks;   // pass 1 leaves one (max, sum) pair per block of 128 vision tokens
+  p.stat_floats = (size_t)heads * (size_t)h_cu_txt[batch] * (size_t)p.max_vis_blocks * 2;
   p.part_floats = (size_t)heads * (size_t)h_cu_vis[batch];
   return p;
 }
@@ -222,7 +259,7 @@ template <typename T, int DH>
 static hipError_t launch_xi_t(const XiPlan &plan, const XiArgs &g, int xi_mode, int max_t, hipStream_t stream) {
   const bool vision_lse = (xi_mode == 1);
   if (xi_mode == 0 && g.lse == nullptr) {
-    const unsigned grid = (unsigned)(g.batch * g.heads * plan.max_text_tiles * plan.vsplit);
+    const unsigned grid = (unsigned)(g.batch * g.heads * plan.max_vis_blocks);
     if (grid) hipLaunchKernelGGL((xi_rowstat_kernel<T, DH>), dim3(grid), dim3(XI_THREADS), 0, stream, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -237,7 +274,7 @@ static hipError_t launch_xi_t(const XiPlan &plan, const XiArgs &g, int xi_mode, 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  if (g.sum_n) hipLaunchKernelGGL(xi_heads_kernel, dim3((unsigned)((g.sum_n + 255) / 256)), dim3(256), 0, stream, g);
+  if (g.sum_n) hipLaunchKernelGGL(xi_heads_kernel, dim3((unsigned)((g.sum_n + 63) / 64)), dim3(64), 0, stream, g);
   return hipGetLastError();
 }
 

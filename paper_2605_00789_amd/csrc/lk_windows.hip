@@ -1,44 +1,141 @@
 // Window partition of the vision tokens (paper Sec. 3.2 and Sec. 3.2.2 "Window partitioning"):
 // every token is assigned to a window by its cell in the original image grid, and the tokens of
-// each window are listed in ascending sequence order (CSR).  One workgroup per sequence; the
-// stable grouping is an LDS bitonic sort of (window id, local index) keys.
+// each window are listed in ascending sequence order (CSR).  One workgroup per sequence.
+//
+// Fast path (count table fits LDS): a stable multi-bin partition.  Every wave-sized run of 64
+// consecutive tokens counts its tokens per window with ballots; a prefix over the runs and a scan
+// over the windows give each token its slot directly -- no sort, no atomics, order preserved.
+// Fallback: LDS bitonic sort of (window id, local index) keys.
 #include "lk_common.h"
 #include "lk_launch.h"
 
 namespace lk {
 
 constexpr int WIN_THREADS = 1024;
-constexpr int LOCAL_BITS = 14;   // local token index < 16384
+constexpr int LOCAL_BITS = 14;             // local token index < 16384
+constexpr size_t WIN_TABLE_LDS_MAX = 60 * 1024;   // bytes of LDS the (run, window) count table may take
 
-__global__ __launch_bounds__(WIN_THREADS) void build_windows_kernel(
-    const int32_t *__restrict__ cu_vis, const int32_t *__restrict__ pos, int batch, int tiles, int grid_h,
-    int grid_w, int w, int win_per_seq, int32_t *__restrict__ win_offsets, int32_t *__restrict__ win_tokens) {
+struct WinArgs {
+  const int32_t *cu_vis, *pos;
+  int batch, tiles, grid_h, grid_w, w, win_per_seq;
+  int32_t *win_offsets, *win_tokens;
+};
+
+__device__ __forceinline__ int window_of(const WinArgs &g, int p) {
+  if (g.w == 0) return 0;
+  const int cells = g.grid_h * g.grid_w;
+  p = p < 0 ? 0 : p;
+  int tile = p / cells;
+  const int cell = p - tile * cells;
+  tile = tile >= g.tiles ? g.tiles - 1 : tile;
+  int row = cell / g.grid_w;
+  const int col = cell - row * g.grid_w;
+  row = row >= g.grid_h ? g.grid_h - 1 : row;
+  return tile * g.w * g.w + (row * g.w / g.grid_h) * g.w + (col * g.w / g.grid_w);
+}
+
+// rank of this lane among the lanes of its wave that share its window id, and the size of that group
+__device__ __forceinline__ void wave_bin_rank(int wid, bool valid, int lane, int &rank, int &group_size, bool &is_leader) {
+  unsigned long long remaining = __ballot(valid);
+  rank = 0; group_size = 0; is_leader = false;
+  while (remaining) {
+    const int leader = __ffsll((long long)remaining) - 1;
+    const int lw = __shfl(wid, leader, 64);
+    const unsigned long long m = __ballot(valid && wid == lw);
+    if (valid && wid == lw) {
+      rank = __popcll(m & ((1ull << lane) - 1ull));
+      group_size = __popcll(m);
+      is_leader = (lane == leader);
+    }
+    remaining &= ~m;
+  }
+}
+
+__global__ __launch_bounds__(WIN_THREADS) void build_windows_table_kernel(WinArgs g) {
+  extern __shared__ uint16_t table[];   // [runs][win_per_seq] counts, then exclusive prefixes over the runs
+  __shared__ int scan_lds[64];
+  const int b = blockIdx.x;
+  const int base = g.cu_vis[b];
+  const int n = g.cu_vis[b + 1] - base;
+  const int wps = g.win_per_seq;
+  const int wbase = b * wps;
+  const int runs = (n + 63) >> 6;
+  int *winbase = reinterpret_cast<int *>(table + (size_t)runs * wps + ((runs * wps) & 1));   // [wps] after the table
+  const int lane = threadIdx.x & 63;
+
+  for (int e = threadIdx.x; e < runs * wps; e += WIN_THREADS) table[e] = 0;
+  __syncthreads();
+  // phase 1: per-run counts
+  for (int i0 = 0; i0 < n; i0 += WIN_THREADS) {
+    const int i = i0 + threadIdx.x;
+    const bool valid = i < n;
+    const int wid = valid ? window_of(g, g.pos[base + i]) : -1;
+    int rank, gs; bool leader;
+    wave_bin_rank(wid, valid, lane, rank, gs, leader);
+    if (leader) table[(i >> 6) * wps + wid] = (uint16_t)gs;
+  }
+  __syncthreads();
+  // phase 2: exclusive prefix over the runs for every window, then a scan over the windows
+  int carry = 0;
+  for (int w0 = 0; w0 < wps; w0 += WIN_THREADS) {
+    const int w = w0 + threadIdx.x;
+    int total = 0;
+    if (w < wps) {
+      for (int r = 0; r < runs; ++r) {
+        const int c = table[r * wps + w];
+        table[r * wps + w] = (uint16_t)total;
+        total += c;
+      }
+    }
+    // block exclusive scan of `total`
+    const int wave = threadIdx.x >> 6;
+    int inc = total;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += t;
+    }
+    if (lane == 63) scan_lds[wave] = inc;
+    __syncthreads();
+    if (wave == 0) {
+      int ws = (lane < WIN_THREADS / 64) ? scan_lds[lane] : 0;
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) {
+        const int t = __shfl_up(ws, o, 64);
+        if (lane >= o) ws += t;
+      }
+      if (lane < WIN_THREADS / 64) scan_lds[32 + lane] = ws;
+    }
+    __syncthreads();
+    const int excl = carry + (wave ? scan_lds[32 + wave - 1] : 0) + inc - total;
+    if (w < wps) {
+      winbase[w] = excl;
+      g.win_offsets[wbase + w] = base + excl;
+    }
+    carry += scan_lds[32 + WIN_THREADS / 64 - 1];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0 && b == g.batch - 1) g.win_offsets[wbase + wps] = base + n;
+  // phase 3: slots
+  for (int i0 = 0; i0 < n; i0 += WIN_THREADS) {
+    const int i = i0 + threadIdx.x;
+    const bool valid = i < n;
+    const int wid = valid ? window_of(g, g.pos[base + i]) : -1;
+    int rank, gs; bool leader;
+    wave_bin_rank(wid, valid, lane, rank, gs, leader);
+    if (valid) g.win_tokens[base + winbase[wid] + table[(i >> 6) * wps + wid] + rank] = base + i;
+  }
+}
+
+__global__ __launch_bounds__(WIN_THREADS) void build_windows_sort_kernel(WinArgs g) {
   extern __shared__ uint32_t keys[];
   const int b = blockIdx.x;
-  const int base = cu_vis[b];
-  const int n = cu_vis[b + 1] - base;
-  const int wbase = b * win_per_seq;
+  const int base = g.cu_vis[b];
+  const int n = g.cu_vis[b + 1] - base;
+  const int wbase = b * g.win_per_seq;
   const int p2 = next_pow2(n > 1 ? n : 1);
-  const int cells = grid_h * grid_w;
-  for (int i = threadIdx.x; i < p2; i += blockDim.x) {
-    uint32_t key = 0xffffffffu;
-    if (i < n) {
-      int wid = 0;
-      if (w > 0) {
-        int p = pos[base + i];
-        p = p < 0 ? 0 : p;
-        int tile = p / cells;
-        int cell = p - tile * cells;
-        tile = tile >= tiles ? tiles - 1 : tile;
-        int row = cell / grid_w;
-        int col = cell - row * grid_w;
-        row = row >= grid_h ? grid_h - 1 : row;
-        wid = tile * w * w + (row * w / grid_h) * w + (col * w / grid_w);
-      }
-      key = ((uint32_t)wid << LOCAL_BITS) | (uint32_t)i;
-    }
-    keys[i] = key;
-  }
+  for (int i = threadIdx.x; i < p2; i += blockDim.x)
+    keys[i] = (i < n) ? (((uint32_t)window_of(g, g.pos[base + i]) << LOCAL_BITS) | (uint32_t)i) : 0xffffffffu;
   bitonic_sort_lds(keys, p2);
   // sorted position k holds the k-th token of the window-major order
   for (int k = threadIdx.x; k <= n; k += blockDim.x) {
@@ -46,21 +143,30 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_kernel(
     int cur;
     if (k < n) {
       cur = (int)(keys[k] >> LOCAL_BITS);
-      win_tokens[base + k] = base + (int)(keys[k] & ((1u << LOCAL_BITS) - 1u));
+      g.win_tokens[base + k] = base + (int)(keys[k] & ((1u << LOCAL_BITS) - 1u));
     } else {
-      cur = (b == batch - 1) ? win_per_seq : win_per_seq - 1;   // the next sequence writes its own first offset
+      cur = (b == g.batch - 1) ? g.win_per_seq : g.win_per_seq - 1;   // the next sequence writes its own first offset
     }
-    for (int id = prev + 1; id <= cur; ++id) win_offsets[wbase + id] = base + k;
+    for (int id = prev + 1; id <= cur; ++id) g.win_offsets[wbase + id] = base + k;
   }
 }
 
 hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, int batch, int max_seq, int tiles,
                                 int grid_h, int grid_w, int w, int32_t *win_offsets, int32_t *win_tokens,
                                 hipStream_t stream) {
-  const int win_per_seq = (w == 0) ? 1 : tiles * w * w;
-  const int p2 = next_pow2(max_seq > 1 ? max_seq : 1);
-  hipLaunchKernelGGL(build_windows_kernel, dim3(batch), dim3(WIN_THREADS), p2 * sizeof(uint32_t), stream, cu_vis,
-                     pos, batch, tiles, grid_h, grid_w, w, win_per_seq, win_offsets, win_tokens);
+  WinArgs g{};
+  g.cu_vis = cu_vis; g.pos = pos; g.batch = batch; g.tiles = tiles; g.grid_h = grid_h; g.grid_w = grid_w; g.w = w;
+  g.win_per_seq = (w == 0) ? 1 : tiles * w * w;
+  g.win_offsets = win_offsets; g.win_tokens = win_tokens;
+  const int runs = (max_seq + 63) / 64;
+  const int64_t entries = (int64_t)runs * g.win_per_seq;
+  const size_t lds = (size_t)(entries + (entries & 1)) * sizeof(uint16_t) + (size_t)g.win_per_seq * sizeof(int);
+  if (lds <= WIN_TABLE_LDS_MAX) {
+    hipLaunchKernelGGL(build_windows_table_kernel, dim3(batch), dim3(WIN_THREADS), lds, stream, g);
+  } else {
+    const int p2 = next_pow2(max_seq > 1 ? max_seq : 1);
+    hipLaunchKernelGGL(build_windows_sort_kernel, dim3(batch), dim3(WIN_THREADS), p2 * sizeof(uint32_t), stream, g);
+  }
   return hipGetLastError();
 }
 

@@ -205,3 +205,42 @@ def test_strided_rows_and_error_paths_on_device():
     with pytest.raises(L.LightKVError) as e:
         L.lightkv_score(st.problem, X, Q, K, st.xi, st.best_fd, st.best_dst, pipe.ws, xi_mode=L.XI_VISION_QUERY)
     assert e.value.status == 1
+
+
+@pytest.mark.parametrize("case", [
+    dict(batch=1, tiles=1, gh=24, gw=24, w=4, holes=0.0),
+    dict(batch=3, tiles=2, gh=7, gw=9, w=3, holes=0.3),
+    dict(batch=2, tiles=5, gh=24, gw=24, w=6, holes=0.2),
+    dict(batch=2, tiles=1, gh=24, gw=24, w=0, holes=0.5),
+    dict(batch=1, tiles=5, gh=24, gw=24, w=24, holes=0.1),      # one cell per window: count table too big -> sort path
+    dict(batch=2, tiles=2, gh=64, gw=64, w=32, holes=0.4),      # long sequences, many windows -> sort path
+    dict(batch=4, tiles=1, gh=3, gw=3, w=5, holes=0.0),         # more windows than cells: empty windows
+])
+def test_build_windows_matches_oracle(case):
+    """The window partition alone, on sequences with holes (tokens removed by earlier stages) and ragged lengths."""
+    import paper_2605_00789_amd as L
+    from oracle import lightkv_oracle as O
+    rng = np.random.default_rng(77)
+    cells = case["tiles"] * case["gh"] * case["gw"]
+    pos_list, cu = [], [0]
+    for b in range(case["batch"]):
+        keep = rng.random(cells) >= case["holes"]
+        if b == 1:
+            keep[:] = False if case["batch"] > 2 else keep      # an empty sequence in the middle of a batch
+        p = np.nonzero(keep)[0].astype(np.int32)
+        pos_list.append(p)
+        cu.append(cu[-1] + len(p))
+    pos = np.concatenate(pos_list).astype(np.int32)
+    h_cu = np.asarray(cu, dtype=np.int32)
+    wps = 1 if case["w"] == 0 else case["tiles"] * case["w"] ** 2
+    n_win = case["batch"] * wps
+    d_cu = torch.from_numpy(h_cu).cuda()
+    d_pos = torch.from_numpy(pos).cuda() if len(pos) else torch.zeros(1, dtype=torch.int32, device="cuda")
+    wo = torch.full((n_win + 1,), -7, dtype=torch.int32, device="cuda")
+    wt = torch.full((max(len(pos), 1),), -7, dtype=torch.int32, device="cuda")
+    print("[windows]", case, "tokens", len(pos), flush=True)
+    L.lightkv_build_windows(case["batch"], h_cu, d_cu, d_pos, case["tiles"], case["gh"], case["gw"], case["w"], wo, wt)
+    torch.cuda.synchronize()
+    ro, rt = O.build_windows(pos, h_cu, case["tiles"], case["gh"], case["gw"], case["w"])
+    np.testing.assert_array_equal(wo.cpu().numpy(), ro)
+    np.testing.assert_array_equal(wt.cpu().numpy()[:len(rt)], rt)
