@@ -75,13 +75,22 @@ lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool n
 }
 
 struct WsLayout {
-  size_t fd_partial = 0, xi_stats = 0, xi_part = 0, sel_cnt = 0, sel_rank = 0, total = 0;
+  size_t fd_partial = 0, fd_norm = 0, fd_keys = 0, fd_counters = 0, xi_stats = 0, xi_part = 0, sel_cnt = 0,
+         sel_rank = 0, total = 0;
 };
 
-WsLayout ws_layout(const FdPlan &fd, const XiPlan &xi, int sum_n) {
+bool use_big_fd(const lightkv_problem *p, const Checked &c) {
+  // the large-window kernel wants whole pairs of 128-element k-steps; other shapes take the small-tile path
+  return p->dtype == LIGHTKV_BF16 && c.max_window >= FD_BIG_MIN_WINDOW && p->d % 256 == 0;
+}
+
+WsLayout ws_layout(const FdPlan &fd, const FdBigPlan &big, bool use_big, const XiPlan &xi, int sum_n) {
   WsLayout l;
   size_t off = 0;
-  l.fd_partial = off; off = align_up(off + fd.partial_floats * sizeof(float));
+  l.fd_partial = off; off = align_up(off + (use_big ? 0 : fd.partial_floats * sizeof(float)));
+  l.fd_norm = off;    off = align_up(off + (use_big ? big.norm_floats * sizeof(float) : 0));
+  l.fd_keys = off;    off = align_up(off + (use_big ? big.key_bytes : 0));
+  l.fd_counters = off; off = align_up(off + (use_big ? (size_t)big.n_counters * sizeof(int) : 0));
   l.xi_stats = off;   off = align_up(off + xi.stat_floats * sizeof(float));
   l.xi_part = off;    off = align_up(off + xi.part_floats * sizeof(float));
   l.sel_cnt = off;    off = align_up(off + (size_t)sum_n * sizeof(int32_t));
@@ -126,7 +135,8 @@ lightkv_status lightkv_workspace_size(const lightkv_problem *p, size_t *bytes) {
   if (st != LIGHTKV_OK) return st;
   const FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
   const XiPlan xi = make_xi_plan(p->batch, p->h_cu_vis, have_txt ? p->h_cu_txt : nullptr, p->heads, 0);
-  *bytes = ws_layout(fd, xi, c.sum_n).total;
+  const FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
+  *bytes = ws_layout(fd, big, use_big_fd(p, c), xi, c.sum_n).total;
   return LIGHTKV_OK;
 }
 
@@ -172,7 +182,9 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
   }
   const FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
   const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, need_xi ? p->h_cu_txt : nullptr, p->heads, xi_mode);
-  const WsLayout l = ws_layout(fd, xp, c.sum_n);
+  const FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
+  const bool use_big = use_big_fd(p, c);
+  const WsLayout l = ws_layout(fd, big, use_big, xp, c.sum_n);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) != 0 || ws_bytes < l.total) return LIGHTKV_ERR_WORKSPACE;
   char *wsb = static_cast<char *>(ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -185,9 +197,17 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
         != hipSuccess)
       return LIGHTKV_ERR_LAUNCH;
   }
-  if (launch_fd(fd, p->dtype, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
-                reinterpret_cast<float *>(wsb + l.fd_partial), best_fd, best_dst, s) != hipSuccess)
+  if (use_big && (uint64_t)c.sum_n * (uint64_t)ldx * 2u >= (1ull << 32)) return LIGHTKV_ERR_UNSUPPORTED;   // 32-bit row offsets
+  if (use_big) {
+    if (launch_fd_big(big, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
+                      reinterpret_cast<double *>(wsb + l.fd_norm),
+                      reinterpret_cast<unsigned long long *>(wsb + l.fd_keys),
+                      reinterpret_cast<int *>(wsb + l.fd_counters), best_fd, best_dst, s) != hipSuccess)
+      return LIGHTKV_ERR_LAUNCH;
+  } else if (launch_fd(fd, p->dtype, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
+                       reinterpret_cast<float *>(wsb + l.fd_partial), best_fd, best_dst, s) != hipSuccess) {
     return LIGHTKV_ERR_LAUNCH;
+  }
   return LIGHTKV_OK;
 }
 
@@ -202,7 +222,8 @@ lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, co
   const FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
   const bool have_txt = p->h_cu_txt && p->cu_txt;
   const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, have_txt ? p->h_cu_txt : nullptr, p->heads, 0);
-  const WsLayout l = ws_layout(fd, xp, c.sum_n);
+  const FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
+  const WsLayout l = ws_layout(fd, big, use_big_fd(p, c), xp, c.sum_n);
   // only the selection scratch is used here; accept a workspace that just covers it as laid out
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) != 0 || ws_bytes < l.total) return LIGHTKV_ERR_WORKSPACE;
   char *wsb = static_cast<char *>(ws);

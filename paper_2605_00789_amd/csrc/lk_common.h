@@ -77,6 +77,10 @@ __device__ __forceinline__ void bitonic_sort_lds(KeyT *keys, int n) {
   __syncthreads();
 }
 
+// Workgroup barrier that orders LDS traffic only: waits for this wave's outstanding LDS operations, then
+// s_barrier.  Unlike __syncthreads() it does not wait for global loads, so prefetches stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 __host__ __device__ __forceinline__ int next_pow2(int v) {
   int p = 1;
   while (p < v) p <<= 1;

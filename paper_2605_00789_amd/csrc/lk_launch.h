@@ -33,12 +33,26 @@ hipError_t launch_fd(const FdPlan &plan, int dtype, const void *X, int64_t ldx, 
                      const int32_t *win_offsets, const int32_t *win_tokens, float *partial, float *best_fd,
                      int32_t *best_dst, hipStream_t stream);
 
+// Large windows (compute bound): LDS-tiled MFMA GEMM with the row arg-min fused into its epilogue.
+struct FdBigPlan {
+  int wb;            // wave tile = (16*wb)^2, workgroup tile = (32*wb)^2
+  int mt, nt;        // workgroup tiles per window along A and B
+  int n_counters;    // arrival counters: one per (window, row block)
+  size_t norm_floats, key_bytes;
+};
+constexpr int FD_BIG_MIN_WINDOW = 256;   // windows bounded by fewer tokens use the small-tile path
+FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n);
+hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
+                         const int32_t *win_offsets, const int32_t *win_tokens, double *rnorm,
+                         unsigned long long *best_key, int *counters, float *best_fd, int32_t *best_dst,
+                         hipStream_t stream);
+
 // ---- prompt-guidance weight xi (Step 3) ----------------------------------------------------
 struct XiPlan {
-  int vsplit;          // workgroups sharing the vision axis of one (sequence, head, 32 text rows) job in pass 1
+  int vsplit;          // (max, sum) pairs pass 1 leaves per prompt row = max_vis_blocks
   int max_text_tiles;  // ceil(max T_b / 32)
   int max_vis_blocks;  // ceil(max N_b / 128)
-  size_t stat_floats;  // pass-1 partial (max, sum) pairs: heads * sumT * vsplit * 2
+  size_t stat_floats;  // pass-1 partial (max, sum) pairs: heads * sumT * max_vis_blocks * 2
   size_t part_floats;  // per-head partial xi: heads * sumN
 };
 XiPlan make_xi_plan(int batch, const int32_t *h_cu_vis, const int32_t *h_cu_txt, int heads, int xi_mode);

@@ -1,0 +1,334 @@
+// Feature divergence for LARGE windows (paper Sec. 3.2.1 Steps 1-2, Eq. "similarity"; the global stage of
+// the hierarchical schedule, Sec. 3.2.2): here the |A| x |B| x d contraction is compute bound and is run as a
+// classic LDS-tiled MFMA GEMM with the row arg-min fused into its epilogue.
+//
+//   row_norms_kernel : 1/|x| of every token (|x|^2 summed in fp32, inverse root in fp64), and initialisation of the
+//                      per-row best keys / arrival counters.
+//   fd_big_kernel    : workgroup tile 96 x 96, four waves, v_mfma_f32_16x16x32_bf16.  Rows are gathered through the
+//                      window's token list; 128-element k-steps travel global -> register ring (3 steps in flight)
+//                      -> double-buffered LDS (rows padded to 272 bytes: conflict-free 16-byte operand reads).
+//                      Every wave accumulates the whole tile over its quarter of each k-step; the partial tiles are
+//                      merged through LDS (fixed order), which also gives a two-level fp32 summation (error of a
+//                      4096-long dot product near 2e-7 relative).
+//                      Epilogue: cos = dot * (1/|a|) * (1/|b|) in fp64, FD = max(1 - cos, 0) rounded to fp32,
+//                      row minimum over the block's columns by shuffles, then one 64-bit integer atomicMin per row
+//                      on the key (FD bits << 32 | B token): integer min is order independent, so the result is
+//                      bit-reproducible and equal FDs go to the earlier B token.
+//   fd_big_finalize_kernel: keys -> best_fd / best_dst.
+#include "lk_common.h"
+#include "lk_launch.h"
+
+namespace lk {
+
+constexpr int BIG_THREADS = 256;
+constexpr int BIG_BK = 128;                    // elements per k-step
+constexpr int BIG_PITCH = BIG_BK * 2 + 16;     // bytes per staged row
+constexpr int BIG_DEPTH = 2;                   // k-steps of global loads in flight per thread (even)
+
+struct BigArgs {
+  const void *X;
+  int64_t ldx;
+  int d, n_windows, sum_n;
+  const int32_t *win_offsets, *win_tokens;
+  double *rnorm;                 // [sum_n]  1 / max(|x|, 1e-12)
+  unsigned long long *best_key;  // [sum_n]
+  int *counters;                 // [n_windows * mt]
+  float *best_fd;
+  int32_t *best_dst;
+  int mt, nt, n_counters;
+};
+
+// ---- 1/|x| per token (|x|^2 summed in fp32); also resets keys and counters ------------------------------------------------
+__global__ __launch_bounds__(256) void row_norms_kernel(BigArgs g) {
+  const int lane = threadIdx.x & 63;
+  const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int gid = blockIdx.x * 256 + threadIdx.x;
+  if (gid < g.n_counters) g.counters[gid] = 0;
+  if (tok >= g.sum_n) return;
+  const char *row = static_cast<const char *>(g.X) + (int64_t)tok * g.ldx * 2;
+  const int n_chunks = g.d >> 3;
+  float s = 0.f;
+  for (int c0 = 0; c0 < n_chunks; c0 += 64 * 8) {
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int c = c0 + u * 64 + lane;
+      v[u] = ld16(row + (int64_t)(c < n_chunks ? c : n_chunks - 1) * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int c = c0 + u * 64 + lane;
+      const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+      float t = 0.f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float lo = __uint_as_float(w[q] << 16), hi = __uint_as_float(w[q] & 0xffff0000u);
+        t = fmaf(lo, lo, t);
+        t = fmaf(hi, hi, t);
+      }
+      s += (c < n_chunks) ? t : 0.f;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (lane == 0) {
+    g.rnorm[tok] = 1.0 / fmax(sqrt((double)s), 1e-12);   // the only fp64 sqrt/div of the path: once per token
+    g.best_key[tok] = ~0ull;
+  }
+}
+
+// Workgroup tile 96 x 96, four waves.  The waves do NOT split the tile: each one accumulates the whole 96 x 96
+// block (6 x 6 MFMA blocks of 16 x 16) over its own quarter of every 128-element k-step.  Per MFMA this halves the
+// LDS operand traffic of a 2 x 2 wave arrangement (48 flop per LDS byte instead of 24), and the four partial sums
+// give a two-level fp32 summation for free.  The partial tiles are merged through LDS at the end.
+constexpr int BIG_TM = 96;
+constexpr int BIG_NB = BIG_TM / 16;            // 6 blocks per edge
+constexpr int BIG_OWN = BIG_NB * BIG_NB / 4;   // 9 blocks per wave in the epilogue
+constexpr int BIG_STAGE = 2 * BIG_TM * BIG_PITCH;
+
+__global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
+  constexpr int PASSES = BIG_TM / 16;          // 16 rows x 16 chunks of 16 bytes are staged per pass
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+
+  // Workgroups are dealt to the 8 XCDs round robin; give every XCD a contiguous run of logical tiles, and order the
+  // tiles of a window in column panels of 4, so that the tiles sharing an L2 touch few distinct row/column blocks.
+  const int per = g.mt * g.nt;
+  const int n_tiles = g.n_windows * per;
+  const int per_xcd = (n_tiles + 7) >> 3;
+  const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (lid >= n_tiles) return;
+  const int w = lid / per;
+  const int rem = lid - w * per;
+  constexpr int PW = 4;
+  const int panel = rem / (g.mt * PW);
+  const int in_panel = rem - panel * g.mt * PW;
+  const int pw = min(PW, g.nt - panel * PW);
+  const int mt = in_panel / pw, nt = panel * PW + (in_panel - mt * pw);
+  const int off = g.win_offsets[w];
+  const int v = g.win_offsets[w + 1] - off;
+  const int nA = (v + 1) >> 1, nB = v >> 1;
+  const int row0 = mt * BIG_TM, col0 = nt * BIG_TM;
+  if (row0 >= nA || col0 >= nB) return;
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int l16 = lane & 15, kg = lane >> 4;
+
+  // rows this thread stages: 16 rows per pass, 16 threads per row.  Row offsets are 32-bit (the tensor is far
+  // below 4 GB, checked by the launcher) so that every load is "uniform base + per-lane offset": the k position
+  // advances on the scalar unit and the loop body carries no address arithmetic on the vector unit.
+  const int srow = tid >> 4, schunk = tid & 15;
+  uint32_t offa[PASSES], offb[PASSES];
+#pragma unroll
+  for (int p = 0; p < PASSES; ++p) {
+    int la = row0 + p * 16 + srow, lb = col0 + p * 16 + srow;
+    la = la < nA ? la : nA - 1;                 // padding rows repeat the last valid one; never read back
+    lb = lb < nB ? lb : nB - 1;
+    int ta = g.win_tokens[off + 2 * la], tb = g.win_tokens[off + 2 * lb + 1];
+    ta = ((unsigned)ta < (unsigned)g.sum_n) ? ta : 0;
+    tb = ((unsigned)tb < (unsigned)g.sum_n) ? tb : 0;
+    offa[p] = (uint32_t)ta * (uint32_t)g.ldx * 2u + (uint32_t)schunk * 16u;
+    offb[p] = (uint32_t)tb * (uint32_t)g.ldx * 2u + (uint32_t)schunk * 16u;
+  }
+  // token and 1/|x| of the tile row / column this thread publishes for the epilogue (threads 0..191), fetched now so
+  // that the latency hides behind the k loop
+  int e_tok = -1;
+  double e_rn = 0.0;
+  if (tid < 2 * BIG_TM) {
+    const bool is_b = tid >= BIG_TM;
+    const int l = (is_b ? col0 : row0) + (is_b ? tid - BIG_TM : tid);
+    const int lim = is_b ? nB : nA;
+    const int t = g.win_tokens[off + 2 * (l < lim ? l : lim - 1) + (is_b ? 1 : 0)];
+    const bool ok = l < lim && (unsigned)t < (unsigned)g.sum_n;
+    e_rn = g.rnorm[ok ? t : 0];
+    e_tok = ok ? t : -1;
+  }
+
+  f32x4 acc[BIG_NB][BIG_NB];
+#pragma unroll
+  for (int i = 0; i < BIG_NB; ++i)
+#pragma unroll
+    for (int j = 0; j < BIG_NB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // d is a multiple of 2 * BIG_BK (checked by the launcher): an even number of whole k-steps, no tails.
+  const int n_ksteps = g.d / BIG_BK;
+  const char *xbase = static_cast<const char *>(g.X);
+  // Global -> register ring (BIG_DEPTH k-steps in flight) -> LDS (double buffered) -> MFMA operands.
+  uint4 ring[BIG_DEPTH][2 * PASSES];
+  auto gload = [&](int ks, uint4 *r) {   // unconditional: steps past the end re-read the last one
+    const char *kb = xbase + (size_t)(ks < n_ksteps ? ks : n_ksteps - 1) * (BIG_BK * 2);   // scalar
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      r[p] = ld16(kb + offa[p]);
+      r[PASSES + p] = ld16(kb + offb[p]);
+    }
+  };
+  char *lds_w = lds + srow * BIG_PITCH + schunk * 16;
+  auto lstore = [&](int stage, const uint4 *r) {
+    char *base = lds_w + stage * BIG_STAGE;
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      *reinterpret_cast<uint4 *>(base + p * 16 * BIG_PITCH) = r[p];
+      *reinterpret_cast<uint4 *>(base + BIG_TM * BIG_PITCH + p * 16 * BIG_PITCH) = r[PASSES + p];
+    }
+  };
+  const char *lds_r = lds + l16 * BIG_PITCH + wave * 64 + kg * 16;
+  auto compute = [&](int stage) {
+    // this wave's quarter of the k-step: 32 elements = one MFMA deep; lane supplies row l16, k-group kg
+    const char *abase = lds_r + stage * BIG_STAGE;
+    const char *bbase = abase + BIG_TM * BIG_PITCH;
+    bf16x8 fa[BIG_NB], fb[BIG_NB];
+#pragma unroll
+    for (int i = 0; i < BIG_NB; ++i) {
+      fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(abase + i * 16 * BIG_PITCH));
+      fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(bbase + i * 16 * BIG_PITCH));
+    }
+#pragma unroll
+    for (int i = 0; i < BIG_NB; ++i)
+#pragma unroll
+      for (int j = 0; j < BIG_NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+  };
+  // sched_barrier(0) pins the issue order: loads complete in order, so the wait before an LDS store only has to
+  // cover the oldest slot while the younger ones stay in flight.
+#pragma unroll
+  for (int j = 0; j < BIG_DEPTH; ++j) {
+    gload(j, ring[j]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  lstore(0, ring[0]);
+  __builtin_amdgcn_sched_barrier(0);
+  gload(BIG_DEPTH, ring[0]);
+  __builtin_amdgcn_sched_barrier(0);
+  lds_barrier();
+  // The body is branch free: with control flow inside, the compiler's wait-count bookkeeping falls back to waiting
+  // for every load in flight.  Step ks computes from LDS stage ks & 1 while the data of step ks + 1 moves from its
+  // ring slot to the other stage (after the last step that copy is a harmless repeat).
+  for (int ks0 = 0; ks0 < n_ksteps; ks0 += BIG_DEPTH) {
+#pragma unroll
+    for (int u = 0; u < BIG_DEPTH; ++u) {
+      const int ks = ks0 + u;
+      const int slot = (u + 1) % BIG_DEPTH;        // ring slot of step ks + 1
+      const int stage = u & 1;                     // BIG_DEPTH is even: the stage parity is static
+      __builtin_amdgcn_sched_barrier(0);
+      lstore(stage ^ 1, ring[slot]);
+      __builtin_amdgcn_sched_barrier(0);
+      gload(ks + 1 + BIG_DEPTH, ring[slot]);
+      __builtin_amdgcn_sched_barrier(0);           // keep the refill ahead of the MFMA block
+      compute(stage);
+      lds_barrier();
+    }
+  }
+
+  // ---- merge the four partial tiles: wave w ends up owning the blocks whose linear id is w mod 4.
+  // LDS is free now: [0, 1536) bytes hold 1/|a| and 1/|b| of the tile, then 4 x 9 KB exchange buffers.
+  double *e_rnorm = reinterpret_cast<double *>(lds);              // [96] rows then [96] cols
+  int *e_token = reinterpret_cast<int *>(lds + 2 * BIG_TM * 8);   // [96] row tokens then [96] col tokens
+  float *xbuf = reinterpret_cast<float *>(lds + 4096);            // [4 waves][9 blocks][256 floats]
+  if (tid < 2 * BIG_TM) { e_rnorm[tid] = e_rn; e_token[tid] = e_tok; }
+  f32x4 own[BIG_OWN];
+#pragma unroll
+  for (int b = 0; b < BIG_NB * BIG_NB; ++b)
+    if ((b & 3) == wave) own[b >> 2] = acc[b / BIG_NB][b % BIG_NB];   // resolved at compile time per wave value below
+  // (the selection above depends on `wave`; spell the four cases out so that every index is static)
+#pragma unroll
+  for (int r = 1; r < 4; ++r) {
+    const int to = (wave + r) & 3;        // owner this wave sends to in round r
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < BIG_NB * BIG_NB; ++b) {
+      if ((b & 3) == to) {
+        float *dst = xbuf + ((wave * BIG_OWN + (b >> 2)) * 64 + lane) * 4;
+        *reinterpret_cast<f32x4 *>(dst) = acc[b / BIG_NB][b % BIG_NB];
+      }
+    }
+    __syncthreads();
+    const int from = (wave - r) & 3;      // its buffer now holds partials of the blocks this wave owns
+#pragma unroll
+    for (int o = 0; o < BIG_OWN; ++o)
+      own[o] += *reinterpret_cast<const f32x4 *>(xbuf + ((from * BIG_OWN + o) * 64 + lane) * 4);
+  }
+
+  // ---- epilogue on the owned blocks: block id b = 4*o + wave -> (i, j) = (b / 6, b % 6)
+  // accumulator layout of a 16x16 block: lane holds column (lane % 16) and rows 4*(lane/16) + 0..3
+#pragma unroll
+  for (int o = 0; o < BIG_OWN; ++o) {
+    const int b = 4 * o + wave;
+    const int bi = b / BIG_NB, bj = b - bi * BIG_NB;
+    const int cl = bj * 16 + l16;
+    const double rb = e_rnorm[BIG_TM + cl];
+    const int tb = e_token[BIG_TM + cl];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int rl = bi * 16 + kg * 4 + q;
+      const double ra = e_rnorm[rl];
+      const int ta = e_token[rl];
+      const double cosv = (double)own[o][q] * ra * rb;
+      const float fd = (float)fmax(1.0 - cosv, 0.0);
+      // key = (FD bits, B token): tokens of a window ascend with their local position, so the smaller token is the
+      // earlier column; NaN never competes
+      unsigned long long key = ((unsigned long long)__float_as_uint(fd) << 32) | (unsigned)tb;
+      key = (ta >= 0 && tb >= 0 && fd == fd) ? key : ~0ull;
+#pragma unroll
+      for (int m = 8; m >= 1; m >>= 1) {   // the 16 lanes with the same lane/16 hold the same row
+        const unsigned long long ok = __shfl_xor(key, m, 64);
+        key = ok < key ? ok : key;
+      }
+      if (l16 == 0 && key != ~0ull) atomicMin(&g.best_key[ta], key);
+    }
+  }
+}
+
+// Keys -> best_fd / best_dst for every token.  A token no key was offered for (B nodes, A nodes of windows without
+// a B node, rows of NaNs) gets +inf / -1.
+__global__ __launch_bounds__(256) void fd_big_finalize_kernel(BigArgs g) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= g.sum_n) return;
+  const unsigned long long key = g.best_key[i];
+  g.best_fd[i] = key == ~0ull ? __uint_as_float(0x7f800000u) : __uint_as_float((unsigned)(key >> 32));
+  g.best_dst[i] = key == ~0ull ? -1 : (int)(key & 0xffffffffu);
+}
+
+FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n) {
+  FdBigPlan p{};
+  const int maxA = (max_window_tokens + 1) / 2, maxB = max_window_tokens / 2;
+  p.wb = BIG_NB;   // 96 x 96 workgroup tiles: 15 x 15 = 225 tiles for the 1440 x 1440 case, one round on 256 CUs
+  p.mt = (maxA + BIG_TM - 1) / BIG_TM;
+  p.nt = maxB > 0 ? (maxB + BIG_TM - 1) / BIG_TM : 1;
+  p.n_counters = 0;
+  p.norm_floats = (size_t)sum_n * 2;   // doubles
+  p.key_bytes = (size_t)sum_n * 8;
+  return p;
+}
+
+hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
+                         const int32_t *win_offsets, const int32_t *win_tokens, double *rnorm,
+                         unsigned long long *best_key, int *counters, float *best_fd, int32_t *best_dst,
+                         hipStream_t stream) {
+  if (n_windows == 0 || sum_n == 0) return hipSuccess;
+  BigArgs g{};
+  g.X = X; g.ldx = ldx; g.d = d; g.n_windows = n_windows; g.sum_n = sum_n;
+  g.win_offsets = win_offsets; g.win_tokens = win_tokens;
+  g.rnorm = rnorm; g.best_key = best_key; g.counters = counters; g.best_fd = best_fd; g.best_dst = best_dst;
+  g.mt = plan.mt; g.nt = plan.nt; g.n_counters = 0;
+  hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((sum_n + 3) / 4)), dim3(256), 0, stream, g);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const unsigned n_tiles = (unsigned)(n_windows * plan.mt * plan.nt);
+  const unsigned grid = (n_tiles + 7u) / 8u * 8u;   // whole rounds over the XCDs; surplus workgroups exit at once
+  constexpr size_t lds = (size_t)2 * BIG_STAGE;      // 102 KB: above the 64 KB default, the attribute below allows it
+  static bool attr_set = false;                      // a property of the loaded kernel, set once per process
+  if (!attr_set) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(fd_big_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(fd_big_kernel, dim3(grid), dim3(BIG_THREADS), lds, stream, g);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fd_big_finalize_kernel, dim3((unsigned)((sum_n + 255) / 256)), dim3(256), 0, stream, g);
+  return hipGetLastError();
+}
+
+}  // namespace lk
