@@ -4,6 +4,7 @@
 #include "lk_launch.h"
 
 #include <math.h>
+#include <mutex>
 
 namespace {
 
@@ -72,6 +73,40 @@ lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool n
     if (c.max_window > LIGHTKV_MAX_WINDOW_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;
   }
   return LIGHTKV_OK;
+}
+
+// The two halves of lightkv_score (xi from Q/K, FD from X) share no data, so they are enqueued as a fork/join:
+// xi on a helper stream, FD on the caller's stream, joined by events before the call returns.  Under stream capture
+// the fork/join becomes two parallel branches of the graph.  The helper stream and its two events are the only
+// objects the library ever creates: host-side handles, one set per device, made on the first (non-capturing) call
+// at default priority and kept for the life of the process.  If they cannot be made the work runs serially.
+struct Fork {
+  hipStream_t side = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  bool ready = false;
+};
+
+Fork *fork_for_current_device(hipStream_t main) {
+  static Fork forks[64];
+  static std::mutex mu;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  Fork &f = forks[dev];
+  if (f.ready) return &f;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(main, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
+    (void)hipGetLastError();
+    return nullptr;   // never create objects while the caller is capturing
+  }
+  if (hipStreamCreateWithFlags(&f.side, hipStreamNonBlocking) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  if (hipEventCreateWithFlags(&f.fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&f.join, hipEventDisableTiming) != hipSuccess) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  f.ready = true;
+  return &f;
 }
 
 struct WsLayout {
@@ -189,26 +224,39 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
   char *wsb = static_cast<char *>(ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
 
-  if (need_xi) {
-    const float scale = softmax_scale != 0.f ? softmax_scale : 1.0f / sqrtf((float)p->head_dim);
-    if (launch_xi(xp, p->dtype, xi_mode, p->batch, p->heads, p->head_dim, c.sum_n, c.sum_t, p->cu_vis, p->cu_txt,
-                  Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, lse, scale,
-                  reinterpret_cast<float *>(wsb + l.xi_stats), reinterpret_cast<float *>(wsb + l.xi_part), xi, s)
-        != hipSuccess)
-      return LIGHTKV_ERR_LAUNCH;
-  }
   if (use_big && (uint64_t)c.sum_n * (uint64_t)ldx * 2u >= (1ull << 32)) return LIGHTKV_ERR_UNSUPPORTED;   // 32-bit row offsets
+  Fork *fk = nullptr;
+  if (need_xi) {
+    fk = fork_for_current_device(s);
+    hipStream_t xs = s;
+    if (fk) {
+      if (hipEventRecord(fk->fork, s) == hipSuccess && hipStreamWaitEvent(fk->side, fk->fork, 0) == hipSuccess) xs = fk->side;
+      else { (void)hipGetLastError(); fk = nullptr; }
+    }
+    const float scale = softmax_scale != 0.f ? softmax_scale : 1.0f / sqrtf((float)p->head_dim);
+    const hipError_t e = launch_xi(xp, p->dtype, xi_mode, p->batch, p->heads, p->head_dim, c.sum_n, c.sum_t, p->cu_vis,
+                                   p->cu_txt, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, lse, scale,
+                                   reinterpret_cast<float *>(wsb + l.xi_stats),
+                                   reinterpret_cast<float *>(wsb + l.xi_part), xi, xs);
+    if (fk && hipEventRecord(fk->join, fk->side) != hipSuccess) return LIGHTKV_ERR_LAUNCH;
+    if (e != hipSuccess) {   // the helper stream must rejoin the caller's stream whatever happened on it
+      if (fk) (void)hipStreamWaitEvent(s, fk->join, 0);
+      return LIGHTKV_ERR_LAUNCH;
+    }
+  }
+  lightkv_status fd_status = LIGHTKV_OK;
   if (use_big) {
     if (launch_fd_big(big, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
                       reinterpret_cast<double *>(wsb + l.fd_norm),
                       reinterpret_cast<unsigned long long *>(wsb + l.fd_keys),
                       reinterpret_cast<int *>(wsb + l.fd_counters), best_fd, best_dst, s) != hipSuccess)
-      return LIGHTKV_ERR_LAUNCH;
+      fd_status = LIGHTKV_ERR_LAUNCH;
   } else if (launch_fd(fd, p->dtype, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
                        reinterpret_cast<float *>(wsb + l.fd_partial), best_fd, best_dst, s) != hipSuccess) {
-    return LIGHTKV_ERR_LAUNCH;
+    fd_status = LIGHTKV_ERR_LAUNCH;
   }
-  return LIGHTKV_OK;
+  if (fk && hipStreamWaitEvent(s, fk->join, 0) != hipSuccess) return LIGHTKV_ERR_LAUNCH;   // join
+  return fd_status;
 }
 
 lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, const int32_t *best_dst,

@@ -56,18 +56,41 @@ constexpr int ROWS_PER_WG = ROW_THREADS / WAVE;
 constexpr int ROW_UNROLL = 8;   // 16-byte chunks per lane and pass
 
 // MODE 0: aggregate in place   1: compact   2: aggregate + compact
+//
+// Dependent loads are what this kernel waits for, so they are arranged in as few rounds as possible:
+//   round 1  the row itself, xi of the row, new_index and the group bounds (all depend on the row number only)
+//   round 2  the source list of the group
+//   round 3  xi of the sources and the rows of the first two sources, together
+// A row without sources is stored after round 1.  Third and later sources of a group (rare) are fetched one by one.
 template <typename T, int MODE>
 __global__ __launch_bounds__(ROW_THREADS) void rows_kernel(RowArgs g) {
   using IO = RowIO<T>;
   constexpr int N = IO::N;
   constexpr int BYTES = Elem<T>::BYTES;
+  constexpr int HU = ROW_UNROLL / 2;
   const int lane = threadIdx.x & 63;
   const int b = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 6);
   const int which = blockIdx.y;
   if (b >= g.sum_n) return;
   const char *in = static_cast<const char *>(g.t.in[which]);
   char *out = static_cast<char *>(g.t.out[which]);
+  const int64_t ld_in = g.t.ld_in[which] * BYTES;
+  const int n_chunks = g.d / N;
+  const bool single_pass = n_chunks <= WAVE * ROW_UNROLL;
 
+  // round 1 (the in-place mode touches few rows: it looks at the group bounds first instead of fetching every row)
+  uint4 v[ROW_UNROLL];
+  const char *row_in = in ? in + (int64_t)b * ld_in : nullptr;
+  if (MODE == 0 && g.grp_offsets[b + 1] == g.grp_offsets[b]) return;
+  if (in != nullptr) {
+#pragma unroll
+    for (int u = 0; u < ROW_UNROLL; ++u) {
+      const int c = u * WAVE + lane;
+      v[u] = ld16(row_in + (int64_t)(c < n_chunks ? c : n_chunks - 1) * 16);
+    }
+  }
+  float xb = 0.f;
+  if (MODE != 1) xb = g.xi[b];
   int out_row = b, s0 = 0, s1 = 0;
   if (MODE != 0) out_row = g.new_index[b];
   if (MODE != 1) { s0 = g.grp_offsets[b]; s1 = g.grp_offsets[b + 1]; }
@@ -76,45 +99,73 @@ __global__ __launch_bounds__(ROW_THREADS) void rows_kernel(RowArgs g) {
   if (MODE == 0 && m == 0) return;                                    // in place: nothing to do for this row
   if (MODE != 0 && which == 0 && lane == 0 && g.pos && g.pos_out) g.pos_out[out_row] = g.pos[b];
   if (in == nullptr) return;
-
-  const char *row_in = in + (int64_t)b * g.t.ld_in[which] * BYTES;
   char *row_out = out + (int64_t)out_row * g.t.ld_out[which] * BYTES;
-  const int64_t ld_in = g.t.ld_in[which] * BYTES;
-  const int n_chunks = g.d / N;
 
-  // sources and weights: lane s holds source s (groups beyond 64 sources take the slow loop below)
+  // rounds 2 and 3: lane s holds source s and its weight (groups beyond 64 sources take the slow loop)
   int a_l = b;
   float w_l = 0.f;
+  const char *row_a0 = row_in, *row_a1 = row_in;
   if (MODE != 1 && m > 0) {
     const int mm = m < WAVE ? m : WAVE;
     a_l = g.grp_src[s0 + (lane < mm ? lane : mm - 1)];
-    float x_l = g.xi[a_l];
-    x_l = lane < mm ? x_l : 0.f;
-    float den = x_l;
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) den += __shfl_xor(den, o, 64);   // fixed butterfly: reproducible
-    den += g.xi[b];
-    for (int s = s0 + WAVE; s < s1; ++s) den += g.xi[g.grp_src[s]];
-    w_l = x_l / den;
-    if (m > WAVE) w_l = 1.f / den;   // slow path keeps 1/den instead
+    row_a0 = in + (int64_t)__shfl(a_l, 0, 64) * ld_in;
+    row_a1 = in + (int64_t)__shfl(a_l, mm > 1 ? 1 : 0, 64) * ld_in;
   }
 
   for (int c0 = 0; c0 < n_chunks; c0 += WAVE * ROW_UNROLL) {
-    uint4 v[ROW_UNROLL];
+    if (c0 > 0) {   // rows longer than one pass: later passes reload
 #pragma unroll
-    for (int u = 0; u < ROW_UNROLL; ++u) {
-      const int c = c0 + u * WAVE + lane;
-      v[u] = ld16(row_in + (int64_t)(c < n_chunks ? c : n_chunks - 1) * 16);
+      for (int u = 0; u < ROW_UNROLL; ++u) {
+        const int c = c0 + u * WAVE + lane;
+        v[u] = ld16(row_in + (int64_t)(c < n_chunks ? c : n_chunks - 1) * 16);
+      }
     }
     if (MODE != 1 && m > 0) {
-      // two halves of the pass, to keep the accumulators at 4 chunks (register budget -> occupancy)
+      // first half of the pass: its source chunks go out together with the xi loads below
+      uint4 va0[HU], va1[HU];
 #pragma unroll
-      for (int hb = 0; hb < ROW_UNROLL; hb += ROW_UNROLL / 2) {
-        constexpr int HU = ROW_UNROLL / 2;
+      for (int u = 0; u < HU; ++u) {
+        const int c = c0 + u * WAVE + lane;
+        const int64_t o = (int64_t)(c < n_chunks ? c : n_chunks - 1) * 16;
+        va0[u] = ld16(row_a0 + o);
+        va1[u] = ld16(row_a1 + o);
+      }
+      if (c0 == 0) {
+        const int mm = m < WAVE ? m : WAVE;
+        float x_l = g.xi[a_l];
+        x_l = lane < mm ? x_l : 0.f;
+        float den = x_l;
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) den += __shfl_xor(den, o, 64);   // fixed butterfly: reproducible
+        den += xb;
+        for (int s = s0 + WAVE; s < s1; ++s) den += g.xi[g.grp_src[s]];
+        w_l = x_l / den;
+        if (m > WAVE) w_l = 1.f / den;   // slow path keeps 1/den instead
+      }
+      const float w0 = (m <= WAVE) ? __shfl(w_l, 0, 64) : g.xi[__shfl(a_l, 0, 64)] * __shfl(w_l, 0, 64);
+      const float w1 = (m <= 1) ? 0.f : ((m <= WAVE) ? __shfl(w_l, 1, 64) : g.xi[g.grp_src[s0 + 1]] * __shfl(w_l, 0, 64));
+#pragma unroll
+      for (int hb = 0; hb < ROW_UNROLL; hb += HU) {
+        if (hb > 0) {
+#pragma unroll
+          for (int u = 0; u < HU; ++u) {
+            const int c = c0 + (hb + u) * WAVE + lane;
+            const int64_t o = (int64_t)(c < n_chunks ? c : n_chunks - 1) * 16;
+            va0[u] = ld16(row_a0 + o);
+            va1[u] = ld16(row_a1 + o);
+          }
+        }
         float acc[HU][N];   // y_b stays packed in v[] and is unpacked where it is used
 #pragma unroll
-        for (int u = 0; u < HU; ++u) IO::unpack(v[hb + u], acc[u]);
-        for (int s = 0; s < m; ++s) {
+        for (int u = 0; u < HU; ++u) {
+          float y0[N], y1[N], yb[N];
+          IO::unpack(v[hb + u], yb);
+          IO::unpack(va0[u], y0);
+          IO::unpack(va1[u], y1);
+#pragma unroll
+          for (int e = 0; e < N; ++e) acc[u][e] = fmaf(w1, y1[e] - yb[e], fmaf(w0, y0[e] - yb[e], yb[e]));
+        }
+        for (int s = 2; s < m; ++s) {   // third and later sources
           int a;
           float w;
           if (m <= WAVE) {
@@ -150,6 +201,7 @@ __global__ __launch_bounds__(ROW_THREADS) void rows_kernel(RowArgs g) {
       if (c < n_chunks) *reinterpret_cast<uint4 *>(row_out + (int64_t)c * 16) = v[u];
     }
   }
+  (void)single_pass;
 }
 
 hipError_t launch_rows(int mode, int dtype, int d, int sum_n, const RowTensors &t, const int32_t *new_index,

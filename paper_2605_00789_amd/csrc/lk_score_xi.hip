@@ -51,16 +51,52 @@ __device__ __forceinline__ void load_half_row(const void *base, int first, int i
   for (int c = 0; c < XiShape<T, DH>::NCH; ++c) v[c] = ld16(p + c * 16);
 }
 
+// Prompt rows of one head are shared by the four waves of a workgroup: they are staged through LDS once per
+// workgroup (coalesced 16-byte loads, rows padded by 16 bytes so that the MFMA operand reads are conflict free)
+// instead of being fetched by every wave on its own.
+template <typename T, int DH> struct XiStage {
+  static constexpr int ROW_BYTES = DH * Elem<T>::BYTES;
+  static constexpr int PITCH = ROW_BYTES + 16;
+  static constexpr int ROWS = ROW_BYTES > 256 ? 64 : 128;   // prompt rows per staged chunk (<= 34 KB of LDS)
+  static constexpr int TILES = ROWS / 32;
+  static constexpr int CPR = ROW_BYTES / 16;                // 16-byte chunks per row
+};
+
+// Copies prompt rows [j0, j0 + ROWS) of head h into LDS (rows past nT repeat the last one).
+template <typename T, int DH>
+__device__ __forceinline__ void stage_prompt_rows(const XiArgs &g, char *q_lds, int t0, int nT, int j0, int64_t txt_ho) {
+  using S = XiStage<T, DH>;
+  constexpr int BYTES = Elem<T>::BYTES;
+  constexpr int PER_PASS = XI_THREADS / S::CPR;             // rows covered by one pass of the workgroup
+  const int c = threadIdx.x % S::CPR, r0 = threadIdx.x / S::CPR;
+#pragma unroll
+  for (int p = 0; p < S::ROWS / PER_PASS; ++p) {
+    const int r = p * PER_PASS + r0;
+    const int j = j0 + r;
+    const int tok = t0 + (j < nT ? j : nT - 1);
+    const uint4 v = ld16(static_cast<const char *>(g.txt) + ((int64_t)tok * g.txt_ts + txt_ho) * BYTES + c * 16);
+    *reinterpret_cast<uint4 *>(q_lds + r * S::PITCH + c * 16) = v;
+  }
+}
+
+template <typename T, int DH>
+__device__ __forceinline__ void read_prompt_frag(const char *q_lds, int row, int half, uint4 *v) {
+  using S = XiStage<T, DH>;
+  const char *p = q_lds + row * S::PITCH + half * (S::ROW_BYTES / 2);
+#pragma unroll
+  for (int c = 0; c < XiShape<T, DH>::NCH; ++c) v[c] = *reinterpret_cast<const uint4 *>(p + c * 16);
+}
+
 // ---- pass 1: (max, sum of exponentials) of every prompt row over one block of 128 vision keys ----------
 // Workgroup = (sequence, head, vision block); wave w owns the 32 vision tokens blk*128 + w*32 .. +32 and keeps
-// their key rows in registers as the MFMA row operand; the prompt rows stream through as the column operand.
-constexpr int XI_TT_CHUNK = 8;   // prompt tiles merged per LDS round
-
+// their key rows in registers as the MFMA row operand; the prompt rows come from LDS as the column operand.
 template <typename T, int DH>
 __global__ __launch_bounds__(XI_THREADS) void xi_rowstat_kernel(XiArgs g) {
   using E = Elem<T>;
+  using S = XiStage<T, DH>;
   constexpr int NCH = XiShape<T, DH>::NCH;
-  __shared__ float2 part[4][XI_TT_CHUNK * 32];
+  __shared__ __attribute__((aligned(16))) char q_lds[S::ROWS * S::PITCH];
+  __shared__ float2 part[4][S::ROWS];
 
   int id = blockIdx.x;
   const int blk = id % g.max_vis_blocks; id /= g.max_vis_blocks;
@@ -74,22 +110,22 @@ __global__ __launch_bounds__(XI_THREADS) void xi_rowstat_kernel(XiArgs g) {
   const int r = lane & 31, half = lane >> 5;
   const float NEG_INF = __uint_as_float(0xff800000u);
   const int vt = blk * 4 + wave;
-  const int i = vt * 32 + r;
   const int64_t vis_ho = (int64_t)h * g.vis_hs, txt_ho = (int64_t)h * g.txt_hs;
 
   uint4 k[NCH];
-  load_half_row<T, DH>(g.vis, v0, i, nV, g.vis_ts, vis_ho, half, k);
+  load_half_row<T, DH>(g.vis, v0, vt * 32 + r, nV, g.vis_ts, vis_ho, half, k);
   bool row_ok[16];
 #pragma unroll
   for (int x = 0; x < 16; ++x) row_ok[x] = (vt * 32 + acc_row(x, lane)) < nV;
 
-  const int n_tt = (nT + 31) >> 5;
-  uint4 q[NCH], qn[NCH];
-  load_half_row<T, DH>(g.txt, t0, r, nT, g.txt_ts, txt_ho, half, q);
-  for (int tc = 0; tc < n_tt; tc += XI_TT_CHUNK) {
-    const int tt_end = min(tc + XI_TT_CHUNK, n_tt);
-    for (int tt = tc; tt < tt_end; ++tt) {
-      load_half_row<T, DH>(g.txt, t0, (tt + 1) * 32 + r, nT, g.txt_ts, txt_ho, half, qn);   // next tile in flight
+  for (int j0 = 0; j0 < nT; j0 += S::ROWS) {
+    __syncthreads();   // the previous chunk has been consumed
+    stage_prompt_rows<T, DH>(g, q_lds, t0, nT, j0, txt_ho);
+    __syncthreads();
+    const int n_tt = min(S::TILES, (nT - j0 + 31) >> 5);
+    for (int tt = 0; tt < n_tt; ++tt) {
+      uint4 q[NCH];
+      read_prompt_frag<T, DH>(q_lds, tt * 32 + r, half, q);
       f32x16 acc = {0};
 #pragma unroll
       for (int c = 0; c < NCH; ++c) E::mma32(k[c], q[c], acc);   // rows: vision tokens, cols: prompt rows
@@ -107,13 +143,11 @@ __global__ __launch_bounds__(XI_THREADS) void xi_rowstat_kernel(XiArgs g) {
         for (int x = 0; x < 16; ++x) s += exp2f(t[x] - m);   // exp2(-inf) = 0 on masked rows
       }
       s += __shfl_xor(s, 32, 64);
-      if (half == 0) part[wave][(tt - tc) * 32 + r] = make_float2(m, s);
-#pragma unroll
-      for (int c = 0; c < NCH; ++c) q[c] = qn[c];
+      if (half == 0) part[wave][tt * 32 + r] = make_float2(m, s);
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < (tt_end - tc) * 32; idx += XI_THREADS) {
-      const int j = tc * 32 + idx;
+    for (int idx = threadIdx.x; idx < n_tt * 32; idx += XI_THREADS) {
+      const int j = j0 + idx;
       if (j < nT) {
         float m = NEG_INF;
 #pragma unroll
@@ -126,7 +160,6 @@ __global__ __launch_bounds__(XI_THREADS) void xi_rowstat_kernel(XiArgs g) {
         reinterpret_cast<float2 *>(g.stats)[((int64_t)h * g.sum_t + t0 + j) * g.max_vis_blocks + blk] = make_float2(m, s);
       }
     }
-    __syncthreads();
   }
 }
 
@@ -136,8 +169,10 @@ __global__ __launch_bounds__(XI_THREADS) void xi_rowstat_kernel(XiArgs g) {
 template <typename T, int DH, bool VISION_LSE>
 __global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
   using E = Elem<T>;
+  using S = XiStage<T, DH>;
   constexpr int NCH = XiShape<T, DH>::NCH;
-  extern __shared__ float2 rowstat[];   // per prompt row: (max in exp2 domain, 1/sum)
+  __shared__ __attribute__((aligned(16))) char q_lds[S::ROWS * S::PITCH];
+  __shared__ float2 rowstat[S::ROWS];   // per prompt row of the chunk: (max in exp2 domain, 1/sum)
 
   int id = blockIdx.x;
   const int blk = id % g.max_vis_blocks; id /= g.max_vis_blocks;
@@ -159,64 +194,65 @@ __global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
   const int64_t vis_ho = (int64_t)h * g.vis_hs, txt_ho = (int64_t)h * g.txt_hs;
   uint4 k[NCH];
   load_half_row<T, DH>(g.vis, v0, i, nV, g.vis_ts, vis_ho, half, k);
-  uint4 q[NCH], qn[NCH];
-  load_half_row<T, DH>(g.txt, t0, r, nT, g.txt_ts, txt_ho, half, q);
-
-  if (!VISION_LSE) {
-    const int nblk = (nV + 127) >> 7;
-    for (int j = threadIdx.x; j < nT; j += XI_THREADS) {
-      float m, inv;
-      if (g.lse) {
-        m = g.lse[(int64_t)h * g.sum_t + t0 + j] * LOG2E;
-        inv = 1.f;
-      } else {
-        const float2 *p = reinterpret_cast<const float2 *>(g.stats) + ((int64_t)h * g.sum_t + t0 + j) * g.max_vis_blocks;
-        m = NEG_INF;
-        float sum = 0.f;
-        int s = 0;
-        for (; s + 4 <= nblk; s += 4) {   // four partials in flight; merged in index order
-          const float2 a0 = p[s], a1 = p[s + 1], a2 = p[s + 2], a3 = p[s + 3];
-          const float mn = fmaxf(fmaxf(m, fmaxf(a0.x, a1.x)), fmaxf(a2.x, a3.x));
-          sum = sum * exp2f(m - mn) + a0.y * exp2f(a0.x - mn) + a1.y * exp2f(a1.x - mn) + a2.y * exp2f(a2.x - mn) +
-                a3.y * exp2f(a3.x - mn);
-          m = mn;
-        }
-        for (; s < nblk; ++s) {
-          const float2 a = p[s];
-          const float mn = fmaxf(m, a.x);
-          sum = sum * exp2f(m - mn) + a.y * exp2f(a.x - mn);
-          m = mn;
-        }
-        inv = 1.f / sum;
-      }
-      rowstat[j] = make_float2(m, inv);
-    }
-    __syncthreads();
-  }
   float col_m = 0.f;
   if (VISION_LSE) col_m = (i < nV) ? g.lse[(int64_t)h * g.sum_n + v0 + i] * LOG2E : 0.f;
+  const int nblk = (nV + 127) >> 7;
 
   float colsum = 0.f;
-  const int n_tt = (nT + 31) >> 5;
-  for (int tt = 0; tt < n_tt; ++tt) {
-    load_half_row<T, DH>(g.txt, t0, (tt + 1) * 32 + r, nT, g.txt_ts, txt_ho, half, qn);   // next tile in flight
-    f32x16 acc = {0};
+  for (int j0 = 0; j0 < nT; j0 += S::ROWS) {
+    __syncthreads();   // the previous chunk has been consumed
+    stage_prompt_rows<T, DH>(g, q_lds, t0, nT, j0, txt_ho);
+    if (!VISION_LSE) {
+      for (int idx = threadIdx.x; idx < S::ROWS; idx += XI_THREADS) {
+        const int j = j0 + idx;
+        float m = 3.0e38f, inv = 0.f;   // rows past nT: exp2(x - huge) = 0, times 0
+        if (j < nT) {
+          if (g.lse) {
+            m = g.lse[(int64_t)h * g.sum_t + t0 + j] * LOG2E;
+            inv = 1.f;
+          } else {
+            const float2 *p = reinterpret_cast<const float2 *>(g.stats) + ((int64_t)h * g.sum_t + t0 + j) * g.max_vis_blocks;
+            m = NEG_INF;
+            float sum = 0.f;
+            int s = 0;
+            for (; s + 4 <= nblk; s += 4) {   // four partials in flight; merged in index order
+              const float2 a0 = p[s], a1 = p[s + 1], a2 = p[s + 2], a3 = p[s + 3];
+              const float mn = fmaxf(fmaxf(m, fmaxf(a0.x, a1.x)), fmaxf(a2.x, a3.x));
+              sum = sum * exp2f(m - mn) + a0.y * exp2f(a0.x - mn) + a1.y * exp2f(a1.x - mn) + a2.y * exp2f(a2.x - mn) +
+                    a3.y * exp2f(a3.x - mn);
+              m = mn;
+            }
+            for (; s < nblk; ++s) {
+              const float2 a = p[s];
+              const float mn = fmaxf(m, a.x);
+              sum = sum * exp2f(m - mn) + a.y * exp2f(a.x - mn);
+              m = mn;
+            }
+            inv = 1.f / sum;
+          }
+        }
+        rowstat[idx] = make_float2(m, inv);   // rows past nT get weight 0
+      }
+    }
+    __syncthreads();
+    const int n_tt = min(S::TILES, (nT - j0 + 31) >> 5);
+    for (int tt = 0; tt < n_tt; ++tt) {
+      uint4 q[NCH];
+      read_prompt_frag<T, DH>(q_lds, tt * 32 + r, half, q);
+      f32x16 acc = {0};
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) E::mma32(q[c], k[c], acc);   // rows: prompt tokens, cols: vision tokens
+      for (int c = 0; c < NCH; ++c) E::mma32(q[c], k[c], acc);   // rows: prompt tokens, cols: vision tokens
 #pragma unroll
-    for (int x = 0; x < 16; ++x) {
-      const int row = tt * 32 + acc_row(x, lane);
-      if (row < nT) {
+      for (int x = 0; x < 16; ++x) {
+        const int row = tt * 32 + acc_row(x, lane);
         if (VISION_LSE) {
-          colsum += exp2f(acc[x] * g.scale_log2 - col_m);
+          colsum += (j0 + row < nT) ? exp2f(acc[x] * g.scale_log2 - col_m) : 0.f;
         } else {
           const float2 st = rowstat[row];
           colsum += exp2f(acc[x] * g.scale_log2 - st.x) * st.y;
         }
       }
     }
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) q[c] = qn[c];
   }
   colsum += __shfl_xor(colsum, 32, 64);
   if (half == 0 && i < nV) g.xi_part[(int64_t)h * g.sum_n + v0 + i] = colsum;
@@ -269,8 +305,7 @@ static hipError_t launch_xi_t(const XiPlan &plan, const XiArgs &g, int xi_mode, 
     if (vision_lse)
       hipLaunchKernelGGL((xi_colsum_kernel<T, DH, true>), dim3(grid2), dim3(XI_THREADS), 0, stream, g);
     else
-      hipLaunchKernelGGL((xi_colsum_kernel<T, DH, false>), dim3(grid2), dim3(XI_THREADS),
-                         (size_t)max_t * sizeof(float2), stream, g);
+      hipLaunchKernelGGL((xi_colsum_kernel<T, DH, false>), dim3(grid2), dim3(XI_THREADS), 0, stream, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
