@@ -49,6 +49,19 @@ def rows_bytes(wl, n_in, n_out):
     return 3 * _elem_bytes(wl.dtype) * wl.d * wl.batch * (n_in + n_out)
 
 
+def measured_traffic(workload_name):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE, scaled by a copy-kernel calibration); None where no such summary exists for the workload."""
+    path = os.path.join(ROOT, "profiles", "rows_kernel_hbm_traffic_%s.txt" % {"llava_next": "llava_next_n2880"}.get(workload_name, workload_name))
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = _parse()
     if args.gpus != 1:
@@ -108,6 +121,15 @@ def main():
 
         # ---- per-call durations with HIP events on the launch stream.  A sleep kernel in front lets the
         # host enqueue the whole step before the GPU starts it, so event intervals hold GPU time only.
+        # interval of an empty event pair on this stream (event bookkeeping), removed from every call interval
+        nulls = []
+        for _ in range(20):
+            a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda._sleep(200_000)
+            a.record(stream); b2.record(stream)
+            stream.synchronize()
+            nulls.append(a.elapsed_time(b2) * 1e3)
+        null_us = sorted(nulls)[len(nulls) // 2]
         names = ("build_windows", "score", "select", "aggregate_compact")
         n_inst = max(5, min(args.steps, 50))
         acc = {(s, n): 0.0 for s in range(wl.stages) for n in names}
@@ -137,7 +159,7 @@ def main():
             stream.synchronize()
             for s, e in enumerate(evs):
                 for k, n in enumerate(names):
-                    acc[(s, n)] += e[k].elapsed_time(e[k + 1]) * 1e3 / n_inst   # microseconds
+                    acc[(s, n)] += max(e[k].elapsed_time(e[k + 1]) * 1e3 - null_us, 0.0) / n_inst   # microseconds
     calls_us = {"stage%d.%s" % (s + 1, n): round(acc[(s, n)], 2) for s in range(wl.stages) for n in names}
 
     # ---- roofline of the dominant kernel: message passing + compaction (one kernel per stage, HBM bound)
@@ -146,7 +168,7 @@ def main():
     achieved = rows_b / (rows_us * 1e-6) / 1e9 if rows_us > 0 else 0.0
     roofline = {"kernel": "rows_kernel (lightkv_aggregate_compact)", "bound": "hbm",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(wl.name),
                 "launches_per_step": wl.stages,
                 "avg_launch_us": round(rows_us / wl.stages, 2),
                 "algorithmic_bytes_per_launch": int(rows_b / wl.stages)}
@@ -170,6 +192,7 @@ def main():
                    "launch": args.mode},
         "roofline": roofline,
         "calls_us": calls_us,
+        "event_overhead_us": round(null_us, 2),
     }
 
     if not args.no_cpu_baseline:

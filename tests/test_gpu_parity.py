@@ -244,3 +244,78 @@ def test_build_windows_matches_oracle(case):
     ro, rt = O.build_windows(pos, h_cu, case["tiles"], case["gh"], case["gw"], case["w"])
     np.testing.assert_array_equal(wo.cpu().numpy(), ro)
     np.testing.assert_array_equal(wt.cpu().numpy()[:len(rt)], rt)
+
+
+def test_graph_replay_equals_eager_in_the_benchmark_launch_configuration():
+    """bench.py times hipGraph replays of the whole 3-stage schedule at N=2880.  Replays must reproduce the eager
+    results bit for bit (which test_measured_configs checks against the oracle), also when other work and
+    synchronisations happen between replays."""
+    from workloads import make_workload
+    from parity import to_dev
+    from paper_2605_00789_amd import CompressionPipeline
+    wl = make_workload(3)
+    pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                               tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                               windows_per_axis=wl.windows_per_axis, targets=wl.targets)
+    X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+    pos = torch.from_numpy(wl.pos).cuda()
+    stream = torch.cuda.Stream()
+
+    def snapshot():
+        out = []
+        for st in pipe.stages:
+            out += [t.clone() for t in (st.X_out, st.K_out, st.V_out, st.pos_out, st.dst, st.new_index, st.grp_offsets,
+                                         st.xi, st.best_fd, st.best_dst, st.cu_vis_out, st.win_offsets, st.win_tokens)]
+        return out
+
+    def scribble():   # make sure a replay really recomputes everything
+        for st in pipe.stages:
+            for t in (st.X_out, st.K_out, st.V_out):
+                t.zero_()
+            for t in (st.dst, st.new_index, st.best_dst, st.pos_out):
+                t.fill_(-5)
+            st.xi.fill_(float("nan"))
+
+    with torch.cuda.stream(stream):
+        pipe.run(X, K, V, Q, pos)
+        pipe.run(X, K, V, Q, pos)
+        stream.synchronize()
+        eager = snapshot()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            pipe.run(X, K, V, Q, pos)
+        for rep in range(4):
+            scribble()
+            junk = torch.randn(1 << 20, device="cuda").sum()     # unrelated eager work between replays
+            torch.cuda.synchronize()
+            g.replay()
+            stream.synchronize()
+            for a, b in zip(eager, snapshot()):
+                assert torch.equal(a, b, ), "replay %d differs from the eager run" % rep
+            assert junk.item() == junk.item()
+
+
+def test_nan_rows_keep_the_counts_exact():
+    """Rows of NaNs never win a comparison; the step still removes exactly r tokens per window and writes inside the
+    output buffers."""
+    from workloads import make_custom
+    from parity import to_dev
+    from paper_2605_00789_amd import CompressionPipeline
+    from oracle import lightkv_oracle as O
+    wl = make_custom(name="nan", seed=4, dtype="bf16", batch=1, grid_h=8, grid_w=8, text_lens=(8,), d=256, heads=2,
+                     head_dim=128, n_c=8, structure="iid", windows_per_axis=(2,), n_final=32)    # r = |A|: all of A leaves
+    X = wl.X.copy()
+    X[[0, 2, 17, 40]] = 0x7FC0                                    # bf16 NaN rows (A and B nodes alike)
+    pipe = CompressionPipeline(dtype="bf16", batch=1, d=256, heads=2, head_dim=128, tiles=1, grid_h=8, grid_w=8,
+                               cu_txt=wl.cu_txt, windows_per_axis=(2,), targets=(32,))
+    st = pipe.run_stage(0, to_dev(X, "bf16"), to_dev(wl.K, "bf16"), to_dev(wl.V, "bf16"), to_dev(wl.Q, "bf16"),
+                        torch.from_numpy(wl.pos).cuda())
+    torch.cuda.synchronize()
+    dst = st.dst.cpu().numpy()
+    assert int((dst >= 0).sum()) == 32 and st.cu_vis_out.cpu().tolist() == [0, 32]
+    wo, wt = O.build_windows(wl.pos, wl.cu_vis, 1, 8, 8, 2)
+    for w in range(4):
+        t = wt[wo[w]:wo[w + 1]]
+        assert np.all(dst[t[0::2]] >= 0) and np.all(dst[t[1::2]] == -1)
+        assert set(dst[t[0::2]].tolist()) <= set(t[1::2].tolist())       # partners stay inside the window's B set
+    np.testing.assert_array_equal(st.new_index.cpu().numpy(), O.kept_index(dst))
