@@ -132,6 +132,10 @@ lightkv_status lightkv_build_windows(int32_t batch, const int32_t *h_cu_vis, con
  *     GIVEN       : Q, K, lse ignored, xi is read-only input and left as is.
  *     element (token t, head h, e) of Q sits at Q[t*q_tok_stride + h*q_head_stride + e], K alike.
  *   softmax_scale: 0 selects 1/sqrt(head_dim).   lse: natural-log units, layout [heads, tokens], or NULL.
+ *   The two halves are independent and may be enqueued by two calls, e.g. on two streams with the same workspace:
+ *   X == NULL computes xi only (windows, best_fd, best_dst are not touched), xi_mode GIVEN computes the FD half only.
+ *   When both halves are requested in one call the library runs them concurrently (xi on an internal helper stream
+ *   that forks from and joins `stream`; the only object the library ever creates, one per device).
  */
 lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ldx,
                              const void *Q, int64_t q_tok_stride, int64_t q_head_stride,

@@ -202,11 +202,13 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
                              void *ws, size_t ws_bytes, void *stream) {
   if (xi_mode < LIGHTKV_XI_TEXT_QUERY || xi_mode > LIGHTKV_XI_GIVEN) return LIGHTKV_ERR_UNSUPPORTED;
   const bool need_xi = xi_mode != LIGHTKV_XI_GIVEN;
+  const bool need_fd = X != nullptr;   // X == NULL: only xi is wanted (the two halves may be enqueued separately)
+  if (!need_fd && !need_xi) return LIGHTKV_ERR_NULL;
   Checked c;
-  lightkv_status st = check_problem(p, true, need_xi, c);
+  lightkv_status st = check_problem(p, need_fd, need_xi, c);
   if (st != LIGHTKV_OK) return st;
-  if (!X || !xi || !best_fd || !best_dst) return LIGHTKV_ERR_NULL;
-  if (!row_tensor_ok(X, ldx, p->d, c.elem_bytes, st)) return st;
+  if (!xi || (need_fd && (!best_fd || !best_dst))) return LIGHTKV_ERR_NULL;
+  if (need_fd && !row_tensor_ok(X, ldx, p->d, c.elem_bytes, st)) return st;
   if (need_xi) {
     if (!Q || !K) return LIGHTKV_ERR_NULL;
     if (xi_mode == LIGHTKV_XI_VISION_QUERY && !lse) return LIGHTKV_ERR_NULL;
@@ -215,8 +217,21 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
       return LIGHTKV_ERR_UNSUPPORTED;
     if (q_tok_stride < 0 || q_head_stride < 0 || k_tok_stride < 0 || k_head_stride < 0) return LIGHTKV_ERR_SHAPE;
   }
+  // the workspace layout is the same whichever halves are requested, so that an xi-only call and an FD-only call
+  // on two streams can share one workspace (their regions are disjoint)
+  int max_window = c.max_window;
+  if (!need_fd) {   // windows were not validated: take the bound as given, clamped, just to lay the workspace out
+    max_window = p->max_window_tokens > 0 ? p->max_window_tokens : 0;
+    if (max_window > LIGHTKV_MAX_WINDOW_TOKENS) max_window = LIGHTKV_MAX_WINDOW_TOKENS;
+    if (max_window == 0 && p->h_win_offsets)
+      for (int w = 0; w < p->n_windows; ++w) {
+        const int v = p->h_win_offsets[w + 1] - p->h_win_offsets[w];
+        max_window = v > max_window ? v : max_window;
+      }
+    c.max_window = max_window;
+  }
   const FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
-  const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, need_xi ? p->h_cu_txt : nullptr, p->heads, xi_mode);
+  const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, p->h_cu_txt && p->cu_txt ? p->h_cu_txt : nullptr, p->heads, 0);
   const FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
   const bool use_big = use_big_fd(p, c);
   const WsLayout l = ws_layout(fd, big, use_big, xp, c.sum_n);
@@ -227,7 +242,7 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
   if (use_big && (uint64_t)c.sum_n * (uint64_t)ldx * 2u >= (1ull << 32)) return LIGHTKV_ERR_UNSUPPORTED;   // 32-bit row offsets
   Fork *fk = nullptr;
   if (need_xi) {
-    fk = fork_for_current_device(s);
+    if (need_fd) fk = fork_for_current_device(s);
     hipStream_t xs = s;
     if (fk) {
       if (hipEventRecord(fk->fork, s) == hipSuccess && hipStreamWaitEvent(fk->side, fk->fork, 0) == hipSuccess) xs = fk->side;
@@ -245,7 +260,9 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
     }
   }
   lightkv_status fd_status = LIGHTKV_OK;
-  if (use_big) {
+  if (!need_fd) {
+    // xi only
+  } else if (use_big) {
     if (launch_fd_big(big, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
                       reinterpret_cast<double *>(wsb + l.fd_norm),
                       reinterpret_cast<unsigned long long *>(wsb + l.fd_keys),

@@ -87,6 +87,10 @@ class CompressionPipeline:
             self.stages.append(st)
             n_in = n_out
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        # xi needs neither the windows nor the FD scores and is only consumed by the merge, so it is enqueued on a
+        # second stream (default priority) that forks at the start of a stage and joins before aggregate/compact
+        self.side = torch.cuda.Stream(device=dev)
+        self.side2 = torch.cuda.Stream(device=dev)   # builds the next stage's windows during the merge
         # scratch copies for the unfused path (aggregate works in place)
         if not fused:
             s0 = self.stages[0]
@@ -95,24 +99,45 @@ class CompressionPipeline:
 
     # one stage; inputs are device tensors of this stage's shape
     def run_stage(self, s: int, X, K, V, Q, pos, *, xi_mode=B.XI_TEXT_QUERY, lse=None, softmax_scale=0.0,
-                  xi_given: Optional[torch.Tensor] = None, score_K=None, stream=None):
+                  xi_given: Optional[torch.Tensor] = None, score_K=None, stream=None, windows_ready=False,
+                  prepare_next=False):
         """score_K: keys of the xi contraction when they are not the K rows being merged
-        (vision-query mode: Q holds the vision queries, score_K the prompt keys)."""
+        (vision-query mode: Q holds the vision queries, score_K the prompt keys).
+        windows_ready: the window lists of this stage were already built on the second helper stream
+        (by the previous stage's prepare_next); prepare_next: build the next stage's windows while this
+        stage's rows are being merged (they only need pos and new_index, not the merged rows)."""
         st = self.stages[s]
         p = st.problem
-        B.lightkv_build_windows(self.batch, st.h_cu_vis, st.cu_vis, pos, self.tiles, self.grid_h, self.grid_w, st.w,
-                                st.win_offsets, st.win_tokens, stream=stream)
+        main = torch.cuda.current_stream() if stream is None else stream
         xi = st.xi
         if xi_given is not None:
             xi = xi_given
-            xi_mode = B.XI_GIVEN
-        B.lightkv_score(p, X, Q, K if score_K is None else score_K, xi, st.best_fd, st.best_dst, self.ws, xi_mode=xi_mode, lse=lse,
-                        softmax_scale=softmax_scale, stream=stream)
+        else:
+            self.side.wait_stream(main)                                   # fork
+            B.lightkv_score(p, None, Q, K if score_K is None else score_K, xi, None, None, self.ws, xi_mode=xi_mode,
+                            lse=lse, softmax_scale=softmax_scale, stream=self.side)          # xi half only
+        if windows_ready:
+            main.wait_stream(self.side2)
+        else:
+            B.lightkv_build_windows(self.batch, st.h_cu_vis, st.cu_vis, pos, self.tiles, self.grid_h, self.grid_w, st.w,
+                                    st.win_offsets, st.win_tokens, stream=main)
+        B.lightkv_score(p, X, None, None, xi, st.best_fd, st.best_dst, self.ws, xi_mode=B.XI_GIVEN, stream=main)  # FD half
         B.lightkv_select(p, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets, st.grp_src,
-                         st.cu_vis_out, self.ws, stream=stream)
+                         st.cu_vis_out, self.ws, stream=main)
+        pos_here = pos
+        if prepare_next and self.fused and s + 1 < len(self.stages):
+            nx = self.stages[s + 1]
+            self.side2.wait_stream(main)                                  # fork after select
+            B.lightkv_compact(p, st.new_index, None, None, None, pos, None, None, None, st.pos_out, stream=self.side2)
+            B.lightkv_build_windows(self.batch, nx.h_cu_vis, nx.cu_vis, st.pos_out, self.tiles, self.grid_h,
+                                    self.grid_w, nx.w, nx.win_offsets, nx.win_tokens, stream=self.side2)
+            pos_here = None                                               # pos_out is written on the helper stream
+        if xi_given is None:
+            main.wait_stream(self.side)                                   # join: the merge needs xi
+        stream = main
         if self.fused:
-            B.lightkv_aggregate_compact(p, st.new_index, st.grp_offsets, st.grp_src, xi, X, K, V, pos, st.X_out,
-                                        st.K_out, st.V_out, st.pos_out, stream=stream)
+            B.lightkv_aggregate_compact(p, st.new_index, st.grp_offsets, st.grp_src, xi, X, K, V, pos_here, st.X_out,
+                                        st.K_out, st.V_out, None if pos_here is None else st.pos_out, stream=stream)
         else:
             n = X.shape[0]
             tx, tk, tv = (t[:n] for t in self.tmp)
@@ -125,7 +150,10 @@ class CompressionPipeline:
     def run(self, X, K, V, Q, pos, stream=None):
         """All stages back to back; returns the last stage's buffers (its *_out tensors hold the result)."""
         st = None
+        main = torch.cuda.current_stream() if stream is None else stream
         for s in range(len(self.stages)):
-            st = self.run_stage(s, X, K, V, Q, pos, stream=stream)
+            st = self.run_stage(s, X, K, V, Q, pos, stream=main, windows_ready=(s > 0 and self.fused),
+                                prepare_next=True)
             X, K, V, pos = st.X_out, st.K_out, st.V_out, st.pos_out
+        main.wait_stream(self.side2)   # nothing is left running on a helper stream when run() returns
         return st
