@@ -160,6 +160,19 @@ lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, co
                               int32_t *cu_vis_out, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * lightkv_score followed by lightkv_select in one call: same arguments, same outputs.  When every window holds at
+ * most 64 tokens, the row arg-min and the per-window selection run in one kernel (one launch less); otherwise the
+ * call is the two calls in sequence.  X must not be NULL; xi_mode GIVEN skips the xi half as in lightkv_score.
+ */
+lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int64_t ldx,
+                                    const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
+                                    const void *K, int64_t k_tok_stride, int64_t k_head_stride,
+                                    int32_t xi_mode, const float *lse, float softmax_scale,
+                                    float *xi, float *best_fd, int32_t *best_dst,
+                                    int32_t *dst, int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src,
+                                    int32_t *cu_vis_out, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Message passing (Step 3, Eq. "message-passing"), in place: every token b that has sources becomes
  *   y_b <- (xi_b*y_b + sum_a xi_a*y_a) / (xi_b + sum_a xi_a)       for y in {X, K, V} rows,
  * evaluated as y_b + sum_a w_a*(y_a - y_b), w_a = xi_a/(xi_b + sum xi_a), in fp32 (identical rows stay

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     lightkv_build_windows,
     lightkv_compact,
     lightkv_score,
+    lightkv_score_select,
     lightkv_select,
     lightkv_status_string,
     lightkv_version,

@@ -54,6 +54,9 @@ def _load():
     lib.lightkv_build_windows.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     lib.lightkv_score.restype = C.c_int
     lib.lightkv_score.argtypes = [P, vp, i64, vp, i64, i64, vp, i64, i64, i32, vp, f32, vp, vp, vp, vp, sz, vp]
+    lib.lightkv_score_select.restype = C.c_int
+    lib.lightkv_score_select.argtypes = [P, vp, i64, vp, i64, i64, vp, i64, i64, i32, vp, f32, vp, vp, vp,
+                                         vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lightkv_select.restype = C.c_int
     lib.lightkv_select.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lightkv_aggregate.restype = C.c_int
@@ -68,7 +71,7 @@ def _load():
 _lib = _load()
 
 EXPORTS = ("lightkv_status_string", "lightkv_version", "lightkv_workspace_size", "lightkv_build_windows",
-           "lightkv_score", "lightkv_select", "lightkv_aggregate", "lightkv_compact", "lightkv_aggregate_compact")
+           "lightkv_score", "lightkv_score_select", "lightkv_select", "lightkv_aggregate", "lightkv_compact", "lightkv_aggregate_compact")
 
 
 def _dptr(t: Optional[torch.Tensor]):
@@ -166,6 +169,26 @@ def lightkv_score(p: Problem, X, Q, K, xi, best_fd, best_dst, ws, *, heads_major
     _check(_lib.lightkv_score(p.ref(), _dptr(X), _ld(X), _dptr(Q), qts, qhs, _dptr(K), kts, khs, xi_mode,
                               _dptr(lse), float(softmax_scale), _dptr(xi), _dptr(best_fd), _dptr(best_dst),
                               _dptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "lightkv_score")
+
+
+def lightkv_score_select(p: Problem, X, Q, K, xi, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out,
+                         ws, *, heads_major=False, xi_mode=XI_TEXT_QUERY, lse=None, softmax_scale=0.0, stream=None):
+    hd = p.c.head_dim
+
+    def strides(t):
+        if t is None:
+            return 0, 0
+        if heads_major:
+            return int(t.stride(1)), int(t.stride(0))
+        return int(t.stride(0)), hd
+
+    qts, qhs = strides(Q)
+    kts, khs = strides(K)
+    _check(_lib.lightkv_score_select(p.ref(), _dptr(X), _ld(X), _dptr(Q), qts, qhs, _dptr(K), kts, khs, xi_mode,
+                                     _dptr(lse), float(softmax_scale), _dptr(xi), _dptr(best_fd), _dptr(best_dst),
+                                     _dptr(dst), _dptr(new_index), _dptr(grp_offsets), _dptr(grp_src),
+                                     _dptr(cu_vis_out), _dptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
+           "lightkv_score_select")
 
 
 def lightkv_select(p: Problem, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, ws, stream=None):

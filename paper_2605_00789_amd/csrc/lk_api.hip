@@ -194,12 +194,20 @@ lightkv_status lightkv_build_windows(int32_t batch, const int32_t *h_cu_vis, con
   return LIGHTKV_OK;
 }
 
-lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ldx,
-                             const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
-                             const void *K, int64_t k_tok_stride, int64_t k_head_stride,
-                             int32_t xi_mode, const float *lse, float softmax_scale,
-                             float *xi, float *best_fd, int32_t *best_dst,
-                             void *ws, size_t ws_bytes, void *stream) {
+}  // extern "C"
+
+namespace {
+struct SelectOut {   // outputs of lightkv_select, present when selection is to be fused behind the scores
+  int32_t *dst, *new_index, *grp_offsets, *grp_src, *cu_vis_out;
+};
+
+// sel == nullptr: plain lightkv_score.  Otherwise the caller guarantees that make_fd_small_fused_plan applies.
+lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx,
+                          const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
+                          const void *K, int64_t k_tok_stride, int64_t k_head_stride,
+                          int32_t xi_mode, const float *lse, float softmax_scale,
+                          float *xi, float *best_fd, int32_t *best_dst, const SelectOut *sel,
+                          void *ws, size_t ws_bytes, void *stream) {
   if (xi_mode < LIGHTKV_XI_TEXT_QUERY || xi_mode > LIGHTKV_XI_GIVEN) return LIGHTKV_ERR_UNSUPPORTED;
   const bool need_xi = xi_mode != LIGHTKV_XI_GIVEN;
   const bool need_fd = X != nullptr;   // X == NULL: only xi is wanted (the two halves may be enqueued separately)
@@ -262,6 +270,14 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
   lightkv_status fd_status = LIGHTKV_OK;
   if (!need_fd) {
     // xi only
+  } else if (sel) {
+    int32_t *cnt = reinterpret_cast<int32_t *>(wsb + l.sel_cnt), *rank = reinterpret_cast<int32_t *>(wsb + l.sel_rank);
+    if (launch_fd_select_small(fd, p->dtype, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
+                               p->win_remove, reinterpret_cast<float *>(wsb + l.fd_partial), best_fd, best_dst,
+                               sel->dst, cnt, rank, s) != hipSuccess ||
+        launch_select_scan(p->batch, c.sum_n, p->cu_vis, sel->dst, sel->new_index, sel->grp_offsets, sel->grp_src,
+                           sel->cu_vis_out, cnt, rank, s) != hipSuccess)
+      fd_status = LIGHTKV_ERR_LAUNCH;
   } else if (use_big) {
     if (launch_fd_big(big, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
                       reinterpret_cast<double *>(wsb + l.fd_norm),
@@ -274,6 +290,43 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
   }
   if (fk && hipStreamWaitEvent(s, fk->join, 0) != hipSuccess) return LIGHTKV_ERR_LAUNCH;   // join
   return fd_status;
+}
+}  // namespace
+
+extern "C" {
+
+lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ldx,
+                             const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
+                             const void *K, int64_t k_tok_stride, int64_t k_head_stride,
+                             int32_t xi_mode, const float *lse, float softmax_scale,
+                             float *xi, float *best_fd, int32_t *best_dst,
+                             void *ws, size_t ws_bytes, void *stream) {
+  return score_impl(p, X, ldx, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
+                    softmax_scale, xi, best_fd, best_dst, nullptr, ws, ws_bytes, stream);
+}
+
+lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int64_t ldx,
+                                    const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
+                                    const void *K, int64_t k_tok_stride, int64_t k_head_stride,
+                                    int32_t xi_mode, const float *lse, float softmax_scale,
+                                    float *xi, float *best_fd, int32_t *best_dst,
+                                    int32_t *dst, int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src,
+                                    int32_t *cu_vis_out, void *ws, size_t ws_bytes, void *stream) {
+  if (!X || !dst || !new_index || !grp_offsets || !grp_src || !cu_vis_out) return LIGHTKV_ERR_NULL;
+  Checked c;
+  lightkv_status st = check_problem(p, true, false, c);
+  if (st != LIGHTKV_OK) return st;
+  if (!p->win_remove) return LIGHTKV_ERR_NULL;
+  const FdPlan small = make_fd_small_fused_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
+  if ((small.n_tiles > 0 && !use_big_fd(p, c)) || p->n_windows == 0) {
+    const SelectOut sel{dst, new_index, grp_offsets, grp_src, cu_vis_out};
+    return score_impl(p, X, ldx, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
+                      softmax_scale, xi, best_fd, best_dst, &sel, ws, ws_bytes, stream);
+  }
+  st = score_impl(p, X, ldx, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
+                  softmax_scale, xi, best_fd, best_dst, nullptr, ws, ws_bytes, stream);
+  if (st != LIGHTKV_OK) return st;
+  return lightkv_select(p, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, ws, ws_bytes, stream);
 }
 
 lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, const int32_t *best_dst,

@@ -33,6 +33,14 @@ hipError_t launch_fd(const FdPlan &plan, int dtype, const void *X, int64_t ldx, 
                      const int32_t *win_offsets, const int32_t *win_tokens, float *partial, float *best_fd,
                      int32_t *best_dst, hipStream_t stream);
 
+// Windows of at most 64 tokens: partial tiles, then epilogue + per-window selection in one kernel
+// (n_tiles == 0: not applicable).
+FdPlan make_fd_small_fused_plan(int n_windows, int max_window_tokens, int d, int dtype_bytes);
+hipError_t launch_fd_select_small(const FdPlan &plan, int dtype, const void *X, int64_t ldx, int d, int n_windows,
+                                  int sum_n, const int32_t *win_offsets, const int32_t *win_tokens,
+                                  const int32_t *win_remove, float *partial, float *best_fd, int32_t *best_dst,
+                                  int32_t *dst, int32_t *cnt, int32_t *src_rank, hipStream_t stream);
+
 // Large windows (compute bound): LDS-tiled MFMA GEMM with the row arg-min fused into its epilogue.
 struct FdBigPlan {
   int wb;            // wave tile = (16*wb)^2, workgroup tile = (32*wb)^2
@@ -68,6 +76,11 @@ hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int su
                          const float *best_fd, const int32_t *best_dst, int32_t *dst, int32_t *new_index,
                          int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, int32_t *cnt,
                          int32_t *src_rank, hipStream_t stream);
+
+// the scan half of lightkv_select alone (dst, cnt, src_rank already written)
+hipError_t launch_select_scan(int batch, int sum_n, const int32_t *cu_vis, const int32_t *dst, int32_t *new_index,
+                              int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, const int32_t *cnt,
+                              const int32_t *src_rank, hipStream_t stream);
 
 // ---- message passing + compaction (Steps 3-5) ---------------------------------------------------
 struct RowTensors {

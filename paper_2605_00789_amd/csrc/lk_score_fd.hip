@@ -262,6 +262,190 @@ __global__ __launch_bounds__(FD_THREADS) void fd_epilogue_kernel(FdArgs g) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Windows that fit one 32 x 32 tile (at most 64 tokens): the epilogue AND the per-window selection (paper Step 2:
+// the r A nodes with the lowest FD) in one kernel.  fd_partial_kernel leaves the partial tiles; one workgroup per
+// tile sums them in their fixed order and finishes the tile in LDS: cosines, first minimum per row, rank of every
+// A node among the keys (FD bits, position) of its window, then dst / per-target source counts / rank of each
+// source in its group -- exactly what select_window_kernel derives from best_fd and best_dst.
+// (Handing the tile to "the last workgroup to arrive" inside fd_partial_kernel was tried and dropped: the
+// device-scope fence it needs writes back the L2 of the whole XCD and costs far more than a launch.)
+struct SmallSelArgs {
+  const int32_t *win_remove;
+  int32_t *dst, *cnt, *src_rank;
+};
+
+struct SmallTileLds {
+  double tile[32 * 32];
+  double n2[2][32];             // |a|^2 per tile row, |b|^2 per tile column
+  uint32_t row_key[32];         // order-preserving bits of the row's best FD (as stored in fp32)
+  int row_col[32], row_sel[32]; // best tile column (-1: none), 1 if the row is merged away
+  int row_tok[32], col_tok[32]; // token of tile row / column, -1 for padding
+  int row_win[32], col_win[32]; // window slot of tile row / column
+  int slot_r[32];               // r of the window in slot s (clamped)
+};
+
+// Finishes one tile from its summed dots and squared norms (in L.tile / L.n2).  Called by a whole workgroup.
+template <int THREADS>
+__device__ __forceinline__ void small_tile_tail(const FdArgs &g, const SmallSelArgs &q, int tile, SmallTileLds &L) {
+  const int tid = threadIdx.x;
+  if (tid < 32) {
+    const int r = tid;
+    int a_tok = -1, b_tok = -1, my_slot = 0, l = r;
+    WinInfo wi;
+    if (g.group > 1) {
+      my_slot = r / g.slot;
+      l = r - my_slot * g.slot;
+      wi = win_info(g, tile * g.group + my_slot);
+    } else {
+      wi = win_info(g, tile);
+    }
+    if (l < wi.nA) a_tok = checked_token(g, wi.off + 2 * l);
+    if (l < wi.nB) b_tok = checked_token(g, wi.off + 2 * l + 1);
+    L.row_tok[r] = a_tok; L.col_tok[r] = b_tok; L.row_win[r] = my_slot; L.col_win[r] = my_slot;
+    if (l == 0) {   // first row of a window slot: its removal count
+      const int w = (g.group > 1) ? tile * g.group + my_slot : tile;
+      int rr = (w < g.n_windows) ? q.win_remove[w] : 0;
+      const int cap = (g.group > 1) ? g.slot : 32;
+      const int nA = wi.nA < cap ? wi.nA : cap;
+      rr = rr < 0 ? 0 : (rr > nA ? nA : rr);
+      if (wi.nB == 0) rr = 0;
+      L.slot_r[my_slot] = rr;
+    }
+  }
+  __syncthreads();
+  // FD and first minimum per row: THREADS/32 threads per row
+  constexpr int TPR = THREADS / 32;          // threads per row (8 or 16)
+  constexpr int CPT = 32 / TPR;              // columns per thread
+  {
+    const int rr = tid / TPR, cl = tid % TPR;
+    const int ta = L.row_tok[rr];
+    const int sw = L.row_win[rr];
+    double best = __longlong_as_double(0x7ff0000000000000ll);
+    int best_c = 0x7fffffff;
+    const double a2 = L.n2[0][rr];
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int c = cl + TPR * k;
+      if (ta >= 0 && L.col_tok[c] >= 0 && L.col_win[c] == sw) {
+        const double dot = L.tile[rr * 32 + c];
+        const double b2 = L.n2[1][c];
+        double den;
+        if (a2 >= NORM_EPS * NORM_EPS && b2 >= NORM_EPS * NORM_EPS) den = sqrt(a2 * b2);
+        else den = fmax(sqrt(a2), NORM_EPS) * fmax(sqrt(b2), NORM_EPS);
+        const double fd = fmax(1.0 - dot / den, 0.0);
+        if (fd < best) { best = fd; best_c = c; }   // columns ascend: strict < keeps the first minimum
+      }
+    }
+#pragma unroll
+    for (int m = TPR / 2; m >= 1; m >>= 1) {
+      const double ob = __shfl_xor(best, m, 64);
+      const int oc = __shfl_xor(best_c, m, 64);
+      if (ob < best || (ob == best && oc < best_c)) { best = ob; best_c = oc; }
+    }
+    if (cl == 0) {
+      const bool has = best_c != 0x7fffffff;
+      float f = has ? (float)best : __uint_as_float(0x7f800000u);
+      // first column of the row's window: the fall-back partner of a row without any finite score
+      int first_c = -1;
+      for (int c = 0; c < 32; ++c)
+        if (first_c < 0 && L.col_tok[c] >= 0 && L.col_win[c] == sw) first_c = c;
+      const int bc = has ? best_c : first_c;
+      if (!(f >= 0.f)) f = __uint_as_float(0x7f800000u);
+      L.row_key[rr] = f32_order_key(f);
+      L.row_col[rr] = bc;
+      if (ta >= 0) {
+        g.best_fd[ta] = f;
+        g.best_dst[ta] = bc >= 0 ? L.col_tok[bc] : -1;
+      }
+    }
+    if (cl == 1 && L.col_tok[rr] >= 0) {   // B rows carry no proposal
+      g.best_fd[L.col_tok[rr]] = __uint_as_float(0x7f800000u);
+      g.best_dst[L.col_tok[rr]] = -1;
+    }
+  }
+  __syncthreads();
+  // selection: rank of every A node among the keys (FD, position) of its window
+  if (tid < 32) {
+    const int rr = tid;
+    int sel = 0;
+    if (L.row_tok[rr] >= 0 && L.row_col[rr] >= 0) {
+      const uint64_t key = ((uint64_t)L.row_key[rr] << 32) | (uint32_t)rr;
+      int rank = 0;
+      for (int o = 0; o < 32; ++o)
+        if (L.row_tok[o] >= 0 && L.row_win[o] == L.row_win[rr] && ((((uint64_t)L.row_key[o]) << 32) | (uint32_t)o) < key) ++rank;
+      sel = rank < L.slot_r[L.row_win[rr]];
+    }
+    L.row_sel[rr] = sel;
+  }
+  __syncthreads();
+  if (tid < 32) {            // A rows: destination and rank among the sources of that destination
+    const int rr = tid, ta = L.row_tok[rr];
+    if (ta >= 0) {
+      int rank = 0;
+      if (L.row_sel[rr])
+        for (int o = 0; o < rr; ++o)
+          if (L.row_sel[o] && L.row_win[o] == L.row_win[rr] && L.row_col[o] == L.row_col[rr]) ++rank;
+      q.dst[ta] = L.row_sel[rr] ? L.col_tok[L.row_col[rr]] : -1;
+      q.src_rank[ta] = rank;
+      q.cnt[ta] = 0;
+    }
+  } else if (tid < 64) {     // B columns: number of sources
+    const int cc = tid - 32, tb = L.col_tok[cc];
+    if (tb >= 0) {
+      int n = 0;
+      for (int o = 0; o < 32; ++o)
+        if (L.row_sel[o] && L.row_win[o] == L.col_win[cc] && L.row_col[o] == cc) ++n;
+      q.dst[tb] = -1;
+      q.src_rank[tb] = 0;
+      q.cnt[tb] = n;
+    }
+  }
+}
+
+// One workgroup per tile: partial tiles summed in slice order, then the tile is finished in LDS.
+__global__ __launch_bounds__(FD_THREADS) void fd_tail_select_kernel(FdArgs g, SmallSelArgs q) {
+  __shared__ SmallTileLds L;
+  const int tile = blockIdx.x, tid = threadIdx.x;
+  const int64_t ks_stride = (int64_t)g.n_tiles * FD_TILE_FLOATS;
+  const float *base = g.partial + (int64_t)tile * FD_TILE_FLOATS;
+  // a tile without A rows or without B rows was never written by fd_partial_kernel: its sums are not used either
+  for (int e = tid; e < 32 * 32; e += FD_THREADS) L.tile[e] = sum_slices(base + e, ks_stride, g.ksplit);
+  if (tid < 64) L.n2[tid >> 5][tid & 31] = sum_slices(base + 32 * 32 + tid, ks_stride, g.ksplit);
+  __syncthreads();
+  small_tile_tail<FD_THREADS>(g, q, tile, L);
+}
+
+FdPlan make_fd_small_fused_plan(int n_windows, int max_window_tokens, int d, int dtype_bytes) {
+  FdPlan p{};
+  const int maxA = (max_window_tokens + 1) / 2;
+  if (maxA > 32) return p;   // n_tiles == 0: not applicable
+  return make_fd_plan(n_windows, max_window_tokens, d, dtype_bytes);   // single-tile windows: mt == nt == 1
+}
+
+hipError_t launch_fd_select_small(const FdPlan &plan, int dtype, const void *X, int64_t ldx, int d, int n_windows,
+                                  int sum_n, const int32_t *win_offsets, const int32_t *win_tokens,
+                                  const int32_t *win_remove, float *partial, float *best_fd, int32_t *best_dst,
+                                  int32_t *dst, int32_t *cnt, int32_t *src_rank, hipStream_t stream) {
+  if (n_windows == 0 || plan.n_tiles == 0) return hipSuccess;
+  FdArgs g{};
+  g.X = X; g.ldx = ldx; g.d = d; g.n_windows = n_windows; g.sum_n = sum_n;
+  g.win_offsets = win_offsets; g.win_tokens = win_tokens;
+  g.partial = partial; g.best_fd = best_fd; g.best_dst = best_dst;
+  g.slot = plan.slot; g.group = plan.group; g.mt = 1; g.nt = 1; g.n_tiles = plan.n_tiles; g.ksplit = plan.ksplit;
+  const int span = (dtype == 1) ? 64 : 32;
+  g.n_spans = (d + span - 1) / span;
+  g.spans_per_wg = (g.n_spans + plan.ksplit - 1) / plan.ksplit;
+  const dim3 grid((unsigned)(plan.n_tiles * plan.ksplit));
+  if (dtype == 1) hipLaunchKernelGGL(fd_partial_kernel<bf16_t>, grid, dim3(FD_THREADS), 0, stream, g);
+  else hipLaunchKernelGGL(fd_partial_kernel<float>, grid, dim3(FD_THREADS), 0, stream, g);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  SmallSelArgs q{win_remove, dst, cnt, src_rank};
+  hipLaunchKernelGGL(fd_tail_select_kernel, dim3((unsigned)plan.n_tiles), dim3(FD_THREADS), 0, stream, g, q);
+  return hipGetLastError();
+}
+
 FdPlan make_fd_plan(int n_windows, int max_window_tokens, int d, int dtype_bytes) {
   FdPlan p{};
   const int maxA = (max_window_tokens + 1) / 2, maxB = max_window_tokens / 2;

@@ -179,6 +179,17 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g) {
   }
 }
 
+hipError_t launch_select_scan(int batch, int sum_n, const int32_t *cu_vis, const int32_t *dst, int32_t *new_index,
+                              int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, const int32_t *cnt,
+                              const int32_t *src_rank, hipStream_t stream) {
+  SelArgs g{};
+  g.batch = batch; g.sum_n = sum_n; g.cu_vis = cu_vis;
+  g.dst = const_cast<int32_t *>(dst); g.new_index = new_index; g.grp_offsets = grp_offsets; g.grp_src = grp_src;
+  g.cu_vis_out = cu_vis_out; g.cnt = const_cast<int32_t *>(cnt); g.src_rank = const_cast<int32_t *>(src_rank);
+  hipLaunchKernelGGL(select_scan_kernel, dim3(1), dim3(SCAN_THREADS), 0, stream, g);
+  return hipGetLastError();
+}
+
 hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int sum_n, const int32_t *cu_vis,
                          const int32_t *win_offsets, const int32_t *win_tokens, const int32_t *win_remove,
                          const float *best_fd, const int32_t *best_dst, int32_t *dst, int32_t *new_index,

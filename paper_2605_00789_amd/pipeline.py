@@ -121,9 +121,13 @@ class CompressionPipeline:
         else:
             B.lightkv_build_windows(self.batch, st.h_cu_vis, st.cu_vis, pos, self.tiles, self.grid_h, self.grid_w, st.w,
                                     st.win_offsets, st.win_tokens, stream=main)
-        B.lightkv_score(p, X, None, None, xi, st.best_fd, st.best_dst, self.ws, xi_mode=B.XI_GIVEN, stream=main)  # FD half
-        B.lightkv_select(p, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets, st.grp_src,
-                         st.cu_vis_out, self.ws, stream=main)
+        if self.fused:   # FD half + selection (one kernel where the windows are small)
+            B.lightkv_score_select(p, X, None, None, xi, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets,
+                                   st.grp_src, st.cu_vis_out, self.ws, xi_mode=B.XI_GIVEN, stream=main)
+        else:
+            B.lightkv_score(p, X, None, None, xi, st.best_fd, st.best_dst, self.ws, xi_mode=B.XI_GIVEN, stream=main)
+            B.lightkv_select(p, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets, st.grp_src,
+                             st.cu_vis_out, self.ws, stream=main)
         pos_here = pos
         if prepare_next and self.fused and s + 1 < len(self.stages):
             nx = self.stages[s + 1]

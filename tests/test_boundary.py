@@ -107,6 +107,12 @@ def test_entry_points_reject_bad_arguments_before_launch(B):
     assert lib.lightkv_score(*args(ws=None)) == 6
     assert lib.lightkv_score(*args(wsb=ws - 1)) == 6
     assert lib.lightkv_score(*args(ws=C.c_void_p(0x1010))) == 6                  # workspace alignment
+    # score_select: the union of both argument lists
+    ss = lambda **o: [C.byref(p), o.get("X", fake), 64, fake, 64, 32, fake, 64, 32, 0, None, 0.0, fake, fake, fake,
+                      o.get("dst", fake), fake, fake, fake, fake, o.get("ws", fake), o.get("wsb", ws), None]
+    assert lib.lightkv_score_select(*ss(X=None)) == 1
+    assert lib.lightkv_score_select(*ss(dst=None)) == 1
+    assert lib.lightkv_score_select(*ss(wsb=8)) == 6
     # select
     assert lib.lightkv_select(C.byref(p), fake, fake, None, fake, fake, fake, fake, fake, ws, None) == 1
     assert lib.lightkv_select(C.byref(p), fake, fake, fake, fake, fake, fake, fake, fake, 16, None) == 6
