@@ -57,7 +57,8 @@ __device__ __forceinline__ void load_half_row(const void *base, int first, int i
 template <typename T, int DH> struct XiStage {
   static constexpr int ROW_BYTES = DH * Elem<T>::BYTES;
   static constexpr int PITCH = ROW_BYTES + 16;
-  static constexpr int ROWS = ROW_BYTES > 256 ? 64 : 128;   // prompt rows per staged chunk (<= 34 KB of LDS)
+  static constexpr int ROWS = 64;   // prompt rows per staged chunk: at most 34 KB of LDS (17 KB for bf16 heads of 128), which
+                                    // leaves room on the CU for the kernels of the FD branch that run next to this one
   static constexpr int TILES = ROWS / 32;
   static constexpr int CPR = ROW_BYTES / 16;                // 16-byte chunks per row
 };
