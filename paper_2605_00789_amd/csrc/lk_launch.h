@@ -20,7 +20,8 @@ struct FdPlan {
   int ksplit;
   size_t partial_floats;   // n_tiles * ksplit * FD_TILE_FLOATS
 };
-constexpr int FD_TILE_FLOATS = 32 * 32 + 32 + 32;   // dots, |a|^2 partials, |b|^2 partials
+constexpr int FD_TOK_OFFSET = 32 * 32 + 32 + 32;    // dots, |a|^2 partials, |b|^2 partials ...
+constexpr int FD_TILE_FLOATS = FD_TOK_OFFSET + 64;  // ... then (slice 0 only) the tokens of the 32 rows and 32 columns
 constexpr int FD_MAX_COLS = 2048;                   // |B| of the largest supported window
 
 FdPlan make_fd_plan(int n_windows, int max_window_tokens, int d, int dtype_bytes);

@@ -85,6 +85,9 @@ __global__ __launch_bounds__(FD_THREADS) void fd_partial_kernel(FdArgs g) {
     need_na = (nt == 0);
     need_nb = (mt == 0);
   }
+  // slice 0 leaves the tile's token lists (rows, then columns) for the kernel that finishes the tile
+  if (ks == 0 && wave == 0)
+    reinterpret_cast<int32_t *>(g.partial + (int64_t)tile * FD_TILE_FLOATS + FD_TOK_OFFSET)[lane] = half ? b_tok : a_tok;
   // a tile without A rows or without B rows is never read by the epilogue
   if (__ballot(a_tok >= 0) == 0ull || __ballot(b_tok >= 0) == 0ull) return;
 
@@ -279,63 +282,73 @@ struct SmallTileLds {
   double tile[32 * 32];
   double n2[2][32];             // |a|^2 per tile row, |b|^2 per tile column
   uint32_t row_key[32];         // order-preserving bits of the row's best FD (as stored in fp32)
-  int row_col[32], row_sel[32]; // best tile column (-1: none), 1 if the row is merged away
+  int row_col[32];              // best tile column (-1: none)
   int row_tok[32], col_tok[32]; // token of tile row / column, -1 for padding
-  int row_win[32], col_win[32]; // window slot of tile row / column
   int slot_r[32];               // r of the window in slot s (clamped)
+  uint32_t col_mask;            // bit c set: tile column c holds a B node
 };
 
-// Finishes one tile from its summed dots and squared norms (in L.tile / L.n2).  Called by a whole workgroup.
-template <int THREADS>
-__device__ __forceinline__ void small_tile_tail(const FdArgs &g, const SmallSelArgs &q, int tile, SmallTileLds &L) {
-  const int tid = threadIdx.x;
-  if (tid < 32) {
-    const int r = tid;
-    int a_tok = -1, b_tok = -1, my_slot = 0, l = r;
-    WinInfo wi;
-    if (g.group > 1) {
-      my_slot = r / g.slot;
-      l = r - my_slot * g.slot;
-      wi = win_info(g, tile * g.group + my_slot);
-    } else {
-      wi = win_info(g, tile);
-    }
-    if (l < wi.nA) a_tok = checked_token(g, wi.off + 2 * l);
-    if (l < wi.nB) b_tok = checked_token(g, wi.off + 2 * l + 1);
-    L.row_tok[r] = a_tok; L.col_tok[r] = b_tok; L.row_win[r] = my_slot; L.col_win[r] = my_slot;
-    if (l == 0) {   // first row of a window slot: its removal count
-      const int w = (g.group > 1) ? tile * g.group + my_slot : tile;
-      int rr = (w < g.n_windows) ? q.win_remove[w] : 0;
+// One workgroup per tile: partial tiles summed in slice order, then the tile is finished in LDS.
+// Every global load of the kernel is independent of the others (the token lists of the tile come from the
+// record fd_partial_kernel left with slice 0), so all of them are in flight together.
+__global__ __launch_bounds__(FD_THREADS) void fd_tail_select_kernel(FdArgs g, SmallSelArgs q) {
+  __shared__ SmallTileLds L;
+  const int tile = blockIdx.x, tid = threadIdx.x;
+  const int64_t ks_stride = (int64_t)g.n_tiles * FD_TILE_FLOATS;
+  const float *base = g.partial + (int64_t)tile * FD_TILE_FLOATS;
+  const int shift = (g.group > 1) ? (g.slot == 8 ? 3 : 4) : 5;   // tile row or column >> shift = its window slot
+
+  // ---- metadata (wave 0) and partial sums (everyone)
+  int m_tok = -1, m_off = 0, m_end = 0, m_rem = 0;
+  if (tid < 64) {
+    m_tok = reinterpret_cast<const int32_t *>(base + FD_TOK_OFFSET)[tid];   // rows 0..31, then columns 0..31
+    const int rr = tid & 31;
+    const int w = tile * g.group + (rr >> shift);
+    const int wc = w < g.n_windows ? w : g.n_windows - 1;
+    m_off = g.win_offsets[wc]; m_end = g.win_offsets[wc + 1]; m_rem = q.win_remove[wc];
+    if (w >= g.n_windows) { m_end = m_off; m_rem = 0; }
+  }
+  // a tile without A rows or without B rows has no sums from fd_partial_kernel: they are not used either
+  for (int e = tid; e < 32 * 32; e += FD_THREADS) L.tile[e] = sum_slices(base + e, ks_stride, g.ksplit);
+  if (tid < 64) {
+    L.n2[tid >> 5][tid & 31] = sum_slices(base + 32 * 32 + tid, ks_stride, g.ksplit);
+    if (tid < 32) L.row_tok[tid] = m_tok; else L.col_tok[tid - 32] = m_tok;
+    const unsigned long long cm = __ballot(tid >= 32 && m_tok >= 0);
+    if (tid == 0) L.col_mask = (uint32_t)(cm >> 32);
+    if (tid < 32 && (tid & ((1 << shift) - 1)) == 0) {   // first row of a window slot: its removal count
+      const int v = m_end - m_off;
       const int cap = (g.group > 1) ? g.slot : 32;
-      const int nA = wi.nA < cap ? wi.nA : cap;
-      rr = rr < 0 ? 0 : (rr > nA ? nA : rr);
-      if (wi.nB == 0) rr = 0;
-      L.slot_r[my_slot] = rr;
+      int nA = (v + 1) >> 1;
+      nA = nA < cap ? nA : cap;
+      int rr = m_rem < 0 ? 0 : (m_rem > nA ? nA : m_rem);
+      if ((v >> 1) == 0) rr = 0;
+      L.slot_r[tid >> shift] = rr;
     }
   }
   __syncthreads();
-  // FD and first minimum per row: THREADS/32 threads per row
-  constexpr int TPR = THREADS / 32;          // threads per row (8 or 16)
-  constexpr int CPT = 32 / TPR;              // columns per thread
+
+  // ---- FD and first minimum per row: 8 threads per row, 4 columns each
+  constexpr int TPR = FD_THREADS / 32;
+  constexpr int CPT = 32 / TPR;
   {
     const int rr = tid / TPR, cl = tid % TPR;
     const int ta = L.row_tok[rr];
-    const int sw = L.row_win[rr];
+    const int sw = rr >> shift;
+    const uint32_t cols = L.col_mask & ((shift == 5) ? 0xffffffffu : (((1u << (1 << shift)) - 1u) << (sw << shift)));
     double best = __longlong_as_double(0x7ff0000000000000ll);
     int best_c = 0x7fffffff;
     const double a2 = L.n2[0][rr];
 #pragma unroll
     for (int k = 0; k < CPT; ++k) {
       const int c = cl + TPR * k;
-      if (ta >= 0 && L.col_tok[c] >= 0 && L.col_win[c] == sw) {
-        const double dot = L.tile[rr * 32 + c];
-        const double b2 = L.n2[1][c];
-        double den;
-        if (a2 >= NORM_EPS * NORM_EPS && b2 >= NORM_EPS * NORM_EPS) den = sqrt(a2 * b2);
-        else den = fmax(sqrt(a2), NORM_EPS) * fmax(sqrt(b2), NORM_EPS);
-        const double fd = fmax(1.0 - dot / den, 0.0);
-        if (fd < best) { best = fd; best_c = c; }   // columns ascend: strict < keeps the first minimum
-      }
+      const double dot = L.tile[rr * 32 + c];
+      const double b2 = L.n2[1][c];
+      double den;
+      if (a2 >= NORM_EPS * NORM_EPS && b2 >= NORM_EPS * NORM_EPS) den = sqrt(a2 * b2);
+      else den = fmax(sqrt(a2), NORM_EPS) * fmax(sqrt(b2), NORM_EPS);
+      const double fd = fmax(1.0 - dot / den, 0.0);
+      const bool live = ta >= 0 && ((cols >> c) & 1u);
+      if (live && fd < best) { best = fd; best_c = c; }   // columns ascend: strict < keeps the first minimum
     }
 #pragma unroll
     for (int m = TPR / 2; m >= 1; m >>= 1) {
@@ -346,10 +359,8 @@ __device__ __forceinline__ void small_tile_tail(const FdArgs &g, const SmallSelA
     if (cl == 0) {
       const bool has = best_c != 0x7fffffff;
       float f = has ? (float)best : __uint_as_float(0x7f800000u);
-      // first column of the row's window: the fall-back partner of a row without any finite score
-      int first_c = -1;
-      for (int c = 0; c < 32; ++c)
-        if (first_c < 0 && L.col_tok[c] >= 0 && L.col_win[c] == sw) first_c = c;
+      // a row without any finite score falls back to the first B node of its window
+      const int first_c = cols ? __ffs((int)cols) - 1 : -1;
       const int bc = has ? best_c : first_c;
       if (!(f >= 0.f)) f = __uint_as_float(0x7f800000u);
       L.row_key[rr] = f32_order_key(f);
@@ -365,55 +376,49 @@ __device__ __forceinline__ void small_tile_tail(const FdArgs &g, const SmallSelA
     }
   }
   __syncthreads();
-  // selection: rank of every A node among the keys (FD, position) of its window
-  if (tid < 32) {
-    const int rr = tid;
-    int sel = 0;
-    if (L.row_tok[rr] >= 0 && L.row_col[rr] >= 0) {
-      const uint64_t key = ((uint64_t)L.row_key[rr] << 32) | (uint32_t)rr;
-      int rank = 0;
-      for (int o = 0; o < 32; ++o)
-        if (L.row_tok[o] >= 0 && L.row_win[o] == L.row_win[rr] && ((((uint64_t)L.row_key[o]) << 32) | (uint32_t)o) < key) ++rank;
-      sel = rank < L.slot_r[L.row_win[rr]];
-    }
-    L.row_sel[rr] = sel;
-  }
-  __syncthreads();
-  if (tid < 32) {            // A rows: destination and rank among the sources of that destination
-    const int rr = tid, ta = L.row_tok[rr];
-    if (ta >= 0) {
-      int rank = 0;
-      if (L.row_sel[rr])
-        for (int o = 0; o < rr; ++o)
-          if (L.row_sel[o] && L.row_win[o] == L.row_win[rr] && L.row_col[o] == L.row_col[rr]) ++rank;
-      q.dst[ta] = L.row_sel[rr] ? L.col_tok[L.row_col[rr]] : -1;
-      q.src_rank[ta] = rank;
-      q.cnt[ta] = 0;
-    }
-  } else if (tid < 64) {     // B columns: number of sources
-    const int cc = tid - 32, tb = L.col_tok[cc];
-    if (tb >= 0) {
-      int n = 0;
-      for (int o = 0; o < 32; ++o)
-        if (L.row_sel[o] && L.row_win[o] == L.col_win[cc] && L.row_col[o] == cc) ++n;
-      q.dst[tb] = -1;
-      q.src_rank[tb] = 0;
-      q.cnt[tb] = n;
-    }
-  }
-}
 
-// One workgroup per tile: partial tiles summed in slice order, then the tile is finished in LDS.
-__global__ __launch_bounds__(FD_THREADS) void fd_tail_select_kernel(FdArgs g, SmallSelArgs q) {
-  __shared__ SmallTileLds L;
-  const int tile = blockIdx.x, tid = threadIdx.x;
-  const int64_t ks_stride = (int64_t)g.n_tiles * FD_TILE_FLOATS;
-  const float *base = g.partial + (int64_t)tile * FD_TILE_FLOATS;
-  // a tile without A rows or without B rows was never written by fd_partial_kernel: its sums are not used either
-  for (int e = tid; e < 32 * 32; e += FD_THREADS) L.tile[e] = sum_slices(base + e, ks_stride, g.ksplit);
-  if (tid < 64) L.n2[tid >> 5][tid & 31] = sum_slices(base + 32 * 32 + tid, ks_stride, g.ksplit);
-  __syncthreads();
-  small_tile_tail<FD_THREADS>(g, q, tile, L);
+  // ---- selection by wave 0, row data in registers: lanes 0..31 act for the tile rows (A nodes), lanes 32..63
+  // for the tile columns (B nodes).  Values of other rows are read with constant-lane broadcasts.
+  if (tid < 64) {
+    const int rr = tid & 31;
+    const int tok = L.row_tok[rr], col = L.row_col[rr];
+    const uint32_t key = L.row_key[rr];
+    const int win = rr >> shift;
+    const int valid = tok >= 0 ? 1 : 0;
+    int rank = 0;
+#pragma unroll
+    for (int o = 0; o < 32; ++o) {
+      const uint32_t ko = (uint32_t)__builtin_amdgcn_readlane((int)key, o);
+      const int vo = __builtin_amdgcn_readlane(valid, o);
+      rank += (vo && (o >> shift) == win && (ko < key || (ko == key && o < rr))) ? 1 : 0;
+    }
+    const bool sel = valid && col >= 0 && rank < L.slot_r[win];
+    const uint32_t selmask = (uint32_t)__ballot(sel);   // lanes 0..31
+    // rows: rank among the earlier sources of the same destination; columns: number of sources
+    const bool is_col = tid >= 32;
+    const int target = is_col ? rr : col;
+    const int limit = is_col ? 32 : rr;
+    int n = 0;
+#pragma unroll
+    for (int o = 0; o < 32; ++o) {
+      const int co = __builtin_amdgcn_readlane(col, o);
+      n += (((selmask >> o) & 1u) && (o >> shift) == win && co == target && o < limit) ? 1 : 0;
+    }
+    if (!is_col) {
+      if (tok >= 0) {
+        q.dst[tok] = sel ? L.col_tok[col] : -1;
+        q.src_rank[tok] = sel ? n : 0;
+        q.cnt[tok] = 0;
+      }
+    } else {
+      const int tb = L.col_tok[rr];
+      if (tb >= 0) {
+        q.dst[tb] = -1;
+        q.src_rank[tb] = 0;
+        q.cnt[tb] = n;
+      }
+    }
+  }
 }
 
 FdPlan make_fd_small_fused_plan(int n_windows, int max_window_tokens, int d, int dtype_bytes) {

@@ -109,73 +109,102 @@ __global__ __launch_bounds__(THREADS) void select_window_kernel(SelArgs g) {
   }
 }
 
-// Single workgroup: scans over all tokens of the batch.
+// Single workgroup: scans over all tokens of the batch.  Every thread owns a run of consecutive tokens, so one
+// pass needs a single workgroup scan (two values at once) instead of one per 1024 tokens; all loads of a pass are
+// issued together.
 constexpr int SCAN_THREADS = 1024;
-__device__ __forceinline__ int block_exclusive_scan(int v, int *lds, int &total) {
-  // lds: SCAN_THREADS ints
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(inc, o, 64);
-    if (lane >= o) inc += t;
-  }
-  if (lane == 63) lds[wave] = inc;
-  __syncthreads();
-  if (wave == 0) {
-    int ws = (lane < SCAN_THREADS / 64) ? lds[lane] : 0;
-#pragma unroll
-    for (int o = 1; o < 16; o <<= 1) {
-      const int t = __shfl_up(ws, o, 64);
-      if (lane >= o) ws += t;
-    }
-    if (lane < SCAN_THREADS / 64) lds[32 + lane] = ws;   // inclusive over waves
-  }
-  __syncthreads();
-  const int wave_off = wave ? lds[32 + wave - 1] : 0;
-  total = lds[32 + SCAN_THREADS / 64 - 1];
-  __syncthreads();
-  return wave_off + inc - v;
-}
+constexpr int SCAN_ITEMS = 12;     // tokens per thread and pass (12288 tokens per pass)
+constexpr int FILL_UNROLL = 4;
 
 __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g) {
-  __shared__ int lds[64];
+  __shared__ int kb[SCAN_THREADS * SCAN_ITEMS];   // staying tokens before each token of the pass
+  __shared__ int2 wsum[SCAN_THREADS / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int s_first = g.cu_vis[tid <= g.batch ? tid : g.batch];   // sequence start handled by this thread (first round)
+  int per = (g.sum_n + SCAN_THREADS - 1) / SCAN_THREADS;
+  per = per < 1 ? 1 : (per > SCAN_ITEMS ? SCAN_ITEMS : per);
+  const int pass_tokens = per * SCAN_THREADS;
   int keep_base = 0, cnt_base = 0;
-  for (int i0 = 0; i0 < g.sum_n; i0 += SCAN_THREADS) {
-    const int i = i0 + threadIdx.x;
-    int keep = 0, c = 0;
-    if (i < g.sum_n) {
-      keep = g.dst[i] < 0 ? 1 : 0;
-      c = g.cnt[i];
+  for (int pass_base = 0; pass_base < g.sum_n; pass_base += pass_tokens) {
+    const int i0 = pass_base + tid * per;
+    int d[SCAN_ITEMS], c[SCAN_ITEMS];
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+      const bool ok = k < per && i0 + k < g.sum_n;
+      const int ic = ok ? i0 + k : 0;            // unconditional loads from a clamped index
+      const int dv = g.dst[ic], cv = g.cnt[ic];
+      d[k] = ok ? dv : 0;
+      c[k] = ok ? cv : 0;
     }
-    int tk, tc;
-    const int ek = block_exclusive_scan(keep, lds, tk);
-    const int ec = block_exclusive_scan(c, lds, tc);
-    if (i < g.sum_n) {
-      g.new_index[i] = keep ? keep_base + ek : -1;
-      g.grp_offsets[i] = cnt_base + ec;
+    int ks = 0, cs = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+      const bool ok = k < per && i0 + k < g.sum_n;
+      ks += (ok && d[k] < 0) ? 1 : 0;
+      cs += c[k];
     }
-    keep_base += tk;
-    cnt_base += tc;
+    int ik = ks, ic2 = cs;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int tk = __shfl_up(ik, o, 64), tc = __shfl_up(ic2, o, 64);
+      if (lane >= o) { ik += tk; ic2 += tc; }
+    }
+    if (lane == 63) wsum[wave] = make_int2(ik, ic2);
+    __syncthreads();
+    int wk = 0, wc = 0, tot_k = 0, tot_c = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < SCAN_THREADS / 64; ++w2) {
+      const int2 v = wsum[w2];
+      wk += (w2 < wave) ? v.x : 0;
+      wc += (w2 < wave) ? v.y : 0;
+      tot_k += v.x;
+      tot_c += v.y;
+    }
+    int ek = keep_base + wk + ik - ks, ec = cnt_base + wc + ic2 - cs;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+      const bool ok = k < per && i0 + k < g.sum_n;
+      if (ok) {
+        const int keep = d[k] < 0 ? 1 : 0;
+        kb[tid * per + k] = ek;
+        g.new_index[i0 + k] = keep ? ek : -1;
+        g.grp_offsets[i0 + k] = ec;
+        ek += keep;
+        ec += c[k];
+      }
+    }
+    __syncthreads();
+    // vision offsets after the step: staying tokens before each sequence start that falls into this pass
+    const int pass_end = min(pass_base + pass_tokens, g.sum_n);
+    for (int b = tid; b <= g.batch; b += SCAN_THREADS) {
+      const int s = (b == tid) ? s_first : g.cu_vis[b];
+      if (s >= pass_base && s < pass_end) g.cu_vis_out[b] = kb[s - pass_base];
+    }
+    keep_base += tot_k;
+    cnt_base += tot_c;
+    __syncthreads();
   }
-  if (threadIdx.x == 0) g.grp_offsets[g.sum_n] = cnt_base;
-  __syncthreads();   // new_index / grp_offsets written by this workgroup are visible to it below
-  // vision offsets after the step: staying tokens before each sequence start
-  for (int b = threadIdx.x; b <= g.batch; b += SCAN_THREADS) {
-    const int s = g.cu_vis[b];
-    int val;
-    if (s >= g.sum_n) val = keep_base;
-    else {
-      // new_index of the first staying token at or after s == number of staying tokens before s
-      int i = s;
-      while (i < g.sum_n && g.dst[i] >= 0) ++i;
-      val = (i < g.sum_n) ? g.new_index[i] : keep_base;
-    }
-    g.cu_vis_out[b] = val;
+  for (int b = tid; b <= g.batch; b += SCAN_THREADS) {
+    const int s = (b == tid) ? s_first : g.cu_vis[b];
+    if (s >= g.sum_n) g.cu_vis_out[b] = keep_base;
   }
-  for (int a = threadIdx.x; a < g.sum_n; a += SCAN_THREADS) {
-    const int b = g.dst[a];
-    if (b >= 0) g.grp_src[g.grp_offsets[b] + g.src_rank[a]] = a;
+  if (tid == 0) g.grp_offsets[g.sum_n] = cnt_base;
+  __syncthreads();   // grp_offsets written by this workgroup are visible to it below
+  for (int a0 = 0; a0 < g.sum_n; a0 += FILL_UNROLL * SCAN_THREADS) {
+    int b[FILL_UNROLL], sr[FILL_UNROLL], go[FILL_UNROLL];
+#pragma unroll
+    for (int j = 0; j < FILL_UNROLL; ++j) {
+      const int a = a0 + j * SCAN_THREADS + tid;
+      const int ac = a < g.sum_n ? a : 0;
+      const int bv = g.dst[ac], sv = g.src_rank[ac];
+      b[j] = a < g.sum_n ? bv : -1;
+      sr[j] = sv;
+    }
+#pragma unroll
+    for (int j = 0; j < FILL_UNROLL; ++j) go[j] = g.grp_offsets[b[j] >= 0 ? b[j] : 0];
+#pragma unroll
+    for (int j = 0; j < FILL_UNROLL; ++j)
+      if (b[j] >= 0) g.grp_src[go[j] + sr[j]] = a0 + j * SCAN_THREADS + tid;
   }
 }
 
