@@ -173,21 +173,40 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
     }
   };
   const char *lds_r = lds + l16 * BIG_PITCH + wave * 64 + kg * 16;
-  auto compute = [&](int stage) {
-    // this wave's quarter of the k-step: 32 elements = one MFMA deep; lane supplies row l16, k-group kg
+  // One k-step: the operand fragments of `stage` are read first; then the 36 MFMAs are issued with the 12 LDS stores
+  // that move step ks + 1 from its ring slot into the other stage slotted between them (3 MFMAs, 1 store, ...), so
+  // the matrix pipe runs while the LDS port takes the stores, and the global loads feeding those stores get the
+  // whole fragment-read time on top of their two k-steps to arrive.  Each ring register is refilled right after its store.
+  auto step = [&](int stage, uint4 *r, int ks_refill) {
     const char *abase = lds_r + stage * BIG_STAGE;
     const char *bbase = abase + BIG_TM * BIG_PITCH;
+    char *wbase = lds_w + (stage ^ 1) * BIG_STAGE;
     bf16x8 fa[BIG_NB], fb[BIG_NB];
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < BIG_NB; ++i) {
-      fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(abase + i * 16 * BIG_PITCH));
-      fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(bbase + i * 16 * BIG_PITCH));
-    }
+    for (int i = 0; i < BIG_NB; ++i) fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(bbase + i * 16 * BIG_PITCH));
+#pragma unroll
+    for (int i = 0; i < BIG_NB; ++i) fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(abase + i * 16 * BIG_PITCH));
 #pragma unroll
     for (int i = 0; i < BIG_NB; ++i)
 #pragma unroll
       for (int j = 0; j < BIG_NB; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      *reinterpret_cast<uint4 *>(wbase + p * 16 * BIG_PITCH) = r[p];
+      *reinterpret_cast<uint4 *>(wbase + BIG_TM * BIG_PITCH + p * 16 * BIG_PITCH) = r[PASSES + p];
+    }
+    gload(ks_refill, r);
+    // issue order for the block above: 12 LDS reads, then (3 MFMA, 1 LDS write, the refill of that register) x 12
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * BIG_NB, 0);
+#pragma unroll
+    for (int q = 0; q < 2 * PASSES; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, BIG_NB * BIG_NB / (2 * PASSES), 0);
+      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   };
   // sched_barrier(0) pins the issue order: loads complete in order, so the wait before an LDS store only has to
   // cover the oldest slot while the younger ones stay in flight.
@@ -204,78 +223,115 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
   // The body is branch free: with control flow inside, the compiler's wait-count bookkeeping falls back to waiting
   // for every load in flight.  Step ks computes from LDS stage ks & 1 while the data of step ks + 1 moves from its
   // ring slot to the other stage (after the last step that copy is a harmless repeat).
+  // (an empty statement that ties every accumulator to the accumulation registers at this point: without it the
+  // register allocator rotates the accumulators through other registers inside the k loop, ~100 copies per step)
+#pragma unroll
+  for (int i = 0; i < BIG_NB; ++i)
+#pragma unroll
+    for (int j = 0; j < BIG_NB; ++j) asm volatile("" : "+a"(acc[i][j]));
   for (int ks0 = 0; ks0 < n_ksteps; ks0 += BIG_DEPTH) {
 #pragma unroll
     for (int u = 0; u < BIG_DEPTH; ++u) {
       const int ks = ks0 + u;
       const int slot = (u + 1) % BIG_DEPTH;        // ring slot of step ks + 1
-      const int stage = u & 1;                     // BIG_DEPTH is even: the stage parity is static
-      __builtin_amdgcn_sched_barrier(0);
-      lstore(stage ^ 1, ring[slot]);
-      __builtin_amdgcn_sched_barrier(0);
-      gload(ks + 1 + BIG_DEPTH, ring[slot]);
-      __builtin_amdgcn_sched_barrier(0);           // keep the refill ahead of the MFMA block
-      compute(stage);
+      step(u & 1, ring[slot], ks + 1 + BIG_DEPTH);   // BIG_DEPTH is even: the stage parity is static
       lds_barrier();
     }
   }
 
+  // (an empty statement that ties every accumulator to the accumulation registers at this point: without it the
+  // register allocator rotates the accumulators through other registers inside the k loop, ~100 copies per step)
+#pragma unroll
+  for (int i = 0; i < BIG_NB; ++i)
+#pragma unroll
+    for (int j = 0; j < BIG_NB; ++j) asm volatile("" : "+a"(acc[i][j]));
   // ---- merge the four partial tiles: wave w ends up owning the blocks whose linear id is w mod 4.
-  // LDS is free now: [0, 1536) bytes hold 1/|a| and 1/|b| of the tile, then 4 x 9 KB exchange buffers.
+  // LDS is free now: [0, 1536) bytes hold 1/|a| and 1/|b| of the tile, [1536, 2304) the tokens, [2304, 3072) the row
+  // keys, then from 4096 on the 4 x 12 KB exchange buffers.
   double *e_rnorm = reinterpret_cast<double *>(lds);              // [96] rows then [96] cols
   int *e_token = reinterpret_cast<int *>(lds + 2 * BIG_TM * 8);   // [96] row tokens then [96] col tokens
-  float *xbuf = reinterpret_cast<float *>(lds + 4096);            // [4 waves][9 blocks][256 floats]
+  float *xbuf = reinterpret_cast<float *>(lds + 4096);            // [4 waves][12 blocks][256 floats]
+  unsigned long long *row_key = reinterpret_cast<unsigned long long *>(lds + 2 * BIG_TM * 8 + 2 * BIG_TM * 4);   // [96]
   if (tid < 2 * BIG_TM) { e_rnorm[tid] = e_rn; e_token[tid] = e_tok; }
+  if (tid < BIG_TM) row_key[tid] = ~0ull;
+  // Three rounds of 12 blocks: every wave leaves its partials of the round's blocks in LDS, the owner of a block
+  // (wave w owns blocks 12 t + 3 w + 0..2 of round t) adds the four partials in a fixed order.  Register indices
+  // are static everywhere -- only LDS addresses depend on the wave -- so the accumulators stay in place in the k loop.
   f32x4 own[BIG_OWN];
+  __syncthreads();
 #pragma unroll
-  for (int b = 0; b < BIG_NB * BIG_NB; ++b)
-    if ((b & 3) == wave) own[b >> 2] = acc[b / BIG_NB][b % BIG_NB];   // resolved at compile time per wave value below
-  // (the selection above depends on `wave`; spell the four cases out so that every index is static)
+  for (int t = 0; t < 3; ++t) {
 #pragma unroll
-  for (int r = 1; r < 4; ++r) {
-    const int to = (wave + r) & 3;        // owner this wave sends to in round r
-    __syncthreads();
-#pragma unroll
-    for (int b = 0; b < BIG_NB * BIG_NB; ++b) {
-      if ((b & 3) == to) {
-        float *dst = xbuf + ((wave * BIG_OWN + (b >> 2)) * 64 + lane) * 4;
-        *reinterpret_cast<f32x4 *>(dst) = acc[b / BIG_NB][b % BIG_NB];
-      }
+    for (int k = 0; k < 12; ++k) {
+      const int b = 12 * t + k;
+      *reinterpret_cast<f32x4 *>(xbuf + ((wave * 12 + k) * 64 + lane) * 4) = acc[b / BIG_NB][b % BIG_NB];
     }
     __syncthreads();
-    const int from = (wave - r) & 3;      // its buffer now holds partials of the blocks this wave owns
 #pragma unroll
-    for (int o = 0; o < BIG_OWN; ++o)
-      own[o] += *reinterpret_cast<const f32x4 *>(xbuf + ((from * BIG_OWN + o) * 64 + lane) * 4);
+    for (int k = 0; k < 3; ++k) {
+      const float *src = xbuf + ((3 * wave + k) * 64 + lane) * 4;
+      const f32x4 p0 = *reinterpret_cast<const f32x4 *>(src);
+      const f32x4 p1 = *reinterpret_cast<const f32x4 *>(src + 12 * 256);
+      const f32x4 p2 = *reinterpret_cast<const f32x4 *>(src + 2 * 12 * 256);
+      const f32x4 p3 = *reinterpret_cast<const f32x4 *>(src + 3 * 12 * 256);
+      own[3 * t + k] = (p0 + p1) + (p2 + p3);
+    }
+    __syncthreads();
   }
 
-  // ---- epilogue on the owned blocks: block id b = 4*o + wave -> (i, j) = (b / 6, b % 6)
-  // accumulator layout of a 16x16 block: lane holds column (lane % 16) and rows 4*(lane/16) + 0..3
+  // ---- epilogue on the owned blocks.  Round t, wave w: blocks (i, j) = (2 t + w / 2, 3 (w % 2) + k), k = 0..2 --
+  // three neighbours in one block row, so a lane first takes the minimum over its three columns, and only 12 keys
+  // per lane go through the 16-lane reduction.  The reductions run side by side (all shuffles of a step are issued
+  // before the first is used): with one wave per SIMD a chain of dependent shuffles would expose every latency.
+  // Accumulator layout of a 16x16 block: lane holds column (lane % 16) and rows 4*(lane/16) + 0..3.
+  unsigned long long kmin[12];
 #pragma unroll
-  for (int o = 0; o < BIG_OWN; ++o) {
-    const int b = 4 * o + wave;
-    const int bi = b / BIG_NB, bj = b - bi * BIG_NB;
-    const int cl = bj * 16 + l16;
-    const double rb = e_rnorm[BIG_TM + cl];
-    const int tb = e_token[BIG_TM + cl];
+  for (int t = 0; t < 3; ++t) {
+    const int bi = 2 * t + (wave >> 1);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int rl = bi * 16 + kg * 4 + q;
-      const double ra = e_rnorm[rl];
-      const int ta = e_token[rl];
-      const double cosv = (double)own[o][q] * ra * rb;
-      const float fd = (float)fmax(1.0 - cosv, 0.0);
-      // key = (FD bits, B token): tokens of a window ascend with their local position, so the smaller token is the
-      // earlier column; NaN never competes
-      unsigned long long key = ((unsigned long long)__float_as_uint(fd) << 32) | (unsigned)tb;
-      key = (ta >= 0 && tb >= 0 && fd == fd) ? key : ~0ull;
+    for (int q = 0; q < 4; ++q) kmin[4 * t + q] = ~0ull;
 #pragma unroll
-      for (int m = 8; m >= 1; m >>= 1) {   // the 16 lanes with the same lane/16 hold the same row
-        const unsigned long long ok = __shfl_xor(key, m, 64);
-        key = ok < key ? ok : key;
+    for (int k = 0; k < 3; ++k) {
+      const int cl = (3 * (wave & 1) + k) * 16 + l16;
+      const double rb = e_rnorm[BIG_TM + cl];
+      const int tb = e_token[BIG_TM + cl];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int rl = bi * 16 + kg * 4 + q;
+        const double ra = e_rnorm[rl];
+        const int ta = e_token[rl];
+        const double cosv = (double)own[3 * t + k][q] * ra * rb;
+        const float fd = (float)fmax(1.0 - cosv, 0.0);
+        // key = (FD bits, B token): tokens of a window ascend with their local position, so the smaller token is the
+        // earlier column; NaN never competes
+        unsigned long long key = ((unsigned long long)__float_as_uint(fd) << 32) | (unsigned)tb;
+        key = (ta >= 0 && tb >= 0 && fd == fd) ? key : ~0ull;
+        kmin[4 * t + q] = key < kmin[4 * t + q] ? key : kmin[4 * t + q];
       }
-      if (l16 == 0 && key != ~0ull) atomicMin(&g.best_key[ta], key);
     }
+  }
+#pragma unroll
+  for (int m = 8; m >= 1; m >>= 1) {   // the 16 lanes with the same lane/16 hold the same rows
+    unsigned long long other[12];
+#pragma unroll
+    for (int e = 0; e < 12; ++e) other[e] = __shfl_xor(kmin[e], m, 64);
+#pragma unroll
+    for (int e = 0; e < 12; ++e) kmin[e] = other[e] < kmin[e] ? other[e] : kmin[e];
+  }
+  if (l16 == 0) {   // LDS: minimum over the tile's 6 column blocks (two waves contribute to every row)
+#pragma unroll
+    for (int e = 0; e < 12; ++e) {
+      const int rl = (2 * (e >> 2) + (wave >> 1)) * 16 + kg * 4 + (e & 3);
+      if (kmin[e] != ~0ull) atomicMin(&row_key[rl], kmin[e]);
+    }
+  }
+  __syncthreads();
+  // one global atomic per row and tile; integer min is order independent, so the result does not depend on which
+  // tile arrives first
+  if (tid < BIG_TM) {
+    const unsigned long long key = row_key[tid];
+    const int ta = e_token[tid];
+    if (ta >= 0 && key != ~0ull) atomicMin(&g.best_key[ta], key);
   }
 }
 
