@@ -6,7 +6,8 @@
 // sort of (destination, source) pairs yields each source's rank inside its group, which makes the
 // inverse map (grp_offsets / grp_src) deterministic without atomics on the output.
 //
-//   select_window_kernel : per window -> dst[], per-token source counts, per-source ranks
+//   select_window_kernel : per window -> dst[], per-token source counts, per-source ranks (up to 256 A nodes)
+//   select_rank_kernel   : the same results for larger windows, by counting smaller keys
 //   select_scan_kernel   : one workgroup -> exclusive scans (new_index, grp_offsets), cu_vis_out, grp_src
 #include "lk_common.h"
 #include "lk_launch.h"
@@ -106,6 +107,128 @@ __global__ __launch_bounds__(THREADS) void select_window_kernel(SelArgs g) {
     g.src_rank[a_tok] = k - start[k];
     const bool last = (k == r - 1) || ((keys[k + 1] >> 32) != (pk >> 32));
     if (last) g.cnt[b_tok] = k - start[k] + 1;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Large windows (more than 256 A nodes): selection by counting instead of sorting.  The rank of an A node among the
+// keys of its window is the number of smaller keys -- |A|^2 comparisons, but they spread over many workgroups and
+// need no barrier ladder, where a 2048-key bitonic sort in one workgroup is 66 dependent passes.
+//   MODE 0: rank of every A node -> dst (and the default dst of the B nodes)
+//   MODE 1: from dst: rank of every merged A node among the earlier sources of its target, sources per B node
+// One workgroup = 32 A positions (and the 32 B positions beside them) of one window; 8 threads share a position and
+// split the window's key list between them.
+constexpr int RANK_ROWS = 32;
+constexpr int RANK_SEGS = 8;
+constexpr int RANK_MAX_A = 2048;   // |A| of the largest window the library accepts (4096 tokens)
+
+template <int MODE>
+__global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelArgs g, int blocks_per_window) {
+  // MODE 0: order-preserving FD bits; MODE 1: dst of every A node.  Padded with all-ones up to whole 4-entry groups
+  // per segment: an all-ones entry is never smaller than a key and never a valid target.
+  __shared__ __attribute__((aligned(16))) uint32_t vals[RANK_MAX_A + 4 * RANK_SEGS];
+  __shared__ int part[2][RANK_SEGS][RANK_ROWS];
+  const int w = blockIdx.x / blocks_per_window, rb = blockIdx.x - w * blocks_per_window;
+  const int off = g.win_offsets[w];
+  const int v = g.win_offsets[w + 1] - off;
+  int nA = (v + 1) >> 1;
+  const int nB = v >> 1;
+  if (nA > g.cap) nA = g.cap;
+  if (rb * RANK_ROWS >= nA) return;
+  if (MODE == 0 && rb == 0) {   // tokens of a window beyond the caller's bound stay
+    for (int t = 2 * nA + (int)threadIdx.x; t < v; t += RANK_ROWS * RANK_SEGS) {
+      const int tok = g.win_tokens[off + t];
+      if ((unsigned)tok < (unsigned)g.sum_n) { g.dst[tok] = -1; g.cnt[tok] = 0; g.src_rank[tok] = 0; }
+    }
+  }
+  int r = g.win_remove[w];
+  r = r < 0 ? 0 : (r > nA ? nA : r);
+  if (nB == 0) r = 0;
+  const int tid = threadIdx.x;
+
+  // the window's list: one value per A node
+  const int seg_len = ((nA + RANK_SEGS - 1) / RANK_SEGS + 3) & ~3;   // entries per segment, a multiple of 4
+  for (int la0 = 0; la0 < seg_len * RANK_SEGS; la0 += RANK_ROWS * RANK_SEGS) {
+    const int la = la0 + tid;
+    const int tok = g.win_tokens[off + 2 * (la < nA ? la : nA - 1)];
+    const bool ok = (unsigned)tok < (unsigned)g.sum_n;
+    uint32_t val;
+    if (MODE == 0) {
+      float fd = g.best_fd[ok ? tok : 0];
+      if (!ok || !(fd >= 0.f)) fd = __uint_as_float(0x7f800000u);   // NaN or negative never wins
+      val = f32_order_key(fd);
+    } else {
+      const int d = g.dst[ok ? tok : 0];
+      val = ok ? (uint32_t)d : 0xffffffffu;
+    }
+    if (la < seg_len * RANK_SEGS) vals[la] = la < nA ? val : 0xffffffffu;
+  }
+  // this thread's position and the tokens there
+  const int row = tid & (RANK_ROWS - 1), seg = tid / RANK_ROWS;
+  const int la = rb * RANK_ROWS + row;
+  const bool has_a = la < nA, has_b = la < nB;
+  int a_tok = g.win_tokens[off + 2 * (has_a ? la : 0)];
+  int b_tok = g.win_tokens[off + (has_b ? 2 * la + 1 : 0)];
+  if (!has_a || (unsigned)a_tok >= (unsigned)g.sum_n) a_tok = -1;
+  if (!has_b || (unsigned)b_tok >= (unsigned)g.sum_n) b_tok = -1;
+  int prop = -1;
+  if (MODE == 0 && seg == 0) {   // the proposal of this A node, or the first B node of the window
+    prop = g.best_dst[a_tok >= 0 ? a_tok : 0];
+    const int first_b = g.win_tokens[off + (nB > 0 ? 1 : 0)];
+    if (a_tok < 0) prop = -1;
+    else if ((unsigned)prop >= (unsigned)g.sum_n) prop = (nB > 0 && (unsigned)first_b < (unsigned)g.sum_n) ? first_b : -1;
+  }
+  __syncthreads();
+
+  const int o_begin = seg * seg_len;
+  int c0 = 0, c1 = 0;
+  if (MODE == 0) {
+    const uint32_t mine = vals[has_a ? la : 0];
+#pragma unroll 4
+    for (int o = o_begin; o < o_begin + seg_len; o += 4) {
+      const uint4 k = *reinterpret_cast<const uint4 *>(&vals[o]);
+      c0 += (k.x < mine || (k.x == mine && o < la)) ? 1 : 0;
+      c0 += (k.y < mine || (k.y == mine && o + 1 < la)) ? 1 : 0;
+      c0 += (k.z < mine || (k.z == mine && o + 2 < la)) ? 1 : 0;
+      c0 += (k.w < mine || (k.w == mine && o + 3 < la)) ? 1 : 0;
+    }
+  } else {
+    const uint32_t mine = has_a ? vals[la] : 0xffffffffu;    // target of this A node (all-ones: stays)
+    const uint32_t self = (uint32_t)b_tok;                   // this B node as a target
+#pragma unroll 4
+    for (int o = o_begin; o < o_begin + seg_len; o += 4) {
+      const uint4 d = *reinterpret_cast<const uint4 *>(&vals[o]);
+      c0 += (d.x == mine && o < la) ? 1 : 0;
+      c0 += (d.y == mine && o + 1 < la) ? 1 : 0;
+      c0 += (d.z == mine && o + 2 < la) ? 1 : 0;
+      c0 += (d.w == mine && o + 3 < la) ? 1 : 0;
+      c1 += (d.x == self) ? 1 : 0;
+      c1 += (d.y == self) ? 1 : 0;
+      c1 += (d.z == self) ? 1 : 0;
+      c1 += (d.w == self) ? 1 : 0;
+    }
+  }
+  part[0][seg][row] = c0;
+  part[1][seg][row] = c1;
+  __syncthreads();
+  if (seg == 0) {
+    int s0 = 0, s1 = 0;
+#pragma unroll
+    for (int q = 0; q < RANK_SEGS; ++q) { s0 += part[0][q][row]; s1 += part[1][q][row]; }
+    if (MODE == 0) {
+      if (a_tok >= 0) g.dst[a_tok] = (s0 < r) ? prop : -1;
+      if (b_tok >= 0) g.dst[b_tok] = -1;
+    } else {
+      if (a_tok >= 0) {
+        const bool merged = vals[la] != 0xffffffffu;
+        g.src_rank[a_tok] = merged ? s0 : 0;
+        g.cnt[a_tok] = 0;
+      }
+      if (b_tok >= 0) {
+        g.src_rank[b_tok] = 0;
+        g.cnt[b_tok] = s1;
+      }
+    }
   }
 }
 
@@ -234,9 +357,21 @@ hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int su
   g.cap = next_pow2(maxA > 1 ? maxA : 1);
   const size_t lds = (size_t)g.cap * (sizeof(uint64_t) + sizeof(int));
   if (n_windows > 0) {
-    if (g.cap <= 256) hipLaunchKernelGGL(select_window_kernel<256>, dim3(n_windows), dim3(256), lds, stream, g);
-    else hipLaunchKernelGGL(select_window_kernel<1024>, dim3(n_windows), dim3(1024), lds, stream, g);
-    hipError_t e = hipGetLastError();
+    hipError_t e;
+    if (g.cap <= 256) {
+      hipLaunchKernelGGL(select_window_kernel<256>, dim3(n_windows), dim3(256), lds, stream, g);
+      e = hipGetLastError();
+    } else {
+      // counting selection; a window beyond the library's limit keeps its surplus A nodes, as everywhere else
+      g.cap = maxA < RANK_MAX_A ? maxA : RANK_MAX_A;
+      const int bpw = (g.cap + RANK_ROWS - 1) / RANK_ROWS;
+      const dim3 grid((unsigned)(n_windows * bpw)), block(RANK_ROWS * RANK_SEGS);
+      hipLaunchKernelGGL(select_rank_kernel<0>, grid, block, 0, stream, g, bpw);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(select_rank_kernel<1>, grid, block, 0, stream, g, bpw);
+      e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(select_scan_kernel, dim3(1), dim3(SCAN_THREADS), 0, stream, g);

@@ -38,6 +38,10 @@ def test_measured_configs_match_oracle(cfg):
          head_dim=64, n_c=9, structure="grid", windows_per_axis=(3,), n_final=100),
     dict(name="headdim128_f32_bigwindow", dtype="f32", batch=1, grid_h=20, grid_w=20, text_lens=(40,), d=256,
          heads=2, head_dim=128, n_c=30, structure="grid", windows_per_axis=(1,), n_final=230),
+    dict(name="big_windows_bf16", dtype="bf16", batch=2, grid_h=30, grid_w=40, text_lens=(9, 21), d=256, heads=2,
+         head_dim=128, n_c=40, structure="grid", windows_per_axis=(1, 1), n_final=700),
+    dict(name="big_windows_f32", dtype="f32", batch=1, grid_h=26, grid_w=27, text_lens=(17,), d=64, heads=2,
+         head_dim=32, n_c=25, structure="grid", windows_per_axis=(1, 0), n_final=400),
     dict(name="no_removal", dtype="bf16", batch=1, grid_h=8, grid_w=8, text_lens=(8,), d=128, heads=1,
          head_dim=128, n_c=4, structure="iid", windows_per_axis=(2,), n_final=64),
     dict(name="all_of_A_leaves", dtype="bf16", batch=2, grid_h=8, grid_w=8, text_lens=(8, 9), d=128, heads=1,
