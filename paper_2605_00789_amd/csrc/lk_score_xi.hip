@@ -204,36 +204,51 @@ __global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
     __syncthreads();   // the previous chunk has been consumed
     stage_prompt_rows<T, DH>(g, q_lds, t0, nT, j0, txt_ho);
     if (!VISION_LSE) {
-      for (int idx = threadIdx.x; idx < S::ROWS; idx += XI_THREADS) {
-        const int j = j0 + idx;
-        float m = 3.0e38f, inv = 0.f;   // rows past nT: exp2(x - huge) = 0, times 0
-        if (j < nT) {
-          if (g.lse) {
-            m = g.lse[(int64_t)h * g.sum_t + t0 + j] * LOG2E;
-            inv = 1.f;
-          } else {
-            const float2 *p = reinterpret_cast<const float2 *>(g.stats) + ((int64_t)h * g.sum_t + t0 + j) * g.max_vis_blocks;
-            m = NEG_INF;
-            float sum = 0.f;
-            int s = 0;
-            for (; s + 4 <= nblk; s += 4) {   // four partials in flight; merged in index order
-              const float2 a0 = p[s], a1 = p[s + 1], a2 = p[s + 2], a3 = p[s + 3];
-              const float mn = fmaxf(fmaxf(m, fmaxf(a0.x, a1.x)), fmaxf(a2.x, a3.x));
-              sum = sum * exp2f(m - mn) + a0.y * exp2f(a0.x - mn) + a1.y * exp2f(a1.x - mn) + a2.y * exp2f(a2.x - mn) +
-                    a3.y * exp2f(a3.x - mn);
-              m = mn;
-            }
-            for (; s < nblk; ++s) {
-              const float2 a = p[s];
-              const float mn = fmaxf(m, a.x);
-              sum = sum * exp2f(m - mn) + a.y * exp2f(a.x - mn);
-              m = mn;
-            }
-            inv = 1.f / sum;
+      // (max, 1/sum) of every prompt row of the chunk.  Four threads share a row: each merges every fourth
+      // per-block pair of pass 1 (its loads in flight together), then the four partial results are merged by
+      // shuffles -- a fixed order, and a dependent chain of nblk / 4 + 2 instead of nblk.
+      static_assert(S::ROWS * 4 == XI_THREADS, "four threads per prompt row of a chunk");
+      const int idx = threadIdx.x >> 2, part = threadIdx.x & 3;
+      const int j = j0 + idx;
+      float m = 3.0e38f, inv = 0.f;   // rows past nT: exp2(x - huge) = 0, times 0
+      if (g.lse) {
+        if (j < nT) { m = g.lse[(int64_t)h * g.sum_t + t0 + j] * LOG2E; inv = 1.f; }
+      } else {
+        const float2 *p = reinterpret_cast<const float2 *>(g.stats) +
+                          ((int64_t)h * g.sum_t + t0 + (j < nT ? j : nT - 1)) * g.max_vis_blocks;
+        float pm = NEG_INF, psum = 0.f;
+        for (int s0 = 0; s0 < nblk; s0 += 32) {   // eight pairs per thread in flight; merged in index order
+          float2 a[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int sb = s0 + 4 * u + part;
+            a[u] = p[sb < nblk ? sb : nblk - 1];
+            if (sb >= nblk) a[u] = make_float2(NEG_INF, 0.f);
+          }
+          float mn = pm;
+#pragma unroll
+          for (int u = 0; u < 8; ++u) mn = fmaxf(mn, a[u].x);
+          if (mn > NEG_INF) {
+            float acc = psum * exp2f(pm - mn);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += a[u].y * exp2f(a[u].x - mn);   // a pair of (-inf, 0) adds 0
+            psum = acc;
+            pm = mn;
           }
         }
-        rowstat[idx] = make_float2(m, inv);   // rows past nT get weight 0
+#pragma unroll
+        for (int o = 1; o <= 2; o <<= 1) {   // the four threads of a row are neighbouring lanes
+          const float om = __shfl_xor(pm, o, 64), os = __shfl_xor(psum, o, 64);
+          const float mn = fmaxf(pm, om);
+          // lower lane's pair first, so that both lanes of a pair compute the same bits
+          const float lo_m = (threadIdx.x & o) ? om : pm, lo_s = (threadIdx.x & o) ? os : psum;
+          const float hi_m = (threadIdx.x & o) ? pm : om, hi_s = (threadIdx.x & o) ? psum : os;
+          psum = (mn > NEG_INF) ? lo_s * exp2f(lo_m - mn) + hi_s * exp2f(hi_m - mn) : 0.f;
+          pm = mn;
+        }
+        if (j < nT) { m = pm; inv = 1.f / psum; }
       }
+      if (part == 0) rowstat[idx] = make_float2(m, inv);   // rows past nT get weight 0
     }
     __syncthreads();
     const int n_tt = min(S::TILES, (nT - j0 + 31) >> 5);
