@@ -205,15 +205,29 @@ def xi_vision_query(Qv: np.ndarray, Kt: np.ndarray, lse: np.ndarray, cu_vis, cu_
 # ---------------------------------------------------------------------------
 # Steps 1-2: FD, best edge per A node, the r merged nodes per window
 # ---------------------------------------------------------------------------
-def feature_divergence(XA: np.ndarray, XB: np.ndarray) -> np.ndarray:
-    """Eq. (similarity) for all pairs: 1 - <a,b>/(max(|a|,eps) max(|b|,eps)), clamped at 0."""
-    na = np.maximum(np.sqrt((XA * XA).sum(axis=1)), NORM_EPS)
-    nb = np.maximum(np.sqrt((XB * XB).sum(axis=1)), NORM_EPS)
-    cos = (XA @ XB.T) / (na[:, None] * nb[None, :])
-    return np.maximum(1.0 - cos, 0.0)
+METRICS = ("cosine", "euclidean", "l2sq")
 
 
-def best_edges(X: np.ndarray, win_offsets: np.ndarray, win_tokens: np.ndarray):
+def feature_divergence(XA: np.ndarray, XB: np.ndarray, metric: str = "cosine") -> np.ndarray:
+    """Pairwise divergence of the rows of XA and XB.
+    "cosine" (the method's choice): Eq. (similarity), 1 - <a,b>/(max(|a|,eps) max(|b|,eps)), clamped at 0.
+    "euclidean" / "l2sq" (the similarity-metric ablation of the appendix): |a - b| and |a - b|^2,
+    written out as the sum of squared coordinate differences."""
+    if metric == "cosine":
+        na = np.maximum(np.sqrt((XA * XA).sum(axis=1)), NORM_EPS)
+        nb = np.maximum(np.sqrt((XB * XB).sum(axis=1)), NORM_EPS)
+        cos = (XA @ XB.T) / (na[:, None] * nb[None, :])
+        return np.maximum(1.0 - cos, 0.0)
+    if metric not in METRICS:
+        raise ValueError("unknown metric %r" % (metric,))
+    d2 = np.empty((XA.shape[0], XB.shape[0]))
+    for i in range(XA.shape[0]):
+        diff = XB - XA[i][None, :]
+        d2[i] = (diff * diff).sum(axis=1)
+    return np.sqrt(d2) if metric == "euclidean" else d2
+
+
+def best_edges(X: np.ndarray, win_offsets: np.ndarray, win_tokens: np.ndarray, metric: str = "cosine"):
     """For every A node its lowest-FD B node of the same window.
     Returns best_fd[float64, N] (+inf on B rows and on A rows of windows without a
     B node) and best_dst[int32, N] (token index, -1 where there is none).
@@ -226,7 +240,7 @@ def best_edges(X: np.ndarray, win_offsets: np.ndarray, win_tokens: np.ndarray):
         A, B = split_window(toks)
         if len(B) == 0:
             continue
-        fd = feature_divergence(X[A], X[B])
+        fd = feature_divergence(X[A], X[B], metric)
         j = np.argmin(fd, axis=1)                # first minimum = lowest local B position
         best_fd[A] = fd[np.arange(len(A)), j]
         best_dst[A] = B[j]
@@ -336,11 +350,11 @@ class StageResult:
 
 
 def compress_stage(X, K, V, Q, pos, cu_vis, cu_txt, heads, head_dim, win_offsets, win_tokens,
-                   win_remove, scale=None, lse=None, xi=None) -> StageResult:
+                   win_remove, scale=None, lse=None, xi=None, metric: str = "cosine") -> StageResult:
     """One whole compression step on float64 inputs (already widened from storage)."""
     if xi is None:
         xi = xi_text_query(Q, K, cu_vis, cu_txt, heads, head_dim, scale=scale, lse=lse)
-    best_fd, best_dst = best_edges(X, win_offsets, win_tokens)
+    best_fd, best_dst = best_edges(X, win_offsets, win_tokens, metric)
     dst = select(best_fd, best_dst, win_offsets, win_tokens, win_remove)
     new_index = kept_index(dst)
     go, gs = groups_csr(dst)
@@ -361,7 +375,7 @@ def stage_removals(batch: int, n_in: int, n_out: int, windows_per_seq: int) -> n
     return np.tile(one, batch)
 
 
-def compress_schedule(wl, stages: Optional[int] = None) -> List[StageResult]:
+def compress_schedule(wl, stages: Optional[int] = None, metric: str = "cosine") -> List[StageResult]:
     """Runs the hierarchical schedule (Sec. 3.2.2) of a workload: after every stage the
     outputs are rounded to the storage dtype, as a KV cache would hold them."""
     X, K, V = wl.X, wl.K, wl.V
@@ -375,7 +389,7 @@ def compress_schedule(wl, stages: Optional[int] = None) -> List[StageResult]:
         per_seq = (len(wo) - 1) // wl.batch
         rem = stage_removals(wl.batch, n_in, wl.targets[s], per_seq)
         res = compress_stage(widen(X, wl.dtype), widen(K, wl.dtype), widen(V, wl.dtype), Q, pos, cu_vis,
-                             wl.cu_txt, wl.heads, wl.head_dim, wo, wt, rem)
+                             wl.cu_txt, wl.heads, wl.head_dim, wo, wt, rem, metric=metric)
         out.append(res)
         X, K, V = (round_to_storage(t, wl.dtype) for t in (res.X, res.K, res.V))
         pos, cu_vis, n_in = res.pos, res.cu_vis, wl.targets[s]

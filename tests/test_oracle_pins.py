@@ -135,6 +135,45 @@ def test_fd_against_library_and_scaling():
     np.testing.assert_allclose(O.feature_divergence(XB, XA), ref.T, atol=1e-13)
 
 
+def test_distance_metrics_closed_forms_library_and_selection():
+    """Euclidean and squared-L2 divergences of the similarity-metric ablation (appendix, "Influence of similarity
+    metrics"): textbook values, scipy's cdist, and what the two share with / differ from the cosine score."""
+    A = np.array([[0.0, 0.0], [1.0, 1.0], [3.0, 4.0]])
+    Bm = np.array([[3.0, 4.0], [0.0, 0.0], [6.0, 8.0], [4.0, 5.0]])
+    eu = O.feature_divergence(A, Bm, "euclidean")
+    np.testing.assert_allclose(eu[0], [5.0, 0.0, 10.0, math.sqrt(41.0)], atol=1e-14)   # 3-4-5 triangle and its double
+    np.testing.assert_allclose(eu[2], [0.0, 5.0, 5.0, math.sqrt(2.0)], atol=1e-14)
+    np.testing.assert_allclose(O.feature_divergence(A, Bm, "l2sq")[1], [13.0, 2.0, 74.0, 25.0], atol=1e-13)
+    rng = np.random.default_rng(3)
+    XA, XB = rng.standard_normal((9, 21)), rng.standard_normal((6, 21))
+    from scipy.spatial.distance import cdist
+    np.testing.assert_allclose(O.feature_divergence(XA, XB, "euclidean"), cdist(XA, XB, "euclidean"), atol=1e-13)
+    np.testing.assert_allclose(O.feature_divergence(XA, XB, "l2sq"), cdist(XA, XB, "sqeuclidean"), atol=1e-12)
+    np.testing.assert_allclose(O.feature_divergence(XB, XA, "l2sq"), cdist(XA, XB, "sqeuclidean").T, atol=1e-12)
+    # translation invariant, not scale invariant (the opposite of the cosine score)
+    shift = rng.standard_normal((1, 21))
+    np.testing.assert_allclose(O.feature_divergence(XA + shift, XB + shift, "euclidean"), cdist(XA, XB), atol=1e-12)
+    np.testing.assert_allclose(O.feature_divergence(2 * XA, 2 * XB, "l2sq"), 4 * cdist(XA, XB, "sqeuclidean"), atol=1e-11)
+    assert O.feature_divergence(XA[:1], 2 * XA[:1], "cosine")[0, 0] < 1e-15 < O.feature_divergence(XA[:1], 2 * XA[:1], "l2sq")[0, 0]
+    # the square root is monotone: both distances select the same edges and the same merged set
+    X = rng.standard_normal((40, 16))
+    wo, wt = np.array([0, 17, 40], dtype=np.int32), np.arange(40, dtype=np.int32)
+    rem = np.array([4, 7], dtype=np.int32)
+    fe, de = O.best_edges(X, wo, wt, "euclidean")
+    fs, ds = O.best_edges(X, wo, wt, "l2sq")
+    np.testing.assert_array_equal(de, ds)
+    np.testing.assert_allclose(fe[np.isfinite(fe)] ** 2, fs[np.isfinite(fs)], rtol=1e-13)
+    np.testing.assert_array_equal(O.select(fe, de, wo, wt, rem), O.select(fs, ds, wo, wt, rem))
+    # ... and on unit-norm rows they order pairs exactly as the cosine score does (|a-b|^2 = 2 - 2 cos)
+    U = X / np.linalg.norm(X, axis=1, keepdims=True)
+    fc, dc = O.best_edges(U, wo, wt, "cosine")
+    fu, du = O.best_edges(U, wo, wt, "l2sq")
+    np.testing.assert_array_equal(dc, du)
+    np.testing.assert_allclose(fu[np.isfinite(fu)], 2.0 * fc[np.isfinite(fc)], atol=1e-13)
+    with pytest.raises(ValueError):
+        O.feature_divergence(XA, XB, "manhattan")
+
+
 # ---------------------------------------------------------------- selection
 def _explicit_fd(X, a, b):
     xa, xb = X[a], X[b]
