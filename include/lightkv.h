@@ -66,6 +66,15 @@ typedef enum {
   LIGHTKV_XI_GIVEN = 2
 } lightkv_xi_mode;
 
+/* Divergence between two hidden states used for the token pairing (Step 1).  The method uses the cosine form;
+   the two distances are those of the paper's similarity-metric ablation (appendix).  best_fd then holds
+   |a - b| or |a - b|^2; the rest of the step is unchanged. */
+typedef enum {
+  LIGHTKV_METRIC_COSINE = 0,     /* FD = 1 - cos(a, b)  (Eq. "similarity") */
+  LIGHTKV_METRIC_EUCLIDEAN = 1,  /* |a - b|   */
+  LIGHTKV_METRIC_L2SQ = 2        /* |a - b|^2 */
+} lightkv_metric;
+
 /* Limits of this build. */
 #define LIGHTKV_MAX_WINDOW_TOKENS 4096   /* tokens in one window                    */
 #define LIGHTKV_MAX_SEQ_TOKENS    16384  /* vision tokens in one sequence           */
@@ -87,6 +96,8 @@ typedef struct lightkv_problem {
   int32_t n_windows;
   int32_t max_window_tokens;  /* host-side upper bound on the size of any window; sizes launches.
                                  0 = take it from h_win_offsets (then required).                 */
+  int32_t metric;             /* lightkv_metric; 0 (a zeroed struct) = cosine FD; other values ->
+                                 LIGHTKV_ERR_UNSUPPORTED                                          */
   const int32_t *h_cu_vis;    /* HOST [batch+1] vision-token offsets, h_cu_vis[0] = 0            */
   const int32_t *h_cu_txt;    /* HOST [batch+1] prompt-token offsets (may be NULL for XI_GIVEN)  */
   const int32_t *cu_vis;      /* device copy of h_cu_vis                                         */

@@ -28,7 +28,7 @@ class LightKVError(RuntimeError):
 class _CProblem(C.Structure):
     _fields_ = [
         ("batch", C.c_int32), ("d", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32),
-        ("dtype", C.c_int32), ("n_windows", C.c_int32), ("max_window_tokens", C.c_int32),
+        ("dtype", C.c_int32), ("n_windows", C.c_int32), ("max_window_tokens", C.c_int32), ("metric", C.c_int32),
         ("h_cu_vis", C.c_void_p), ("h_cu_txt", C.c_void_p), ("cu_vis", C.c_void_p), ("cu_txt", C.c_void_p),
         ("win_offsets", C.c_void_p), ("win_tokens", C.c_void_p), ("win_remove", C.c_void_p),
         ("h_win_offsets", C.c_void_p), ("h_win_remove", C.c_void_p),
@@ -109,12 +109,15 @@ def _ld(t: Optional[torch.Tensor]) -> int:
     return 0 if t is None else int(t.stride(0))
 
 
+METRICS = {"cosine": 0, "euclidean": 1, "l2sq": 2}
+
+
 class Problem:
     """Python mirror of `lightkv_problem`; keeps the host arrays and device tensors it points to alive."""
 
     def __init__(self, *, batch, d, heads, head_dim, dtype, h_cu_vis, cu_vis, h_cu_txt=None, cu_txt=None,
                  n_windows=0, max_window_tokens=0, win_offsets=None, win_tokens=None, win_remove=None,
-                 h_win_offsets=None, h_win_remove=None):
+                 h_win_offsets=None, h_win_remove=None, metric="cosine"):
         self.refs = dict(h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=h_cu_txt, cu_txt=cu_txt,
                          win_offsets=win_offsets, win_tokens=win_tokens, win_remove=win_remove,
                          h_win_offsets=h_win_offsets, h_win_remove=h_win_remove)
@@ -122,6 +125,7 @@ class Problem:
         self.c.batch, self.c.d, self.c.heads, self.c.head_dim = batch, d, heads, head_dim
         self.c.dtype = {"f32": F32, "bf16": BF16, F32: F32, BF16: BF16}[dtype]
         self.c.n_windows, self.c.max_window_tokens = n_windows, max_window_tokens
+        self.c.metric = METRICS[metric] if isinstance(metric, str) else int(metric)
         for name in ("h_cu_vis", "h_cu_txt", "h_win_offsets", "h_win_remove"):
             setattr(self.c, name, _hptr(self.refs[name]))
         for name in ("cu_vis", "cu_txt", "win_offsets", "win_tokens", "win_remove"):

@@ -22,6 +22,7 @@ lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool n
   if (!p || !p->h_cu_vis || !p->cu_vis) return LIGHTKV_ERR_NULL;
   if (p->batch < 1 || p->d < 1 || p->heads < 1 || p->head_dim < 1 || p->n_windows < 0) return LIGHTKV_ERR_SHAPE;
   if (p->dtype != LIGHTKV_F32 && p->dtype != LIGHTKV_BF16) return LIGHTKV_ERR_UNSUPPORTED;
+  if (p->metric < LIGHTKV_METRIC_COSINE || p->metric > LIGHTKV_METRIC_L2SQ) return LIGHTKV_ERR_UNSUPPORTED;
   c.elem_bytes = p->dtype == LIGHTKV_BF16 ? 2 : 4;
   if (p->d % (16 / c.elem_bytes) != 0) return LIGHTKV_ERR_UNSUPPORTED;
   if ((int64_t)p->heads * p->head_dim != p->d) return LIGHTKV_ERR_SHAPE;
@@ -110,7 +111,7 @@ Fork *fork_for_current_device(hipStream_t main) {
 }
 
 struct WsLayout {
-  size_t fd_partial = 0, fd_norm = 0, fd_keys = 0, fd_counters = 0, xi_stats = 0, xi_part = 0, sel_cnt = 0,
+  size_t fd_partial = 0, fd_norm = 0, fd_keys = 0, xi_stats = 0, xi_part = 0, sel_cnt = 0,
          sel_rank = 0, total = 0;
 };
 
@@ -125,7 +126,6 @@ WsLayout ws_layout(const FdPlan &fd, const FdBigPlan &big, bool use_big, const X
   l.fd_partial = off; off = align_up(off + (use_big ? 0 : fd.partial_floats * sizeof(float)));
   l.fd_norm = off;    off = align_up(off + (use_big ? big.norm_floats * sizeof(float) : 0));
   l.fd_keys = off;    off = align_up(off + (use_big ? big.key_bytes : 0));
-  l.fd_counters = off; off = align_up(off + (use_big ? (size_t)big.n_counters * sizeof(int) : 0));
   l.xi_stats = off;   off = align_up(off + xi.stat_floats * sizeof(float));
   l.xi_part = off;    off = align_up(off + xi.part_floats * sizeof(float));
   l.sel_cnt = off;    off = align_up(off + (size_t)sum_n * sizeof(int32_t));
@@ -238,9 +238,10 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx,
       }
     c.max_window = max_window;
   }
-  const FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
+  FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
   const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, p->h_cu_txt && p->cu_txt ? p->h_cu_txt : nullptr, p->heads, 0);
-  const FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
+  FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
+  fd.metric = big.metric = p->metric;
   const bool use_big = use_big_fd(p, c);
   const WsLayout l = ws_layout(fd, big, use_big, xp, c.sum_n);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) != 0 || ws_bytes < l.total) return LIGHTKV_ERR_WORKSPACE;
@@ -281,8 +282,7 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx,
   } else if (use_big) {
     if (launch_fd_big(big, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
                       reinterpret_cast<double *>(wsb + l.fd_norm),
-                      reinterpret_cast<unsigned long long *>(wsb + l.fd_keys),
-                      reinterpret_cast<int *>(wsb + l.fd_counters), best_fd, best_dst, s) != hipSuccess)
+                      reinterpret_cast<unsigned long long *>(wsb + l.fd_keys), best_fd, best_dst, s) != hipSuccess)
       fd_status = LIGHTKV_ERR_LAUNCH;
   } else if (launch_fd(fd, p->dtype, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
                        reinterpret_cast<float *>(wsb + l.fd_partial), best_fd, best_dst, s) != hipSuccess) {

@@ -19,6 +19,7 @@ struct FdPlan {
   int n_rowblocks;  // epilogue jobs (one per 32 A rows)
   int ksplit;
   size_t partial_floats;   // n_tiles * ksplit * FD_TILE_FLOATS
+  int metric;              // 0 cosine FD, 1 Euclidean, 2 squared L2 (set by the caller after planning)
 };
 constexpr int FD_TOK_OFFSET = 32 * 32 + 32 + 32;    // dots, |a|^2 partials, |b|^2 partials ...
 constexpr int FD_TILE_FLOATS = FD_TOK_OFFSET + 64;  // ... then (slice 0 only) the tokens of the 32 rows and 32 columns
@@ -46,15 +47,14 @@ hipError_t launch_fd_select_small(const FdPlan &plan, int dtype, const void *X, 
 struct FdBigPlan {
   int wb;            // wave tile = (16*wb)^2, workgroup tile = (32*wb)^2
   int mt, nt;        // workgroup tiles per window along A and B
-  int n_counters;    // arrival counters: one per (window, row block)
   size_t norm_floats, key_bytes;
+  int metric;        // as in FdPlan
 };
 constexpr int FD_BIG_MIN_WINDOW = 256;   // windows bounded by fewer tokens use the small-tile path
 FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n);
 hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
                          const int32_t *win_offsets, const int32_t *win_tokens, double *rnorm,
-                         unsigned long long *best_key, int *counters, float *best_fd, int32_t *best_dst,
-                         hipStream_t stream);
+                         unsigned long long *best_key, float *best_fd, int32_t *best_dst, hipStream_t stream);
 
 // ---- prompt-guidance weight xi (Step 3) ----------------------------------------------------
 struct XiPlan {

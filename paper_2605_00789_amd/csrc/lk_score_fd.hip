@@ -31,7 +31,22 @@ struct FdArgs {
   float *best_fd;
   int32_t *best_dst;
   int slot, group, mt, nt, n_tiles, ksplit, n_spans, spans_per_wg;
+  int metric;   // 0: 1 - cos, 1: |a - b|, 2: |a - b|^2
 };
+
+// Divergence of a pair from its inner product and squared norms (fp64).  The distances use
+// |a - b|^2 = |a|^2 + |b|^2 - 2 <a, b>; the three sums of a pair come from the same instruction sequence, so identical
+// rows give exactly 0.
+__device__ __forceinline__ double divergence(int metric, double dot, double a2, double b2) {
+  if (metric == 0) {
+    double den;
+    if (a2 >= NORM_EPS * NORM_EPS && b2 >= NORM_EPS * NORM_EPS) den = sqrt(a2 * b2);
+    else den = fmax(sqrt(a2), NORM_EPS) * fmax(sqrt(b2), NORM_EPS);
+    return fmax(1.0 - dot / den, 0.0);
+  }
+  const double d2 = fmax(a2 + b2 - 2.0 * dot, 0.0);
+  return metric == 1 ? sqrt(d2) : d2;
+}
 
 struct WinInfo { int off, nA, nB; };
 
@@ -231,11 +246,7 @@ __global__ __launch_bounds__(FD_THREADS) void fd_epilogue_kernel(FdArgs g) {
         const int tc = col_base + c;   // column inside this row block's tile row
         const double dot = sum_slices(g.partial + (int64_t)(tile_row0 + (tc >> 5)) * FD_TILE_FLOATS + r * 32 + (tc & 31),
                                       ks_stride, g.ksplit);
-        const double b2 = nb2[tc];
-        double den;
-        if (a2 >= NORM_EPS * NORM_EPS && b2 >= NORM_EPS * NORM_EPS) den = sqrt(a2 * b2);
-        else den = fmax(sqrt(a2), NORM_EPS) * fmax(sqrt(b2), NORM_EPS);
-        const double fd = fmax(1.0 - dot / den, 0.0);
+        const double fd = divergence(g.metric, dot, a2, nb2[tc]);
         if (fd < best) { best = fd; best_c = c; }   // columns ascend: strict < keeps the first minimum
       }
     }
@@ -342,11 +353,7 @@ __global__ __launch_bounds__(FD_THREADS) void fd_tail_select_kernel(FdArgs g, Sm
     for (int k = 0; k < CPT; ++k) {
       const int c = cl + TPR * k;
       const double dot = L.tile[rr * 32 + c];
-      const double b2 = L.n2[1][c];
-      double den;
-      if (a2 >= NORM_EPS * NORM_EPS && b2 >= NORM_EPS * NORM_EPS) den = sqrt(a2 * b2);
-      else den = fmax(sqrt(a2), NORM_EPS) * fmax(sqrt(b2), NORM_EPS);
-      const double fd = fmax(1.0 - dot / den, 0.0);
+      const double fd = divergence(g.metric, dot, a2, L.n2[1][c]);
       const bool live = ta >= 0 && ((cols >> c) & 1u);
       if (live && fd < best) { best = fd; best_c = c; }   // columns ascend: strict < keeps the first minimum
     }
@@ -438,6 +445,7 @@ hipError_t launch_fd_select_small(const FdPlan &plan, int dtype, const void *X, 
   g.win_offsets = win_offsets; g.win_tokens = win_tokens;
   g.partial = partial; g.best_fd = best_fd; g.best_dst = best_dst;
   g.slot = plan.slot; g.group = plan.group; g.mt = 1; g.nt = 1; g.n_tiles = plan.n_tiles; g.ksplit = plan.ksplit;
+  g.metric = plan.metric;
   const int span = (dtype == 1) ? 64 : 32;
   g.n_spans = (d + span - 1) / span;
   g.spans_per_wg = (g.n_spans + plan.ksplit - 1) / plan.ksplit;
@@ -487,7 +495,7 @@ hipError_t launch_fd(const FdPlan &plan, int dtype, const void *X, int64_t ldx, 
   g.win_offsets = win_offsets; g.win_tokens = win_tokens;
   g.partial = partial; g.best_fd = best_fd; g.best_dst = best_dst;
   g.slot = plan.slot; g.group = plan.group; g.mt = plan.mt; g.nt = plan.nt;
-  g.n_tiles = plan.n_tiles; g.ksplit = plan.ksplit;
+  g.n_tiles = plan.n_tiles; g.ksplit = plan.ksplit; g.metric = plan.metric;
   const int span = (dtype == 1) ? 64 : 32;
   g.n_spans = (d + span - 1) / span;
   g.spans_per_wg = (g.n_spans + plan.ksplit - 1) / plan.ksplit;

@@ -2,8 +2,8 @@
 // the hierarchical schedule, Sec. 3.2.2): here the |A| x |B| x d contraction is compute bound and is run as a
 // classic LDS-tiled MFMA GEMM with the row arg-min fused into its epilogue.
 //
-//   row_norms_kernel : 1/|x| of every token (|x|^2 summed in fp32, inverse root in fp64), and initialisation of the
-//                      per-row best keys / arrival counters.
+//   row_norms_kernel : 1/|x| of every token (|x|^2 summed in fp32, inverse root in fp64; |x|^2 itself for the
+//                      distance metrics), and initialisation of the per-row best keys.
 //   fd_big_kernel    : workgroup tile 96 x 96, four waves, v_mfma_f32_16x16x32_bf16.  Rows are gathered through the
 //                      window's token list; 128-element k-steps travel global -> register ring (3 steps in flight)
 //                      -> double-buffered LDS (rows padded to 272 bytes: conflict-free 16-byte operand reads).
@@ -30,20 +30,18 @@ struct BigArgs {
   int64_t ldx;
   int d, n_windows, sum_n;
   const int32_t *win_offsets, *win_tokens;
-  double *rnorm;                 // [sum_n]  1 / max(|x|, 1e-12)
+  double *rnorm;                 // [sum_n]  1 / max(|x|, 1e-12)  (distance metrics: |x|^2)
   unsigned long long *best_key;  // [sum_n]
-  int *counters;                 // [n_windows * mt]
   float *best_fd;
   int32_t *best_dst;
-  int mt, nt, n_counters;
+  int mt, nt;
+  int metric;                    // 0: 1 - cos, 1: |a - b|, 2: |a - b|^2
 };
 
-// ---- 1/|x| per token (|x|^2 summed in fp32); also resets keys and counters ------------------------------------------------
+// ---- 1/|x| per token (|x|^2 summed in fp32); also resets the keys -------------------------------------------------
 __global__ __launch_bounds__(256) void row_norms_kernel(BigArgs g) {
   const int lane = threadIdx.x & 63;
   const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int gid = blockIdx.x * 256 + threadIdx.x;
-  if (gid < g.n_counters) g.counters[gid] = 0;
   if (tok >= g.sum_n) return;
   const char *row = static_cast<const char *>(g.X) + (int64_t)tok * g.ldx * 2;
   const int n_chunks = g.d >> 3;
@@ -72,7 +70,8 @@ __global__ __launch_bounds__(256) void row_norms_kernel(BigArgs g) {
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
   if (lane == 0) {
-    g.rnorm[tok] = 1.0 / fmax(sqrt((double)s), 1e-12);   // the only fp64 sqrt/div of the path: once per token
+    // the only fp64 sqrt/div of the cosine path: once per token
+    g.rnorm[tok] = g.metric == 0 ? 1.0 / fmax(sqrt((double)s), 1e-12) : (double)s;
     g.best_key[tok] = ~0ull;
   }
 }
@@ -300,8 +299,14 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
         const int rl = bi * 16 + kg * 4 + q;
         const double ra = e_rnorm[rl];
         const int ta = e_token[rl];
-        const double cosv = (double)own[3 * t + k][q] * ra * rb;
-        const float fd = (float)fmax(1.0 - cosv, 0.0);
+        const double dot = (double)own[3 * t + k][q];
+        float fd;
+        if (g.metric == 0) {
+          fd = (float)fmax(1.0 - dot * ra * rb, 0.0);
+        } else {   // |a - b|^2 = |a|^2 + |b|^2 - 2 <a, b>
+          const double d2 = fmax(ra + rb - 2.0 * dot, 0.0);
+          fd = (float)(g.metric == 1 ? sqrt(d2) : d2);
+        }
         // key = (FD bits, B token): tokens of a window ascend with their local position, so the smaller token is the
         // earlier column; NaN never competes
         unsigned long long key = ((unsigned long long)__float_as_uint(fd) << 32) | (unsigned)tb;
@@ -351,7 +356,7 @@ FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n) {
   p.wb = BIG_NB;   // 96 x 96 workgroup tiles: 15 x 15 = 225 tiles for the 1440 x 1440 case, one round on 256 CUs
   p.mt = (maxA + BIG_TM - 1) / BIG_TM;
   p.nt = maxB > 0 ? (maxB + BIG_TM - 1) / BIG_TM : 1;
-  p.n_counters = 0;
+  p.metric = 0;
   p.norm_floats = (size_t)sum_n * 2;   // doubles
   p.key_bytes = (size_t)sum_n * 8;
   return p;
@@ -359,14 +364,13 @@ FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n) {
 
 hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
                          const int32_t *win_offsets, const int32_t *win_tokens, double *rnorm,
-                         unsigned long long *best_key, int *counters, float *best_fd, int32_t *best_dst,
-                         hipStream_t stream) {
+                         unsigned long long *best_key, float *best_fd, int32_t *best_dst, hipStream_t stream) {
   if (n_windows == 0 || sum_n == 0) return hipSuccess;
   BigArgs g{};
   g.X = X; g.ldx = ldx; g.d = d; g.n_windows = n_windows; g.sum_n = sum_n;
   g.win_offsets = win_offsets; g.win_tokens = win_tokens;
-  g.rnorm = rnorm; g.best_key = best_key; g.counters = counters; g.best_fd = best_fd; g.best_dst = best_dst;
-  g.mt = plan.mt; g.nt = plan.nt; g.n_counters = 0;
+  g.rnorm = rnorm; g.best_key = best_key; g.best_fd = best_fd; g.best_dst = best_dst;
+  g.mt = plan.mt; g.nt = plan.nt; g.metric = plan.metric;
   hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((sum_n + 3) / 4)), dim3(256), 0, stream, g);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

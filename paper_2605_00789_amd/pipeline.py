@@ -43,11 +43,12 @@ class StageBuffers:
 class CompressionPipeline:
     def __init__(self, *, dtype: str, batch: int, d: int, heads: int, head_dim: int, tiles: int, grid_h: int,
                  grid_w: int, cu_txt: np.ndarray, windows_per_axis: Sequence[int], targets: Sequence[int],
-                 device="cuda:0", fused: bool = True):
+                 device="cuda:0", fused: bool = True, metric: str = "cosine"):
         self.dtype, self.batch, self.d, self.heads, self.head_dim = dtype, batch, d, heads, head_dim
         self.tiles, self.grid_h, self.grid_w = tiles, grid_h, grid_w
         self.device = torch.device(device)
         self.fused = fused
+        self.metric = metric
         self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.h_cu_txt = np.ascontiguousarray(cu_txt, dtype=np.int32)
         self.cu_txt = torch.from_numpy(self.h_cu_txt).to(self.device)
@@ -70,7 +71,7 @@ class CompressionPipeline:
             prob = B.Problem(batch=batch, d=d, heads=heads, head_dim=head_dim, dtype=dtype, h_cu_vis=h_cu,
                              cu_vis=cu, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt, n_windows=n_windows,
                              max_window_tokens=bound, win_offsets=win_offsets, win_tokens=win_tokens,
-                             win_remove=win_remove, h_win_remove=None)
+                             win_remove=win_remove, h_win_remove=None, metric=metric)
             ws_bytes = max(ws_bytes, B.lightkv_workspace_size(prob))
             st = StageBuffers(
                 n_in=n_in, n_out=n_out, w=w, problem=prob, h_cu_vis=h_cu, cu_vis=cu, win_offsets=win_offsets,

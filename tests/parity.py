@@ -7,6 +7,9 @@ Tolerances (stated by the task's parity bar):
                    (relative on the cosine); such cases are verified by score, and counted
   xi               relative 1e-3 (bf16 inputs) / 1e-5 (fp32)
   best_fd          absolute 1e-5 (bf16 inputs) / 1e-6 (fp32)
+                   (distance metrics: the same figures relative to the window's largest |a|^2 + |b|^2, the scale of
+                   the terms whose difference the distance is, and compared on the squared distance -- the square
+                   root is monotone, so selection is unaffected, but it has no bounded error near zero)
   X, K, V rows     per-row |delta|_2/|ref|_2 and max|delta|/max|ref| <= 2e-2 (bf16 I/O) / 1e-5 (fp32)
 """
 from __future__ import annotations
@@ -74,6 +77,7 @@ def check_stage(pipe, s: int, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_mode=0, lse
     g_xi = (st.xi.cpu().numpy() if xi_given is None else np.asarray(xi_given, dtype=np.float32))
     rep = StageReport(stage=s, n_in=st_cfg.n_in, n_out=st_cfg.n_out)
     bf16 = dtype == "bf16"
+    metric = getattr(pipe, "metric", "cosine")
 
     # ---- windows: exact
     cu_vis = st_cfg.h_cu_vis
@@ -109,7 +113,14 @@ def check_stage(pipe, s: int, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_mode=0, lse
             assert np.all(g["best_dst"][A] == -1) and np.all(np.isinf(g["best_fd"][A]))
             assert np.all(g["dst"][toks] == -1)
             continue
-        fd = O.feature_divergence(X64[A], X64[Bn])                # oracle's dense FD block (fp64)
+        fd = O.feature_divergence(X64[A], X64[Bn], metric)        # oracle's dense FD block (fp64)
+        g_fd = g["best_fd"][A].astype(np.float64)
+        scale = 1.0
+        if metric != "cosine":
+            if metric == "euclidean":
+                fd, g_fd = fd * fd, g_fd * g_fd
+            scale = float((X64[A] ** 2).sum(axis=1).max() + (X64[Bn] ** 2).sum(axis=1).max())
+        band = TIE_BAND * scale
         j_ref = np.argmin(fd, axis=1)
         f_ref = fd[np.arange(len(A)), j_ref]
         assert np.all(g["best_dst"][Bn] == -1) and np.all(np.isinf(g["best_fd"][Bn]))
@@ -119,9 +130,9 @@ def check_stage(pipe, s: int, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_mode=0, lse
         for la in np.nonzero(b_gpu != Bn[j_ref])[0]:
             assert int(b_gpu[la]) in local, "partner of token %d is outside its window's B set" % A[la]
             f_g = fd[la, local[int(b_gpu[la])]]
-            assert f_g <= f_ref[la] + TIE_BAND, "window %d row %d: partner FD %.9g vs best %.9g" % (w, la, f_g, f_ref[la])
+            assert f_g <= f_ref[la] + band, "window %d row %d: partner FD %.9g vs best %.9g" % (w, la, f_g, f_ref[la])
             rep.edge_ties += 1
-        err = np.abs(g["best_fd"][A].astype(np.float64) - f_ref)
+        err = np.abs(g_fd - f_ref) / scale
         rep.max_fd_abs = max(rep.max_fd_abs, float(err.max()))
         # merged set
         r = int(rem[w])
@@ -134,9 +145,9 @@ def check_stage(pipe, s: int, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_mode=0, lse
             tau = f_ref[order[r - 1]]
             for la, a in enumerate(A):
                 if int(a) in gpu_set:
-                    assert f_ref[la] <= tau + TIE_BAND, "window %d: merged token %d has FD %.9g > threshold %.9g" % (w, a, f_ref[la], tau)
+                    assert f_ref[la] <= tau + band, "window %d: merged token %d has FD %.9g > threshold %.9g" % (w, a, f_ref[la], tau)
                 else:
-                    assert f_ref[la] >= tau - TIE_BAND, "window %d: kept token %d has FD %.9g < threshold %.9g" % (w, a, f_ref[la], tau)
+                    assert f_ref[la] >= tau - band, "window %d: kept token %d has FD %.9g < threshold %.9g" % (w, a, f_ref[la], tau)
             rep.window_ties += 1
         # a merged token goes to the partner the score step reported
         for a in gpu_set:
@@ -186,13 +197,13 @@ def check_stage(pipe, s: int, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_mode=0, lse
     return rep, outs
 
 
-def check_workload(wl, pipe=None, stages=None, fused=True):
+def check_workload(wl, pipe=None, stages=None, fused=True, metric="cosine"):
     """Runs all stages of a workload teacher-forced; returns the per-stage reports."""
     from paper_2605_00789_amd import CompressionPipeline
     if pipe is None:
         pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
                                    tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
-                                   windows_per_axis=wl.windows_per_axis, targets=wl.targets, fused=fused)
+                                   windows_per_axis=wl.windows_per_axis, targets=wl.targets, fused=fused, metric=metric)
     X, K, V, pos = wl.X, wl.K, wl.V, wl.pos
     reports = []
     for s in range(wl.stages if stages is None else stages):

@@ -69,6 +69,8 @@ def test_workspace_size_and_descriptor_validation(B):
     assert _ws_size(B, _problem(B, heads=3))[0] == 2                            # heads*head_dim != d
     assert _ws_size(B, _problem(B, d=96, heads=2, head_dim=48))[0] == 5         # head size
     assert _ws_size(B, _problem(B, dtype=7))[0] == 5
+    assert _ws_size(B, _problem(B, metric=2))[0] == 0 and _ws_size(B, _problem(B, metric=3))[0] == 5   # lightkv_metric
+    assert _ws_size(B, _problem(B, metric=-1))[0] == 5
     assert _ws_size(B, _problem(B, batch=0))[0] == 2
     assert _ws_size(B, _problem(B, h_cu_vis=np.array([1, 8], dtype=np.int32)))[0] == 2
     assert _ws_size(B, _problem(B, h_cu_vis=np.array([0, 20000], dtype=np.int32),

@@ -58,6 +58,20 @@ def test_shapes_and_edge_cases(case):
     _report(wl, reps)
 
 
+@pytest.mark.parametrize("metric", ["euclidean", "l2sq"])
+@pytest.mark.parametrize("cfg", [1, 2, "global"])
+def test_distance_metrics_match_oracle(cfg, metric):
+    """The similarity-metric ablation (appendix): Euclidean and squared-L2 pairing on a fp32 config, a bf16
+    config that goes through all three window-size paths, and the single-window case (dense-contraction kernel)."""
+    from workloads import make_workload
+    from parity import check_workload
+    print("[parity] workload", cfg, "metric", metric, flush=True)
+    wl = make_workload(cfg)
+    reps = check_workload(wl, metric=metric)
+    _report(wl, reps)
+    assert [r.n_out for r in reps] == wl.targets
+
+
 def test_unfused_aggregate_then_compact_equals_fused_and_is_deterministic():
     from workloads import make_workload
     from parity import check_workload, to_dev
