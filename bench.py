@@ -36,6 +36,9 @@ def _parse():
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-repeats", type=int, default=3)
+    ap.add_argument("--cold", action="store_true",
+                    help="also time the dominant kernel with L2 and Infinity Cache flushed before every launch "
+                         "(extra object roofline_cold; the headline figures are unchanged)")
     return ap.parse_args()
 
 
@@ -162,6 +165,32 @@ def main():
                     acc[(s, n)] += max(e[k].elapsed_time(e[k + 1]) * 1e3 - null_us, 0.0) / n_inst   # microseconds
     calls_us = {"stage%d.%s" % (s + 1, n): round(acc[(s, n)], 2) for s in range(wl.stages) for n in names}
 
+    cold_us = None
+    if args.cold:
+        # every launch starts from caches that hold none of its inputs: a 1 GiB buffer is READ in front of it (clean
+        # lines: a flush by writing would leave the caches full of dirty lines whose write-back then competes with the
+        # kernel).  Stage inputs and index structures are the ones the eager pass above left behind.
+        flush = torch.zeros(1 << 27, dtype=torch.int64, device=dev)
+        sink = torch.zeros((), dtype=torch.int64, device=dev)
+        cold_us = 0.0
+        with torch.cuda.stream(stream):
+            for it in range(n_inst):
+                Xi, Ki, Vi, pi = X, K, V, pos
+                evs = []
+                for s in range(wl.stages):
+                    st = pipe.stages[s]
+                    torch.sum(flush, dim=(0,), out=sink)
+                    a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(stream)
+                    B.lightkv_aggregate_compact(st.problem, st.new_index, st.grp_offsets, st.grp_src, st.xi, Xi, Ki, Vi, pi,
+                                                st.X_out, st.K_out, st.V_out, st.pos_out)
+                    b2.record(stream)
+                    evs.append((a, b2))
+                    Xi, Ki, Vi, pi = st.X_out, st.K_out, st.V_out, st.pos_out
+                stream.synchronize()
+                cold_us += sum(max(a.elapsed_time(b2) * 1e3 - null_us, 0.0) for a, b2 in evs) / n_inst
+        del flush, sink
+
     # ---- roofline of the dominant kernel: message passing + compaction (one kernel per stage, HBM bound)
     rows_us = sum(acc[(s, "aggregate_compact")] for s in range(wl.stages))
     rows_b = sum(rows_bytes(wl, n_ins[s], wl.targets[s]) for s in range(wl.stages))
@@ -173,6 +202,34 @@ def main():
                 "avg_launch_us": round(rows_us / wl.stages, 2),
                 "algorithmic_bytes_per_launch": int(rows_b / wl.stages)}
 
+    # the dense-contraction case: FD half of lightkv_score on single-window stages (row norms + tiled MFMA kernel + key
+    # unpacking in one call; the profile under profiles/ isolates the MFMA kernel)
+    roofline_fd = None
+    if all(w == 0 for w in wl.windows_per_axis) and wl.dtype == "bf16":
+        fd_us = 0.0
+        with torch.cuda.stream(stream):
+            for it in range(n_inst):
+                torch.cuda._sleep(2_000_000)
+                st = pipe.stages[0]
+                a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                B.lightkv_score(st.problem, X, None, None, st.xi, st.best_fd, st.best_dst, pipe.ws, xi_mode=B.XI_GIVEN)
+                b2.record(stream)
+                stream.synchronize()
+                fd_us += max(a.elapsed_time(b2) * 1e3 - null_us, 0.0) / n_inst
+        nA, nB = (wl.n_per_seq + 1) // 2, wl.n_per_seq // 2
+        flops = 2.0 * wl.batch * nA * nB * wl.d
+        tf = flops / (fd_us * 1e-6) / 1e12
+        roofline_fd = {"call": "lightkv_score, FD half (row_norms + fd_big + finalize)", "bound": "mfma",
+                       "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                       "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "flops_per_call": int(flops),
+                       "avg_call_us": round(fd_us, 2)}
+
+    roofline_cold = None
+    if cold_us:
+        ach = rows_b / (cold_us * 1e-6) / 1e9
+        roofline_cold = {"achieved": round(ach, 1), "frac": round(ach / HBM_PEAK_GBS, 4), "unit": "GB/s",
+                         "avg_launch_us": round(cold_us / wl.stages, 2)}
     value = tokens_per_step / (ms_per_step * 1e-3)
     out = {
         "metric": "vision tokens compressed/sec per layer",
@@ -194,6 +251,10 @@ def main():
         "calls_us": calls_us,
         "event_overhead_us": round(null_us, 2),
     }
+    if roofline_cold:
+        out["roofline_cold"] = roofline_cold
+    if roofline_fd:
+        out["roofline_similarity"] = roofline_fd
 
     if not args.no_cpu_baseline:
         from oracle import lightkv_oracle as O
