@@ -21,6 +21,11 @@ constexpr int XI_THREADS = 256;
 constexpr float XI_FLOOR = 1e-30f;
 constexpr float LOG2E = 1.4426950408889634f;
 
+// 2^x on the hardware unit directly (v_exp_f32).  The library routine wraps it in a range reduction that keeps denormal
+// results; a probability below 2^-126 is zero for every purpose here, and the wrapper is five more instructions on each
+// of the H*T*N exponentials.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 struct XiArgs {
   const void *vis, *txt;                 // vision-side and prompt-side tensors of the contraction
   int64_t vis_ts, vis_hs, txt_ts, txt_hs;   // token / head strides in elements
@@ -54,19 +59,20 @@ __device__ __forceinline__ void load_half_row(const void *base, int first, int i
 // Prompt rows of one head are shared by the four waves of a workgroup: they are staged through LDS once per
 // workgroup (coalesced 16-byte loads, rows padded by 16 bytes so that the MFMA operand reads are conflict free)
 // instead of being fetched by every wave on its own.
-template <typename T, int DH> struct XiStage {
+// RW = prompt rows per staged chunk: 64 for short prompts, 128 otherwise (half as many barrier rounds per workgroup;
+// 34 KB of LDS for bf16 heads of 128, still four workgroups per CU).
+template <typename T, int DH, int RW> struct XiStage {
   static constexpr int ROW_BYTES = DH * Elem<T>::BYTES;
   static constexpr int PITCH = ROW_BYTES + 16;
-  static constexpr int ROWS = 64;   // prompt rows per staged chunk: at most 34 KB of LDS (17 KB for bf16 heads of 128), which
-                                    // leaves room on the CU for the kernels of the FD branch that run next to this one
+  static constexpr int ROWS = RW;
   static constexpr int TILES = ROWS / 32;
   static constexpr int CPR = ROW_BYTES / 16;                // 16-byte chunks per row
 };
 
 // Copies prompt rows [j0, j0 + ROWS) of head h into LDS (rows past nT repeat the last one).
-template <typename T, int DH>
+template <typename T, int DH, int RW>
 __device__ __forceinline__ void stage_prompt_rows(const XiArgs &g, char *q_lds, int t0, int nT, int j0, int64_t txt_ho) {
-  using S = XiStage<T, DH>;
+  using S = XiStage<T, DH, RW>;
   constexpr int BYTES = Elem<T>::BYTES;
   constexpr int PER_PASS = XI_THREADS / S::CPR;             // rows covered by one pass of the workgroup
   const int c = threadIdx.x % S::CPR, r0 = threadIdx.x / S::CPR;
@@ -82,7 +88,7 @@ __device__ __forceinline__ void stage_prompt_rows(const XiArgs &g, char *q_lds, 
 
 template <typename T, int DH>
 __device__ __forceinline__ void read_prompt_frag(const char *q_lds, int row, int half, uint4 *v) {
-  using S = XiStage<T, DH>;
+  using S = XiStage<T, DH, 64>;   // pitch and row size do not depend on the chunk length
   const char *p = q_lds + row * S::PITCH + half * (S::ROW_BYTES / 2);
 #pragma unroll
   for (int c = 0; c < XiShape<T, DH>::NCH; ++c) v[c] = *reinterpret_cast<const uint4 *>(p + c * 16);
@@ -91,10 +97,10 @@ __device__ __forceinline__ void read_prompt_frag(const char *q_lds, int row, int
 // ---- pass 1: (max, sum of exponentials) of every prompt row over one block of 128 vision keys ----------
 // Workgroup = (sequence, head, vision block); wave w owns the 32 vision tokens blk*128 + w*32 .. +32 and keeps
 // their key rows in registers as the MFMA row operand; the prompt rows come from LDS as the column operand.
-template <typename T, int DH>
+template <typename T, int DH, int RW>
 __global__ __launch_bounds__(XI_THREADS) void xi_rowstat_kernel(XiArgs g) {
   using E = Elem<T>;
-  using S = XiStage<T, DH>;
+  using S = XiStage<T, DH, RW>;
   constexpr int NCH = XiShape<T, DH>::NCH;
   __shared__ __attribute__((aligned(16))) char q_lds[S::ROWS * S::PITCH];
   __shared__ float2 part[4][S::ROWS];
@@ -118,10 +124,13 @@ __global__ __launch_bounds__(XI_THREADS) void xi_rowstat_kernel(XiArgs g) {
   bool row_ok[16];
 #pragma unroll
   for (int x = 0; x < 16; ++x) row_ok[x] = (vt * 32 + acc_row(x, lane)) < nV;
+  const bool partial_block = blk * 128 + 128 > nV;          // uniform: only the last block of a sequence masks rows
+  const bool neg_scale = g.scale_log2 < 0.f;
+  const float pad = neg_scale ? __uint_as_float(0x7f800000u) : NEG_INF;   // product whose logit is -inf
 
   for (int j0 = 0; j0 < nT; j0 += S::ROWS) {
     __syncthreads();   // the previous chunk has been consumed
-    stage_prompt_rows<T, DH>(g, q_lds, t0, nT, j0, txt_ho);
+    stage_prompt_rows<T, DH, RW>(g, q_lds, t0, nT, j0, txt_ho);
     __syncthreads();
     const int n_tt = min(S::TILES, (nT - j0 + 31) >> 5);
     for (int tt = 0; tt < n_tt; ++tt) {
@@ -130,19 +139,22 @@ __global__ __launch_bounds__(XI_THREADS) void xi_rowstat_kernel(XiArgs g) {
       f32x16 acc = {0};
 #pragma unroll
       for (int c = 0; c < NCH; ++c) E::mma32(k[c], q[c], acc);   // rows: vision tokens, cols: prompt rows
-      float t[16];
-      float m = NEG_INF;
+      // logits are acc * scale_log2; the extreme is taken on the raw products (maximum for a positive scale, minimum
+      // for a negative one), the scale goes into the exponent's multiply-add
+      if (partial_block) {
 #pragma unroll
-      for (int x = 0; x < 16; ++x) {
-        t[x] = row_ok[x] ? acc[x] * g.scale_log2 : NEG_INF;
-        m = fmaxf(m, t[x]);
+        for (int x = 0; x < 16; ++x) acc[x] = row_ok[x] ? acc[x] : pad;
       }
-      m = fmaxf(m, __shfl_xor(m, 32, 64));   // both half-waves hold rows of the same column
+      float e = acc[0];
+#pragma unroll
+      for (int x = 1; x < 16; ++x) e = neg_scale ? fminf(e, acc[x]) : fmaxf(e, acc[x]);
+      const float eo = __shfl_xor(e, 32, 64);   // both half-waves hold rows of the same column
+      e = neg_scale ? fminf(e, eo) : fmaxf(e, eo);
+      const float m = e * g.scale_log2;
       float s = 0.f;
-      if (m > NEG_INF) {
 #pragma unroll
-        for (int x = 0; x < 16; ++x) s += exp2f(t[x] - m);   // exp2(-inf) = 0 on masked rows
-      }
+      for (int x = 0; x < 16; ++x) s += fast_exp2(fmaf(acc[x], g.scale_log2, -m));   // padded rows: exp2(-inf) = 0
+      s = (m > NEG_INF) ? s : 0.f;              // a tile of padded rows only: (-inf, 0), as the merge expects
       s += __shfl_xor(s, 32, 64);
       if (half == 0) part[wave][tt * 32 + r] = make_float2(m, s);
     }
@@ -167,10 +179,10 @@ __global__ __launch_bounds__(XI_THREADS) void xi_rowstat_kernel(XiArgs g) {
 // ---- pass 2: column sums of exp(logit - lse) over the prompt rows -----------------------------------
 // Same decomposition; the key rows of the wave's 32 vision tokens are now the MFMA column operand, so the sum
 // over prompt rows runs over accumulator registers.
-template <typename T, int DH, bool VISION_LSE>
+template <typename T, int DH, int RW, bool VISION_LSE>
 __global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
   using E = Elem<T>;
-  using S = XiStage<T, DH>;
+  using S = XiStage<T, DH, RW>;
   constexpr int NCH = XiShape<T, DH>::NCH;
   __shared__ __attribute__((aligned(16))) char q_lds[S::ROWS * S::PITCH];
   __shared__ float2 rowstat[S::ROWS];   // per prompt row of the chunk: (max in exp2 domain, 1/sum)
@@ -202,13 +214,14 @@ __global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
   float colsum = 0.f;
   for (int j0 = 0; j0 < nT; j0 += S::ROWS) {
     __syncthreads();   // the previous chunk has been consumed
-    stage_prompt_rows<T, DH>(g, q_lds, t0, nT, j0, txt_ho);
+    stage_prompt_rows<T, DH, RW>(g, q_lds, t0, nT, j0, txt_ho);
     if (!VISION_LSE) {
-      // (max, 1/sum) of every prompt row of the chunk.  Four threads share a row: each merges every fourth
-      // per-block pair of pass 1 (its loads in flight together), then the four partial results are merged by
-      // shuffles -- a fixed order, and a dependent chain of nblk / 4 + 2 instead of nblk.
-      static_assert(S::ROWS * 4 == XI_THREADS, "four threads per prompt row of a chunk");
-      const int idx = threadIdx.x >> 2, part = threadIdx.x & 3;
+      // (max, 1/sum) of every prompt row of the chunk.  TPR threads share a row: each merges every TPR-th
+      // per-block pair of pass 1 (its loads in flight together), then the partial results are merged by
+      // shuffles -- a fixed order, and a dependent chain of nblk / TPR + log2(TPR) instead of nblk.
+      constexpr int TPR = XI_THREADS / S::ROWS;   // threads per prompt row of a chunk: 4 or 2
+      static_assert(TPR == 4 || TPR == 2, "chunk of 64 or 128 prompt rows");
+      const int idx = threadIdx.x / TPR, part = threadIdx.x % TPR;
       const int j = j0 + idx;
       float m = 3.0e38f, inv = 0.f;   // rows past nT: exp2(x - huge) = 0, times 0
       if (g.lse) {
@@ -217,11 +230,11 @@ __global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
         const float2 *p = reinterpret_cast<const float2 *>(g.stats) +
                           ((int64_t)h * g.sum_t + t0 + (j < nT ? j : nT - 1)) * g.max_vis_blocks;
         float pm = NEG_INF, psum = 0.f;
-        for (int s0 = 0; s0 < nblk; s0 += 32) {   // eight pairs per thread in flight; merged in index order
+        for (int s0 = 0; s0 < nblk; s0 += 8 * TPR) {   // eight pairs per thread in flight; merged in index order
           float2 a[8];
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
-            const int sb = s0 + 4 * u + part;
+            const int sb = s0 + TPR * u + part;
             a[u] = p[sb < nblk ? sb : nblk - 1];
             if (sb >= nblk) a[u] = make_float2(NEG_INF, 0.f);
           }
@@ -237,7 +250,7 @@ __global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
           }
         }
 #pragma unroll
-        for (int o = 1; o <= 2; o <<= 1) {   // the four threads of a row are neighbouring lanes
+        for (int o = 1; o < TPR; o <<= 1) {   // the threads of a row are neighbouring lanes
           const float om = __shfl_xor(pm, o, 64), os = __shfl_xor(psum, o, 64);
           const float mn = fmaxf(pm, om);
           // lower lane's pair first, so that both lanes of a pair compute the same bits
@@ -262,10 +275,10 @@ __global__ __launch_bounds__(XI_THREADS) void xi_colsum_kernel(XiArgs g) {
       for (int x = 0; x < 16; ++x) {
         const int row = tt * 32 + acc_row(x, lane);
         if (VISION_LSE) {
-          colsum += (j0 + row < nT) ? exp2f(acc[x] * g.scale_log2 - col_m) : 0.f;
+          colsum += (j0 + row < nT) ? fast_exp2(fmaf(acc[x], g.scale_log2, -col_m)) : 0.f;
         } else {
           const float2 st = rowstat[row];
-          colsum += exp2f(acc[x] * g.scale_log2 - st.x) * st.y;
+          colsum = fmaf(fast_exp2(fmaf(acc[x], g.scale_log2, -st.x)), st.y, colsum);
         }
       }
     }
@@ -307,26 +320,32 @@ XiPlan make_xi_plan(int batch, const int32_t *h_cu_vis, const int32_t *h_cu_txt,
   return p;
 }
 
-template <typename T, int DH>
-static hipError_t launch_xi_t(const XiPlan &plan, const XiArgs &g, int xi_mode, int max_t, hipStream_t stream) {
+template <typename T, int DH, int RW>
+static hipError_t launch_xi_rw(const XiPlan &plan, const XiArgs &g, int xi_mode, hipStream_t stream) {
   const bool vision_lse = (xi_mode == 1);
+  const unsigned grid = (unsigned)(g.batch * g.heads * plan.max_vis_blocks);
   if (xi_mode == 0 && g.lse == nullptr) {
-    const unsigned grid = (unsigned)(g.batch * g.heads * plan.max_vis_blocks);
-    if (grid) hipLaunchKernelGGL((xi_rowstat_kernel<T, DH>), dim3(grid), dim3(XI_THREADS), 0, stream, g);
+    if (grid) hipLaunchKernelGGL((xi_rowstat_kernel<T, DH, RW>), dim3(grid), dim3(XI_THREADS), 0, stream, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  const unsigned grid2 = (unsigned)(g.batch * g.heads * plan.max_vis_blocks);
-  if (grid2) {
+  if (grid) {
     if (vision_lse)
-      hipLaunchKernelGGL((xi_colsum_kernel<T, DH, true>), dim3(grid2), dim3(XI_THREADS), 0, stream, g);
+      hipLaunchKernelGGL((xi_colsum_kernel<T, DH, RW, true>), dim3(grid), dim3(XI_THREADS), 0, stream, g);
     else
-      hipLaunchKernelGGL((xi_colsum_kernel<T, DH, false>), dim3(grid2), dim3(XI_THREADS), 0, stream, g);
+      hipLaunchKernelGGL((xi_colsum_kernel<T, DH, RW, false>), dim3(grid), dim3(XI_THREADS), 0, stream, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   if (g.sum_n) hipLaunchKernelGGL(xi_heads_kernel, dim3((unsigned)((g.sum_n + 63) / 64)), dim3(64), 0, stream, g);
   return hipGetLastError();
+}
+
+template <typename T, int DH>
+static hipError_t launch_xi_t(const XiPlan &plan, const XiArgs &g, int xi_mode, int max_t, hipStream_t stream) {
+  // fp32 heads of 128 would need 67 KB of static LDS for 128-row chunks: they keep the short chunk
+  if (max_t > 64 && XiStage<T, DH, 128>::PITCH * 128 <= 40 * 1024) return launch_xi_rw<T, DH, 128>(plan, g, xi_mode, stream);
+  return launch_xi_rw<T, DH, 64>(plan, g, xi_mode, stream);
 }
 
 hipError_t launch_xi(const XiPlan &plan, int dtype, int xi_mode, int batch, int heads, int head_dim, int sum_n,
