@@ -58,9 +58,8 @@ hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int 
 
 // ---- prompt-guidance weight xi (Step 3) ----------------------------------------------------
 struct XiPlan {
-  int vsplit;          // (max, sum) pairs pass 1 leaves per prompt row = max_vis_blocks
   int max_text_tiles;  // ceil(max T_b / 32)
-  int max_vis_blocks;  // ceil(max N_b / 128)
+  int max_vis_blocks;  // ceil(max N_b / 128): pass 1 leaves one (max, sum) pair per prompt row and block
   size_t stat_floats;  // pass-1 partial (max, sum) pairs: heads * sumT * max_vis_blocks * 2
   size_t part_floats;  // per-head partial xi: heads * sumN
 };

@@ -5,7 +5,7 @@
 //   row_norms_kernel : 1/|x| of every token (|x|^2 summed in fp32, inverse root in fp64; |x|^2 itself for the
 //                      distance metrics), and initialisation of the per-row best keys.
 //   fd_big_kernel    : workgroup tile 96 x 96, four waves, v_mfma_f32_16x16x32_bf16.  Rows are gathered through the
-//                      window's token list; 128-element k-steps travel global -> register ring (3 steps in flight)
+//                      window's token list; 128-element k-steps travel global -> register ring (2 steps in flight)
 //                      -> double-buffered LDS (rows padded to 272 bytes: conflict-free 16-byte operand reads).
 //                      Every wave accumulates the whole tile over its quarter of each k-step; the partial tiles are
 //                      merged through LDS (fixed order), which also gives a two-level fp32 summation (error of a

@@ -32,10 +32,10 @@ struct XiArgs {
   const int32_t *cu_vis, *cu_txt;
   const float *lse;                      // optional, natural log
   float scale_log2;                      // softmax scale * log2(e)
-  float *stats;                          // [heads][sum_t][vsplit][2]  (max, sum) in the exp2 domain
+  float *stats;                          // [heads][sum_t][max_vis_blocks][2]  (max, sum) in the exp2 domain
   float *xi_part;                        // [heads][sum_n]
   float *xi;                             // [sum_n]
-  int batch, heads, sum_n, sum_t, vsplit, max_text_tiles, max_vis_blocks;
+  int batch, heads, sum_n, sum_t, max_text_tiles, max_vis_blocks;
   int lse_per_vision;                    // 1: lse indexed [h][vision token] (vision-query mode)
 };
 
@@ -314,7 +314,6 @@ XiPlan make_xi_plan(int batch, const int32_t *h_cu_vis, const int32_t *h_cu_txt,
   }
   p.max_text_tiles = (max_t + 31) / 32;
   p.max_vis_blocks = (max_n + 127) / 128;
-  p.vsplit = p.max_vis_blocks;   // pass 1 leaves one (max, sum) pair per block of 128 vision tokens
   p.stat_floats = (size_t)heads * (size_t)h_cu_txt[batch] * (size_t)p.max_vis_blocks * 2;
   p.part_floats = (size_t)heads * (size_t)h_cu_vis[batch];
   return p;
@@ -364,7 +363,7 @@ hipError_t launch_xi(const XiPlan &plan, int dtype, int xi_mode, int batch, int 
   g.scale_log2 = scale * LOG2E;
   g.stats = stats; g.xi_part = xi_part; g.xi = xi;
   g.batch = batch; g.heads = heads; g.sum_n = sum_n; g.sum_t = sum_t;
-  g.vsplit = plan.vsplit; g.max_text_tiles = plan.max_text_tiles; g.max_vis_blocks = plan.max_vis_blocks;
+  g.max_text_tiles = plan.max_text_tiles; g.max_vis_blocks = plan.max_vis_blocks;
   g.lse_per_vision = (xi_mode == 1);
   const int max_t = plan.max_text_tiles * 32;
 #define LK_XI_CASE(TT, DHV) return launch_xi_t<TT, DHV>(plan, g, xi_mode, max_t, stream)
