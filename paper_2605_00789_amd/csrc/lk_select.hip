@@ -236,7 +236,7 @@ __global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelA
 // pass needs a single workgroup scan (two values at once) instead of one per 1024 tokens; all loads of a pass are
 // issued together.
 constexpr int SCAN_THREADS = 1024;
-constexpr int SCAN_ITEMS = 12;     // tokens per thread and pass (12288 tokens per pass)
+constexpr int SCAN_ITEMS = 10;     // tokens per thread and pass (10240 tokens per pass)
 constexpr int FILL_UNROLL = 4;
 
 __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g) {
@@ -247,17 +247,19 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g) {
   int per = (g.sum_n + SCAN_THREADS - 1) / SCAN_THREADS;
   per = per < 1 ? 1 : (per > SCAN_ITEMS ? SCAN_ITEMS : per);
   const int pass_tokens = per * SCAN_THREADS;
+  const bool one_pass = g.sum_n <= pass_tokens;   // then dst / src_rank stay in registers for the inverse map below
   int keep_base = 0, cnt_base = 0;
+  int d[SCAN_ITEMS], c[SCAN_ITEMS], sr[SCAN_ITEMS];
   for (int pass_base = 0; pass_base < g.sum_n; pass_base += pass_tokens) {
     const int i0 = pass_base + tid * per;
-    int d[SCAN_ITEMS], c[SCAN_ITEMS];
 #pragma unroll
     for (int k = 0; k < SCAN_ITEMS; ++k) {
       const bool ok = k < per && i0 + k < g.sum_n;
       const int ic = ok ? i0 + k : 0;            // unconditional loads from a clamped index
-      const int dv = g.dst[ic], cv = g.cnt[ic];
+      const int dv = g.dst[ic], cv = g.cnt[ic], sv = g.src_rank[ic];
       d[k] = ok ? dv : 0;
       c[k] = ok ? cv : 0;
+      sr[k] = sv;
     }
     int ks = 0, cs = 0;
 #pragma unroll
@@ -305,29 +307,44 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g) {
     }
     keep_base += tot_k;
     cnt_base += tot_c;
-    __syncthreads();
+    if (!one_pass) __syncthreads();
   }
   for (int b = tid; b <= g.batch; b += SCAN_THREADS) {
     const int s = (b == tid) ? s_first : g.cu_vis[b];
     if (s >= g.sum_n) g.cu_vis_out[b] = keep_base;
   }
   if (tid == 0) g.grp_offsets[g.sum_n] = cnt_base;
-  __syncthreads();   // grp_offsets written by this workgroup are visible to it below
+  // inverse map: source a goes to slot grp_offsets[dst[a]] + (its rank among the sources of that target).  The
+  // grp_offsets read here were written by this workgroup before the barrier above.
+  if (one_pass) {
+    const int i0 = tid * per;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {   // c[] is free now: it takes the group starts
+      const bool ok = k < per && i0 + k < g.sum_n && d[k] >= 0;
+      c[k] = g.grp_offsets[ok ? d[k] : 0];
+      d[k] = ok ? d[k] : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k)
+      if (d[k] >= 0) g.grp_src[c[k] + sr[k]] = i0 + k;
+    return;
+  }
+  __syncthreads();
   for (int a0 = 0; a0 < g.sum_n; a0 += FILL_UNROLL * SCAN_THREADS) {
-    int b[FILL_UNROLL], sr[FILL_UNROLL], go[FILL_UNROLL];
+    int b[FILL_UNROLL], r2[FILL_UNROLL], go[FILL_UNROLL];
 #pragma unroll
     for (int j = 0; j < FILL_UNROLL; ++j) {
       const int a = a0 + j * SCAN_THREADS + tid;
       const int ac = a < g.sum_n ? a : 0;
       const int bv = g.dst[ac], sv = g.src_rank[ac];
       b[j] = a < g.sum_n ? bv : -1;
-      sr[j] = sv;
+      r2[j] = sv;
     }
 #pragma unroll
     for (int j = 0; j < FILL_UNROLL; ++j) go[j] = g.grp_offsets[b[j] >= 0 ? b[j] : 0];
 #pragma unroll
     for (int j = 0; j < FILL_UNROLL; ++j)
-      if (b[j] >= 0) g.grp_src[go[j] + sr[j]] = a0 + j * SCAN_THREADS + tid;
+      if (b[j] >= 0) g.grp_src[go[j] + r2[j]] = a0 + j * SCAN_THREADS + tid;
   }
 }
 
