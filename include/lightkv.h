@@ -28,6 +28,11 @@
  *     multiples of 8 elements (bf16) or 4 elements (fp32).
  *   - element type: LIGHTKV_BF16 (bf16 storage, fp32 accumulation on the matrix
  *     cores) or LIGHTKV_F32.
+ *   - threads: any host thread may call; calls are independent as long as their
+ *     outputs and workspaces do not overlap (two calls that share a workspace must
+ *     be ordered by the caller's streams, except where a function says otherwise).
+ *   - results are bit-reproducible: the same inputs give the same outputs on every
+ *     call, whatever else runs on the device.
  */
 #ifndef LIGHTKV_H
 #define LIGHTKV_H
@@ -146,7 +151,8 @@ lightkv_status lightkv_build_windows(int32_t batch, const int32_t *h_cu_vis, con
  *   The two halves are independent and may be enqueued by two calls, e.g. on two streams with the same workspace:
  *   X == NULL computes xi only (windows, best_fd, best_dst are not touched), xi_mode GIVEN computes the FD half only.
  *   When both halves are requested in one call the library runs them concurrently (xi on an internal helper stream
- *   that forks from and joins `stream`; the only object the library ever creates, one per device).
+ *   that forks from and joins `stream`; the only object the library ever creates, one per device, on the first such
+ *   call outside stream capture; host threads that make such calls on one device take turns enqueueing).
  */
 lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ldx,
                              const void *Q, int64_t q_tok_stride, int64_t q_head_stride,

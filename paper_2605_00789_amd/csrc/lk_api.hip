@@ -85,6 +85,7 @@ struct Fork {
   hipStream_t side = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
   bool ready = false;
+  std::mutex in_use;   // one caller at a time enqueues its fork ... join sequence on the shared helper stream
 };
 
 Fork *fork_for_current_device(hipStream_t main) {
@@ -250,8 +251,10 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx,
 
   if (use_big && (uint64_t)c.sum_n * (uint64_t)ldx * 2u >= (1ull << 32)) return LIGHTKV_ERR_UNSUPPORTED;   // 32-bit row offsets
   Fork *fk = nullptr;
+  std::unique_lock<std::mutex> fork_guard;   // released when this call returns, i.e. after the join has been enqueued
   if (need_xi) {
     if (need_fd) fk = fork_for_current_device(s);
+    if (fk) fork_guard = std::unique_lock<std::mutex>(fk->in_use);
     hipStream_t xs = s;
     if (fk) {
       if (hipEventRecord(fk->fork, s) == hipSuccess && hipStreamWaitEvent(fk->side, fk->fork, 0) == hipSuccess) xs = fk->side;

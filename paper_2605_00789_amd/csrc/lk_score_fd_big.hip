@@ -377,12 +377,14 @@ hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int 
   const unsigned n_tiles = (unsigned)(n_windows * plan.mt * plan.nt);
   const unsigned grid = (n_tiles + 7u) / 8u * 8u;   // whole rounds over the XCDs; surplus workgroups exit at once
   constexpr size_t lds = (size_t)2 * BIG_STAGE;      // 102 KB: above the 64 KB default, the attribute below allows it
-  static bool attr_set = false;                      // a property of the loaded kernel, set once per process
-  if (!attr_set) {
+  static bool attr_set[64] = {};                     // a property of the kernel as loaded on a device, set once per device
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!attr_set[dev]) {
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(fd_big_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set[dev] = true;
   }
   hipLaunchKernelGGL(fd_big_kernel, dim3(grid), dim3(BIG_THREADS), lds, stream, g);
   e = hipGetLastError();
