@@ -42,6 +42,10 @@ def test_measured_configs_match_oracle(cfg):
          head_dim=128, n_c=40, structure="grid", windows_per_axis=(1, 1), n_final=700),
     dict(name="big_windows_f32", dtype="f32", batch=1, grid_h=26, grid_w=27, text_lens=(17,), d=64, heads=2,
          head_dim=32, n_c=25, structure="grid", windows_per_axis=(1, 0), n_final=400),
+    dict(name="max_window_bf16", dtype="bf16", batch=1, grid_h=64, grid_w=64, text_lens=(24,), d=256, heads=2,
+         head_dim=128, n_c=50, structure="grid", windows_per_axis=(0,), n_final=2500),      # one window of 4096 tokens
+    dict(name="max_sequence_f32", dtype="f32", batch=1, grid_h=128, grid_w=128, text_lens=(33,), d=128, heads=4,
+         head_dim=32, n_c=60, structure="grid", windows_per_axis=(8, 4), n_final=9000),     # 16384 tokens in a sequence
     dict(name="no_removal", dtype="bf16", batch=1, grid_h=8, grid_w=8, text_lens=(8,), d=128, heads=1,
          head_dim=128, n_c=4, structure="iid", windows_per_axis=(2,), n_final=64),
     dict(name="all_of_A_leaves", dtype="bf16", batch=2, grid_h=8, grid_w=8, text_lens=(8, 9), d=128, heads=1,
