@@ -305,6 +305,20 @@ def test_graph_replay_equals_eager_in_the_benchmark_launch_configuration():
         pipe.run(X, K, V, Q, pos)
         stream.synchronize()
         eager = snapshot()
+        # the pipelined schedule of run() (helper streams, next stage's windows built during the merge) gives exactly
+        # what the plain stage-by-stage calls give -- the ones the oracle comparison of the measured configs runs
+        plain = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                                    tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                                    windows_per_axis=wl.windows_per_axis, targets=wl.targets)
+        Xi, Ki, Vi, pi = X, K, V, pos
+        for s_ in range(wl.stages):
+            st_ = plain.run_stage(s_, Xi, Ki, Vi, Q, pi)
+            Xi, Ki, Vi, pi = st_.X_out, st_.K_out, st_.V_out, st_.pos_out
+        stream.synchronize()
+        for k_, (a, st_) in enumerate(zip(eager[::13], plain.stages)):
+            for name, t in zip(("X_out", "K_out", "V_out", "pos_out", "dst", "new_index", "grp_offsets", "xi", "best_fd",
+                                "best_dst", "cu_vis_out", "win_offsets", "win_tokens"), eager[13 * k_:13 * k_ + 13]):
+                assert torch.equal(t, getattr(st_, name)), "stage %d: %s differs between run() and run_stage()" % (k_, name)
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g, stream=stream):
             pipe.run(X, K, V, Q, pos)
