@@ -35,7 +35,7 @@ def _parse():
     ap.add_argument("--workload", default="3", help="1..5, halving, global (default 3: the N=2880 LLaVA-NeXT-shaped layer)")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-repeats", type=int, default=3)
+    ap.add_argument("--cpu-repeats", type=int, default=20, help="oracle steps timed for cpu_baseline (about 10 s)")
     ap.add_argument("--cold", action="store_true",
                     help="also time the dominant kernel with L2 and Infinity Cache flushed before every launch "
                          "(extra object roofline_cold; the headline figures are unchanged)")
@@ -77,9 +77,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     from workloads import make_workload
-    from paper_2605_00789_amd import CompressionPipeline
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from parity import to_dev
+    from paper_2605_00789_amd import CompressionPipeline, to_device as to_dev
 
     cfg = int(args.workload) if args.workload.isdigit() else args.workload
     wl = make_workload(cfg)

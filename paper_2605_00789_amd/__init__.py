@@ -23,4 +23,4 @@ from .binding import (  # noqa: F401
     XI_GIVEN,
 )
 from .schedule import removal_counts, windows_per_sequence, max_window_cells  # noqa: F401
-from .pipeline import CompressionPipeline  # noqa: F401
+from .pipeline import CompressionPipeline, from_device, to_device  # noqa: F401

@@ -14,6 +14,21 @@ from . import binding as B
 from .schedule import max_window_cells, removal_counts, windows_per_sequence
 
 
+def to_device(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
+    """Storage array of a tensor (bf16 carried as uint16 bit patterns, or float32) -> device tensor of that dtype."""
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(device)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+def from_device(t: torch.Tensor, dtype: str) -> np.ndarray:
+    """Device tensor -> storage array (uint16 bit patterns for bf16)."""
+    t = t.detach().cpu().contiguous()
+    if dtype == "bf16":
+        return t.view(torch.int16).numpy().view(np.uint16).copy()
+    return t.numpy().copy()
+
+
 @dataclass
 class StageBuffers:
     n_in: int

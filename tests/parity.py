@@ -25,16 +25,13 @@ TIE_BAND = 1e-6
 
 
 def to_dev(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
-    if dtype == "bf16":
-        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(device)
-    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+    from paper_2605_00789_amd import to_device
+    return to_device(a, dtype, device)
 
 
 def from_dev(t: torch.Tensor, dtype: str) -> np.ndarray:
-    t = t.detach().cpu().contiguous()
-    if dtype == "bf16":
-        return t.view(torch.int16).numpy().view(np.uint16).copy()
-    return t.numpy().copy()
+    from paper_2605_00789_amd import from_device
+    return from_device(t, dtype)
 
 
 @dataclass
