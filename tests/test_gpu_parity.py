@@ -76,6 +76,53 @@ def test_distance_metrics_match_oracle(cfg, metric):
     assert [r.n_out for r in reps] == wl.targets
 
 
+def _feasible(wl):
+    """Every window of every stage can give up its share (the even split never asks a window for more than its A set)."""
+    from oracle import lightkv_oracle as O
+    X, K, V, pos, cu_vis, n_in = wl.X, wl.K, wl.V, wl.pos, wl.cu_vis, wl.n_per_seq
+    for s, res in enumerate(O.compress_schedule(wl)):
+        wo, _ = O.build_windows(pos, cu_vis, wl.tiles, wl.grid_h, wl.grid_w, wl.windows_per_axis[s])
+        rem = O.stage_removals(wl.batch, n_in, wl.targets[s], (len(wo) - 1) // wl.batch)
+        v = np.diff(wo)
+        if np.any(rem > np.where(v >= 2, (v + 1) // 2, 0)):
+            return False
+        pos, cu_vis, n_in = res.pos, res.cu_vis, wl.targets[s]
+    return True
+
+
+def test_random_small_shapes_match_oracle():
+    """Seeded sweep over shapes the fixed cases do not name: grids that do not divide into the windows, one- and
+    two-token windows, several tiles and sequences, every head size, one to three stages, both dtypes."""
+    from workloads import make_custom
+    from parity import check_workload
+    rng = np.random.default_rng(20240611)
+    done = 0
+    for trial in range(120):
+        head_dim = int(rng.choice([32, 64, 128]))
+        heads = int(rng.integers(1, 5))
+        batch = int(rng.integers(1, 4))
+        tiles = int(rng.integers(1, 3))
+        gh, gw = int(rng.integers(2, 21)), int(rng.integers(2, 21))
+        stages = int(rng.integers(1, 4))
+        n_seq = tiles * gh * gw
+        case = dict(name="rand%d" % trial, seed=1000 + trial, dtype=str(rng.choice(["bf16", "f32"])), batch=batch,
+                    tiles=tiles, grid_h=gh, grid_w=gw, text_lens=tuple(int(t) for t in rng.integers(1, 71, size=batch)),
+                    d=heads * head_dim, heads=heads, head_dim=head_dim, n_c=int(rng.integers(2, 12)),
+                    structure=str(rng.choice(["iid", "grid"])) if min(gh, gw) >= 4 else "iid",
+                    windows_per_axis=tuple(int(w) for w in rng.integers(0, 5, size=stages)),
+                    n_final=max(1, int(round(n_seq * float(rng.uniform(0.5, 1.0))))))
+        wl = make_custom(**case)
+        if not _feasible(wl):
+            continue
+        print("[parity] random case", case, flush=True)
+        reps = check_workload(wl)
+        assert [r.n_out for r in reps] == wl.targets
+        done += 1
+        if done == 48:
+            break
+    assert done >= 32, "the sweep found too few feasible cases (%d)" % done
+
+
 def test_unfused_aggregate_then_compact_equals_fused_and_is_deterministic():
     from workloads import make_workload
     from parity import check_workload, to_dev
