@@ -84,6 +84,9 @@ typedef enum {
 #define LIGHTKV_MAX_WINDOW_TOKENS 4096   /* tokens in one window                    */
 #define LIGHTKV_MAX_SEQ_TOKENS    16384  /* vision tokens in one sequence           */
 #define LIGHTKV_MAX_TEXT_TOKENS   4096   /* prompt tokens in one sequence           */
+/* Steps of at most this many vision tokens whose windows hold at most 64 tokens: lightkv_score_select runs the xi
+   passes inside the launches of the FD chain, on the caller's stream alone (see there). */
+#define LIGHTKV_ONE_STREAM_MAX_TOKENS 1024
 
 /*
  * Problem descriptor of one compression step (host struct).

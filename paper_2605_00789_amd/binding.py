@@ -110,6 +110,7 @@ def _ld(t: Optional[torch.Tensor]) -> int:
 
 
 METRICS = {"cosine": 0, "euclidean": 1, "l2sq": 2}
+ONE_STREAM_MAX_TOKENS = 1024   # LIGHTKV_ONE_STREAM_MAX_TOKENS
 
 
 class Problem:

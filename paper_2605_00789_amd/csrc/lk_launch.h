@@ -56,6 +56,23 @@ hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int 
                          const int32_t *win_offsets, const int32_t *win_tokens, double *rnorm,
                          unsigned long long *best_key, float *best_fd, int32_t *best_dst, hipStream_t stream);
 
+// ---- scores + selection in three launches on one stream (lk_fused.hip); windows of at most 64 tokens
+struct XiArgs;
+struct XiPlan;
+hipError_t launch_score_select_fused(const XiPlan &xp, const FdPlan &fp, int dtype, int xi_mode, int batch, int heads,
+                                     int head_dim, int d, int n_windows, int sum_n, int sum_t, const int32_t *cu_vis,
+                                     const int32_t *cu_txt, const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
+                                     const void *K, int64_t k_tok_stride, int64_t k_head_stride, const float *lse,
+                                     float scale, float *stats, float *xi_part, float *xi, const void *X, int64_t ldx,
+                                     const int32_t *win_offsets, const int32_t *win_tokens, const int32_t *win_remove,
+                                     float *partial, float *best_fd, int32_t *best_dst, int32_t *dst, int32_t *cnt,
+                                     int32_t *src_rank, int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src,
+                                     int32_t *cu_vis_out, hipStream_t stream);
+// index scan with the head sum of xi in the same launch (x: arguments of the xi passes)
+hipError_t launch_select_scan_heads(int batch, int sum_n, const int32_t *cu_vis, const int32_t *dst, int32_t *new_index,
+                                    int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, const int32_t *cnt,
+                                    const int32_t *src_rank, const XiArgs &x, hipStream_t stream);
+
 // ---- prompt-guidance weight xi (Step 3) ----------------------------------------------------
 struct XiPlan {
   int max_text_tiles;  // ceil(max T_b / 32)

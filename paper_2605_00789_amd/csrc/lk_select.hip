@@ -9,8 +9,7 @@
 //   select_window_kernel : per window -> dst[], per-token source counts, per-source ranks (up to 256 A nodes)
 //   select_rank_kernel   : the same results for larger windows, by counting smaller keys
 //   select_scan_kernel   : one workgroup -> exclusive scans (new_index, grp_offsets), cu_vis_out, grp_src
-#include "lk_common.h"
-#include "lk_launch.h"
+#include "lk_xi_body.h"
 
 namespace lk {
 
@@ -22,6 +21,7 @@ struct SelArgs {
   int32_t *dst, *new_index, *grp_offsets, *grp_src, *cu_vis_out, *cnt, *src_rank;
   int cap;   // power of two >= the largest |A|
 };
+
 
 template <int THREADS>
 __global__ __launch_bounds__(THREADS) void select_window_kernel(SelArgs g) {
@@ -239,7 +239,16 @@ constexpr int SCAN_THREADS = 1024;
 constexpr int SCAN_ITEMS = 10;     // tokens per thread and pass (10240 tokens per pass)
 constexpr int FILL_UNROLL = 4;
 
-__global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g) {
+// WITH_HEADS: the first n_head_blocks workgroups of the launch do something else entirely -- they sum the per-head xi
+// partials (last pass of the xi computation, lk_xi_body.h), which is independent of the scan and as short; the scan
+// is the last workgroup.  (The scan stays written out in the kernel: as an inlined function it costs eight more
+// registers at the 128-register limit of a 1024-thread workgroup and spills.)
+template <bool WITH_HEADS>
+__global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, XiArgs x, int n_head_blocks) {
+  if (WITH_HEADS && (int)blockIdx.x < n_head_blocks) {
+    xi_heads_body(x, blockIdx.x * SCAN_THREADS + threadIdx.x);
+    return;
+  }
   __shared__ int kb[SCAN_THREADS * SCAN_ITEMS];   // staying tokens before each token of the pass
   __shared__ int2 wsum[SCAN_THREADS / 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -327,10 +336,9 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g) {
 #pragma unroll
     for (int k = 0; k < SCAN_ITEMS; ++k)
       if (d[k] >= 0) g.grp_src[c[k] + sr[k]] = i0 + k;
-    return;
   }
   __syncthreads();
-  for (int a0 = 0; a0 < g.sum_n; a0 += FILL_UNROLL * SCAN_THREADS) {
+  for (int a0 = 0; a0 < (one_pass ? 0 : g.sum_n); a0 += FILL_UNROLL * SCAN_THREADS) {
     int b[FILL_UNROLL], r2[FILL_UNROLL], go[FILL_UNROLL];
 #pragma unroll
     for (int j = 0; j < FILL_UNROLL; ++j) {
@@ -348,6 +356,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g) {
   }
 }
 
+
+
 hipError_t launch_select_scan(int batch, int sum_n, const int32_t *cu_vis, const int32_t *dst, int32_t *new_index,
                               int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, const int32_t *cnt,
                               const int32_t *src_rank, hipStream_t stream) {
@@ -355,7 +365,20 @@ hipError_t launch_select_scan(int batch, int sum_n, const int32_t *cu_vis, const
   g.batch = batch; g.sum_n = sum_n; g.cu_vis = cu_vis;
   g.dst = const_cast<int32_t *>(dst); g.new_index = new_index; g.grp_offsets = grp_offsets; g.grp_src = grp_src;
   g.cu_vis_out = cu_vis_out; g.cnt = const_cast<int32_t *>(cnt); g.src_rank = const_cast<int32_t *>(src_rank);
-  hipLaunchKernelGGL(select_scan_kernel, dim3(1), dim3(SCAN_THREADS), 0, stream, g);
+  hipLaunchKernelGGL(select_scan_kernel<false>, dim3(1), dim3(SCAN_THREADS), 0, stream, g, XiArgs{}, 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_scan_heads(int batch, int sum_n, const int32_t *cu_vis, const int32_t *dst, int32_t *new_index,
+                                    int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, const int32_t *cnt,
+                                    const int32_t *src_rank, const XiArgs &x, hipStream_t stream) {
+  SelArgs g{};
+  g.batch = batch; g.sum_n = sum_n; g.cu_vis = cu_vis;
+  g.dst = const_cast<int32_t *>(dst); g.new_index = new_index; g.grp_offsets = grp_offsets; g.grp_src = grp_src;
+  g.cu_vis_out = cu_vis_out; g.cnt = const_cast<int32_t *>(cnt); g.src_rank = const_cast<int32_t *>(src_rank);
+  const int n_head_blocks = (sum_n + SCAN_THREADS - 1) / SCAN_THREADS;
+  hipLaunchKernelGGL(select_scan_kernel<true>, dim3((unsigned)(n_head_blocks + 1)), dim3(SCAN_THREADS), 0, stream, g, x,
+                     n_head_blocks);
   return hipGetLastError();
 }
 
@@ -391,7 +414,7 @@ hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int su
     }
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(select_scan_kernel, dim3(1), dim3(SCAN_THREADS), 0, stream, g);
+  hipLaunchKernelGGL(select_scan_kernel<false>, dim3(1), dim3(SCAN_THREADS), 0, stream, g, XiArgs{}, 0);
   return hipGetLastError();
 }
 

@@ -126,9 +126,13 @@ class CompressionPipeline:
         p = st.problem
         main = torch.cuda.current_stream() if stream is None else stream
         xi = st.xi
+        # small steps with windows of at most 64 tokens: lightkv_score_select runs the xi passes inside the launches of
+        # the FD chain, all on the caller's stream; otherwise xi gets the helper stream
+        one_stream = (self.fused and xi_given is None and 0 < p.c.max_window_tokens <= 64
+                      and X.shape[0] <= B.ONE_STREAM_MAX_TOKENS)
         if xi_given is not None:
             xi = xi_given
-        else:
+        elif not one_stream:
             self.side.wait_stream(main)                                   # fork
             B.lightkv_score(p, None, Q, K if score_K is None else score_K, xi, None, None, self.ws, xi_mode=xi_mode,
                             lse=lse, softmax_scale=softmax_scale, stream=self.side)          # xi half only
@@ -137,7 +141,11 @@ class CompressionPipeline:
         else:
             B.lightkv_build_windows(self.batch, st.h_cu_vis, st.cu_vis, pos, self.tiles, self.grid_h, self.grid_w, st.w,
                                     st.win_offsets, st.win_tokens, stream=main)
-        if self.fused:   # FD half + selection (one kernel where the windows are small)
+        if one_stream:
+            B.lightkv_score_select(p, X, Q, K if score_K is None else score_K, xi, st.best_fd, st.best_dst, st.dst,
+                                   st.new_index, st.grp_offsets, st.grp_src, st.cu_vis_out, self.ws, xi_mode=xi_mode,
+                                   lse=lse, softmax_scale=softmax_scale, stream=main)
+        elif self.fused:   # FD half + selection
             B.lightkv_score_select(p, X, None, None, xi, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets,
                                    st.grp_src, st.cu_vis_out, self.ws, xi_mode=B.XI_GIVEN, stream=main)
         else:
@@ -152,7 +160,7 @@ class CompressionPipeline:
             B.lightkv_build_windows(self.batch, nx.h_cu_vis, nx.cu_vis, st.pos_out, self.tiles, self.grid_h,
                                     self.grid_w, nx.w, nx.win_offsets, nx.win_tokens, stream=self.side2)
             pos_here = None                                               # pos_out is written on the helper stream
-        if xi_given is None:
+        if xi_given is None and not one_stream:
             main.wait_stream(self.side)                                   # join: the merge needs xi
         stream = main
         if self.fused:
