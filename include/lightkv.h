@@ -140,6 +140,19 @@ lightkv_status lightkv_build_windows(int32_t batch, const int32_t *h_cu_vis, con
                                      int32_t w, int32_t *win_offsets, int32_t *win_tokens, void *stream);
 
 /*
+ * The same partition for the NEXT stage of the hierarchical schedule (Sec. 3.2.2), taken from this stage's tensors
+ * before they are compacted: h_cu_vis / cu_vis / pos describe the current tokens, new_index[sumN] (from
+ * lightkv_select) says which of them stay and under which index, cu_vis_out[batch+1] (from lightkv_select) holds
+ * the sequence offsets after compaction.  The outputs list the staying tokens under their new indices, exactly as
+ * lightkv_build_windows would on the compacted pos -- but they depend on the selection only, so the call can be
+ * enqueued next to the merge of the rows instead of behind it.
+ */
+lightkv_status lightkv_build_windows_next(int32_t batch, const int32_t *h_cu_vis, const int32_t *cu_vis,
+                                          const int32_t *pos, const int32_t *new_index, const int32_t *cu_vis_out,
+                                          int32_t tiles, int32_t grid_h, int32_t grid_w, int32_t w,
+                                          int32_t *win_offsets, int32_t *win_tokens, void *stream);
+
+/*
  * Scores (Steps 1-3).
  *   X[sumN, d] (row stride ldx): vision hidden states.  For every A node the lowest-FD B node of its
  *   window: best_fd[i] = FD (fp32, clamped at 0), best_dst[i] = that B token; ties go to the B node that

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     lightkv_aggregate,
     lightkv_aggregate_compact,
     lightkv_build_windows,
+    lightkv_build_windows_next,
     lightkv_compact,
     lightkv_score,
     lightkv_score_select,

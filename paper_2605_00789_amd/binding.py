@@ -52,6 +52,8 @@ def _load():
     lib.lightkv_workspace_size.argtypes = [P, C.POINTER(sz)]
     lib.lightkv_build_windows.restype = C.c_int
     lib.lightkv_build_windows.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
+    lib.lightkv_build_windows_next.restype = C.c_int
+    lib.lightkv_build_windows_next.argtypes = [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     lib.lightkv_score.restype = C.c_int
     lib.lightkv_score.argtypes = [P, vp, i64, vp, i64, i64, vp, i64, i64, i32, vp, f32, vp, vp, vp, vp, sz, vp]
     lib.lightkv_score_select.restype = C.c_int
@@ -71,6 +73,7 @@ def _load():
 _lib = _load()
 
 EXPORTS = ("lightkv_status_string", "lightkv_version", "lightkv_workspace_size", "lightkv_build_windows",
+           "lightkv_build_windows_next",
            "lightkv_score", "lightkv_score_select", "lightkv_select", "lightkv_aggregate", "lightkv_compact", "lightkv_aggregate_compact")
 
 
@@ -155,6 +158,13 @@ def lightkv_build_windows(batch, h_cu_vis, cu_vis, pos, tiles, grid_h, grid_w, w
     _check(_lib.lightkv_build_windows(batch, _hptr(h_cu_vis), _dptr(cu_vis), _dptr(pos), tiles, grid_h, grid_w, w,
                                       _dptr(win_offsets), _dptr(win_tokens), _stream(stream)),
            "lightkv_build_windows")
+
+
+def lightkv_build_windows_next(batch, h_cu_vis, cu_vis, pos, new_index, cu_vis_out, tiles, grid_h, grid_w, w,
+                               win_offsets, win_tokens, stream=None):
+    _check(_lib.lightkv_build_windows_next(batch, _hptr(h_cu_vis), _dptr(cu_vis), _dptr(pos), _dptr(new_index),
+                                           _dptr(cu_vis_out), tiles, grid_h, grid_w, w, _dptr(win_offsets),
+                                           _dptr(win_tokens), _stream(stream)), "lightkv_build_windows_next")
 
 
 def lightkv_score(p: Problem, X, Q, K, xi, best_fd, best_dst, ws, *, heads_major=False, xi_mode=XI_TEXT_QUERY,

@@ -176,9 +176,10 @@ lightkv_status lightkv_workspace_size(const lightkv_problem *p, size_t *bytes) {
   return LIGHTKV_OK;
 }
 
-lightkv_status lightkv_build_windows(int32_t batch, const int32_t *h_cu_vis, const int32_t *cu_vis,
-                                     const int32_t *pos, int32_t tiles, int32_t grid_h, int32_t grid_w,
-                                     int32_t w, int32_t *win_offsets, int32_t *win_tokens, void *stream) {
+static lightkv_status build_windows_impl(int32_t batch, const int32_t *h_cu_vis, const int32_t *cu_vis,
+                                         const int32_t *pos, const int32_t *new_index, const int32_t *cu_vis_out,
+                                         int32_t tiles, int32_t grid_h, int32_t grid_w, int32_t w,
+                                         int32_t *win_offsets, int32_t *win_tokens, void *stream) {
   if (!h_cu_vis || !cu_vis || !pos || !win_offsets || !win_tokens) return LIGHTKV_ERR_NULL;
   if (batch < 1 || tiles < 1 || grid_h < 1 || grid_w < 1 || w < 0 || h_cu_vis[0] != 0) return LIGHTKV_ERR_SHAPE;
   int max_seq = 0;
@@ -189,10 +190,26 @@ lightkv_status lightkv_build_windows(int32_t batch, const int32_t *h_cu_vis, con
   }
   if (max_seq > LIGHTKV_MAX_SEQ_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;
   if ((int64_t)tiles * w * w > (1 << 17) || (int64_t)tiles * grid_h * grid_w > (1ll << 30)) return LIGHTKV_ERR_UNSUPPORTED;
-  if (launch_build_windows(cu_vis, pos, batch, max_seq, tiles, grid_h, grid_w, w, win_offsets, win_tokens,
-                           static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (launch_build_windows(cu_vis, pos, new_index, cu_vis_out, batch, max_seq, tiles, grid_h, grid_w, w, win_offsets,
+                           win_tokens, static_cast<hipStream_t>(stream)) != hipSuccess)
     return LIGHTKV_ERR_LAUNCH;
   return LIGHTKV_OK;
+}
+
+lightkv_status lightkv_build_windows(int32_t batch, const int32_t *h_cu_vis, const int32_t *cu_vis,
+                                     const int32_t *pos, int32_t tiles, int32_t grid_h, int32_t grid_w,
+                                     int32_t w, int32_t *win_offsets, int32_t *win_tokens, void *stream) {
+  return build_windows_impl(batch, h_cu_vis, cu_vis, pos, nullptr, nullptr, tiles, grid_h, grid_w, w, win_offsets,
+                            win_tokens, stream);
+}
+
+lightkv_status lightkv_build_windows_next(int32_t batch, const int32_t *h_cu_vis, const int32_t *cu_vis,
+                                          const int32_t *pos, const int32_t *new_index, const int32_t *cu_vis_out,
+                                          int32_t tiles, int32_t grid_h, int32_t grid_w, int32_t w,
+                                          int32_t *win_offsets, int32_t *win_tokens, void *stream) {
+  if (!new_index || !cu_vis_out) return LIGHTKV_ERR_NULL;
+  return build_windows_impl(batch, h_cu_vis, cu_vis, pos, new_index, cu_vis_out, tiles, grid_h, grid_w, w, win_offsets,
+                            win_tokens, stream);
 }
 
 }  // extern "C"

@@ -27,7 +27,8 @@ constexpr int FD_MAX_COLS = 2048;                   // |B| of the largest suppor
 
 FdPlan make_fd_plan(int n_windows, int max_window_tokens, int d, int dtype_bytes);
 
-hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, int batch, int max_seq, int tiles,
+hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, const int32_t *new_index,
+                                const int32_t *cu_out, int batch, int max_seq, int tiles,
                                 int grid_h, int grid_w, int w, int32_t *win_offsets, int32_t *win_tokens,
                                 hipStream_t stream);
 

@@ -17,9 +17,16 @@ constexpr size_t WIN_TABLE_LDS_MAX = 60 * 1024;   // bytes of LDS the (run, wind
 
 struct WinArgs {
   const int32_t *cu_vis, *pos;
+  // "next stage" form: the tokens are those of the PREVIOUS stage (cu_vis, pos); a token takes part if
+  // new_index[i] >= 0 and is listed under that index; cu_out holds the sequence offsets after compaction.
+  // Both NULL: the plain form (every token takes part under its own index).
+  const int32_t *new_index, *cu_out;
   int batch, tiles, grid_h, grid_w, w, win_per_seq;
   int32_t *win_offsets, *win_tokens;
 };
+
+// index under which token i is listed, or -1 if it does not take part
+__device__ __forceinline__ int listed_as(const WinArgs &g, int i) { return g.new_index ? g.new_index[i] : i; }
 
 __device__ __forceinline__ int window_of(const WinArgs &g, int p) {
   if (g.w == 0) return 0;
@@ -57,6 +64,8 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_table_kernel(WinArg
   const int b = blockIdx.x;
   const int base = g.cu_vis[b];
   const int n = g.cu_vis[b + 1] - base;
+  const int out_base = g.cu_out ? g.cu_out[b] : base;                 // first listed index of the sequence
+  const int out_n = g.cu_out ? g.cu_out[b + 1] - out_base : n;        // tokens that take part
   const int wps = g.win_per_seq;
   const int wbase = b * wps;
   const int runs = (n + 63) >> 6;
@@ -68,7 +77,7 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_table_kernel(WinArg
   // phase 1: per-run counts
   for (int i0 = 0; i0 < n; i0 += WIN_THREADS) {
     const int i = i0 + threadIdx.x;
-    const bool valid = i < n;
+    const bool valid = i < n && listed_as(g, base + (i < n ? i : 0)) >= 0;
     const int wid = valid ? window_of(g, g.pos[base + i]) : -1;
     int rank, gs; bool leader;
     wave_bin_rank(wid, valid, lane, rank, gs, leader);
@@ -110,20 +119,21 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_table_kernel(WinArg
     const int excl = carry + (wave ? scan_lds[32 + wave - 1] : 0) + inc - total;
     if (w < wps) {
       winbase[w] = excl;
-      g.win_offsets[wbase + w] = base + excl;
+      g.win_offsets[wbase + w] = out_base + excl;
     }
     carry += scan_lds[32 + WIN_THREADS / 64 - 1];
     __syncthreads();
   }
-  if (threadIdx.x == 0 && b == g.batch - 1) g.win_offsets[wbase + wps] = base + n;
+  if (threadIdx.x == 0 && b == g.batch - 1) g.win_offsets[wbase + wps] = out_base + out_n;
   // phase 3: slots
   for (int i0 = 0; i0 < n; i0 += WIN_THREADS) {
     const int i = i0 + threadIdx.x;
-    const bool valid = i < n;
+    const int id = i < n ? listed_as(g, base + i) : -1;
+    const bool valid = id >= 0;
     const int wid = valid ? window_of(g, g.pos[base + i]) : -1;
     int rank, gs; bool leader;
     wave_bin_rank(wid, valid, lane, rank, gs, leader);
-    if (valid) g.win_tokens[base + winbase[wid] + table[(i >> 6) * wps + wid] + rank] = base + i;
+    if (valid) g.win_tokens[out_base + winbase[wid] + table[(i >> 6) * wps + wid] + rank] = id;
   }
 }
 
@@ -131,11 +141,15 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_sort_kernel(WinArgs
   extern __shared__ uint32_t keys[];
   const int b = blockIdx.x;
   const int base = g.cu_vis[b];
-  const int n = g.cu_vis[b + 1] - base;
+  const int n_all = g.cu_vis[b + 1] - base;                            // tokens looked at
+  const int out_base = g.cu_out ? g.cu_out[b] : base;
+  const int n = g.cu_out ? g.cu_out[b + 1] - out_base : n_all;         // tokens that take part: they sort to the front
   const int wbase = b * g.win_per_seq;
-  const int p2 = next_pow2(n > 1 ? n : 1);
-  for (int i = threadIdx.x; i < p2; i += blockDim.x)
-    keys[i] = (i < n) ? (((uint32_t)window_of(g, g.pos[base + i]) << LOCAL_BITS) | (uint32_t)i) : 0xffffffffu;
+  const int p2 = next_pow2(n_all > 1 ? n_all : 1);
+  for (int i = threadIdx.x; i < p2; i += blockDim.x) {
+    const bool in = i < n_all && listed_as(g, base + (i < n_all ? i : 0)) >= 0;
+    keys[i] = in ? (((uint32_t)window_of(g, g.pos[base + i]) << LOCAL_BITS) | (uint32_t)i) : 0xffffffffu;
+  }
   bitonic_sort_lds(keys, p2);
   // sorted position k holds the k-th token of the window-major order
   for (int k = threadIdx.x; k <= n; k += blockDim.x) {
@@ -143,19 +157,20 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_sort_kernel(WinArgs
     int cur;
     if (k < n) {
       cur = (int)(keys[k] >> LOCAL_BITS);
-      g.win_tokens[base + k] = base + (int)(keys[k] & ((1u << LOCAL_BITS) - 1u));
+      g.win_tokens[out_base + k] = listed_as(g, base + (int)(keys[k] & ((1u << LOCAL_BITS) - 1u)));
     } else {
       cur = (b == g.batch - 1) ? g.win_per_seq : g.win_per_seq - 1;   // the next sequence writes its own first offset
     }
-    for (int id = prev + 1; id <= cur; ++id) g.win_offsets[wbase + id] = base + k;
+    for (int id = prev + 1; id <= cur; ++id) g.win_offsets[wbase + id] = out_base + k;
   }
 }
 
-hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, int batch, int max_seq, int tiles,
+hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, const int32_t *new_index,
+                                const int32_t *cu_out, int batch, int max_seq, int tiles,
                                 int grid_h, int grid_w, int w, int32_t *win_offsets, int32_t *win_tokens,
                                 hipStream_t stream) {
   WinArgs g{};
-  g.cu_vis = cu_vis; g.pos = pos; g.batch = batch; g.tiles = tiles; g.grid_h = grid_h; g.grid_w = grid_w; g.w = w;
+  g.cu_vis = cu_vis; g.pos = pos; g.new_index = new_index; g.cu_out = cu_out; g.batch = batch; g.tiles = tiles; g.grid_h = grid_h; g.grid_w = grid_w; g.w = w;
   g.win_per_seq = (w == 0) ? 1 : tiles * w * w;
   g.win_offsets = win_offsets; g.win_tokens = win_tokens;
   const int runs = (max_seq + 63) / 64;

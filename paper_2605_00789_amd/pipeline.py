@@ -152,20 +152,20 @@ class CompressionPipeline:
             B.lightkv_score(p, X, None, None, xi, st.best_fd, st.best_dst, self.ws, xi_mode=B.XI_GIVEN, stream=main)
             B.lightkv_select(p, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets, st.grp_src,
                              st.cu_vis_out, self.ws, stream=main)
-        pos_here = pos
         if prepare_next and self.fused and s + 1 < len(self.stages):
+            # the next stage's windows follow from pos and new_index alone: they are built on the second helper stream
+            # while the rows are merged on this one
             nx = self.stages[s + 1]
             self.side2.wait_stream(main)                                  # fork after select
-            B.lightkv_compact(p, st.new_index, None, None, None, pos, None, None, None, st.pos_out, stream=self.side2)
-            B.lightkv_build_windows(self.batch, nx.h_cu_vis, nx.cu_vis, st.pos_out, self.tiles, self.grid_h,
-                                    self.grid_w, nx.w, nx.win_offsets, nx.win_tokens, stream=self.side2)
-            pos_here = None                                               # pos_out is written on the helper stream
+            B.lightkv_build_windows_next(self.batch, st.h_cu_vis, st.cu_vis, pos, st.new_index, st.cu_vis_out, self.tiles,
+                                         self.grid_h, self.grid_w, nx.w, nx.win_offsets, nx.win_tokens,
+                                         stream=self.side2)
         if xi_given is None and not one_stream:
             main.wait_stream(self.side)                                   # join: the merge needs xi
         stream = main
         if self.fused:
-            B.lightkv_aggregate_compact(p, st.new_index, st.grp_offsets, st.grp_src, xi, X, K, V, pos_here, st.X_out,
-                                        st.K_out, st.V_out, None if pos_here is None else st.pos_out, stream=stream)
+            B.lightkv_aggregate_compact(p, st.new_index, st.grp_offsets, st.grp_src, xi, X, K, V, pos, st.X_out,
+                                        st.K_out, st.V_out, st.pos_out, stream=stream)
         else:
             n = X.shape[0]
             tx, tk, tv = (t[:n] for t in self.tmp)

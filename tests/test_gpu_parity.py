@@ -316,6 +316,25 @@ def test_build_windows_matches_oracle(case):
     np.testing.assert_array_equal(wo.cpu().numpy(), ro)
     np.testing.assert_array_equal(wt.cpu().numpy()[:len(rt)], rt)
 
+    # the "next stage" form: a random third of these tokens is merged away; the windows built from (pos, new_index,
+    # offsets after compaction) are those of the oracle on the compacted pos
+    if len(pos):
+        gone = rng.random(len(pos)) < 0.33
+        dst = np.where(gone, 0, -1).astype(np.int32)                 # only the sign matters to kept_index
+        new_index = O.kept_index(dst)
+        cu_out = np.zeros(case["batch"] + 1, dtype=np.int32)
+        for b in range(case["batch"]):
+            cu_out[b + 1] = cu_out[b] + int((~gone[h_cu[b]:h_cu[b + 1]]).sum())
+        wo2 = torch.full((n_win + 1,), -7, dtype=torch.int32, device="cuda")
+        wt2 = torch.full((len(pos),), -7, dtype=torch.int32, device="cuda")
+        L.lightkv_build_windows_next(case["batch"], h_cu, d_cu, d_pos, torch.from_numpy(new_index).cuda(),
+                                     torch.from_numpy(cu_out).cuda(), case["tiles"], case["gh"], case["gw"], case["w"],
+                                     wo2, wt2)
+        torch.cuda.synchronize()
+        ro2, rt2 = O.build_windows(pos[~gone], cu_out, case["tiles"], case["gh"], case["gw"], case["w"])
+        np.testing.assert_array_equal(wo2.cpu().numpy(), ro2)
+        np.testing.assert_array_equal(wt2.cpu().numpy()[:len(rt2)], rt2)
+
 
 def test_graph_replay_equals_eager_in_the_benchmark_launch_configuration():
     """bench.py times hipGraph replays of the whole 3-stage schedule at N=2880.  Replays must reproduce the eager
