@@ -193,9 +193,11 @@ lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, co
                               int32_t *cu_vis_out, void *ws, size_t ws_bytes, void *stream);
 
 /*
- * lightkv_score followed by lightkv_select in one call: same arguments, same outputs.  When every window holds at
- * most 64 tokens, the row arg-min and the per-window selection run in one kernel (one launch less); otherwise the
- * call is the two calls in sequence.  X must not be NULL; xi_mode GIVEN skips the xi half as in lightkv_score.
+ * lightkv_score followed by lightkv_select in one call: same arguments, same outputs (bit for bit).  When every
+ * window holds at most 64 tokens, the row arg-min and the per-window selection run in one kernel (one launch less);
+ * if in addition xi is computed and the step has at most LIGHTKV_ONE_STREAM_MAX_TOKENS tokens, the xi passes share the
+ * launches of the FD kernels and the whole call is three launches on `stream` (no helper stream).  Otherwise the call
+ * is the two calls in sequence.  X must not be NULL; xi_mode GIVEN skips the xi half as in lightkv_score.
  */
 lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int64_t ldx,
                                     const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
