@@ -51,7 +51,9 @@ struct FdBigPlan {
   size_t norm_floats, key_bytes;
   int metric;        // as in FdPlan
 };
-constexpr int FD_BIG_MIN_WINDOW = 256;   // windows bounded by fewer tokens use the small-tile path
+constexpr int FD_BIG_MIN_WINDOW = 256;        // windows bounded by fewer tokens use the small-tile path ...
+constexpr int FD_BIG_MIN_WINDOW_MANY = 128;   // ... unless they are at least this large and make up at least
+constexpr int FD_BIG_MANY_TILES = 32;         //     this many workgroup tiles
 FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n);
 hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
                          const int32_t *win_offsets, const int32_t *win_tokens, double *rnorm,
@@ -87,6 +89,12 @@ hipError_t launch_xi(const XiPlan &plan, int dtype, int xi_mode, int batch, int 
                      int sum_t, const int32_t *cu_vis, const int32_t *cu_txt, const void *Q, int64_t q_tok_stride,
                      int64_t q_head_stride, const void *K, int64_t k_tok_stride, int64_t k_head_stride,
                      const float *lse, float scale, float *stats, float *xi_part, float *xi, hipStream_t stream);
+
+// Batches: one workgroup per (sequence, head) pair, both softmax sweeps in one launch (lk_xi_seq.hip).  Applies to
+// text-query mode without a given lse, prompts of at most 256 tokens and at least XI_SEQ_MIN_PAIRS pairs.
+constexpr int XI_SEQ_MIN_PAIRS = 256;
+bool xi_seq_applies(const XiPlan &plan, int xi_mode, const float *lse, int batch, int heads);
+hipError_t launch_xi_seq(const XiArgs &g, int dtype, int head_dim, hipStream_t stream);
 
 // ---- selection (Step 2) ----------------------------------------------------------------------
 hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int sum_n, const int32_t *cu_vis,

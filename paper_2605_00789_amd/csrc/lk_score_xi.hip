@@ -81,6 +81,12 @@ hipError_t launch_xi(const XiPlan &plan, int dtype, int xi_mode, int batch, int 
   const XiArgs g = make_xi_args(plan, xi_mode, batch, heads, sum_n, sum_t, cu_vis, cu_txt, Q, q_tok_stride, q_head_stride, K,
                                 k_tok_stride, k_head_stride, lse, scale, stats, xi_part, xi);
   const int max_t = plan.max_text_tiles * 32;
+  if (xi_seq_applies(plan, xi_mode, lse, batch, heads)) {
+    const hipError_t e = launch_xi_seq(g, dtype, head_dim, stream);
+    if (e != hipSuccess) return e;
+    if (g.sum_n) hipLaunchKernelGGL(xi_heads_kernel, dim3((unsigned)((g.sum_n + 63) / 64)), dim3(64), 0, stream, g);
+    return hipGetLastError();
+  }
 #define LK_XI_CASE(TT, DHV) return launch_xi_t<TT, DHV>(plan, g, xi_mode, max_t, stream)
   if (dtype == 1) {
     if (head_dim == 128) LK_XI_CASE(bf16_t, 128);

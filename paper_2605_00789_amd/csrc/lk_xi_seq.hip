@@ -1,0 +1,233 @@
+// Prompt-guidance weight xi (paper Sec. 3.2.1 Step 3, Eq. "attention-factor"), text-query mode without a given lse,
+// for batches: one workgroup owns one (sequence, head) pair and never leaves it, so the softmax statistics of the prompt
+// rows stay in registers and nothing but the per-head result is written.
+//
+//   wave w keeps prompt rows 32w .. 32w+31 of the head in registers (prompts of at most 256 tokens);
+//   the vision keys stream through LDS in blocks of 32 (coalesced 16-byte loads, requested XS_PF blocks ahead, three
+//   LDS slots, one barrier per block; the MFMAs of the next block are issued before the exponentials of this one), twice:
+//     sweep 1  keys are the MFMA row operand: every lane follows one prompt row and keeps a running (max, sum of
+//              exponentials) over the keys it sees (its half of every block); the two halves merge once at the end;
+//     sweep 2  prompt rows are the MFMA row operand: exp2(logit * scale - max - log2 sum) summed over the wave's 32
+//              prompt rows inside the lanes, then over the waves in wave order through LDS, gives xi of the block's
+//              32 keys for this head.
+// The heads are summed by xi_heads_kernel afterwards, as in the two-pass path.
+#include "lk_xi_body.h"
+
+namespace lk {
+
+constexpr int XS_WAVES = 8;
+constexpr int XS_THREADS = XS_WAVES * 64;
+constexpr int XS_PF = 2;   // key blocks in flight between the request and the LDS slots (two more are staged there)
+
+template <typename T, int DH> struct XsShape {
+  using S = XiStage<T, DH, 64>;
+  static constexpr int CHUNKS = 32 * S::CPR;                                   // 16-byte chunks of a key block
+  static constexpr int PASSES = (CHUNKS + XS_THREADS - 1) / XS_THREADS;        // chunks per thread
+  static constexpr int BLOCK_BYTES = 32 * S::PITCH;
+  // two workgroups per CU (128 registers per lane) except for 512-byte head rows, whose operands alone take that many
+  static constexpr int WAVES_PER_SIMD = S::ROW_BYTES >= 512 ? 2 : 4;
+  static constexpr int LDS = 3 * BLOCK_BYTES + 2 * XS_WAVES * 32 * 4 + XS_WAVES * 32 * 4;
+};
+
+template <typename T, int DH>
+__global__ __launch_bounds__(XS_THREADS, (XsShape<T, DH>::WAVES_PER_SIMD)) void xi_seq_kernel(XiArgs g) {
+  using E = Elem<T>;
+  using S = XiStage<T, DH, 64>;
+  using X = XsShape<T, DH>;
+  constexpr int NCH = XiShape<T, DH>::NCH;
+  __shared__ __attribute__((aligned(16))) char lds[X::LDS];
+  char *kslot = lds;                                                                         // [3][32 * PITCH]
+  float (*colpart)[XS_WAVES][32] = reinterpret_cast<float (*)[XS_WAVES][32]>(lds + 3 * X::BLOCK_BYTES);   // [2]
+  float (*rowbias)[32] = reinterpret_cast<float (*)[32]>(lds + 3 * X::BLOCK_BYTES + 2 * XS_WAVES * 32 * 4);   // [waves]
+
+  const int h = blockIdx.x % g.heads, b = blockIdx.x / g.heads;
+  const int t0 = g.cu_txt[b], nT = g.cu_txt[b + 1] - t0;
+  const int v0 = g.cu_vis[b], nV = g.cu_vis[b + 1] - v0;
+  if (nV <= 0) return;
+  float *out = g.xi_part + (int64_t)h * g.sum_n + v0;
+  if (nT <= 0) {   // no prompt tokens: xi is zero before the floor
+    for (int i = threadIdx.x; i < nV; i += XS_THREADS) out[i] = 0.f;
+    return;
+  }
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 31, half = lane >> 5;
+  const float NEG_INF = __uint_as_float(0xff800000u);
+  const int64_t vis_ho = (int64_t)h * g.vis_hs, txt_ho = (int64_t)h * g.txt_hs;
+  const int nblk = (nV + 31) >> 5;
+  const int total = 2 * nblk;                      // both sweeps as one sequence of block visits
+  const int n_active = (nT + 31) >> 5;             // waves that own prompt rows
+  const bool active = wave < n_active;
+  const float c2 = g.scale_log2;
+  const bool neg_scale = c2 < 0.f;
+  const float pad = neg_scale ? __uint_as_float(0x7f800000u) : NEG_INF;   // product whose logit is -inf
+
+  // this wave's prompt rows (rows past nT repeat the last one; they are given weight zero in sweep 2)
+  uint4 q[NCH];
+  if (active) load_half_row<T, DH>(g.txt, t0, wave * 32 + r, nT, g.txt_ts, txt_ho, half, q);
+
+  // key block `v` (a visit index; the second sweep repeats the first) -> registers, one 16-byte chunk per pass
+  auto request = [&](int v, uint4 *dst) {
+    v = v < total ? v : total - 1;
+    const int blk = v < nblk ? v : v - nblk;
+#pragma unroll
+    for (int p = 0; p < X::PASSES; ++p) {
+      int idx = p * XS_THREADS + threadIdx.x;
+      idx = idx < X::CHUNKS ? idx : X::CHUNKS - 1;
+      const int row = idx / S::CPR, ch = idx % S::CPR;
+      const int key = blk * 32 + row;
+      const int tok = v0 + (key < nV ? key : nV - 1);
+      dst[p] = ld16(static_cast<const char *>(g.vis) + ((int64_t)tok * g.vis_ts + vis_ho) * E::BYTES + ch * 16);
+    }
+  };
+  auto stage = [&](int slot, const uint4 *src) {
+#pragma unroll
+    for (int p = 0; p < X::PASSES; ++p) {
+      const int idx = p * XS_THREADS + threadIdx.x;
+      if (idx < X::CHUNKS) {
+        const int row = idx / S::CPR, ch = idx % S::CPR;
+        *reinterpret_cast<uint4 *>(kslot + slot * X::BLOCK_BYTES + row * S::PITCH + ch * 16) = src[p];
+      }
+    }
+  };
+
+  // visit v: block v + 2 is staged into the third LDS slot, the MFMAs of block v + 1 are issued, and the exponentials
+  // of block v (products already in `cur`) run in their shadow
+  uint4 ring[XS_PF][X::PASSES];
+  {
+    uint4 f0[X::PASSES], f1[X::PASSES];
+    request(0, f0);
+    request(1, f1);
+#pragma unroll
+    for (int u = 2; u < 2 + XS_PF; ++u) request(u, ring[u % XS_PF]);
+    stage(0, f0);
+    stage(1, f1);
+  }
+  __syncthreads();
+
+  // products of the wave's prompt rows with key block `v` (in LDS slot v % 3): keys as rows in sweep 1, as columns in 2
+  auto products = [&](int v, f32x16 &acc) {
+    uint4 k[NCH];
+    read_prompt_frag<T, DH>(kslot + (v % 3) * X::BLOCK_BYTES, r, half, k);
+#pragma unroll
+    for (int x = 0; x < 16; ++x) acc[x] = 0.f;
+    if (v < nblk) {
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) E::mma32(k[c], q[c], acc);
+    } else {
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) E::mma32(q[c], k[c], acc);
+    }
+  };
+
+  float m = NEG_INF, s = 0.f;   // sweep 1: running statistics of prompt row 32 * wave + r over this lane's key rows
+  f32x16 cur, nxt;
+  if (active) products(0, cur);
+
+  for (int vbase = 0; vbase < total; vbase += XS_PF) {
+#pragma unroll
+    for (int u = 0; u < XS_PF; ++u) {
+      const int v = vbase + u;
+      if (v >= total) break;   // uniform
+      // block v + 2 goes to the slot whose last readers (the products of block v - 1) passed the barrier that ended
+      // visit v - 2; its registers then take the request for block v + 2 + XS_PF
+      stage((v + 2) % 3, ring[(u + 2) % XS_PF]);
+      request(v + 2 + XS_PF, ring[(u + 2) % XS_PF]);
+
+      if (v == nblk) {
+        // between the sweeps: merge the two halves of every prompt row, lower half first in both lanes so that they
+        // hold the same bits; sweep 2 reads the rows' biases in accumulator order
+        if (active) {
+          const float om = __shfl_xor(m, 32, 64), os = __shfl_xor(s, 32, 64);
+          const float mm = fmaxf(m, om);
+          const float lo_m = half ? om : m, lo_s = half ? os : s, hi_m = half ? m : om, hi_s = half ? s : os;
+          const float ss = lo_s * exp2f(lo_m - mm) + hi_s * exp2f(hi_m - mm);
+          const bool row_live = wave * 32 + r < nT;
+          if (half == 0) rowbias[wave][r] = row_live ? -(mm + log2f(ss)) : NEG_INF;
+        }
+        __syncthreads();
+      }
+      if (v > nblk && wave == XS_WAVES - 1 && lane < 32) {
+        // xi of the block visited before this one: the waves' partial sums in wave order
+        const int pb = v - 1 - nblk;
+        float sum = 0.f;
+        for (int w = 0; w < n_active; ++w) sum += colpart[(v - 1) & 1][w][lane];
+        if (pb * 32 + lane < nV) out[pb * 32 + lane] = sum;
+      }
+
+      if (active) {
+        if (v + 1 < total) products(v + 1, nxt);
+        if (v < nblk) {
+          if (v * 32 + 32 > nV) {   // uniform: only the last block of the sequence has rows to mask
+#pragma unroll
+            for (int x = 0; x < 16; ++x) cur[x] = (v * 32 + acc_row(x, lane) < nV) ? cur[x] : pad;
+          }
+          // the extreme is taken on the raw products (maximum for a positive scale, minimum for a negative one), the
+          // scale goes into the exponent's multiply-add
+          float e = cur[0];
+          if (neg_scale) {
+#pragma unroll
+            for (int x = 1; x < 16; ++x) e = fminf(e, cur[x]);
+          } else {
+#pragma unroll
+            for (int x = 1; x < 16; ++x) e = fmaxf(e, cur[x]);
+          }
+          const float mn = fmaxf(m, e * c2);
+          float add = 0.f;
+#pragma unroll
+          for (int x = 0; x < 16; ++x) add += fast_exp2(fmaf(cur[x], c2, -mn));   // masked rows: exp2(-inf) = 0
+          s = (mn > NEG_INF) ? fmaf(s, fast_exp2(m - mn), add) : 0.f;              // nothing but masked rows so far
+          m = mn;
+        } else {
+          // -(max + log2 sum) of the prompt row behind every accumulator register; rows past nT: -inf, weight zero
+          float bias[16];
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) {
+            const f32x4 b4 = *reinterpret_cast<const f32x4 *>(&rowbias[wave][8 * gq + 4 * half]);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) bias[4 * gq + x] = b4[x];
+          }
+          float cs = 0.f;
+#pragma unroll
+          for (int x = 0; x < 16; ++x) cs += fast_exp2(fmaf(cur[x], c2, bias[x]));
+          cs += __shfl_xor(cs, 32, 64);
+          if (half == 0) colpart[v & 1][wave][r] = cs;
+        }
+        cur = nxt;
+      }
+      lds_barrier();
+    }
+  }
+  if (wave == XS_WAVES - 1 && lane < 32) {
+    const int pb = nblk - 1;
+    float sum = 0.f;
+    for (int w = 0; w < n_active; ++w) sum += colpart[(total - 1) & 1][w][lane];
+    if (pb * 32 + lane < nV) out[pb * 32 + lane] = sum;
+  }
+}
+
+bool xi_seq_applies(const XiPlan &plan, int xi_mode, const float *lse, int batch, int heads) {
+  return xi_mode == 0 && lse == nullptr && plan.max_text_tiles > 0 && plan.max_text_tiles * 32 <= XS_WAVES * 32 &&
+         batch * heads >= XI_SEQ_MIN_PAIRS;
+}
+
+template <typename T, int DH>
+static hipError_t launch_xi_seq_t(const XiArgs &g, hipStream_t stream) {
+  hipLaunchKernelGGL((xi_seq_kernel<T, DH>), dim3((unsigned)(g.batch * g.heads)), dim3(XS_THREADS), 0, stream, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_xi_seq(const XiArgs &g, int dtype, int head_dim, hipStream_t stream) {
+  if (g.batch * g.heads <= 0) return hipSuccess;
+  if (dtype == 1) {
+    if (head_dim == 128) return launch_xi_seq_t<bf16_t, 128>(g, stream);
+    if (head_dim == 64) return launch_xi_seq_t<bf16_t, 64>(g, stream);
+    if (head_dim == 32) return launch_xi_seq_t<bf16_t, 32>(g, stream);
+  } else {
+    if (head_dim == 128) return launch_xi_seq_t<float, 128>(g, stream);
+    if (head_dim == 64) return launch_xi_seq_t<float, 64>(g, stream);
+    if (head_dim == 32) return launch_xi_seq_t<float, 32>(g, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace lk

@@ -241,6 +241,59 @@ def test_xi_variants_given_lse_vision_query_scale_and_head_major_layout():
         assert torch.equal(xi_tok, xi2)
 
 
+def test_xi_of_batches_one_workgroup_per_sequence_and_head():
+    """Batches with at least 256 (sequence, head) pairs and prompts of at most 256 tokens take the single-launch xi
+    kernel: ragged prompt and vision lengths (1 token, multiples of 32 +- 1, a sequence without a prompt, one without
+    vision tokens), both dtypes, every head size, a negative softmax scale."""
+    from oracle import lightkv_oracle as O
+    from parity import to_dev
+    from workloads import f32_to_bf16_bits
+    import paper_2605_00789_amd as L
+    from paper_2605_00789_amd import binding as B
+    rng = np.random.default_rng(2718)
+    cases = (("bf16", 32, 128, (576, 1, 31, 33, 100, 0, 45, 257), (144, 1, 32, 33, 256, 64, 0, 97), None),
+             ("bf16", 64, 64, (40, 96, 7, 130), (5, 64, 200, 31), -0.2),
+             ("f32", 128, 32, (65, 3), (33, 250), None),
+             ("f32", 32, 128, (50, 64, 1, 20, 90, 33, 12, 128), (17, 256, 3, 40, 1, 96, 129, 64), 0.3),
+             ("bf16", 256, 32, (20,), (11,), None))
+    for dtype, H, dh, n_vis, n_txt, scale in cases:
+        assert len(n_vis) * H >= 256
+        d = H * dh
+        cu_vis = np.concatenate([[0], np.cumsum(n_vis)]).astype(np.int32)
+        cu_txt = np.concatenate([[0], np.cumsum(n_txt)]).astype(np.int32)
+        Kf = rng.standard_normal((int(cu_vis[-1]), d)).astype(np.float32) * 1.5
+        Qf = rng.standard_normal((int(cu_txt[-1]), d)).astype(np.float32) * 1.5
+        Ks, Qs = (f32_to_bf16_bits(Kf), f32_to_bf16_bits(Qf)) if dtype == "bf16" else (Kf, Qf)
+        want = O.xi_text_query(O.widen(Qs, dtype), O.widen(Ks, dtype), cu_vis, cu_txt, H, dh, scale=scale)
+        dcu_vis, dcu_txt = torch.from_numpy(cu_vis).cuda(), torch.from_numpy(cu_txt).cuda()
+        win = torch.zeros(1, dtype=torch.int32, device="cuda")   # no windows: only the xi half is requested
+        prob = B.Problem(batch=len(n_vis), d=d, heads=H, head_dim=dh, dtype=dtype, h_cu_vis=cu_vis, cu_vis=dcu_vis,
+                         h_cu_txt=cu_txt, cu_txt=dcu_txt, n_windows=0, max_window_tokens=16, win_offsets=win,
+                         win_tokens=win)
+        ws = torch.empty(max(B.lightkv_workspace_size(prob), 16), dtype=torch.uint8, device="cuda")
+        xi = torch.full((int(cu_vis[-1]),), -1.0, dtype=torch.float32, device="cuda")
+        print("[xi batch] %s heads %d x %d, %d sequences" % (dtype, H, dh, len(n_vis)), flush=True)
+        B.lightkv_score(prob, None, to_dev(Qs, dtype), to_dev(Ks, dtype), xi, None, None, ws,
+                        softmax_scale=0.0 if scale is None else scale)
+        torch.cuda.synchronize()
+        got = xi.cpu().numpy().astype(np.float64)
+        tol = 1e-3 if dtype == "bf16" else 1e-5
+        rel = np.abs(got - want) / np.maximum(np.abs(want), 1e-30)
+        # contributions far below the sequence's largest weight carry the rounding of the exponent's argument
+        floor = np.zeros_like(want)
+        for b in range(len(n_vis)):
+            if n_vis[b]:
+                floor[cu_vis[b]:cu_vis[b + 1]] = want[cu_vis[b]:cu_vis[b + 1]].max() * 1e-6
+        bad = (rel > tol) & (np.abs(got - want) > tol * floor)
+        assert not bad.any(), (dtype, H, dh, int(bad.sum()), float(rel.max()))
+        # every prompt row spreads a mass of one over its sequence's keys, in every head
+        for b in range(len(n_vis)):
+            if n_vis[b] and n_txt[b]:
+                assert abs(got[cu_vis[b]:cu_vis[b + 1]].sum() - H * n_txt[b]) <= 1e-4 * H * n_txt[b]
+            elif n_vis[b]:
+                assert np.all(got[cu_vis[b]:cu_vis[b + 1]] == np.float32(1e-30))
+
+
 def test_strided_rows_and_error_paths_on_device():
     """Row strides larger than d (a view into a wider cache), and errors that need real device pointers."""
     from workloads import make_custom
