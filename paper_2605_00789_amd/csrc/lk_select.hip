@@ -6,8 +6,9 @@
 // sort of (destination, source) pairs yields each source's rank inside its group, which makes the
 // inverse map (grp_offsets / grp_src) deterministic without atomics on the output.
 //
-//   select_window_kernel : per window -> dst[], per-token source counts, per-source ranks (up to 256 A nodes)
-//   select_rank_kernel   : the same results for larger windows, by counting smaller keys
+//   select_window_kernel : per window -> dst[], per-token source counts, per-source ranks (up to 256 A nodes), by
+//                          counting smaller keys inside one workgroup
+//   select_rank_kernel   : the same results for larger windows, the counting spread over several workgroups
 //   select_scan_kernel   : one workgroup -> exclusive scans (new_index, grp_offsets), cu_vis_out, grp_src
 #include "lk_xi_body.h"
 
@@ -23,90 +24,84 @@ struct SelArgs {
 };
 
 
-template <int THREADS>
-__global__ __launch_bounds__(THREADS) void select_window_kernel(SelArgs g) {
-  extern __shared__ uint64_t keys[];          // cap entries
-  int *start = reinterpret_cast<int *>(keys + g.cap);   // cap entries: scan buffer
+// Windows of up to COUNT_MAX_A A nodes: one workgroup per window, thread t owns A position t and B position t.  The rank
+// of an A node among the keys of its window is the number of smaller keys (earlier position first among equal keys);
+// a merged node's rank inside its group is the number of earlier merged nodes with the same target, and a B node's
+// source count the number of merged nodes that name it.  Three short counting loops over LDS and two barriers: no sort,
+// and every token of the window is written exactly once.
+constexpr int COUNT_MAX_A = 256;
+
+__global__ __launch_bounds__(COUNT_MAX_A) void select_window_kernel(SelArgs g) {
+  // order-preserving FD bits of every A node, then the target of every merged A node; all-ones beyond |A| (never
+  // smaller than a key, never a valid target), padded to whole groups of four
+  __shared__ __attribute__((aligned(16))) uint32_t key[COUNT_MAX_A + 4];
+  __shared__ __attribute__((aligned(16))) uint32_t tgt[COUNT_MAX_A + 4];
   const int w = blockIdx.x;
   const int off = g.win_offsets[w];
   const int v = g.win_offsets[w + 1] - off;
   int nA = (v + 1) >> 1;
   const int nB = v >> 1;
-  if (nA > g.cap) nA = g.cap;                 // window larger than the caller's bound: surplus rows stay
+  const int cap = g.cap < COUNT_MAX_A ? g.cap : COUNT_MAX_A;
+  if (nA > cap) nA = cap;                     // window larger than the caller's bound: surplus rows stay
   int r = g.win_remove[w];
   r = r < 0 ? 0 : (r > nA ? nA : r);
   if (nB == 0) r = 0;
-
-  // every token of the window starts as "stays, no sources"
-  for (int t = threadIdx.x; t < v; t += THREADS) {
+  const int la = threadIdx.x;
+  for (int t = 2 * nA + la; t < v; t += COUNT_MAX_A) {
     const int tok = g.win_tokens[off + t];
-    if ((unsigned)tok < (unsigned)g.sum_n) {
-      g.dst[tok] = -1;
-      g.cnt[tok] = 0;
-      g.src_rank[tok] = 0;
-    }
+    if ((unsigned)tok < (unsigned)g.sum_n) { g.dst[tok] = -1; g.cnt[tok] = 0; g.src_rank[tok] = 0; }
   }
-  if (r == 0) return;
-
-  const int p2 = next_pow2(nA);
-  for (int la = threadIdx.x; la < p2; la += THREADS) {
-    uint64_t key = ~0ull;
-    if (la < nA) {
-      const int tok = g.win_tokens[off + 2 * la];
-      float fd = __uint_as_float(0x7f800000u);
-      if ((unsigned)tok < (unsigned)g.sum_n) fd = g.best_fd[tok];
-      if (!(fd >= 0.f)) fd = __uint_as_float(0x7f800000u);   // NaN or negative never wins
-      key = ((uint64_t)f32_order_key(fd) << 32) | (uint32_t)la;
-    }
-    keys[la] = key;
-  }
-  bitonic_sort_lds(keys, p2);
-
-  // the first r keys are the merged A nodes; rebuild keys as (destination token, source token)
-  uint64_t pair[(2048 + THREADS - 1) / THREADS];
-  int np = 0;
-  for (int k = threadIdx.x; k < p2; k += THREADS, ++np) {
-    uint64_t pk = ~0ull;
-    if (k < r) {
-      const int la = (int)(keys[k] & 0xffffffffu);
-      const int a_tok = g.win_tokens[off + 2 * la];
-      int b_tok = -1;
-      if ((unsigned)a_tok < (unsigned)g.sum_n) b_tok = g.best_dst[a_tok];
-      if ((unsigned)b_tok >= (unsigned)g.sum_n) b_tok = g.win_tokens[off + 1];   // no usable proposal: first B node
-      if ((unsigned)b_tok < (unsigned)g.sum_n && (unsigned)a_tok < (unsigned)g.sum_n)
-        pk = ((uint64_t)(uint32_t)b_tok << 32) | (uint32_t)a_tok;
-    }
-    pair[np] = pk;
-  }
+  const bool has_a = la < nA, has_b = la < nB && 2 * la + 1 < 2 * nA;
+  int a_tok = g.win_tokens[off + 2 * (has_a ? la : 0)];
+  int b_tok = g.win_tokens[off + (has_b ? 2 * la + 1 : 0)];
+  const int first_b = g.win_tokens[off + (nB > 0 ? 1 : 0)];
+  if (!has_a || (unsigned)a_tok >= (unsigned)g.sum_n) a_tok = -1;
+  if (!has_b || (unsigned)b_tok >= (unsigned)g.sum_n) b_tok = -1;
+  float fd = g.best_fd[a_tok >= 0 ? a_tok : 0];
+  int prop = g.best_dst[a_tok >= 0 ? a_tok : 0];   // the proposal of this A node, or the first B node of the window
+  if (a_tok < 0 || !(fd >= 0.f)) fd = __uint_as_float(0x7f800000u);   // NaN or negative never wins
+  if (a_tok < 0) prop = -1;
+  else if ((unsigned)prop >= (unsigned)g.sum_n) prop = (nB > 0 && (unsigned)first_b < (unsigned)g.sum_n) ? first_b : -1;
+  const int n4 = (nA + 3) & ~3;
+  const uint32_t mine = has_a ? f32_order_key(fd) : 0xffffffffu;
+  if (la < n4) key[la] = mine;
   __syncthreads();
-  np = 0;
-  for (int k = threadIdx.x; k < p2; k += THREADS, ++np) keys[k] = pair[np];
-  const int p2r = next_pow2(r);
-  bitonic_sort_lds(keys, p2r <= p2 ? p2r : p2);   // entries >= r are all ~0 and already in place
-
-  // group starts: inclusive max-scan of (k where the destination changes)
-  for (int k = threadIdx.x; k < p2r; k += THREADS) {
-    const bool head = (k == 0) || ((keys[k] >> 32) != (keys[k - 1] >> 32));
-    start[k] = head ? k : 0;
+  int c0 = 0;
+#pragma unroll 4
+  for (int o = 0; o < n4; o += 4) {
+    const uint4 k = *reinterpret_cast<const uint4 *>(&key[o]);
+    c0 += (k.x < mine || (k.x == mine && o < la)) ? 1 : 0;
+    c0 += (k.y < mine || (k.y == mine && o + 1 < la)) ? 1 : 0;
+    c0 += (k.z < mine || (k.z == mine && o + 2 < la)) ? 1 : 0;
+    c0 += (k.w < mine || (k.w == mine && o + 3 < la)) ? 1 : 0;
   }
+  const bool merged = has_a && c0 < r && prop >= 0;   // a selected node without a usable target stays
+  const uint32_t mine_t = merged ? (uint32_t)prop : 0xffffffffu;
+  if (la < n4) tgt[la] = mine_t;
   __syncthreads();
-  for (int step = 1; step < p2r; step <<= 1) {
-    int val[(2048 + THREADS - 1) / THREADS];
-    int n = 0;
-    for (int k = threadIdx.x; k < p2r; k += THREADS, ++n) val[n] = (k >= step) ? max(start[k], start[k - step]) : start[k];
-    __syncthreads();
-    n = 0;
-    for (int k = threadIdx.x; k < p2r; k += THREADS, ++n) start[k] = val[n];
-    __syncthreads();
+  const uint32_t self = (uint32_t)b_tok;
+  int c1 = 0, c2 = 0;
+#pragma unroll 4
+  for (int o = 0; o < n4; o += 4) {
+    const uint4 d = *reinterpret_cast<const uint4 *>(&tgt[o]);
+    c1 += (d.x == mine_t && o < la) ? 1 : 0;
+    c1 += (d.y == mine_t && o + 1 < la) ? 1 : 0;
+    c1 += (d.z == mine_t && o + 2 < la) ? 1 : 0;
+    c1 += (d.w == mine_t && o + 3 < la) ? 1 : 0;
+    c2 += (d.x == self) ? 1 : 0;
+    c2 += (d.y == self) ? 1 : 0;
+    c2 += (d.z == self) ? 1 : 0;
+    c2 += (d.w == self) ? 1 : 0;
   }
-  for (int k = threadIdx.x; k < r; k += THREADS) {
-    const uint64_t pk = keys[k];
-    if (pk == ~0ull) continue;               // an A node without a valid proposal stays
-    const int b_tok = (int)(pk >> 32), a_tok = (int)(pk & 0xffffffffu);
-    g.dst[a_tok] = b_tok;
-    g.src_rank[a_tok] = k - start[k];
-    const bool last = (k == r - 1) || ((keys[k + 1] >> 32) != (pk >> 32));
-    if (last) g.cnt[b_tok] = k - start[k] + 1;
+  if (a_tok >= 0) {
+    g.dst[a_tok] = merged ? prop : -1;
+    g.src_rank[a_tok] = merged ? c1 : 0;
+    g.cnt[a_tok] = 0;
+  }
+  if (b_tok >= 0) {
+    g.dst[b_tok] = -1;
+    g.src_rank[b_tok] = 0;
+    g.cnt[b_tok] = c2;
   }
 }
 
@@ -394,12 +389,11 @@ hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int su
   g.dst = dst; g.new_index = new_index; g.grp_offsets = grp_offsets; g.grp_src = grp_src;
   g.cu_vis_out = cu_vis_out; g.cnt = cnt; g.src_rank = src_rank;
   const int maxA = (max_window_tokens + 1) / 2;
-  g.cap = next_pow2(maxA > 1 ? maxA : 1);
-  const size_t lds = (size_t)g.cap * (sizeof(uint64_t) + sizeof(int));
+  g.cap = maxA > 1 ? maxA : 1;
   if (n_windows > 0) {
     hipError_t e;
-    if (g.cap <= 256) {
-      hipLaunchKernelGGL(select_window_kernel<256>, dim3(n_windows), dim3(256), lds, stream, g);
+    if (g.cap <= COUNT_MAX_A) {
+      hipLaunchKernelGGL(select_window_kernel, dim3(n_windows), dim3(COUNT_MAX_A), 0, stream, g);
       e = hipGetLastError();
     } else {
       // counting selection; a window beyond the library's limit keeps its surplus A nodes, as everywhere else
