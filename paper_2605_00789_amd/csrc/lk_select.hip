@@ -24,18 +24,21 @@ struct SelArgs {
 };
 
 
-// Windows of up to COUNT_MAX_A A nodes: one workgroup per window, thread t owns A position t and B position t.  The rank
-// of an A node among the keys of its window is the number of smaller keys (earlier position first among equal keys);
-// a merged node's rank inside its group is the number of earlier merged nodes with the same target, and a B node's
-// source count the number of merged nodes that name it.  Three short counting loops over LDS and two barriers: no sort,
-// and every token of the window is written exactly once.
+// Windows of up to COUNT_MAX_A A nodes: one workgroup per window.  The rank of an A node among the keys of its window
+// is the number of smaller keys (earlier position first among equal keys); a merged node's rank inside its group is
+// the number of earlier merged nodes with the same target, and a B node's source count the number of merged nodes
+// that name it.  Three short counting loops over LDS: no sort, and every token of the window is written exactly once.
+// SEGS threads share a position (A node t and B node t) and split the window's list between them: the loops are
+// chains of dependent LDS reads and compares, so longer lists want more waves rather than longer loops.
 constexpr int COUNT_MAX_A = 256;
 
-__global__ __launch_bounds__(COUNT_MAX_A) void select_window_kernel(SelArgs g) {
+template <int SEGS>
+__global__ __launch_bounds__(COUNT_MAX_A * SEGS) void select_window_kernel(SelArgs g) {
   // order-preserving FD bits of every A node, then the target of every merged A node; all-ones beyond |A| (never
   // smaller than a key, never a valid target), padded to whole groups of four
   __shared__ __attribute__((aligned(16))) uint32_t key[COUNT_MAX_A + 4];
   __shared__ __attribute__((aligned(16))) uint32_t tgt[COUNT_MAX_A + 4];
+  __shared__ int part[3][SEGS][COUNT_MAX_A];
   const int w = blockIdx.x;
   const int off = g.win_offsets[w];
   const int v = g.win_offsets[w + 1] - off;
@@ -46,8 +49,8 @@ __global__ __launch_bounds__(COUNT_MAX_A) void select_window_kernel(SelArgs g) {
   int r = g.win_remove[w];
   r = r < 0 ? 0 : (r > nA ? nA : r);
   if (nB == 0) r = 0;
-  const int la = threadIdx.x;
-  for (int t = 2 * nA + la; t < v; t += COUNT_MAX_A) {
+  const int la = threadIdx.x % COUNT_MAX_A, seg = threadIdx.x / COUNT_MAX_A;
+  for (int t = 2 * nA + (int)threadIdx.x; t < v; t += COUNT_MAX_A * SEGS) {
     const int tok = g.win_tokens[off + t];
     if ((unsigned)tok < (unsigned)g.sum_n) { g.dst[tok] = -1; g.cnt[tok] = 0; g.src_rank[tok] = 0; }
   }
@@ -63,26 +66,35 @@ __global__ __launch_bounds__(COUNT_MAX_A) void select_window_kernel(SelArgs g) {
   if (a_tok < 0) prop = -1;
   else if ((unsigned)prop >= (unsigned)g.sum_n) prop = (nB > 0 && (unsigned)first_b < (unsigned)g.sum_n) ? first_b : -1;
   const int n4 = (nA + 3) & ~3;
+  const int seg_len = ((n4 / 4 + SEGS - 1) / SEGS) * 4;   // entries per segment, a multiple of 4
+  const int o_begin = seg * seg_len, o_end = min(n4, o_begin + seg_len);
   const uint32_t mine = has_a ? f32_order_key(fd) : 0xffffffffu;
-  if (la < n4) key[la] = mine;
+  if (seg == 0 && la < n4) key[la] = mine;
   __syncthreads();
   int c0 = 0;
 #pragma unroll 4
-  for (int o = 0; o < n4; o += 4) {
+  for (int o = o_begin; o < o_end; o += 4) {
     const uint4 k = *reinterpret_cast<const uint4 *>(&key[o]);
     c0 += (k.x < mine || (k.x == mine && o < la)) ? 1 : 0;
     c0 += (k.y < mine || (k.y == mine && o + 1 < la)) ? 1 : 0;
     c0 += (k.z < mine || (k.z == mine && o + 2 < la)) ? 1 : 0;
     c0 += (k.w < mine || (k.w == mine && o + 3 < la)) ? 1 : 0;
   }
+  if (SEGS > 1) {
+    part[0][seg][la] = c0;
+    __syncthreads();
+    c0 = 0;
+#pragma unroll
+    for (int q = 0; q < SEGS; ++q) c0 += part[0][q][la];
+  }
   const bool merged = has_a && c0 < r && prop >= 0;   // a selected node without a usable target stays
   const uint32_t mine_t = merged ? (uint32_t)prop : 0xffffffffu;
-  if (la < n4) tgt[la] = mine_t;
+  if (seg == 0 && la < n4) tgt[la] = mine_t;
   __syncthreads();
   const uint32_t self = (uint32_t)b_tok;
   int c1 = 0, c2 = 0;
 #pragma unroll 4
-  for (int o = 0; o < n4; o += 4) {
+  for (int o = o_begin; o < o_end; o += 4) {
     const uint4 d = *reinterpret_cast<const uint4 *>(&tgt[o]);
     c1 += (d.x == mine_t && o < la) ? 1 : 0;
     c1 += (d.y == mine_t && o + 1 < la) ? 1 : 0;
@@ -93,6 +105,15 @@ __global__ __launch_bounds__(COUNT_MAX_A) void select_window_kernel(SelArgs g) {
     c2 += (d.z == self) ? 1 : 0;
     c2 += (d.w == self) ? 1 : 0;
   }
+  if (SEGS > 1) {
+    part[1][seg][la] = c1;
+    part[2][seg][la] = c2;
+    __syncthreads();
+    c1 = c2 = 0;
+#pragma unroll
+    for (int q = 0; q < SEGS; ++q) { c1 += part[1][q][la]; c2 += part[2][q][la]; }
+  }
+  if (seg != 0) return;
   if (a_tok >= 0) {
     g.dst[a_tok] = merged ? prop : -1;
     g.src_rank[a_tok] = merged ? c1 : 0;
@@ -250,6 +271,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
   const int s_first = g.cu_vis[tid <= g.batch ? tid : g.batch];   // sequence start handled by this thread (first round)
   int per = (g.sum_n + SCAN_THREADS - 1) / SCAN_THREADS;
   per = per < 1 ? 1 : (per > SCAN_ITEMS ? SCAN_ITEMS : per);
+  if (per < SCAN_ITEMS && per > 1 && !(per & 1)) ++per;   // an odd run length: thread t's slots in kb[] start at bank t * per
   const int pass_tokens = per * SCAN_THREADS;
   const bool one_pass = g.sum_n <= pass_tokens;   // then dst / src_rank stay in registers for the inverse map below
   int keep_base = 0, cnt_base = 0;
@@ -393,7 +415,8 @@ hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int su
   if (n_windows > 0) {
     hipError_t e;
     if (g.cap <= COUNT_MAX_A) {
-      hipLaunchKernelGGL(select_window_kernel, dim3(n_windows), dim3(COUNT_MAX_A), 0, stream, g);
+      if (g.cap > 96) hipLaunchKernelGGL(select_window_kernel<4>, dim3(n_windows), dim3(COUNT_MAX_A * 4), 0, stream, g);
+      else hipLaunchKernelGGL(select_window_kernel<1>, dim3(n_windows), dim3(COUNT_MAX_A), 0, stream, g);
       e = hipGetLastError();
     } else {
       // counting selection; a window beyond the library's limit keeps its surplus A nodes, as everywhere else
