@@ -148,6 +148,32 @@ bool row_tensor_ok(const void *p, int64_t ld, int d, int elem_bytes, lightkv_sta
   return true;
 }
 
+// from_keys: the scores are the packed keys the tiled FD kernel left in the workspace (best_fd / best_dst are then
+// outputs, written by the selection kernels); otherwise best_fd / best_dst are the inputs.
+lightkv_status select_impl(const lightkv_problem *p, bool from_keys, float *best_fd, int32_t *best_dst,
+                           int32_t *dst, int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src,
+                           int32_t *cu_vis_out, void *ws, size_t ws_bytes, void *stream) {
+  Checked c;
+  lightkv_status st = check_problem(p, true, false, c);
+  if (st != LIGHTKV_OK) return st;
+  if (!p->win_remove || !best_fd || !best_dst || !dst || !new_index || !grp_offsets || !grp_src || !cu_vis_out)
+    return LIGHTKV_ERR_NULL;
+  const FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
+  const bool have_txt = p->h_cu_txt && p->cu_txt;
+  const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, have_txt ? p->h_cu_txt : nullptr, p->heads, 0);
+  const FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
+  const WsLayout l = ws_layout(fd, big, use_big_fd(p, c), xp, c.sum_n);
+  // only the selection scratch (and the keys) are used here; accept a workspace that covers the layout
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) != 0 || ws_bytes < l.total) return LIGHTKV_ERR_WORKSPACE;
+  char *wsb = static_cast<char *>(ws);
+  const unsigned long long *keys = from_keys ? reinterpret_cast<const unsigned long long *>(wsb + l.fd_keys) : nullptr;
+  if (launch_select(p->n_windows, c.max_window, p->batch, c.sum_n, p->cu_vis, p->win_offsets, p->win_tokens,
+                    p->win_remove, keys, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out,
+                    reinterpret_cast<int32_t *>(wsb + l.sel_cnt), reinterpret_cast<int32_t *>(wsb + l.sel_rank),
+                    static_cast<hipStream_t>(stream)) != hipSuccess)
+    return LIGHTKV_ERR_LAUNCH;
+  return LIGHTKV_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -226,11 +252,13 @@ struct SelectOut {   // outputs of lightkv_select, present when selection is to 
 };
 
 // sel == nullptr: plain lightkv_score.  Otherwise the caller guarantees that make_fd_small_fused_plan applies.
+// keys_only: on the tiled MFMA path, leave the packed keys in the workspace and do not write best_fd / best_dst
+// (the caller's selection reads the keys and writes them).
 lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx,
                           const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
                           const void *K, int64_t k_tok_stride, int64_t k_head_stride,
                           int32_t xi_mode, const float *lse, float softmax_scale,
-                          float *xi, float *best_fd, int32_t *best_dst, const SelectOut *sel,
+                          float *xi, float *best_fd, int32_t *best_dst, const SelectOut *sel, bool keys_only,
                           void *ws, size_t ws_bytes, void *stream) {
   if (xi_mode < LIGHTKV_XI_TEXT_QUERY || xi_mode > LIGHTKV_XI_GIVEN) return LIGHTKV_ERR_UNSUPPORTED;
   const bool need_xi = xi_mode != LIGHTKV_XI_GIVEN;
@@ -324,7 +352,8 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx,
   } else if (use_big) {
     if (launch_fd_big(big, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
                       reinterpret_cast<double *>(wsb + l.fd_norm),
-                      reinterpret_cast<unsigned long long *>(wsb + l.fd_keys), best_fd, best_dst, s) != hipSuccess)
+                      reinterpret_cast<unsigned long long *>(wsb + l.fd_keys), best_fd, best_dst, !keys_only,
+                      s) != hipSuccess)
       fd_status = LIGHTKV_ERR_LAUNCH;
   } else if (launch_fd(fd, p->dtype, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
                        reinterpret_cast<float *>(wsb + l.fd_partial), best_fd, best_dst, s) != hipSuccess) {
@@ -344,7 +373,7 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
                              float *xi, float *best_fd, int32_t *best_dst,
                              void *ws, size_t ws_bytes, void *stream) {
   return score_impl(p, X, ldx, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
-                    softmax_scale, xi, best_fd, best_dst, nullptr, ws, ws_bytes, stream);
+                    softmax_scale, xi, best_fd, best_dst, nullptr, false, ws, ws_bytes, stream);
 }
 
 lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int64_t ldx,
@@ -363,36 +392,23 @@ lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int
   if ((small.n_tiles > 0 && !use_big_fd(p, c)) || p->n_windows == 0) {
     const SelectOut sel{dst, new_index, grp_offsets, grp_src, cu_vis_out};
     return score_impl(p, X, ldx, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
-                      softmax_scale, xi, best_fd, best_dst, &sel, ws, ws_bytes, stream);
+                      softmax_scale, xi, best_fd, best_dst, &sel, false, ws, ws_bytes, stream);
   }
+  // the tiled MFMA path leaves packed keys: the selection reads them directly and writes best_fd / best_dst itself
+  const bool from_keys = use_big_fd(p, c);
   st = score_impl(p, X, ldx, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
-                  softmax_scale, xi, best_fd, best_dst, nullptr, ws, ws_bytes, stream);
+                  softmax_scale, xi, best_fd, best_dst, nullptr, from_keys, ws, ws_bytes, stream);
   if (st != LIGHTKV_OK) return st;
-  return lightkv_select(p, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, ws, ws_bytes, stream);
+  return select_impl(p, from_keys, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, ws, ws_bytes,
+                     stream);
 }
 
 lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, const int32_t *best_dst,
                               int32_t *dst, int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src,
                               int32_t *cu_vis_out, void *ws, size_t ws_bytes, void *stream) {
-  Checked c;
-  lightkv_status st = check_problem(p, true, false, c);
-  if (st != LIGHTKV_OK) return st;
-  if (!p->win_remove || !best_fd || !best_dst || !dst || !new_index || !grp_offsets || !grp_src || !cu_vis_out)
-    return LIGHTKV_ERR_NULL;
-  const FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
-  const bool have_txt = p->h_cu_txt && p->cu_txt;
-  const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, have_txt ? p->h_cu_txt : nullptr, p->heads, 0);
-  const FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
-  const WsLayout l = ws_layout(fd, big, use_big_fd(p, c), xp, c.sum_n);
-  // only the selection scratch is used here; accept a workspace that just covers it as laid out
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) != 0 || ws_bytes < l.total) return LIGHTKV_ERR_WORKSPACE;
-  char *wsb = static_cast<char *>(ws);
-  if (launch_select(p->n_windows, c.max_window, p->batch, c.sum_n, p->cu_vis, p->win_offsets, p->win_tokens,
-                    p->win_remove, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out,
-                    reinterpret_cast<int32_t *>(wsb + l.sel_cnt), reinterpret_cast<int32_t *>(wsb + l.sel_rank),
-                    static_cast<hipStream_t>(stream)) != hipSuccess)
-    return LIGHTKV_ERR_LAUNCH;
-  return LIGHTKV_OK;
+  // without keys, best_fd / best_dst are only read
+  return select_impl(p, false, const_cast<float *>(best_fd), const_cast<int32_t *>(best_dst), dst, new_index,
+                     grp_offsets, grp_src, cu_vis_out, ws, ws_bytes, stream);
 }
 
 static lightkv_status rows_call(int mode, const lightkv_problem *p, const int32_t *new_index,

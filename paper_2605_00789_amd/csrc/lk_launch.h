@@ -57,7 +57,8 @@ constexpr int FD_BIG_MANY_TILES = 32;         //     this many workgroup tiles
 FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n);
 hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
                          const int32_t *win_offsets, const int32_t *win_tokens, double *rnorm,
-                         unsigned long long *best_key, float *best_fd, int32_t *best_dst, hipStream_t stream);
+                         unsigned long long *best_key, float *best_fd, int32_t *best_dst, bool finalize,
+                         hipStream_t stream);
 
 // ---- scores + selection in three launches on one stream (lk_fused.hip); windows of at most 64 tokens
 struct XiArgs;
@@ -97,10 +98,12 @@ bool xi_seq_applies(const XiPlan &plan, int xi_mode, const float *lse, int batch
 hipError_t launch_xi_seq(const XiArgs &g, int dtype, int head_dim, hipStream_t stream);
 
 // ---- selection (Step 2) ----------------------------------------------------------------------
+// best_key == nullptr: best_fd / best_dst are the inputs.  Otherwise the packed keys of launch_fd_big(...,
+// finalize = false) are, and best_fd / best_dst are written from them on the way (one launch less than finalizing first).
 hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int sum_n, const int32_t *cu_vis,
                          const int32_t *win_offsets, const int32_t *win_tokens, const int32_t *win_remove,
-                         const float *best_fd, const int32_t *best_dst, int32_t *dst, int32_t *new_index,
-                         int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, int32_t *cnt,
+                         const unsigned long long *best_key, float *best_fd, int32_t *best_dst, int32_t *dst,
+                         int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, int32_t *cnt,
                          int32_t *src_rank, hipStream_t stream);
 
 // the scan half of lightkv_select alone (dst, cnt, src_rank already written)

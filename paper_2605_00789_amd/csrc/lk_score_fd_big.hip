@@ -364,7 +364,8 @@ FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n) {
 
 hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
                          const int32_t *win_offsets, const int32_t *win_tokens, double *rnorm,
-                         unsigned long long *best_key, float *best_fd, int32_t *best_dst, hipStream_t stream) {
+                         unsigned long long *best_key, float *best_fd, int32_t *best_dst, bool finalize,
+                         hipStream_t stream) {
   if (n_windows == 0 || sum_n == 0) return hipSuccess;
   BigArgs g{};
   g.X = X; g.ldx = ldx; g.d = d; g.n_windows = n_windows; g.sum_n = sum_n;
@@ -388,7 +389,7 @@ hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int 
   }
   hipLaunchKernelGGL(fd_big_kernel, dim3(grid), dim3(BIG_THREADS), lds, stream, g);
   e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || !finalize) return e;   // without it the caller's selection reads the keys
   hipLaunchKernelGGL(fd_big_finalize_kernel, dim3((unsigned)((sum_n + 255) / 256)), dim3(256), 0, stream, g);
   return hipGetLastError();
 }

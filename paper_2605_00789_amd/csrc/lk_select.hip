@@ -17,12 +17,30 @@ namespace lk {
 struct SelArgs {
   int n_windows, batch, sum_n;
   const int32_t *cu_vis, *win_offsets, *win_tokens, *win_remove;
-  const float *best_fd;
-  const int32_t *best_dst;
+  float *best_fd;            // inputs of the selection -- or, when best_key is given, outputs derived from the keys
+  int32_t *best_dst;
+  const unsigned long long *best_key;   // optional: (FD bits << 32 | B token) per A token, all-ones where nothing was offered
   int32_t *dst, *new_index, *grp_offsets, *grp_src, *cu_vis_out, *cnt, *src_rank;
   int cap;   // power of two >= the largest |A|
 };
 
+
+// Score and proposal of token `tok` (a valid index): from best_fd / best_dst, or from the packed key the tiled FD
+// kernel leaves per A token.
+__device__ __forceinline__ void proposal_of(const SelArgs &g, int tok, float &fd, int &prop) {
+  if (g.best_key) {
+    const unsigned long long key = g.best_key[tok];
+    fd = key == ~0ull ? __uint_as_float(0x7f800000u) : __uint_as_float((unsigned)(key >> 32));
+    prop = key == ~0ull ? -1 : (int)(key & 0xffffffffu);
+  } else {
+    fd = g.best_fd[tok];
+    prop = g.best_dst[tok];
+  }
+}
+// With keys as the input, the selection also writes best_fd / best_dst (the outputs of the score step).
+__device__ __forceinline__ void publish(const SelArgs &g, int tok, float fd, int prop) {
+  if (g.best_key && tok >= 0) { g.best_fd[tok] = fd; g.best_dst[tok] = prop; }
+}
 
 // Windows of up to COUNT_MAX_A A nodes: one workgroup per window.  The rank of an A node among the keys of its window
 // is the number of smaller keys (earlier position first among equal keys); a merged node's rank inside its group is
@@ -52,7 +70,10 @@ __global__ __launch_bounds__(COUNT_MAX_A * SEGS) void select_window_kernel(SelAr
   const int la = threadIdx.x % COUNT_MAX_A, seg = threadIdx.x / COUNT_MAX_A;
   for (int t = 2 * nA + (int)threadIdx.x; t < v; t += COUNT_MAX_A * SEGS) {
     const int tok = g.win_tokens[off + t];
-    if ((unsigned)tok < (unsigned)g.sum_n) { g.dst[tok] = -1; g.cnt[tok] = 0; g.src_rank[tok] = 0; }
+    if ((unsigned)tok < (unsigned)g.sum_n) {
+      g.dst[tok] = -1; g.cnt[tok] = 0; g.src_rank[tok] = 0;
+      publish(g, tok, __uint_as_float(0x7f800000u), -1);
+    }
   }
   const bool has_a = la < nA, has_b = la < nB && 2 * la + 1 < 2 * nA;
   int a_tok = g.win_tokens[off + 2 * (has_a ? la : 0)];
@@ -60,8 +81,13 @@ __global__ __launch_bounds__(COUNT_MAX_A * SEGS) void select_window_kernel(SelAr
   const int first_b = g.win_tokens[off + (nB > 0 ? 1 : 0)];
   if (!has_a || (unsigned)a_tok >= (unsigned)g.sum_n) a_tok = -1;
   if (!has_b || (unsigned)b_tok >= (unsigned)g.sum_n) b_tok = -1;
-  float fd = g.best_fd[a_tok >= 0 ? a_tok : 0];
-  int prop = g.best_dst[a_tok >= 0 ? a_tok : 0];   // the proposal of this A node, or the first B node of the window
+  float fd;
+  int prop;   // the proposal of this A node, or the first B node of the window
+  proposal_of(g, a_tok >= 0 ? a_tok : 0, fd, prop);
+  if (seg == 0) {
+    publish(g, a_tok, fd, prop);
+    publish(g, b_tok, __uint_as_float(0x7f800000u), -1);
+  }
   if (a_tok < 0 || !(fd >= 0.f)) fd = __uint_as_float(0x7f800000u);   // NaN or negative never wins
   if (a_tok < 0) prop = -1;
   else if ((unsigned)prop >= (unsigned)g.sum_n) prop = (nB > 0 && (unsigned)first_b < (unsigned)g.sum_n) ? first_b : -1;
@@ -154,7 +180,10 @@ __global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelA
   if (MODE == 0 && rb == 0) {   // tokens of a window beyond the caller's bound stay
     for (int t = 2 * nA + (int)threadIdx.x; t < v; t += RANK_ROWS * RANK_SEGS) {
       const int tok = g.win_tokens[off + t];
-      if ((unsigned)tok < (unsigned)g.sum_n) { g.dst[tok] = -1; g.cnt[tok] = 0; g.src_rank[tok] = 0; }
+      if ((unsigned)tok < (unsigned)g.sum_n) {
+        g.dst[tok] = -1; g.cnt[tok] = 0; g.src_rank[tok] = 0;
+        publish(g, tok, __uint_as_float(0x7f800000u), -1);
+      }
     }
   }
   int r = g.win_remove[w];
@@ -170,7 +199,9 @@ __global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelA
     const bool ok = (unsigned)tok < (unsigned)g.sum_n;
     uint32_t val;
     if (MODE == 0) {
-      float fd = g.best_fd[ok ? tok : 0];
+      float fd;
+      int unused;
+      proposal_of(g, ok ? tok : 0, fd, unused);
       if (!ok || !(fd >= 0.f)) fd = __uint_as_float(0x7f800000u);   // NaN or negative never wins
       val = f32_order_key(fd);
     } else {
@@ -189,7 +220,10 @@ __global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelA
   if (!has_b || (unsigned)b_tok >= (unsigned)g.sum_n) b_tok = -1;
   int prop = -1;
   if (MODE == 0 && seg == 0) {   // the proposal of this A node, or the first B node of the window
-    prop = g.best_dst[a_tok >= 0 ? a_tok : 0];
+    float fd;
+    proposal_of(g, a_tok >= 0 ? a_tok : 0, fd, prop);
+    publish(g, a_tok, fd, prop);
+    publish(g, b_tok, __uint_as_float(0x7f800000u), -1);
     const int first_b = g.win_tokens[off + (nB > 0 ? 1 : 0)];
     if (a_tok < 0) prop = -1;
     else if ((unsigned)prop >= (unsigned)g.sum_n) prop = (nB > 0 && (unsigned)first_b < (unsigned)g.sum_n) ? first_b : -1;
@@ -401,10 +435,11 @@ hipError_t launch_select_scan_heads(int batch, int sum_n, const int32_t *cu_vis,
 
 hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int sum_n, const int32_t *cu_vis,
                          const int32_t *win_offsets, const int32_t *win_tokens, const int32_t *win_remove,
-                         const float *best_fd, const int32_t *best_dst, int32_t *dst, int32_t *new_index,
-                         int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, int32_t *cnt,
+                         const unsigned long long *best_key, float *best_fd, int32_t *best_dst, int32_t *dst,
+                         int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, int32_t *cnt,
                          int32_t *src_rank, hipStream_t stream) {
   SelArgs g{};
+  g.best_key = best_key;
   g.n_windows = n_windows; g.batch = batch; g.sum_n = sum_n;
   g.cu_vis = cu_vis; g.win_offsets = win_offsets; g.win_tokens = win_tokens; g.win_remove = win_remove;
   g.best_fd = best_fd; g.best_dst = best_dst;
