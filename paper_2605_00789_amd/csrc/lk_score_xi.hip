@@ -10,6 +10,8 @@
 //             logits and adds exp(logit - max) / sum over the prompt rows -> per-head partial xi.
 //   lse handed in (either mode): pass 2 only.
 //   pass 3  sums the heads in a fixed order and applies the floor.
+// Batches with enough (sequence, head) pairs run passes 1 and 2 as one launch with one workgroup per pair
+// (lk_xi_seq.hip); pass 3 is the same.
 // The operand whose index must be reduced inside a lane is always fed as the MFMA row operand:
 // accumulator registers run over rows, lanes over columns, so both reductions stay in registers.
 #include "lk_xi_body.h"
