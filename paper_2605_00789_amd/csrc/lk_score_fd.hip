@@ -31,7 +31,6 @@ __global__ __launch_bounds__(FD_THREADS) void fd_epilogue_kernel(FdArgs g) {
   __shared__ double nb2[FD_MAX_COLS];
   __shared__ double na2[32];
   const int rb = blockIdx.x;
-  const int c32 = threadIdx.x & 31, rgrp = threadIdx.x >> 5;   // 8 row groups
   const int64_t ks_stride = (int64_t)g.n_tiles * FD_TILE_FLOATS;
   const int per = g.mt * g.nt;
 
@@ -58,57 +57,70 @@ __global__ __launch_bounds__(FD_THREADS) void fd_epilogue_kernel(FdArgs g) {
   __syncthreads();
 
   const int col_cap = (g.group > 1) ? g.slot : g.nt * 32;   // columns this launch really tiled
+  // Eight threads share a row of the block; a thread takes four neighbouring columns of every column tile, so the
+  // slices of a tile arrive as ksplit 16-byte loads per thread, all in flight together (one round trip per column tile).
+  const int r = threadIdx.x >> 3, sub = threadIdx.x & 7;
+  WinInfo wi;
+  int l, col_base;   // local A position; first tile column of this row's window
+  if (g.group > 1) {
+    const int s = r / g.slot;
+    l = r - s * g.slot;
+    wi = win_info(g, rb * g.group + s);
+    col_base = s * g.slot;
+  } else {
+    wi = win_info(g, w_single);
+    l = m_single * 32 + r;
+    col_base = 0;
+  }
+  const bool a_valid = l < wi.nA;
+  const int nB = wi.nB < col_cap ? wi.nB : col_cap;
+  double best = __longlong_as_double(0x7ff0000000000000ll);   // +inf
+  int best_c = 0x7fffffff;
+  const double a2 = na2[r];
+  for (int t = 0; t < ncol_tiles; ++t) {
+    const int tc0 = t * 32 + sub * 4;   // first of this thread's columns inside the block's tile row
+    if (tc0 + 3 < col_base || tc0 >= col_base + nB) continue;   // none of the four belongs to this row's window
+    const float *p = g.partial + (int64_t)(tile_row0 + t) * FD_TILE_FLOATS + r * 32 + sub * 4;
+    f32x4 v[FD_MAX_KSPLIT];
 #pragma unroll
-  for (int rp = 0; rp < 4; ++rp) {
-    const int r = rp * 8 + rgrp;
-    WinInfo wi;
-    int l, col_base;   // local A position; first tile column of this row's window
-    if (g.group > 1) {
-      const int s = r / g.slot;
-      l = r - s * g.slot;
-      wi = win_info(g, rb * g.group + s);
-      col_base = s * g.slot;
-    } else {
-      wi = win_info(g, w_single);
-      l = m_single * 32 + r;
-      col_base = 0;
+    for (int ks = 0; ks < FD_MAX_KSPLIT; ++ks)   // surplus slices re-read the last one and are dropped
+      v[ks] = *reinterpret_cast<const f32x4 *>(p + (ks < g.ksplit ? ks : g.ksplit - 1) * ks_stride);
+    double dot[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int ks = 0; ks < FD_MAX_KSPLIT; ++ks) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) dot[j] += (ks < g.ksplit) ? (double)v[ks][j] : 0.0;
     }
-    const bool a_valid = l < wi.nA;
-    if (wi.nB > col_cap) wi.nB = col_cap;
-    double best = __longlong_as_double(0x7ff0000000000000ll);   // +inf
-    int best_c = 0x7fffffff;
-    if (a_valid && wi.nB > 0) {
-      const double a2 = na2[r];
-      for (int c = c32; c < wi.nB; c += 32) {
-        const int tc = col_base + c;   // column inside this row block's tile row
-        const double dot = sum_slices(g.partial + (int64_t)(tile_row0 + (tc >> 5)) * FD_TILE_FLOATS + r * 32 + (tc & 31),
-                                      ks_stride, g.ksplit);
-        const double fd = divergence(g.metric, dot, a2, nb2[tc]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = tc0 + j - col_base;   // column inside the window
+      if (a_valid && c >= 0 && c < nB) {
+        const double fd = divergence(g.metric, dot[j], a2, nb2[tc0 + j]);
         if (fd < best) { best = fd; best_c = c; }   // columns ascend: strict < keeps the first minimum
       }
     }
-    // reduce over the 32 lanes of the half-wave that share this row
+  }
+  // reduce over the eight lanes that share this row
 #pragma unroll
-    for (int m = 16; m >= 1; m >>= 1) {
-      const double ob = __shfl_xor(best, m, 64);
-      const int oc = __shfl_xor(best_c, m, 64);
-      if (ob < best || (ob == best && oc < best_c)) { best = ob; best_c = oc; }
+  for (int m = 4; m >= 1; m >>= 1) {
+    const double ob = __shfl_xor(best, m, 64);
+    const int oc = __shfl_xor(best_c, m, 64);
+    if (ob < best || (ob == best && oc < best_c)) { best = ob; best_c = oc; }
+  }
+  if (sub == 0 && a_valid) {
+    const int a_tok = checked_token(g, wi.off + 2 * l);
+    if (a_tok >= 0) {
+      // no finite score at all (NaN rows): propose the first B node with FD = +inf, so that counts stay exact
+      const bool has = best_c != 0x7fffffff;
+      g.best_fd[a_tok] = has ? (float)best : __uint_as_float(0x7f800000u);
+      g.best_dst[a_tok] = (wi.nB > 0) ? checked_token(g, wi.off + 2 * (has ? best_c : 0) + 1) : -1;
     }
-    if (c32 == 0 && a_valid) {
-      const int a_tok = checked_token(g, wi.off + 2 * l);
-      if (a_tok >= 0) {
-        // no finite score at all (NaN rows): propose the first B node with FD = +inf, so that counts stay exact
-        const bool has = best_c != 0x7fffffff;
-        g.best_fd[a_tok] = has ? (float)best : __uint_as_float(0x7f800000u);
-        g.best_dst[a_tok] = (wi.nB > 0) ? checked_token(g, wi.off + 2 * (has ? best_c : 0) + 1) : -1;
-      }
-    }
-    if (c32 == 1 && l < wi.nB) {   // B rows carry no proposal
-      const int b_tok = checked_token(g, wi.off + 2 * l + 1);
-      if (b_tok >= 0) {
-        g.best_fd[b_tok] = __uint_as_float(0x7f800000u);
-        g.best_dst[b_tok] = -1;
-      }
+  }
+  if (sub == 1 && l < wi.nB) {   // B rows carry no proposal
+    const int b_tok = checked_token(g, wi.off + 2 * l + 1);
+    if (b_tok >= 0) {
+      g.best_fd[b_tok] = __uint_as_float(0x7f800000u);
+      g.best_dst[b_tok] = -1;
     }
   }
 }
