@@ -13,7 +13,9 @@ namespace lk {
 
 constexpr int WIN_THREADS = 1024;
 constexpr int LOCAL_BITS = 14;             // local token index < 16384
-constexpr size_t WIN_TABLE_LDS_MAX = 60 * 1024;   // bytes of LDS the (run, window) count table may take
+constexpr size_t WIN_TABLE_LDS_MAX = 56 * 1024;   // bytes of LDS the (run, window) count table may take
+constexpr int WIN_KEEP = 4;                // passes of 1024 tokens whose window and rank stay in registers between phases
+constexpr int WIN_RUN_PARTS = 4;           // threads sharing a window's prefix over the runs (up to 256 windows per sequence)
 
 struct WinArgs {
   const int32_t *cu_vis, *pos;
@@ -61,6 +63,7 @@ __device__ __forceinline__ void wave_bin_rank(int wid, bool valid, int lane, int
 __global__ __launch_bounds__(WIN_THREADS) void build_windows_table_kernel(WinArgs g) {
   extern __shared__ uint16_t table[];   // [runs][win_per_seq] counts, then exclusive prefixes over the runs
   __shared__ int scan_lds[64];
+  __shared__ int part_sum[WIN_RUN_PARTS][WIN_THREADS / WIN_RUN_PARTS];
   const int b = blockIdx.x;
   const int base = g.cu_vis[b];
   const int n = g.cu_vis[b + 1] - base;
@@ -74,8 +77,24 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_table_kernel(WinArg
 
   for (int e = threadIdx.x; e < runs * wps; e += WIN_THREADS) table[e] = 0;
   __syncthreads();
-  // phase 1: per-run counts
-  for (int i0 = 0; i0 < n; i0 += WIN_THREADS) {
+  // phase 1: per-run counts.  The first WIN_KEEP passes keep (listed index, window, rank inside the run's group) in
+  // registers for phase 3; longer sequences recompute them there.
+  int k_id[WIN_KEEP], k_wid[WIN_KEEP], k_rank[WIN_KEEP];
+#pragma unroll
+  for (int p = 0; p < WIN_KEEP; ++p) {
+    k_id[p] = -1; k_wid[p] = 0; k_rank[p] = 0;
+    const int i = p * WIN_THREADS + (int)threadIdx.x;
+    if (p * WIN_THREADS < n) {   // uniform
+      const int id = i < n ? listed_as(g, base + i) : -1;
+      const bool valid = id >= 0;
+      const int wid = valid ? window_of(g, g.pos[base + i]) : -1;
+      int rank, gs; bool leader;
+      wave_bin_rank(wid, valid, lane, rank, gs, leader);
+      if (leader) table[(i >> 6) * wps + wid] = (uint16_t)gs;
+      k_id[p] = id; k_wid[p] = wid; k_rank[p] = rank;
+    }
+  }
+  for (int i0 = WIN_KEEP * WIN_THREADS; i0 < n; i0 += WIN_THREADS) {
     const int i = i0 + threadIdx.x;
     const bool valid = i < n && listed_as(g, base + (i < n ? i : 0)) >= 0;
     const int wid = valid ? window_of(g, g.pos[base + i]) : -1;
@@ -86,10 +105,38 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_table_kernel(WinArg
   __syncthreads();
   // phase 2: exclusive prefix over the runs for every window, then a scan over the windows
   int carry = 0;
+  const bool split_runs = wps <= WIN_THREADS / WIN_RUN_PARTS;   // uniform: WIN_RUN_PARTS threads share a window's runs
   for (int w0 = 0; w0 < wps; w0 += WIN_THREADS) {
-    const int w = w0 + threadIdx.x;
+    const int w = split_runs ? (int)threadIdx.x % (WIN_THREADS / WIN_RUN_PARTS) : w0 + (int)threadIdx.x;
     int total = 0;
-    if (w < wps) {
+    if (split_runs) {
+      // the runs of a window in WIN_RUN_PARTS contiguous parts: part sums, then every part rewrites its own counts
+      // as prefixes -- a quarter of the dependent LDS steps of one thread per window
+      const int part = (int)threadIdx.x / (WIN_THREADS / WIN_RUN_PARTS);
+      const int per_part = (runs + WIN_RUN_PARTS - 1) / WIN_RUN_PARTS;
+      const int r_begin = min(part * per_part, runs), r_end = min(r_begin + per_part, runs);
+      int mine = 0;
+      if (w < wps)
+        for (int r = r_begin; r < r_end; ++r) mine += table[r * wps + w];
+      part_sum[part][w & (WIN_THREADS / WIN_RUN_PARTS - 1)] = mine;
+      __syncthreads();
+      int before = 0;
+#pragma unroll
+      for (int q = 0; q < WIN_RUN_PARTS; ++q) {
+        const int v = part_sum[q][w & (WIN_THREADS / WIN_RUN_PARTS - 1)];
+        before += (q < part) ? v : 0;
+        total += v;
+      }
+      if (w < wps) {
+        int running = before;
+        for (int r = r_begin; r < r_end; ++r) {
+          const int c = table[r * wps + w];
+          table[r * wps + w] = (uint16_t)running;
+          running += c;
+        }
+      }
+      total = (part == 0 && w < wps) ? total : 0;   // one thread per window enters the scan over the windows
+    } else if (w < wps) {
       for (int r = 0; r < runs; ++r) {
         const int c = table[r * wps + w];
         table[r * wps + w] = (uint16_t)total;
@@ -117,7 +164,7 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_table_kernel(WinArg
     }
     __syncthreads();
     const int excl = carry + (wave ? scan_lds[32 + wave - 1] : 0) + inc - total;
-    if (w < wps) {
+    if (w < wps && (!split_runs || (int)threadIdx.x < WIN_THREADS / WIN_RUN_PARTS)) {
       winbase[w] = excl;
       g.win_offsets[wbase + w] = out_base + excl;
     }
@@ -126,7 +173,13 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_table_kernel(WinArg
   }
   if (threadIdx.x == 0 && b == g.batch - 1) g.win_offsets[wbase + wps] = out_base + out_n;
   // phase 3: slots
-  for (int i0 = 0; i0 < n; i0 += WIN_THREADS) {
+#pragma unroll
+  for (int p = 0; p < WIN_KEEP; ++p) {
+    const int i = p * WIN_THREADS + (int)threadIdx.x;
+    if (k_id[p] >= 0)
+      g.win_tokens[out_base + winbase[k_wid[p]] + table[(i >> 6) * wps + k_wid[p]] + k_rank[p]] = k_id[p];
+  }
+  for (int i0 = WIN_KEEP * WIN_THREADS; i0 < n; i0 += WIN_THREADS) {
     const int i = i0 + threadIdx.x;
     const int id = i < n ? listed_as(g, base + i) : -1;
     const bool valid = id >= 0;
