@@ -158,6 +158,11 @@ lightkv_status lightkv_build_windows_next(int32_t batch, const int32_t *h_cu_vis
  *   window: best_fd[i] = FD (fp32, clamped at 0), best_dst[i] = that B token; ties go to the B node that
  *   comes first in the window.  B rows, and A rows of windows without a B node, get +inf / -1.
  *   FD(a,b) = 1 - <x_a,x_b> / (max(|x_a|,1e-12) * max(|x_b|,1e-12))          (Eq. "similarity")
+ *   x_sqnorm[sumN] (device, fp32, may be NULL): |x_i|^2 = sum_j X[i,j]^2 of every row of X as stored, if the caller
+ *     already has it -- lightkv_compact / lightkv_aggregate_compact produce it for the rows they write.  It is trusted,
+ *     not checked; it saves one pass over X where the library would compute the norms on their own (large windows on
+ *     the matrix-core path) and is ignored elsewhere.  With the values those calls produce the results are bit-identical
+ *     to passing NULL.
  *   xi[sumN]: prompt-guidance weight (Eq. "attention-factor"), floored at 1e-30.
  *     TEXT_QUERY  : Q = prompt queries [sumT, heads, head_dim], K = vision keys [sumN, heads, head_dim]
  *     VISION_QUERY: Q = vision queries [sumN, ...],             K = prompt keys [sumT, ...], lse required
@@ -170,7 +175,7 @@ lightkv_status lightkv_build_windows_next(int32_t batch, const int32_t *h_cu_vis
  *   that forks from and joins `stream`; the only object the library ever creates, one per device, on the first such
  *   call outside stream capture; host threads that make such calls on one device take turns enqueueing).
  */
-lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ldx,
+lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ldx, const float *x_sqnorm,
                              const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
                              const void *K, int64_t k_tok_stride, int64_t k_head_stride,
                              int32_t xi_mode, const float *lse, float softmax_scale,
@@ -199,7 +204,7 @@ lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, co
  * launches of the FD kernels and the whole call is three launches on `stream` (no helper stream).  Otherwise the call
  * is the two calls in sequence.  X must not be NULL; xi_mode GIVEN skips the xi half as in lightkv_score.
  */
-lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int64_t ldx,
+lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int64_t ldx, const float *x_sqnorm,
                                     const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
                                     const void *K, int64_t k_tok_stride, int64_t k_head_stride,
                                     int32_t xi_mode, const float *lse, float softmax_scale,
@@ -225,23 +230,26 @@ lightkv_status lightkv_aggregate(const lightkv_problem *p, const int32_t *grp_of
  * token whose new_index does not fit is dropped, never written out of bounds -- compare
  * cu_vis_out[batch] from lightkv_select with out_rows to detect that.
  * NULL tensors are skipped (in and out together).
+ * x_sqnorm_out[out_rows] (device, fp32, may be NULL; needs X): |x|^2 of every row written to X_out, as stored -- the
+ * x_sqnorm argument of the next stage's lightkv_score; the rows pass through registers here anyway.
  */
 lightkv_status lightkv_compact(const lightkv_problem *p, const int32_t *new_index,
                                const void *X, int64_t ldx, const void *K, int64_t ldk,
                                const void *V, int64_t ldv, const int32_t *pos,
-                               void *X_out, void *K_out, void *V_out, int32_t *pos_out, int64_t out_rows,
-                               void *stream);
+                               void *X_out, void *K_out, void *V_out, int32_t *pos_out, float *x_sqnorm_out,
+                               int64_t out_rows, void *stream);
 
 /*
  * lightkv_aggregate followed by lightkv_compact in one pass over the rows: reads every input row once,
- * writes every output row once, leaves the inputs untouched.  Same results as the two calls.
+ * writes every output row once, leaves the inputs untouched.  Same results as the two calls (x_sqnorm_out as in
+ * lightkv_compact).
  */
 lightkv_status lightkv_aggregate_compact(const lightkv_problem *p, const int32_t *new_index,
                                          const int32_t *grp_offsets, const int32_t *grp_src, const float *xi,
                                          const void *X, int64_t ldx, const void *K, int64_t ldk,
                                          const void *V, int64_t ldv, const int32_t *pos,
                                          void *X_out, void *K_out, void *V_out, int32_t *pos_out,
-                                         int64_t out_rows, void *stream);
+                                         float *x_sqnorm_out, int64_t out_rows, void *stream);
 
 #ifdef __cplusplus
 }

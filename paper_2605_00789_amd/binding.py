@@ -55,18 +55,18 @@ def _load():
     lib.lightkv_build_windows_next.restype = C.c_int
     lib.lightkv_build_windows_next.argtypes = [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     lib.lightkv_score.restype = C.c_int
-    lib.lightkv_score.argtypes = [P, vp, i64, vp, i64, i64, vp, i64, i64, i32, vp, f32, vp, vp, vp, vp, sz, vp]
+    lib.lightkv_score.argtypes = [P, vp, i64, vp, vp, i64, i64, vp, i64, i64, i32, vp, f32, vp, vp, vp, vp, sz, vp]
     lib.lightkv_score_select.restype = C.c_int
-    lib.lightkv_score_select.argtypes = [P, vp, i64, vp, i64, i64, vp, i64, i64, i32, vp, f32, vp, vp, vp,
+    lib.lightkv_score_select.argtypes = [P, vp, i64, vp, vp, i64, i64, vp, i64, i64, i32, vp, f32, vp, vp, vp,
                                          vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lightkv_select.restype = C.c_int
     lib.lightkv_select.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lightkv_aggregate.restype = C.c_int
     lib.lightkv_aggregate.argtypes = [P, vp, vp, vp, vp, i64, vp, i64, vp, i64, vp]
     lib.lightkv_compact.restype = C.c_int
-    lib.lightkv_compact.argtypes = [P, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, i64, vp]
+    lib.lightkv_compact.argtypes = [P, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.lightkv_aggregate_compact.restype = C.c_int
-    lib.lightkv_aggregate_compact.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, i64, vp]
+    lib.lightkv_aggregate_compact.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
     return lib
 
 
@@ -168,8 +168,9 @@ def lightkv_build_windows_next(batch, h_cu_vis, cu_vis, pos, new_index, cu_vis_o
 
 
 def lightkv_score(p: Problem, X, Q, K, xi, best_fd, best_dst, ws, *, heads_major=False, xi_mode=XI_TEXT_QUERY,
-                  lse=None, softmax_scale=0.0, stream=None):
-    """X [sumN, d]; Q, K token-major [tokens, heads*head_dim] (or [heads, tokens, head_dim] with heads_major)."""
+                  lse=None, softmax_scale=0.0, x_sqnorm=None, stream=None):
+    """X [sumN, d]; Q, K token-major [tokens, heads*head_dim] (or [heads, tokens, head_dim] with heads_major);
+    x_sqnorm: optional fp32 [sumN], |x|^2 of the rows of X (from lightkv_compact / lightkv_aggregate_compact)."""
     hd = p.c.head_dim
 
     def strides(t):
@@ -181,13 +182,14 @@ def lightkv_score(p: Problem, X, Q, K, xi, best_fd, best_dst, ws, *, heads_major
 
     qts, qhs = strides(Q)
     kts, khs = strides(K)
-    _check(_lib.lightkv_score(p.ref(), _dptr(X), _ld(X), _dptr(Q), qts, qhs, _dptr(K), kts, khs, xi_mode,
+    _check(_lib.lightkv_score(p.ref(), _dptr(X), _ld(X), _dptr(x_sqnorm), _dptr(Q), qts, qhs, _dptr(K), kts, khs, xi_mode,
                               _dptr(lse), float(softmax_scale), _dptr(xi), _dptr(best_fd), _dptr(best_dst),
                               _dptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "lightkv_score")
 
 
 def lightkv_score_select(p: Problem, X, Q, K, xi, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out,
-                         ws, *, heads_major=False, xi_mode=XI_TEXT_QUERY, lse=None, softmax_scale=0.0, stream=None):
+                         ws, *, heads_major=False, xi_mode=XI_TEXT_QUERY, lse=None, softmax_scale=0.0, x_sqnorm=None,
+                         stream=None):
     hd = p.c.head_dim
 
     def strides(t):
@@ -199,7 +201,7 @@ def lightkv_score_select(p: Problem, X, Q, K, xi, best_fd, best_dst, dst, new_in
 
     qts, qhs = strides(Q)
     kts, khs = strides(K)
-    _check(_lib.lightkv_score_select(p.ref(), _dptr(X), _ld(X), _dptr(Q), qts, qhs, _dptr(K), kts, khs, xi_mode,
+    _check(_lib.lightkv_score_select(p.ref(), _dptr(X), _ld(X), _dptr(x_sqnorm), _dptr(Q), qts, qhs, _dptr(K), kts, khs, xi_mode,
                                      _dptr(lse), float(softmax_scale), _dptr(xi), _dptr(best_fd), _dptr(best_dst),
                                      _dptr(dst), _dptr(new_index), _dptr(grp_offsets), _dptr(grp_src),
                                      _dptr(cu_vis_out), _dptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
@@ -217,16 +219,18 @@ def lightkv_aggregate(p: Problem, grp_offsets, grp_src, xi, X, K, V, stream=None
                                   _dptr(K), _ld(K), _dptr(V), _ld(V), _stream(stream)), "lightkv_aggregate")
 
 
-def lightkv_compact(p: Problem, new_index, X, K, V, pos, X_out, K_out, V_out, pos_out, stream=None):
+def lightkv_compact(p: Problem, new_index, X, K, V, pos, X_out, K_out, V_out, pos_out, x_sqnorm_out=None, stream=None):
     _check(_lib.lightkv_compact(p.ref(), _dptr(new_index), _dptr(X), _ld(X), _dptr(K), _ld(K), _dptr(V), _ld(V),
                                 _dptr(pos), _dptr(X_out), _dptr(K_out), _dptr(V_out), _dptr(pos_out),
-                                _out_rows(X_out, K_out, V_out, pos_out), _stream(stream)), "lightkv_compact")
+                                _dptr(x_sqnorm_out), _out_rows(X_out, K_out, V_out, pos_out), _stream(stream)),
+           "lightkv_compact")
 
 
 def lightkv_aggregate_compact(p: Problem, new_index, grp_offsets, grp_src, xi, X, K, V, pos, X_out, K_out, V_out,
-                              pos_out, stream=None):
+                              pos_out, x_sqnorm_out=None, stream=None):
     _check(_lib.lightkv_aggregate_compact(p.ref(), _dptr(new_index), _dptr(grp_offsets), _dptr(grp_src), _dptr(xi),
                                           _dptr(X), _ld(X), _dptr(K), _ld(K), _dptr(V), _ld(V), _dptr(pos),
                                           _dptr(X_out), _dptr(K_out), _dptr(V_out), _dptr(pos_out),
-                                          _out_rows(X_out, K_out, V_out, pos_out), _stream(stream)),
+                                          _dptr(x_sqnorm_out), _out_rows(X_out, K_out, V_out, pos_out),
+                                          _stream(stream)),
            "lightkv_aggregate_compact")

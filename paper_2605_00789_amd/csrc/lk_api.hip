@@ -168,7 +168,7 @@ lightkv_status select_impl(const lightkv_problem *p, bool from_keys, float *best
   char *wsb = static_cast<char *>(ws);
   const unsigned long long *keys = from_keys ? reinterpret_cast<const unsigned long long *>(wsb + l.fd_keys) : nullptr;
   if (launch_select(p->n_windows, c.max_window, p->batch, c.sum_n, p->cu_vis, p->win_offsets, p->win_tokens,
-                    p->win_remove, keys, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out,
+                    p->win_remove, keys, big.mt, big.nt_store, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out,
                     reinterpret_cast<int32_t *>(wsb + l.sel_cnt), reinterpret_cast<int32_t *>(wsb + l.sel_rank),
                     static_cast<hipStream_t>(stream)) != hipSuccess)
     return LIGHTKV_ERR_LAUNCH;
@@ -254,7 +254,7 @@ struct SelectOut {   // outputs of lightkv_select, present when selection is to 
 // sel == nullptr: plain lightkv_score.  Otherwise the caller guarantees that make_fd_small_fused_plan applies.
 // keys_only: on the tiled MFMA path, leave the packed keys in the workspace and do not write best_fd / best_dst
 // (the caller's selection reads the keys and writes them).
-lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx,
+lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, const float *x_sqnorm,
                           const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
                           const void *K, int64_t k_tok_stride, int64_t k_head_stride,
                           int32_t xi_mode, const float *lse, float softmax_scale,
@@ -269,6 +269,7 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx,
   if (st != LIGHTKV_OK) return st;
   if (!xi || (need_fd && (!best_fd || !best_dst))) return LIGHTKV_ERR_NULL;
   if (need_fd && !row_tensor_ok(X, ldx, p->d, c.elem_bytes, st)) return st;
+  if (x_sqnorm && (reinterpret_cast<uintptr_t>(x_sqnorm) & 3)) return LIGHTKV_ERR_UNSUPPORTED;
   if (need_xi) {
     if (!Q || !K) return LIGHTKV_ERR_NULL;
     if (xi_mode == LIGHTKV_XI_VISION_QUERY && !lse) return LIGHTKV_ERR_NULL;
@@ -351,7 +352,7 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx,
       fd_status = LIGHTKV_ERR_LAUNCH;
   } else if (use_big) {
     if (launch_fd_big(big, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
-                      reinterpret_cast<double *>(wsb + l.fd_norm),
+                      x_sqnorm, reinterpret_cast<float *>(wsb + l.fd_norm),
                       reinterpret_cast<unsigned long long *>(wsb + l.fd_keys), best_fd, best_dst, !keys_only,
                       s) != hipSuccess)
       fd_status = LIGHTKV_ERR_LAUNCH;
@@ -366,17 +367,17 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx,
 
 extern "C" {
 
-lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ldx,
+lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ldx, const float *x_sqnorm,
                              const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
                              const void *K, int64_t k_tok_stride, int64_t k_head_stride,
                              int32_t xi_mode, const float *lse, float softmax_scale,
                              float *xi, float *best_fd, int32_t *best_dst,
                              void *ws, size_t ws_bytes, void *stream) {
-  return score_impl(p, X, ldx, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
+  return score_impl(p, X, ldx, x_sqnorm, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
                     softmax_scale, xi, best_fd, best_dst, nullptr, false, ws, ws_bytes, stream);
 }
 
-lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int64_t ldx,
+lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int64_t ldx, const float *x_sqnorm,
                                     const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
                                     const void *K, int64_t k_tok_stride, int64_t k_head_stride,
                                     int32_t xi_mode, const float *lse, float softmax_scale,
@@ -391,12 +392,12 @@ lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int
   const FdPlan small = make_fd_small_fused_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
   if ((small.n_tiles > 0 && !use_big_fd(p, c)) || p->n_windows == 0) {
     const SelectOut sel{dst, new_index, grp_offsets, grp_src, cu_vis_out};
-    return score_impl(p, X, ldx, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
+    return score_impl(p, X, ldx, x_sqnorm, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
                       softmax_scale, xi, best_fd, best_dst, &sel, false, ws, ws_bytes, stream);
   }
   // the tiled MFMA path leaves packed keys: the selection reads them directly and writes best_fd / best_dst itself
   const bool from_keys = use_big_fd(p, c);
-  st = score_impl(p, X, ldx, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
+  st = score_impl(p, X, ldx, x_sqnorm, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
                   softmax_scale, xi, best_fd, best_dst, nullptr, from_keys, ws, ws_bytes, stream);
   if (st != LIGHTKV_OK) return st;
   return select_impl(p, from_keys, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, ws, ws_bytes,
@@ -414,8 +415,8 @@ lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, co
 static lightkv_status rows_call(int mode, const lightkv_problem *p, const int32_t *new_index,
                                 const int32_t *grp_offsets, const int32_t *grp_src, const float *xi,
                                 const void *X, int64_t ldx, const void *K, int64_t ldk, const void *V, int64_t ldv,
-                                const int32_t *pos, void *Xo, void *Ko, void *Vo, int32_t *pos_out, int64_t out_rows,
-                                void *stream) {
+                                const int32_t *pos, void *Xo, void *Ko, void *Vo, int32_t *pos_out,
+                                float *x_sqnorm_out, int64_t out_rows, void *stream) {
   Checked c;
   lightkv_status st = check_problem(p, false, false, c);
   if (st != LIGHTKV_OK) return st;
@@ -445,8 +446,9 @@ static lightkv_status rows_call(int mode, const lightkv_problem *p, const int32_
   }
   if (mode != 0 && ((pos == nullptr) != (pos_out == nullptr))) return LIGHTKV_ERR_NULL;
   if (mode != 0 && pos && pos == pos_out) return LIGHTKV_ERR_SHAPE;
-  if (launch_rows(mode, p->dtype, p->d, c.sum_n, t, new_index, grp_offsets, grp_src, xi, pos, pos_out, out_rows,
-                  static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (x_sqnorm_out && (!X || (reinterpret_cast<uintptr_t>(x_sqnorm_out) & 3))) return LIGHTKV_ERR_NULL;
+  if (launch_rows(mode, p->dtype, p->d, c.sum_n, t, new_index, grp_offsets, grp_src, xi, pos, pos_out, x_sqnorm_out,
+                  out_rows, static_cast<hipStream_t>(stream)) != hipSuccess)
     return LIGHTKV_ERR_LAUNCH;
   return LIGHTKV_OK;
 }
@@ -455,16 +457,16 @@ lightkv_status lightkv_aggregate(const lightkv_problem *p, const int32_t *grp_of
                                  const float *xi, void *X, int64_t ldx, void *K, int64_t ldk,
                                  void *V, int64_t ldv, void *stream) {
   return rows_call(0, p, nullptr, grp_offsets, grp_src, xi, X, ldx, K, ldk, V, ldv, nullptr, nullptr, nullptr,
-                   nullptr, nullptr, 0, stream);
+                   nullptr, nullptr, nullptr, 0, stream);
 }
 
 lightkv_status lightkv_compact(const lightkv_problem *p, const int32_t *new_index,
                                const void *X, int64_t ldx, const void *K, int64_t ldk,
                                const void *V, int64_t ldv, const int32_t *pos,
-                               void *X_out, void *K_out, void *V_out, int32_t *pos_out, int64_t out_rows,
-                               void *stream) {
+                               void *X_out, void *K_out, void *V_out, int32_t *pos_out, float *x_sqnorm_out,
+                               int64_t out_rows, void *stream) {
   return rows_call(1, p, new_index, nullptr, nullptr, nullptr, X, ldx, K, ldk, V, ldv, pos, X_out, K_out, V_out,
-                   pos_out, out_rows, stream);
+                   pos_out, x_sqnorm_out, out_rows, stream);
 }
 
 lightkv_status lightkv_aggregate_compact(const lightkv_problem *p, const int32_t *new_index,
@@ -472,9 +474,9 @@ lightkv_status lightkv_aggregate_compact(const lightkv_problem *p, const int32_t
                                          const void *X, int64_t ldx, const void *K, int64_t ldk,
                                          const void *V, int64_t ldv, const int32_t *pos,
                                          void *X_out, void *K_out, void *V_out, int32_t *pos_out,
-                                         int64_t out_rows, void *stream) {
+                                         float *x_sqnorm_out, int64_t out_rows, void *stream) {
   return rows_call(2, p, new_index, grp_offsets, grp_src, xi, X, ldx, K, ldk, V, ldv, pos, X_out, K_out, V_out,
-                   pos_out, out_rows, stream);
+                   pos_out, x_sqnorm_out, out_rows, stream);
 }
 
 }  // extern "C"

@@ -81,6 +81,58 @@ __device__ __forceinline__ void bitonic_sort_lds(KeyT *keys, int n) {
 // s_barrier.  Unlike __syncthreads() it does not wait for global loads, so prefetches stay in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// |x|^2 of the eight bf16 values of one 16-byte chunk, in a fixed order.  Every kernel that produces squared row
+// norms uses this, the same chunk-to-lane assignment (chunk c of a row belongs to lane c % 64, chunks in ascending
+// order) and the same butterfly over the wave, so that their results agree bit for bit.
+__device__ __forceinline__ float sumsq_chunk_bf16(const uint4 &v) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  float t = 0.f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const float lo = __uint_as_float(w[q] << 16), hi = __uint_as_float(w[q] & 0xffff0000u);
+    t = fmaf(lo, lo, t);
+    t = fmaf(hi, hi, t);
+  }
+  return t;
+}
+__device__ __forceinline__ float sumsq_chunk_f32(const uint4 &v) {
+  float t = 0.f;
+  t = fmaf(__uint_as_float(v.x), __uint_as_float(v.x), t);
+  t = fmaf(__uint_as_float(v.y), __uint_as_float(v.y), t);
+  t = fmaf(__uint_as_float(v.z), __uint_as_float(v.z), t);
+  t = fmaf(__uint_as_float(v.w), __uint_as_float(v.w), t);
+  return t;
+}
+__device__ __forceinline__ float wave_sum_butterfly(float s) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+  return s;
+}
+
+// Packed keys of the tiled FD kernel, [column tile][list position]: column tiles a window of nB B nodes really has,
+// and the minimum over them for one position.
+__device__ __forceinline__ int fd_big_col_tiles(int nB, int plan_nt) {
+  const int n = (nB + 95) / 96;   // FD_BIG_TILE columns per tile
+  return n < plan_nt ? n : plan_nt;
+}
+__device__ __forceinline__ unsigned long long fd_big_best_key(const unsigned long long *cand, int sum_n, int pos,
+                                                              int n_col_tiles) {
+  unsigned long long best = ~0ull;
+  int n = 0;
+  for (; n + 4 <= n_col_tiles; n += 4) {   // four loads in flight
+    unsigned long long c[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) c[u] = cand[(size_t)(n + u) * (size_t)sum_n + (size_t)pos];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) best = c[u] < best ? c[u] : best;
+  }
+  for (; n < n_col_tiles; ++n) {
+    const unsigned long long c = cand[(size_t)n * (size_t)sum_n + (size_t)pos];
+    best = c < best ? c : best;
+  }
+  return best;
+}
+
 __host__ __device__ __forceinline__ int next_pow2(int v) {
   int p = 1;
   while (p < v) p <<= 1;

@@ -46,18 +46,24 @@ hipError_t launch_fd_select_small(const FdPlan &plan, int dtype, const void *X, 
 
 // Large windows (compute bound): LDS-tiled MFMA GEMM with the row arg-min fused into its epilogue.
 struct FdBigPlan {
-  int wb;            // wave tile = (16*wb)^2, workgroup tile = (32*wb)^2
+  int wb;            // MFMA blocks (16 x 16) per edge of the workgroup tile
   int mt, nt;        // workgroup tiles per window along A and B
-  size_t norm_floats, key_bytes;
+  int max_window;    // the caller's bound on the tokens of a window
+  size_t norm_floats;   // |x|^2 per token (used when the caller does not hand them in)
+  int nt_store;      // column tiles that keep keys of their own: nt, or 1 (all tiles of a window share one key per row)
+  size_t key_bytes;  // [nt_store][sum_n] packed keys (FD bits << 32 | B token): per column tile, the best key of the A
+                     // row at every position of the window lists; all-ones where nothing was offered
   int metric;        // as in FdPlan
 };
+constexpr int FD_BIG_TILE = 96;            // rows and columns of a workgroup tile
+constexpr int FD_BIG_KEYS_PER_TILE_MAX_NT = 4;   // up to this many column tiles per window, each keeps keys of its own
 constexpr int FD_BIG_MIN_WINDOW = 256;        // windows bounded by fewer tokens use the small-tile path ...
 constexpr int FD_BIG_MIN_WINDOW_MANY = 128;   // ... unless they are at least this large and make up at least
 constexpr int FD_BIG_MANY_TILES = 32;         //     this many workgroup tiles
 FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n);
 hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
-                         const int32_t *win_offsets, const int32_t *win_tokens, double *rnorm,
-                         unsigned long long *best_key, float *best_fd, int32_t *best_dst, bool finalize,
+                         const int32_t *win_offsets, const int32_t *win_tokens, const float *x_sqnorm, float *sq_ws,
+                         unsigned long long *keys, float *best_fd, int32_t *best_dst, bool finalize,
                          hipStream_t stream);
 
 // ---- scores + selection in three launches on one stream (lk_fused.hip); windows of at most 64 tokens
@@ -98,11 +104,12 @@ bool xi_seq_applies(const XiPlan &plan, int xi_mode, const float *lse, int batch
 hipError_t launch_xi_seq(const XiArgs &g, int dtype, int head_dim, hipStream_t stream);
 
 // ---- selection (Step 2) ----------------------------------------------------------------------
-// best_key == nullptr: best_fd / best_dst are the inputs.  Otherwise the packed keys of launch_fd_big(...,
-// finalize = false) are, and best_fd / best_dst are written from them on the way (one launch less than finalizing first).
+// keys == nullptr: best_fd / best_dst are the inputs.  Otherwise the packed keys of launch_fd_big(..., finalize = false)
+// are (planned with key_mt row tiles and key_nt stored column tiles per window), and best_fd / best_dst are written from them on the way (one
+// launch less than finalizing first).
 hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int sum_n, const int32_t *cu_vis,
                          const int32_t *win_offsets, const int32_t *win_tokens, const int32_t *win_remove,
-                         const unsigned long long *best_key, float *best_fd, int32_t *best_dst, int32_t *dst,
+                         const unsigned long long *keys, int key_mt, int key_nt, float *best_fd, int32_t *best_dst, int32_t *dst,
                          int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, int32_t *cnt,
                          int32_t *src_rank, hipStream_t stream);
 
@@ -120,8 +127,9 @@ struct RowTensors {
 };
 // mode 0: aggregate in place (out == in, only rows with sources are written)
 // mode 1: compact (copy staying rows to new_index)      mode 2: aggregate + compact
+// x_sqnorm_out (optional, modes 1 and 2): |x|^2 of every output row of the first tensor, fp32
 hipError_t launch_rows(int mode, int dtype, int d, int sum_n, const RowTensors &t, const int32_t *new_index,
                        const int32_t *grp_offsets, const int32_t *grp_src, const float *xi, const int32_t *pos,
-                       int32_t *pos_out, int64_t out_rows, hipStream_t stream);
+                       int32_t *pos_out, float *x_sqnorm_out, int64_t out_rows, hipStream_t stream);
 
 }  // namespace lk

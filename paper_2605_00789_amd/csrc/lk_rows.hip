@@ -16,6 +16,7 @@ struct RowArgs {
   RowTensors t;
   const int32_t *new_index, *grp_offsets, *grp_src, *pos;
   int32_t *pos_out;
+  float *x_sqnorm_out;   // optional: |x|^2 of every output row of tensor 0 (as stored), fp32
   const float *xi;
   int d, sum_n, mode;
   int look_first;     // 1: read new_index before fetching the row (see rows_kernel)
@@ -125,6 +126,10 @@ __global__ __launch_bounds__(ROW_THREADS) void rows_kernel(RowArgs g) {
     row_a1 = in + (int64_t)__shfl(a_l, mm > 1 ? 1 : 0, 64) * ld_in;
   }
 
+  // |x|^2 of the row as it is stored (tensor 0 only, on request): the next stage's feature divergence wants it, and
+  // here the row is in registers anyway.  Same order of summation as the stand-alone pass over X.
+  const bool want_sq = MODE != 0 && which == 0 && g.x_sqnorm_out != nullptr;
+  float sq = 0.f;
   for (int c0 = 0; c0 < n_chunks; c0 += WAVE * ROW_UNROLL) {
     if (c0 > 0) {   // rows longer than one pass: later passes reload
 #pragma unroll
@@ -213,15 +218,28 @@ __global__ __launch_bounds__(ROW_THREADS) void rows_kernel(RowArgs g) {
       const int c = c0 + u * WAVE + lane;
       if (c < n_chunks) *reinterpret_cast<uint4 *>(row_out + (int64_t)c * 16) = v[u];
     }
+    if (want_sq) {
+#pragma unroll
+      for (int u = 0; u < ROW_UNROLL; ++u) {
+        const int c = c0 + u * WAVE + lane;
+        const float t = BYTES == 2 ? sumsq_chunk_bf16(v[u]) : sumsq_chunk_f32(v[u]);
+        sq += (c < n_chunks) ? t : 0.f;
+      }
+    }
+  }
+  if (want_sq) {
+    sq = wave_sum_butterfly(sq);
+    if (lane == 0) g.x_sqnorm_out[out_row] = sq;
   }
   (void)single_pass;
 }
 
 hipError_t launch_rows(int mode, int dtype, int d, int sum_n, const RowTensors &t, const int32_t *new_index,
                        const int32_t *grp_offsets, const int32_t *grp_src, const float *xi, const int32_t *pos,
-                       int32_t *pos_out, int64_t out_rows, hipStream_t stream) {
+                       int32_t *pos_out, float *x_sqnorm_out, int64_t out_rows, hipStream_t stream) {
   if (sum_n == 0) return hipSuccess;
   RowArgs g{};
+  g.x_sqnorm_out = x_sqnorm_out;
   g.t = t; g.new_index = new_index; g.grp_offsets = grp_offsets; g.grp_src = grp_src; g.pos = pos;
   g.pos_out = pos_out; g.xi = xi; g.d = d; g.sum_n = sum_n; g.mode = mode; g.out_rows = out_rows;
   int n_tensors = 0;

@@ -2,19 +2,22 @@
 // the hierarchical schedule, Sec. 3.2.2): here the |A| x |B| x d contraction is compute bound and is run as a
 // classic LDS-tiled MFMA GEMM with the row arg-min fused into its epilogue.
 //
-//   row_norms_kernel : 1/|x| of every token (|x|^2 summed in fp32, inverse root in fp64; |x|^2 itself for the
-//                      distance metrics), and initialisation of the per-row best keys.
+//   row_norms_kernel : |x|^2 of every token (fp32) -- skipped when the caller hands the squared norms in (the kernel
+//                      that wrote X can produce them on the way).
 //   fd_big_kernel    : workgroup tile 96 x 96, four waves, v_mfma_f32_16x16x32_bf16.  Rows are gathered through the
 //                      window's token list; 128-element k-steps travel global -> register ring (2 steps in flight)
 //                      -> double-buffered LDS (rows padded to 272 bytes: conflict-free 16-byte operand reads).
 //                      Every wave accumulates the whole tile over its quarter of each k-step; the partial tiles are
 //                      merged through LDS (fixed order), which also gives a two-level fp32 summation (error of a
 //                      4096-long dot product near 2e-7 relative).
-//                      Epilogue: cos = dot * (1/|a|) * (1/|b|) in fp64, FD = max(1 - cos, 0) rounded to fp32,
-//                      row minimum over the block's columns by shuffles, then one 64-bit integer atomicMin per row
-//                      on the key (FD bits << 32 | B token): integer min is order independent, so the result is
-//                      bit-reproducible and equal FDs go to the earlier B token.
-//   fd_big_finalize_kernel: keys -> best_fd / best_dst.
+//                      Epilogue: cos = dot * (1/|a|) * (1/|b|) in fp64 (inverse roots in fp64, once per tile row and
+//                      column), FD = max(1 - cos, 0) rounded to fp32, row minimum over the tile's columns by shuffles
+//                      and an LDS integer min on the key (FD bits << 32 | B token): integer min is order independent,
+//                      so the result is bit-reproducible and equal FDs go to the earlier B token.  With up to four
+//                      column tiles per window the tile's key of every row is stored per column tile and whoever
+//                      reads the scores takes the minimum over them (no atomics on global memory, nothing to
+//                      initialise); with more, the column tiles meet in one key per row by a 64-bit atomicMin.
+//   fd_big_finalize_kernel: keys -> best_fd / best_dst (the selection kernels can read the keys themselves).
 #include "lk_common.h"
 #include "lk_launch.h"
 
@@ -30,15 +33,19 @@ struct BigArgs {
   int64_t ldx;
   int d, n_windows, sum_n;
   const int32_t *win_offsets, *win_tokens;
-  double *rnorm;                 // [sum_n]  1 / max(|x|, 1e-12)  (distance metrics: |x|^2)
-  unsigned long long *best_key;  // [sum_n]
+  const float *sq;               // [sum_n] |x|^2 of every token (fp32)
+  float *sq_out;                 // row_norms_kernel: where it writes them
+  unsigned long long *cand;      // [nt_store][sum_n]: per column tile, the best key of the A row at every list position
+  int nt_store;                  // nt: every column tile stores its own keys; 1: all column tiles of a window meet in one
+                                 // key per position by atomicMin (the keys are reset first)
+  int reset_keys;                // row_norms_kernel: also reset the keys
   float *best_fd;
   int32_t *best_dst;
   int mt, nt;
   int metric;                    // 0: 1 - cos, 1: |a - b|, 2: |a - b|^2
 };
 
-// ---- 1/|x| per token (|x|^2 summed in fp32); also resets the keys -------------------------------------------------
+// ---- |x|^2 per token, summed in fp32 ----------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void row_norms_kernel(BigArgs g) {
   const int lane = threadIdx.x & 63;
   const int tok = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -56,31 +63,27 @@ __global__ __launch_bounds__(256) void row_norms_kernel(BigArgs g) {
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int c = c0 + u * 64 + lane;
-      const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-      float t = 0.f;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float lo = __uint_as_float(w[q] << 16), hi = __uint_as_float(w[q] & 0xffff0000u);
-        t = fmaf(lo, lo, t);
-        t = fmaf(hi, hi, t);
-      }
+      const float t = sumsq_chunk_bf16(v[u]);
       s += (c < n_chunks) ? t : 0.f;
     }
   }
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+  s = wave_sum_butterfly(s);
   if (lane == 0) {
-    // the only fp64 sqrt/div of the cosine path: once per token
-    g.rnorm[tok] = g.metric == 0 ? 1.0 / fmax(sqrt((double)s), 1e-12) : (double)s;
-    g.best_key[tok] = ~0ull;
+    g.sq_out[tok] = s;
+    if (g.reset_keys) g.cand[tok] = ~0ull;
   }
+}
+
+__global__ __launch_bounds__(256) void reset_keys_kernel(BigArgs g) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < g.sum_n) g.cand[i] = ~0ull;
 }
 
 // Workgroup tile 96 x 96, four waves.  The waves do NOT split the tile: each one accumulates the whole 96 x 96
 // block (6 x 6 MFMA blocks of 16 x 16) over its own quarter of every 128-element k-step.  Per MFMA this halves the
 // LDS operand traffic of a 2 x 2 wave arrangement (48 flop per LDS byte instead of 24), and the four partial sums
 // give a two-level fp32 summation for free.  The partial tiles are merged through LDS at the end.
-constexpr int BIG_TM = 96;
+constexpr int BIG_TM = FD_BIG_TILE;
 constexpr int BIG_NB = BIG_TM / 16;            // 6 blocks per edge
 constexpr int BIG_OWN = BIG_NB * BIG_NB / 4;   // 9 blocks per wave in the epilogue
 constexpr int BIG_STAGE = 2 * BIG_TM * BIG_PITCH;
@@ -129,17 +132,17 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
     offa[p] = (uint32_t)ta * (uint32_t)g.ldx * 2u + (uint32_t)schunk * 16u;
     offb[p] = (uint32_t)tb * (uint32_t)g.ldx * 2u + (uint32_t)schunk * 16u;
   }
-  // token and 1/|x| of the tile row / column this thread publishes for the epilogue (threads 0..191), fetched now so
+  // token and |x|^2 of the tile row / column this thread publishes for the epilogue (threads 0..191), fetched now so
   // that the latency hides behind the k loop
   int e_tok = -1;
-  double e_rn = 0.0;
+  float e_sq = 0.f;
   if (tid < 2 * BIG_TM) {
     const bool is_b = tid >= BIG_TM;
     const int l = (is_b ? col0 : row0) + (is_b ? tid - BIG_TM : tid);
     const int lim = is_b ? nB : nA;
     const int t = g.win_tokens[off + 2 * (l < lim ? l : lim - 1) + (is_b ? 1 : 0)];
     const bool ok = l < lim && (unsigned)t < (unsigned)g.sum_n;
-    e_rn = g.rnorm[ok ? t : 0];
+    e_sq = g.sq[ok ? t : 0];
     e_tok = ok ? t : -1;
   }
 
@@ -251,7 +254,11 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
   int *e_token = reinterpret_cast<int *>(lds + 2 * BIG_TM * 8);   // [96] row tokens then [96] col tokens
   float *xbuf = reinterpret_cast<float *>(lds + 4096);            // [4 waves][12 blocks][256 floats]
   unsigned long long *row_key = reinterpret_cast<unsigned long long *>(lds + 2 * BIG_TM * 8 + 2 * BIG_TM * 4);   // [96]
-  if (tid < 2 * BIG_TM) { e_rnorm[tid] = e_rn; e_token[tid] = e_tok; }
+  if (tid < 2 * BIG_TM) {
+    // the only fp64 sqrt/div of the cosine path: once per tile row and column
+    e_rnorm[tid] = g.metric == 0 ? 1.0 / fmax(sqrt((double)e_sq), 1e-12) : (double)e_sq;
+    e_token[tid] = e_tok;
+  }
   if (tid < BIG_TM) row_key[tid] = ~0ull;
   // Three rounds of 12 blocks: every wave leaves its partials of the round's blocks in LDS, the owner of a block
   // (wave w owns blocks 12 t + 3 w + 0..2 of round t) adds the four partials in a fixed order.  Register indices
@@ -331,23 +338,33 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
     }
   }
   __syncthreads();
-  // one global atomic per row and tile; integer min is order independent, so the result does not depend on which
-  // tile arrives first
-  if (tid < BIG_TM) {
-    const unsigned long long key = row_key[tid];
-    const int ta = e_token[tid];
-    if (ta >= 0 && key != ~0ull) atomicMin(&g.best_key[ta], key);
+  // the tile's best key of every row, filed under the row's position in the window list and this column tile: the
+  // reader takes the minimum over the window's column tiles (integer min: equal FDs go to the earlier B token)
+  // With many column tiles per window that minimum is taken here instead, by one integer atomicMin per row and tile
+  // on a single key per position (order independent, so still bit-reproducible).
+  if (tid < BIG_TM && row0 + tid < nA) {
+    const size_t pos = (size_t)(off + 2 * (row0 + tid));
+    if (g.nt_store > 1 || g.nt == 1) g.cand[(size_t)nt * (size_t)g.sum_n + pos] = row_key[tid];
+    else if (row_key[tid] != ~0ull) atomicMin(&g.cand[pos], row_key[tid]);
   }
 }
 
-// Keys -> best_fd / best_dst for every token.  A token no key was offered for (B nodes, A nodes of windows without
-// a B node, rows of NaNs) gets +inf / -1.
-__global__ __launch_bounds__(256) void fd_big_finalize_kernel(BigArgs g) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= g.sum_n) return;
-  const unsigned long long key = g.best_key[i];
-  g.best_fd[i] = key == ~0ull ? __uint_as_float(0x7f800000u) : __uint_as_float((unsigned)(key >> 32));
-  g.best_dst[i] = key == ~0ull ? -1 : (int)(key & 0xffffffffu);
+// Keys -> best_fd / best_dst for every token, window by window (the keys are filed by list position).  A token no
+// key was offered for (B nodes, A nodes of windows without a B node, rows of NaNs, rows beyond the caller's window
+// bound) gets +inf / -1.
+__global__ __launch_bounds__(256) void fd_big_finalize_kernel(BigArgs g, int chunks_per_window) {
+  const int w = blockIdx.x / chunks_per_window, c = blockIdx.x - w * chunks_per_window;
+  const int off = g.win_offsets[w];
+  const int v = g.win_offsets[w + 1] - off;
+  const int n_col = fd_big_col_tiles(v >> 1, g.nt_store);
+  for (int t = c * 256 + (int)threadIdx.x; t < v; t += chunks_per_window * 256) {
+    const int tok = g.win_tokens[off + t];
+    if ((unsigned)tok >= (unsigned)g.sum_n) continue;
+    const bool scored = !(t & 1) && (t >> 1) < g.mt * FD_BIG_TILE;
+    const unsigned long long key = scored ? fd_big_best_key(g.cand, g.sum_n, off + t, n_col) : ~0ull;
+    g.best_fd[tok] = key == ~0ull ? __uint_as_float(0x7f800000u) : __uint_as_float((unsigned)(key >> 32));
+    g.best_dst[tok] = key == ~0ull ? -1 : (int)(key & 0xffffffffu);
+  }
 }
 
 FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n) {
@@ -357,24 +374,36 @@ FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n) {
   p.mt = (maxA + BIG_TM - 1) / BIG_TM;
   p.nt = maxB > 0 ? (maxB + BIG_TM - 1) / BIG_TM : 1;
   p.metric = 0;
-  p.norm_floats = (size_t)sum_n * 2;   // doubles
-  p.key_bytes = (size_t)sum_n * 8;
+  p.max_window = max_window_tokens;
+  p.norm_floats = (size_t)sum_n;
+  p.nt_store = p.nt <= FD_BIG_KEYS_PER_TILE_MAX_NT ? p.nt : 1;
+  p.key_bytes = (size_t)sum_n * 8 * (size_t)p.nt_store;
   return p;
 }
 
 hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
-                         const int32_t *win_offsets, const int32_t *win_tokens, double *rnorm,
-                         unsigned long long *best_key, float *best_fd, int32_t *best_dst, bool finalize,
+                         const int32_t *win_offsets, const int32_t *win_tokens, const float *x_sqnorm, float *sq_ws,
+                         unsigned long long *keys, float *best_fd, int32_t *best_dst, bool finalize,
                          hipStream_t stream) {
   if (n_windows == 0 || sum_n == 0) return hipSuccess;
   BigArgs g{};
   g.X = X; g.ldx = ldx; g.d = d; g.n_windows = n_windows; g.sum_n = sum_n;
   g.win_offsets = win_offsets; g.win_tokens = win_tokens;
-  g.rnorm = rnorm; g.best_key = best_key; g.best_fd = best_fd; g.best_dst = best_dst;
+  g.cand = keys; g.best_fd = best_fd; g.best_dst = best_dst;
   g.mt = plan.mt; g.nt = plan.nt; g.metric = plan.metric;
-  hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((sum_n + 3) / 4)), dim3(256), 0, stream, g);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  g.sq = x_sqnorm ? x_sqnorm : sq_ws; g.sq_out = sq_ws;
+  g.nt_store = plan.nt_store;
+  g.reset_keys = plan.nt_store == 1 && plan.nt > 1;   // one key per position, reached by atomicMin: start from all-ones
+  hipError_t e;
+  if (!x_sqnorm) {   // nobody computed the squared norms on the way: one pass over X (which also resets the keys)
+    hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((sum_n + 3) / 4)), dim3(256), 0, stream, g);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  } else if (g.reset_keys) {
+    hipLaunchKernelGGL(reset_keys_kernel, dim3((unsigned)((sum_n + 255) / 256)), dim3(256), 0, stream, g);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   const unsigned n_tiles = (unsigned)(n_windows * plan.mt * plan.nt);
   const unsigned grid = (n_tiles + 7u) / 8u * 8u;   // whole rounds over the XCDs; surplus workgroups exit at once
   constexpr size_t lds = (size_t)2 * BIG_STAGE;      // 102 KB: above the 64 KB default, the attribute below allows it
@@ -390,7 +419,8 @@ hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int 
   hipLaunchKernelGGL(fd_big_kernel, dim3(grid), dim3(BIG_THREADS), lds, stream, g);
   e = hipGetLastError();
   if (e != hipSuccess || !finalize) return e;   // without it the caller's selection reads the keys
-  hipLaunchKernelGGL(fd_big_finalize_kernel, dim3((unsigned)((sum_n + 255) / 256)), dim3(256), 0, stream, g);
+  const int cpw = (plan.max_window + 255) / 256 > 0 ? (plan.max_window + 255) / 256 : 1;
+  hipLaunchKernelGGL(fd_big_finalize_kernel, dim3((unsigned)(n_windows * cpw)), dim3(256), 0, stream, g, cpw);
   return hipGetLastError();
 }
 

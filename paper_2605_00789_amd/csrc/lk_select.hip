@@ -19,17 +19,19 @@ struct SelArgs {
   const int32_t *cu_vis, *win_offsets, *win_tokens, *win_remove;
   float *best_fd;            // inputs of the selection -- or, when best_key is given, outputs derived from the keys
   int32_t *best_dst;
-  const unsigned long long *best_key;   // optional: (FD bits << 32 | B token) per A token, all-ones where nothing was offered
+  const unsigned long long *best_key;   // optional: packed keys of the tiled FD kernel, [column tile][list position]
+  int key_mt, key_nt;                   // tiles per window that kernel was planned with
   int32_t *dst, *new_index, *grp_offsets, *grp_src, *cu_vis_out, *cnt, *src_rank;
   int cap;   // power of two >= the largest |A|
 };
 
 
-// Score and proposal of token `tok` (a valid index): from best_fd / best_dst, or from the packed key the tiled FD
-// kernel leaves per A token.
-__device__ __forceinline__ void proposal_of(const SelArgs &g, int tok, float &fd, int &prop) {
+// Score and proposal of the A node at list position `pos`, local position `la` (token `tok`, a valid index): from
+// best_fd / best_dst, or from the packed keys the tiled FD kernel leaves per column tile (n_col of them for this window).
+__device__ __forceinline__ void proposal_of(const SelArgs &g, int tok, int pos, int la, int n_col, float &fd, int &prop) {
   if (g.best_key) {
-    const unsigned long long key = g.best_key[tok];
+    const unsigned long long key =
+        la < g.key_mt * FD_BIG_TILE ? fd_big_best_key(g.best_key, g.sum_n, pos, n_col) : ~0ull;   // else: beyond the tiles
     fd = key == ~0ull ? __uint_as_float(0x7f800000u) : __uint_as_float((unsigned)(key >> 32));
     prop = key == ~0ull ? -1 : (int)(key & 0xffffffffu);
   } else {
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(COUNT_MAX_A * SEGS) void select_window_kernel(SelAr
   if (!has_b || (unsigned)b_tok >= (unsigned)g.sum_n) b_tok = -1;
   float fd;
   int prop;   // the proposal of this A node, or the first B node of the window
-  proposal_of(g, a_tok >= 0 ? a_tok : 0, fd, prop);
+  proposal_of(g, a_tok >= 0 ? a_tok : 0, off + 2 * (has_a ? la : 0), has_a ? la : 0, fd_big_col_tiles(nB, g.key_nt), fd, prop);
   if (seg == 0) {
     publish(g, a_tok, fd, prop);
     publish(g, b_tok, __uint_as_float(0x7f800000u), -1);
@@ -201,7 +203,8 @@ __global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelA
     if (MODE == 0) {
       float fd;
       int unused;
-      proposal_of(g, ok ? tok : 0, fd, unused);
+      const int lc = la < nA ? la : nA - 1;
+      proposal_of(g, ok ? tok : 0, off + 2 * lc, lc, fd_big_col_tiles(nB, g.key_nt), fd, unused);
       if (!ok || !(fd >= 0.f)) fd = __uint_as_float(0x7f800000u);   // NaN or negative never wins
       val = f32_order_key(fd);
     } else {
@@ -221,7 +224,7 @@ __global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelA
   int prop = -1;
   if (MODE == 0 && seg == 0) {   // the proposal of this A node, or the first B node of the window
     float fd;
-    proposal_of(g, a_tok >= 0 ? a_tok : 0, fd, prop);
+    proposal_of(g, a_tok >= 0 ? a_tok : 0, off + 2 * (has_a ? la : 0), has_a ? la : 0, fd_big_col_tiles(nB, g.key_nt), fd, prop);
     publish(g, a_tok, fd, prop);
     publish(g, b_tok, __uint_as_float(0x7f800000u), -1);
     const int first_b = g.win_tokens[off + (nB > 0 ? 1 : 0)];
@@ -435,11 +438,11 @@ hipError_t launch_select_scan_heads(int batch, int sum_n, const int32_t *cu_vis,
 
 hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int sum_n, const int32_t *cu_vis,
                          const int32_t *win_offsets, const int32_t *win_tokens, const int32_t *win_remove,
-                         const unsigned long long *best_key, float *best_fd, int32_t *best_dst, int32_t *dst,
-                         int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, int32_t *cnt,
-                         int32_t *src_rank, hipStream_t stream) {
+                         const unsigned long long *keys, int key_mt, int key_nt, float *best_fd, int32_t *best_dst,
+                         int32_t *dst, int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out,
+                         int32_t *cnt, int32_t *src_rank, hipStream_t stream) {
   SelArgs g{};
-  g.best_key = best_key;
+  g.best_key = keys; g.key_mt = key_mt; g.key_nt = key_nt;
   g.n_windows = n_windows; g.batch = batch; g.sum_n = sum_n;
   g.cu_vis = cu_vis; g.win_offsets = win_offsets; g.win_tokens = win_tokens; g.win_remove = win_remove;
   g.best_fd = best_fd; g.best_dst = best_dst;

@@ -53,6 +53,7 @@ class StageBuffers:
     K_out: torch.Tensor
     V_out: torch.Tensor
     pos_out: torch.Tensor
+    x_sq_out: torch.Tensor     # |x|^2 of the rows of X_out: the next stage's feature divergence takes it as given
 
 
 class CompressionPipeline:
@@ -99,7 +100,8 @@ class CompressionPipeline:
                 X_out=torch.empty(sum_out, d, dtype=self.tdtype, device=dev),
                 K_out=torch.empty(sum_out, d, dtype=self.tdtype, device=dev),
                 V_out=torch.empty(sum_out, d, dtype=self.tdtype, device=dev),
-                pos_out=torch.empty(sum_out, **i32))
+                pos_out=torch.empty(sum_out, **i32),
+                x_sq_out=torch.empty(max(sum_out, 1), dtype=torch.float32, device=dev))
             self.stages.append(st)
             n_in = n_out
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
@@ -116,12 +118,13 @@ class CompressionPipeline:
     # one stage; inputs are device tensors of this stage's shape
     def run_stage(self, s: int, X, K, V, Q, pos, *, xi_mode=B.XI_TEXT_QUERY, lse=None, softmax_scale=0.0,
                   xi_given: Optional[torch.Tensor] = None, score_K=None, stream=None, windows_ready=False,
-                  prepare_next=False):
+                  prepare_next=False, x_sqnorm: Optional[torch.Tensor] = None):
         """score_K: keys of the xi contraction when they are not the K rows being merged
         (vision-query mode: Q holds the vision queries, score_K the prompt keys).
         windows_ready: the window lists of this stage were already built on the second helper stream
         (by the previous stage's prepare_next); prepare_next: build the next stage's windows while this
-        stage's rows are being merged (they only need pos and new_index, not the merged rows)."""
+        stage's rows are being merged (they only need pos and new_index, not the merged rows).
+        x_sqnorm: |x|^2 of the rows of X when X is the previous stage's X_out (that stage's x_sq_out)."""
         st = self.stages[s]
         p = st.problem
         main = torch.cuda.current_stream() if stream is None else stream
@@ -144,12 +147,13 @@ class CompressionPipeline:
         if one_stream:
             B.lightkv_score_select(p, X, Q, K if score_K is None else score_K, xi, st.best_fd, st.best_dst, st.dst,
                                    st.new_index, st.grp_offsets, st.grp_src, st.cu_vis_out, self.ws, xi_mode=xi_mode,
-                                   lse=lse, softmax_scale=softmax_scale, stream=main)
+                                   lse=lse, softmax_scale=softmax_scale, x_sqnorm=x_sqnorm, stream=main)
         elif self.fused:   # FD half + selection
             B.lightkv_score_select(p, X, None, None, xi, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets,
-                                   st.grp_src, st.cu_vis_out, self.ws, xi_mode=B.XI_GIVEN, stream=main)
+                                   st.grp_src, st.cu_vis_out, self.ws, xi_mode=B.XI_GIVEN, x_sqnorm=x_sqnorm, stream=main)
         else:
-            B.lightkv_score(p, X, None, None, xi, st.best_fd, st.best_dst, self.ws, xi_mode=B.XI_GIVEN, stream=main)
+            B.lightkv_score(p, X, None, None, xi, st.best_fd, st.best_dst, self.ws, xi_mode=B.XI_GIVEN,
+                            x_sqnorm=x_sqnorm, stream=main)
             B.lightkv_select(p, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets, st.grp_src,
                              st.cu_vis_out, self.ws, stream=main)
         if prepare_next and self.fused and s + 1 < len(self.stages):
@@ -165,14 +169,14 @@ class CompressionPipeline:
         stream = main
         if self.fused:
             B.lightkv_aggregate_compact(p, st.new_index, st.grp_offsets, st.grp_src, xi, X, K, V, pos, st.X_out,
-                                        st.K_out, st.V_out, st.pos_out, stream=stream)
+                                        st.K_out, st.V_out, st.pos_out, x_sqnorm_out=st.x_sq_out, stream=stream)
         else:
             n = X.shape[0]
             tx, tk, tv = (t[:n] for t in self.tmp)
             tx.copy_(X); tk.copy_(K); tv.copy_(V)
             B.lightkv_aggregate(p, st.grp_offsets, st.grp_src, xi, tx, tk, tv, stream=stream)
             B.lightkv_compact(p, st.new_index, tx, tk, tv, pos, st.X_out, st.K_out, st.V_out, st.pos_out,
-                              stream=stream)
+                              x_sqnorm_out=st.x_sq_out, stream=stream)
         return st
 
     def run(self, X, K, V, Q, pos, stream=None):
@@ -181,7 +185,7 @@ class CompressionPipeline:
         main = torch.cuda.current_stream() if stream is None else stream
         for s in range(len(self.stages)):
             st = self.run_stage(s, X, K, V, Q, pos, stream=main, windows_ready=(s > 0 and self.fused),
-                                prepare_next=True)
+                                prepare_next=True, x_sqnorm=(st.x_sq_out if st is not None else None))
             X, K, V, pos = st.X_out, st.K_out, st.V_out, st.pos_out
         main.wait_stream(self.side2)   # nothing is left running on a helper stream when run() returns
         return st

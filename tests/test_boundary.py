@@ -97,20 +97,21 @@ def test_entry_points_reject_bad_arguments_before_launch(B):
     p = _problem(B)
     _, ws = _ws_size(B, p)
     # score: NULL outputs, misaligned X, short row stride, bad mode, missing workspace
-    args = lambda **o: [o.get("p", C.byref(p)), o.get("X", fake), o.get("ldx", 64), fake, 64, 32, fake, 64, 32,
+    args = lambda **o: [o.get("p", C.byref(p)), o.get("X", fake), o.get("ldx", 64), o.get("sq", None), fake, 64, 32, fake, 64, 32,
                         o.get("mode", 0), o.get("lse", None), 0.0, o.get("xi", fake), fake, fake,
                         o.get("ws", fake), o.get("wsb", ws), None]
     assert lib.lightkv_score(*args(xi=None)) == 1
     assert lib.lightkv_score(*args(X=C.c_void_p(0x1008))) == 5
     assert lib.lightkv_score(*args(ldx=32)) == 2
     assert lib.lightkv_score(*args(ldx=68)) == 5
+    assert lib.lightkv_score(*args(sq=C.c_void_p(0x1002))) == 5                  # misaligned squared norms
     assert lib.lightkv_score(*args(mode=3)) == 5
     assert lib.lightkv_score(*args(mode=1)) == 1                                 # vision-query needs lse
     assert lib.lightkv_score(*args(ws=None)) == 6
     assert lib.lightkv_score(*args(wsb=ws - 1)) == 6
     assert lib.lightkv_score(*args(ws=C.c_void_p(0x1010))) == 6                  # workspace alignment
     # score_select: the union of both argument lists
-    ss = lambda **o: [C.byref(p), o.get("X", fake), 64, fake, 64, 32, fake, 64, 32, 0, None, 0.0, fake, fake, fake,
+    ss = lambda **o: [C.byref(p), o.get("X", fake), 64, None, fake, 64, 32, fake, 64, 32, 0, None, 0.0, fake, fake, fake,
                       o.get("dst", fake), fake, fake, fake, fake, o.get("ws", fake), o.get("wsb", ws), None]
     assert lib.lightkv_score_select(*ss(X=None)) == 1
     assert lib.lightkv_score_select(*ss(dst=None)) == 1
@@ -122,11 +123,12 @@ def test_entry_points_reject_bad_arguments_before_launch(B):
     assert lib.lightkv_aggregate(C.byref(p), None, fake, fake, fake, 64, fake, 64, fake, 64, None) == 1
     assert lib.lightkv_aggregate(C.byref(p), fake, fake, fake, fake, 8, fake, 64, fake, 64, None) == 2
     other = C.c_void_p(0x100000)
-    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, fake, None, None, None, 8, None) == 2   # in == out
-    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, None, None, None, None, 8, None) == 1   # out missing
-    assert lib.lightkv_compact(C.byref(p), None, fake, 64, None, 0, None, 0, None, other, None, None, None, 8, None) == 1
-    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, fake, other, None, None, None, 8, None) == 1  # pos without pos_out
-    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, C.c_void_p(0x1100), None, None, None, 8, None) == 2  # overlap
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, fake, None, None, None, None, 8, None) == 2   # in == out
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, None, None, None, None, None, 8, None) == 1   # out missing
+    assert lib.lightkv_compact(C.byref(p), None, fake, 64, None, 0, None, 0, None, other, None, None, None, None, 8, None) == 1
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, fake, other, None, None, None, None, 8, None) == 1  # pos without pos_out
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, C.c_void_p(0x1100), None, None, None, None, 8, None) == 2  # overlap
+    assert lib.lightkv_compact(C.byref(p), fake, None, 0, fake, 64, None, 0, None, None, other, None, None, other, 8, None) == 1  # norms of X without X
     # build_windows
     hcu = np.array([0, 8], dtype=np.int32)
     hp = C.c_void_p(hcu.ctypes.data)

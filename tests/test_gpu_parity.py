@@ -389,6 +389,41 @@ def test_build_windows_matches_oracle(case):
         np.testing.assert_array_equal(wt2.cpu().numpy()[:len(rt2)], rt2)
 
 
+@pytest.mark.parametrize("cfg", [2, 5])
+def test_row_norms_from_the_merge_equal_a_pass_over_the_rows(cfg):
+    """lightkv_aggregate_compact (and lightkv_compact) can leave |x|^2 of the rows they write; the next stage's
+    lightkv_score takes them instead of computing them.  They are the squared norms of the rows as stored, and a
+    schedule that hands them on gives bit for bit what the stage-by-stage calls without them give (config 2: one
+    window on the matrix-core path in stage 3; config 5: 64 and 16 windows on it in stages 2 and 3)."""
+    from workloads import make_workload
+    from parity import to_dev, from_dev
+    from oracle import lightkv_oracle as O
+    from paper_2605_00789_amd import CompressionPipeline
+    wl = make_workload(cfg)
+    kw = dict(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, tiles=wl.tiles,
+              grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt, windows_per_axis=wl.windows_per_axis,
+              targets=wl.targets)
+    X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+    pos = torch.from_numpy(wl.pos).cuda()
+    names = ("X_out", "K_out", "V_out", "pos_out", "dst", "new_index", "grp_offsets", "xi", "best_fd", "best_dst")
+    for fused in (True, False):
+        handed = CompressionPipeline(fused=fused, **kw)
+        handed.run(X, K, V, Q, pos)                       # every stage after the first gets the previous x_sq_out
+        plain = CompressionPipeline(fused=fused, **kw)
+        Xi, Ki, Vi, pi = X, K, V, pos
+        for s_ in range(wl.stages):
+            st_ = plain.run_stage(s_, Xi, Ki, Vi, Q, pi)  # x_sqnorm not given: the library makes its own pass
+            Xi, Ki, Vi, pi = st_.X_out, st_.K_out, st_.V_out, st_.pos_out
+        torch.cuda.synchronize()
+        for s_, (a, b) in enumerate(zip(handed.stages, plain.stages)):
+            for n in names:
+                assert torch.equal(getattr(a, n), getattr(b, n)), "stage %d: %s differs (fused=%s)" % (s_, n, fused)
+            rows = O.widen(from_dev(a.X_out, wl.dtype), wl.dtype)
+            want = (rows * rows).sum(axis=1)
+            got = a.x_sq_out.cpu().numpy().astype(np.float64)[:len(want)]
+            assert np.all(np.abs(got - want) <= 1e-5 * want + 1e-30), (s_, float(np.abs(got / want - 1).max()))
+
+
 def test_graph_replay_equals_eager_in_the_benchmark_launch_configuration():
     """bench.py times hipGraph replays of the whole 3-stage schedule at N=2880.  Replays must reproduce the eager
     results bit for bit (which test_measured_configs checks against the oracle), also when other work and
