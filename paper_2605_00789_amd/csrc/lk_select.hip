@@ -291,6 +291,7 @@ __global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelA
 constexpr int SCAN_THREADS = 1024;
 constexpr int SCAN_ITEMS = 10;     // tokens per thread and pass (10240 tokens per pass)
 constexpr int FILL_UNROLL = 4;
+constexpr size_t SCAN_LDS_BYTES = (size_t)2 * SCAN_THREADS * SCAN_ITEMS * sizeof(int);   // 80 KB: above the 64 KB default
 
 // WITH_HEADS: the first n_head_blocks workgroups of the launch do something else entirely -- they sum the per-head xi
 // partials (last pass of the xi computation, lk_xi_body.h), which is independent of the scan and as short; the scan
@@ -302,7 +303,9 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
     xi_heads_body(x, blockIdx.x * SCAN_THREADS + threadIdx.x);
     return;
   }
-  __shared__ int kb[SCAN_THREADS * SCAN_ITEMS];   // staying tokens before each token of the pass
+  extern __shared__ int scan_lds[];               // SCAN_LDS_BYTES
+  int *kb = scan_lds;                              // staying tokens before each token of the pass
+  int *gb = scan_lds + SCAN_THREADS * SCAN_ITEMS;  // sources before each token of the pass (= its group's first slot)
   __shared__ int2 wsum[SCAN_THREADS / 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int s_first = g.cu_vis[tid <= g.batch ? tid : g.batch];   // sequence start handled by this thread (first round)
@@ -355,13 +358,16 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
       if (ok) {
         const int keep = d[k] < 0 ? 1 : 0;
         kb[tid * per + k] = ek;
+        gb[tid * per + k] = ec;
         g.new_index[i0 + k] = keep ? ek : -1;
         g.grp_offsets[i0 + k] = ec;
         ek += keep;
         ec += c[k];
       }
     }
-    __syncthreads();
+    // a single pass reads nothing back from global memory (the group starts come from LDS below): then the barrier need
+    // not wait for the stores above
+    if (one_pass) lds_barrier(); else __syncthreads();
     // vision offsets after the step: staying tokens before each sequence start that falls into this pass
     const int pass_end = min(pass_base + pass_tokens, g.sum_n);
     for (int b = tid; b <= g.batch; b += SCAN_THREADS) {
@@ -377,14 +383,15 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
     if (s >= g.sum_n) g.cu_vis_out[b] = keep_base;
   }
   if (tid == 0) g.grp_offsets[g.sum_n] = cnt_base;
-  // inverse map: source a goes to slot grp_offsets[dst[a]] + (its rank among the sources of that target).  The
-  // grp_offsets read here were written by this workgroup before the barrier above.
+  // inverse map: source a goes to slot grp_offsets[dst[a]] + (its rank among the sources of that target).  In a single
+  // pass the group starts of all tokens are in LDS (written before the barrier above); otherwise they are read back
+  // from global memory after the barrier below.
   if (one_pass) {
     const int i0 = tid * per;
 #pragma unroll
     for (int k = 0; k < SCAN_ITEMS; ++k) {   // c[] is free now: it takes the group starts
-      const bool ok = k < per && i0 + k < g.sum_n && d[k] >= 0;
-      c[k] = g.grp_offsets[ok ? d[k] : 0];
+      const bool ok = k < per && i0 + k < g.sum_n && d[k] >= 0 && d[k] < g.sum_n;
+      c[k] = gb[ok ? d[k] : 0];
       d[k] = ok ? d[k] : -1;
     }
 #pragma unroll
@@ -412,6 +419,23 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
 
 
 
+// The scan kernels take more dynamic LDS than the default limit: a property of a kernel as loaded on a device, set once
+// per device.
+static hipError_t allow_scan_lds() {
+  static bool done[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (done[dev]) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(select_scan_kernel<false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)SCAN_LDS_BYTES);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(select_scan_kernel<true>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)SCAN_LDS_BYTES);
+  if (e != hipSuccess) return e;
+  done[dev] = true;
+  return hipSuccess;
+}
+
 hipError_t launch_select_scan(int batch, int sum_n, const int32_t *cu_vis, const int32_t *dst, int32_t *new_index,
                               int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, const int32_t *cnt,
                               const int32_t *src_rank, hipStream_t stream) {
@@ -419,7 +443,9 @@ hipError_t launch_select_scan(int batch, int sum_n, const int32_t *cu_vis, const
   g.batch = batch; g.sum_n = sum_n; g.cu_vis = cu_vis;
   g.dst = const_cast<int32_t *>(dst); g.new_index = new_index; g.grp_offsets = grp_offsets; g.grp_src = grp_src;
   g.cu_vis_out = cu_vis_out; g.cnt = const_cast<int32_t *>(cnt); g.src_rank = const_cast<int32_t *>(src_rank);
-  hipLaunchKernelGGL(select_scan_kernel<false>, dim3(1), dim3(SCAN_THREADS), 0, stream, g, XiArgs{}, 0);
+  hipError_t e = allow_scan_lds();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(select_scan_kernel<false>, dim3(1), dim3(SCAN_THREADS), SCAN_LDS_BYTES, stream, g, XiArgs{}, 0);
   return hipGetLastError();
 }
 
@@ -431,8 +457,10 @@ hipError_t launch_select_scan_heads(int batch, int sum_n, const int32_t *cu_vis,
   g.dst = const_cast<int32_t *>(dst); g.new_index = new_index; g.grp_offsets = grp_offsets; g.grp_src = grp_src;
   g.cu_vis_out = cu_vis_out; g.cnt = const_cast<int32_t *>(cnt); g.src_rank = const_cast<int32_t *>(src_rank);
   const int n_head_blocks = (sum_n + SCAN_THREADS - 1) / SCAN_THREADS;
-  hipLaunchKernelGGL(select_scan_kernel<true>, dim3((unsigned)(n_head_blocks + 1)), dim3(SCAN_THREADS), 0, stream, g, x,
-                     n_head_blocks);
+  hipError_t e = allow_scan_lds();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(select_scan_kernel<true>, dim3((unsigned)(n_head_blocks + 1)), dim3(SCAN_THREADS), SCAN_LDS_BYTES,
+                     stream, g, x, n_head_blocks);
   return hipGetLastError();
 }
 
@@ -469,8 +497,7 @@ hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int su
     }
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(select_scan_kernel<false>, dim3(1), dim3(SCAN_THREADS), 0, stream, g, XiArgs{}, 0);
-  return hipGetLastError();
+  return launch_select_scan(batch, sum_n, cu_vis, dst, new_index, grp_offsets, grp_src, cu_vis_out, cnt, src_rank, stream);
 }
 
 }  // namespace lk
