@@ -118,13 +118,12 @@ struct WsLayout {
 
 bool use_big_fd(const lightkv_problem *p, const Checked &c) {
   // the large-window kernel wants whole pairs of 128-element k-steps; other shapes take the small-tile path
-  if (p->dtype != LIGHTKV_BF16 || p->d % 256 != 0) return false;
-  if (c.max_window >= FD_BIG_MIN_WINDOW) return true;
-  // smaller windows only when there are enough of them to give the chip work (one or four 96 x 96 tiles each): a batch
-  // of 64 windows of 144 tokens takes 109 us per score call this way against 123 us on the small-tile path
-  if (c.max_window < FD_BIG_MIN_WINDOW_MANY) return false;
+  if (p->dtype != LIGHTKV_BF16 || p->d % 256 != 0 || c.max_window < FD_BIG_MIN_WINDOW) return false;
+  // ... and enough 96 x 96 tiles to give the chip work: with few, its long k loop per tile is all latency.  Measured per
+  // step: one window of 387 tokens (9 tiles) 169 us tiled against 165 us on the small-tile path; 64 windows of 144
+  // tokens (64 tiles) 109 against 123 us per score call; one window of 2880 tokens is 225 tiles.
   const FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
-  return (int64_t)p->n_windows * big.mt * big.nt >= FD_BIG_MANY_TILES;
+  return (int64_t)p->n_windows * big.mt * big.nt >= FD_BIG_MIN_TILES;
 }
 
 WsLayout ws_layout(const FdPlan &fd, const FdBigPlan &big, bool use_big, const XiPlan &xi, int sum_n) {

@@ -57,9 +57,8 @@ struct FdBigPlan {
 };
 constexpr int FD_BIG_TILE = 96;            // rows and columns of a workgroup tile
 constexpr int FD_BIG_KEYS_PER_TILE_MAX_NT = 4;   // up to this many column tiles per window, each keeps keys of its own
-constexpr int FD_BIG_MIN_WINDOW = 256;        // windows bounded by fewer tokens use the small-tile path ...
-constexpr int FD_BIG_MIN_WINDOW_MANY = 128;   // ... unless they are at least this large and make up at least
-constexpr int FD_BIG_MANY_TILES = 32;         //     this many workgroup tiles
+constexpr int FD_BIG_MIN_WINDOW = 128;   // windows bounded by fewer tokens use the small-tile path, and so do
+constexpr int FD_BIG_MIN_TILES = 32;     // problems that make up fewer workgroup tiles than this
 FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n);
 hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
                          const int32_t *win_offsets, const int32_t *win_tokens, const float *x_sqnorm, float *sq_ws,
