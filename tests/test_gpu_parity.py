@@ -389,17 +389,23 @@ def test_build_windows_matches_oracle(case):
         np.testing.assert_array_equal(wt2.cpu().numpy()[:len(rt2)], rt2)
 
 
-@pytest.mark.parametrize("cfg", [2, 5])
+@pytest.mark.parametrize("cfg", [2, 5, "two_big_windows"])
 def test_row_norms_from_the_merge_equal_a_pass_over_the_rows(cfg):
     """lightkv_aggregate_compact (and lightkv_compact) can leave |x|^2 of the rows they write; the next stage's
     lightkv_score takes them instead of computing them.  They are the squared norms of the rows as stored, and a
-    schedule that hands them on gives bit for bit what the stage-by-stage calls without them give (config 2: one
-    window on the matrix-core path in stage 3; config 5: 64 and 16 windows on it in stages 2 and 3)."""
-    from workloads import make_workload
+    schedule that hands them on gives bit for bit what the stage-by-stage calls without them give (config 2: small-tile
+    paths only, the norms are ignored; config 5: 64 and 16 windows on the matrix-core path in stages 2 and 3, keys per
+    column tile; two windows of 1200 tokens, twice: five and more column tiles per window, one shared key per row,
+    which is reset by a kernel of its own when the norms pass is skipped)."""
+    from workloads import make_workload, make_custom
     from parity import to_dev, from_dev
     from oracle import lightkv_oracle as O
     from paper_2605_00789_amd import CompressionPipeline
-    wl = make_workload(cfg)
+    if cfg == "two_big_windows":
+        wl = make_custom(name="two_big_windows", seed=77, dtype="bf16", batch=2, grid_h=30, grid_w=40, text_lens=(9, 21),
+                         d=256, heads=2, head_dim=128, n_c=40, structure="grid", windows_per_axis=(1, 1), n_final=700)
+    else:
+        wl = make_workload(cfg)
     kw = dict(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, tiles=wl.tiles,
               grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt, windows_per_axis=wl.windows_per_axis,
               targets=wl.targets)
