@@ -2,12 +2,16 @@
 // for batches: one workgroup owns one (sequence, head) pair and never leaves it, so the softmax statistics of the prompt
 // rows stay in registers and nothing but the per-head result is written.
 //
-//   wave w keeps prompt rows 32w .. 32w+31 of the head in registers (prompts of at most 256 tokens);
-//   the vision keys stream through LDS in blocks of 32 (coalesced 16-byte loads, requested XS_PF blocks ahead, three
-//   LDS slots, one barrier per block; the MFMAs of the next block are issued before the exponentials of this one),
+//   the prompt (at most 256 tokens) is cut into chunks of 32 rows; a wave keeps ONE chunk in registers, and when the
+//   prompt has fewer chunks than the workgroup has waves, several waves (`groups`, up to GMAX) hold the same chunk and
+//   share the keys among them: a visit then covers `groups` key blocks at once and the sequence of visits -- each
+//   ending in a barrier, which is what the kernel's time is made of -- is that much shorter;
+//   the vision keys stream through LDS in blocks of 32 (coalesced 16-byte loads, requested XS_PF visits ahead, three
+//   LDS slots, one barrier per visit; the MFMAs of the next visit are issued before the exponentials of this one),
 //   twice -- forwards, then backwards (the blocks seen last are the ones still in L2):
 //     sweep 1  keys are the MFMA row operand: every lane follows one prompt row and keeps a running (max, sum of
-//              exponentials) over the keys it sees (its half of every block); the two halves merge once at the end;
+//              exponentials) over the keys it sees (its half of every block of its group); the halves, then the groups
+//              in group order, merge once at the end;
 //     sweep 2  prompt rows are the MFMA row operand: exp2(logit * scale - max - log2 sum) summed over the wave's 32
 //              prompt rows inside the lanes, then over the waves in wave order through LDS, gives xi of the block's
 //              32 keys for this head.
@@ -17,31 +21,46 @@
 
 namespace lk {
 
-constexpr int XS_WAVES = 8;
-constexpr int XS_THREADS = XS_WAVES * 64;
-constexpr int XS_PF = 2;   // key blocks in flight between the request and the LDS slots (two more are staged there)
+constexpr int XS_MAX_CHUNKS = 8;   // prompt chunks of 32 rows: prompts of at most 256 tokens
+constexpr int XS_PF = 2;   // visits in flight between the request and the LDS slots (two more are staged there)
 
 template <typename T, int DH> struct XsShape {
   using S = XiStage<T, DH, 64>;
+  // head rows of 256 bytes or more: operands, products and request registers do not fit 128 registers per lane, so
+  // eight waves with 256 each; otherwise sixteen waves with 128
+  static constexpr int WAVES = S::ROW_BYTES >= 256 ? 8 : 16;
+  static constexpr int THREADS = WAVES * 64;
+  static constexpr int WAVES_PER_SIMD = WAVES / 4;
+  static constexpr int GMAX = S::ROW_BYTES >= 256 ? 2 : 4;                     // key blocks per visit, at most (LDS)
+  static constexpr int RED_WAVES = GMAX * 32 / 64;                             // waves that add up a visit's column sums
   static constexpr int CHUNKS = 32 * S::CPR;                                   // 16-byte chunks of a key block
-  static constexpr int PASSES = (CHUNKS + XS_THREADS - 1) / XS_THREADS;        // chunks per thread
+  static constexpr int passes(int groups) { return (groups * CHUNKS + THREADS - 1) / THREADS; }   // per thread and visit
   static constexpr int BLOCK_BYTES = 32 * S::PITCH;
-  // 128 registers per lane except for 512-byte head rows, whose operands alone take that many
-  static constexpr int WAVES_PER_SIMD = S::ROW_BYTES >= 512 ? 2 : 4;
-  static constexpr int LDS = 3 * BLOCK_BYTES + 2 * XS_WAVES * 32 * 4 + XS_WAVES * 32 * 4;
+  static constexpr int SLOT_BYTES = GMAX * BLOCK_BYTES;
+  static constexpr int COLPART_OFF = 3 * SLOT_BYTES;                           // float [2][WAVES][32]
+  static constexpr int ROWBIAS_OFF = COLPART_OFF + 2 * WAVES * 32 * 4;         // float [XS_MAX_CHUNKS][32]
+  static constexpr int STATS_OFF = ROWBIAS_OFF + XS_MAX_CHUNKS * 32 * 4;       // float2 [WAVES][32]
+  static constexpr int LDS = STATS_OFF + WAVES * 32 * 8;
+  // One workgroup per CU: the launch asks for more than half of a CU's LDS whatever the shape uses.  This kernel never
+  // runs alone in a step (the feature-divergence chain runs beside it), and a second workgroup would take the CU's
+  // remaining registers for the whole length of the kernel, leaving the other chain to wait for a CU to drain.
+  static constexpr int LDS_REQUEST = LDS > 84 * 1024 ? LDS : 84 * 1024;
 };
 
 // NEG: the softmax scale is negative (the row extreme is then the minimum of the raw products)
-template <typename T, int DH, bool NEG>
-__global__ __launch_bounds__(XS_THREADS, (XsShape<T, DH>::WAVES_PER_SIMD)) void xi_seq_kernel(XiArgs g) {
+// G: waves that share a prompt chunk = key blocks per visit
+template <typename T, int DH, bool NEG, int G>
+__device__ __forceinline__ void xi_seq_body(const XiArgs &g) {
   using E = Elem<T>;
   using S = XiStage<T, DH, 64>;
   using X = XsShape<T, DH>;
   constexpr int NCH = XiShape<T, DH>::NCH;
-  extern __shared__ __attribute__((aligned(16))) char lds[];   // X::LDS bytes are used; the launch asks for XS_LDS_REQUEST
-  char *kslot = lds;                                                                         // [3][32 * PITCH]
-  float (*colpart)[XS_WAVES][32] = reinterpret_cast<float (*)[XS_WAVES][32]>(lds + 3 * X::BLOCK_BYTES);   // [2]
-  float (*rowbias)[32] = reinterpret_cast<float (*)[32]>(lds + 3 * X::BLOCK_BYTES + 2 * XS_WAVES * 32 * 4);   // [waves]
+  constexpr int WAVES = X::WAVES, THREADS = X::THREADS;
+  extern __shared__ __attribute__((aligned(16))) char lds[];   // X::LDS bytes are used; the launch asks for X::LDS_REQUEST
+  char *kslot = lds;                                                                         // [3][GMAX][32 * PITCH]
+  float (*colpart)[WAVES][32] = reinterpret_cast<float (*)[WAVES][32]>(lds + X::COLPART_OFF);   // [2]
+  float (*rowbias)[32] = reinterpret_cast<float (*)[32]>(lds + X::ROWBIAS_OFF);                 // [chunks]
+  float2 (*stats)[32] = reinterpret_cast<float2 (*)[32]>(lds + X::STATS_OFF);                   // [waves]
 
   const int h = blockIdx.x % g.heads, b = blockIdx.x / g.heads;
   const int t0 = g.cu_txt[b], nT = g.cu_txt[b + 1] - t0;
@@ -49,58 +68,65 @@ __global__ __launch_bounds__(XS_THREADS, (XsShape<T, DH>::WAVES_PER_SIMD)) void 
   if (nV <= 0) return;
   float *out = g.xi_part + (int64_t)h * g.sum_n + v0;
   if (nT <= 0) {   // no prompt tokens: xi is zero before the floor
-    for (int i = threadIdx.x; i < nV; i += XS_THREADS) out[i] = 0.f;
+    for (int i = threadIdx.x; i < nV; i += THREADS) out[i] = 0.f;
     return;
   }
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = lane & 31, half = lane >> 5;
   const float NEG_INF = __uint_as_float(0xff800000u);
   const int64_t vis_ho = (int64_t)h * g.vis_hs, txt_ho = (int64_t)h * g.txt_hs;
-  // an even number of blocks per sweep (the last one may lie entirely past the sequence: masked in sweep 1, not stored
-  // in sweep 2), so that visits come in pairs and the two sets of request registers alternate without a branch
-  const int nblk = ((nV + 63) >> 6) << 1;
-  const int total = 2 * nblk;                      // both sweeps as one sequence of block visits
-  const int n_active = (nT + 31) >> 5;             // waves that own prompt rows
-  const bool active = wave < n_active;
+  // waves -> (group, chunk)
+  constexpr int groups = G, CW = WAVES / G, PASSES = X::passes(G);
+  static_assert(G <= X::GMAX && CW * G == WAVES && CW <= XS_MAX_CHUNKS, "groups x chunks = waves");
+  const int n_active = (nT + 31) >> 5;             // prompt chunks: at most CW (the caller's choice of G)
+  const int chunk = wave % CW, grp = wave / CW;
+  const bool active = chunk < n_active;
+  // a visit covers `groups` key blocks; both sweeps as one sequence of 2 * nvis visits (an even number, so that the
+  // two sets of request registers alternate without a branch).  Blocks past the sequence (in the last visit of sweep 1
+  // = the first of sweep 2 only) are masked in sweep 1 and not stored in sweep 2.
+  const int nvis = ((nV + 31) / 32 + groups - 1) / groups;
+  const int total = 2 * nvis;
   const float c2 = g.scale_log2;
   constexpr bool neg_scale = NEG;
   const float pad = neg_scale ? __uint_as_float(0x7f800000u) : NEG_INF;   // product whose logit is -inf
 
   // this wave's prompt rows (rows past nT repeat the last one; they are given weight zero in sweep 2)
   uint4 q[NCH];
-  if (active) load_half_row<T, DH>(g.txt, t0, wave * 32 + r, nT, g.txt_ts, txt_ho, half, q);
+  if (active) load_half_row<T, DH>(g.txt, t0, chunk * 32 + r, nT, g.txt_ts, txt_ho, half, q);
 
-  // key block `v` (a visit index; the second sweep repeats the first) -> registers, one 16-byte chunk per pass
+  // the key blocks of visit `v` (the second sweep repeats the first, backwards: its first blocks are still in L2)
+  // -> registers, one 16-byte chunk per pass
   auto request = [&](int v, uint4 *dst) {
     v = v < total ? v : total - 1;
-    const int blk = v < nblk ? v : total - 1 - v;   // sweep 2 runs backwards: its first blocks are still in L2
+    const int step = v < nvis ? v : total - 1 - v;
 #pragma unroll
-    for (int p = 0; p < X::PASSES; ++p) {
-      int idx = p * XS_THREADS + threadIdx.x;
-      idx = idx < X::CHUNKS ? idx : X::CHUNKS - 1;
-      const int row = idx / S::CPR, ch = idx % S::CPR;
-      const int key = blk * 32 + row;
+    for (int p = 0; p < PASSES; ++p) {
+      int idx = p * THREADS + threadIdx.x;
+      idx = idx < G * X::CHUNKS ? idx : G * X::CHUNKS - 1;
+      const int row = idx / S::CPR, ch = idx % S::CPR;   // row within the visit's G * 32 keys
+      const int key = step * (G * 32) + row;
       const int tok = v0 + (key < nV ? key : nV - 1);
       dst[p] = ld16(static_cast<const char *>(g.vis) + ((int64_t)tok * g.vis_ts + vis_ho) * E::BYTES + ch * 16);
     }
   };
   auto stage = [&](int slot, const uint4 *src) {
 #pragma unroll
-    for (int p = 0; p < X::PASSES; ++p) {
-      const int idx = p * XS_THREADS + threadIdx.x;
-      if (idx < X::CHUNKS) {
-        const int row = idx / S::CPR, ch = idx % S::CPR;
-        *reinterpret_cast<uint4 *>(kslot + slot * X::BLOCK_BYTES + row * S::PITCH + ch * 16) = src[p];
+    for (int p = 0; p < PASSES; ++p) {
+      const int idx = p * THREADS + threadIdx.x;
+      if (idx < G * X::CHUNKS) {
+        const int row = idx / S::CPR, ch = idx % S::CPR;   // the blocks of a slot lie back to back
+        *reinterpret_cast<uint4 *>(kslot + slot * X::SLOT_BYTES + row * S::PITCH + ch * 16) = src[p];
       }
     }
   };
+  const char *my_blocks = kslot + grp * X::BLOCK_BYTES;   // this wave's block inside a slot
 
-  // visit v: block v + 2 is staged into the third LDS slot, the MFMAs of block v + 1 are issued, and the exponentials
-  // of block v (products already in `cur`) run in their shadow
+  // visit v: the blocks of visit v + 2 are staged into the third LDS slot, the MFMAs of visit v + 1 are issued, and the
+  // exponentials of visit v (products already in `cur`) run in their shadow
   static_assert(XS_PF == 2, "the two sets of request registers alternate with the parity of the visit");
-  uint4 ring[XS_PF][X::PASSES];
+  uint4 ring[XS_PF][PASSES];
   {
-    uint4 f0[X::PASSES], f1[X::PASSES];
+    uint4 f0[PASSES], f1[PASSES];
     request(0, f0);
     request(1, f1);
 #pragma unroll
@@ -110,48 +136,57 @@ __global__ __launch_bounds__(XS_THREADS, (XsShape<T, DH>::WAVES_PER_SIMD)) void 
   }
   __syncthreads();
 
-  float m = NEG_INF, s = 0.f;   // sweep 1: running statistics of prompt row 32 * wave + r over this lane's key rows
-  f32x16 cur;                   // products of the wave's prompt rows with the block of this visit
-  if (active) {                 // block 0, keys as rows
+  float m = NEG_INF, s = 0.f;   // sweep 1: running statistics of prompt row 32 * chunk + r over this lane's key rows
+  f32x16 cur;                   // products of the wave's prompt rows with its block of this visit
+  if (active) {                 // visit 0, keys as rows
     uint4 k[NCH];
-    read_prompt_frag<T, DH>(kslot, r, half, k);
+    read_prompt_frag<T, DH>(my_blocks, r, half, k);
 #pragma unroll
     for (int x = 0; x < 16; ++x) cur[x] = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) E::mma32(k[c], q[c], cur);
   }
 
-  // One visit.  PROD: orientation of the products of block v + 1 issued in this visit (1: keys as rows, sweep 1;
-  // 2: keys as columns, sweep 2; 0: none).  VAL: what happens to the products of block v (1: running statistics,
-  // 2: column sums).  MASK: block v may have rows past the sequence (sweep 1 only).  The compute part is one basic
-  // block: the MFMAs of the next block are spread between the exponentials of this one.
+  // xi of the blocks of sweep-2 visit `pv`: the chunks' partial sums in chunk order
+  auto reduce_columns = [&](int pv) {
+    if (wave >= WAVES - X::RED_WAVES) {
+      const int idx = (wave - (WAVES - X::RED_WAVES)) * 64 + lane;
+      const int gi = idx >> 5, kk = idx & 31;
+      if (gi < groups) {
+        float sum = 0.f;
+        for (int c = 0; c < n_active; ++c) sum += colpart[pv & 1][gi * CW + c][kk];
+        const int key = ((total - 1 - pv) * groups + gi) * 32 + kk;
+        if (key < nV) out[key] = sum;
+      }
+    }
+  };
+
+  // One visit.  PROD: orientation of the products of visit v + 1 issued in this visit (1: keys as rows, sweep 1;
+  // 2: keys as columns, sweep 2; 0: none).  VAL: what happens to the products of visit v (1: running statistics,
+  // 2: column sums).  MASK: the blocks of visit v may have rows past the sequence (sweep 1 only).  The compute part is
+  // one basic block: the MFMAs of the next visit are spread between the exponentials of this one.
   auto visit = [&](int v, uint4 *rg, auto prod_tag, auto val_tag, auto mask_tag) {
     constexpr int PROD = decltype(prod_tag)::value, VAL = decltype(val_tag)::value;
     constexpr bool MASK = decltype(mask_tag)::value;
-    if (VAL == 2 && v > nblk && wave == XS_WAVES - 1 && lane < 32) {
-      // xi of the block visited before this one: the waves' partial sums in wave order
-      const int pb = total - v;   // block of visit v - 1
-      float sum = 0.f;
-      for (int w = 0; w < n_active; ++w) sum += colpart[(v - 1) & 1][w][lane];
-      if (pb * 32 + lane < nV) out[pb * 32 + lane] = sum;
-    }
+    if (VAL == 2 && v > nvis) reduce_columns(v - 1);
     if (active) {
       f32x16 nxt;
       uint4 k[NCH];
-      if (PROD) read_prompt_frag<T, DH>(kslot + ((v + 1) % 3) * X::BLOCK_BYTES, r, half, k);
+      if (PROD) read_prompt_frag<T, DH>(my_blocks + ((v + 1) % 3) * X::SLOT_BYTES, r, half, k);
       float bias[16];
       if (VAL == 2) {
         // -(max + log2 sum) of the prompt row behind every accumulator register; rows past nT: -inf, weight zero
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-          const f32x4 b4 = *reinterpret_cast<const f32x4 *>(&rowbias[wave][8 * gq + 4 * half]);
+          const f32x4 b4 = *reinterpret_cast<const f32x4 *>(&rowbias[chunk][8 * gq + 4 * half]);
 #pragma unroll
           for (int x = 0; x < 4; ++x) bias[4 * gq + x] = b4[x];
         }
       }
       if (VAL == 1 && MASK) {
+        const int key0 = (v * groups + grp) * 32;
 #pragma unroll
-        for (int x = 0; x < 16; ++x) cur[x] = (v * 32 + acc_row(x, lane) < nV) ? cur[x] : pad;
+        for (int x = 0; x < 16; ++x) cur[x] = (key0 + acc_row(x, lane) < nV) ? cur[x] : pad;
       }
       if (PROD) {
 #pragma unroll
@@ -208,9 +243,9 @@ __global__ __launch_bounds__(XS_THREADS, (XsShape<T, DH>::WAVES_PER_SIMD)) void 
       }
       if (PROD) cur = nxt;
     }
-    // block v + 2 goes to the slot whose last readers (the products of block v - 1) passed the barrier that ended
-    // visit v - 2; its registers then take the request for block v + 2 + XS_PF.  This comes after the compute part
-    // because a wave runs in order: waiting here for the data first would hold back work that does not need it.
+    // the blocks of visit v + 2 go to the slot whose last readers (the products of visit v - 1) passed the barrier that
+    // ended visit v - 2; its registers then take the request for visit v + 2 + XS_PF.  This comes after the compute
+    // part because a wave runs in order: waiting here for the data first would hold back work that does not need it.
     stage((v + 2) % 3, rg);
     request(v + 2 + XS_PF, rg);
     lds_barrier();
@@ -221,53 +256,82 @@ __global__ __launch_bounds__(XS_THREADS, (XsShape<T, DH>::WAVES_PER_SIMD)) void 
   const std::false_type no_mask{};
   const std::true_type mask{};
 
+  // between the sweeps: merge the two halves of every prompt row (lower half first in both lanes so that they hold
+  // the same bits), then the groups in group order; sweep 2 reads the rows' biases in accumulator order
+  auto between_sweeps = [&]() {
+    if (active) {
+      const float om = __shfl_xor(m, 32, 64), os = __shfl_xor(s, 32, 64);
+      const float mm = fmaxf(m, om);
+      const float ref = (mm > NEG_INF) ? mm : 0.f;   // a group that saw nothing but masked rows: sum 0, maximum -inf
+      const float lo_m = half ? om : m, lo_s = half ? os : s, hi_m = half ? m : om, hi_s = half ? s : os;
+      const float ss = lo_s * exp2f(lo_m - ref) + hi_s * exp2f(hi_m - ref);
+      if (half == 0) stats[wave][r] = make_float2(mm, ss);
+    }
+    __syncthreads();
+    if (active && grp == 0 && half == 0) {
+      float mm = NEG_INF;   // group 0 saw key 0: finite
+      for (int gi = 0; gi < groups; ++gi) mm = fmaxf(mm, stats[gi * CW + chunk][r].x);
+      float ss = 0.f;
+      for (int gi = 0; gi < groups; ++gi) {
+        const float2 st = stats[gi * CW + chunk][r];
+        ss += st.y * exp2f(st.x - mm);
+      }
+      const bool row_live = chunk * 32 + r < nT;
+      rowbias[chunk][r] = row_live ? -(mm + log2f(ss)) : NEG_INF;
+    }
+    __syncthreads();
+  };
+
+  // visits 0 .. nvis-2: sweep 1; nvis-1: its last (masked; the products of sweep 2 start); nvis .. total-2: sweep 2;
+  // total-1: the last (no more products).  Pairs (even visit, odd visit) use the two sets of request registers in turn.
   int v = 0;
-  for (; v < nblk - 2; v += 2) {
+  for (; v + 2 <= nvis - 1; v += 2) {
     visit(v, ring[0], I1{}, I1{}, no_mask);
     visit(v + 1, ring[1], I1{}, I1{}, no_mask);
   }
-  visit(v, ring[0], I1{}, I1{}, mask);       // the last two blocks of sweep 1 may have rows past the sequence;
-  visit(v + 1, ring[1], I2{}, I1{}, mask);   // the products of sweep 2 start
-  v += 2;
-  // between the sweeps: merge the two halves of every prompt row, lower half first in both lanes so that they hold
-  // the same bits; sweep 2 reads the rows' biases in accumulator order
-  if (active) {
-    const float om = __shfl_xor(m, 32, 64), os = __shfl_xor(s, 32, 64);
-    const float mm = fmaxf(m, om);
-    const float lo_m = half ? om : m, lo_s = half ? os : s, hi_m = half ? m : om, hi_s = half ? s : os;
-    const float ss = lo_s * exp2f(lo_m - mm) + hi_s * exp2f(hi_m - mm);
-    const bool row_live = wave * 32 + r < nT;
-    if (half == 0) rowbias[wave][r] = row_live ? -(mm + log2f(ss)) : NEG_INF;
+  if (nvis - 1 - v == 1) {   // an even number of visits per sweep
+    visit(v, ring[0], I1{}, I1{}, no_mask);
+    visit(v + 1, ring[1], I2{}, I1{}, mask);
+    between_sweeps();
+  } else {                   // an odd number: the pair straddles the sweeps
+    visit(v, ring[0], I2{}, I1{}, mask);
+    between_sweeps();
+    if (nvis == 1) visit(v + 1, ring[1], I0{}, I2{}, no_mask);
+    else visit(v + 1, ring[1], I2{}, I2{}, no_mask);
   }
-  __syncthreads();
-  for (; v < total - 2; v += 2) {
+  v += 2;
+  for (; v + 2 < total; v += 2) {
     visit(v, ring[0], I2{}, I2{}, no_mask);
     visit(v + 1, ring[1], I2{}, I2{}, no_mask);
   }
-  visit(v, ring[0], I2{}, I2{}, no_mask);
-  visit(v + 1, ring[1], I0{}, I2{}, no_mask);
-  if (wave == XS_WAVES - 1 && lane < 32) {
-    const int pb = 0;   // the last visit of sweep 2
-    float sum = 0.f;
-    for (int w = 0; w < n_active; ++w) sum += colpart[(total - 1) & 1][w][lane];
-    if (pb * 32 + lane < nV) out[pb * 32 + lane] = sum;
+  if (v < total) {
+    visit(v, ring[0], I2{}, I2{}, no_mask);
+    visit(v + 1, ring[1], I0{}, I2{}, no_mask);
   }
+  reduce_columns(total - 1);
+}
+
+// Every workgroup takes the largest group count that leaves a wave to each 32-row chunk of ITS prompt.
+template <typename T, int DH, bool NEG>
+__global__ __launch_bounds__((XsShape<T, DH>::THREADS), (XsShape<T, DH>::WAVES_PER_SIMD)) void xi_seq_kernel(XiArgs g) {
+  using X = XsShape<T, DH>;
+  const int b = blockIdx.x / g.heads;
+  const int chunks = (g.cu_txt[b + 1] - g.cu_txt[b] + 31) >> 5;
+  if constexpr (X::GMAX >= 4) {
+    if (chunks * 4 <= X::WAVES) return xi_seq_body<T, DH, NEG, 4>(g);
+  }
+  if (chunks * 2 <= X::WAVES) return xi_seq_body<T, DH, NEG, 2>(g);
+  if constexpr (X::WAVES <= XS_MAX_CHUNKS) xi_seq_body<T, DH, NEG, 1>(g);   // sixteen waves: two groups always fit
 }
 
 bool xi_seq_applies(const XiPlan &plan, int xi_mode, const float *lse, int batch, int heads) {
-  return xi_mode == 0 && lse == nullptr && plan.max_text_tiles > 0 && plan.max_text_tiles * 32 <= XS_WAVES * 32 &&
+  return xi_mode == 0 && lse == nullptr && plan.max_text_tiles > 0 && plan.max_text_tiles <= XS_MAX_CHUNKS &&
          batch * heads >= XI_SEQ_MIN_PAIRS;
 }
 
-// The kernel is launched with more LDS than it uses, so that only ONE workgroup fits a CU: this kernel never runs alone
-// in a step (the feature-divergence chain runs beside it), and two workgroups per CU take every register of the CU for
-// the whole length of the kernel, leaving the other chain to wait for a CU to drain.  With one, xi takes two rounds
-// instead of one, and the step of a batch of 16 is 2 % shorter (472 -> 463 us).
-constexpr size_t XS_LDS_REQUEST = 84 * 1024;
-
 template <typename T, int DH>
 static hipError_t launch_xi_seq_t(const XiArgs &g, hipStream_t stream) {
-  static_assert(XsShape<T, DH>::LDS <= XS_LDS_REQUEST, "the request covers what the kernel uses");
+  constexpr int XS_LDS_REQUEST = XsShape<T, DH>::LDS_REQUEST;
   static bool allowed[64] = {};   // more than the 64 KB default: a property of the kernels as loaded on a device
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
@@ -280,7 +344,7 @@ static hipError_t launch_xi_seq_t(const XiArgs &g, hipStream_t stream) {
     if (e != hipSuccess) return e;
     allowed[dev] = true;
   }
-  const dim3 grid((unsigned)(g.batch * g.heads)), block(XS_THREADS);
+  const dim3 grid((unsigned)(g.batch * g.heads)), block((XsShape<T, DH>::THREADS));
   if (g.scale_log2 < 0.f) hipLaunchKernelGGL((xi_seq_kernel<T, DH, true>), grid, block, XS_LDS_REQUEST, stream, g);
   else hipLaunchKernelGGL((xi_seq_kernel<T, DH, false>), grid, block, XS_LDS_REQUEST, stream, g);
   return hipGetLastError();

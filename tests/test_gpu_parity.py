@@ -244,7 +244,8 @@ def test_xi_variants_given_lse_vision_query_scale_and_head_major_layout():
 def test_xi_of_batches_one_workgroup_per_sequence_and_head():
     """Batches with at least 256 (sequence, head) pairs and prompts of at most 256 tokens take the single-launch xi
     kernel: ragged prompt and vision lengths (1 token, multiples of 32 +- 1, a sequence without a prompt, one without
-    vision tokens), both dtypes, every head size, a negative softmax scale."""
+    vision tokens), both dtypes, every head size, a negative softmax scale, and longest prompts of up to 64, 128 and 256
+    tokens (four, two and one key blocks per visit)."""
     from oracle import lightkv_oracle as O
     from parity import to_dev
     from workloads import f32_to_bf16_bits
@@ -255,7 +256,12 @@ def test_xi_of_batches_one_workgroup_per_sequence_and_head():
              ("bf16", 64, 64, (40, 96, 7, 130), (5, 64, 200, 31), -0.2),
              ("f32", 128, 32, (65, 3), (33, 250), None),
              ("f32", 32, 128, (50, 64, 1, 20, 90, 33, 12, 128), (17, 256, 3, 40, 1, 96, 129, 64), 0.3),
-             ("bf16", 256, 32, (20,), (11,), None))
+             ("bf16", 256, 32, (20,), (11,), None),
+             # shorter prompts: several waves share a prompt chunk and a visit covers two or four key blocks
+             ("bf16", 32, 128, (576, 130, 127, 1, 64, 300, 97, 129), (64, 33, 1, 64, 0, 17, 50, 32), None),
+             ("bf16", 32, 128, (576, 255, 257, 2, 65, 31, 190, 64), (128, 65, 100, 3, 96, 128, 1, 127), -0.1),
+             ("f32", 32, 128, (200, 65, 64, 1, 130, 63, 12, 257), (128, 100, 1, 65, 32, 127, 96, 64), None),
+             ("f32", 64, 64, (129, 40, 577, 3), (64, 1, 33, 50), None))
     for dtype, H, dh, n_vis, n_txt, scale in cases:
         assert len(n_vis) * H >= 256
         d = H * dh
