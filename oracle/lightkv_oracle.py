@@ -17,8 +17,12 @@ What it computes follows the paper's Sec. 3.2.1 (Steps 1-5), Sec. 3.2.2
                  is left unchanged.  Reading used here: every A node proposes its
                  lowest-FD B node, and the r A nodes with the lowest proposals are
                  the ones merged (several A may share one B; exactly r tokens go).
-                 The literal "k globally lowest edges" reading is kept as
-                 `select_edge_topk` for comparison.
+                 The literal reading -- the k lowest-FD edges of the window's
+                 complete bipartite graph, an A node owning as many of them as
+                 rank that low -- is `select_edge_topk` with
+                 `message_passing_edges` / `compress_stage_edges`: every A node
+                 with at least one selected edge leaves, so the number of tokens
+                 that go depends on the data.
   xi             Step 3, Eq. (attention-factor): attention between a vision token
                  and the prompt tokens, summed over heads and prompt tokens.
   message pass   Eq. (message-passing): X_B <- (xi_B + M^T xi_A)^-1 (X_B*xi_B + M^T (X_A*xi_A)),
@@ -270,10 +274,10 @@ def select(best_fd: np.ndarray, best_dst: np.ndarray, win_offsets: np.ndarray,
     return dst
 
 
-def select_edge_topk(X: np.ndarray, win_offsets, win_tokens, win_edges: np.ndarray):
+def select_edge_topk(X: np.ndarray, win_offsets, win_tokens, win_edges: np.ndarray, metric: str = "cosine"):
     """Step 2 read literally: the k lowest-FD EDGES of the window's complete
-    bipartite graph.  Returns a list of (a_token, b_token) edges; an A node may
-    own several edges.  Kept for comparison; not the reading the step uses."""
+    bipartite graph (ties: lower A position, then lower B position).  Returns a
+    list of (a_token, b_token) edges; an A node may own several edges."""
     edges = []
     for wdx in range(len(win_offsets) - 1):
         toks = win_tokens[win_offsets[wdx]:win_offsets[wdx + 1]]
@@ -281,7 +285,7 @@ def select_edge_topk(X: np.ndarray, win_offsets, win_tokens, win_edges: np.ndarr
         k = int(win_edges[wdx])
         if k == 0 or len(B) == 0:
             continue
-        fd = feature_divergence(X[A], X[B])
+        fd = feature_divergence(X[A], X[B], metric)
         cand = sorted(((fd[i, j], i, j) for i in range(len(A)) for j in range(len(B))))
         edges += [(int(A[i]), int(B[j])) for _, i, j in cand[:k]]
     return edges
@@ -328,6 +332,44 @@ def message_passing(Y: np.ndarray, xi: np.ndarray, dst: np.ndarray) -> np.ndarra
     return out
 
 
+def message_passing_edges(Y: np.ndarray, xi: np.ndarray, edges) -> np.ndarray:
+    """Eq. (message-passing) for an adjacency matrix M with any number of ones per
+    row: row b becomes (xi_b Y_b + sum_{a: M[a,b]=1} xi_a Y_a) / (xi_b + sum_{a: M[a,b]=1} xi_a).
+    An A node with several selected edges contributes to each of its B nodes with
+    its full weight.  All reads are of the values before the update."""
+    num = Y * xi[:, None]
+    den = xi.copy()
+    has = np.zeros(Y.shape[0], dtype=bool)
+    for a, b in edges:
+        num[b] += xi[a] * Y[a]
+        den[b] += xi[a]
+        has[b] = True
+    out = Y.copy()
+    out[has] = num[has] / den[has][:, None]
+    return out
+
+
+def edges_csr(n: int, edges) -> Tuple[np.ndarray, np.ndarray]:
+    """Sources of token b under an edge list: grp_src[grp_offsets[b]:grp_offsets[b+1]], ascending."""
+    srcs: List[List[int]] = [[] for _ in range(n)]
+    for a, b in edges:
+        srcs[b].append(a)
+    offs = np.zeros(n + 1, dtype=np.int32)
+    for b in range(n):
+        srcs[b].sort()
+        offs[b + 1] = offs[b] + len(srcs[b])
+    flat = np.array([a for l in srcs for a in l], dtype=np.int32).reshape(-1)
+    return offs, flat
+
+
+def removed_by_edges(n: int, edges) -> np.ndarray:
+    """Steps 4-5 under an edge list: True for every A node with at least one selected edge."""
+    gone = np.zeros(n, dtype=bool)
+    for a, _ in edges:
+        gone[a] = True
+    return gone
+
+
 def compact(Y: np.ndarray, dst: np.ndarray) -> np.ndarray:
     """Steps 4-5: drop merged A rows; R and B rows keep their relative order."""
     return Y[dst < 0]
@@ -367,6 +409,40 @@ def compress_stage(X, K, V, Q, pos, cu_vis, cu_txt, heads, head_dim, win_offsets
         cu_out[b + 1] = cu_out[b] + int(keep[int(cu_vis[b]):int(cu_vis[b + 1])].sum())
     return StageResult(xi, best_fd, best_dst, dst, new_index, go, gs, Xo, Ko, Vo,
                        np.asarray(pos)[keep].astype(np.int32), cu_out)
+
+
+@dataclass
+class EdgeStageResult:
+    xi: np.ndarray
+    edges: list          # (a_token, b_token) pairs
+    gone: np.ndarray     # bool per token
+    new_index: np.ndarray
+    grp_offsets: np.ndarray
+    grp_src: np.ndarray
+    X: np.ndarray
+    K: np.ndarray
+    V: np.ndarray
+    pos: np.ndarray
+    cu_vis: np.ndarray
+
+
+def compress_stage_edges(X, K, V, Q, pos, cu_vis, cu_txt, heads, head_dim, win_offsets, win_tokens,
+                         win_edges, scale=None, lse=None, xi=None, metric: str = "cosine") -> EdgeStageResult:
+    """One whole compression step with Step 2 read literally (k lowest edges per window)."""
+    if xi is None:
+        xi = xi_text_query(Q, K, cu_vis, cu_txt, heads, head_dim, scale=scale, lse=lse)
+    edges = select_edge_topk(X, win_offsets, win_tokens, win_edges, metric)
+    n = X.shape[0]
+    gone = removed_by_edges(n, edges)
+    keep = ~gone
+    new_index = np.where(keep, np.cumsum(keep) - 1, -1).astype(np.int32)
+    go, gs = edges_csr(n, edges)
+    Xo, Ko, Vo = (message_passing_edges(Y, xi, edges)[keep] for Y in (X, K, V))
+    cu_out = np.zeros_like(np.asarray(cu_vis, dtype=np.int32))
+    for b in range(len(cu_vis) - 1):
+        cu_out[b + 1] = cu_out[b] + int(keep[int(cu_vis[b]):int(cu_vis[b + 1])].sum())
+    return EdgeStageResult(xi, edges, gone, new_index, go, gs, Xo, Ko, Vo,
+                           np.asarray(pos)[keep].astype(np.int32), cu_out)
 
 
 def stage_removals(batch: int, n_in: int, n_out: int, windows_per_seq: int) -> np.ndarray:

@@ -400,6 +400,68 @@ def test_message_passing_invariants():
     np.testing.assert_array_equal(O.message_passing(Y, xi, np.full(n, -1, dtype=np.int32)), Y)
 
 
+def test_message_passing_with_several_edges_per_node():
+    """Step 2 read literally lets an A node own several edges; the message-passing equation then adds it, with its
+    full weight, to each of its B nodes."""
+    # worked by hand: A = 0, 2 ; B = 1, 3.  Edges 0->1, 0->3, 2->3.
+    Y = np.array([[2.0, 0.0], [0.0, 4.0], [6.0, 6.0], [1.0, 1.0]])
+    xi = np.array([1.0, 3.0, 2.0, 1.0])
+    edges = [(0, 1), (0, 3), (2, 3)]
+    out = O.message_passing_edges(Y, xi, edges)
+    np.testing.assert_allclose(out[1], [(3 * 0 + 1 * 2) / 4, (3 * 4 + 1 * 0) / 4])
+    np.testing.assert_allclose(out[3], [(1 * 1 + 1 * 2 + 2 * 6) / 4, (1 * 1 + 1 * 0 + 2 * 6) / 4])
+    np.testing.assert_array_equal(out[[0, 2]], Y[[0, 2]])
+    assert O.removed_by_edges(4, edges).tolist() == [True, False, True, False]
+    go, gs = O.edges_csr(4, edges)
+    assert go.tolist() == [0, 0, 1, 1, 3] and gs.tolist() == [0, 0, 2]
+    # the adjacency-matrix form of the equation, written with matrix products
+    rng = np.random.default_rng(12)
+    n, d = 12, 3
+    Y = rng.standard_normal((n, d)); xi = rng.uniform(0.1, 2, n)
+    A, B = np.arange(0, n, 2), np.arange(1, n, 2)
+    M = (rng.random((len(A), len(B))) < 0.3).astype(np.float64)
+    edges = [(int(A[i]), int(B[j])) for i in range(len(A)) for j in range(len(B)) if M[i, j]]
+    XB = (Y[B] * xi[B, None] + M.T @ (Y[A] * xi[A, None])) / (xi[B] + M.T @ xi[A])[:, None]
+    out = O.message_passing_edges(Y, xi, edges)
+    np.testing.assert_allclose(out[B], XB, rtol=1e-13)
+    # one edge per A node: the same result as the single-target form
+    dst = np.full(n, -1, dtype=np.int32)
+    for a in A[:4]:
+        dst[a] = int(rng.choice(B))
+    one = [(int(a), int(dst[a])) for a in A[:4]]
+    np.testing.assert_array_equal(O.message_passing_edges(Y, xi, one), O.message_passing(Y, xi, dst))
+    np.testing.assert_array_equal(O.edges_csr(n, one)[1], O.groups_csr(dst)[1])
+    # convexity and scale invariance hold edge list or not
+    np.testing.assert_allclose(O.message_passing_edges(Y, 7.0 * xi, edges), out, rtol=1e-13)
+    for j, b in enumerate(B):
+        grp = np.vstack([Y[b:b + 1]] + [Y[A[i]:A[i] + 1] for i in range(len(A)) if M[i, j]])
+        assert np.all(out[b] <= grp.max(axis=0) + 1e-12) and np.all(out[b] >= grp.min(axis=0) - 1e-12)
+
+
+def test_edge_stage_counts_depend_on_the_data():
+    """With the k lowest edges, between ceil(k / |B|) and min(k, |A|) tokens leave a window."""
+    rng = np.random.default_rng(8)
+    n, d, H, dh = 24, 8, 2, 4
+    X = rng.standard_normal((n, d)); K = rng.standard_normal((n, d)); V = rng.standard_normal((n, d))
+    Q = rng.standard_normal((5, d))
+    toks = np.arange(n, dtype=np.int32)
+    offs = np.array([0, 12, 24], dtype=np.int32)
+    pos = np.arange(n, dtype=np.int32)
+    k = np.array([9, 4])
+    res = O.compress_stage_edges(X, K, V, Q, pos, np.array([0, n]), np.array([0, 5]), H, dh, offs, toks, k)
+    assert len(res.edges) == 13 and len(set(res.edges)) == 13
+    for w in range(2):
+        gone = int(res.gone[offs[w]:offs[w + 1]].sum())
+        assert -(-int(k[w]) // 6) <= gone <= min(int(k[w]), 6)
+    assert res.X.shape[0] == n - int(res.gone.sum()) == res.cu_vis[1]
+    assert np.all(np.diff(res.pos) > 0)
+    # k = |A| * |B|: every edge is selected, every A node leaves, and each B row is the mean over the whole window
+    full = O.compress_stage_edges(X, K, V, Q, pos, np.array([0, n]), np.array([0, 5]), H, dh, offs, toks,
+                                  np.array([36, 36]), xi=np.ones(n))
+    assert full.gone[0::2].all() and not full.gone[1::2].any()
+    np.testing.assert_allclose(full.X[0], (X[1] + X[0:12:2].sum(axis=0)) / 7, rtol=1e-13)
+
+
 # ---------------------------------------------------------------- storage casts
 def test_storage_roundtrip():
     x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, -2.5, 3.140625, 1e-3])
