@@ -80,10 +80,24 @@ typedef enum {
   LIGHTKV_METRIC_L2SQ = 2        /* |a - b|^2 */
 } lightkv_metric;
 
+/* How Step 2 builds the candidate set T_rho of a window from the FD of its |A| x |B| pairs. */
+typedef enum {
+  /* every A node offers its lowest-FD B node, and the r_w A nodes with the lowest offers are merged: exactly r_w tokens
+     leave the window (the reading all sizes in this header assume). */
+  LIGHTKV_MATCH_BEST_PER_A = 0,
+  /* the sentence of Step 2 taken literally: the win_remove[w] lowest-FD EDGES of the window (ties: lower A position,
+     then lower B position).  An A node may own several of them -- it is averaged into each of those B nodes with its
+     full weight -- and leaves if it owns at least one, so the number of tokens that leave is known only on the
+     device (cu_vis_out): between ceil(k / |B|) and min(k, |A|) per window.  Supported by lightkv_score_select for
+     windows of at most LIGHTKV_EDGE_MAX_WINDOW_TOKENS tokens; see there. */
+  LIGHTKV_MATCH_EDGE_TOPK = 1
+} lightkv_match;
+
 /* Limits of this build. */
 #define LIGHTKV_MAX_WINDOW_TOKENS 4096   /* tokens in one window                    */
 #define LIGHTKV_MAX_SEQ_TOKENS    16384  /* vision tokens in one sequence           */
 #define LIGHTKV_MAX_TEXT_TOKENS   4096   /* prompt tokens in one sequence           */
+#define LIGHTKV_EDGE_MAX_WINDOW_TOKENS 256  /* tokens in one window with LIGHTKV_MATCH_EDGE_TOPK */
 /* Steps of at most this many vision tokens whose windows hold at most 64 tokens: lightkv_score_select runs the xi
    passes inside the launches of the FD chain, on the caller's stream alone (see there). */
 #define LIGHTKV_ONE_STREAM_MAX_TOKENS 1024
@@ -106,6 +120,10 @@ typedef struct lightkv_problem {
                                  0 = take it from h_win_offsets (then required).                 */
   int32_t metric;             /* lightkv_metric; 0 (a zeroed struct) = cosine FD; other values ->
                                  LIGHTKV_ERR_UNSUPPORTED                                          */
+  int32_t match;              /* lightkv_match; 0 (a zeroed struct) = one edge per A node.  With
+                                 LIGHTKV_MATCH_EDGE_TOPK win_remove[w] counts EDGES (0 <= k_w <= |A_w| |B_w|)
+                                 and h_win_remove is required                                     */
+  int32_t reserved;           /* must be 0                                                       */
   const int32_t *h_cu_vis;    /* HOST [batch+1] vision-token offsets, h_cu_vis[0] = 0            */
   const int32_t *h_cu_txt;    /* HOST [batch+1] prompt-token offsets (may be NULL for XI_GIVEN)  */
   const int32_t *cu_vis;      /* device copy of h_cu_vis                                         */
@@ -203,6 +221,17 @@ lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, co
  * if in addition xi is computed and the step has at most LIGHTKV_ONE_STREAM_MAX_TOKENS tokens, the xi passes share the
  * launches of the FD kernels and the whole call is three launches on `stream` (no helper stream).  Otherwise the call
  * is the two calls in sequence.  X must not be NULL; xi_mode GIVEN skips the xi half as in lightkv_score.
+ *
+ * With p->match == LIGHTKV_MATCH_EDGE_TOPK (this call only; lightkv_select alone returns LIGHTKV_ERR_UNSUPPORTED,
+ * because the selection needs the FD of every pair, which never leaves the workspace):
+ *   win_remove[w] = k_w, the number of EDGES taken in window w (device values above |A_w| |B_w| are clamped);
+ *   dst[a]        the B token of a's lowest selected edge, -1 if a owns none (a stays)
+ *   grp_offsets / grp_src   sources of every B token over ALL selected edges, ascending; grp_src needs sum k_w ints
+ *   new_index, cu_vis_out   as above; the number of staying tokens is data dependent -- a caller that needs it on the
+ *                           host reads cu_vis_out back.  lightkv_aggregate_compact / lightkv_compact then write that
+ *                           many rows; size their outputs for sumN - (number of windows with k_w > 0) rows or more.
+ *   best_fd / best_dst      the lowest-FD edge of every A node, selected or not.
+ * The scores are fp32 when they are ranked: pairs whose FD agree to fp32 rounding are ordered by position.
  */
 lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int64_t ldx, const float *x_sqnorm,
                                     const void *Q, int64_t q_tok_stride, int64_t q_head_stride,

@@ -23,5 +23,5 @@ from .binding import (  # noqa: F401
     XI_VISION_QUERY,
     XI_GIVEN,
 )
-from .schedule import removal_counts, windows_per_sequence, max_window_cells  # noqa: F401
-from .pipeline import CompressionPipeline, from_device, to_device  # noqa: F401
+from .schedule import edge_counts, removal_counts, windows_per_sequence, max_window_cells  # noqa: F401
+from .pipeline import CompressionPipeline, EdgeTopKSchedule, from_device, to_device  # noqa: F401

@@ -29,6 +29,7 @@ class _CProblem(C.Structure):
     _fields_ = [
         ("batch", C.c_int32), ("d", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32),
         ("dtype", C.c_int32), ("n_windows", C.c_int32), ("max_window_tokens", C.c_int32), ("metric", C.c_int32),
+        ("match", C.c_int32), ("reserved", C.c_int32),
         ("h_cu_vis", C.c_void_p), ("h_cu_txt", C.c_void_p), ("cu_vis", C.c_void_p), ("cu_txt", C.c_void_p),
         ("win_offsets", C.c_void_p), ("win_tokens", C.c_void_p), ("win_remove", C.c_void_p),
         ("h_win_offsets", C.c_void_p), ("h_win_remove", C.c_void_p),
@@ -113,6 +114,8 @@ def _ld(t: Optional[torch.Tensor]) -> int:
 
 
 METRICS = {"cosine": 0, "euclidean": 1, "l2sq": 2}
+MATCH_BEST_PER_A, MATCH_EDGE_TOPK = 0, 1
+EDGE_MAX_WINDOW_TOKENS = 256   # LIGHTKV_EDGE_MAX_WINDOW_TOKENS
 ONE_STREAM_MAX_TOKENS = 1024   # LIGHTKV_ONE_STREAM_MAX_TOKENS
 
 
@@ -121,7 +124,7 @@ class Problem:
 
     def __init__(self, *, batch, d, heads, head_dim, dtype, h_cu_vis, cu_vis, h_cu_txt=None, cu_txt=None,
                  n_windows=0, max_window_tokens=0, win_offsets=None, win_tokens=None, win_remove=None,
-                 h_win_offsets=None, h_win_remove=None, metric="cosine"):
+                 h_win_offsets=None, h_win_remove=None, metric="cosine", match=MATCH_BEST_PER_A):
         self.refs = dict(h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=h_cu_txt, cu_txt=cu_txt,
                          win_offsets=win_offsets, win_tokens=win_tokens, win_remove=win_remove,
                          h_win_offsets=h_win_offsets, h_win_remove=h_win_remove)
@@ -130,6 +133,7 @@ class Problem:
         self.c.dtype = {"f32": F32, "bf16": BF16, F32: F32, BF16: BF16}[dtype]
         self.c.n_windows, self.c.max_window_tokens = n_windows, max_window_tokens
         self.c.metric = METRICS[metric] if isinstance(metric, str) else int(metric)
+        self.c.match, self.c.reserved = int(match), 0
         for name in ("h_cu_vis", "h_cu_txt", "h_win_offsets", "h_win_remove"):
             setattr(self.c, name, _hptr(self.refs[name]))
         for name in ("cu_vis", "cu_txt", "win_offsets", "win_tokens", "win_remove"):

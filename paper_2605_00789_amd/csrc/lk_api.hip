@@ -16,6 +16,7 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 struct Checked {
   int sum_n = 0, sum_t = 0, max_seq = 0, max_window = 0, elem_bytes = 0;
+  int64_t sum_remove = 0;   // sum of h_win_remove (when given)
 };
 
 lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool need_txt, Checked &c) {
@@ -23,6 +24,8 @@ lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool n
   if (p->batch < 1 || p->d < 1 || p->heads < 1 || p->head_dim < 1 || p->n_windows < 0) return LIGHTKV_ERR_SHAPE;
   if (p->dtype != LIGHTKV_F32 && p->dtype != LIGHTKV_BF16) return LIGHTKV_ERR_UNSUPPORTED;
   if (p->metric < LIGHTKV_METRIC_COSINE || p->metric > LIGHTKV_METRIC_L2SQ) return LIGHTKV_ERR_UNSUPPORTED;
+  if (p->match < LIGHTKV_MATCH_BEST_PER_A || p->match > LIGHTKV_MATCH_EDGE_TOPK || p->reserved != 0)
+    return LIGHTKV_ERR_UNSUPPORTED;
   c.elem_bytes = p->dtype == LIGHTKV_BF16 ? 2 : 4;
   if (p->d % (16 / c.elem_bytes) != 0) return LIGHTKV_ERR_UNSUPPORTED;
   if ((int64_t)p->heads * p->head_dim != p->d) return LIGHTKV_ERR_SHAPE;
@@ -62,8 +65,10 @@ lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool n
         for (int w = 0; w < p->n_windows; ++w) {
           const int v = p->h_win_offsets[w + 1] - p->h_win_offsets[w];
           const int r = p->h_win_remove[w];
-          const int cap = (v >= 2) ? (v + 1) / 2 : 0;
+          // tokens of A at most; with the k lowest edges, pairs of the window at most
+          const int cap = (v < 2) ? 0 : (p->match == LIGHTKV_MATCH_EDGE_TOPK ? ((v + 1) / 2) * (v / 2) : (v + 1) / 2);
           if (r < 0 || r > cap) return LIGHTKV_ERR_REMOVE_COUNT;
+          c.sum_remove += r;
         }
       }
       c.max_window = p->max_window_tokens > 0 ? p->max_window_tokens : maxw;
@@ -72,6 +77,11 @@ lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool n
       c.max_window = p->max_window_tokens;
     }
     if (c.max_window > LIGHTKV_MAX_WINDOW_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;
+    if (p->match == LIGHTKV_MATCH_EDGE_TOPK) {
+      // the edge list is sized from the host's counts, and the whole |A| x |B| block of a window is ranked in LDS
+      if (!p->h_win_offsets || !p->h_win_remove) return LIGHTKV_ERR_NULL;
+      if (c.max_window > LIGHTKV_EDGE_MAX_WINDOW_TOKENS || c.sum_remove >= (1ll << 28)) return LIGHTKV_ERR_UNSUPPORTED;
+    }
   }
   return LIGHTKV_OK;
 }
@@ -113,10 +123,15 @@ Fork *fork_for_current_device(hipStream_t main) {
 
 struct WsLayout {
   size_t fd_partial = 0, fd_norm = 0, fd_keys = 0, xi_stats = 0, xi_part = 0, sel_cnt = 0,
-         sel_rank = 0, total = 0;
+         sel_rank = 0, edges = 0, total = 0;
 };
 
+bool edge_topk(const lightkv_problem *p) { return p->match == LIGHTKV_MATCH_EDGE_TOPK; }
+// ints of scratch for the edge list (A token, B token, position among the B token's sources)
+size_t edge_ints(const lightkv_problem *p, const Checked &c) { return edge_topk(p) ? (size_t)3 * (size_t)c.sum_remove : 0; }
+
 bool use_big_fd(const lightkv_problem *p, const Checked &c) {
+  if (edge_topk(p)) return false;   // every pair's FD is ranked: the small tiles keep them all, the tiled kernel only row minima
   // the large-window kernel wants whole pairs of 128-element k-steps; other shapes take the small-tile path
   if (p->dtype != LIGHTKV_BF16 || p->d % 256 != 0 || c.max_window < FD_BIG_MIN_WINDOW) return false;
   // ... and enough 96 x 96 tiles to give the chip work: with few, its long k loop per tile is all latency.  Measured per
@@ -126,7 +141,7 @@ bool use_big_fd(const lightkv_problem *p, const Checked &c) {
   return (int64_t)p->n_windows * big.mt * big.nt >= FD_BIG_MIN_TILES;
 }
 
-WsLayout ws_layout(const FdPlan &fd, const FdBigPlan &big, bool use_big, const XiPlan &xi, int sum_n) {
+WsLayout ws_layout(const FdPlan &fd, const FdBigPlan &big, bool use_big, const XiPlan &xi, int sum_n, size_t n_edge_ints) {
   WsLayout l;
   size_t off = 0;
   l.fd_partial = off; off = align_up(off + (use_big ? 0 : fd.partial_floats * sizeof(float)));
@@ -136,6 +151,7 @@ WsLayout ws_layout(const FdPlan &fd, const FdBigPlan &big, bool use_big, const X
   l.xi_part = off;    off = align_up(off + xi.part_floats * sizeof(float));
   l.sel_cnt = off;    off = align_up(off + (size_t)sum_n * sizeof(int32_t));
   l.sel_rank = off;   off = align_up(off + (size_t)sum_n * sizeof(int32_t));
+  l.edges = off;      off = align_up(off + n_edge_ints * sizeof(int32_t));
   l.total = off + ALIGN;
   return l;
 }
@@ -161,7 +177,8 @@ lightkv_status select_impl(const lightkv_problem *p, bool from_keys, float *best
   const bool have_txt = p->h_cu_txt && p->cu_txt;
   const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, have_txt ? p->h_cu_txt : nullptr, p->heads, 0);
   const FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
-  const WsLayout l = ws_layout(fd, big, use_big_fd(p, c), xp, c.sum_n);
+  if (edge_topk(p)) return LIGHTKV_ERR_UNSUPPORTED;   // needs every pair's FD: lightkv_score_select only
+  const WsLayout l = ws_layout(fd, big, use_big_fd(p, c), xp, c.sum_n, 0);
   // only the selection scratch (and the keys) are used here; accept a workspace that covers the layout
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) != 0 || ws_bytes < l.total) return LIGHTKV_ERR_WORKSPACE;
   char *wsb = static_cast<char *>(ws);
@@ -203,7 +220,7 @@ lightkv_status lightkv_workspace_size(const lightkv_problem *p, size_t *bytes) {
   const FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
   const XiPlan xi = make_xi_plan(p->batch, p->h_cu_vis, have_txt ? p->h_cu_txt : nullptr, p->heads, 0);
   const FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
-  *bytes = ws_layout(fd, big, use_big_fd(p, c), xi, c.sum_n).total;
+  *bytes = ws_layout(fd, big, use_big_fd(p, c), xi, c.sum_n, edge_ints(p, c)).total;
   return LIGHTKV_OK;
 }
 
@@ -295,7 +312,8 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
   FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
   fd.metric = big.metric = p->metric;
   const bool use_big = use_big_fd(p, c);
-  const WsLayout l = ws_layout(fd, big, use_big, xp, c.sum_n);
+  const bool edge = sel && need_fd && edge_topk(p);
+  const WsLayout l = ws_layout(fd, big, use_big, xp, c.sum_n, need_fd ? edge_ints(p, c) : 0);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) != 0 || ws_bytes < l.total) return LIGHTKV_ERR_WORKSPACE;
   char *wsb = static_cast<char *>(ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -305,7 +323,7 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
   // running a step of the xi chain next to a step of the FD chain (no helper stream, no fork/join).  Larger steps fill
   // the chip with either chain alone; there the shared launches take as long as the two in a row and the helper
   // stream is the better arrangement (measured: 2880 tokens 248 vs 237 us per three stages, 576 tokens 190 vs 199).
-  if (need_xi && need_fd && sel && fd.n_tiles > 0 && c.sum_n > 0 && c.sum_n <= LIGHTKV_ONE_STREAM_MAX_TOKENS &&
+  if (need_xi && need_fd && sel && !edge && fd.n_tiles > 0 && c.sum_n > 0 && c.sum_n <= LIGHTKV_ONE_STREAM_MAX_TOKENS &&
       p->n_windows > 0) {
     const float scale = softmax_scale != 0.f ? softmax_scale : 1.0f / sqrtf((float)p->head_dim);
     int32_t *cnt = reinterpret_cast<int32_t *>(wsb + l.sel_cnt), *rank = reinterpret_cast<int32_t *>(wsb + l.sel_rank);
@@ -341,6 +359,18 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
   lightkv_status fd_status = LIGHTKV_OK;
   if (!need_fd) {
     // xi only
+  } else if (edge) {
+    // the k lowest edges of every window: partial tiles, ranking per window, index scan, group lists from the edge list
+    int32_t *cnt = reinterpret_cast<int32_t *>(wsb + l.sel_cnt), *rank = reinterpret_cast<int32_t *>(wsb + l.sel_rank);
+    int32_t *edges = reinterpret_cast<int32_t *>(wsb + l.edges);
+    const int sum_k = (int)c.sum_remove;
+    if (launch_edge_select(fd, p->dtype, X, ldx, p->d, p->n_windows, c.max_window, c.sum_n, sum_k, p->win_offsets,
+                           p->win_tokens, p->win_remove, reinterpret_cast<float *>(wsb + l.fd_partial), best_fd,
+                           best_dst, sel->dst, cnt, rank, edges, s) != hipSuccess ||
+        launch_select_scan(p->batch, c.sum_n, p->cu_vis, sel->dst, sel->new_index, sel->grp_offsets, sel->grp_src,
+                           sel->cu_vis_out, cnt, rank, s) != hipSuccess ||
+        launch_edge_fill(sum_k, c.sum_n, edges, sel->grp_offsets, sel->grp_src, s) != hipSuccess)
+      fd_status = LIGHTKV_ERR_LAUNCH;
   } else if (sel) {
     int32_t *cnt = reinterpret_cast<int32_t *>(wsb + l.sel_cnt), *rank = reinterpret_cast<int32_t *>(wsb + l.sel_rank);
     if (launch_fd_select_small(fd, p->dtype, X, ldx, p->d, p->n_windows, c.sum_n, p->win_offsets, p->win_tokens,
@@ -389,7 +419,7 @@ lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int
   if (st != LIGHTKV_OK) return st;
   if (!p->win_remove) return LIGHTKV_ERR_NULL;
   const FdPlan small = make_fd_small_fused_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
-  if ((small.n_tiles > 0 && !use_big_fd(p, c)) || p->n_windows == 0) {
+  if ((small.n_tiles > 0 && !use_big_fd(p, c)) || p->n_windows == 0 || edge_topk(p)) {
     const SelectOut sel{dst, new_index, grp_offsets, grp_src, cu_vis_out};
     return score_impl(p, X, ldx, x_sqnorm, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
                       softmax_scale, xi, best_fd, best_dst, &sel, false, ws, ws_bytes, stream);

@@ -175,6 +175,16 @@ FdPlan make_fd_plan(int n_windows, int max_window_tokens, int d, int dtype_bytes
   return p;
 }
 
+hipError_t launch_fd_partial(const FdPlan &plan, int dtype, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
+                             const int32_t *win_offsets, const int32_t *win_tokens, float *partial, hipStream_t stream) {
+  if (n_windows == 0 || plan.n_tiles == 0) return hipSuccess;
+  const FdArgs g = make_fd_args(plan, dtype, X, ldx, d, n_windows, sum_n, win_offsets, win_tokens, partial, nullptr, nullptr);
+  const dim3 grid((unsigned)(plan.n_tiles * plan.ksplit));
+  if (dtype == 1) hipLaunchKernelGGL(fd_partial_kernel<bf16_t>, grid, dim3(FD_THREADS), 0, stream, g);
+  else hipLaunchKernelGGL(fd_partial_kernel<float>, grid, dim3(FD_THREADS), 0, stream, g);
+  return hipGetLastError();
+}
+
 hipError_t launch_fd(const FdPlan &plan, int dtype, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
                      const int32_t *win_offsets, const int32_t *win_tokens, float *partial, float *best_fd,
                      int32_t *best_dst, hipStream_t stream) {

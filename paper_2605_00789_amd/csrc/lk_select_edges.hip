@@ -1,0 +1,296 @@
+// Step 2 of the paper's Sec. 3.2.1 read literally: the candidate set T_rho of a window is made of the k lowest-FD EDGES
+// of the complete bipartite graph between its node sets A and B -- not one edge per A node.  An A node then owns as
+// many edges as rank that low (it is averaged into each of those B nodes with its full weight, Eq. "message-passing"
+// with several ones in a row of M) and leaves if it owns at least one, so the number of tokens that go depends on
+// the data: between ceil(k / |B|) and min(k, |A|) per window.
+//
+//   edge_select_kernel : one workgroup per window.  Reads the partial inner-product tiles that fd_partial_kernel left
+//                        (lk_score_fd.hip), forms FD of every (a, b) pair into LDS as an order-preserving integer key,
+//                        finds the k-th smallest key by a 4-pass radix select (8 bits per pass, LDS histogram; integer
+//                        counts, so the result does not depend on the order of the atomics), breaks a tie AT the
+//                        threshold by (A position, B position), and writes
+//                          dst[a]      the B token of a's lowest selected edge, -1 if a stays
+//                          src_rank[a] position of a among the sources of that B token
+//                          cnt[b]      number of selected edges into b
+//                          best_fd / best_dst  of every A node, as the default selection reports them
+//                        plus the window's edge list (a, b, position of a among b's sources) at a fixed offset
+//                        (the k of the windows before it) for edge_fill_kernel.
+//   select_scan_kernel : unchanged (lk_select.hip): new_index from dst, grp_offsets from cnt.
+//   edge_fill_kernel   : grp_src[grp_offsets[b] + position] = a for every edge.
+#include "lk_fd_body.h"
+
+namespace lk {
+
+constexpr int EDGE_THREADS = 256;
+constexpr int EDGE_WAVES = EDGE_THREADS / 64;
+
+struct EdgeArgs {
+  const int32_t *win_remove;   // k per window
+  int32_t *dst, *cnt, *src_rank;
+  int32_t *edges;              // [3][sum_k]: A token, B token, position among the B token's sources
+  int sum_k;
+};
+
+// Workgroup-wide sum of one int per thread; every thread gets the total.
+__device__ __forceinline__ int edge_block_sum(int v, int *wsum) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();   // wsum may still be read from the call before
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = v;
+  __syncthreads();
+  int t = 0;
+#pragma unroll
+  for (int w = 0; w < EDGE_WAVES; ++w) t += wsum[w];
+  return t;
+}
+
+__global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, EdgeArgs q) {
+  extern __shared__ uint32_t keys[];   // [nA][pitch]
+  __shared__ double na2[EDGE_MAX_SIDE], nb2[EDGE_MAX_SIDE];
+  __shared__ int hist[256];
+  __shared__ int col_cnt[EDGE_MAX_SIDE], col_start[EDGE_MAX_SIDE];
+  __shared__ int wsum[EDGE_WAVES];
+  __shared__ int pick[2];
+  const int w = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const WinInfo wi = win_info(g, w);
+  const int nA = wi.nA, nB = wi.nB;
+  if (nA > EDGE_MAX_SIDE || nB > EDGE_MAX_SIDE) return;   // the host refuses such windows; nothing is written
+  const int E = nA * nB;
+  int k = q.win_remove[w];
+  k = k < 0 ? 0 : (k > E ? E : k);
+
+  // slots of this window in the edge list: the k of the windows before it
+  int before = 0;
+  for (int i = tid; i < w; i += EDGE_THREADS) before += q.win_remove[i];
+  const int edge_base = edge_block_sum(before, wsum);
+
+  if (nB == 0) {   // a window of one token (or none): no pair, nothing leaves
+    for (int i = tid; i < nA; i += EDGE_THREADS) {
+      const int tok = checked_token(g, wi.off + i);
+      if (tok >= 0) {
+        q.dst[tok] = -1; q.cnt[tok] = 0; q.src_rank[tok] = 0;
+        g.best_fd[tok] = __uint_as_float(0x7f800000u);
+        g.best_dst[tok] = -1;
+      }
+    }
+    return;
+  }
+
+  // ---- where the sums of pair (la, lb) lie in the partial tiles
+  const int64_t ks_stride = (int64_t)g.n_tiles * FD_TILE_FLOATS;
+  const int per = g.mt * g.nt;
+  const int grp_s = (g.group > 1) ? w % g.group : 0;
+  const int row_shift = grp_s * g.slot;                 // rows and columns of this window inside a packed tile
+  const int tile0 = (g.group > 1) ? w / g.group : w * per;
+  auto tile_of = [&](int la, int lb) { return (g.group > 1) ? tile0 : tile0 + (la >> 5) * g.nt + (lb >> 5); };
+  for (int i = tid; i < nA + nB; i += EDGE_THREADS) {
+    if (i < nA) {
+      const int r = (g.group > 1) ? row_shift + i : (i & 31);
+      na2[i] = sum_slices(g.partial + (int64_t)tile_of(i, 0) * FD_TILE_FLOATS + 32 * 32 + r, ks_stride, g.ksplit);
+    } else {
+      const int lb = i - nA;
+      const int c = (g.group > 1) ? row_shift + lb : (lb & 31);
+      nb2[lb] = sum_slices(g.partial + (int64_t)tile_of(0, lb) * FD_TILE_FLOATS + 32 * 32 + 32 + c, ks_stride, g.ksplit);
+    }
+  }
+  __syncthreads();
+
+  // ---- FD of every pair -> order-preserving key in LDS
+  const int pitch = nB | 1;   // odd: a thread per row and a thread per column both walk the array without bank conflicts
+  for (int e = tid; e < E; e += EDGE_THREADS) {
+    const int la = e / nB, lb = e - la * nB;
+    const int r = (g.group > 1) ? row_shift + la : (la & 31);
+    const int c = (g.group > 1) ? row_shift + lb : (lb & 31);
+    const double dot = sum_slices(g.partial + (int64_t)tile_of(la, lb) * FD_TILE_FLOATS + r * 32 + c, ks_stride, g.ksplit);
+    float f = (float)divergence(g.metric, dot, na2[la], nb2[lb]);
+    if (!(f >= 0.f)) f = __uint_as_float(0x7f800000u);   // NaN ranks last, like +inf
+    keys[la * pitch + lb] = f32_order_key(f);
+  }
+  __syncthreads();
+
+  // ---- k-th smallest key: radix select, most significant byte first
+  uint32_t prefix = 0, mask = 0;
+  int remaining = k;   // how many of the keys that match the prefix so far are wanted
+  int n_equal = 0;     // keys equal to the threshold (after the last pass)
+  static_assert(EDGE_THREADS == 256 && EDGE_MAX_SIDE == 128, "one thread per histogram bin; a half of the workgroup per node set");
+  for (int shift = 24; k > 0 && shift >= 0; shift -= 8) {   // k is uniform over the workgroup
+    hist[tid] = 0;
+    __syncthreads();
+    for (int e = tid; e < E; e += EDGE_THREADS) {
+      const int la = e / nB, lb = e - la * nB;
+      const uint32_t key = keys[la * pitch + lb];
+      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    // inclusive scan of the 256 bins, one per thread
+    const int h = hist[tid];
+    int inc = h;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += t;
+    }
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    for (int w2 = 0; w2 < wave; ++w2) inc += wsum[w2];
+    const int exc = inc - h;
+    if (exc < remaining && remaining <= inc) { pick[0] = tid; pick[1] = remaining - exc; }   // exactly one bin
+    __syncthreads();
+    prefix |= (uint32_t)pick[0] << shift;
+    mask |= 255u << shift;
+    remaining = pick[1];
+    n_equal = hist[pick[0]];
+    __syncthreads();
+  }
+  // k == 0: no key is selected (a flag rather than a sentinel threshold)
+  const bool any = k > 0;
+  const uint32_t threshold = prefix;
+  // `remaining` of the n_equal keys AT the threshold are wanted: the first ones in (A position, B position) order.
+  // The others are pushed past every real key (the largest real key is that of +inf), so that afterwards
+  // "selected" simply means key <= threshold.
+  if (any && remaining < n_equal) {
+    int base = 0;
+    for (int e0 = 0; e0 < E; e0 += EDGE_THREADS) {   // workgroup-uniform trip count
+      const int e = e0 + tid;
+      const int la = e < E ? e / nB : 0, lb = e < E ? e - la * nB : 0;
+      const bool eq = e < E && keys[la * pitch + lb] == threshold;
+      const unsigned long long bal = __ballot(eq);
+      const int in_wave = __popcll(bal & ((1ull << lane) - 1ull));
+      __syncthreads();
+      if (lane == 0) wsum[wave] = __popcll(bal);
+      __syncthreads();
+      int before_me = base + in_wave, all = 0;
+#pragma unroll
+      for (int w2 = 0; w2 < EDGE_WAVES; ++w2) {
+        before_me += (w2 < wave) ? wsum[w2] : 0;
+        all += wsum[w2];
+      }
+      if (eq && before_me >= remaining) keys[la * pitch + lb] = 0xffffffffu;
+      base += all;
+    }
+  }
+  __syncthreads();
+
+  // ---- per B node: number of selected edges; their slots inside the window's edge list
+  int my_cnt = 0;
+  if (tid < nB)
+    for (int la = 0; la < nA; ++la) my_cnt += (any && keys[la * pitch + tid] <= threshold) ? 1 : 0;
+  if (tid < EDGE_MAX_SIDE) col_cnt[tid] = tid < nB ? my_cnt : 0;
+  __syncthreads();
+  if (tid < 64) {   // exclusive prefix over at most 128 columns: two per lane
+    const int c0 = col_cnt[2 * tid], c1 = col_cnt[2 * tid + 1];
+    int inc = c0 + c1;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += t;
+    }
+    col_start[2 * tid] = inc - c0 - c1;
+    col_start[2 * tid + 1] = inc - c1;
+  }
+  __syncthreads();
+  if (tid < nB) {
+    const int b_tok = checked_token(g, wi.off + 2 * tid + 1);
+    if (b_tok >= 0) {
+      q.dst[b_tok] = -1; q.cnt[b_tok] = my_cnt; q.src_rank[b_tok] = 0;
+      g.best_fd[b_tok] = __uint_as_float(0x7f800000u);
+      g.best_dst[b_tok] = -1;
+    }
+    int pos = 0;
+    for (int la = 0; la < nA; ++la) {
+      if (any && keys[la * pitch + tid] <= threshold) {
+        const int slot = edge_base + col_start[tid] + pos;
+        if (slot < q.sum_k) {
+          q.edges[slot] = checked_token(g, wi.off + 2 * la);
+          q.edges[q.sum_k + slot] = b_tok;
+          q.edges[2 * q.sum_k + slot] = pos;
+        }
+        ++pos;
+      }
+    }
+  }
+  // ---- per A node (the upper half of the workgroup): lowest selected edge, and the best edge whether selected or not
+  if (tid >= EDGE_MAX_SIDE && tid - EDGE_MAX_SIDE < nA) {
+    const int la = tid - EDGE_MAX_SIDE;
+    uint32_t best = 0xffffffffu, best_sel = 0xffffffffu;
+    int best_c = -1, sel_c = -1;
+    for (int lb = 0; lb < nB; ++lb) {
+      const uint32_t key = keys[la * pitch + lb];
+      // a key pushed past the threshold above was equal to it before
+      const uint32_t real = key == 0xffffffffu ? threshold : key;
+      if (real < best) { best = real; best_c = lb; }            // columns ascend: strict < keeps the first minimum
+      if (any && key <= threshold && key < best_sel) { best_sel = key; sel_c = lb; }
+    }
+    int rank = 0;
+    if (sel_c >= 0)
+      for (int l2 = 0; l2 < la; ++l2) rank += keys[l2 * pitch + sel_c] <= threshold ? 1 : 0;   // sel_c >= 0 implies any
+    const int a_tok = checked_token(g, wi.off + 2 * la);
+    if (a_tok >= 0) {
+      q.dst[a_tok] = sel_c >= 0 ? checked_token(g, wi.off + 2 * sel_c + 1) : -1;
+      q.src_rank[a_tok] = rank;
+      q.cnt[a_tok] = 0;
+      // order key back to the float it came from
+      const uint32_t u = (best & 0x80000000u) ? (best & 0x7fffffffu) : ~best;
+      g.best_fd[a_tok] = __uint_as_float(u);
+      g.best_dst[a_tok] = best_c >= 0 ? checked_token(g, wi.off + 2 * best_c + 1) : -1;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void edge_fill_kernel(EdgeArgs q, const int32_t *grp_offsets, int32_t *grp_src, int sum_n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= q.sum_k) return;
+  const int a = q.edges[i], b = q.edges[q.sum_k + i], pos = q.edges[2 * q.sum_k + i];
+  if ((unsigned)a >= (unsigned)sum_n || (unsigned)b >= (unsigned)sum_n) return;
+  const int slot = grp_offsets[b] + pos;
+  if (slot >= 0 && slot < q.sum_k) grp_src[slot] = a;
+}
+
+// Every slot of the edge list starts out empty (-1): a window whose k was clipped on the device leaves some unwritten.
+__global__ __launch_bounds__(256) void edge_clear_kernel(EdgeArgs q) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < 3 * q.sum_k) q.edges[i] = -1;
+}
+
+hipError_t launch_edge_select(const FdPlan &plan, int dtype, const void *X, int64_t ldx, int d, int n_windows,
+                              int max_window, int sum_n, int sum_k, const int32_t *win_offsets,
+                              const int32_t *win_tokens, const int32_t *win_remove, float *partial, float *best_fd,
+                              int32_t *best_dst, int32_t *dst, int32_t *cnt, int32_t *src_rank, int32_t *edges,
+                              hipStream_t stream) {
+  if (n_windows == 0 || plan.n_tiles == 0) return hipSuccess;
+  const int maxA = (max_window + 1) / 2, maxB = max_window / 2;
+  if (maxA > EDGE_MAX_SIDE) return hipErrorInvalidValue;
+  hipError_t e = launch_fd_partial(plan, dtype, X, ldx, d, n_windows, sum_n, win_offsets, win_tokens, partial, stream);
+  if (e != hipSuccess) return e;
+  const FdArgs g = make_fd_args(plan, dtype, X, ldx, d, n_windows, sum_n, win_offsets, win_tokens, partial, best_fd, best_dst);
+  EdgeArgs q{win_remove, dst, cnt, src_rank, edges, sum_k};
+  if (sum_k > 0) {
+    hipLaunchKernelGGL(edge_clear_kernel, dim3((unsigned)((3 * sum_k + 255) / 256)), dim3(256), 0, stream, q);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const size_t lds = (size_t)maxA * (size_t)(maxB | 1) * sizeof(uint32_t);
+  static bool allowed[64] = {};   // up to 66 KB of dynamic LDS: above the 64 KB default, set once per device
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!allowed[dev]) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(edge_select_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)((size_t)EDGE_MAX_SIDE * (EDGE_MAX_SIDE | 1) * sizeof(uint32_t)));
+    if (e != hipSuccess) return e;
+    allowed[dev] = true;
+  }
+  hipLaunchKernelGGL(edge_select_kernel, dim3((unsigned)n_windows), dim3(EDGE_THREADS), lds, stream, g, q);
+  return hipGetLastError();
+}
+
+hipError_t launch_edge_fill(int sum_k, int sum_n, const int32_t *edges, const int32_t *grp_offsets, int32_t *grp_src,
+                            hipStream_t stream) {
+  if (sum_k <= 0) return hipSuccess;
+  EdgeArgs q{};
+  q.edges = const_cast<int32_t *>(edges);
+  q.sum_k = sum_k;
+  hipLaunchKernelGGL(edge_fill_kernel, dim3((unsigned)((sum_k + 255) / 256)), dim3(256), 0, stream, q, grp_offsets, grp_src, sum_n);
+  return hipGetLastError();
+}
+
+}  // namespace lk

@@ -11,7 +11,7 @@ import numpy as np
 import torch
 
 from . import binding as B
-from .schedule import max_window_cells, removal_counts, windows_per_sequence
+from .schedule import edge_counts, max_window_cells, removal_counts, windows_per_sequence
 
 
 def to_device(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
@@ -189,3 +189,88 @@ class CompressionPipeline:
             X, K, V, pos = st.X_out, st.K_out, st.V_out, st.pos_out
         main.wait_stream(self.side2)   # nothing is left running on a helper stream when run() returns
         return st
+
+
+@dataclass
+class EdgeStepResult:
+    """Outputs of one step with Step 2 read literally; every tensor is cut to the rows the step really wrote."""
+    h_cu_vis_out: np.ndarray
+    X: torch.Tensor
+    K: torch.Tensor
+    V: torch.Tensor
+    pos: torch.Tensor
+    xi: torch.Tensor
+    best_fd: torch.Tensor
+    best_dst: torch.Tensor
+    dst: torch.Tensor
+    new_index: torch.Tensor
+    grp_offsets: torch.Tensor
+    grp_src: torch.Tensor
+    win_offsets: torch.Tensor
+    win_tokens: torch.Tensor
+    h_win_edges: np.ndarray
+
+
+class EdgeTopKSchedule:
+    """The hierarchical schedule with the k lowest-FD edges per window (LIGHTKV_MATCH_EDGE_TOPK, k = floor(rho v / 2)
+    as Sec. 3.2.1 counts the pairs).  How many tokens leave depends on the data, so the host reads two small arrays back
+    per stage -- the window sizes (to count k and size the edge list) and the sequence lengths after the step -- and
+    allocates the stage's buffers then; nothing here is captured in a graph."""
+
+    def __init__(self, *, dtype: str, batch: int, d: int, heads: int, head_dim: int, tiles: int, grid_h: int,
+                 grid_w: int, cu_txt: np.ndarray, windows_per_axis: Sequence[int], rho: Sequence[float],
+                 device="cuda:0", metric: str = "cosine"):
+        self.dtype, self.batch, self.d, self.heads, self.head_dim = dtype, batch, d, heads, head_dim
+        self.tiles, self.grid_h, self.grid_w = tiles, grid_h, grid_w
+        self.windows_per_axis, self.rho = list(windows_per_axis), list(rho)
+        self.device = torch.device(device)
+        self.metric = metric
+        self.h_cu_txt = np.ascontiguousarray(cu_txt, dtype=np.int32)
+        self.cu_txt = torch.from_numpy(self.h_cu_txt).to(self.device)
+
+    def run_step(self, s: int, h_cu_vis: np.ndarray, X, K, V, Q, pos, *, xi_given=None, h_win_edges=None) -> EdgeStepResult:
+        dev, i32 = self.device, dict(dtype=torch.int32, device=self.device)
+        batch, w = self.batch, self.windows_per_axis[s]
+        h_cu_vis = np.ascontiguousarray(h_cu_vis, dtype=np.int32)
+        cu_vis = torch.from_numpy(h_cu_vis).to(dev)
+        sum_n = int(h_cu_vis[-1])
+        n_windows = batch * windows_per_sequence(self.tiles, w)
+        win_offsets = torch.empty(n_windows + 1, **i32)
+        win_tokens = torch.empty(max(sum_n, 1), **i32)
+        B.lightkv_build_windows(batch, h_cu_vis, cu_vis, pos, self.tiles, self.grid_h, self.grid_w, w, win_offsets,
+                                win_tokens)
+        h_win_offsets = win_offsets.cpu().numpy()            # first read-back: the window sizes
+        h_k = edge_counts(h_win_offsets, self.rho[s]) if h_win_edges is None else np.ascontiguousarray(h_win_edges, dtype=np.int32)
+        win_remove = torch.from_numpy(h_k).to(dev)
+        prob = B.Problem(batch=batch, d=self.d, heads=self.heads, head_dim=self.head_dim, dtype=self.dtype,
+                         h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt,
+                         n_windows=n_windows, max_window_tokens=0, win_offsets=win_offsets, win_tokens=win_tokens,
+                         win_remove=win_remove, h_win_offsets=h_win_offsets, h_win_remove=h_k, metric=self.metric,
+                         match=B.MATCH_EDGE_TOPK)
+        ws = torch.empty(B.lightkv_workspace_size(prob), dtype=torch.uint8, device=dev)
+        tdt = X.dtype
+        xi = torch.empty(sum_n, dtype=torch.float32, device=dev) if xi_given is None else xi_given
+        best_fd = torch.empty(sum_n, dtype=torch.float32, device=dev)
+        best_dst, dst, new_index = (torch.empty(sum_n, **i32) for _ in range(3))
+        grp_offsets = torch.empty(sum_n + 1, **i32)
+        grp_src = torch.empty(max(int(h_k.sum()), 1), **i32)
+        cu_vis_out = torch.empty(batch + 1, **i32)
+        B.lightkv_score_select(prob, X, Q, K, xi, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, ws,
+                               xi_mode=B.XI_TEXT_QUERY if xi_given is None else B.XI_GIVEN)
+        # every window that takes an edge loses at least one token: an upper bound on the rows written
+        rows = max(sum_n - int((h_k > 0).sum()), 1)
+        X_out, K_out, V_out = (torch.empty(rows, self.d, dtype=tdt, device=dev) for _ in range(3))
+        pos_out = torch.empty(rows, **i32)
+        B.lightkv_aggregate_compact(prob, new_index, grp_offsets, grp_src, xi, X, K, V, pos, X_out, K_out, V_out, pos_out)
+        h_out = cu_vis_out.cpu().numpy()                     # second read-back: the sequence lengths after the step
+        n_out = int(h_out[-1])
+        return EdgeStepResult(h_out, X_out[:n_out], K_out[:n_out], V_out[:n_out], pos_out[:n_out], xi, best_fd, best_dst,
+                              dst, new_index, grp_offsets, grp_src, win_offsets, win_tokens, h_k)
+
+    def run(self, h_cu_vis: np.ndarray, X, K, V, Q, pos) -> List[EdgeStepResult]:
+        out = []
+        for s in range(len(self.windows_per_axis)):
+            r = self.run_step(s, h_cu_vis, X, K, V, Q, pos)
+            out.append(r)
+            h_cu_vis, X, K, V, pos = r.h_cu_vis_out, r.X, r.K, r.V, r.pos
+        return out

@@ -29,3 +29,11 @@ def removal_counts(batch: int, n_in: int, n_out: int, win_per_seq: int) -> np.nd
     one = np.full(win_per_seq, base, dtype=np.int32)
     one[:extra] += 1
     return np.tile(one, batch)
+
+
+def edge_counts(h_win_offsets: np.ndarray, rho: float) -> np.ndarray:
+    """Edges taken per window when Step 2 is read literally (Sec. 3.2.1): floor(rho * v / 2) pairs for a window of v
+    tokens, never more than the window has pairs."""
+    v = np.diff(np.asarray(h_win_offsets, dtype=np.int64))
+    k = np.floor(rho * v / 2.0 + 1e-9).astype(np.int64)
+    return np.minimum(k, ((v + 1) // 2) * (v // 2)).astype(np.int32)

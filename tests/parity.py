@@ -208,3 +208,159 @@ def check_workload(wl, pipe=None, stages=None, fused=True, metric="cosine"):
         reports.append(rep)
         X, K, V, pos = out["X"], out["K"], out["V"], out["pos"]
     return reports
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Step 2 read literally: the k lowest-FD edges of every window (LIGHTKV_MATCH_EDGE_TOPK)
+# ---------------------------------------------------------------------------------------------------------------
+@dataclass
+class EdgeReport:
+    stage: int
+    n_in: int
+    n_out: int
+    edges: int = 0
+    window_ties: int = 0        # windows whose edge set differs from the oracle's but ties within the band
+    max_xi_rel: float = 0.0
+    max_row_rel: float = 0.0
+
+
+def check_edge_step(sched, s: int, h_cu_vis, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_given=None, h_win_edges=None):
+    """Runs step s of an EdgeTopKSchedule on storage arrays and checks every output against the oracle, which gets
+    exactly the tensors the GPU step consumed.  Edge sets are compared exactly; where they differ every edge the GPU
+    took must lie within TIE_BAND of the oracle's k-th lowest FD and every edge it left out not below it."""
+    batch = sched.batch
+    dX, dK, dV = to_dev(Xs, dtype), to_dev(Ks, dtype), to_dev(Vs, dtype)
+    dQ = to_dev(Qs, dtype)
+    dpos = torch.from_numpy(np.ascontiguousarray(pos, dtype=np.int32)).to(dX.device)
+    dxi = None if xi_given is None else torch.from_numpy(np.ascontiguousarray(xi_given, dtype=np.float32)).to(dX.device)
+    r = sched.run_step(s, h_cu_vis, dX, dK, dV, dQ, dpos, xi_given=dxi, h_win_edges=h_win_edges)
+    torch.cuda.synchronize()
+    g = {k: getattr(r, k).cpu().numpy() for k in ("win_offsets", "win_tokens", "best_fd", "best_dst", "dst", "new_index",
+                                                  "grp_offsets", "grp_src", "pos")}
+    g_xi = r.xi.cpu().numpy()
+    bf16 = dtype == "bf16"
+    metric = sched.metric
+    n = int(h_cu_vis[-1])
+    rep = EdgeReport(stage=s, n_in=n, n_out=int(r.h_cu_vis_out[-1]))
+
+    wo, wt = O.build_windows(pos, h_cu_vis, sched.tiles, sched.grid_h, sched.grid_w, sched.windows_per_axis[s])
+    np.testing.assert_array_equal(g["win_offsets"], wo, err_msg="win_offsets")
+    np.testing.assert_array_equal(g["win_tokens"][:len(wt)], wt, err_msg="win_tokens")
+    h_k = r.h_win_edges
+
+    X64, K64, V64 = O.widen(Xs, dtype), O.widen(Ks, dtype), O.widen(Vs, dtype)
+    if xi_given is None:
+        xi_ref = O.xi_text_query(O.widen(Qs, dtype), K64, h_cu_vis, sched.h_cu_txt, sched.heads, sched.head_dim)
+        rel = np.abs(g_xi - xi_ref) / np.maximum(np.abs(xi_ref), 1e-300)
+        rep.max_xi_rel = float(rel.max()) if len(rel) else 0.0
+        assert rep.max_xi_rel <= (1e-3 if bf16 else 1e-5), "xi relative error %.3g" % rep.max_xi_rel
+    else:
+        xi_ref = np.asarray(xi_given, dtype=np.float64)
+
+    go, gs = g["grp_offsets"], g["grp_src"]
+    assert go[0] == 0 and go[n] == int(h_k.sum()) and np.all(np.diff(go[:n + 1]) >= 0)
+    gpu_edges = []
+    gone = np.zeros(n, dtype=bool)
+    for w in range(len(wo) - 1):
+        toks = wt[wo[w]:wo[w + 1]]
+        A, Bn = O.split_window(toks)
+        k = int(h_k[w])
+        assert np.all(go[A + 1] - go[A] == 0), "an A token has sources"
+        if len(Bn) == 0:
+            assert k == 0 and np.all(g["dst"][toks] == -1)
+            continue
+        fd = O.feature_divergence(X64[A], X64[Bn], metric)
+        scale = 1.0
+        fd_cmp = fd
+        if metric != "cosine":
+            if metric == "euclidean":
+                fd_cmp = fd * fd
+            scale = float((X64[A] ** 2).sum(axis=1).max() + (X64[Bn] ** 2).sum(axis=1).max())
+        band = TIE_BAND * scale
+        la_of = {int(t): i for i, t in enumerate(A)}
+        mine = []
+        for j, b in enumerate(Bn):
+            src = gs[go[b]:go[b + 1]]
+            assert np.all(np.diff(src) > 0), "sources of token %d are not ascending and distinct" % b
+            for a in src:
+                assert int(a) in la_of, "source %d of token %d is not an A node of its window" % (a, b)
+                mine.append((la_of[int(a)], j))
+        assert len(mine) == k, "window %d: %d edges, expected %d" % (w, len(mine), k)
+        ref = sorted(((fd[i, j], i, j) for i in range(len(A)) for j in range(len(Bn))))[:k]
+        ref_set = set((i, j) for _, i, j in ref)
+        mine_set = set(mine)
+        assert len(mine_set) == k, "window %d: an edge is listed twice" % w
+        if mine_set != ref_set:
+            tau = fd_cmp[ref[-1][1], ref[-1][2]]
+            for i in range(len(A)):
+                for j in range(len(Bn)):
+                    if (i, j) in mine_set:
+                        assert fd_cmp[i, j] <= tau + band, "window %d: edge (%d,%d) FD %.9g > threshold %.9g" % (w, i, j, fd_cmp[i, j], tau)
+                    else:
+                        assert fd_cmp[i, j] >= tau - band, "window %d: left-out edge (%d,%d) FD %.9g < threshold %.9g" % (w, i, j, fd_cmp[i, j], tau)
+            rep.window_ties += 1
+        # dst: the lowest selected edge of every A node that owns one; best_fd / best_dst: its lowest edge of all
+        own = {}
+        for i, j in mine:
+            own.setdefault(i, []).append(j)
+        for i, a in enumerate(A):
+            if i in own:
+                gone[a] = True
+                jd = int(np.nonzero(Bn == g["dst"][a])[0][0])
+                assert jd in own[i] and fd_cmp[i, jd] <= min(fd_cmp[i, j] for j in own[i]) + band
+            else:
+                assert g["dst"][a] == -1
+            jb = int(np.nonzero(Bn == g["best_dst"][a])[0][0])
+            assert fd_cmp[i, jb] <= fd_cmp[i].min() + band
+            got = float(g["best_fd"][a]) ** (2 if metric == "euclidean" else 1)
+            assert abs(got - fd_cmp[i].min()) / scale <= (1e-5 if bf16 else 1e-6)
+        assert np.all(g["dst"][Bn] == -1) and np.all(g["best_dst"][Bn] == -1)
+        gpu_edges += [(int(A[i]), int(Bn[j])) for i, j in mine]
+        rep.edges += k
+
+    keep = ~gone
+    np.testing.assert_array_equal(g["new_index"], np.where(keep, np.cumsum(keep) - 1, -1), err_msg="new_index")
+    cu_out = np.zeros(batch + 1, dtype=np.int32)
+    for b in range(batch):
+        cu_out[b + 1] = cu_out[b] + int(keep[h_cu_vis[b]:h_cu_vis[b + 1]].sum())
+    np.testing.assert_array_equal(r.h_cu_vis_out, cu_out, err_msg="cu_vis_out")
+    n_out = int(keep.sum())
+    np.testing.assert_array_equal(g["pos"], np.asarray(pos)[keep], err_msg="pos_out")
+    ego, egs = O.edges_csr(n, gpu_edges)
+    np.testing.assert_array_equal(go[:n + 1], ego, err_msg="grp_offsets")
+    np.testing.assert_array_equal(gs[:len(egs)], egs, err_msg="grp_src")
+
+    outs = {}
+    tol = 2e-2 if bf16 else 1e-5
+    for name, Y64, dev_out, src_store in (("X", X64, r.X, Xs), ("K", K64, r.K, Ks), ("V", V64, r.V, Vs)):
+        ref = O.message_passing_edges(Y64, xi_ref, gpu_edges)[keep]
+        got_store = from_dev(dev_out, dtype)
+        got = O.widen(got_store, dtype)
+        assert got.shape[0] == n_out
+        num = np.linalg.norm(got - ref, axis=1)
+        den = np.maximum(np.linalg.norm(ref, axis=1), 1e-300)
+        row_rel = float((num / den).max()) if n_out else 0.0
+        elem_rel = float((np.abs(got - ref).max(axis=1) / np.maximum(np.abs(ref).max(axis=1), 1e-300)).max()) if n_out else 0.0
+        rep.max_row_rel = max(rep.max_row_rel, row_rel)
+        assert row_rel <= tol and elem_rel <= tol, "%s rows: rel %.3g / %.3g" % (name, row_rel, elem_rel)
+        untouched = (ego[1:] - ego[:-1])[keep] == 0
+        np.testing.assert_array_equal(got_store[untouched], np.asarray(src_store)[keep][untouched], err_msg=name + " copied rows")
+        outs[name] = got_store
+    outs["pos"] = g["pos"].copy()
+    outs["cu_vis"] = cu_out
+    return rep, outs
+
+
+def check_edge_workload(wl, rho, stages=None, metric="cosine"):
+    from paper_2605_00789_amd import EdgeTopKSchedule
+    n_st = wl.stages if stages is None else stages
+    sched = EdgeTopKSchedule(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, tiles=wl.tiles,
+                             grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                             windows_per_axis=wl.windows_per_axis[:n_st], rho=list(rho)[:n_st], metric=metric)
+    X, K, V, pos, cu = wl.X, wl.K, wl.V, wl.pos, wl.cu_vis
+    reports = []
+    for s in range(n_st):
+        rep, out = check_edge_step(sched, s, cu, X, K, V, wl.Q, pos, wl.dtype)
+        reports.append(rep)
+        X, K, V, pos, cu = out["X"], out["K"], out["V"], out["pos"], out["cu_vis"]
+    return reports

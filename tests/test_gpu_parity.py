@@ -523,3 +523,104 @@ def test_nan_rows_keep_the_counts_exact():
         assert np.all(dst[t[0::2]] >= 0) and np.all(dst[t[1::2]] == -1)
         assert set(dst[t[0::2]].tolist()) <= set(t[1::2].tolist())       # partners stay inside the window's B set
     np.testing.assert_array_equal(st.new_index.cpu().numpy(), O.kept_index(dst))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Step 2 read literally: the k lowest-FD edges per window
+# ---------------------------------------------------------------------------------------------------------------
+@pytest.mark.gpu
+@pytest.mark.parametrize("cfg,rho,stages", [(1, (0.5,), 1), (2, (0.5, 0.5), 2), (4, (0.6,), 1), (3, (0.5, 0.5), 2),
+                                            (5, (0.5, 0.3), 2)])
+def test_edge_topk_matching_matches_oracle(cfg, rho, stages):
+    """floor(rho v / 2) lowest-FD edges per window at the measured configurations' sizes: packed 16-token windows
+    (configs 1, 3), single-tile and multi-tile windows (2, 4, 5), a ragged batch after the first stage (5)."""
+    from workloads import make_workload
+    from parity import check_edge_workload
+    wl = make_workload(cfg)
+    print("[edge top-k] config %s" % cfg, flush=True)
+    reps = check_edge_workload(wl, rho, stages=stages)
+    for r in reps:
+        print("  stage %d: %d -> %d tokens, %d edges, %d tied windows, xi rel %.2e, rows rel %.2e"
+              % (r.stage, r.n_in, r.n_out, r.edges, r.window_ties, r.max_xi_rel, r.max_row_rel), flush=True)
+        assert r.n_out < r.n_in
+    assert sum(r.window_ties for r in reps) <= 2
+
+
+@pytest.mark.gpu
+def test_edge_topk_edge_cases():
+    """k = 0 in some windows, every edge of a window, windows of one token, identical tokens (all FD tie at zero: the
+    order by position decides, exactly as in the oracle), a grid that the windows do not divide, both dtypes, the
+    distance metrics."""
+    from workloads import make_custom
+    from parity import check_edge_step
+    from oracle import lightkv_oracle as O
+    from paper_2605_00789_amd import EdgeTopKSchedule
+
+    def sched_for(wl, w, metric="cosine"):
+        return EdgeTopKSchedule(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                                tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                                windows_per_axis=[w], rho=[0.5], metric=metric)
+
+    # (a) hand-set k per window: none, one, all pairs, a few
+    wl = make_custom(name="edge_a", seed=31, dtype="f32", batch=2, grid_h=10, grid_w=7, text_lens=(9, 20), d=64, heads=2,
+                     head_dim=32, windows_per_axis=(3,), n_final=40)
+    wo, _ = O.build_windows(wl.pos, wl.cu_vis, wl.tiles, wl.grid_h, wl.grid_w, 3)
+    v = np.diff(wo)
+    pairs = ((v + 1) // 2) * (v // 2)
+    k = np.array([[0, 1, p, min(5, p), p // 2, max(p - 1, 0)][i % 6] for i, p in enumerate(pairs)], dtype=np.int32)
+    rep, _ = check_edge_step(sched_for(wl, 3), 0, wl.cu_vis, wl.X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype, h_win_edges=k)
+    print("[edge cases] (a) %d -> %d tokens, %d edges" % (rep.n_in, rep.n_out, rep.edges), flush=True)
+    # (b) windows of one token and of two (w = grid: every cell its own window would be 1 token; 5 x 5 windows on a 6 x 6 grid)
+    wl = make_custom(name="edge_b", seed=32, dtype="bf16", batch=1, grid_h=6, grid_w=6, text_lens=(5,), d=256, heads=2,
+                     head_dim=128, windows_per_axis=(5,), n_final=30)
+    rep, _ = check_edge_step(sched_for(wl, 5), 0, wl.cu_vis, wl.X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
+    print("[edge cases] (b) %d -> %d tokens, %d edges" % (rep.n_in, rep.n_out, rep.edges), flush=True)
+    # (c) identical tokens inside every window: every FD is exactly zero, positions decide
+    wl = make_custom(name="edge_c", seed=33, dtype="bf16", batch=1, grid_h=12, grid_w=12, text_lens=(7,), d=256, heads=2,
+                     head_dim=128, windows_per_axis=(2,), n_final=100)
+    X = wl.X.copy()
+    X[:] = X[0]
+    rep, _ = check_edge_step(sched_for(wl, 2), 0, wl.cu_vis, X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
+    assert rep.window_ties == 0
+    print("[edge cases] (c) %d -> %d tokens, %d edges" % (rep.n_in, rep.n_out, rep.edges), flush=True)
+    # (d) the largest supported window (256 tokens: a 16 x 16 grid as one window), distances
+    for metric in ("cosine", "euclidean", "l2sq"):
+        wl = make_custom(name="edge_d", seed=34, dtype="bf16", batch=1, grid_h=16, grid_w=16, text_lens=(33,), d=512,
+                         heads=4, head_dim=128, windows_per_axis=(1,), n_final=200, structure="grid")
+        rep, _ = check_edge_step(sched_for(wl, 1, metric), 0, wl.cu_vis, wl.X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
+        print("[edge cases] (d) %s %d -> %d tokens, %d edges, %d tied" % (metric, rep.n_in, rep.n_out, rep.edges, rep.window_ties), flush=True)
+
+
+@pytest.mark.gpu
+def test_edge_topk_refusals():
+    """What the edge reading does not support is refused before any launch."""
+    import paper_2605_00789_amd as L
+    from paper_2605_00789_amd import binding as B
+    dev = "cuda:0"
+    n, d = 600, 64
+    h_cu = np.array([0, n], dtype=np.int32)
+    cu = torch.from_numpy(h_cu).to(dev)
+    offs = np.array([0, n], dtype=np.int32)
+    win = torch.from_numpy(offs).to(dev)
+    toks = torch.arange(n, dtype=torch.int32, device=dev)
+    k = np.array([3], dtype=np.int32)
+
+    def prob(**kw):
+        a = dict(batch=1, d=d, heads=2, head_dim=32, dtype="f32", h_cu_vis=h_cu, cu_vis=cu, n_windows=1, win_offsets=win,
+                 win_tokens=toks, win_remove=torch.from_numpy(k).to(dev), h_win_offsets=offs, h_win_remove=k,
+                 match=B.MATCH_EDGE_TOPK)
+        a.update(kw)
+        return B.Problem(**a)
+
+    with pytest.raises(L.LightKVError) as e:      # a window of 600 tokens
+        B.lightkv_workspace_size(prob())
+    assert e.value.status == 5
+    with pytest.raises(L.LightKVError) as e:      # the host's counts are required
+        B.lightkv_workspace_size(prob(h_win_remove=None))
+    assert e.value.status in (1, 5)
+    small = np.array([0, 200, n], dtype=np.int32)
+    with pytest.raises(L.LightKVError) as e:      # more edges than the window has pairs
+        B.lightkv_workspace_size(prob(n_windows=2, h_win_offsets=small, win_offsets=torch.from_numpy(small).to(dev),
+                                      h_win_remove=np.array([100 * 100 + 1, 0], dtype=np.int32),
+                                      win_remove=torch.zeros(2, dtype=torch.int32, device=dev)))
+    assert e.value.status in (4, 5)
