@@ -34,6 +34,11 @@ def _parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="3", help="1..5, halving, global (default 3: the N=2880 LLaVA-NeXT-shaped layer)")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
+    ap.add_argument("--match", default="best_per_a", choices=["best_per_a", "edge_topk"],
+                    help="edge_topk: Step 2 read literally, floor(rho v / 2) lowest-FD edges per window (token counts "
+                         "depend on the data: eager, two small read-backs per stage)")
+    ap.add_argument("--rho", type=float, default=0.36, help="edge_topk: ratio rho of Step 2 (0.36: as many edges per "
+                    "window as the default schedule of config 3 removes tokens)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-repeats", type=int, default=20, help="oracle steps timed for cpu_baseline (about 10 s)")
     ap.add_argument("--cold", action="store_true",
@@ -65,12 +70,99 @@ def measured_traffic(workload_name):
     return None
 
 
+def bench_edge_topk(args):
+    """The schedule with the k lowest edges per window: stages whose windows fit the variant's limit, eager, host
+    read-backs included in the timed region (they are part of the step: the next stage cannot be sized without them)."""
+    import numpy as np
+    import torch
+    from workloads import make_workload
+    from paper_2605_00789_amd import EdgeTopKSchedule, to_device as to_dev, max_window_cells
+    from paper_2605_00789_amd import binding as B
+    cfg = int(args.workload) if args.workload.isdigit() else args.workload
+    wl = make_workload(cfg)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    ws_axis = [w for w in wl.windows_per_axis
+               if w > 0 and max_window_cells(wl.tiles, wl.grid_h, wl.grid_w, w) <= B.EDGE_MAX_WINDOW_TOKENS]
+    sched = EdgeTopKSchedule(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, tiles=wl.tiles,
+                             grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt, windows_per_axis=ws_axis,
+                             rho=[args.rho] * len(ws_axis))
+    X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+    pos = torch.from_numpy(wl.pos).to(dev)
+    for _ in range(max(args.warmup, 1)):
+        res = sched.run(wl.cu_vis, X, K, V, Q, pos)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        res = sched.run(wl.cu_vis, X, K, V, Q, pos)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    # per-call GPU time from events around the calls (a pass of its own)
+    acc = {}
+    n_inst = max(5, min(args.steps, 30))
+    for _ in range(n_inst):
+        marks = []
+        sched.run(wl.cu_vis, X, K, V, Q, pos, marks=marks)
+        torch.cuda.synchronize()
+        stage = 0
+        for (na, ea), (nb, eb) in zip(marks[0::2], marks[1::2]):
+            if na == "build_windows":
+                stage += 1
+            acc.setdefault("stage%d.%s" % (stage, na), []).append(ea.elapsed_time(eb) * 1e3)
+    calls_us = {k: round(sorted(v)[len(v) // 2], 2) for k, v in acc.items()}
+    n_in = [int(wl.cu_vis[-1])] + [int(r.h_cu_vis_out[-1]) for r in res[:-1]]
+    n_out = [int(r.h_cu_vis_out[-1]) for r in res]
+    eb_ = _elem_bytes(wl.dtype)
+    rows_b = sum(3 * (a + b) * wl.d * eb_ for a, b in zip(n_in, n_out))
+    rows_us = sum(v for k, v in calls_us.items() if k.endswith("aggregate_compact"))
+    ach = rows_b / (rows_us * 1e-6) / 1e9
+    out = {
+        "metric": "vision tokens compressed/sec per layer", "value": round(sum(n_in) / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "match": "edge_topk", "rho": args.rho, "batch": wl.batch, "stages": len(ws_axis),
+                   "windows_per_axis": ws_axis, "tokens_in_per_stage": n_in, "tokens_out_per_stage": n_out,
+                   "edges_per_stage": [int(r.h_win_edges.sum()) for r in res], "launch": "eager + 2 read-backs per stage"},
+        "roofline": {"kernel": "rows_kernel (lightkv_aggregate_compact)", "bound": "hbm", "achieved": round(ach, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                     "launches_per_step": len(ws_axis), "avg_launch_us": round(rows_us / len(ws_axis), 2),
+                     "algorithmic_bytes_per_launch": rows_b // len(ws_axis),
+                     "note": "call interval from events around the call (includes launch overhead of an eager call)"},
+        "calls_us": calls_us,
+    }
+    if not args.no_cpu_baseline:
+        from oracle import lightkv_oracle as O
+        t0 = time.perf_counter()
+        reps = max(1, args.cpu_repeats // 4)
+        for _ in range(reps):
+            Xc, Kc, Vc, posc, cu = wl.X, wl.K, wl.V, wl.pos, wl.cu_vis
+            Q64 = O.widen(wl.Q, wl.dtype)
+            for s, w in enumerate(ws_axis):
+                wo, wt = O.build_windows(posc, cu, wl.tiles, wl.grid_h, wl.grid_w, w)
+                v = np.diff(wo)
+                k = np.minimum(np.floor(args.rho * v / 2.0 + 1e-9).astype(np.int64), ((v + 1) // 2) * (v // 2))
+                r = O.compress_stage_edges(O.widen(Xc, wl.dtype), O.widen(Kc, wl.dtype), O.widen(Vc, wl.dtype), Q64, posc, cu,
+                                           wl.cu_txt, wl.heads, wl.head_dim, wo, wt, k)
+                Xc, Kc, Vc = (O.round_to_storage(t, wl.dtype) for t in (r.X, r.K, r.V))
+                posc, cu = r.pos, r.cu_vis
+        dt = (time.perf_counter() - t0) / reps
+        out["cpu_baseline"] = {"value": round(sum(n_in) / dt, 1), "unit": "tokens/s", "cores": os.cpu_count() or 1,
+                               "kind": "oracle", "sample": "%d full schedules of the same workload, numpy fp64, %.2f s each" % (reps, dt)}
+    print(json.dumps(out))
+
+
 def main():
     args = _parse()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the step has no cross-GPU part); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+    if args.match == "edge_topk":
+        import torch
+        if not torch.cuda.is_available():
+            print("bench.py: no GPU visible", file=sys.stderr)
+            sys.exit(1)
+        return bench_edge_topk(args)
     import numpy as np
     import torch
     if not torch.cuda.is_available():

@@ -14,7 +14,7 @@
 //                          cnt[b]      number of selected edges into b
 //                          best_fd / best_dst  of every A node, as the default selection reports them
 //                        plus the window's edge list (a, b, position of a among b's sources) at a fixed offset
-//                        (the k of the windows before it) for edge_fill_kernel.
+//                        (the k of the windows before it) for edge_fill_kernel; every window writes all of its slots.
 //   select_scan_kernel : unchanged (lk_select.hip): new_index from dst, grp_offsets from cnt.
 //   edge_fill_kernel   : grp_src[grp_offsets[b] + position] = a for every edge.
 #include "lk_fd_body.h"
@@ -23,6 +23,7 @@ namespace lk {
 
 constexpr int EDGE_THREADS = 256;
 constexpr int EDGE_WAVES = EDGE_THREADS / 64;
+constexpr int EDGE_UNROLL = 4;
 
 struct EdgeArgs {
   const int32_t *win_remove;   // k per window
@@ -44,6 +45,20 @@ __device__ __forceinline__ int edge_block_sum(int v, int *wsum) {
   return t;
 }
 
+// Sum of the KS slices of one partial sum, in slice order (fp64), all loads issued together.
+template <int KS>
+__device__ __forceinline__ double edge_sum_slices(const float *p, int64_t ks_stride) {
+  float v[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) v[ks] = p[ks * ks_stride];
+  double s = 0.0;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) s += (double)v[ks];
+  return s;
+}
+
+// KS: slices of the hidden axis the partial tiles were computed in (g.ksplit)
+template <int KS>
 __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, EdgeArgs q) {
   extern __shared__ uint32_t keys[];   // [nA][pitch]
   __shared__ double na2[EDGE_MAX_SIDE], nb2[EDGE_MAX_SIDE];
@@ -51,26 +66,34 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
   __shared__ int col_cnt[EDGE_MAX_SIDE], col_start[EDGE_MAX_SIDE];
   __shared__ int wsum[EDGE_WAVES];
   __shared__ int pick[2];
+  __shared__ int tok[2 * EDGE_MAX_SIDE];   // the window's tokens (checked), in list order: a token lookup inside a loop
+                                           // must not be a trip to global memory
   const int w = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const WinInfo wi = win_info(g, w);
   const int nA = wi.nA, nB = wi.nB;
   if (nA > EDGE_MAX_SIDE || nB > EDGE_MAX_SIDE) return;   // the host refuses such windows; nothing is written
   const int E = nA * nB;
-  int k = q.win_remove[w];
-  k = k < 0 ? 0 : (k > E ? E : k);
+  const int k_asked = q.win_remove[w];
+  const int k = k_asked < 0 ? 0 : (k_asked > E ? E : k_asked);
 
-  // slots of this window in the edge list: the k of the windows before it
+  for (int i = tid; i < nA + nB; i += EDGE_THREADS) tok[i] = checked_token(g, wi.off + i);
+  // slots of this window in the edge list: the k of the windows before it (the barriers inside also publish tok[])
   int before = 0;
   for (int i = tid; i < w; i += EDGE_THREADS) before += q.win_remove[i];
   const int edge_base = edge_block_sum(before, wsum);
 
+  // slots this window was given but does not use (a device-side count above its number of pairs) are marked empty
+  for (int i = k + tid; i < k_asked; i += EDGE_THREADS) {
+    const int slot = edge_base + i;
+    if (slot < q.sum_k) { q.edges[slot] = -1; q.edges[q.sum_k + slot] = -1; q.edges[2 * q.sum_k + slot] = 0; }
+  }
   if (nB == 0) {   // a window of one token (or none): no pair, nothing leaves
     for (int i = tid; i < nA; i += EDGE_THREADS) {
-      const int tok = checked_token(g, wi.off + i);
-      if (tok >= 0) {
-        q.dst[tok] = -1; q.cnt[tok] = 0; q.src_rank[tok] = 0;
-        g.best_fd[tok] = __uint_as_float(0x7f800000u);
-        g.best_dst[tok] = -1;
+      const int t = tok[i];
+      if (t >= 0) {
+        q.dst[t] = -1; q.cnt[t] = 0; q.src_rank[t] = 0;
+        g.best_fd[t] = __uint_as_float(0x7f800000u);
+        g.best_dst[t] = -1;
       }
     }
     return;
@@ -86,25 +109,46 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
   for (int i = tid; i < nA + nB; i += EDGE_THREADS) {
     if (i < nA) {
       const int r = (g.group > 1) ? row_shift + i : (i & 31);
-      na2[i] = sum_slices(g.partial + (int64_t)tile_of(i, 0) * FD_TILE_FLOATS + 32 * 32 + r, ks_stride, g.ksplit);
+      na2[i] = edge_sum_slices<KS>(g.partial + (int64_t)tile_of(i, 0) * FD_TILE_FLOATS + 32 * 32 + r, ks_stride);
     } else {
       const int lb = i - nA;
       const int c = (g.group > 1) ? row_shift + lb : (lb & 31);
-      nb2[lb] = sum_slices(g.partial + (int64_t)tile_of(0, lb) * FD_TILE_FLOATS + 32 * 32 + 32 + c, ks_stride, g.ksplit);
+      nb2[lb] = edge_sum_slices<KS>(g.partial + (int64_t)tile_of(0, lb) * FD_TILE_FLOATS + 32 * 32 + 32 + c, ks_stride);
     }
   }
   __syncthreads();
 
-  // ---- FD of every pair -> order-preserving key in LDS
+  // ---- FD of every pair -> order-preserving key in LDS.  EDGE_UNROLL pairs per thread and round: the loads of all
+  // of them (every slice) are issued before the first is used; a round is one trip to memory, so this loop is as long
+  // as its number of rounds
   const int pitch = nB | 1;   // odd: a thread per row and a thread per column both walk the array without bank conflicts
-  for (int e = tid; e < E; e += EDGE_THREADS) {
-    const int la = e / nB, lb = e - la * nB;
-    const int r = (g.group > 1) ? row_shift + la : (la & 31);
-    const int c = (g.group > 1) ? row_shift + lb : (lb & 31);
-    const double dot = sum_slices(g.partial + (int64_t)tile_of(la, lb) * FD_TILE_FLOATS + r * 32 + c, ks_stride, g.ksplit);
-    float f = (float)divergence(g.metric, dot, na2[la], nb2[lb]);
-    if (!(f >= 0.f)) f = __uint_as_float(0x7f800000u);   // NaN ranks last, like +inf
-    keys[la * pitch + lb] = f32_order_key(f);
+  // pair index -> (A position, B position) without a division per pair: a step of EDGE_THREADS pairs moves the position
+  // by (step_a, step_b) with at most one carry
+  const int step_a = EDGE_THREADS / nB, step_b = EDGE_THREADS - step_a * nB;
+  const int la0 = tid / nB, lb0 = tid - la0 * nB;   // this thread's first pair
+  {
+    int la_n = la0, lb_n = lb0;
+    for (int e0 = tid; e0 < E; e0 += EDGE_THREADS * EDGE_UNROLL) {
+      double dot[EDGE_UNROLL];
+      int la[EDGE_UNROLL], lb[EDGE_UNROLL];
+#pragma unroll
+      for (int u = 0; u < EDGE_UNROLL; ++u) {
+        const bool ok = e0 + u * EDGE_THREADS < E;
+        la[u] = ok ? la_n : nA - 1;   // surplus pairs re-read the last one and are dropped
+        lb[u] = ok ? lb_n : nB - 1;
+        lb_n += step_b; la_n += step_a;
+        if (lb_n >= nB) { lb_n -= nB; ++la_n; }
+        const int r = (g.group > 1) ? row_shift + la[u] : (la[u] & 31);
+        const int c = (g.group > 1) ? row_shift + lb[u] : (lb[u] & 31);
+        dot[u] = edge_sum_slices<KS>(g.partial + (int64_t)tile_of(la[u], lb[u]) * FD_TILE_FLOATS + r * 32 + c, ks_stride);
+      }
+#pragma unroll
+      for (int u = 0; u < EDGE_UNROLL; ++u) {
+        float f = (float)divergence(g.metric, dot[u], na2[la[u]], nb2[lb[u]]);
+        if (!(f >= 0.f)) f = __uint_as_float(0x7f800000u);   // NaN ranks last, like +inf
+        if (e0 + u * EDGE_THREADS < E) keys[la[u] * pitch + lb[u]] = f32_order_key(f);
+      }
+    }
   }
   __syncthreads();
 
@@ -116,10 +160,32 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
   for (int shift = 24; k > 0 && shift >= 0; shift -= 8) {   // k is uniform over the workgroup
     hist[tid] = 0;
     __syncthreads();
-    for (int e = tid; e < E; e += EDGE_THREADS) {
-      const int la = e / nB, lb = e - la * nB;
-      const uint32_t key = keys[la * pitch + lb];
-      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+    if (shift == 24) {
+      // FD lies in [0, 2]: nearly all keys share their top byte, and 64 lanes adding to one LDS word take 64 turns.
+      // The lanes of a wave that hold the same byte are counted with a ballot and added once.
+      int la = la0, lb = lb0;
+      for (int e0 = 0; e0 < E; e0 += EDGE_THREADS) {   // workgroup-uniform trip count
+        const int e = e0 + tid;
+        const int digit = e < E ? (int)(keys[la * pitch + lb] >> 24) : -1;
+        lb += step_b; la += step_a;
+        if (lb >= nB) { lb -= nB; ++la; }
+        unsigned long long todo = __ballot(digit >= 0);
+        while (todo) {
+          const int leader = __ffsll((long long)todo) - 1;
+          const int dl = __shfl(digit, leader, 64);
+          const unsigned long long same = __ballot(digit == dl);
+          if (lane == leader) atomicAdd(&hist[dl], __popcll(same));
+          todo &= ~same;
+        }
+      }
+    } else {
+      int la = la0, lb = lb0;
+      for (int e = tid; e < E; e += EDGE_THREADS) {
+        const uint32_t key = keys[la * pitch + lb];
+        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        lb += step_b; la += step_a;
+        if (lb >= nB) { lb -= nB; ++la; }
+      }
     }
     __syncthreads();
     // inclusive scan of the 256 bins, one per thread
@@ -150,9 +216,12 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
   // "selected" simply means key <= threshold.
   if (any && remaining < n_equal) {
     int base = 0;
+    int la_n = la0, lb_n = lb0;
     for (int e0 = 0; e0 < E; e0 += EDGE_THREADS) {   // workgroup-uniform trip count
       const int e = e0 + tid;
-      const int la = e < E ? e / nB : 0, lb = e < E ? e - la * nB : 0;
+      const int la = e < E ? la_n : 0, lb = e < E ? lb_n : 0;
+      lb_n += step_b; la_n += step_a;
+      if (lb_n >= nB) { lb_n -= nB; ++la_n; }
       const bool eq = e < E && keys[la * pitch + lb] == threshold;
       const unsigned long long bal = __ballot(eq);
       const int in_wave = __popcll(bal & ((1ull << lane) - 1ull));
@@ -190,7 +259,7 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
   }
   __syncthreads();
   if (tid < nB) {
-    const int b_tok = checked_token(g, wi.off + 2 * tid + 1);
+    const int b_tok = tok[2 * tid + 1];
     if (b_tok >= 0) {
       q.dst[b_tok] = -1; q.cnt[b_tok] = my_cnt; q.src_rank[b_tok] = 0;
       g.best_fd[b_tok] = __uint_as_float(0x7f800000u);
@@ -201,7 +270,7 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
       if (any && keys[la * pitch + tid] <= threshold) {
         const int slot = edge_base + col_start[tid] + pos;
         if (slot < q.sum_k) {
-          q.edges[slot] = checked_token(g, wi.off + 2 * la);
+          q.edges[slot] = tok[2 * la];
           q.edges[q.sum_k + slot] = b_tok;
           q.edges[2 * q.sum_k + slot] = pos;
         }
@@ -224,15 +293,15 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
     int rank = 0;
     if (sel_c >= 0)
       for (int l2 = 0; l2 < la; ++l2) rank += keys[l2 * pitch + sel_c] <= threshold ? 1 : 0;   // sel_c >= 0 implies any
-    const int a_tok = checked_token(g, wi.off + 2 * la);
+    const int a_tok = tok[2 * la];
     if (a_tok >= 0) {
-      q.dst[a_tok] = sel_c >= 0 ? checked_token(g, wi.off + 2 * sel_c + 1) : -1;
+      q.dst[a_tok] = sel_c >= 0 ? tok[2 * sel_c + 1] : -1;
       q.src_rank[a_tok] = rank;
       q.cnt[a_tok] = 0;
       // order key back to the float it came from
       const uint32_t u = (best & 0x80000000u) ? (best & 0x7fffffffu) : ~best;
       g.best_fd[a_tok] = __uint_as_float(u);
-      g.best_dst[a_tok] = best_c >= 0 ? checked_token(g, wi.off + 2 * best_c + 1) : -1;
+      g.best_dst[a_tok] = best_c >= 0 ? tok[2 * best_c + 1] : -1;
     }
   }
 }
@@ -244,12 +313,6 @@ __global__ __launch_bounds__(256) void edge_fill_kernel(EdgeArgs q, const int32_
   if ((unsigned)a >= (unsigned)sum_n || (unsigned)b >= (unsigned)sum_n) return;
   const int slot = grp_offsets[b] + pos;
   if (slot >= 0 && slot < q.sum_k) grp_src[slot] = a;
-}
-
-// Every slot of the edge list starts out empty (-1): a window whose k was clipped on the device leaves some unwritten.
-__global__ __launch_bounds__(256) void edge_clear_kernel(EdgeArgs q) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < 3 * q.sum_k) q.edges[i] = -1;
 }
 
 hipError_t launch_edge_select(const FdPlan &plan, int dtype, const void *X, int64_t ldx, int d, int n_windows,
@@ -264,22 +327,30 @@ hipError_t launch_edge_select(const FdPlan &plan, int dtype, const void *X, int6
   if (e != hipSuccess) return e;
   const FdArgs g = make_fd_args(plan, dtype, X, ldx, d, n_windows, sum_n, win_offsets, win_tokens, partial, best_fd, best_dst);
   EdgeArgs q{win_remove, dst, cnt, src_rank, edges, sum_k};
-  if (sum_k > 0) {
-    hipLaunchKernelGGL(edge_clear_kernel, dim3((unsigned)((3 * sum_k + 255) / 256)), dim3(256), 0, stream, q);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
   const size_t lds = (size_t)maxA * (size_t)(maxB | 1) * sizeof(uint32_t);
   static bool allowed[64] = {};   // up to 66 KB of dynamic LDS: above the 64 KB default, set once per device
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   if (!allowed[dev]) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(edge_select_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)((size_t)EDGE_MAX_SIDE * (EDGE_MAX_SIDE | 1) * sizeof(uint32_t)));
-    if (e != hipSuccess) return e;
+    const int max_lds = (int)((size_t)EDGE_MAX_SIDE * (EDGE_MAX_SIDE | 1) * sizeof(uint32_t));
+    const void *kernels[5] = {reinterpret_cast<const void *>(edge_select_kernel<1>), reinterpret_cast<const void *>(edge_select_kernel<2>),
+                              reinterpret_cast<const void *>(edge_select_kernel<4>), reinterpret_cast<const void *>(edge_select_kernel<8>),
+                              reinterpret_cast<const void *>(edge_select_kernel<16>)};
+    for (const void *kf : kernels) {
+      e = hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+      if (e != hipSuccess) return e;
+    }
     allowed[dev] = true;
   }
-  hipLaunchKernelGGL(edge_select_kernel, dim3((unsigned)n_windows), dim3(EDGE_THREADS), lds, stream, g, q);
+  const dim3 grid((unsigned)n_windows), block(EDGE_THREADS);
+  switch (plan.ksplit) {
+    case 1: hipLaunchKernelGGL(edge_select_kernel<1>, grid, block, lds, stream, g, q); break;
+    case 2: hipLaunchKernelGGL(edge_select_kernel<2>, grid, block, lds, stream, g, q); break;
+    case 4: hipLaunchKernelGGL(edge_select_kernel<4>, grid, block, lds, stream, g, q); break;
+    case 8: hipLaunchKernelGGL(edge_select_kernel<8>, grid, block, lds, stream, g, q); break;
+    case 16: hipLaunchKernelGGL(edge_select_kernel<16>, grid, block, lds, stream, g, q); break;
+    default: return hipErrorInvalidValue;   // make_fd_plan doubles from 1 up to 16
+  }
   return hipGetLastError();
 }
 

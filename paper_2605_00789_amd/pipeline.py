@@ -228,7 +228,15 @@ class EdgeTopKSchedule:
         self.h_cu_txt = np.ascontiguousarray(cu_txt, dtype=np.int32)
         self.cu_txt = torch.from_numpy(self.h_cu_txt).to(self.device)
 
-    def run_step(self, s: int, h_cu_vis: np.ndarray, X, K, V, Q, pos, *, xi_given=None, h_win_edges=None) -> EdgeStepResult:
+    def run_step(self, s: int, h_cu_vis: np.ndarray, X, K, V, Q, pos, *, xi_given=None, h_win_edges=None,
+                 marks: Optional[list] = None) -> EdgeStepResult:
+        """marks: if a list, (name, event) pairs are appended around the three library calls (current stream)."""
+        def mark(name):
+            if marks is not None:
+                ev = torch.cuda.Event(enable_timing=True)
+                ev.record()
+                marks.append((name, ev))
+
         dev, i32 = self.device, dict(dtype=torch.int32, device=self.device)
         batch, w = self.batch, self.windows_per_axis[s]
         h_cu_vis = np.ascontiguousarray(h_cu_vis, dtype=np.int32)
@@ -237,8 +245,10 @@ class EdgeTopKSchedule:
         n_windows = batch * windows_per_sequence(self.tiles, w)
         win_offsets = torch.empty(n_windows + 1, **i32)
         win_tokens = torch.empty(max(sum_n, 1), **i32)
+        mark("build_windows")
         B.lightkv_build_windows(batch, h_cu_vis, cu_vis, pos, self.tiles, self.grid_h, self.grid_w, w, win_offsets,
                                 win_tokens)
+        mark("end")
         h_win_offsets = win_offsets.cpu().numpy()            # first read-back: the window sizes
         h_k = edge_counts(h_win_offsets, self.rho[s]) if h_win_edges is None else np.ascontiguousarray(h_win_edges, dtype=np.int32)
         win_remove = torch.from_numpy(h_k).to(dev)
@@ -255,22 +265,26 @@ class EdgeTopKSchedule:
         grp_offsets = torch.empty(sum_n + 1, **i32)
         grp_src = torch.empty(max(int(h_k.sum()), 1), **i32)
         cu_vis_out = torch.empty(batch + 1, **i32)
+        mark("score_select")
         B.lightkv_score_select(prob, X, Q, K, xi, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, ws,
                                xi_mode=B.XI_TEXT_QUERY if xi_given is None else B.XI_GIVEN)
+        mark("end")
         # every window that takes an edge loses at least one token: an upper bound on the rows written
         rows = max(sum_n - int((h_k > 0).sum()), 1)
         X_out, K_out, V_out = (torch.empty(rows, self.d, dtype=tdt, device=dev) for _ in range(3))
         pos_out = torch.empty(rows, **i32)
+        mark("aggregate_compact")
         B.lightkv_aggregate_compact(prob, new_index, grp_offsets, grp_src, xi, X, K, V, pos, X_out, K_out, V_out, pos_out)
+        mark("end")
         h_out = cu_vis_out.cpu().numpy()                     # second read-back: the sequence lengths after the step
         n_out = int(h_out[-1])
         return EdgeStepResult(h_out, X_out[:n_out], K_out[:n_out], V_out[:n_out], pos_out[:n_out], xi, best_fd, best_dst,
                               dst, new_index, grp_offsets, grp_src, win_offsets, win_tokens, h_k)
 
-    def run(self, h_cu_vis: np.ndarray, X, K, V, Q, pos) -> List[EdgeStepResult]:
+    def run(self, h_cu_vis: np.ndarray, X, K, V, Q, pos, marks: Optional[list] = None) -> List[EdgeStepResult]:
         out = []
         for s in range(len(self.windows_per_axis)):
-            r = self.run_step(s, h_cu_vis, X, K, V, Q, pos)
+            r = self.run_step(s, h_cu_vis, X, K, V, Q, pos, marks=marks)
             out.append(r)
             h_cu_vis, X, K, V, pos = r.h_cu_vis_out, r.X, r.K, r.V, r.pos
         return out

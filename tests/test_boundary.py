@@ -71,6 +71,19 @@ def test_workspace_size_and_descriptor_validation(B):
     assert _ws_size(B, _problem(B, dtype=7))[0] == 5
     assert _ws_size(B, _problem(B, metric=2))[0] == 0 and _ws_size(B, _problem(B, metric=3))[0] == 5   # lightkv_metric
     assert _ws_size(B, _problem(B, metric=-1))[0] == 5
+    # lightkv_match: the k lowest edges need the host's counts, count pairs instead of A nodes, and bound the window
+    assert _ws_size(B, _problem(B, match=2))[0] == 5 and _ws_size(B, _problem(B, match=-1))[0] == 5
+    assert _ws_size(B, _problem(B, reserved=1))[0] == 5
+    st_e, n_e = _ws_size(B, _problem(B, match=1, h_win_remove=np.array([4, 3], dtype=np.int32)))   # 2 x 2 pairs per window
+    assert st_e == 0 and n_e >= _ws_size(B, _problem(B))[1]
+    assert _ws_size(B, _problem(B, match=0, h_win_remove=np.array([4, 3], dtype=np.int32)))[0] == 4   # more than |A| = 2
+    assert _ws_size(B, _problem(B, match=1, h_win_remove=np.array([5, 0], dtype=np.int32)))[0] == 4   # more than 4 pairs
+    p_nohost = _problem(B, match=1)
+    p_nohost.h_win_remove = None
+    assert _ws_size(B, p_nohost)[0] == 1
+    big = np.array([0, 300], dtype=np.int32)
+    assert _ws_size(B, _problem(B, match=1, n_windows=1, h_cu_vis=big, h_win_offsets=big,
+                                h_win_remove=np.array([1], dtype=np.int32)))[0] == 5                  # 300-token window
     assert _ws_size(B, _problem(B, batch=0))[0] == 2
     assert _ws_size(B, _problem(B, h_cu_vis=np.array([1, 8], dtype=np.int32)))[0] == 2
     assert _ws_size(B, _problem(B, h_cu_vis=np.array([0, 20000], dtype=np.int32),
@@ -119,6 +132,9 @@ def test_entry_points_reject_bad_arguments_before_launch(B):
     # select
     assert lib.lightkv_select(C.byref(p), fake, fake, None, fake, fake, fake, fake, fake, ws, None) == 1
     assert lib.lightkv_select(C.byref(p), fake, fake, fake, fake, fake, fake, fake, fake, 16, None) == 6
+    # the k lowest edges cannot be chosen from per-node scores: only lightkv_score_select takes that reading
+    pe = _problem(B, match=1)
+    assert lib.lightkv_select(C.byref(pe), fake, fake, fake, fake, fake, fake, fake, fake, ws, None) == 5
     # aggregate / compact
     assert lib.lightkv_aggregate(C.byref(p), None, fake, fake, fake, 64, fake, 64, fake, 64, None) == 1
     assert lib.lightkv_aggregate(C.byref(p), fake, fake, fake, fake, 8, fake, 64, fake, 64, None) == 2
