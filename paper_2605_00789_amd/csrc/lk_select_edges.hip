@@ -24,12 +24,14 @@ namespace lk {
 constexpr int EDGE_THREADS = 256;
 constexpr int EDGE_WAVES = EDGE_THREADS / 64;
 constexpr int EDGE_UNROLL = 4;
+constexpr int EDGE_ITEMS = EDGE_MAX_SIDE * EDGE_MAX_SIDE / EDGE_THREADS;   // keys per thread, at most
 
 struct EdgeArgs {
   const int32_t *win_remove;   // k per window
   int32_t *dst, *cnt, *src_rank;
   int32_t *edges;              // [3][sum_k]: A token, B token, position among the B token's sources
   int sum_k;
+  int key_capacity;            // 32-bit keys the launch reserved LDS for
 };
 
 // Workgroup-wide sum of one int per thread; every thread gets the total.
@@ -71,7 +73,9 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
   const int w = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const WinInfo wi = win_info(g, w);
   const int nA = wi.nA, nB = wi.nB;
-  if (nA > EDGE_MAX_SIDE || nB > EDGE_MAX_SIDE) return;   // the host refuses such windows; nothing is written
+  // the host refuses such windows, and sizes the LDS from its own bound on the window: a device-side list that breaks
+  // either is left alone
+  if (nA > EDGE_MAX_SIDE || nB > EDGE_MAX_SIDE || nA * (nB | 1) > q.key_capacity) return;
   const int E = nA * nB;
   const int k_asked = q.win_remove[w];
   const int k = k_asked < 0 ? 0 : (k_asked > E ? E : k_asked);
@@ -152,6 +156,20 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
   }
   __syncthreads();
 
+  // ---- every thread takes its keys into registers (pair e = it * EDGE_THREADS + tid): the passes below then touch
+  // LDS for the histogram only
+  uint32_t kreg[EDGE_ITEMS];
+  {
+    int la = la0, lb = lb0;
+#pragma unroll
+    for (int it = 0; it < EDGE_ITEMS; ++it) {
+      if (it * EDGE_THREADS >= E) break;   // uniform over the workgroup
+      kreg[it] = (it * EDGE_THREADS + tid < E) ? keys[la * pitch + lb] : 0u;
+      lb += step_b; la += step_a;
+      if (lb >= nB) { lb -= nB; ++la; }
+    }
+  }
+
   // ---- k-th smallest key: radix select, most significant byte first
   uint32_t prefix = 0, mask = 0;
   int remaining = k;   // how many of the keys that match the prefix so far are wanted
@@ -160,33 +178,23 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
   for (int shift = 24; k > 0 && shift >= 0; shift -= 8) {   // k is uniform over the workgroup
     hist[tid] = 0;
     __syncthreads();
-    if (shift == 24) {
-      // FD lies in [0, 2]: nearly all keys share their top byte, and 64 lanes adding to one LDS word take 64 turns.
-      // The lanes of a wave that hold the same byte are counted with a ballot and added once.
-      int la = la0, lb = lb0;
-      for (int e0 = 0; e0 < E; e0 += EDGE_THREADS) {   // workgroup-uniform trip count
-        const int e = e0 + tid;
-        const int digit = e < E ? (int)(keys[la * pitch + lb] >> 24) : -1;
-        lb += step_b; la += step_a;
-        if (lb >= nB) { lb -= nB; ++la; }
-        unsigned long long todo = __ballot(digit >= 0);
-        while (todo) {
-          const int leader = __ffsll((long long)todo) - 1;
-          const int dl = __shfl(digit, leader, 64);
-          const unsigned long long same = __ballot(digit == dl);
-          if (lane == leader) atomicAdd(&hist[dl], __popcll(same));
-          todo &= ~same;
-        }
+    // FD lies in [0, 2], so most keys share their leading bytes and plain atomics would queue on one LDS word: a thread
+    // adds a run of equal digits once
+    int run_digit = -1, run = 0;
+#pragma unroll
+    for (int it = 0; it < EDGE_ITEMS; ++it) {
+      if (it * EDGE_THREADS >= E) break;
+      const uint32_t key = kreg[it];
+      const bool in = it * EDGE_THREADS + tid < E && (key & mask) == prefix;
+      const int digit = in ? (int)((key >> shift) & 255u) : run_digit;
+      if (digit != run_digit) {
+        if (run > 0) atomicAdd(&hist[run_digit], run);
+        run_digit = digit;
+        run = 0;
       }
-    } else {
-      int la = la0, lb = lb0;
-      for (int e = tid; e < E; e += EDGE_THREADS) {
-        const uint32_t key = keys[la * pitch + lb];
-        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
-        lb += step_b; la += step_a;
-        if (lb >= nB) { lb -= nB; ++la; }
-      }
+      run += in ? 1 : 0;
     }
+    if (run > 0) atomicAdd(&hist[run_digit], run);
     __syncthreads();
     // inclusive scan of the 256 bins, one per thread
     const int h = hist[tid];
@@ -216,13 +224,11 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
   // "selected" simply means key <= threshold.
   if (any && remaining < n_equal) {
     int base = 0;
-    int la_n = la0, lb_n = lb0;
-    for (int e0 = 0; e0 < E; e0 += EDGE_THREADS) {   // workgroup-uniform trip count
-      const int e = e0 + tid;
-      const int la = e < E ? la_n : 0, lb = e < E ? lb_n : 0;
-      lb_n += step_b; la_n += step_a;
-      if (lb_n >= nB) { lb_n -= nB; ++la_n; }
-      const bool eq = e < E && keys[la * pitch + lb] == threshold;
+    int la = la0, lb = lb0;
+#pragma unroll
+    for (int it = 0; it < EDGE_ITEMS; ++it) {
+      if (it * EDGE_THREADS >= E) break;
+      const bool eq = it * EDGE_THREADS + tid < E && kreg[it] == threshold;
       const unsigned long long bal = __ballot(eq);
       const int in_wave = __popcll(bal & ((1ull << lane) - 1ull));
       __syncthreads();
@@ -234,18 +240,32 @@ __global__ __launch_bounds__(EDGE_THREADS) void edge_select_kernel(FdArgs g, Edg
         before_me += (w2 < wave) ? wsum[w2] : 0;
         all += wsum[w2];
       }
-      if (eq && before_me >= remaining) keys[la * pitch + lb] = 0xffffffffu;
+      if (eq && before_me >= remaining) {
+        kreg[it] = 0xffffffffu;
+        keys[la * pitch + lb] = 0xffffffffu;
+      }
       base += all;
+      lb += step_b; la += step_a;
+      if (lb >= nB) { lb -= nB; ++la; }
+    }
+  }
+  // ---- per B node: number of selected edges (every thread adds those among its own keys)
+  if (tid < EDGE_MAX_SIDE) col_cnt[tid] = 0;
+  __syncthreads();   // also publishes the keys changed above
+  if (any) {
+    int lb = lb0;   // only the column of a pair matters here
+#pragma unroll
+    for (int it = 0; it < EDGE_ITEMS; ++it) {
+      if (it * EDGE_THREADS >= E) break;
+      if (it * EDGE_THREADS + tid < E && kreg[it] <= threshold) atomicAdd(&col_cnt[lb], 1);
+      lb += step_b;
+      if (lb >= nB) lb -= nB;
     }
   }
   __syncthreads();
 
-  // ---- per B node: number of selected edges; their slots inside the window's edge list
-  int my_cnt = 0;
-  if (tid < nB)
-    for (int la = 0; la < nA; ++la) my_cnt += (any && keys[la * pitch + tid] <= threshold) ? 1 : 0;
-  if (tid < EDGE_MAX_SIDE) col_cnt[tid] = tid < nB ? my_cnt : 0;
-  __syncthreads();
+  // ---- slots of every B node's edges inside the window's edge list
+  const int my_cnt = tid < nB ? col_cnt[tid] : 0;
   if (tid < 64) {   // exclusive prefix over at most 128 columns: two per lane
     const int c0 = col_cnt[2 * tid], c1 = col_cnt[2 * tid + 1];
     int inc = c0 + c1;
@@ -326,7 +346,7 @@ hipError_t launch_edge_select(const FdPlan &plan, int dtype, const void *X, int6
   hipError_t e = launch_fd_partial(plan, dtype, X, ldx, d, n_windows, sum_n, win_offsets, win_tokens, partial, stream);
   if (e != hipSuccess) return e;
   const FdArgs g = make_fd_args(plan, dtype, X, ldx, d, n_windows, sum_n, win_offsets, win_tokens, partial, best_fd, best_dst);
-  EdgeArgs q{win_remove, dst, cnt, src_rank, edges, sum_k};
+  EdgeArgs q{win_remove, dst, cnt, src_rank, edges, sum_k, maxA * (maxB | 1)};
   const size_t lds = (size_t)maxA * (size_t)(maxB | 1) * sizeof(uint32_t);
   static bool allowed[64] = {};   // up to 66 KB of dynamic LDS: above the 64 KB default, set once per device
   int dev = 0;
