@@ -281,6 +281,36 @@ def main():
                 cold_us += sum(max(a.elapsed_time(b2) * 1e3 - null_us, 0.0) for a, b2 in evs) / n_inst
         del flush, sink
 
+    # ---- per call: algorithmic bytes and flops over the event interval of the call (eager pass above)
+    #   score             reads X once (feature divergence) and Q, K once (xi): e d (N + T + N) bytes;
+    #                     2 d sum_w |A_w| |B_w| flops for FD (window sizes read back from the device) + 2 d sum_b T_b N_b for xi
+    #   aggregate_compact 3 e d (N + n') bytes
+    eb_ = _elem_bytes(wl.dtype)
+    sum_t = int(wl.cu_txt[-1])
+    t_b = np.diff(np.asarray(wl.cu_txt, dtype=np.int64))
+    calls_roofline = {}
+    for s in range(wl.stages):
+        st = pipe.stages[s]
+        n_s = wl.batch * n_ins[s]
+        v = np.diff(st.win_offsets.cpu().numpy().astype(np.int64))
+        fd_flops = 2.0 * wl.d * float((((v + 1) // 2) * (v // 2)).sum())
+        xi_flops = 2.0 * wl.d * float((t_b * n_ins[s]).sum())
+        sc_bytes = eb_ * wl.d * (2 * n_s + sum_t)
+        sc_us = acc[(s, "score")]
+        rw_bytes = rows_bytes(wl, n_ins[s], wl.targets[s])
+        rw_us = acc[(s, "aggregate_compact")]
+        st_us = sum(acc[(s, n)] for n in names)
+        calls_roofline["stage%d" % (s + 1)] = {
+            "tokens_in": n_s,
+            "tokens_per_s_eager": round(n_s / (st_us * 1e-6), 1) if st_us > 0 else None,
+            "score": {"bytes": int(sc_bytes), "GBps": round(sc_bytes / (sc_us * 1e-6) / 1e9, 1) if sc_us > 0 else None,
+                      "fd_flops": int(fd_flops), "xi_flops": int(xi_flops),
+                      "TFLOPs": round((fd_flops + xi_flops) / (sc_us * 1e-6) / 1e12, 2) if sc_us > 0 else None,
+                      "mfma_frac": round((fd_flops + xi_flops) / (sc_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5) if sc_us > 0 else None},
+            "select": {"us": round(acc[(s, "select")], 2), "share_of_stage": round(acc[(s, "select")] / st_us, 3) if st_us > 0 else None},
+            "aggregate_compact": {"bytes": int(rw_bytes), "GBps": round(rw_bytes / (rw_us * 1e-6) / 1e9, 1) if rw_us > 0 else None,
+                                  "hbm_frac": round(rw_bytes / (rw_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if rw_us > 0 else None}}
+
     # ---- roofline of the dominant kernel: message passing + compaction (one kernel per stage, HBM bound)
     rows_us = sum(acc[(s, "aggregate_compact")] for s in range(wl.stages))
     rows_b = sum(rows_bytes(wl, n_ins[s], wl.targets[s]) for s in range(wl.stages))
@@ -339,6 +369,7 @@ def main():
                    "launch": args.mode},
         "roofline": roofline,
         "calls_us": calls_us,
+        "calls_roofline": calls_roofline,
         "event_overhead_us": round(null_us, 2),
     }
     if roofline_cold:
