@@ -41,9 +41,10 @@ def _parse():
                     "window as the default schedule of config 3 removes tokens)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-repeats", type=int, default=20, help="oracle steps timed for cpu_baseline (about 10 s)")
-    ap.add_argument("--cold", action="store_true",
+    ap.add_argument("--cold", action="store_true", default=True,
                     help="also time the dominant kernel with L2 and Infinity Cache flushed before every launch "
-                         "(extra object roofline_cold; the headline figures are unchanged)")
+                         "(extra object roofline_cold; the headline figures are unchanged); on by default")
+    ap.add_argument("--no-cold", dest="cold", action="store_false", help="skip the flushed-cache pass")
     return ap.parse_args()
 
 
