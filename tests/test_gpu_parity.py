@@ -300,6 +300,49 @@ def test_xi_of_batches_one_workgroup_per_sequence_and_head():
                 assert np.all(got[cu_vis[b]:cu_vis[b + 1]] == np.float32(1e-30))
 
 
+def test_xi_with_the_longest_supported_prompt():
+    """Prompts of 4096 tokens (the stated limit) and of a length that is no multiple of any tile, against short and
+    long vision spans; single sequences take the two-pass kernels."""
+    from oracle import lightkv_oracle as O
+    from parity import to_dev
+    from workloads import f32_to_bf16_bits
+    from paper_2605_00789_amd import binding as B
+    rng = np.random.default_rng(4096)
+    for dtype, H, dh, n_vis, n_txt in (("bf16", 2, 128, (300,), (4096,)), ("f32", 4, 32, (1000, 37), (4096, 1001)),
+                                       ("bf16", 3, 64, (129,), (4095,))):
+        d = H * dh
+        cu_vis = np.concatenate([[0], np.cumsum(n_vis)]).astype(np.int32)
+        cu_txt = np.concatenate([[0], np.cumsum(n_txt)]).astype(np.int32)
+        Kf = rng.standard_normal((int(cu_vis[-1]), d)).astype(np.float32)
+        Qf = rng.standard_normal((int(cu_txt[-1]), d)).astype(np.float32)
+        Ks, Qs = (f32_to_bf16_bits(Kf), f32_to_bf16_bits(Qf)) if dtype == "bf16" else (Kf, Qf)
+        want = O.xi_text_query(O.widen(Qs, dtype), O.widen(Ks, dtype), cu_vis, cu_txt, H, dh)
+        win = torch.zeros(1, dtype=torch.int32, device="cuda")
+        prob = B.Problem(batch=len(n_vis), d=d, heads=H, head_dim=dh, dtype=dtype, h_cu_vis=cu_vis,
+                         cu_vis=torch.from_numpy(cu_vis).cuda(), h_cu_txt=cu_txt, cu_txt=torch.from_numpy(cu_txt).cuda(),
+                         n_windows=0, max_window_tokens=16, win_offsets=win, win_tokens=win)
+        ws = torch.empty(max(B.lightkv_workspace_size(prob), 16), dtype=torch.uint8, device="cuda")
+        xi = torch.full((int(cu_vis[-1]),), -1.0, dtype=torch.float32, device="cuda")
+        print("[xi long prompt] %s heads %d x %d, T %s" % (dtype, H, dh, n_txt), flush=True)
+        B.lightkv_score(prob, None, to_dev(Qs, dtype), to_dev(Ks, dtype), xi, None, None, ws)
+        torch.cuda.synchronize()
+        got = xi.cpu().numpy().astype(np.float64)
+        rel = np.abs(got - want) / np.maximum(np.abs(want), 1e-30)
+        assert rel.max() <= (1e-3 if dtype == "bf16" else 1e-5), (dtype, float(rel.max()))
+        for b in range(len(n_vis)):
+            assert abs(got[cu_vis[b]:cu_vis[b + 1]].sum() - H * n_txt[b]) <= 1e-4 * H * n_txt[b]
+    # one token more than the limit is refused
+    cu_txt = np.array([0, 4097], dtype=np.int32)
+    cu_vis = np.array([0, 8], dtype=np.int32)
+    win = torch.zeros(1, dtype=torch.int32, device="cuda")
+    prob = B.Problem(batch=1, d=64, heads=2, head_dim=32, dtype="f32", h_cu_vis=cu_vis, cu_vis=torch.from_numpy(cu_vis).cuda(),
+                     h_cu_txt=cu_txt, cu_txt=torch.from_numpy(cu_txt).cuda(), n_windows=0, max_window_tokens=16,
+                     win_offsets=win, win_tokens=win)
+    with pytest.raises(B.LightKVError) as e:
+        B.lightkv_workspace_size(prob)
+    assert e.value.status == 5
+
+
 def test_strided_rows_and_error_paths_on_device():
     """Row strides larger than d (a view into a wider cache), and errors that need real device pointers."""
     from workloads import make_custom
