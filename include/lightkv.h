@@ -280,6 +280,54 @@ lightkv_status lightkv_aggregate_compact(const lightkv_problem *p, const int32_t
                                          void *X_out, void *K_out, void *V_out, int32_t *pos_out,
                                          float *x_sqnorm_out, int64_t out_rows, void *stream);
 
+/*
+ * One stage of the hierarchical schedule (Sec. 3.2.2) for lightkv_compress_schedule: the stage's descriptor and every
+ * buffer the stage writes.  All device buffers are the caller's; sizes as in the calls they are passed to.
+ */
+typedef struct lightkv_stage {
+  lightkv_problem problem;   /* the stage's descriptor; win_offsets / win_tokens point to the two arrays below          */
+  int32_t w;                 /* windows per axis of a tile in this stage (0: one window per sequence)                   */
+  int32_t reserved;          /* must be 0                                                                               */
+  int32_t *win_offsets;      /* [n_windows+1]  written by the schedule (lightkv_build_windows / _next)                  */
+  int32_t *win_tokens;       /* [sumN]                                                                                  */
+  float *xi;                 /* [sumN]                                                                                  */
+  float *best_fd;            /* [sumN]                                                                                  */
+  int32_t *best_dst, *dst, *new_index;   /* [sumN] each                                                                 */
+  int32_t *grp_offsets;      /* [sumN+1]                                                                                */
+  int32_t *grp_src;          /* [sum r_w]                                                                               */
+  int32_t *cu_vis_out;       /* [batch+1]; must equal the next stage's problem.cu_vis contents (the caller's schedule   */
+                             /* fixes every stage's token counts in advance)                                            */
+  void *X_out, *K_out, *V_out;   /* [out_rows, d] dense                                                                 */
+  int32_t *pos_out;          /* [out_rows]                                                                              */
+  float *x_sqnorm_out;       /* [out_rows] or NULL: squared norms of X_out, handed to the next stage's scores          */
+  int64_t out_rows;
+} lightkv_stage;
+
+/*
+ * The whole schedule in one call (Sec. 3.2.2: several compression stages at chosen layers, each with its own window
+ * size; here the stages run back to back on the same K/V/Q, every stage consuming what the one before wrote):
+ *   stage 0 reads X, K, V, pos; stage s > 0 reads stage s-1's X_out, K_out, V_out, pos_out (row stride d).
+ *   Q[sumT, heads, head_dim] (prompt queries, TEXT_QUERY) is the same for all stages; xi of stage s is computed
+ *   against the K rows that stage merges.  softmax_scale as in lightkv_score.
+ * Per stage the call enqueues what the single calls would -- lightkv_build_windows (stage 0; later stages' windows are
+ * built by lightkv_build_windows_next next to the previous stage's merge), lightkv_score (xi) next to
+ * lightkv_score_select (FD + selection), lightkv_aggregate_compact -- with the same results, bit for bit.  xi and the
+ * next stage's windows run on two internal helper streams that fork from and join `stream` (created per device on the
+ * first call outside stream capture, default priority, kept for the life of the process; if they cannot be made, or
+ * the first call on a device comes under capture, everything is enqueued on `stream` in order).  Steps of at most
+ * LIGHTKV_ONE_STREAM_MAX_TOKENS tokens whose windows hold at most 64 tokens use the one-stream form of
+ * lightkv_score_select instead.  One workspace serves all stages: ws_bytes must cover lightkv_workspace_size of every
+ * stage.  Host threads calling this on one device take turns enqueueing.  Only LIGHTKV_MATCH_BEST_PER_A (fixed token
+ * counts) is supported here.
+ * Errors: the first failing call's status; stages before it have been enqueued.
+ */
+lightkv_status lightkv_compress_schedule(const lightkv_stage *stages, int32_t n_stages,
+                                         int32_t tiles, int32_t grid_h, int32_t grid_w,
+                                         const void *X, int64_t ldx, const void *K, int64_t ldk,
+                                         const void *V, int64_t ldv, const int32_t *pos,
+                                         const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
+                                         float softmax_scale, void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

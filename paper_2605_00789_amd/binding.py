@@ -36,6 +36,16 @@ class _CProblem(C.Structure):
     ]
 
 
+class _CStage(C.Structure):
+    _fields_ = [
+        ("problem", _CProblem), ("w", C.c_int32), ("reserved", C.c_int32),
+        ("win_offsets", C.c_void_p), ("win_tokens", C.c_void_p), ("xi", C.c_void_p), ("best_fd", C.c_void_p),
+        ("best_dst", C.c_void_p), ("dst", C.c_void_p), ("new_index", C.c_void_p), ("grp_offsets", C.c_void_p),
+        ("grp_src", C.c_void_p), ("cu_vis_out", C.c_void_p), ("X_out", C.c_void_p), ("K_out", C.c_void_p),
+        ("V_out", C.c_void_p), ("pos_out", C.c_void_p), ("x_sqnorm_out", C.c_void_p), ("out_rows", C.c_int64),
+    ]
+
+
 def _load():
     path = lib_path()
     if not os.path.exists(path):
@@ -68,12 +78,15 @@ def _load():
     lib.lightkv_compact.argtypes = [P, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.lightkv_aggregate_compact.restype = C.c_int
     lib.lightkv_aggregate_compact.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.lightkv_compress_schedule.restype = C.c_int
+    lib.lightkv_compress_schedule.argtypes = [C.POINTER(_CStage), i32, i32, i32, i32, vp, i64, vp, i64, vp, i64, vp,
+                                              vp, i64, i64, f32, vp, sz, vp]
     return lib
 
 
 _lib = _load()
 
-EXPORTS = ("lightkv_status_string", "lightkv_version", "lightkv_workspace_size", "lightkv_build_windows",
+EXPORTS = ("lightkv_status_string", "lightkv_version", "lightkv_workspace_size", "lightkv_build_windows", "lightkv_compress_schedule",
            "lightkv_build_windows_next",
            "lightkv_score", "lightkv_score_select", "lightkv_select", "lightkv_aggregate", "lightkv_compact", "lightkv_aggregate_compact")
 
@@ -238,3 +251,32 @@ def lightkv_aggregate_compact(p: Problem, new_index, grp_offsets, grp_src, xi, X
                                           _dptr(x_sqnorm_out), _out_rows(X_out, K_out, V_out, pos_out),
                                           _stream(stream)),
            "lightkv_aggregate_compact")
+
+
+class StageArray:
+    """A C array of `lightkv_stage` built from Problems and the stages' tensors; keeps everything it points to alive."""
+
+    def __init__(self, stages):
+        """stages: sequence of dicts with keys problem (Problem), w and the tensors named in lightkv_stage."""
+        self.keep = list(stages)
+        self.n = len(self.keep)
+        self.c = (_CStage * self.n)()
+        for i, st in enumerate(self.keep):
+            c = self.c[i]
+            C.memmove(C.byref(c.problem), C.byref(st["problem"].c), C.sizeof(_CProblem))
+            c.w, c.reserved = int(st["w"]), 0
+            for name in ("win_offsets", "win_tokens", "xi", "best_fd", "best_dst", "dst", "new_index", "grp_offsets",
+                         "grp_src", "cu_vis_out", "X_out", "K_out", "V_out", "pos_out", "x_sqnorm_out"):
+                t = st.get(name)
+                setattr(c, name, None if t is None else t.data_ptr())
+            c.out_rows = _out_rows(st["X_out"], st["K_out"], st["V_out"], st["pos_out"])
+
+
+def lightkv_compress_schedule(stages: StageArray, tiles, grid_h, grid_w, X, K, V, pos, Q, ws, *, softmax_scale=0.0,
+                              stream=None):
+    """All stages of a schedule in one call; X, K, V [sumN, d], Q [sumT, heads*head_dim] token-major."""
+    hd = stages.keep[0]["problem"].c.head_dim
+    _check(_lib.lightkv_compress_schedule(stages.c, stages.n, tiles, grid_h, grid_w, _dptr(X), _ld(X), _dptr(K), _ld(K),
+                                          _dptr(V), _ld(V), _dptr(pos), _dptr(Q), int(Q.stride(0)), hd,
+                                          float(softmax_scale), _dptr(ws), ws.numel() * ws.element_size(),
+                                          _stream(stream)), "lightkv_compress_schedule")

@@ -1,0 +1,148 @@
+// The hierarchical schedule (paper Sec. 3.2.2) as one call: every stage's windows, scores, selection and merge are
+// enqueued through the library's own entry points, arranged over the caller's stream and two helper streams so that
+//   - xi (needs only Q and the stage's K rows) runs next to the feature-divergence chain and the selection,
+//   - the next stage's windows (need only pos and the selection) are built next to the merge of the rows.
+// Nothing here launches a kernel itself, allocates device memory or synchronises.
+#include "../../include/lightkv.h"
+
+#include <hip/hip_runtime.h>
+#include <mutex>
+
+namespace {
+
+// Helper streams and events of one device: host-side handles, made once outside stream capture, default priority,
+// never destroyed.  Distinct from the helper stream lightkv_score uses for its own fork.
+struct Helpers {
+  hipStream_t xi = nullptr, win = nullptr;
+  hipEvent_t fork_xi = nullptr, join_xi = nullptr, fork_win = nullptr, join_win = nullptr;
+  bool ready = false;
+  std::mutex in_use;
+};
+
+Helpers *helpers_for_current_device(hipStream_t main) {
+  static Helpers all[64];
+  static std::mutex mu;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  Helpers &h = all[dev];
+  if (h.ready) return &h;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(main, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
+    (void)hipGetLastError();
+    return nullptr;   // never create objects while the caller is capturing
+  }
+  bool ok = hipStreamCreateWithFlags(&h.xi, hipStreamNonBlocking) == hipSuccess &&
+            hipStreamCreateWithFlags(&h.win, hipStreamNonBlocking) == hipSuccess;
+  hipEvent_t *evs[4] = {&h.fork_xi, &h.join_xi, &h.fork_win, &h.join_win};
+  for (int i = 0; ok && i < 4; ++i) ok = hipEventCreateWithFlags(evs[i], hipEventDisableTiming) == hipSuccess;
+  if (!ok) { (void)hipGetLastError(); return nullptr; }
+  h.ready = true;
+  return &h;
+}
+
+// `to` waits for everything enqueued on `from` so far
+bool order_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
+  return hipEventRecord(ev, from) == hipSuccess && hipStreamWaitEvent(to, ev, 0) == hipSuccess;
+}
+
+}  // namespace
+
+extern "C" lightkv_status lightkv_compress_schedule(const lightkv_stage *stages, int32_t n_stages,
+                                                    int32_t tiles, int32_t grid_h, int32_t grid_w,
+                                                    const void *X, int64_t ldx, const void *K, int64_t ldk,
+                                                    const void *V, int64_t ldv, const int32_t *pos,
+                                                    const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
+                                                    float softmax_scale, void *ws, size_t ws_bytes, void *stream) {
+  if (!stages || !X || !K || !V || !pos || !Q) return LIGHTKV_ERR_NULL;
+  if (n_stages < 1) return LIGHTKV_ERR_SHAPE;
+  for (int s = 0; s < n_stages; ++s) {
+    const lightkv_stage &st = stages[s];
+    if (st.reserved != 0 || st.problem.match != LIGHTKV_MATCH_BEST_PER_A) return LIGHTKV_ERR_UNSUPPORTED;
+    if (!st.win_offsets || !st.win_tokens || !st.xi || !st.best_fd || !st.best_dst || !st.dst || !st.new_index ||
+        !st.grp_offsets || !st.grp_src || !st.cu_vis_out || !st.X_out || !st.K_out || !st.V_out || !st.pos_out)
+      return LIGHTKV_ERR_NULL;
+    if (st.problem.win_offsets != st.win_offsets || st.problem.win_tokens != st.win_tokens) return LIGHTKV_ERR_SHAPE;
+    if (!st.problem.h_cu_vis || !st.problem.cu_vis) return LIGHTKV_ERR_NULL;
+    if (st.problem.batch != stages[0].problem.batch || st.problem.d != stages[0].problem.d) return LIGHTKV_ERR_SHAPE;
+    size_t need = 0;
+    const lightkv_status ws_st = lightkv_workspace_size(&st.problem, &need);
+    if (ws_st != LIGHTKV_OK) return ws_st;
+    if (!ws || ws_bytes < need) return LIGHTKV_ERR_WORKSPACE;
+  }
+  hipStream_t main = static_cast<hipStream_t>(stream);
+  Helpers *h = helpers_for_current_device(main);
+  std::unique_lock<std::mutex> guard;
+  if (h) guard = std::unique_lock<std::mutex>(h->in_use);
+
+  const int d = stages[0].problem.d, head_dim = stages[0].problem.head_dim;
+  const void *Xi = X, *Ki = K, *Vi = V;
+  int64_t ldxi = ldx, ldki = ldk, ldvi = ldv;
+  const int32_t *posi = pos;
+  const float *sq = nullptr;          // squared norms of Xi, once a stage has produced them
+  bool windows_pending = false;       // this stage's windows are being built on the window stream
+  lightkv_status rc = LIGHTKV_OK;
+  bool xi_forked = false, win_forked = false;
+  for (int s = 0; s < n_stages && rc == LIGHTKV_OK; ++s) {
+    const lightkv_stage &st = stages[s];
+    const lightkv_problem *p = &st.problem;
+    const int sum_n = p->h_cu_vis[p->batch];
+    const bool one_stream = p->max_window_tokens > 0 && p->max_window_tokens <= 64 &&
+                            sum_n <= LIGHTKV_ONE_STREAM_MAX_TOKENS;
+    // ---- xi on its helper stream (or, if there is none, first on the caller's)
+    xi_forked = false;
+    if (!one_stream) {
+      hipStream_t xs = main;
+      if (h && order_after(h->xi, main, h->fork_xi)) { xs = h->xi; xi_forked = true; }
+      else if (h) (void)hipGetLastError();
+      rc = lightkv_score(p, nullptr, 0, nullptr, Q, q_tok_stride, q_head_stride, Ki, ldki, head_dim, LIGHTKV_XI_TEXT_QUERY,
+                         nullptr, softmax_scale, st.xi, nullptr, nullptr, ws, ws_bytes, xs);
+      if (xi_forked && hipEventRecord(h->join_xi, h->xi) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
+    }
+    // ---- windows: built by the previous stage's tail, or here
+    if (windows_pending) {
+      if (win_forked && hipStreamWaitEvent(main, h->join_win, 0) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
+    } else if (rc == LIGHTKV_OK) {
+      rc = lightkv_build_windows(p->batch, p->h_cu_vis, p->cu_vis, posi, tiles, grid_h, grid_w, st.w, st.win_offsets,
+                                 st.win_tokens, main);
+    }
+    windows_pending = false;
+    // ---- feature divergence + selection
+    if (rc == LIGHTKV_OK) {
+      if (one_stream)
+        rc = lightkv_score_select(p, Xi, ldxi, sq, Q, q_tok_stride, q_head_stride, Ki, ldki, head_dim,
+                                  LIGHTKV_XI_TEXT_QUERY, nullptr, softmax_scale, st.xi, st.best_fd, st.best_dst, st.dst,
+                                  st.new_index, st.grp_offsets, st.grp_src, st.cu_vis_out, ws, ws_bytes, main);
+      else
+        rc = lightkv_score_select(p, Xi, ldxi, sq, nullptr, 0, 0, nullptr, 0, 0, LIGHTKV_XI_GIVEN, nullptr, softmax_scale,
+                                  st.xi, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets, st.grp_src,
+                                  st.cu_vis_out, ws, ws_bytes, main);
+    }
+    // ---- the next stage's windows, next to the merge
+    win_forked = false;
+    if (rc == LIGHTKV_OK && s + 1 < n_stages) {
+      const lightkv_stage &nx = stages[s + 1];
+      hipStream_t wsx = main;
+      if (h && order_after(h->win, main, h->fork_win)) { wsx = h->win; win_forked = true; }
+      else if (h) (void)hipGetLastError();
+      rc = lightkv_build_windows_next(p->batch, p->h_cu_vis, p->cu_vis, posi, st.new_index, st.cu_vis_out, tiles, grid_h,
+                                      grid_w, nx.w, nx.win_offsets, nx.win_tokens, wsx);
+      if (win_forked && hipEventRecord(h->join_win, h->win) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
+      windows_pending = true;
+    }
+    // ---- join xi, merge and compact
+    if (xi_forked && hipStreamWaitEvent(main, h->join_xi, 0) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
+    xi_forked = false;
+    if (rc == LIGHTKV_OK)
+      rc = lightkv_aggregate_compact(p, st.new_index, st.grp_offsets, st.grp_src, st.xi, Xi, ldxi, Ki, ldki, Vi, ldvi,
+                                     posi, st.X_out, st.K_out, st.V_out, st.pos_out, st.x_sqnorm_out, st.out_rows, main);
+    Xi = st.X_out; Ki = st.K_out; Vi = st.V_out;
+    ldxi = ldki = ldvi = d;
+    posi = st.pos_out;
+    sq = st.x_sqnorm_out;
+  }
+  // whatever happened, nothing stays forked: the helper streams rejoin the caller's
+  if (xi_forked) (void)hipStreamWaitEvent(main, h->join_xi, 0);
+  if (win_forked) (void)hipStreamWaitEvent(main, h->join_win, 0);
+  return rc;
+}

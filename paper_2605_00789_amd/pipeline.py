@@ -105,6 +105,12 @@ class CompressionPipeline:
             self.stages.append(st)
             n_in = n_out
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        # the whole schedule as one library call (lightkv_compress_schedule): the stages' descriptors and buffers as a C array
+        self.c_stages = B.StageArray([dict(problem=st.problem, w=st.w, win_offsets=st.win_offsets, win_tokens=st.win_tokens,
+                                           xi=st.xi, best_fd=st.best_fd, best_dst=st.best_dst, dst=st.dst,
+                                           new_index=st.new_index, grp_offsets=st.grp_offsets, grp_src=st.grp_src,
+                                           cu_vis_out=st.cu_vis_out, X_out=st.X_out, K_out=st.K_out, V_out=st.V_out,
+                                           pos_out=st.pos_out, x_sqnorm_out=st.x_sq_out) for st in self.stages])
         # xi needs neither the windows nor the FD scores and is only consumed by the merge, so it is enqueued on a
         # second stream (default priority) that forks at the start of a stage and joins before aggregate/compact
         self.side = torch.cuda.Stream(device=dev)
@@ -180,7 +186,13 @@ class CompressionPipeline:
         return st
 
     def run(self, X, K, V, Q, pos, stream=None):
-        """All stages back to back; returns the last stage's buffers (its *_out tensors hold the result)."""
+        """All stages back to back; returns the last stage's buffers (its *_out tensors hold the result).  The fused
+        pipeline is one call of lightkv_compress_schedule; the unfused one (separate lightkv_aggregate and
+        lightkv_compact, kept for comparison) is driven stage by stage from here."""
+        if self.fused:
+            B.lightkv_compress_schedule(self.c_stages, self.tiles, self.grid_h, self.grid_w, X, K, V, pos, Q, self.ws,
+                                        stream=stream)
+            return self.stages[-1]
         st = None
         main = torch.cuda.current_stream() if stream is None else stream
         for s in range(len(self.stages)):

@@ -135,6 +135,34 @@ def test_entry_points_reject_bad_arguments_before_launch(B):
     # the k lowest edges cannot be chosen from per-node scores: only lightkv_score_select takes that reading
     pe = _problem(B, match=1)
     assert lib.lightkv_select(C.byref(pe), fake, fake, fake, fake, fake, fake, fake, fake, ws, None) == 5
+    # the schedule driver validates every stage before it enqueues anything
+    sched = lib.lightkv_compress_schedule
+    stage = B._CStage()
+    C.memmove(C.byref(stage.problem), C.byref(p), C.sizeof(B._CProblem))
+    for name in ("win_offsets", "win_tokens", "xi", "best_fd", "best_dst", "dst", "new_index", "grp_offsets", "grp_src",
+                 "cu_vis_out", "X_out", "K_out", "V_out", "pos_out"):
+        setattr(stage, name, 0x1000)
+    stage.out_rows = 5
+
+    def sc(stages=None, n=1, X=fake, Q=fake, wsb=1 << 30):
+        arr = (B._CStage * 1)(stage) if stages is None else stages
+        return sched(arr, n, 1, 2, 4, X, 64, fake, 64, fake, 64, fake, Q, 64, 32, 0.0, fake, wsb, None)
+
+    assert sched(None, 1, 1, 2, 4, fake, 64, fake, 64, fake, 64, fake, fake, 64, 32, 0.0, fake, 1 << 30, None) == 1
+    assert sc(n=0) == 2 and sc(X=None) == 1 and sc(Q=None) == 1
+    assert sc(wsb=16) == 6
+    stage.xi = None
+    assert sc() == 1
+    stage.xi = 0x1000
+    stage.win_tokens = 0x2000                      # not the array the descriptor points to
+    assert sc() == 2
+    stage.win_tokens = 0x1000
+    stage.problem.match = 1                        # data-dependent token counts: not in a fixed schedule
+    assert sc() == 5
+    stage.problem.match = 0
+    stage.reserved = 3
+    assert sc() == 5
+    stage.reserved = 0
     # aggregate / compact
     assert lib.lightkv_aggregate(C.byref(p), None, fake, fake, fake, 64, fake, 64, fake, 64, None) == 1
     assert lib.lightkv_aggregate(C.byref(p), fake, fake, fake, fake, 8, fake, 64, fake, 64, None) == 2
