@@ -41,10 +41,11 @@ def _parse():
                     "window as the default schedule of config 3 removes tokens)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-repeats", type=int, default=20, help="oracle steps timed for cpu_baseline (about 10 s)")
-    ap.add_argument("--cold", action="store_true", default=True,
+    ap.add_argument("--cold", action="store_true",
                     help="also time the dominant kernel with L2 and Infinity Cache flushed before every launch "
-                         "(extra object roofline_cold; the headline figures are unchanged); on by default")
-    ap.add_argument("--no-cold", dest="cold", action="store_false", help="skip the flushed-cache pass")
+                         "(extra object roofline_cold; the headline figures are unchanged).  Not part of the default "
+                         "run, so that a kernel trace of the default command holds the launches of the step only")
+    ap.add_argument("--no-cold", dest="cold", action="store_false", help="(the default)")
     return ap.parse_args()
 
 
