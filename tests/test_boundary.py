@@ -195,3 +195,11 @@ def test_schedule_helpers_agree_with_the_oracle():
         assert np.diff(wo).max() == max_window_cells(1, gh, gw, w)
     with pytest.raises(ValueError):
         removal_counts(1, 10, 11, 2)
+    # edges per window under the literal reading of Step 2: floor(rho v / 2), never more than the window has pairs
+    from paper_2605_00789_amd.schedule import edge_counts
+    offs = np.array([0, 36, 36, 37, 39, 183, 199], dtype=np.int32)          # windows of 36, 0, 1, 2, 144, 16 tokens
+    assert edge_counts(offs, 0.5).tolist() == [9, 0, 0, 0, 36, 4]
+    assert edge_counts(offs, 0.36).tolist() == [6, 0, 0, 0, 25, 2]
+    assert edge_counts(offs, 1.0).tolist() == [18, 0, 0, 1, 72, 8]
+    assert edge_counts(np.array([0, 2, 5], dtype=np.int32), 40.0).tolist() == [1, 2]   # capped at |A| |B|
+    assert edge_counts(offs, 0.0).tolist() == [0] * 6
