@@ -542,6 +542,55 @@ def test_graph_replay_equals_eager_in_the_benchmark_launch_configuration():
             assert junk.item() == junk.item()
 
 
+def test_first_call_of_a_process_under_stream_capture():
+    """A process whose very first library call is captured into a graph: the helper streams cannot be created then, so
+    the schedule is captured in stream order -- it must still replay to the results of an eager run.  Runs in a child
+    process (the helper streams of this one exist already)."""
+    import subprocess
+    import sys
+    code = r"""
+import sys
+sys.path.insert(0, '.')
+import numpy as np, torch
+from workloads import make_workload
+from paper_2605_00789_amd import CompressionPipeline, to_device as to_dev
+for cfg in (2, 3):
+    wl = make_workload(cfg)
+    pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                               tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                               windows_per_axis=wl.windows_per_axis, targets=wl.targets)
+    X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+    pos = torch.from_numpy(wl.pos).cuda()
+    stream = torch.cuda.Stream()
+    names = ("X_out", "K_out", "V_out", "pos_out", "xi", "dst", "new_index", "grp_offsets", "cu_vis_out")
+    with torch.cuda.stream(stream):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):      # no call of the library before this one (config 2)
+            pipe.run(X, K, V, Q, pos)
+        graph.replay()
+        stream.synchronize()
+        got = [[getattr(st, n).clone() for n in names] for st in pipe.stages]
+        for st in pipe.stages:
+            st.X_out.zero_(); st.K_out.zero_(); st.V_out.zero_(); st.xi.fill_(float('nan')); st.dst.fill_(-7)
+        pipe.run(X, K, V, Q, pos)                           # eager: the helper streams are made now
+        stream.synchronize()
+        for s, st in enumerate(pipe.stages):
+            for n, a in zip(names, got[s]):
+                assert torch.equal(a, getattr(st, n)), (cfg, s, n)
+        graph.replay()                                      # and the captured graph still replays after that
+        stream.synchronize()
+        for s, st in enumerate(pipe.stages):
+            for n, a in zip(names, got[s]):
+                assert torch.equal(a, getattr(st, n)), (cfg, s, n, 'replay')
+    print('capture-first ok', cfg, flush=True)
+"""
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-u", "-c", code], cwd=root, capture_output=True, text=True, timeout=280)
+    print(r.stdout[-2000:], r.stderr[-3000:], flush=True)
+    assert r.returncode == 0 and "capture-first ok 3" in r.stdout
+
+
 def test_nan_rows_keep_the_counts_exact():
     """Rows of NaNs never win a comparison; the step still removes exactly r tokens per window and writes inside the
     output buffers."""
