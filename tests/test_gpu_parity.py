@@ -591,6 +591,68 @@ for cfg in (2, 3):
     assert r.returncode == 0 and "capture-first ok 3" in r.stdout
 
 
+def test_host_threads_share_the_helper_streams():
+    """Two host threads run schedules on their own streams, buffers and workspaces at the same time.  The library's
+    helper streams and events are per device, so the threads take turns enqueueing; each must get the results of a
+    run on its own, bit for bit (lightkv_compress_schedule, and lightkv_score with both halves in one call)."""
+    import threading
+    from workloads import make_workload
+    from parity import to_dev
+    from paper_2605_00789_amd import CompressionPipeline
+    from paper_2605_00789_amd import binding as B
+    names = ("X_out", "K_out", "V_out", "pos_out", "xi", "dst", "new_index", "grp_offsets", "cu_vis_out", "best_fd")
+    jobs = []
+    for cfg in (2, "halving", 3):
+        wl = make_workload(cfg)
+        pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                                   tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                                   windows_per_axis=wl.windows_per_axis, targets=wl.targets)
+        X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+        pos = torch.from_numpy(wl.pos).cuda()
+        pipe.run(X, K, V, Q, pos)
+        torch.cuda.synchronize()
+        want = [[getattr(st, n).clone() for n in names] for st in pipe.stages]
+        st0 = pipe.stages[0]
+        xi0, fd0, bd0 = (torch.empty_like(t) for t in (st0.xi, st0.best_fd, st0.best_dst))
+        B.lightkv_score(st0.problem, X, Q, K, xi0, fd0, bd0, pipe.ws)     # both halves: the library forks inside
+        torch.cuda.synchronize()
+        jobs.append(dict(pipe=pipe, args=(X, K, V, Q, pos), want=want, score=(xi0.clone(), fd0.clone(), bd0.clone())))
+    errors = []
+
+    def work(job, rounds):
+        try:
+            stream = torch.cuda.Stream()
+            pipe = job["pipe"]
+            X, K, V, Q, pos = job["args"]
+            st0 = pipe.stages[0]
+            with torch.cuda.stream(stream):
+                for it in range(rounds):
+                    for st in pipe.stages:
+                        st.X_out.zero_(); st.xi.fill_(float("nan")); st.dst.fill_(-3)
+                    pipe.run(X, K, V, Q, pos)
+                    stream.synchronize()
+                    for s, st in enumerate(pipe.stages):
+                        for n, a in zip(names, job["want"][s]):
+                            if not torch.equal(a, getattr(st, n)):
+                                errors.append(("schedule", pipe.stages[0].n_in, it, s, n))
+                    xi, fd, bd = (torch.empty_like(t) for t in job["score"])
+                    B.lightkv_score(st0.problem, X, Q, K, xi, fd, bd, pipe.ws)
+                    stream.synchronize()
+                    for a, b in zip(job["score"], (xi, fd, bd)):
+                        if not torch.equal(a, b):
+                            errors.append(("score", pipe.stages[0].n_in, it))
+        except Exception as e:   # noqa: BLE001
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=(j, 6)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=200)
+    assert not any(t.is_alive() for t in threads), "a thread did not finish"
+    assert not errors, errors[:5]
+
+
 def test_nan_rows_keep_the_counts_exact():
     """Rows of NaNs never win a comparison; the step still removes exactly r tokens per window and writes inside the
     output buffers."""
