@@ -208,7 +208,7 @@ const char *lightkv_status_string(int status) {
   }
 }
 
-int lightkv_version(void) { return 100; }
+int lightkv_version(void) { return 200; }   // 0.2.0: match and reserved fields in lightkv_problem, lightkv_compress_schedule
 
 lightkv_status lightkv_workspace_size(const lightkv_problem *p, size_t *bytes) {
   if (!bytes) return LIGHTKV_ERR_NULL;
