@@ -98,6 +98,7 @@ typedef enum {
 #define LIGHTKV_MAX_SEQ_TOKENS    16384  /* vision tokens in one sequence           */
 #define LIGHTKV_MAX_TEXT_TOKENS   4096   /* prompt tokens in one sequence           */
 #define LIGHTKV_EDGE_MAX_WINDOW_TOKENS 256  /* tokens in one window with LIGHTKV_MATCH_EDGE_TOPK */
+#define LIGHTKV_SELECT_STATIC_MAX_TOKENS 65536  /* vision tokens of a batch in lightkv_select_static */
 /* Steps of at most this many vision tokens whose windows hold at most 64 tokens: lightkv_score_select runs the xi
    passes inside the launches of the FD chain, on the caller's stream alone (see there). */
 #define LIGHTKV_ONE_STREAM_MAX_TOKENS 1024
@@ -214,6 +215,19 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
 lightkv_status lightkv_select(const lightkv_problem *p, const float *best_fd, const int32_t *best_dst,
                               int32_t *dst, int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src,
                               int32_t *cu_vis_out, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * lightkv_select for callers that cannot allocate and carry no workspace: code under HIP graph capture, serving loops
+ * with a fixed memory plan, harnesses that forbid hipMalloc.  Same inputs, same outputs (bit for bit) as lightkv_select
+ * with LIGHTKV_MATCH_BEST_PER_A; the two per-token scratch arrays of the selection live in a static device array of
+ * the library (512 KB on every device the library has run on, held until the process ends) instead of `ws`.  The call
+ * allocates and frees nothing.  At most LIGHTKV_SELECT_STATIC_MAX_TOKENS vision tokens in the batch (more ->
+ * LIGHTKV_ERR_UNSUPPORTED, nothing launched).  All calls on one device share that array: calls that may overlap on a
+ * device (different streams, different host threads) race and must be ordered by the caller.
+ */
+lightkv_status lightkv_select_static(const lightkv_problem *p, const float *best_fd, const int32_t *best_dst,
+                                     int32_t *dst, int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src,
+                                     int32_t *cu_vis_out, void *stream);
 
 /*
  * lightkv_score followed by lightkv_select in one call: same arguments, same outputs (bit for bit).  When every

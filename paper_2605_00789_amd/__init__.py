@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     lightkv_score,
     lightkv_score_select,
     lightkv_select,
+    lightkv_select_static,
     lightkv_status_string,
     lightkv_version,
     lightkv_workspace_size,

@@ -72,6 +72,8 @@ def _load():
                                          vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lightkv_select.restype = C.c_int
     lib.lightkv_select.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lightkv_select_static.restype = C.c_int
+    lib.lightkv_select_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.lightkv_aggregate.restype = C.c_int
     lib.lightkv_aggregate.argtypes = [P, vp, vp, vp, vp, i64, vp, i64, vp, i64, vp]
     lib.lightkv_compact.restype = C.c_int
@@ -88,7 +90,7 @@ _lib = _load()
 
 EXPORTS = ("lightkv_status_string", "lightkv_version", "lightkv_workspace_size", "lightkv_build_windows", "lightkv_compress_schedule",
            "lightkv_build_windows_next",
-           "lightkv_score", "lightkv_score_select", "lightkv_select", "lightkv_aggregate", "lightkv_compact", "lightkv_aggregate_compact")
+           "lightkv_score", "lightkv_score_select", "lightkv_select", "lightkv_select_static", "lightkv_aggregate", "lightkv_compact", "lightkv_aggregate_compact")
 
 
 def _dptr(t: Optional[torch.Tensor]):
@@ -129,6 +131,7 @@ def _ld(t: Optional[torch.Tensor]) -> int:
 METRICS = {"cosine": 0, "euclidean": 1, "l2sq": 2}
 MATCH_BEST_PER_A, MATCH_EDGE_TOPK = 0, 1
 EDGE_MAX_WINDOW_TOKENS = 256   # LIGHTKV_EDGE_MAX_WINDOW_TOKENS
+SELECT_STATIC_MAX_TOKENS = 65536   # LIGHTKV_SELECT_STATIC_MAX_TOKENS
 ONE_STREAM_MAX_TOKENS = 1024   # LIGHTKV_ONE_STREAM_MAX_TOKENS
 
 
@@ -229,6 +232,12 @@ def lightkv_select(p: Problem, best_fd, best_dst, dst, new_index, grp_offsets, g
     _check(_lib.lightkv_select(p.ref(), _dptr(best_fd), _dptr(best_dst), _dptr(dst), _dptr(new_index),
                                _dptr(grp_offsets), _dptr(grp_src), _dptr(cu_vis_out), _dptr(ws),
                                ws.numel() * ws.element_size(), _stream(stream)), "lightkv_select")
+
+
+def lightkv_select_static(p: Problem, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, stream=None):
+    _check(_lib.lightkv_select_static(p.ref(), _dptr(best_fd), _dptr(best_dst), _dptr(dst), _dptr(new_index),
+                                      _dptr(grp_offsets), _dptr(grp_src), _dptr(cu_vis_out), _stream(stream)),
+           "lightkv_select_static")
 
 
 def lightkv_aggregate(p: Problem, grp_offsets, grp_src, xi, X, K, V, stream=None):

@@ -509,3 +509,61 @@ lightkv_status lightkv_aggregate_compact(const lightkv_problem *p, const int32_t
 }
 
 }  // extern "C"
+
+// ---- lightkv_select without a workspace argument ---------------------------------------------------------------
+// For callers that can neither allocate nor carry a workspace (code under graph capture, serving loops with a fixed
+// memory plan): the selection's two per-token scratch arrays live in a static device array of this library.  Each
+// device holds its own copy of the array at its own address; the address is looked up once per device and used from
+// then on -- the array's name itself is only a host-side stand-in.
+constexpr int STATIC_SELECT_MAX_TOKENS = LIGHTKV_SELECT_STATIC_MAX_TOKENS;
+static __device__ __align__(256) int32_t scratch[2 * STATIC_SELECT_MAX_TOKENS];   // [0, MAX): source counts, [MAX, 2 MAX): source ranks
+
+namespace {
+
+__global__ __launch_bounds__(256) void clear_scratch_kernel(int32_t *a, int32_t *b, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) { a[i] = 0; b[i] = 0; }
+}
+
+// device address of `scratch` on the current device (nullptr if it cannot be had)
+int32_t *static_scratch_for_current_device() {
+  static int32_t *ptr[64] = {};
+  static std::mutex mu;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return nullptr; }
+    ptr[dev] = static_cast<int32_t *>(p);
+  }
+  return ptr[dev];
+}
+}  // namespace
+
+extern "C" lightkv_status lightkv_select_static(const lightkv_problem *p, const float *best_fd, const int32_t *best_dst,
+                                                int32_t *dst, int32_t *new_index, int32_t *grp_offsets,
+                                                int32_t *grp_src, int32_t *cu_vis_out, void *stream) {
+  Checked c;
+  lightkv_status st = check_problem(p, true, false, c);
+  if (st != LIGHTKV_OK) return st;
+  if (!p->win_remove || !best_fd || !best_dst || !dst || !new_index || !grp_offsets || !grp_src || !cu_vis_out)
+    return LIGHTKV_ERR_NULL;
+  if (edge_topk(p)) return LIGHTKV_ERR_UNSUPPORTED;
+  if (c.sum_n > STATIC_SELECT_MAX_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;   // beyond the static array
+  int32_t *base = static_scratch_for_current_device();
+  if (!base) return LIGHTKV_ERR_LAUNCH;
+  int32_t *cnt = base, *rank = base + STATIC_SELECT_MAX_TOKENS;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (c.sum_n > 0) {
+    // the array keeps the previous call's contents: what this call reads starts from zero (a fill kernel rather than
+    // a memset node, so that the call can be captured into a graph)
+    hipLaunchKernelGGL(clear_scratch_kernel, dim3((unsigned)((c.sum_n + 255) / 256)), dim3(256), 0, s, cnt, rank, c.sum_n);
+    if (hipGetLastError() != hipSuccess) return LIGHTKV_ERR_LAUNCH;
+  }
+  if (launch_select(p->n_windows, c.max_window, p->batch, c.sum_n, p->cu_vis, p->win_offsets, p->win_tokens,
+                    p->win_remove, nullptr, 0, 0, const_cast<float *>(best_fd), const_cast<int32_t *>(best_dst), dst,
+                    new_index, grp_offsets, grp_src, cu_vis_out, cnt, rank, s) != hipSuccess)
+    return LIGHTKV_ERR_LAUNCH;
+  return LIGHTKV_OK;
+}
