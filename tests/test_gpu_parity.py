@@ -25,6 +25,85 @@ def test_measured_configs_match_oracle(cfg):
     reps = check_workload(wl)
     _report(wl, reps)
     assert [r.n_out for r in reps] == wl.targets
+    _report_free_running(wl)
+
+
+def _report_free_running(wl):
+    """Information only: every stage fed with the GPU's own previous outputs (no teacher forcing) against the oracle
+    run the same way.  Storage rounding of a stage's outputs can move a near-tied score across the selection
+    threshold of the next one, so the kept sets may drift apart; the share of common tokens per stage is printed."""
+    from oracle import lightkv_oracle as O
+    from parity import to_dev
+    from paper_2605_00789_amd import CompressionPipeline
+    pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                               tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                               windows_per_axis=wl.windows_per_axis, targets=wl.targets)
+    X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+    pipe.run(X, K, V, Q, torch.from_numpy(wl.pos).cuda())
+    torch.cuda.synchronize()
+    ref = O.compress_schedule(wl)
+    for s, (st, r) in enumerate(zip(pipe.stages, ref)):
+        n_out = wl.batch * wl.targets[s]
+        got_pos = st.pos_out.cpu().numpy()[:n_out]
+        cu = st.cu_vis_out.cpu().numpy()
+        same = 0
+        for b in range(wl.batch):
+            same += len(np.intersect1d(got_pos[cu[b]:cu[b + 1]], r.pos[r.cu_vis[b]:r.cu_vis[b + 1]]))
+        print("[free-running] %s stage %d: %d of %d kept tokens in common with the free-running oracle (%.2f %%)"
+              % (wl.name, s, same, n_out, 100.0 * same / max(n_out, 1)), flush=True)
+
+
+@pytest.mark.parametrize("cfg", [2, 4])
+def test_xi_modes_at_configuration_size(cfg):
+    """The xi variants at the measured configurations' sizes (N = 576 keys per sequence, prompts of 64 and 256 tokens,
+    32 and 40 heads of 128: the multi-block and 128-row prompt-chunk paths of the two-pass kernels), each through the
+    whole stage against the oracle: (a) text-query with the layer's own log-sum-exp handed in, (b) an explicit softmax
+    scale, (c) the printed index order of Eq. attention-factor -- vision queries against prompt keys with the
+    log-sum-exp of the whole causal attention row (prompt keys and the vision keys up to the query)."""
+    from workloads import make_workload, f32_to_bf16_bits
+    from parity import check_stage
+    from oracle import lightkv_oracle as O
+    from paper_2605_00789_amd import CompressionPipeline
+    import paper_2605_00789_amd as L
+    wl = make_workload(cfg)
+    H, dh, dtype = wl.heads, wl.head_dim, wl.dtype
+    Q64, K64 = O.widen(wl.Q, dtype), O.widen(wl.K, dtype)
+    n, sumT = wl.n_per_seq, int(wl.cu_txt[-1])
+    scale = 1.0 / math.sqrt(dh)
+    # (a) the layer's softmax also covered keys outside the vision span: they took between a third and two thirds of each row
+    rng = np.random.default_rng(100 + cfg)
+    lse = np.zeros((H, sumT))
+    for h in range(H):
+        l = (Q64[:, h * dh:(h + 1) * dh] @ K64[:, h * dh:(h + 1) * dh].T) * scale
+        m = l.max(axis=1)
+        lse[h] = m + np.log(np.exp(l - m[:, None]).sum(axis=1)) + np.log(rng.uniform(1.5, 3.0, sumT))
+    # (c) vision queries (seeded N(0,1), stored as bf16) against prompt keys (the workload's prompt rows)
+    Qv = f32_to_bf16_bits(rng.standard_normal((n, wl.d)).astype(np.float32))
+    Kt = wl.Q
+    Qv64, Kt64 = O.widen(Qv, dtype), O.widen(Kt, dtype)
+    lse_v = np.zeros((H, n))
+    for h in range(H):
+        qh = Qv64[:, h * dh:(h + 1) * dh]
+        lp = (qh @ Kt64[:, h * dh:(h + 1) * dh].T) * scale                       # prompt keys
+        lv = (qh @ K64[:, h * dh:(h + 1) * dh].T) * scale                        # vision keys, causal: i' <= i
+        lv = np.where(np.tril(np.ones((n, n), dtype=bool)), lv, -np.inf)
+        m = np.maximum(lp.max(axis=1), lv.max(axis=1))
+        lse_v[h] = m + np.log(np.exp(lp - m[:, None]).sum(axis=1) + np.exp(lv - m[:, None]).sum(axis=1))
+    # fused: the xi passes ride in the launches of the FD chain (small steps); unfused: lightkv_score's own xi kernels
+    for fused in (True, False):
+        pipe = CompressionPipeline(dtype=dtype, batch=wl.batch, d=wl.d, heads=H, head_dim=dh, tiles=wl.tiles,
+                                   grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                                   windows_per_axis=wl.windows_per_axis, targets=wl.targets, fused=fused)
+        tag = "%s fused=%s" % (wl.name, fused)
+        rep, out = check_stage(pipe, 0, wl.X, wl.K, wl.V, wl.Q, wl.pos, dtype, lse=lse)
+        print("[xi modes] %s given lse: xi rel %.2e, mass %.1f of %d" % (tag, rep.max_xi_rel, out["xi"].sum(), H * sumT), flush=True)
+        assert H * sumT / 3.0 - 1 <= out["xi"].sum() <= H * sumT / 1.5 + 1
+        # (b) explicit scale (a softer softmax than 1/sqrt(d_h))
+        rep, _ = check_stage(pipe, 0, wl.X, wl.K, wl.V, wl.Q, wl.pos, dtype, softmax_scale=0.03)
+        print("[xi modes] %s scale 0.03: xi rel %.2e" % (tag, rep.max_xi_rel), flush=True)
+        rep, out = check_stage(pipe, 0, wl.X, wl.K, wl.V, Qv, wl.pos, dtype, xi_mode=L.XI_VISION_QUERY, lse=lse_v, score_K=Kt)
+        print("[xi modes] %s vision-query: xi rel %.2e, xi in [%.3g, %.3g]" % (tag, rep.max_xi_rel, out["xi"].min(), out["xi"].max()), flush=True)
+        assert np.all(out["xi"] <= H * (1 + 1e-5))      # a row's prompt share of its softmax mass is at most one per head
 
 
 @pytest.mark.parametrize("case", [
@@ -285,13 +364,7 @@ def test_xi_of_batches_one_workgroup_per_sequence_and_head():
         got = xi.cpu().numpy().astype(np.float64)
         tol = 1e-3 if dtype == "bf16" else 1e-5
         rel = np.abs(got - want) / np.maximum(np.abs(want), 1e-30)
-        # contributions far below the sequence's largest weight carry the rounding of the exponent's argument
-        floor = np.zeros_like(want)
-        for b in range(len(n_vis)):
-            if n_vis[b]:
-                floor[cu_vis[b]:cu_vis[b + 1]] = want[cu_vis[b]:cu_vis[b + 1]].max() * 1e-6
-        bad = (rel > tol) & (np.abs(got - want) > tol * floor)
-        assert not bad.any(), (dtype, H, dh, int(bad.sum()), float(rel.max()))
+        assert rel.max() <= tol, (dtype, H, dh, int((rel > tol).sum()), float(rel.max()))
         # every prompt row spreads a mass of one over its sequence's keys, in every head
         for b in range(len(n_vis)):
             if n_vis[b] and n_txt[b]:

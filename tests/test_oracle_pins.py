@@ -208,17 +208,45 @@ def test_selection_is_the_brute_force_minimiser(seed):
     assert all(a in A.tolist() and b in B.tolist() for a, b in got)
 
 
-def test_edge_topk_is_the_brute_force_minimiser_over_edge_sets():
-    rng = np.random.default_rng(5)
-    X = rng.standard_normal((7, 4))
-    toks = np.arange(7, dtype=np.int32)
-    offs = np.array([0, 7], dtype=np.int32)
+@pytest.mark.parametrize("seed,n,k", [(5, 7, 3), (6, 6, 1), (7, 8, 5), (8, 5, 6), (9, 8, 16), (10, 7, 4), (11, 4, 2)])
+def test_edge_topk_is_the_brute_force_minimiser_over_edge_sets(seed, n, k):
+    """Step 2 read literally: among all k-subsets of the window's |A| x |B| edges the one with the lowest total FD
+    (random rows: no ties, so the minimiser is unique), for several window sizes and k up to every edge."""
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, 4))
+    toks = np.arange(n, dtype=np.int32)
+    offs = np.array([0, n], dtype=np.int32)
     A, B = toks[0::2], toks[1::2]
-    k = 3
     got = sorted(O.select_edge_topk(X, offs, toks, np.array([k])))
     all_edges = [(int(a), int(b)) for a in A for b in B]
+    assert k <= len(all_edges)
     best = min(itertools.combinations(all_edges, k), key=lambda es: sum(_explicit_fd(X, a, b) for a, b in es))
-    assert got == sorted(best)
+    assert got == sorted(best) and len(set(got)) == k
+
+
+def test_edge_topk_ties_go_to_the_lower_a_position_then_the_lower_b_position():
+    """Worked by hand.  Unit basis rows, so every cosine is exactly 1 or 0: window tokens 0..5, A = {0, 2, 4} holds
+    e1, e1, e2 and B = {1, 3, 5} holds e1, e1, e2.  FD is 0 on the five edges (0,1) (0,3) (2,1) (2,3) (4,5) and 1 on the
+    other four.  The tied edges rank by A position, then B position; the FD-1 edges follow in the same order."""
+    e1, e2 = [1.0, 0.0, 0.0], [0.0, 1.0, 0.0]
+    X = np.array([e1, e1, e1, e1, e2, e2])
+    toks = np.arange(6, dtype=np.int32)
+    offs = np.array([0, 6], dtype=np.int32)
+    order = [(0, 1), (0, 3), (2, 1), (2, 3), (4, 5),       # FD 0
+             (0, 5), (2, 5), (4, 1), (4, 3)]               # FD 1
+    for k in range(10):
+        assert O.select_edge_topk(X, offs, toks, np.array([k])) == order[:k], k
+    # with k = 3 token 0 owns two edges, token 2 one: both leave, token 4 stays; B token 1 receives 0 and 2, B token 3 receives 0
+    edges = O.select_edge_topk(X, offs, toks, np.array([3]))
+    assert O.removed_by_edges(6, edges).tolist() == [True, False, True, False, False, False]
+    go, gs = O.edges_csr(6, edges)
+    assert go.tolist() == [0, 0, 2, 2, 3, 3, 3] and gs.tolist() == [0, 2, 0]
+    # the order is a property of positions in the window, not of token numbers: list the same rows under other token ids
+    toks2 = np.array([10, 3, 11, 4, 12, 5], dtype=np.int32) - 3          # tokens 7,0,8,1,9,2: A = 7,8,9  B = 0,1,2
+    X2 = np.zeros((10, 3))
+    X2[toks2] = X
+    got = O.select_edge_topk(X2, offs, toks2, np.array([3]))
+    assert got == [(7, 0), (7, 1), (8, 0)]
 
 
 def test_selection_ties_and_hub():
