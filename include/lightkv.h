@@ -9,18 +9,29 @@
  * selected A nodes are averaged into their B node with the prompt-attention
  * weights xi (Step 3, Eq. "attention-factor" and Eq. "message-passing"), and the
  * merged A nodes are dropped from the hidden states and from the layer's K/V rows
- * (Steps 4-5; "key and value tokens are compressed simultaneously", appendix
- * "Method overview").
+ * alike (Steps 4-5; appendix figure "Method overview").
  *
  * Conventions
  *   - plain C, no C++ types cross the boundary; every function returns a
- *     lightkv_status (0 = OK) and never throws; on error no output is touched.
+ *     lightkv_status (0 = OK) and never throws.  Arguments are validated before
+ *     anything is enqueued: a single-step call that returns an error has touched no
+ *     output.  lightkv_compress_schedule validates every stage first, too; if a
+ *     later stage's launch then fails, the stages before it stay enqueued.
  *   - pointers named h_* are HOST memory, read during the call only.  Every other
- *     pointer is DEVICE memory owned by the caller; the library allocates nothing,
- *     frees nothing and keeps no state between calls.  Scratch comes from the
- *     caller's workspace `ws` (size from lightkv_workspace_size, 256-byte aligned).
+ *     pointer is DEVICE memory owned by the caller; the library allocates no device
+ *     memory and frees none.  Scratch comes from the caller's workspace `ws` (size
+ *     from lightkv_workspace_size, 256-byte aligned); lightkv_select_static uses a
+ *     static device array instead.
+ *   - state the library keeps between calls (per device, host-side handles only,
+ *     created on first use outside stream capture, default priority, never
+ *     destroyed): one helper stream with two events for lightkv_score, two helper
+ *     streams with four events for lightkv_compress_schedule, and the "large LDS"
+ *     attribute of three kernels.  Calls whose `stream` is being captured never
+ *     touch the helper streams: they enqueue everything on `stream` in order, so
+ *     a capture only ever contains the caller's stream.
  *   - all work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
- *     default stream); no call synchronises or reads device memory on the host.
+ *     default stream) or on helper streams that fork from and rejoin it before the
+ *     call returns; no call synchronises or reads device memory on the host.
  *   - tensors are token-major: row i holds the `d` contiguous elements of token i;
  *     `ld*` are row strides in elements.  Sequences of a batch are packed one after
  *     the other; cu_vis / cu_txt are their [batch+1] offsets.
@@ -31,6 +42,7 @@
  *   - threads: any host thread may call; calls are independent as long as their
  *     outputs and workspaces do not overlap (two calls that share a workspace must
  *     be ordered by the caller's streams, except where a function says otherwise).
+ *     Calls that use a helper stream take turns enqueueing (a mutex per device).
  *   - results are bit-reproducible: the same inputs give the same outputs on every
  *     call, whatever else runs on the device.
  */
@@ -171,6 +183,40 @@ lightkv_status lightkv_build_windows_next(int32_t batch, const int32_t *h_cu_vis
                                           int32_t tiles, int32_t grid_h, int32_t grid_w, int32_t w,
                                           int32_t *win_offsets, int32_t *win_tokens, void *stream);
 
+/* Host arithmetic of the partition: windows a sequence owns (tiles*w*w, or 1 for w = 0) and the largest number of
+   grid cells a window can cover (the bound callers pass as max_window_tokens).  Negative on invalid arguments. */
+int32_t lightkv_windows_per_sequence(int32_t tiles, int32_t w);
+int32_t lightkv_max_window_cells(int32_t tiles, int32_t grid_h, int32_t grid_w, int32_t w);
+
+/* How lightkv_window_counts turns the schedule's ratio or token budget into per-window counts. */
+typedef enum {
+  /* Sec. 3.2.2: a fraction rho of every window's tokens leaves, r_w = floor(rho * v_w), never more than the window's
+     set A (one step removes at most half: limitations paragraph). */
+  LIGHTKV_COUNT_RATIO = 0,
+  /* Step 2 as printed, for LIGHTKV_MATCH_EDGE_TOPK: k_w = floor(rho * v_w / 2) pairs, never more than |A_w| |B_w|. */
+  LIGHTKV_COUNT_EDGES = 1,
+  /* every sequence is given the length it must have after the step; the difference is spread over its windows as
+     evenly as their sizes allow: with cap_w = |A_w| (0 for windows of fewer than two tokens) and q the largest level
+     for which sum_w min(cap_w, q) stays within the budget, window w gives min(cap_w, q), and the first windows (in
+     window order) with cap_w > q give one more until the budget is met.  Equal windows: floor(R/W) each, one more
+     for the first R mod W. */
+  LIGHTKV_COUNT_TARGET = 2
+} lightkv_count_mode;
+
+/*
+ * Per-window counts r_w (or k_w) on the device, from the window sizes as they are (after earlier stages the windows
+ * of a sequence no longer hold equal numbers of tokens).  Every sequence owns n_windows / batch windows.
+ *   win_offsets[n_windows+1]  device, from lightkv_build_windows
+ *   rho                       RATIO / EDGES; a double, so that the floor is the one a host program computes
+ *   cu_vis, cu_vis_target     TARGET: device [batch+1] offsets of the sequences now and after the step
+ *   win_remove[n_windows]     device, out
+ *   status[batch]             device, out, may be NULL: 1 where a sequence's budget cannot be met (negative, or more
+ *                             than its sets A hold: then every window gives its whole set A), else 0
+ */
+lightkv_status lightkv_window_counts(int32_t batch, int32_t n_windows, const int32_t *win_offsets, int32_t mode,
+                                     double rho, const int32_t *cu_vis, const int32_t *cu_vis_target,
+                                     int32_t *win_remove, int32_t *status, void *stream);
+
 /*
  * Scores (Steps 1-3).
  *   X[sumN, d] (row stride ldx): vision hidden states.  For every A node the lowest-FD B node of its
@@ -188,6 +234,12 @@ lightkv_status lightkv_build_windows_next(int32_t batch, const int32_t *h_cu_vis
  *     GIVEN       : Q, K, lse ignored, xi is read-only input and left as is.
  *     element (token t, head h, e) of Q sits at Q[t*q_tok_stride + h*q_head_stride + e], K alike.
  *   softmax_scale: 0 selects 1/sqrt(head_dim).   lse: natural-log units, layout [heads, tokens], or NULL.
+ *   fd_dump (device, fp32, may be NULL; debugging): the FD of EVERY pair, window after window, each window a row-major
+ *     |A_w| x |B_w| block (rows: A nodes in window order, columns: B nodes); block w starts at sum_{u<w} |A_u| |B_u|.
+ *     fd_dump_floats is the capacity of the buffer in floats; pairs beyond it are not written.  The scoring kernels
+ *     never form these values (they keep row minima): the dump comes from a plain kernel of its own that accumulates
+ *     in fp64, so it agrees with best_fd to the accuracy of the scoring kernels' fp32 accumulation (about 1e-6), not
+ *     bit for bit.  At most 65535 windows; needs X.
  *   The two halves are independent and may be enqueued by two calls, e.g. on two streams with the same workspace:
  *   X == NULL computes xi only (windows, best_fd, best_dst are not touched), xi_mode GIVEN computes the FD half only.
  *   When both halves are requested in one call the library runs them concurrently (xi on an internal helper stream
@@ -198,7 +250,7 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
                              const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
                              const void *K, int64_t k_tok_stride, int64_t k_head_stride,
                              int32_t xi_mode, const float *lse, float softmax_scale,
-                             float *xi, float *best_fd, int32_t *best_dst,
+                             float *xi, float *best_fd, int32_t *best_dst, float *fd_dump, int64_t fd_dump_floats,
                              void *ws, size_t ws_bytes, void *stream);
 
 /*
@@ -275,24 +327,31 @@ lightkv_status lightkv_aggregate(const lightkv_problem *p, const int32_t *grp_of
  * NULL tensors are skipped (in and out together).
  * x_sqnorm_out[out_rows] (device, fp32, may be NULL; needs X): |x|^2 of every row written to X_out, as stored -- the
  * x_sqnorm argument of the next stage's lightkv_score; the rows pass through registers here anyway.
+ * Rows behind the vision span (Step 5 and the appendix "Method overview" figure: the sequence continues with the
+ * prompt's text behind the now shorter vision span): with tail_rows > 0 the inputs X, K, V, pos hold tail_rows more
+ * rows directly behind their sumN vision rows (for one sequence: its text tokens; for a batch: the callers' block of
+ * trailing rows), and these are copied to the outputs directly behind the vision rows that stay, input row sumN + j
+ * to output row cu_vis_out[batch] + j.  cu_vis_out (device, from lightkv_select) is then required and out_rows must
+ * cover the staying vision rows plus tail_rows.  tail_rows == 0: cu_vis_out may be NULL.
  */
 lightkv_status lightkv_compact(const lightkv_problem *p, const int32_t *new_index,
                                const void *X, int64_t ldx, const void *K, int64_t ldk,
                                const void *V, int64_t ldv, const int32_t *pos,
                                void *X_out, void *K_out, void *V_out, int32_t *pos_out, float *x_sqnorm_out,
-                               int64_t out_rows, void *stream);
+                               int64_t out_rows, int64_t tail_rows, const int32_t *cu_vis_out, void *stream);
 
 /*
  * lightkv_aggregate followed by lightkv_compact in one pass over the rows: reads every input row once,
- * writes every output row once, leaves the inputs untouched.  Same results as the two calls (x_sqnorm_out as in
- * lightkv_compact).
+ * writes every output row once, leaves the inputs untouched.  Same results as the two calls (x_sqnorm_out, tail_rows
+ * and cu_vis_out as in lightkv_compact).
  */
 lightkv_status lightkv_aggregate_compact(const lightkv_problem *p, const int32_t *new_index,
                                          const int32_t *grp_offsets, const int32_t *grp_src, const float *xi,
                                          const void *X, int64_t ldx, const void *K, int64_t ldk,
                                          const void *V, int64_t ldv, const int32_t *pos,
                                          void *X_out, void *K_out, void *V_out, int32_t *pos_out,
-                                         float *x_sqnorm_out, int64_t out_rows, void *stream);
+                                         float *x_sqnorm_out, int64_t out_rows, int64_t tail_rows,
+                                         const int32_t *cu_vis_out, void *stream);
 
 /*
  * One stage of the hierarchical schedule (Sec. 3.2.2) for lightkv_compress_schedule: the stage's descriptor and every
@@ -310,11 +369,18 @@ typedef struct lightkv_stage {
   int32_t *grp_offsets;      /* [sumN+1]                                                                                */
   int32_t *grp_src;          /* [sum r_w]                                                                               */
   int32_t *cu_vis_out;       /* [batch+1]; must equal the next stage's problem.cu_vis contents (the caller's schedule   */
-                             /* fixes every stage's token counts in advance)                                            */
+                             /* fixes every stage's token counts in advance; with cu_vis_target below the library       */
+                             /* derives the per-window counts that meet them and reports in `status` if it cannot)      */
   void *X_out, *K_out, *V_out;   /* [out_rows, d] dense                                                                 */
   int32_t *pos_out;          /* [out_rows]                                                                              */
   float *x_sqnorm_out;       /* [out_rows] or NULL: squared norms of X_out, handed to the next stage's scores          */
   int64_t out_rows;
+  /* Counts from the stage's token budget (NULL: problem.win_remove is the caller's and is used as it is).  When given,  */
+  /* the schedule calls lightkv_window_counts(LIGHTKV_COUNT_TARGET) on the windows it has just built and writes          */
+  /* win_remove, which must be the array problem.win_remove points to.                                                   */
+  const int32_t *cu_vis_target;   /* device [batch+1]: sequence offsets this stage must leave (= its cu_vis_out)       */
+  int32_t *win_remove;            /* device [n_windows], written by the schedule                                       */
+  int32_t *status;                /* device [batch] or NULL: 1 where the budget of a sequence could not be met         */
 } lightkv_stage;
 
 /*

@@ -153,6 +153,56 @@ def removal_counts_ratio(win_offsets: np.ndarray, rho: float) -> np.ndarray:
     return np.minimum(np.floor(rho * v + 1e-9).astype(np.int64), (v + 1) // 2).astype(np.int32)
 
 
+def removal_counts_target(win_offsets: np.ndarray, batch: int, n_remove: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:
+    """Removal counts that take n_remove[b] tokens out of sequence b, whatever sizes its windows have
+    (later stages: the windows no longer hold equal numbers of tokens).  Reading of Step 2 / Sec. 3.2.2 when a stage
+    is given a token budget instead of a ratio: the budget is spread as evenly as the windows allow.  A window of v
+    tokens can give up at most its set A, cap = ceil(v/2) (0 if v < 2: nothing to merge into).  With q the largest
+    level for which sum_w min(cap_w, q) does not exceed the budget, window w gives min(cap_w, q), and what is then
+    still missing comes one token each from the first windows (in window order) that can give more than q.  Where no
+    cap binds this is floor(R/W) per window and one more for the first R mod W windows.
+    Returns (win_remove[int32, n_windows], infeasible[bool, batch]): a budget above sum_w cap_w cannot be met; then
+    every window gives its cap and the sequence is flagged."""
+    v = np.diff(np.asarray(win_offsets, dtype=np.int64))
+    per_seq = len(v) // batch
+    out = np.zeros(len(v), dtype=np.int32)
+    bad = np.zeros(batch, dtype=bool)
+    for b in range(batch):
+        vs = v[b * per_seq:(b + 1) * per_seq]
+        cap = [int((x + 1) // 2) if x >= 2 else 0 for x in vs]
+        R = int(n_remove[b])
+        if R < 0:
+            raise ValueError("a stage cannot add tokens")
+        if R > sum(cap):
+            out[b * per_seq:(b + 1) * per_seq] = cap
+            bad[b] = True
+            continue
+        q = 0
+        while sum(min(c, q + 1) for c in cap) <= R:
+            q += 1
+            if q > max(cap + [0]):
+                break
+        r = [min(c, q) for c in cap]
+        missing = R - sum(r)
+        for k in range(per_seq):
+            if missing == 0:
+                break
+            if cap[k] > q:
+                r[k] += 1
+                missing -= 1
+        assert missing == 0
+        out[b * per_seq:(b + 1) * per_seq] = r
+    return out, bad
+
+
+def edge_counts_ratio(win_offsets: np.ndarray, rho: float) -> np.ndarray:
+    """Step 2 as printed: floor(rho * v / 2) lowest-FD pairs in a window of v tokens, never more than the window has
+    pairs (|A| * |B|)."""
+    v = np.diff(np.asarray(win_offsets, dtype=np.int64))
+    k = np.floor(rho * v / 2.0 + 1e-9).astype(np.int64)
+    return np.minimum(k, ((v + 1) // 2) * (v // 2)).astype(np.int32)
+
+
 def split_window(tokens: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """Step 1: local positions 0,2,4,.. -> A ; 1,3,5,.. -> B."""
     tokens = np.asarray(tokens)
@@ -446,7 +496,8 @@ def compress_stage_edges(X, K, V, Q, pos, cu_vis, cu_txt, heads, head_dim, win_o
 
 
 def stage_removals(batch: int, n_in: int, n_out: int, windows_per_seq: int) -> np.ndarray:
-    """Removal counts for all windows of a batch whose sequences all go n_in -> n_out."""
+    """Removal counts for all windows of a batch whose sequences all go n_in -> n_out, when no window's cap binds
+    (equal windows of the first stage): the even spread."""
     one = removal_counts_even(n_in - n_out, windows_per_seq)
     return np.tile(one, batch)
 
@@ -462,8 +513,10 @@ def compress_schedule(wl, stages: Optional[int] = None, metric: str = "cosine") 
     for s in range(wl.stages if stages is None else stages):
         w = wl.windows_per_axis[s]
         wo, wt = build_windows(pos, cu_vis, wl.tiles, wl.grid_h, wl.grid_w, w)
-        per_seq = (len(wo) - 1) // wl.batch
-        rem = stage_removals(wl.batch, n_in, wl.targets[s], per_seq)
+        n_seq = np.diff(np.asarray(cu_vis, dtype=np.int64))
+        rem, bad = removal_counts_target(wo, wl.batch, n_seq - wl.targets[s])
+        if bad.any():
+            raise ValueError("stage %d: the windows cannot give up %s tokens" % (s, (n_seq - wl.targets[s]).tolist()))
         res = compress_stage(widen(X, wl.dtype), widen(K, wl.dtype), widen(V, wl.dtype), Q, pos, cu_vis,
                              wl.cu_txt, wl.heads, wl.head_dim, wo, wt, rem, metric=metric)
         out.append(res)

@@ -20,9 +20,12 @@ from .binding import (  # noqa: F401
     lightkv_status_string,
     lightkv_version,
     lightkv_workspace_size,
+    lightkv_window_counts,
+    lightkv_windows_per_sequence,
+    lightkv_max_window_cells,
     XI_TEXT_QUERY,
     XI_VISION_QUERY,
     XI_GIVEN,
 )
-from .schedule import edge_counts, removal_counts, windows_per_sequence, max_window_cells  # noqa: F401
+from .schedule import windows_per_sequence, max_window_cells  # noqa: F401
 from .pipeline import CompressionPipeline, EdgeTopKSchedule, from_device, to_device  # noqa: F401

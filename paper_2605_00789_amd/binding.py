@@ -43,6 +43,7 @@ class _CStage(C.Structure):
         ("best_dst", C.c_void_p), ("dst", C.c_void_p), ("new_index", C.c_void_p), ("grp_offsets", C.c_void_p),
         ("grp_src", C.c_void_p), ("cu_vis_out", C.c_void_p), ("X_out", C.c_void_p), ("K_out", C.c_void_p),
         ("V_out", C.c_void_p), ("pos_out", C.c_void_p), ("x_sqnorm_out", C.c_void_p), ("out_rows", C.c_int64),
+        ("cu_vis_target", C.c_void_p), ("win_remove", C.c_void_p), ("status", C.c_void_p),
     ]
 
 
@@ -66,20 +67,26 @@ def _load():
     lib.lightkv_build_windows_next.restype = C.c_int
     lib.lightkv_build_windows_next.argtypes = [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     lib.lightkv_score.restype = C.c_int
-    lib.lightkv_score.argtypes = [P, vp, i64, vp, vp, i64, i64, vp, i64, i64, i32, vp, f32, vp, vp, vp, vp, sz, vp]
+    lib.lightkv_score.argtypes = [P, vp, i64, vp, vp, i64, i64, vp, i64, i64, i32, vp, f32, vp, vp, vp, vp, i64, vp, sz, vp]
     lib.lightkv_score_select.restype = C.c_int
     lib.lightkv_score_select.argtypes = [P, vp, i64, vp, vp, i64, i64, vp, i64, i64, i32, vp, f32, vp, vp, vp,
                                          vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lightkv_select.restype = C.c_int
     lib.lightkv_select.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lightkv_windows_per_sequence.restype = C.c_int32
+    lib.lightkv_windows_per_sequence.argtypes = [i32, i32]
+    lib.lightkv_max_window_cells.restype = C.c_int32
+    lib.lightkv_max_window_cells.argtypes = [i32, i32, i32, i32]
+    lib.lightkv_window_counts.restype = C.c_int
+    lib.lightkv_window_counts.argtypes = [i32, i32, vp, i32, C.c_double, vp, vp, vp, vp, vp]
     lib.lightkv_select_static.restype = C.c_int
     lib.lightkv_select_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.lightkv_aggregate.restype = C.c_int
     lib.lightkv_aggregate.argtypes = [P, vp, vp, vp, vp, i64, vp, i64, vp, i64, vp]
     lib.lightkv_compact.restype = C.c_int
-    lib.lightkv_compact.argtypes = [P, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.lightkv_compact.argtypes = [P, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp]
     lib.lightkv_aggregate_compact.restype = C.c_int
-    lib.lightkv_aggregate_compact.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.lightkv_aggregate_compact.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp]
     lib.lightkv_compress_schedule.restype = C.c_int
     lib.lightkv_compress_schedule.argtypes = [C.POINTER(_CStage), i32, i32, i32, i32, vp, i64, vp, i64, vp, i64, vp,
                                               vp, i64, i64, f32, vp, sz, vp]
@@ -89,7 +96,7 @@ def _load():
 _lib = _load()
 
 EXPORTS = ("lightkv_status_string", "lightkv_version", "lightkv_workspace_size", "lightkv_build_windows", "lightkv_compress_schedule",
-           "lightkv_build_windows_next",
+           "lightkv_build_windows_next", "lightkv_windows_per_sequence", "lightkv_max_window_cells", "lightkv_window_counts",
            "lightkv_score", "lightkv_score_select", "lightkv_select", "lightkv_select_static", "lightkv_aggregate", "lightkv_compact", "lightkv_aggregate_compact")
 
 
@@ -187,8 +194,32 @@ def lightkv_build_windows_next(batch, h_cu_vis, cu_vis, pos, new_index, cu_vis_o
                                            _dptr(win_tokens), _stream(stream)), "lightkv_build_windows_next")
 
 
+COUNT_RATIO, COUNT_EDGES, COUNT_TARGET = 0, 1, 2
+
+
+def lightkv_windows_per_sequence(tiles: int, w: int) -> int:
+    n = int(_lib.lightkv_windows_per_sequence(tiles, w))
+    if n < 0:
+        raise ValueError("invalid tiles / w")
+    return n
+
+
+def lightkv_max_window_cells(tiles: int, grid_h: int, grid_w: int, w: int) -> int:
+    n = int(_lib.lightkv_max_window_cells(tiles, grid_h, grid_w, w))
+    if n < 0:
+        raise ValueError("invalid grid")
+    return n
+
+
+def lightkv_window_counts(batch, n_windows, win_offsets, mode, win_remove, *, rho=0.0, cu_vis=None, cu_vis_target=None,
+                          status=None, stream=None):
+    _check(_lib.lightkv_window_counts(batch, n_windows, _dptr(win_offsets), int(mode), float(rho), _dptr(cu_vis),
+                                      _dptr(cu_vis_target), _dptr(win_remove), _dptr(status), _stream(stream)),
+           "lightkv_window_counts")
+
+
 def lightkv_score(p: Problem, X, Q, K, xi, best_fd, best_dst, ws, *, heads_major=False, xi_mode=XI_TEXT_QUERY,
-                  lse=None, softmax_scale=0.0, x_sqnorm=None, stream=None):
+                  lse=None, softmax_scale=0.0, x_sqnorm=None, fd_dump=None, stream=None):
     """X [sumN, d]; Q, K token-major [tokens, heads*head_dim] (or [heads, tokens, head_dim] with heads_major);
     x_sqnorm: optional fp32 [sumN], |x|^2 of the rows of X (from lightkv_compact / lightkv_aggregate_compact)."""
     hd = p.c.head_dim
@@ -204,6 +235,7 @@ def lightkv_score(p: Problem, X, Q, K, xi, best_fd, best_dst, ws, *, heads_major
     kts, khs = strides(K)
     _check(_lib.lightkv_score(p.ref(), _dptr(X), _ld(X), _dptr(x_sqnorm), _dptr(Q), qts, qhs, _dptr(K), kts, khs, xi_mode,
                               _dptr(lse), float(softmax_scale), _dptr(xi), _dptr(best_fd), _dptr(best_dst),
+                              _dptr(fd_dump), 0 if fd_dump is None else fd_dump.numel(),
                               _dptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "lightkv_score")
 
 
@@ -245,20 +277,22 @@ def lightkv_aggregate(p: Problem, grp_offsets, grp_src, xi, X, K, V, stream=None
                                   _dptr(K), _ld(K), _dptr(V), _ld(V), _stream(stream)), "lightkv_aggregate")
 
 
-def lightkv_compact(p: Problem, new_index, X, K, V, pos, X_out, K_out, V_out, pos_out, x_sqnorm_out=None, stream=None):
+def lightkv_compact(p: Problem, new_index, X, K, V, pos, X_out, K_out, V_out, pos_out, x_sqnorm_out=None, tail_rows=0,
+                    cu_vis_out=None, stream=None):
     _check(_lib.lightkv_compact(p.ref(), _dptr(new_index), _dptr(X), _ld(X), _dptr(K), _ld(K), _dptr(V), _ld(V),
                                 _dptr(pos), _dptr(X_out), _dptr(K_out), _dptr(V_out), _dptr(pos_out),
-                                _dptr(x_sqnorm_out), _out_rows(X_out, K_out, V_out, pos_out), _stream(stream)),
+                                _dptr(x_sqnorm_out), _out_rows(X_out, K_out, V_out, pos_out), int(tail_rows),
+                                _dptr(cu_vis_out), _stream(stream)),
            "lightkv_compact")
 
 
 def lightkv_aggregate_compact(p: Problem, new_index, grp_offsets, grp_src, xi, X, K, V, pos, X_out, K_out, V_out,
-                              pos_out, x_sqnorm_out=None, stream=None):
+                              pos_out, x_sqnorm_out=None, tail_rows=0, cu_vis_out=None, stream=None):
     _check(_lib.lightkv_aggregate_compact(p.ref(), _dptr(new_index), _dptr(grp_offsets), _dptr(grp_src), _dptr(xi),
                                           _dptr(X), _ld(X), _dptr(K), _ld(K), _dptr(V), _ld(V), _dptr(pos),
                                           _dptr(X_out), _dptr(K_out), _dptr(V_out), _dptr(pos_out),
                                           _dptr(x_sqnorm_out), _out_rows(X_out, K_out, V_out, pos_out),
-                                          _stream(stream)),
+                                          int(tail_rows), _dptr(cu_vis_out), _stream(stream)),
            "lightkv_aggregate_compact")
 
 
@@ -275,7 +309,8 @@ class StageArray:
             C.memmove(C.byref(c.problem), C.byref(st["problem"].c), C.sizeof(_CProblem))
             c.w, c.reserved = int(st["w"]), 0
             for name in ("win_offsets", "win_tokens", "xi", "best_fd", "best_dst", "dst", "new_index", "grp_offsets",
-                         "grp_src", "cu_vis_out", "X_out", "K_out", "V_out", "pos_out", "x_sqnorm_out"):
+                         "grp_src", "cu_vis_out", "X_out", "K_out", "V_out", "pos_out", "x_sqnorm_out", "cu_vis_target",
+                         "win_remove", "status"):
                 t = st.get(name)
                 setattr(c, name, None if t is None else t.data_ptr())
             c.out_rows = _out_rows(st["X_out"], st["K_out"], st["V_out"], st["pos_out"])

@@ -2,6 +2,7 @@
 // Nothing here allocates, synchronises or reads device memory.
 #include "../../include/lightkv.h"
 #include "lk_launch.h"
+#include "lk_helpers.h"
 
 #include <math.h>
 #include <mutex>
@@ -88,38 +89,9 @@ lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool n
 
 // The two halves of lightkv_score (xi from Q/K, FD from X) share no data, so they are enqueued as a fork/join:
 // xi on a helper stream, FD on the caller's stream, joined by events before the call returns.  Under stream capture
-// the fork/join becomes two parallel branches of the graph.  The helper stream and its two events are the only
-// objects the library ever creates: host-side handles, one set per device, made on the first (non-capturing) call
-// at default priority and kept for the life of the process.  If they cannot be made the work runs serially.
-struct Fork {
-  hipStream_t side = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr;
-  bool ready = false;
-  std::mutex in_use;   // one caller at a time enqueues its fork ... join sequence on the shared helper stream
-};
-
-Fork *fork_for_current_device(hipStream_t main) {
-  static Fork forks[64];
-  static std::mutex mu;
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-  std::lock_guard<std::mutex> lock(mu);
-  Fork &f = forks[dev];
-  if (f.ready) return &f;
-  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-  if (hipStreamIsCapturing(main, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
-    (void)hipGetLastError();
-    return nullptr;   // never create objects while the caller is capturing
-  }
-  if (hipStreamCreateWithFlags(&f.side, hipStreamNonBlocking) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
-  if (hipEventCreateWithFlags(&f.fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&f.join, hipEventDisableTiming) != hipSuccess) {
-    (void)hipGetLastError();
-    return nullptr;
-  }
-  f.ready = true;
-  return &f;
-}
+// the fork/join becomes two parallel branches of the graph.  Helper sets come from a per-device pool (lk_helpers.h);
+// without one the work runs serially on the caller's stream.
+using Fork = HelperSet<1, 2>;   // stream[0]: xi; event[0]: fork, event[1]: join
 
 struct WsLayout {
   size_t fd_partial = 0, fd_norm = 0, fd_keys = 0, xi_stats = 0, xi_part = 0, sel_cnt = 0,
@@ -208,7 +180,7 @@ const char *lightkv_status_string(int status) {
   }
 }
 
-int lightkv_version(void) { return 200; }   // 0.2.0: match and reserved fields in lightkv_problem, lightkv_compress_schedule
+int lightkv_version(void) { return 300; }   // 0.3.0: lightkv_stage gained cu_vis_target / win_remove / status; new entry points
 
 lightkv_status lightkv_workspace_size(const lightkv_problem *p, size_t *bytes) {
   if (!bytes) return LIGHTKV_ERR_NULL;
@@ -260,6 +232,43 @@ lightkv_status lightkv_build_windows_next(int32_t batch, const int32_t *h_cu_vis
                             win_tokens, stream);
 }
 
+int32_t lightkv_windows_per_sequence(int32_t tiles, int32_t w) {
+  if (tiles < 1 || w < 0 || (int64_t)tiles * w * w > (1 << 17)) return -1;
+  return w == 0 ? 1 : tiles * w * w;
+}
+
+int32_t lightkv_max_window_cells(int32_t tiles, int32_t grid_h, int32_t grid_w, int32_t w) {
+  if (tiles < 1 || grid_h < 1 || grid_w < 1 || w < 0 || (int64_t)tiles * grid_h * grid_w > (1ll << 30)) return -1;
+  if (w == 0) return tiles * grid_h * grid_w;
+  // window k of an axis of g cells holds the cells c with floor(c * w / g) == k
+  auto widest = [](int g, int w_) {
+    int best = 0, run = 0, prev = -1;
+    for (int c = 0; c < g; ++c) {
+      const int k = (int)((int64_t)c * w_ / g);
+      run = k == prev ? run + 1 : 1;
+      prev = k;
+      best = run > best ? run : best;
+    }
+    return best;
+  };
+  return widest(grid_h, w) * widest(grid_w, w);
+}
+
+lightkv_status lightkv_window_counts(int32_t batch, int32_t n_windows, const int32_t *win_offsets, int32_t mode,
+                                     double rho, const int32_t *cu_vis, const int32_t *cu_vis_target,
+                                     int32_t *win_remove, int32_t *status, void *stream) {
+  if (!win_offsets || !win_remove) return LIGHTKV_ERR_NULL;
+  if (batch < 1 || n_windows < 0 || n_windows % batch != 0) return LIGHTKV_ERR_SHAPE;
+  if (mode < LIGHTKV_COUNT_RATIO || mode > LIGHTKV_COUNT_TARGET) return LIGHTKV_ERR_UNSUPPORTED;
+  if (mode == LIGHTKV_COUNT_TARGET && (!cu_vis || !cu_vis_target)) return LIGHTKV_ERR_NULL;
+  if (mode != LIGHTKV_COUNT_TARGET && !(rho >= 0.0 && rho <= 1e6)) return LIGHTKV_ERR_SHAPE;   // also refuses NaN
+  if (n_windows == 0) return LIGHTKV_OK;
+  if (launch_window_counts(batch, n_windows / batch, win_offsets, mode, rho, cu_vis, cu_vis_target, win_remove, status,
+                           static_cast<hipStream_t>(stream)) != hipSuccess)
+    return LIGHTKV_ERR_LAUNCH;
+  return LIGHTKV_OK;
+}
+
 }  // extern "C"
 
 namespace {
@@ -275,7 +284,7 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
                           const void *K, int64_t k_tok_stride, int64_t k_head_stride,
                           int32_t xi_mode, const float *lse, float softmax_scale,
                           float *xi, float *best_fd, int32_t *best_dst, const SelectOut *sel, bool keys_only,
-                          void *ws, size_t ws_bytes, void *stream) {
+                          float *fd_dump, int64_t fd_dump_floats, void *ws, size_t ws_bytes, void *stream) {
   if (xi_mode < LIGHTKV_XI_TEXT_QUERY || xi_mode > LIGHTKV_XI_GIVEN) return LIGHTKV_ERR_UNSUPPORTED;
   const bool need_xi = xi_mode != LIGHTKV_XI_GIVEN;
   const bool need_fd = X != nullptr;   // X == NULL: only xi is wanted (the two halves may be enqueued separately)
@@ -286,6 +295,11 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
   if (!xi || (need_fd && (!best_fd || !best_dst))) return LIGHTKV_ERR_NULL;
   if (need_fd && !row_tensor_ok(X, ldx, p->d, c.elem_bytes, st)) return st;
   if (x_sqnorm && (reinterpret_cast<uintptr_t>(x_sqnorm) & 3)) return LIGHTKV_ERR_UNSUPPORTED;
+  if (fd_dump) {
+    if (!need_fd) return LIGHTKV_ERR_NULL;
+    if (fd_dump_floats < 0) return LIGHTKV_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(fd_dump) & 3) || p->n_windows > 65535) return LIGHTKV_ERR_UNSUPPORTED;
+  }
   if (need_xi) {
     if (!Q || !K) return LIGHTKV_ERR_NULL;
     if (xi_mode == LIGHTKV_XI_VISION_QUERY && !lse) return LIGHTKV_ERR_NULL;
@@ -338,11 +352,10 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
   Fork *fk = nullptr;
   std::unique_lock<std::mutex> fork_guard;   // released when this call returns, i.e. after the join has been enqueued
   if (need_xi) {
-    if (need_fd) fk = fork_for_current_device(s);
-    if (fk) fork_guard = std::unique_lock<std::mutex>(fk->in_use);
+    if (need_fd) fk = acquire_helpers<1, 2>(s, fork_guard);
     hipStream_t xs = s;
     if (fk) {
-      if (hipEventRecord(fk->fork, s) == hipSuccess && hipStreamWaitEvent(fk->side, fk->fork, 0) == hipSuccess) xs = fk->side;
+      if (hipEventRecord(fk->event[0], s) == hipSuccess && hipStreamWaitEvent(fk->stream[0], fk->event[0], 0) == hipSuccess) xs = fk->stream[0];
       else { (void)hipGetLastError(); fk = nullptr; }
     }
     const float scale = softmax_scale != 0.f ? softmax_scale : 1.0f / sqrtf((float)p->head_dim);
@@ -350,9 +363,9 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
                                    p->cu_txt, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, lse, scale,
                                    reinterpret_cast<float *>(wsb + l.xi_stats),
                                    reinterpret_cast<float *>(wsb + l.xi_part), xi, xs);
-    if (fk && hipEventRecord(fk->join, fk->side) != hipSuccess) return LIGHTKV_ERR_LAUNCH;
+    if (fk && hipEventRecord(fk->event[1], fk->stream[0]) != hipSuccess) return LIGHTKV_ERR_LAUNCH;
     if (e != hipSuccess) {   // the helper stream must rejoin the caller's stream whatever happened on it
-      if (fk) (void)hipStreamWaitEvent(s, fk->join, 0);
+      if (fk) (void)hipStreamWaitEvent(s, fk->event[1], 0);
       return LIGHTKV_ERR_LAUNCH;
     }
   }
@@ -389,7 +402,11 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
                        reinterpret_cast<float *>(wsb + l.fd_partial), best_fd, best_dst, s) != hipSuccess) {
     fd_status = LIGHTKV_ERR_LAUNCH;
   }
-  if (fk && hipStreamWaitEvent(s, fk->join, 0) != hipSuccess) return LIGHTKV_ERR_LAUNCH;   // join
+  if (fd_dump && fd_status == LIGHTKV_OK &&
+      launch_fd_dump(p->dtype, X, ldx, p->d, p->n_windows, c.max_window, c.sum_n, p->metric, p->win_offsets,
+                     p->win_tokens, fd_dump, (long long)fd_dump_floats, s) != hipSuccess)
+    fd_status = LIGHTKV_ERR_LAUNCH;
+  if (fk && hipStreamWaitEvent(s, fk->event[1], 0) != hipSuccess) return LIGHTKV_ERR_LAUNCH;   // join
   return fd_status;
 }
 }  // namespace
@@ -400,10 +417,10 @@ lightkv_status lightkv_score(const lightkv_problem *p, const void *X, int64_t ld
                              const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
                              const void *K, int64_t k_tok_stride, int64_t k_head_stride,
                              int32_t xi_mode, const float *lse, float softmax_scale,
-                             float *xi, float *best_fd, int32_t *best_dst,
+                             float *xi, float *best_fd, int32_t *best_dst, float *fd_dump, int64_t fd_dump_floats,
                              void *ws, size_t ws_bytes, void *stream) {
   return score_impl(p, X, ldx, x_sqnorm, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
-                    softmax_scale, xi, best_fd, best_dst, nullptr, false, ws, ws_bytes, stream);
+                    softmax_scale, xi, best_fd, best_dst, nullptr, false, fd_dump, fd_dump_floats, ws, ws_bytes, stream);
 }
 
 lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int64_t ldx, const float *x_sqnorm,
@@ -422,12 +439,12 @@ lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int
   if ((small.n_tiles > 0 && !use_big_fd(p, c)) || p->n_windows == 0 || edge_topk(p)) {
     const SelectOut sel{dst, new_index, grp_offsets, grp_src, cu_vis_out};
     return score_impl(p, X, ldx, x_sqnorm, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
-                      softmax_scale, xi, best_fd, best_dst, &sel, false, ws, ws_bytes, stream);
+                      softmax_scale, xi, best_fd, best_dst, &sel, false, nullptr, 0, ws, ws_bytes, stream);
   }
   // the tiled MFMA path leaves packed keys: the selection reads them directly and writes best_fd / best_dst itself
   const bool from_keys = use_big_fd(p, c);
   st = score_impl(p, X, ldx, x_sqnorm, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
-                  softmax_scale, xi, best_fd, best_dst, nullptr, from_keys, ws, ws_bytes, stream);
+                  softmax_scale, xi, best_fd, best_dst, nullptr, from_keys, nullptr, 0, ws, ws_bytes, stream);
   if (st != LIGHTKV_OK) return st;
   return select_impl(p, from_keys, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, ws, ws_bytes,
                      stream);
@@ -445,14 +462,17 @@ static lightkv_status rows_call(int mode, const lightkv_problem *p, const int32_
                                 const int32_t *grp_offsets, const int32_t *grp_src, const float *xi,
                                 const void *X, int64_t ldx, const void *K, int64_t ldk, const void *V, int64_t ldv,
                                 const int32_t *pos, void *Xo, void *Ko, void *Vo, int32_t *pos_out,
-                                float *x_sqnorm_out, int64_t out_rows, void *stream) {
+                                float *x_sqnorm_out, int64_t out_rows, int64_t tail_rows, const int32_t *cu_vis_out,
+                                void *stream) {
   Checked c;
   lightkv_status st = check_problem(p, false, false, c);
   if (st != LIGHTKV_OK) return st;
+  if (tail_rows < 0 || (uint64_t)tail_rows > (1ull << 31)) return LIGHTKV_ERR_SHAPE;
+  if (tail_rows > 0 && !cu_vis_out) return LIGHTKV_ERR_NULL;
   if (mode != 1 && (!grp_offsets || !grp_src || !xi)) return LIGHTKV_ERR_NULL;
   if (mode != 0 && !new_index) return LIGHTKV_ERR_NULL;
   if (mode != 0 && out_rows < 0) return LIGHTKV_ERR_SHAPE;
-  if (mode != 0 && out_rows > c.sum_n) out_rows = c.sum_n;
+  if (mode != 0 && out_rows > c.sum_n + tail_rows) out_rows = c.sum_n + tail_rows;
   const void *in[3] = {X, K, V};
   void *out[3] = {Xo, Ko, Vo};
   const int64_t ld[3] = {ldx, ldk, ldv};
@@ -464,7 +484,7 @@ static lightkv_status rows_call(int mode, const lightkv_problem *p, const int32_
       if (!aligned16(out[i])) return LIGHTKV_ERR_UNSUPPORTED;
       const char *a = static_cast<const char *>(in[i]);
       const char *b = static_cast<const char *>(out[i]);
-      const size_t in_bytes = (size_t)c.sum_n * (size_t)ld[i] * c.elem_bytes;
+      const size_t in_bytes = ((size_t)c.sum_n + (size_t)tail_rows) * (size_t)ld[i] * c.elem_bytes;
       const size_t out_bytes = (size_t)out_rows * (size_t)p->d * c.elem_bytes;
       if (a == b || (b > a && b < a + in_bytes) || (a > b && a < b + out_bytes)) return LIGHTKV_ERR_SHAPE;
     }
@@ -479,6 +499,9 @@ static lightkv_status rows_call(int mode, const lightkv_problem *p, const int32_
   if (launch_rows(mode, p->dtype, p->d, c.sum_n, t, new_index, grp_offsets, grp_src, xi, pos, pos_out, x_sqnorm_out,
                   out_rows, static_cast<hipStream_t>(stream)) != hipSuccess)
     return LIGHTKV_ERR_LAUNCH;
+  if (tail_rows > 0 && launch_tail_rows(p->dtype, p->d, c.sum_n, p->batch, t, pos, pos_out, cu_vis_out, tail_rows, out_rows,
+                                        static_cast<hipStream_t>(stream)) != hipSuccess)
+    return LIGHTKV_ERR_LAUNCH;
   return LIGHTKV_OK;
 }
 
@@ -486,16 +509,16 @@ lightkv_status lightkv_aggregate(const lightkv_problem *p, const int32_t *grp_of
                                  const float *xi, void *X, int64_t ldx, void *K, int64_t ldk,
                                  void *V, int64_t ldv, void *stream) {
   return rows_call(0, p, nullptr, grp_offsets, grp_src, xi, X, ldx, K, ldk, V, ldv, nullptr, nullptr, nullptr,
-                   nullptr, nullptr, nullptr, 0, stream);
+                   nullptr, nullptr, nullptr, 0, 0, nullptr, stream);
 }
 
 lightkv_status lightkv_compact(const lightkv_problem *p, const int32_t *new_index,
                                const void *X, int64_t ldx, const void *K, int64_t ldk,
                                const void *V, int64_t ldv, const int32_t *pos,
                                void *X_out, void *K_out, void *V_out, int32_t *pos_out, float *x_sqnorm_out,
-                               int64_t out_rows, void *stream) {
+                               int64_t out_rows, int64_t tail_rows, const int32_t *cu_vis_out, void *stream) {
   return rows_call(1, p, new_index, nullptr, nullptr, nullptr, X, ldx, K, ldk, V, ldv, pos, X_out, K_out, V_out,
-                   pos_out, x_sqnorm_out, out_rows, stream);
+                   pos_out, x_sqnorm_out, out_rows, tail_rows, cu_vis_out, stream);
 }
 
 lightkv_status lightkv_aggregate_compact(const lightkv_problem *p, const int32_t *new_index,
@@ -503,9 +526,10 @@ lightkv_status lightkv_aggregate_compact(const lightkv_problem *p, const int32_t
                                          const void *X, int64_t ldx, const void *K, int64_t ldk,
                                          const void *V, int64_t ldv, const int32_t *pos,
                                          void *X_out, void *K_out, void *V_out, int32_t *pos_out,
-                                         float *x_sqnorm_out, int64_t out_rows, void *stream) {
+                                         float *x_sqnorm_out, int64_t out_rows, int64_t tail_rows,
+                                         const int32_t *cu_vis_out, void *stream) {
   return rows_call(2, p, new_index, grp_offsets, grp_src, xi, X, ldx, K, ldk, V, ldv, pos, X_out, K_out, V_out,
-                   pos_out, x_sqnorm_out, out_rows, stream);
+                   pos_out, x_sqnorm_out, out_rows, tail_rows, cu_vis_out, stream);
 }
 
 }  // extern "C"

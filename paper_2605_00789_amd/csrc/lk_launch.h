@@ -32,6 +32,11 @@ hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, const
                                 int grid_h, int grid_w, int w, int32_t *win_offsets, int32_t *win_tokens,
                                 hipStream_t stream);
 
+// per-window counts from a ratio (mode 0: tokens, 1: edges) or from per-sequence target lengths (mode 2)
+hipError_t launch_window_counts(int batch, int win_per_seq, const int32_t *win_offsets, int mode, double rho,
+                                const int32_t *cu_vis, const int32_t *cu_target, int32_t *win_remove, int32_t *status,
+                                hipStream_t stream);
+
 hipError_t launch_fd(const FdPlan &plan, int dtype, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
                      const int32_t *win_offsets, const int32_t *win_tokens, float *partial, float *best_fd,
                      int32_t *best_dst, hipStream_t stream);
@@ -56,6 +61,11 @@ hipError_t launch_edge_select(const FdPlan &plan, int dtype, const void *X, int6
                               hipStream_t stream);
 hipError_t launch_edge_fill(int sum_k, int sum_n, const int32_t *edges, const int32_t *grp_offsets, int32_t *grp_src,
                             hipStream_t stream);
+
+// Debug dump of the FD of every pair (lk_fd_dump.hip); at most 65535 windows.
+hipError_t launch_fd_dump(int dtype, const void *X, int64_t ldx, int d, int n_windows, int max_window, int sum_n,
+                          int metric, const int32_t *win_offsets, const int32_t *win_tokens, float *out,
+                          long long capacity, hipStream_t stream);
 
 // Large windows (compute bound): LDS-tiled MFMA GEMM with the row arg-min fused into its epilogue.
 struct FdBigPlan {
@@ -143,5 +153,10 @@ struct RowTensors {
 hipError_t launch_rows(int mode, int dtype, int d, int sum_n, const RowTensors &t, const int32_t *new_index,
                        const int32_t *grp_offsets, const int32_t *grp_src, const float *xi, const int32_t *pos,
                        int32_t *pos_out, float *x_sqnorm_out, int64_t out_rows, hipStream_t stream);
+
+// rows behind the vision span (modes 1 and 2): input row sum_n + j -> output row cu_vis_out[batch] + j
+hipError_t launch_tail_rows(int dtype, int d, int sum_n, int batch, const RowTensors &t, const int32_t *pos,
+                            int32_t *pos_out, const int32_t *cu_vis_out, int64_t tail_rows, int64_t out_rows,
+                            hipStream_t stream);
 
 }  // namespace lk

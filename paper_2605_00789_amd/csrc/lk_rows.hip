@@ -247,6 +247,60 @@ __global__ __launch_bounds__(ROW_THREADS) void rows_kernel(RowArgs g) {
   (void)single_pass;
 }
 
+// Rows that trail the vision span in the caller's tensors (the prompt's text behind the image, Steps 4-5: the sequence
+// is rebuilt behind the shorter vision span): row sum_n + j of the input moves to row n' + j of the output, n' being
+// the number of vision rows that stay, read from the device (cu_vis_out[batch]).  One wave per (row, tensor).
+struct TailArgs {
+  RowTensors t;
+  const int32_t *pos, *cu_vis_out;
+  int32_t *pos_out;
+  int d, sum_n, batch, elem_bytes;
+  int64_t tail_rows, out_rows;
+};
+
+__global__ __launch_bounds__(ROW_THREADS) void tail_rows_kernel(TailArgs g) {
+  const int lane = threadIdx.x & 63;
+  const int64_t j = (int64_t)blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 6);
+  const int which = blockIdx.y;
+  if (j >= g.tail_rows) return;
+  int n_keep = g.cu_vis_out[g.batch];
+  n_keep = n_keep < 0 ? 0 : (n_keep > g.sum_n ? g.sum_n : n_keep);
+  const int64_t out_row = (int64_t)n_keep + j;
+  if (out_row >= g.out_rows) return;   // no room in the output: dropped, never written out of bounds
+  if (which == 0 && lane == 0 && g.pos && g.pos_out) g.pos_out[out_row] = g.pos[g.sum_n + j];
+  const char *in = static_cast<const char *>(g.t.in[which]);
+  char *out = static_cast<char *>(g.t.out[which]);
+  if (!in) return;
+  const char *row_in = in + ((int64_t)g.sum_n + j) * g.t.ld_in[which] * g.elem_bytes;
+  char *row_out = out + out_row * g.t.ld_out[which] * g.elem_bytes;
+  const int n_chunks = g.d * g.elem_bytes / 16;
+  for (int c0 = 0; c0 < n_chunks; c0 += WAVE * ROW_UNROLL) {
+    uint4 v[ROW_UNROLL];
+#pragma unroll
+    for (int u = 0; u < ROW_UNROLL; ++u) {
+      const int c = c0 + u * WAVE + lane;
+      v[u] = ld16(row_in + (int64_t)(c < n_chunks ? c : n_chunks - 1) * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < ROW_UNROLL; ++u) {
+      const int c = c0 + u * WAVE + lane;
+      if (c < n_chunks) *reinterpret_cast<uint4 *>(row_out + (int64_t)c * 16) = v[u];
+    }
+  }
+}
+
+hipError_t launch_tail_rows(int dtype, int d, int sum_n, int batch, const RowTensors &t, const int32_t *pos,
+                            int32_t *pos_out, const int32_t *cu_vis_out, int64_t tail_rows, int64_t out_rows,
+                            hipStream_t stream) {
+  if (tail_rows <= 0) return hipSuccess;
+  TailArgs g{};
+  g.t = t; g.pos = pos; g.pos_out = pos_out; g.cu_vis_out = cu_vis_out; g.d = d; g.sum_n = sum_n; g.batch = batch;
+  g.elem_bytes = dtype == 1 ? 2 : 4; g.tail_rows = tail_rows; g.out_rows = out_rows;
+  const dim3 grid((unsigned)((tail_rows + ROWS_PER_WG - 1) / ROWS_PER_WG), 3);
+  hipLaunchKernelGGL(tail_rows_kernel, grid, dim3(ROW_THREADS), 0, stream, g);
+  return hipGetLastError();
+}
+
 hipError_t launch_rows(int mode, int dtype, int d, int sum_n, const RowTensors &t, const int32_t *new_index,
                        const int32_t *grp_offsets, const int32_t *grp_src, const float *xi, const int32_t *pos,
                        int32_t *pos_out, float *x_sqnorm_out, int64_t out_rows, hipStream_t stream) {

@@ -5,41 +5,18 @@
 // Nothing here launches a kernel itself, allocates device memory or synchronises.
 #include "../../include/lightkv.h"
 
+#include "lk_helpers.h"
+
 #include <hip/hip_runtime.h>
 #include <mutex>
 
 namespace {
 
-// Helper streams and events of one device: host-side handles, made once outside stream capture, default priority,
-// never destroyed.  Distinct from the helper stream lightkv_score uses for its own fork.
-struct Helpers {
-  hipStream_t xi = nullptr, win = nullptr;
-  hipEvent_t fork_xi = nullptr, join_xi = nullptr, fork_win = nullptr, join_win = nullptr;
-  bool ready = false;
-  std::mutex in_use;
-};
-
-Helpers *helpers_for_current_device(hipStream_t main) {
-  static Helpers all[64];
-  static std::mutex mu;
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-  std::lock_guard<std::mutex> lock(mu);
-  Helpers &h = all[dev];
-  if (h.ready) return &h;
-  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-  if (hipStreamIsCapturing(main, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
-    (void)hipGetLastError();
-    return nullptr;   // never create objects while the caller is capturing
-  }
-  bool ok = hipStreamCreateWithFlags(&h.xi, hipStreamNonBlocking) == hipSuccess &&
-            hipStreamCreateWithFlags(&h.win, hipStreamNonBlocking) == hipSuccess;
-  hipEvent_t *evs[4] = {&h.fork_xi, &h.join_xi, &h.fork_win, &h.join_win};
-  for (int i = 0; ok && i < 4; ++i) ok = hipEventCreateWithFlags(evs[i], hipEventDisableTiming) == hipSuccess;
-  if (!ok) { (void)hipGetLastError(); return nullptr; }
-  h.ready = true;
-  return &h;
-}
+// Helper streams and events of one call: stream[0] runs xi, stream[1] builds the next stage's windows; event[0..3] =
+// fork_xi, join_xi, fork_win, join_win.  Sets come from a per-device pool (lk_helpers.h), distinct from the one
+// lightkv_score uses for its own fork.
+using Helpers = lk::HelperSet<2, 4>;
+enum { EV_FORK_XI = 0, EV_JOIN_XI = 1, EV_FORK_WIN = 2, EV_JOIN_WIN = 3 };
 
 // `to` waits for everything enqueued on `from` so far
 bool order_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
@@ -65,15 +42,18 @@ extern "C" lightkv_status lightkv_compress_schedule(const lightkv_stage *stages,
     if (st.problem.win_offsets != st.win_offsets || st.problem.win_tokens != st.win_tokens) return LIGHTKV_ERR_SHAPE;
     if (!st.problem.h_cu_vis || !st.problem.cu_vis) return LIGHTKV_ERR_NULL;
     if (st.problem.batch != stages[0].problem.batch || st.problem.d != stages[0].problem.d) return LIGHTKV_ERR_SHAPE;
+    if (st.cu_vis_target) {   // counts from the token budget: the schedule writes the array the descriptor points to
+      if (!st.win_remove) return LIGHTKV_ERR_NULL;
+      if (st.problem.win_remove != st.win_remove || st.problem.n_windows % st.problem.batch != 0) return LIGHTKV_ERR_SHAPE;
+    }
     size_t need = 0;
     const lightkv_status ws_st = lightkv_workspace_size(&st.problem, &need);
     if (ws_st != LIGHTKV_OK) return ws_st;
     if (!ws || ws_bytes < need) return LIGHTKV_ERR_WORKSPACE;
   }
   hipStream_t main = static_cast<hipStream_t>(stream);
-  Helpers *h = helpers_for_current_device(main);
   std::unique_lock<std::mutex> guard;
-  if (h) guard = std::unique_lock<std::mutex>(h->in_use);
+  Helpers *h = lk::acquire_helpers<2, 4>(main, guard);
 
   const int d = stages[0].problem.d, head_dim = stages[0].problem.head_dim;
   const void *Xi = X, *Ki = K, *Vi = V;
@@ -93,18 +73,21 @@ extern "C" lightkv_status lightkv_compress_schedule(const lightkv_stage *stages,
     xi_forked = false;
     if (!one_stream) {
       hipStream_t xs = main;
-      if (h && order_after(h->xi, main, h->fork_xi)) { xs = h->xi; xi_forked = true; }
+      if (h && order_after(h->stream[0], main, h->event[EV_FORK_XI])) { xs = h->stream[0]; xi_forked = true; }
       else if (h) (void)hipGetLastError();
       rc = lightkv_score(p, nullptr, 0, nullptr, Q, q_tok_stride, q_head_stride, Ki, ldki, head_dim, LIGHTKV_XI_TEXT_QUERY,
-                         nullptr, softmax_scale, st.xi, nullptr, nullptr, ws, ws_bytes, xs);
-      if (xi_forked && hipEventRecord(h->join_xi, h->xi) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
+                         nullptr, softmax_scale, st.xi, nullptr, nullptr, nullptr, 0, ws, ws_bytes, xs);
+      if (xi_forked && hipEventRecord(h->event[EV_JOIN_XI], h->stream[0]) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
     }
     // ---- windows: built by the previous stage's tail, or here
     if (windows_pending) {
-      if (win_forked && hipStreamWaitEvent(main, h->join_win, 0) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
+      if (win_forked && hipStreamWaitEvent(main, h->event[EV_JOIN_WIN], 0) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
     } else if (rc == LIGHTKV_OK) {
       rc = lightkv_build_windows(p->batch, p->h_cu_vis, p->cu_vis, posi, tiles, grid_h, grid_w, st.w, st.win_offsets,
                                  st.win_tokens, main);
+      if (rc == LIGHTKV_OK && st.cu_vis_target)
+        rc = lightkv_window_counts(p->batch, p->n_windows, st.win_offsets, LIGHTKV_COUNT_TARGET, 0.0, p->cu_vis,
+                                   st.cu_vis_target, st.win_remove, st.status, main);
     }
     windows_pending = false;
     // ---- feature divergence + selection
@@ -123,26 +106,31 @@ extern "C" lightkv_status lightkv_compress_schedule(const lightkv_stage *stages,
     if (rc == LIGHTKV_OK && s + 1 < n_stages) {
       const lightkv_stage &nx = stages[s + 1];
       hipStream_t wsx = main;
-      if (h && order_after(h->win, main, h->fork_win)) { wsx = h->win; win_forked = true; }
+      if (h && order_after(h->stream[1], main, h->event[EV_FORK_WIN])) { wsx = h->stream[1]; win_forked = true; }
       else if (h) (void)hipGetLastError();
       rc = lightkv_build_windows_next(p->batch, p->h_cu_vis, p->cu_vis, posi, st.new_index, st.cu_vis_out, tiles, grid_h,
                                       grid_w, nx.w, nx.win_offsets, nx.win_tokens, wsx);
-      if (win_forked && hipEventRecord(h->join_win, h->win) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
+      // ... and their counts: the next stage's budget over the windows as they now are (cu_vis_out of this stage is
+      // the next stage's cu_vis)
+      if (rc == LIGHTKV_OK && nx.cu_vis_target)
+        rc = lightkv_window_counts(nx.problem.batch, nx.problem.n_windows, nx.win_offsets, LIGHTKV_COUNT_TARGET, 0.0,
+                                   st.cu_vis_out, nx.cu_vis_target, nx.win_remove, nx.status, wsx);
+      if (win_forked && hipEventRecord(h->event[EV_JOIN_WIN], h->stream[1]) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
       windows_pending = true;
     }
     // ---- join xi, merge and compact
-    if (xi_forked && hipStreamWaitEvent(main, h->join_xi, 0) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
+    if (xi_forked && hipStreamWaitEvent(main, h->event[EV_JOIN_XI], 0) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
     xi_forked = false;
     if (rc == LIGHTKV_OK)
       rc = lightkv_aggregate_compact(p, st.new_index, st.grp_offsets, st.grp_src, st.xi, Xi, ldxi, Ki, ldki, Vi, ldvi,
-                                     posi, st.X_out, st.K_out, st.V_out, st.pos_out, st.x_sqnorm_out, st.out_rows, main);
+                                     posi, st.X_out, st.K_out, st.V_out, st.pos_out, st.x_sqnorm_out, st.out_rows, 0, nullptr, main);
     Xi = st.X_out; Ki = st.K_out; Vi = st.V_out;
     ldxi = ldki = ldvi = d;
     posi = st.pos_out;
     sq = st.x_sqnorm_out;
   }
   // whatever happened, nothing stays forked: the helper streams rejoin the caller's
-  if (xi_forked) (void)hipStreamWaitEvent(main, h->join_xi, 0);
-  if (win_forked) (void)hipStreamWaitEvent(main, h->join_win, 0);
+  if (xi_forked) (void)hipStreamWaitEvent(main, h->event[EV_JOIN_XI], 0);
+  if (win_forked) (void)hipStreamWaitEvent(main, h->event[EV_JOIN_WIN], 0);
   return rc;
 }

@@ -18,6 +18,7 @@
 //                      reads the scores takes the minimum over them (no atomics on global memory, nothing to
 //                      initialise); with more, the column tiles meet in one key per row by a 64-bit atomicMin.
 //   fd_big_finalize_kernel: keys -> best_fd / best_dst (the selection kernels can read the keys themselves).
+#include <atomic>
 #include "lk_common.h"
 #include "lk_launch.h"
 
@@ -407,14 +408,14 @@ hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int 
   const unsigned n_tiles = (unsigned)(n_windows * plan.mt * plan.nt);
   const unsigned grid = (n_tiles + 7u) / 8u * 8u;   // whole rounds over the XCDs; surplus workgroups exit at once
   constexpr size_t lds = (size_t)2 * BIG_STAGE;      // 102 KB: above the 64 KB default, the attribute below allows it
-  static bool attr_set[64] = {};                     // a property of the kernel as loaded on a device, set once per device
+  static std::atomic<bool> attr_set[64];                     // a property of the kernel as loaded on a device, set once per device
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  if (!attr_set[dev]) {
+  if (!attr_set[dev].load(std::memory_order_acquire)) {
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(fd_big_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds);
     if (e != hipSuccess) return e;
-    attr_set[dev] = true;
+    attr_set[dev].store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(fd_big_kernel, dim3(grid), dim3(BIG_THREADS), lds, stream, g);
   e = hipGetLastError();

@@ -1,15 +1,17 @@
 // Edge selection (paper Sec. 3.2.1 Step 2) and the index structures of the merge.
 //
 // In every window the r A nodes with the lowest best-edge FD are merged into their B node; the order
-// is fixed by the 64-bit key (order-preserving bits of FD, local position), so equal FDs go to the
-// earlier token.  Selection is an LDS bitonic sort of the window's keys by one workgroup; a second
-// sort of (destination, source) pairs yields each source's rank inside its group, which makes the
-// inverse map (grp_offsets / grp_src) deterministic without atomics on the output.
+// is fixed by the key (order-preserving bits of FD, then local position), so equal FDs go to the
+// earlier token.  Selection is by counting, not sorting: the rank of an A node is the number of
+// smaller keys in its window, and the rank of a merged node inside its group is the number of
+// earlier merged nodes with the same destination, which makes the inverse map (grp_offsets /
+// grp_src) deterministic without atomics on the output.
 //
 //   select_window_kernel : per window -> dst[], per-token source counts, per-source ranks (up to 256 A nodes), by
 //                          counting smaller keys inside one workgroup
 //   select_rank_kernel   : the same results for larger windows, the counting spread over several workgroups
 //   select_scan_kernel   : one workgroup -> exclusive scans (new_index, grp_offsets), cu_vis_out, grp_src
+#include <atomic>
 #include "lk_xi_body.h"
 
 namespace lk {
@@ -420,19 +422,19 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
 
 
 // The scan kernels take more dynamic LDS than the default limit: a property of a kernel as loaded on a device, set once
-// per device.
+// per device (setting it twice is harmless: the flag only has to be free of data races).
 static hipError_t allow_scan_lds() {
-  static bool done[64] = {};
+  static std::atomic<bool> done[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  if (done[dev]) return hipSuccess;
+  if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(select_scan_kernel<false>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)SCAN_LDS_BYTES);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute(reinterpret_cast<const void *>(select_scan_kernel<true>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SCAN_LDS_BYTES);
   if (e != hipSuccess) return e;
-  done[dev] = true;
+  done[dev].store(true, std::memory_order_release);
   return hipSuccess;
 }
 

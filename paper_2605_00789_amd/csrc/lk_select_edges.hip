@@ -17,6 +17,7 @@
 //                        (the k of the windows before it) for edge_fill_kernel; every window writes all of its slots.
 //   select_scan_kernel : unchanged (lk_select.hip): new_index from dst, grp_offsets from cnt.
 //   edge_fill_kernel   : grp_src[grp_offsets[b] + position] = a for every edge.
+#include <atomic>
 #include "lk_fd_body.h"
 
 namespace lk {
@@ -348,10 +349,10 @@ hipError_t launch_edge_select(const FdPlan &plan, int dtype, const void *X, int6
   const FdArgs g = make_fd_args(plan, dtype, X, ldx, d, n_windows, sum_n, win_offsets, win_tokens, partial, best_fd, best_dst);
   EdgeArgs q{win_remove, dst, cnt, src_rank, edges, sum_k, maxA * (maxB | 1)};
   const size_t lds = (size_t)maxA * (size_t)(maxB | 1) * sizeof(uint32_t);
-  static bool allowed[64] = {};   // up to 66 KB of dynamic LDS: above the 64 KB default, set once per device
+  static std::atomic<bool> allowed[64];   // up to 66 KB of dynamic LDS: above the 64 KB default, set once per device
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  if (!allowed[dev]) {
+  if (!allowed[dev].load(std::memory_order_acquire)) {
     const int max_lds = (int)((size_t)EDGE_MAX_SIDE * (EDGE_MAX_SIDE | 1) * sizeof(uint32_t));
     const void *kernels[5] = {reinterpret_cast<const void *>(edge_select_kernel<1>), reinterpret_cast<const void *>(edge_select_kernel<2>),
                               reinterpret_cast<const void *>(edge_select_kernel<4>), reinterpret_cast<const void *>(edge_select_kernel<8>),
@@ -360,7 +361,7 @@ hipError_t launch_edge_select(const FdPlan &plan, int dtype, const void *X, int6
       e = hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
       if (e != hipSuccess) return e;
     }
-    allowed[dev] = true;
+    allowed[dev].store(true, std::memory_order_release);
   }
   const dim3 grid((unsigned)n_windows), block(EDGE_THREADS);
   switch (plan.ksplit) {

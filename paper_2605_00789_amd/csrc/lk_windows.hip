@@ -218,6 +218,109 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_sort_kernel(WinArgs
   }
 }
 
+// ---- per-window counts (Sec. 3.2.1 Step 2, Sec. 3.2.2: the ratios P of the schedule) -----------------------------
+// One workgroup per sequence.  mode 0: r_w = min(floor(rho v_w), ceil(v_w / 2)) tokens; mode 1: k_w = min(floor(rho v_w / 2),
+// |A_w| |B_w|) edges; mode 2: the sequence has to go from its current length to a target length, and the difference
+// is spread over its windows as evenly as their sizes allow (no window gives more than its set A): with q the largest
+// level for which sum_w min(cap_w, q) stays within the budget, window w gives min(cap_w, q), and the first windows
+// that can give more than q give one more until the budget is met.  Integer work throughout; rho is a double so that
+// the floor is taken in the precision a host program would use.
+constexpr int CNT_THREADS = 256;
+
+struct CountArgs {
+  const int32_t *win_offsets, *cu_vis, *cu_target;
+  int32_t *win_remove, *status;
+  int win_per_seq, mode;
+  double rho;
+};
+
+__device__ __forceinline__ int block_sum_256(int v, int *lds4) {
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();                              // lds4 may still be read from the previous call
+  if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return lds4[0] + lds4[1] + lds4[2] + lds4[3];
+}
+
+__global__ __launch_bounds__(CNT_THREADS) void window_counts_kernel(CountArgs g) {
+  __shared__ int red[4];
+  __shared__ int wave_tot[4];
+  const int b = blockIdx.x, W = g.win_per_seq, w0 = b * W;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (g.mode != 2) {
+    for (int w = tid; w < W; w += CNT_THREADS) {
+      const long long v = g.win_offsets[w0 + w + 1] - g.win_offsets[w0 + w];
+      long long r, cap;
+      if (g.mode == 0) { r = (long long)floor(g.rho * (double)v + 1e-9); cap = (v + 1) / 2; }
+      else             { r = (long long)floor(g.rho * (double)v / 2.0 + 1e-9); cap = ((v + 1) / 2) * (v / 2); }
+      r = r < 0 ? 0 : (r > cap ? cap : r);
+      g.win_remove[w0 + w] = (int)r;
+    }
+    if (g.status && tid == 0) g.status[b] = 0;
+    return;
+  }
+  const int budget = (g.cu_vis[b + 1] - g.cu_vis[b]) - (g.cu_target[b + 1] - g.cu_target[b]);
+  auto cap_of = [&](int w) {
+    const int v = g.win_offsets[w0 + w + 1] - g.win_offsets[w0 + w];
+    return v >= 2 ? (v + 1) >> 1 : 0;
+  };
+  int total = 0, maxcap = 0;
+  for (int w = tid; w < W; w += CNT_THREADS) { const int c = cap_of(w); total += c; maxcap = c > maxcap ? c : maxcap; }
+  total = block_sum_256(total, red);
+  for (int o = 32; o >= 1; o >>= 1) { const int t = __shfl_xor(maxcap, o, 64); maxcap = t > maxcap ? t : maxcap; }
+  __syncthreads();
+  if (lane == 0) red[wave] = maxcap;
+  __syncthreads();
+  maxcap = max(max(red[0], red[1]), max(red[2], red[3]));
+  const bool infeasible = budget < 0 || budget > total;
+  if (g.status && tid == 0) g.status[b] = infeasible ? 1 : 0;
+  if (infeasible) {   // more than every set A holds: all of them go; a negative budget: nothing goes
+    for (int w = tid; w < W; w += CNT_THREADS) g.win_remove[w0 + w] = budget < 0 ? 0 : cap_of(w);
+    return;
+  }
+  // largest level q in [0, maxcap + 1] with sum_w min(cap_w, q) <= budget
+  int lo = 0, hi = maxcap + 1;
+  while (lo < hi) {   // uniform
+    const int mid = (lo + hi + 1) >> 1;
+    int f = 0;
+    for (int w = tid; w < W; w += CNT_THREADS) { const int c = cap_of(w); f += c < mid ? c : mid; }
+    f = block_sum_256(f, red);
+    if (f <= budget) lo = mid; else hi = mid - 1;
+  }
+  const int q = lo;
+  int given = 0;
+  for (int w = tid; w < W; w += CNT_THREADS) { const int c = cap_of(w); given += c < q ? c : q; }
+  given = block_sum_256(given, red);
+  const int missing = budget - given;
+  // one more from the first `missing` windows (in order) whose cap exceeds q
+  int carry = 0;
+  for (int wb = 0; wb < W; wb += CNT_THREADS) {   // uniform
+    const int w = wb + tid;
+    const int c = w < W ? cap_of(w) : 0;
+    const int more = (w < W && c > q) ? 1 : 0;
+    int inc = more;
+    for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(inc, o, 64); if (lane >= o) inc += t; }
+    __syncthreads();
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    int before = carry;
+    for (int k = 0; k < wave; ++k) before += wave_tot[k];
+    const int excl = before + inc - more;
+    if (w < W) g.win_remove[w0 + w] = (c < q ? c : q) + ((more && excl < missing) ? 1 : 0);
+    carry += wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+  }
+}
+
+hipError_t launch_window_counts(int batch, int win_per_seq, const int32_t *win_offsets, int mode, double rho,
+                                const int32_t *cu_vis, const int32_t *cu_target, int32_t *win_remove, int32_t *status,
+                                hipStream_t stream) {
+  CountArgs g{};
+  g.win_offsets = win_offsets; g.cu_vis = cu_vis; g.cu_target = cu_target; g.win_remove = win_remove; g.status = status;
+  g.win_per_seq = win_per_seq; g.mode = mode; g.rho = rho;
+  hipLaunchKernelGGL(window_counts_kernel, dim3(batch), dim3(CNT_THREADS), 0, stream, g);
+  return hipGetLastError();
+}
+
 hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, const int32_t *new_index,
                                 const int32_t *cu_out, int batch, int max_seq, int tiles,
                                 int grid_h, int grid_w, int w, int32_t *win_offsets, int32_t *win_tokens,

@@ -16,6 +16,7 @@
 //              prompt rows inside the lanes, then over the waves in wave order through LDS, gives xi of the block's
 //              32 keys for this head.
 // The heads are summed by xi_heads_kernel afterwards, as in the two-pass path.
+#include <atomic>
 #include "lk_xi_body.h"
 #include <type_traits>
 
@@ -332,17 +333,17 @@ bool xi_seq_applies(const XiPlan &plan, int xi_mode, const float *lse, int batch
 template <typename T, int DH>
 static hipError_t launch_xi_seq_t(const XiArgs &g, hipStream_t stream) {
   constexpr int XS_LDS_REQUEST = XsShape<T, DH>::LDS_REQUEST;
-  static bool allowed[64] = {};   // more than the 64 KB default: a property of the kernels as loaded on a device
+  static std::atomic<bool> allowed[64];   // more than the 64 KB default: a property of the kernels as loaded on a device
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  if (!allowed[dev]) {
+  if (!allowed[dev].load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(xi_seq_kernel<T, DH, true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)XS_LDS_REQUEST);
     if (e == hipSuccess)
       e = hipFuncSetAttribute(reinterpret_cast<const void *>(xi_seq_kernel<T, DH, false>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)XS_LDS_REQUEST);
     if (e != hipSuccess) return e;
-    allowed[dev] = true;
+    allowed[dev].store(true, std::memory_order_release);
   }
   const dim3 grid((unsigned)(g.batch * g.heads)), block((XsShape<T, DH>::THREADS));
   if (g.scale_log2 < 0.f) hipLaunchKernelGGL((xi_seq_kernel<T, DH, true>), grid, block, XS_LDS_REQUEST, stream, g);

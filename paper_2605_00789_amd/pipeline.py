@@ -11,7 +11,7 @@ import numpy as np
 import torch
 
 from . import binding as B
-from .schedule import edge_counts, max_window_cells, removal_counts, windows_per_sequence
+from .schedule import max_window_cells, windows_per_sequence
 
 
 def to_device(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
@@ -39,8 +39,9 @@ class StageBuffers:
     cu_vis: torch.Tensor
     win_offsets: torch.Tensor
     win_tokens: torch.Tensor
-    win_remove: torch.Tensor
-    h_win_remove: np.ndarray
+    win_remove: torch.Tensor       # written on the device by lightkv_window_counts (from the stage's token budget)
+    cu_target: torch.Tensor        # sequence offsets the stage must leave
+    status: torch.Tensor           # [batch]: 1 where the budget of a sequence could not be met
     xi: torch.Tensor
     best_fd: torch.Tensor
     best_dst: torch.Tensor
@@ -79,10 +80,13 @@ class CompressionPipeline:
             n_windows = batch * wps
             h_cu = (np.arange(batch + 1, dtype=np.int32) * n_in).astype(np.int32)
             cu = torch.from_numpy(h_cu).to(dev)
-            h_rem = removal_counts(batch, n_in, n_out, wps)
+            if n_out > n_in:
+                raise ValueError("a stage cannot add tokens")
             win_offsets = torch.empty(n_windows + 1, **i32)
             win_tokens = torch.empty(max(sum_in, 1), **i32)
-            win_remove = torch.from_numpy(h_rem).to(dev)
+            win_remove = torch.zeros(max(n_windows, 1), **i32)
+            cu_target = torch.from_numpy((np.arange(batch + 1, dtype=np.int32) * n_out).astype(np.int32)).to(dev)
+            status = torch.zeros(batch, **i32)
             bound = min(max_window_cells(tiles, grid_h, grid_w, w), n_in)
             prob = B.Problem(batch=batch, d=d, heads=heads, head_dim=head_dim, dtype=dtype, h_cu_vis=h_cu,
                              cu_vis=cu, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt, n_windows=n_windows,
@@ -91,7 +95,7 @@ class CompressionPipeline:
             ws_bytes = max(ws_bytes, B.lightkv_workspace_size(prob))
             st = StageBuffers(
                 n_in=n_in, n_out=n_out, w=w, problem=prob, h_cu_vis=h_cu, cu_vis=cu, win_offsets=win_offsets,
-                win_tokens=win_tokens, win_remove=win_remove, h_win_remove=h_rem,
+                win_tokens=win_tokens, win_remove=win_remove, cu_target=cu_target, status=status,
                 xi=torch.empty(sum_in, dtype=torch.float32, device=dev),
                 best_fd=torch.empty(sum_in, dtype=torch.float32, device=dev),
                 best_dst=torch.empty(sum_in, **i32), dst=torch.empty(sum_in, **i32),
@@ -110,7 +114,8 @@ class CompressionPipeline:
                                            xi=st.xi, best_fd=st.best_fd, best_dst=st.best_dst, dst=st.dst,
                                            new_index=st.new_index, grp_offsets=st.grp_offsets, grp_src=st.grp_src,
                                            cu_vis_out=st.cu_vis_out, X_out=st.X_out, K_out=st.K_out, V_out=st.V_out,
-                                           pos_out=st.pos_out, x_sqnorm_out=st.x_sq_out) for st in self.stages])
+                                           pos_out=st.pos_out, x_sqnorm_out=st.x_sq_out, cu_vis_target=st.cu_target,
+                                           win_remove=st.win_remove, status=st.status) for st in self.stages])
         # xi needs neither the windows nor the FD scores and is only consumed by the merge, so it is enqueued on a
         # second stream (default priority) that forks at the start of a stage and joins before aggregate/compact
         self.side = torch.cuda.Stream(device=dev)
@@ -150,6 +155,8 @@ class CompressionPipeline:
         else:
             B.lightkv_build_windows(self.batch, st.h_cu_vis, st.cu_vis, pos, self.tiles, self.grid_h, self.grid_w, st.w,
                                     st.win_offsets, st.win_tokens, stream=main)
+            B.lightkv_window_counts(self.batch, p.c.n_windows, st.win_offsets, B.COUNT_TARGET, st.win_remove,
+                                    cu_vis=st.cu_vis, cu_vis_target=st.cu_target, status=st.status, stream=main)
         if one_stream:
             B.lightkv_score_select(p, X, Q, K if score_K is None else score_K, xi, st.best_fd, st.best_dst, st.dst,
                                    st.new_index, st.grp_offsets, st.grp_src, st.cu_vis_out, self.ws, xi_mode=xi_mode,
@@ -170,6 +177,8 @@ class CompressionPipeline:
             B.lightkv_build_windows_next(self.batch, st.h_cu_vis, st.cu_vis, pos, st.new_index, st.cu_vis_out, self.tiles,
                                          self.grid_h, self.grid_w, nx.w, nx.win_offsets, nx.win_tokens,
                                          stream=self.side2)
+            B.lightkv_window_counts(self.batch, nx.problem.c.n_windows, nx.win_offsets, B.COUNT_TARGET, nx.win_remove,
+                                    cu_vis=st.cu_vis_out, cu_vis_target=nx.cu_target, status=nx.status, stream=self.side2)
         if xi_given is None and not one_stream:
             main.wait_stream(self.side)                                   # join: the merge needs xi
         stream = main
@@ -261,9 +270,14 @@ class EdgeTopKSchedule:
         B.lightkv_build_windows(batch, h_cu_vis, cu_vis, pos, self.tiles, self.grid_h, self.grid_w, w, win_offsets,
                                 win_tokens)
         mark("end")
-        h_win_offsets = win_offsets.cpu().numpy()            # first read-back: the window sizes
-        h_k = edge_counts(h_win_offsets, self.rho[s]) if h_win_edges is None else np.ascontiguousarray(h_win_edges, dtype=np.int32)
-        win_remove = torch.from_numpy(h_k).to(dev)
+        if h_win_edges is None:                              # k_w = floor(rho v_w / 2), on the device
+            win_remove = torch.empty(max(n_windows, 1), **i32)
+            B.lightkv_window_counts(batch, n_windows, win_offsets, B.COUNT_EDGES, win_remove, rho=self.rho[s])
+            h_k = win_remove.cpu().numpy()[:n_windows]       # first read-back: the counts ...
+        else:
+            h_k = np.ascontiguousarray(h_win_edges, dtype=np.int32)
+            win_remove = torch.from_numpy(h_k).to(dev)
+        h_win_offsets = win_offsets.cpu().numpy()            # ... and the window sizes
         prob = B.Problem(batch=batch, d=self.d, heads=self.heads, head_dim=self.head_dim, dtype=self.dtype,
                          h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt,
                          n_windows=n_windows, max_window_tokens=0, win_offsets=win_offsets, win_tokens=win_tokens,

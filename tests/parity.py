@@ -81,7 +81,12 @@ def check_stage(pipe, s: int, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_mode=0, lse
     wo, wt = O.build_windows(pos, cu_vis, pipe.tiles, pipe.grid_h, pipe.grid_w, st_cfg.w)
     np.testing.assert_array_equal(g["win_offsets"], wo, err_msg="win_offsets")
     np.testing.assert_array_equal(g["win_tokens"][:len(wt)], wt, err_msg="win_tokens")
-    rem = st_cfg.h_win_remove
+    # per-window counts: the stage's token budget spread over the windows as they are (exact)
+    n_seq = np.diff(np.asarray(cu_vis, dtype=np.int64))
+    rem, infeasible = O.removal_counts_target(wo, batch, n_seq - st_cfg.n_out)
+    assert not infeasible.any(), "the stage's budget cannot be met by these windows"
+    np.testing.assert_array_equal(st.win_remove.cpu().numpy()[:len(rem)], rem, err_msg="win_remove")
+    np.testing.assert_array_equal(st.status.cpu().numpy(), np.zeros(batch, dtype=np.int32), err_msg="status")
 
     X64, K64, V64 = O.widen(Xs, dtype), O.widen(Ks, dtype), O.widen(Vs, dtype)
     # ---- xi

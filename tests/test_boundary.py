@@ -18,7 +18,7 @@ def B():
 
 def test_every_declared_symbol_is_exported(B):
     header = open(os.path.join(ROOT, "include", "lightkv.h")).read()
-    declared = set(re.findall(r"^(?:const char \*|int |lightkv_status )(lightkv_[a-z_]+)\(", header, re.M))
+    declared = set(re.findall(r"^(?:const char \*|int |int32_t |lightkv_status )(lightkv_[a-z_]+)\(", header, re.M))
     assert declared == set(B.EXPORTS)
     lib = C.CDLL(B.lib_path())
     for name in declared:
@@ -112,7 +112,7 @@ def test_entry_points_reject_bad_arguments_before_launch(B):
     # score: NULL outputs, misaligned X, short row stride, bad mode, missing workspace
     args = lambda **o: [o.get("p", C.byref(p)), o.get("X", fake), o.get("ldx", 64), o.get("sq", None), fake, 64, 32, fake, 64, 32,
                         o.get("mode", 0), o.get("lse", None), 0.0, o.get("xi", fake), fake, fake,
-                        o.get("ws", fake), o.get("wsb", ws), None]
+                        o.get("dump", None), o.get("dumpn", 0), o.get("ws", fake), o.get("wsb", ws), None]
     assert lib.lightkv_score(*args(xi=None)) == 1
     assert lib.lightkv_score(*args(X=C.c_void_p(0x1008))) == 5
     assert lib.lightkv_score(*args(ldx=32)) == 2
@@ -123,6 +123,9 @@ def test_entry_points_reject_bad_arguments_before_launch(B):
     assert lib.lightkv_score(*args(ws=None)) == 6
     assert lib.lightkv_score(*args(wsb=ws - 1)) == 6
     assert lib.lightkv_score(*args(ws=C.c_void_p(0x1010))) == 6                  # workspace alignment
+    assert lib.lightkv_score(*args(dump=fake, dumpn=-1)) == 2                    # FD dump: negative capacity
+    assert lib.lightkv_score(*args(dump=C.c_void_p(0x1002), dumpn=64)) == 5     # ... misaligned
+    assert lib.lightkv_score(*args(dump=fake, dumpn=64, X=None)) == 1           # ... needs the FD half
     # score_select: the union of both argument lists
     ss = lambda **o: [C.byref(p), o.get("X", fake), 64, None, fake, 64, 32, fake, 64, 32, 0, None, 0.0, fake, fake, fake,
                       o.get("dst", fake), fake, fake, fake, fake, o.get("ws", fake), o.get("wsb", ws), None]
@@ -167,12 +170,14 @@ def test_entry_points_reject_bad_arguments_before_launch(B):
     assert lib.lightkv_aggregate(C.byref(p), None, fake, fake, fake, 64, fake, 64, fake, 64, None) == 1
     assert lib.lightkv_aggregate(C.byref(p), fake, fake, fake, fake, 8, fake, 64, fake, 64, None) == 2
     other = C.c_void_p(0x100000)
-    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, fake, None, None, None, None, 8, None) == 2   # in == out
-    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, None, None, None, None, None, 8, None) == 1   # out missing
-    assert lib.lightkv_compact(C.byref(p), None, fake, 64, None, 0, None, 0, None, other, None, None, None, None, 8, None) == 1
-    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, fake, other, None, None, None, None, 8, None) == 1  # pos without pos_out
-    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, C.c_void_p(0x1100), None, None, None, None, 8, None) == 2  # overlap
-    assert lib.lightkv_compact(C.byref(p), fake, None, 0, fake, 64, None, 0, None, None, other, None, None, other, 8, None) == 1  # norms of X without X
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, fake, None, None, None, None, 8, 0, None, None) == 2   # in == out
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, None, None, None, None, None, 8, 0, None, None) == 1   # out missing
+    assert lib.lightkv_compact(C.byref(p), None, fake, 64, None, 0, None, 0, None, other, None, None, None, None, 8, 0, None, None) == 1
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, fake, other, None, None, None, None, 8, 0, None, None) == 1  # pos without pos_out
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, C.c_void_p(0x1100), None, None, None, None, 8, 0, None, None) == 2  # overlap
+    assert lib.lightkv_compact(C.byref(p), fake, None, 0, fake, 64, None, 0, None, None, other, None, None, other, 8, 0, None, None) == 1  # norms of X without X
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, other, None, None, None, None, 8, 3, None, None) == 1   # trailing rows need cu_vis_out
+    assert lib.lightkv_compact(C.byref(p), fake, fake, 64, None, 0, None, 0, None, other, None, None, None, None, 8, -1, fake, None) == 2
     # build_windows
     hcu = np.array([0, 8], dtype=np.int32)
     hp = C.c_void_p(hcu.ctypes.data)
@@ -182,24 +187,31 @@ def test_entry_points_reject_bad_arguments_before_launch(B):
     assert lib.lightkv_build_windows(1, hp, fake, fake, 1, 4, 2, 1000, fake, fake, None) == 5
 
 
-def test_schedule_helpers_agree_with_the_oracle():
-    from paper_2605_00789_amd.schedule import removal_counts, windows_per_sequence, max_window_cells
+def test_partition_helpers_agree_with_the_oracle():
+    """Host arithmetic exported by the library (no device needed): windows per sequence, and the bound on a window's size."""
+    from paper_2605_00789_amd.schedule import windows_per_sequence, max_window_cells
     from oracle import lightkv_oracle as O
-    for batch, n_in, n_out, wps in ((1, 576, 472, 16), (16, 472, 387, 4), (1, 2880, 2360, 180), (2, 64, 36, 4), (1, 10, 10, 3)):
-        np.testing.assert_array_equal(removal_counts(batch, n_in, n_out, wps), O.stage_removals(batch, n_in, n_out, wps))
     assert windows_per_sequence(5, 6) == 180 and windows_per_sequence(5, 0) == 1
     assert max_window_cells(1, 24, 24, 4) == 36 and max_window_cells(5, 24, 24, 0) == 2880
     # the bound really bounds every window the oracle builds, also on grids that do not divide
-    for gh, gw, w in ((24, 24, 6), (5, 7, 2), (7, 9, 4), (3, 3, 3)):
+    for gh, gw, w in ((24, 24, 6), (5, 7, 2), (7, 9, 4), (3, 3, 3), (3, 3, 5), (64, 64, 32)):
         wo, _ = O.build_windows(np.arange(gh * gw), np.array([0, gh * gw]), 1, gh, gw, w)
         assert np.diff(wo).max() == max_window_cells(1, gh, gw, w)
     with pytest.raises(ValueError):
-        removal_counts(1, 10, 11, 2)
-    # edges per window under the literal reading of Step 2: floor(rho v / 2), never more than the window has pairs
-    from paper_2605_00789_amd.schedule import edge_counts
-    offs = np.array([0, 36, 36, 37, 39, 183, 199], dtype=np.int32)          # windows of 36, 0, 1, 2, 144, 16 tokens
-    assert edge_counts(offs, 0.5).tolist() == [9, 0, 0, 0, 36, 4]
-    assert edge_counts(offs, 0.36).tolist() == [6, 0, 0, 0, 25, 2]
-    assert edge_counts(offs, 1.0).tolist() == [18, 0, 0, 1, 72, 8]
-    assert edge_counts(np.array([0, 2, 5], dtype=np.int32), 40.0).tolist() == [1, 2]   # capped at |A| |B|
-    assert edge_counts(offs, 0.0).tolist() == [0] * 6
+        windows_per_sequence(0, 2)
+    with pytest.raises(ValueError):
+        max_window_cells(1, 0, 4, 2)
+
+
+def test_window_counts_rejects_bad_arguments_before_any_launch(B):
+    lib = B._lib
+    fake = C.c_void_p(0x1000)
+    f = lib.lightkv_window_counts
+    assert f(1, 4, None, 0, 0.5, None, None, fake, None, None) == 1
+    assert f(1, 4, fake, 0, 0.5, None, None, None, None, None) == 1
+    assert f(3, 4, fake, 0, 0.5, None, None, fake, None, None) == 2          # windows do not divide over the sequences
+    assert f(1, 4, fake, 7, 0.5, None, None, fake, None, None) == 5          # unknown mode
+    assert f(1, 4, fake, 2, 0.0, None, fake, fake, None, None) == 1          # target mode without the current offsets
+    assert f(1, 4, fake, 0, float("nan"), None, None, fake, None, None) == 2
+    assert f(1, 4, fake, 1, -0.1, None, None, fake, None, None) == 2
+    assert f(2, 0, fake, 0, 0.5, None, None, fake, None, None) == 0          # nothing to do

@@ -156,16 +156,12 @@ def test_distance_metrics_match_oracle(cfg, metric):
 
 
 def _feasible(wl):
-    """Every window of every stage can give up its share (the even split never asks a window for more than its A set)."""
+    """Every stage's token budget fits into the A sets of its windows (the oracle refuses a schedule otherwise)."""
     from oracle import lightkv_oracle as O
-    X, K, V, pos, cu_vis, n_in = wl.X, wl.K, wl.V, wl.pos, wl.cu_vis, wl.n_per_seq
-    for s, res in enumerate(O.compress_schedule(wl)):
-        wo, _ = O.build_windows(pos, cu_vis, wl.tiles, wl.grid_h, wl.grid_w, wl.windows_per_axis[s])
-        rem = O.stage_removals(wl.batch, n_in, wl.targets[s], (len(wo) - 1) // wl.batch)
-        v = np.diff(wo)
-        if np.any(rem > np.where(v >= 2, (v + 1) // 2, 0)):
-            return False
-        pos, cu_vis, n_in = res.pos, res.cu_vis, wl.targets[s]
+    try:
+        O.compress_schedule(wl)
+    except ValueError:
+        return False
     return True
 
 
@@ -851,3 +847,235 @@ def test_edge_topk_refusals():
                                       h_win_remove=np.array([100 * 100 + 1, 0], dtype=np.int32),
                                       win_remove=torch.zeros(2, dtype=torch.int32, device=dev)))
     assert e.value.status in (4, 5)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# per-window counts on the device, helper-stream pool
+# ---------------------------------------------------------------------------------------------------------------
+def test_window_counts_match_oracle():
+    """lightkv_window_counts against the oracle's rules, exactly: ratio (tokens), ratio (edges, Step 2 as printed) and a
+    token budget per sequence spread over windows of very unequal sizes -- budgets that no cap touches, budgets that
+    small windows bind, the whole of every A set, one token too many (flagged), zero; up to 700 windows per sequence."""
+    from oracle import lightkv_oracle as O
+    from paper_2605_00789_amd import binding as B
+    rng = np.random.default_rng(606)
+    dev = "cuda:0"
+    for trial in range(40):
+        batch = int(rng.integers(1, 5))
+        per = int(rng.choice([1, 2, 5, 16, 180, 257, 700]))
+        top = int(rng.choice([3, 12, 40, 300]))
+        sizes = rng.integers(0, top + 1, size=batch * per)
+        if trial % 7 == 0:
+            sizes[:] = sizes[0] if sizes[0] >= 2 else 6            # equal windows: the even rule
+        wo = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+        cu = wo[::per].copy()
+        n_seq = np.diff(cu)
+        cap = np.where(sizes >= 2, (sizes + 1) // 2, 0).reshape(batch, per).sum(axis=1)
+        kind = trial % 5
+        budget = [int(c) if kind == 0 else int(c) + 1 if kind == 1 else 0 if kind == 2 else int(rng.integers(0, c + 1))
+                  for c in cap]
+        target = np.concatenate([[0], np.cumsum(n_seq - np.asarray(budget))]).astype(np.int32)
+        d_wo, d_cu, d_tg = (torch.from_numpy(a).to(dev) for a in (wo, cu, target))
+        out = torch.full((batch * per,), -3, dtype=torch.int32, device=dev)
+        status = torch.full((batch,), -3, dtype=torch.int32, device=dev)
+        B.lightkv_window_counts(batch, batch * per, d_wo, B.COUNT_TARGET, out, cu_vis=d_cu, cu_vis_target=d_tg, status=status)
+        want, bad = O.removal_counts_target(wo, batch, budget)
+        np.testing.assert_array_equal(out.cpu().numpy(), want, err_msg="target counts, trial %d" % trial)
+        np.testing.assert_array_equal(status.cpu().numpy(), bad.astype(np.int32), err_msg="status, trial %d" % trial)
+        for rho in (0.5, 0.36, 0.7, 1.0, 0.1, 0.0, 0.45):
+            B.lightkv_window_counts(batch, batch * per, d_wo, B.COUNT_RATIO, out, rho=rho)
+            np.testing.assert_array_equal(out.cpu().numpy(), O.removal_counts_ratio(wo, rho), err_msg="ratio %g" % rho)
+            B.lightkv_window_counts(batch, batch * per, d_wo, B.COUNT_EDGES, out, rho=rho)
+            np.testing.assert_array_equal(out.cpu().numpy(), O.edge_counts_ratio(wo, rho), err_msg="edges %g" % rho)
+
+
+def test_uneven_windows_still_hit_the_stage_targets():
+    """A schedule whose second stage has windows of unequal sizes, some of them short of tokens: one global stage thins
+    the grid unevenly (576 -> 322), then 6 x 6 windows of 8 to 14 tokens have to give up 142 of them, which takes the
+    whole set A of the small ones (33 windows end at their cap) and correspondingly more of the others.  Every stage
+    must land on its target exactly, with the counts the oracle's rule gives, and report a clean status."""
+    from workloads import make_custom
+    from parity import check_workload
+    wl = make_custom(name="uneven", seed=99, dtype="bf16", batch=2, grid_h=24, grid_w=24, text_lens=(20, 50), d=256,
+                     heads=2, head_dim=128, n_c=40, structure="grid", windows_per_axis=(1, 6), n_final=180)
+    reps = check_workload(wl)
+    _report(wl, reps)
+    assert [r.n_out for r in reps] == wl.targets
+
+
+def test_an_open_capture_does_not_block_other_callers():
+    """While one host thread has a stream capture open that contains a schedule (helper streams forked into the
+    capture), another thread runs a schedule eagerly on its own stream: it must get a helper set of its own and the
+    right results, and the capture must end and replay correctly afterwards."""
+    import threading
+    from workloads import make_workload
+    from parity import to_dev
+    from paper_2605_00789_amd import CompressionPipeline
+    names = ("X_out", "K_out", "V_out", "pos_out", "xi", "dst", "new_index", "grp_offsets", "cu_vis_out", "win_remove")
+    jobs = []
+    for cfg in (3, "halving"):
+        wl = make_workload(cfg)
+        pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                                   tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                                   windows_per_axis=wl.windows_per_axis, targets=wl.targets)
+        args = tuple(to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q)) + (torch.from_numpy(wl.pos).cuda(),)
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            pipe.run(*args)
+            stream.synchronize()
+        want = [[getattr(st, n).clone() for n in names] for st in pipe.stages]
+        jobs.append(dict(pipe=pipe, args=args, stream=stream, want=want))
+
+    def scribble(pipe):
+        for st in pipe.stages:
+            st.X_out.zero_(); st.xi.fill_(float("nan")); st.dst.fill_(-3); st.win_remove.fill_(-1)
+
+    def differs(job):
+        return [(s, n) for s, st in enumerate(job["pipe"].stages) for n, a in zip(names, job["want"][s])
+                if not torch.equal(a, getattr(st, n))]
+
+    a, b = jobs
+    errors = []
+
+    def eager_b():
+        try:
+            with torch.cuda.stream(b["stream"]):
+                for _ in range(3):
+                    scribble(b["pipe"])
+                    b["pipe"].run(*b["args"])
+                    b["stream"].synchronize()
+                    errors.extend(differs(b))
+        except Exception as e:   # noqa: BLE001
+            errors.append(repr(e))
+
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=a["stream"], capture_error_mode="thread_local"):
+        a["pipe"].run(*a["args"])
+        t = threading.Thread(target=eager_b)          # the capture is still open
+        t.start()
+        t.join(timeout=100)
+        assert not t.is_alive()
+    assert not errors, errors[:4]
+    for _ in range(2):
+        with torch.cuda.stream(a["stream"]):
+            scribble(a["pipe"])
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert not differs(a)
+
+
+@pytest.mark.parametrize("cfg,metric", [(1, "cosine"), (2, "cosine"), (2, "l2sq"), ("bigwin", "cosine"), ("bigwin", "euclidean")])
+def test_fd_dump_holds_the_divergence_of_every_pair(cfg, metric):
+    """The debug output of lightkv_score: every window's |A| x |B| block of FD values against the oracle's dense
+    blocks, and against the scores the call reports (best_fd is the row minimum, best_dst its first column, up to the
+    accuracy of the scoring kernels).  fp32 and bf16, packed small windows, multi-tile windows, a window on the tiled
+    matrix-core path, a capacity that cuts the dump short."""
+    from workloads import make_workload, make_custom
+    from parity import to_dev
+    from oracle import lightkv_oracle as O
+    from paper_2605_00789_amd import CompressionPipeline
+    from paper_2605_00789_amd import binding as B
+    if cfg == "bigwin":
+        wl = make_custom(name="dump_big", seed=21, dtype="bf16", batch=2, grid_h=30, grid_w=40, text_lens=(9, 21), d=256,
+                         heads=2, head_dim=128, n_c=40, structure="grid", windows_per_axis=(1,), n_final=700)
+    else:
+        wl = make_workload(cfg)
+    pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                               tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                               windows_per_axis=wl.windows_per_axis, targets=wl.targets, metric=metric)
+    st = pipe.stages[0]
+    X = to_dev(wl.X, wl.dtype)
+    pos = torch.from_numpy(wl.pos).cuda()
+    B.lightkv_build_windows(pipe.batch, st.h_cu_vis, st.cu_vis, pos, pipe.tiles, pipe.grid_h, pipe.grid_w, st.w,
+                            st.win_offsets, st.win_tokens)
+    wo, wt = O.build_windows(wl.pos, wl.cu_vis, wl.tiles, wl.grid_h, wl.grid_w, st.w)
+    v = np.diff(wo).astype(np.int64)
+    total = int((((v + 1) // 2) * (v // 2)).sum())
+    dump = torch.full((total + 7,), -5.0, dtype=torch.float32, device="cuda")
+    B.lightkv_score(st.problem, X, None, None, st.xi, st.best_fd, st.best_dst, pipe.ws, xi_mode=B.XI_GIVEN, fd_dump=dump)
+    torch.cuda.synchronize()
+    got = dump.cpu().numpy()
+    assert np.all(got[total:] == -5.0)                                   # nothing behind the last block
+    best_fd, best_dst = st.best_fd.cpu().numpy(), st.best_dst.cpu().numpy()
+    X64 = O.widen(wl.X, wl.dtype)
+    tol = 1e-5 if wl.dtype == "bf16" else 1e-6
+    at, worst, worst_best = 0, 0.0, 0.0
+    for w in range(len(v)):
+        toks = wt[wo[w]:wo[w + 1]]
+        A, Bn = O.split_window(toks)
+        if len(Bn) == 0:
+            continue
+        ref = O.feature_divergence(X64[A], X64[Bn], metric)
+        blk = got[at:at + ref.size].reshape(ref.shape).astype(np.float64)
+        at += ref.size
+        scale = 1.0 if metric == "cosine" else float((X64[A] ** 2).sum(axis=1).max() + (X64[Bn] ** 2).sum(axis=1).max())
+        a_, b_ = (blk, ref) if metric != "euclidean" else (blk * blk, ref * ref)
+        worst = max(worst, float(np.abs(a_ - b_).max()) / scale)
+        bf = best_fd[A].astype(np.float64)
+        rowmin = blk.min(axis=1)
+        c_, d_ = (bf, rowmin) if metric != "euclidean" else (bf * bf, rowmin * rowmin)
+        worst_best = max(worst_best, float(np.abs(c_ - d_).max()) / scale)
+        col = {int(t): j for j, t in enumerate(Bn)}
+        picked = np.array([a_[i, col[int(best_dst[a])]] for i, a in enumerate(A)])
+        assert np.all(picked <= a_.min(axis=1) + tol * scale)             # the reported partner is a row minimum of the dump
+    assert at == total
+    print("[fd dump] %s %s: %d pairs, dump vs oracle %.2e, row minimum vs best_fd %.2e" % (wl.name, metric, total, worst, worst_best), flush=True)
+    assert worst <= 2e-7 and worst_best <= tol
+    # a buffer that holds only part of the dump is filled up to its capacity and not beyond
+    part = torch.full((total // 2 + 3,), -5.0, dtype=torch.float32, device="cuda")
+    B.lightkv_score(st.problem, X, None, None, st.xi, st.best_fd, st.best_dst, pipe.ws, xi_mode=B.XI_GIVEN,
+                    fd_dump=part[:total // 2])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(part.cpu().numpy()[:total // 2], got[:total // 2])
+    assert np.all(part.cpu().numpy()[total // 2:] == -5.0)
+
+
+@pytest.mark.parametrize("fused", [True, False])
+def test_rows_behind_the_vision_span_are_shifted(fused):
+    """Steps 4-5: the sequence continues behind the shorter vision span.  The caller's X, K, V, pos hold 37 text rows
+    behind the 144 vision rows; after the step they sit directly behind the vision rows that stay, bit for bit, and
+    the vision part is what the call without trailing rows gives.  An output with too little room drops the surplus
+    rows instead of writing beyond it."""
+    from workloads import make_custom
+    from parity import to_dev
+    from paper_2605_00789_amd import CompressionPipeline
+    from paper_2605_00789_amd import binding as B
+    wl = make_custom(name="tails", seed=8, dtype="bf16", batch=1, grid_h=12, grid_w=12, text_lens=(37,), d=256, heads=2,
+                     head_dim=128, n_c=12, structure="grid", windows_per_axis=(3,), n_final=90)
+    pipe = CompressionPipeline(dtype="bf16", batch=1, d=256, heads=2, head_dim=128, tiles=1, grid_h=12, grid_w=12,
+                               cu_txt=wl.cu_txt, windows_per_axis=(3,), targets=(90,))
+    X, K, V, Q = (to_dev(t, "bf16") for t in (wl.X, wl.K, wl.V, wl.Q))
+    pos = torch.from_numpy(wl.pos).cuda()
+    st = pipe.run_stage(0, X, K, V, Q, pos)
+    torch.cuda.synchronize()
+    n, n_out, tail = 144, 90, 37
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    full = [torch.cat([t, torch.randn(tail, 256, device="cuda", generator=gen).to(torch.bfloat16)]) for t in (X, K, V)]
+    pos_full = torch.cat([pos, torch.arange(1000, 1000 + tail, dtype=torch.int32, device="cuda")])
+    outs = [torch.full((n_out + tail + 2, 256), 7.0, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    pos_out = torch.full((n_out + tail + 2,), -7, dtype=torch.int32, device="cuda")
+    if fused:
+        B.lightkv_aggregate_compact(st.problem, st.new_index, st.grp_offsets, st.grp_src, st.xi, *full, pos_full, *outs,
+                                    pos_out, tail_rows=tail, cu_vis_out=st.cu_vis_out)
+    else:
+        tmp = [t.clone() for t in full]
+        B.lightkv_aggregate(st.problem, st.grp_offsets, st.grp_src, st.xi, *[t[:n] for t in tmp])
+        B.lightkv_compact(st.problem, st.new_index, *tmp, pos_full, *outs, pos_out, tail_rows=tail, cu_vis_out=st.cu_vis_out)
+    torch.cuda.synchronize()
+    for got, want, src in zip(outs, (st.X_out, st.K_out, st.V_out), full):
+        assert torch.equal(got[:n_out], want[:n_out])                  # the vision part is unchanged by the extra rows
+        assert torch.equal(got[n_out:n_out + tail], src[n:])           # the text rows, shifted, bit for bit
+        assert torch.all(got[n_out + tail:] == 7.0)                    # nothing behind them
+    assert torch.equal(pos_out[:n_out], st.pos_out[:n_out]) and torch.equal(pos_out[n_out:n_out + tail], pos_full[n:])
+    assert torch.all(pos_out[n_out + tail:] == -7)
+    # too little room: 10 of the 37 text rows fit
+    small = [torch.full((n_out + 12, 256), 7.0, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    small_pos = torch.full((n_out + 12,), -7, dtype=torch.int32, device="cuda")
+    B.lightkv_compact(st.problem, st.new_index, *full, pos_full, *[t[:n_out + 10] for t in small], small_pos[:n_out + 10],
+                      tail_rows=tail, cu_vis_out=st.cu_vis_out)
+    torch.cuda.synchronize()
+    for got, src in zip(small, full):
+        assert torch.equal(got[n_out:n_out + 10], src[n:n + 10]) and torch.all(got[n_out + 10:] == 7.0)
+    assert torch.all(small_pos[n_out + 10:] == -7)

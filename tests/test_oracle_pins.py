@@ -525,3 +525,77 @@ def test_whole_schedule_tiny_config():
         assert win_of[a] == win_of[r.dst[a]] and half[a] == 0 and half[r.dst[a]] == 1
     # with mixture data the merged pairs overwhelmingly share a centre: their FD is far below the median FD
     assert np.median(r.best_fd[r.dst >= 0]) < 0.05
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# per-window counts from a stage's token budget (reading R1: even spread, no window above its set A)
+# ---------------------------------------------------------------------------------------------------------------
+def test_budget_spread_is_the_even_rule_when_no_window_is_short():
+    # 16 equal windows of 36 tokens, 104 to remove: 6 each and one more for the first 8 (104 = 6*16 + 8)
+    offs = np.arange(17) * 36
+    r, bad = O.removal_counts_target(offs, 1, [104])
+    assert r.tolist() == [7] * 8 + [6] * 8 and not bad.any()
+    np.testing.assert_array_equal(r, O.removal_counts_even(104, 16))
+    # two sequences, each with its own budget
+    offs = np.arange(9) * 10
+    r, bad = O.removal_counts_target(offs, 2, [9, 2])
+    assert r.tolist() == [3, 2, 2, 2, 1, 1, 0, 0] and not bad.any()
+
+
+def test_budget_spread_by_hand_when_small_windows_bind():
+    # window sizes 2, 9, 1, 6, 3 -> caps 1, 5, 0, 3, 2 (a one-token window has nothing to merge into); budget 9:
+    # level 2 gives 1+2+0+2+2 = 7, level 3 would give 1+3+0+3+2 = 9 <= 9 -> q = 3, nothing missing
+    offs = np.cumsum([0, 2, 9, 1, 6, 3])
+    r, bad = O.removal_counts_target(offs, 1, [9])
+    assert r.tolist() == [1, 3, 0, 3, 2] and not bad[0]
+    # budget 8: q = 2 (7 tokens), one missing -> the first window that can give more than 2 is window 1
+    r, _ = O.removal_counts_target(offs, 1, [8])
+    assert r.tolist() == [1, 3, 0, 2, 2]
+    # the whole of every A set is the most a step can take (limitations paragraph): 11 here; 12 is flagged
+    r, bad = O.removal_counts_target(offs, 1, [11])
+    assert r.tolist() == [1, 5, 0, 3, 2] and not bad[0]
+    r, bad = O.removal_counts_target(offs, 1, [12])
+    assert r.tolist() == [1, 5, 0, 3, 2] and bad[0]
+    r, bad = O.removal_counts_target(offs, 1, [0])
+    assert r.tolist() == [0] * 5 and not bad[0]
+
+
+def test_budget_spread_invariants_on_random_windows():
+    rng = np.random.default_rng(12)
+    for _ in range(200):
+        batch = int(rng.integers(1, 4))
+        per = int(rng.integers(1, 9))
+        sizes = rng.integers(0, 12, size=batch * per)
+        offs = np.concatenate([[0], np.cumsum(sizes)])
+        cap = np.where(sizes >= 2, (sizes + 1) // 2, 0).reshape(batch, per)
+        budget = [int(rng.integers(0, cap[b].sum() + 2)) for b in range(batch)]
+        r, bad = O.removal_counts_target(offs, batch, budget)
+        r = r.reshape(batch, per)
+        for b in range(batch):
+            assert np.all(r[b] <= cap[b]) and np.all(r[b] >= 0)
+            if budget[b] > cap[b].sum():
+                assert bad[b] and np.all(r[b] == cap[b])
+                continue
+            assert not bad[b] and r[b].sum() == budget[b]                      # the budget is met exactly
+            free = r[b] < cap[b]                                               # windows that could have given more
+            if free.any():
+                top = r[b][free].max()
+                assert np.all(r[b][free] >= top - 1)                           # ... differ by at most one token
+                assert np.all(r[b][~free] <= top + 1)                          # and a window at its cap gives no more than one above them
+                hi = np.nonzero(free & (r[b] == top))[0]
+                lo = np.nonzero(free & (r[b] == top - 1))[0]
+                if len(hi) and len(lo) and r[b][free].min() != top:
+                    assert hi.max() < lo.min()                                 # the extra tokens come from the first windows
+
+
+def test_edge_counts_follow_step_2_as_printed():
+    offs = np.cumsum([0, 36, 16, 1, 2, 97])
+    assert O.edge_counts_ratio(offs, 0.5).tolist() == [9, 4, 0, 0, 24]
+    assert O.edge_counts_ratio(offs, 1.0).tolist() == [18, 8, 0, 1, 48]
+    assert O.edge_counts_ratio(np.array([0, 2]), 8.0).tolist() == [1]          # never more than the window has pairs
+    offs = np.array([0, 36, 36, 37, 39, 183, 199], dtype=np.int32)             # windows of 36, 0, 1, 2, 144, 16 tokens
+    assert O.edge_counts_ratio(offs, 0.5).tolist() == [9, 0, 0, 0, 36, 4]
+    assert O.edge_counts_ratio(offs, 0.36).tolist() == [6, 0, 0, 0, 25, 2]
+    assert O.edge_counts_ratio(offs, 1.0).tolist() == [18, 0, 0, 1, 72, 8]
+    assert O.edge_counts_ratio(np.array([0, 2, 5], dtype=np.int32), 40.0).tolist() == [1, 2]
+    assert O.edge_counts_ratio(offs, 0.0).tolist() == [0] * 6
