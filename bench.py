@@ -2,14 +2,23 @@
 """Benchmark of the LightKV compression step on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch of synthetic input: every stage of the
-workload's hierarchical schedule, each stage = window partition -> scores (FD + xi) -> selection ->
-message passing + compaction.  All inputs are resident in HBM before the timed region.
+workload's hierarchical schedule, each stage = window partition -> per-window counts -> scores (FD + xi)
+-> selection -> message passing + compaction.  All inputs are resident in HBM before the timed region.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 3] [--mode graph|eager]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 3] [--mode graph|eager] [--pass all|...]
 
 Prints ONE JSON line: metric "vision tokens compressed/sec per layer" (tokens entering the compression
-stages of one step / time of the step), the roofline of the dominant kernel and the CPU oracle timed
-on the host cores.
+stages of one step / time of the step), the roofline of the dominant kernel (message passing +
+compaction, HBM bound, quoted with caches flushed in front of every launch), the same kernel as it runs
+inside the step and on the batched workload, the two dense contractions (bipartite and full pairwise
+feature divergence of the 2880-token window) against the bf16 matrix-core peak, and the CPU oracle
+timed on the host cores.
+
+Passes (--pass): "all" (default) runs everything; "step", "cold", "hbm_primary", "similarity", "pairwise"
+run the set-up and that measurement alone, so that a kernel trace of the command holds the launches of
+one regime (the summaries under profiles/ are made that way).  Two maintenance modes need no workload:
+--calibrate-counters (plain device copies of known size, to scale FETCH_SIZE / WRITE_SIZE) and
+--summarize DB [COMMAND] (a rocprofv3 kernel-trace database as the short text kept under profiles/).
 """
 from __future__ import annotations
 
@@ -23,8 +32,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+PASSES = ("all", "step", "cold", "hbm_primary", "similarity", "pairwise")
 
 
 def _parse():
@@ -34,18 +44,18 @@ def _parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="3", help="1..5, halving, global (default 3: the N=2880 LLaVA-NeXT-shaped layer)")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"])
-    ap.add_argument("--match", default="best_per_a", choices=["best_per_a", "edge_topk"],
-                    help="edge_topk: Step 2 read literally, floor(rho v / 2) lowest-FD edges per window (token counts "
-                         "depend on the data: eager, two small read-backs per stage)")
-    ap.add_argument("--rho", type=float, default=0.36, help="edge_topk: ratio rho of Step 2 (0.36: as many edges per "
-                    "window as the default schedule of config 3 removes tokens)")
+    ap.add_argument("--pass", dest="only", default="all", choices=PASSES,
+                    help="run one measurement only (after the set-up it needs); default: all of them")
+    ap.add_argument("--match", default="best_per_a", choices=["best_per_a", "edge_topk", "full_pairwise"],
+                    help="edge_topk: Step 2 read literally, floor(rho v / 2) lowest-FD edges per window; full_pairwise: "
+                         "the appendix ablation, at most floor(rho v) tokens leave a window (token counts depend on the "
+                         "data in both: eager, small read-backs per stage)")
+    ap.add_argument("--rho", type=float, default=None, help="edge_topk / full_pairwise: the ratio rho (defaults 0.36 / 0.18: "
+                    "about the tokens per stage the default schedule of config 3 removes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-repeats", type=int, default=20, help="oracle steps timed for cpu_baseline (about 10 s)")
-    ap.add_argument("--cold", action="store_true",
-                    help="also time the dominant kernel with L2 and Infinity Cache flushed before every launch "
-                         "(extra object roofline_cold; the headline figures are unchanged).  Not part of the default "
-                         "run, so that a kernel trace of the default command holds the launches of the step only")
-    ap.add_argument("--no-cold", dest="cold", action="store_false", help="(the default)")
+    ap.add_argument("--cpu-repeats", type=int, default=4, help="oracle steps timed per cpu_baseline leg")
+    ap.add_argument("--calibrate-counters", action="store_true")
+    ap.add_argument("--summarize", nargs="+", metavar=("DB", "COMMAND"))
     return ap.parse_args()
 
 
@@ -61,20 +71,203 @@ def rows_bytes(wl, n_in, n_out):
 
 def measured_traffic(workload_name):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE and
-    WRITE_SIZE, scaled by a copy-kernel calibration); None where no such summary exists for the workload."""
+    WRITE_SIZE, scaled by a copy-kernel calibration); None where no such summary exists for the workload.  The
+    figure is read from the file: this run does not measure it."""
     path = os.path.join(ROOT, "profiles", "rows_kernel_hbm_traffic_%s.txt" % {"llava_next": "llava_next_n2880"}.get(workload_name, workload_name))
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
-                return int(line.split("=")[1])
+                return int(line.split("=")[1]), os.path.relpath(path, ROOT)
     except OSError:
         pass
-    return None
+    return None, None
 
 
-def bench_edge_topk(args):
-    """The schedule with the k lowest edges per window: stages whose windows fit the variant's limit, eager, host
-    read-backs included in the timed region (they are part of the step: the next stage cannot be sized without them)."""
+def summarize(db_path: str, command: str) -> str:
+    """rocprofv3 --kernel-trace database -> per-kernel text summary."""
+    import sqlite3
+    con = sqlite3.connect(db_path)
+    rows = list(con.execute(
+        "select name, count(*), avg(end-start), min(end-start), max(end-start), sum(end-start) "
+        "from kernels group by name order by 6 desc"))
+    total = sum(r[5] for r in rows) or 1
+    lines = ["command: " + command, "source : rocprofv3 --kernel-trace (rocpd database), durations in microseconds", "",
+             "%-78s %7s %10s %10s %10s %7s" % ("kernel", "calls", "avg_us", "min_us", "max_us", "share")]
+    for name, n, avg, mn, mx, tot in rows:
+        lines.append("%-78s %7d %10.2f %10.2f %10.2f %6.1f%%" % (name[:78], n, avg / 1e3, mn / 1e3, mx / 1e3, 100.0 * tot / total))
+    return "\n".join(lines) + "\n"
+
+
+def calibrate_counters():
+    """Plain device-to-device copies of known size (64 MiB and 512 MiB, four each).  Run under
+    `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: what those counters report for a kernel whose HBM traffic is
+    known (reads N bytes, writes N bytes) scales the counters of the LightKV kernels."""
+    import torch
+    for mib in (64, 512):
+        a = torch.empty(mib * 1024 * 1024 // 2, dtype=torch.bfloat16, device="cuda").normal_()
+        b = torch.empty_like(a)
+        for _ in range(4):
+            b.copy_(a)
+        torch.cuda.synchronize()
+    print(json.dumps({"calibration": "copies of 64 MiB and 512 MiB, four each"}))
+
+
+class _Timer:
+    """HIP events on the launch stream; the interval of an empty event pair is measured the same way and removed."""
+
+    def __init__(self, stream):
+        import torch
+        self.torch, self.stream = torch, stream
+        nulls = []
+        for _ in range(20):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda._sleep(200_000)
+            a.record(stream); b.record(stream)
+            stream.synchronize()
+            nulls.append(a.elapsed_time(b) * 1e3)
+        self.null_us = sorted(nulls)[len(nulls) // 2]
+
+    def pair(self):
+        return self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+
+    def us(self, a, b):
+        return max(a.elapsed_time(b) * 1e3 - self.null_us, 0.0)
+
+
+def _pipeline(wl, dev):
+    import torch
+    from paper_2605_00789_amd import CompressionPipeline, to_device as to_dev
+    pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                               tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                               windows_per_axis=wl.windows_per_axis, targets=wl.targets, fused=True)
+    X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+    pos = torch.from_numpy(wl.pos).to(dev)
+    return pipe, (X, K, V, Q, pos)
+
+
+def rows_cold_pass(wl, pipe, tensors, stream, timer, n_inst):
+    """The merge kernel of every stage with L2 and Infinity Cache holding none of its inputs: a 1 GiB buffer is READ in
+    front of every launch (clean lines: a flush by writing would leave the caches full of dirty lines whose write-back
+    then competes with the kernel).  Stage inputs and index structures are those a run of the schedule left behind.
+    Returns microseconds per stage (mean over n_inst launches)."""
+    import torch
+    from paper_2605_00789_amd import binding as B
+    X, K, V, Q, pos = tensors
+    dev = X.device
+    flush = torch.zeros(1 << 27, dtype=torch.int64, device=dev)
+    sink = torch.zeros((), dtype=torch.int64, device=dev)
+    per_stage = [0.0] * wl.stages
+    with torch.cuda.stream(stream):
+        pipe.run(X, K, V, Q, pos)
+        stream.synchronize()
+        for _ in range(n_inst):
+            Xi, Ki, Vi, pi = X, K, V, pos
+            evs = []
+            for s in range(wl.stages):
+                st = pipe.stages[s]
+                torch.sum(flush, dim=(0,), out=sink)
+                a, b = timer.pair()
+                a.record(stream)
+                B.lightkv_aggregate_compact(st.problem, st.new_index, st.grp_offsets, st.grp_src, st.xi, Xi, Ki, Vi, pi,
+                                            st.X_out, st.K_out, st.V_out, st.pos_out)
+                b.record(stream)
+                evs.append((a, b))
+                Xi, Ki, Vi, pi = st.X_out, st.K_out, st.V_out, st.pos_out
+            stream.synchronize()
+            for s, (a, b) in enumerate(evs):
+                per_stage[s] += timer.us(a, b) / n_inst
+    del flush, sink
+    return per_stage
+
+
+def _rows_roofline(wl, per_stage_us, n_ins, regime):
+    rows_b = [rows_bytes(wl, n_ins[s], wl.targets[s]) for s in range(wl.stages)]
+    tot_us, tot_b = sum(per_stage_us), sum(rows_b)
+    ach = tot_b / (tot_us * 1e-6) / 1e9 if tot_us > 0 else 0.0
+    return {"kernel": "rows_kernel (lightkv_aggregate_compact)", "bound": "hbm", "regime": regime,
+            "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+            "launches_per_step": wl.stages, "avg_launch_us": round(tot_us / wl.stages, 2),
+            "launch_us_per_stage": [round(u, 2) for u in per_stage_us],
+            "algorithmic_bytes_per_launch": int(tot_b / wl.stages), "workload": wl.name}
+
+
+def similarity_pass(stream, timer, n_inst, full_pairwise):
+    """The dense contraction on the 2880-token window of config 3's tensors: the FD half of lightkv_score, bipartite
+    (1440 x 1440 x 4096) or full pairwise (2880 x 2880 x 4096), i.e. squared norms + tiled MFMA kernel + key unpacking in
+    one call.  The profiles under profiles/ isolate the MFMA kernel."""
+    import torch
+    from workloads import make_workload
+    from paper_2605_00789_amd import binding as B
+    from paper_2605_00789_amd import to_device as to_dev
+    wl = make_workload("global")
+    dev = torch.device("cuda:0")
+    n = wl.n_per_seq
+    h_cu = wl.cu_vis.astype("int32")
+    cu = torch.from_numpy(h_cu).to(dev)
+    X = to_dev(wl.X, wl.dtype)
+    pos = torch.from_numpy(wl.pos).to(dev)
+    wo = torch.empty(2, dtype=torch.int32, device=dev)
+    wt = torch.empty(n, dtype=torch.int32, device=dev)
+    rem = torch.zeros(1, dtype=torch.int32, device=dev)
+    prob = B.Problem(batch=1, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, dtype=wl.dtype, h_cu_vis=h_cu, cu_vis=cu,
+                     n_windows=1, max_window_tokens=n, win_offsets=wo, win_tokens=wt, win_remove=rem,
+                     match=B.MATCH_FULL_PAIRWISE if full_pairwise else B.MATCH_BEST_PER_A)
+    ws = torch.empty(B.lightkv_workspace_size(prob), dtype=torch.uint8, device=dev)
+    xi = torch.ones(n, dtype=torch.float32, device=dev)
+    best_fd = torch.empty(n, dtype=torch.float32, device=dev)
+    best_dst = torch.empty(n, dtype=torch.int32, device=dev)
+    us = 0.0
+    with torch.cuda.stream(stream):
+        B.lightkv_build_windows(1, h_cu, cu, pos, wl.tiles, wl.grid_h, wl.grid_w, 0, wo, wt)
+        for _ in range(3):
+            B.lightkv_score(prob, X, None, None, xi, best_fd, best_dst, ws, xi_mode=B.XI_GIVEN)
+        stream.synchronize()
+        for _ in range(n_inst):
+            torch.cuda._sleep(1_000_000)
+            a, b = timer.pair()
+            a.record(stream)
+            B.lightkv_score(prob, X, None, None, xi, best_fd, best_dst, ws, xi_mode=B.XI_GIVEN)
+            b.record(stream)
+            stream.synchronize()
+            us += timer.us(a, b) / n_inst
+    flops = 2.0 * n * n * wl.d if full_pairwise else 2.0 * ((n + 1) // 2) * (n // 2) * wl.d
+    tf = flops / (us * 1e-6) / 1e12
+    return {"call": "lightkv_score, FD half, " + ("full pairwise: row_norms + fd_pair + finalize, 2880 x 2880 x 4096"
+                                                   if full_pairwise else "bipartite: row_norms + fd_big + finalize, 1440 x 1440 x 4096"),
+            "bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "flops_per_call": int(flops), "avg_call_us": round(us, 2),
+            "workload": wl.name}
+
+
+def cpu_baseline(run_once, tokens_per_step, repeats, sample):
+    """The oracle as it stands on the host cores: all threads the BLAS behind numpy takes, and one thread."""
+    out = {}
+    try:
+        from threadpoolctl import threadpool_info, threadpool_limits
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:   # noqa: BLE001
+        threadpool_limits, cores = None, os.cpu_count() or 1
+    t0 = time.perf_counter()
+    for _ in range(repeats):
+        run_once()
+    dt = (time.perf_counter() - t0) / repeats
+    out["cpu_baseline"] = {"value": round(tokens_per_step / dt, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+                           "sample": "%d %s, numpy fp64, %.2f s each" % (repeats, sample, dt)}
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            for _ in range(repeats):
+                run_once()
+            dt1 = (time.perf_counter() - t0) / repeats
+        out["cpu_baseline_1thread"] = {"value": round(tokens_per_step / dt1, 1), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                       "sample": "%d %s, numpy fp64, %.2f s each" % (repeats, sample, dt1)}
+    return out
+
+
+def bench_variant(args):
+    """The schedules whose token counts depend on the data (the k lowest edges per window; full pairwise matching):
+    eager, host read-backs included in the timed region (they are part of the step: the next stage cannot be sized
+    without them)."""
     import numpy as np
     import torch
     from workloads import make_workload
@@ -84,11 +277,14 @@ def bench_edge_topk(args):
     wl = make_workload(cfg)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    ws_axis = [w for w in wl.windows_per_axis
-               if w > 0 and max_window_cells(wl.tiles, wl.grid_h, wl.grid_w, w) <= B.EDGE_MAX_WINDOW_TOKENS]
+    pairwise = args.match == "full_pairwise"
+    rho = args.rho if args.rho is not None else (0.18 if pairwise else 0.36)
+    ws_axis = list(wl.windows_per_axis) if pairwise else [
+        w for w in wl.windows_per_axis
+        if w > 0 and max_window_cells(wl.tiles, wl.grid_h, wl.grid_w, w) <= B.EDGE_MAX_WINDOW_TOKENS]
     sched = EdgeTopKSchedule(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, tiles=wl.tiles,
                              grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt, windows_per_axis=ws_axis,
-                             rho=[args.rho] * len(ws_axis))
+                             rho=[rho] * len(ws_axis), match=args.match)
     X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
     pos = torch.from_numpy(wl.pos).to(dev)
     for _ in range(max(args.warmup, 1)):
@@ -99,7 +295,6 @@ def bench_edge_topk(args):
         res = sched.run(wl.cu_vis, X, K, V, Q, pos)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    # per-call GPU time from events around the calls (a pass of its own)
     acc = {}
     n_inst = max(5, min(args.steps, 30))
     for _ in range(n_inst):
@@ -122,278 +317,209 @@ def bench_edge_topk(args):
         "metric": "vision tokens compressed/sec per layer", "value": round(sum(n_in) / (ms_per_step * 1e-3), 1),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": wl.name, "match": "edge_topk", "rho": args.rho, "batch": wl.batch, "stages": len(ws_axis),
+        "config": {"workload": wl.name, "match": args.match, "rho": rho, "batch": wl.batch, "stages": len(ws_axis),
                    "windows_per_axis": ws_axis, "tokens_in_per_stage": n_in, "tokens_out_per_stage": n_out,
-                   "edges_per_stage": [int(r.h_win_edges.sum()) for r in res], "launch": "eager + 2 read-backs per stage"},
-        "roofline": {"kernel": "rows_kernel (lightkv_aggregate_compact)", "bound": "hbm", "achieved": round(ach, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
-                     "launches_per_step": len(ws_axis), "avg_launch_us": round(rows_us / len(ws_axis), 2),
+                   "counts_per_stage": [int(r.h_win_edges.sum()) for r in res], "launch": "eager + read-backs per stage"},
+        "roofline": {"kernel": "rows_kernel (lightkv_aggregate_compact)", "bound": "hbm", "regime": "in the step",
+                     "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                     "traffic": None, "launches_per_step": len(ws_axis), "avg_launch_us": round(rows_us / len(ws_axis), 2),
                      "algorithmic_bytes_per_launch": rows_b // len(ws_axis),
                      "note": "call interval from events around the call (includes launch overhead of an eager call)"},
         "calls_us": calls_us,
     }
     if not args.no_cpu_baseline:
         from oracle import lightkv_oracle as O
-        t0 = time.perf_counter()
-        reps = max(1, args.cpu_repeats // 4)
-        for _ in range(reps):
+
+        def once():
             Xc, Kc, Vc, posc, cu = wl.X, wl.K, wl.V, wl.pos, wl.cu_vis
             Q64 = O.widen(wl.Q, wl.dtype)
             for s, w in enumerate(ws_axis):
                 wo, wt = O.build_windows(posc, cu, wl.tiles, wl.grid_h, wl.grid_w, w)
-                v = np.diff(wo)
-                k = np.minimum(np.floor(args.rho * v / 2.0 + 1e-9).astype(np.int64), ((v + 1) // 2) * (v // 2))
-                r = O.compress_stage_edges(O.widen(Xc, wl.dtype), O.widen(Kc, wl.dtype), O.widen(Vc, wl.dtype), Q64, posc, cu,
-                                           wl.cu_txt, wl.heads, wl.head_dim, wo, wt, k)
+                args_ = (O.widen(Xc, wl.dtype), O.widen(Kc, wl.dtype), O.widen(Vc, wl.dtype), Q64, posc, cu, wl.cu_txt,
+                         wl.heads, wl.head_dim, wo, wt)
+                if pairwise:
+                    r = O.compress_stage_full_pairwise(*args_, O.removal_counts_ratio(wo, rho))
+                else:
+                    r = O.compress_stage_edges(*args_, O.edge_counts_ratio(wo, rho))
                 Xc, Kc, Vc = (O.round_to_storage(t, wl.dtype) for t in (r.X, r.K, r.V))
                 posc, cu = r.pos, r.cu_vis
-        dt = (time.perf_counter() - t0) / reps
-        out["cpu_baseline"] = {"value": round(sum(n_in) / dt, 1), "unit": "tokens/s", "cores": os.cpu_count() or 1,
-                               "kind": "oracle", "sample": "%d full schedules of the same workload, numpy fp64, %.2f s each" % (reps, dt)}
+        out.update(cpu_baseline(once, sum(n_in), max(1, args.cpu_repeats // 2), "full schedules of the same workload"))
     print(json.dumps(out))
 
 
 def main():
     args = _parse()
+    if args.summarize:
+        sys.stdout.write(summarize(args.summarize[0], args.summarize[1] if len(args.summarize) > 1 else ""))
+        return
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the step has no cross-GPU part); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
-    if args.match == "edge_topk":
-        import torch
-        if not torch.cuda.is_available():
-            print("bench.py: no GPU visible", file=sys.stderr)
-            sys.exit(1)
-        return bench_edge_topk(args)
-    import numpy as np
     import torch
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.calibrate_counters:
+        return calibrate_counters()
+    if args.match != "best_per_a":
+        return bench_variant(args)
+    import numpy as np
     from workloads import make_workload
-    from paper_2605_00789_amd import CompressionPipeline, to_device as to_dev
+    from paper_2605_00789_amd import binding as B
 
     cfg = int(args.workload) if args.workload.isdigit() else args.workload
     wl = make_workload(cfg)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
-                               tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
-                               windows_per_axis=wl.windows_per_axis, targets=wl.targets, fused=True)
-    X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
-    pos = torch.from_numpy(wl.pos).to(dev)
+    pipe, tensors = _pipeline(wl, dev)
+    X, K, V, Q, pos = tensors
     n_ins = [wl.n_per_seq] + list(wl.targets[:-1])
     tokens_per_step = wl.batch * sum(n_ins)
+    only = args.only
+    want = lambda name: only in ("all", name)   # noqa: E731
+    main_workload = cfg == 3                    # the extra objects of the default line belong to the default workload
 
     stream = torch.cuda.Stream()
-    graph = None
+    out = {
+        "metric": "vision tokens compressed/sec per layer", "value": None, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": None, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "description": wl.notes, "batch": wl.batch, "stages": wl.stages,
+                   "tokens_in_per_stage": [wl.batch * n for n in n_ins], "windows_per_axis": wl.windows_per_axis,
+                   "launch": args.mode, "pass": only},
+    }
     with torch.cuda.stream(stream):
         for _ in range(max(args.warmup, 1)):
             pipe.run(X, K, V, Q, pos)
         stream.synchronize()
-        if args.mode == "graph":
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=stream):
-                pipe.run(X, K, V, Q, pos)
-            for _ in range(3):
-                graph.replay()
-            stream.synchronize()
-
-        def step():
-            if graph is not None:
-                graph.replay()
-            else:
-                pipe.run(X, K, V, Q, pos)
-
-        # ---- timed region: exactly K steps, synchronised on both sides
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-        # ---- per-call durations with HIP events on the launch stream.  A sleep kernel in front lets the
-        # host enqueue the whole step before the GPU starts it, so event intervals hold GPU time only.
-        # interval of an empty event pair on this stream (event bookkeeping), removed from every call interval
-        nulls = []
-        for _ in range(20):
-            a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda._sleep(200_000)
-            a.record(stream); b2.record(stream)
-            stream.synchronize()
-            nulls.append(a.elapsed_time(b2) * 1e3)
-        null_us = sorted(nulls)[len(nulls) // 2]
-        names = ("build_windows", "score", "select", "aggregate_compact")
+        status = [int(st.status.sum().item()) for st in pipe.stages]
+        if any(status):
+            print("bench.py: a stage's token budget could not be met (status %s)" % status, file=sys.stderr)
+            sys.exit(1)
+        timer = _Timer(stream)
+        out["event_overhead_us"] = round(timer.null_us, 2)
         n_inst = max(5, min(args.steps, 50))
-        acc = {(s, n): 0.0 for s in range(wl.stages) for n in names}
-        from paper_2605_00789_amd import binding as B
-        for it in range(n_inst):
-            evs = []
-            torch.cuda._sleep(2_000_000)
-            Xi, Ki, Vi, pi = X, K, V, pos
-            for s in range(wl.stages):
-                st = pipe.stages[s]
-                p = st.problem
-                e = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
-                e[0].record(stream)
-                B.lightkv_build_windows(pipe.batch, st.h_cu_vis, st.cu_vis, pi, pipe.tiles, pipe.grid_h, pipe.grid_w,
-                                        st.w, st.win_offsets, st.win_tokens)
-                e[1].record(stream)
-                B.lightkv_score(p, Xi, Q, Ki, st.xi, st.best_fd, st.best_dst, pipe.ws)
-                e[2].record(stream)
-                B.lightkv_select(p, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets, st.grp_src,
-                                 st.cu_vis_out, pipe.ws)
-                e[3].record(stream)
-                B.lightkv_aggregate_compact(p, st.new_index, st.grp_offsets, st.grp_src, st.xi, Xi, Ki, Vi, pi,
-                                            st.X_out, st.K_out, st.V_out, st.pos_out)
-                e[4].record(stream)
-                evs.append(e)
-                Xi, Ki, Vi, pi = st.X_out, st.K_out, st.V_out, st.pos_out
-            stream.synchronize()
-            for s, e in enumerate(evs):
-                for k, n in enumerate(names):
-                    acc[(s, n)] += max(e[k].elapsed_time(e[k + 1]) * 1e3 - null_us, 0.0) / n_inst   # microseconds
-    calls_us = {"stage%d.%s" % (s + 1, n): round(acc[(s, n)], 2) for s in range(wl.stages) for n in names}
 
-    cold_us = None
-    if args.cold:
-        # every launch starts from caches that hold none of its inputs: a 1 GiB buffer is READ in front of it (clean
-        # lines: a flush by writing would leave the caches full of dirty lines whose write-back then competes with the
-        # kernel).  Stage inputs and index structures are the ones the eager pass above left behind.
-        flush = torch.zeros(1 << 27, dtype=torch.int64, device=dev)
-        sink = torch.zeros((), dtype=torch.int64, device=dev)
-        cold_us = 0.0
-        with torch.cuda.stream(stream):
-            for it in range(n_inst):
-                Xi, Ki, Vi, pi = X, K, V, pos
+        if want("step"):
+            graph = None
+            if args.mode == "graph":
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=stream):
+                    pipe.run(X, K, V, Q, pos)
+                for _ in range(3):
+                    graph.replay()
+                stream.synchronize()
+            # ---- timed region: exactly K steps, synchronised on both sides
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                if graph is not None:
+                    graph.replay()
+                else:
+                    pipe.run(X, K, V, Q, pos)
+            torch.cuda.synchronize()
+            ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+            out["ms_per_step"] = round(ms_per_step, 5)
+            out["value"] = round(tokens_per_step / (ms_per_step * 1e-3), 1)
+
+            # ---- per-call durations with HIP events on the launch stream.  A sleep kernel in front lets the host enqueue
+            # the whole step before the GPU starts it, so event intervals hold GPU time only.
+            names = ("build_windows", "score", "select", "aggregate_compact")
+            acc = {(s, n): 0.0 for s in range(wl.stages) for n in names}
+            for _ in range(n_inst):
                 evs = []
+                torch.cuda._sleep(2_000_000)
+                Xi, Ki, Vi, pi = X, K, V, pos
                 for s in range(wl.stages):
                     st = pipe.stages[s]
-                    torch.sum(flush, dim=(0,), out=sink)
-                    a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record(stream)
-                    B.lightkv_aggregate_compact(st.problem, st.new_index, st.grp_offsets, st.grp_src, st.xi, Xi, Ki, Vi, pi,
+                    p = st.problem
+                    e = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+                    e[0].record(stream)
+                    B.lightkv_build_windows(pipe.batch, st.h_cu_vis, st.cu_vis, pi, pipe.tiles, pipe.grid_h, pipe.grid_w,
+                                            st.w, st.win_offsets, st.win_tokens)
+                    B.lightkv_window_counts(pipe.batch, p.c.n_windows, st.win_offsets, B.COUNT_TARGET, st.win_remove,
+                                            cu_vis=st.cu_vis, cu_vis_target=st.cu_target, status=st.status)
+                    e[1].record(stream)
+                    B.lightkv_score(p, Xi, Q, Ki, st.xi, st.best_fd, st.best_dst, pipe.ws)
+                    e[2].record(stream)
+                    B.lightkv_select(p, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets, st.grp_src,
+                                     st.cu_vis_out, pipe.ws)
+                    e[3].record(stream)
+                    B.lightkv_aggregate_compact(p, st.new_index, st.grp_offsets, st.grp_src, st.xi, Xi, Ki, Vi, pi,
                                                 st.X_out, st.K_out, st.V_out, st.pos_out)
-                    b2.record(stream)
-                    evs.append((a, b2))
+                    e[4].record(stream)
+                    evs.append(e)
                     Xi, Ki, Vi, pi = st.X_out, st.K_out, st.V_out, st.pos_out
                 stream.synchronize()
-                cold_us += sum(max(a.elapsed_time(b2) * 1e3 - null_us, 0.0) for a, b2 in evs) / n_inst
-        del flush, sink
+                for s, e in enumerate(evs):
+                    for k, n in enumerate(names):
+                        acc[(s, n)] += timer.us(e[k], e[k + 1]) / n_inst
+            out["calls_us"] = {"stage%d.%s" % (s + 1, n): round(acc[(s, n)], 2) for s in range(wl.stages) for n in names}
+            # per call: algorithmic bytes and flops over the event interval of the call
+            #   score             reads X once (feature divergence) and Q, K once (xi): e d (N + T + N) bytes;
+            #                     2 d sum_w |A_w| |B_w| flops for FD (window sizes read back) + 2 d sum_b T_b N_b for xi
+            #   aggregate_compact 3 e d (N + n') bytes
+            eb_ = _elem_bytes(wl.dtype)
+            sum_t = int(wl.cu_txt[-1])
+            t_b = np.diff(np.asarray(wl.cu_txt, dtype=np.int64))
+            calls_roofline = {}
+            for s in range(wl.stages):
+                st = pipe.stages[s]
+                n_s = wl.batch * n_ins[s]
+                v = np.diff(st.win_offsets.cpu().numpy().astype(np.int64))
+                fd_flops = 2.0 * wl.d * float((((v + 1) // 2) * (v // 2)).sum())
+                xi_flops = 2.0 * wl.d * float((t_b * n_ins[s]).sum())
+                sc_bytes = eb_ * wl.d * (2 * n_s + sum_t)
+                sc_us, rw_us = acc[(s, "score")], acc[(s, "aggregate_compact")]
+                rw_bytes = rows_bytes(wl, n_ins[s], wl.targets[s])
+                st_us = sum(acc[(s, n)] for n in names)
+                calls_roofline["stage%d" % (s + 1)] = {
+                    "tokens_in": n_s,
+                    "tokens_per_s_eager": round(n_s / (st_us * 1e-6), 1) if st_us > 0 else None,
+                    "score": {"bytes": int(sc_bytes), "GBps": round(sc_bytes / (sc_us * 1e-6) / 1e9, 1) if sc_us > 0 else None,
+                              "fd_flops": int(fd_flops), "xi_flops": int(xi_flops),
+                              "TFLOPs": round((fd_flops + xi_flops) / (sc_us * 1e-6) / 1e12, 2) if sc_us > 0 else None,
+                              "mfma_frac": round((fd_flops + xi_flops) / (sc_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5) if sc_us > 0 else None},
+                    "select": {"us": round(acc[(s, "select")], 2), "share_of_stage": round(acc[(s, "select")] / st_us, 3) if st_us > 0 else None},
+                    "aggregate_compact": {"bytes": int(rw_bytes), "GBps": round(rw_bytes / (rw_us * 1e-6) / 1e9, 1) if rw_us > 0 else None,
+                                          "hbm_frac": round(rw_bytes / (rw_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if rw_us > 0 else None}}
+            out["calls_roofline"] = calls_roofline
+            warm = _rows_roofline(wl, [acc[(s, "aggregate_compact")] for s in range(wl.stages)], n_ins,
+                                  "in the step (inputs just read by the score kernels: cache resident where they fit)")
+            out["roofline_warm"] = warm
 
-    # ---- per call: algorithmic bytes and flops over the event interval of the call (eager pass above)
-    #   score             reads X once (feature divergence) and Q, K once (xi): e d (N + T + N) bytes;
-    #                     2 d sum_w |A_w| |B_w| flops for FD (window sizes read back from the device) + 2 d sum_b T_b N_b for xi
-    #   aggregate_compact 3 e d (N + n') bytes
-    eb_ = _elem_bytes(wl.dtype)
-    sum_t = int(wl.cu_txt[-1])
-    t_b = np.diff(np.asarray(wl.cu_txt, dtype=np.int64))
-    calls_roofline = {}
-    for s in range(wl.stages):
-        st = pipe.stages[s]
-        n_s = wl.batch * n_ins[s]
-        v = np.diff(st.win_offsets.cpu().numpy().astype(np.int64))
-        fd_flops = 2.0 * wl.d * float((((v + 1) // 2) * (v // 2)).sum())
-        xi_flops = 2.0 * wl.d * float((t_b * n_ins[s]).sum())
-        sc_bytes = eb_ * wl.d * (2 * n_s + sum_t)
-        sc_us = acc[(s, "score")]
-        rw_bytes = rows_bytes(wl, n_ins[s], wl.targets[s])
-        rw_us = acc[(s, "aggregate_compact")]
-        st_us = sum(acc[(s, n)] for n in names)
-        calls_roofline["stage%d" % (s + 1)] = {
-            "tokens_in": n_s,
-            "tokens_per_s_eager": round(n_s / (st_us * 1e-6), 1) if st_us > 0 else None,
-            "score": {"bytes": int(sc_bytes), "GBps": round(sc_bytes / (sc_us * 1e-6) / 1e9, 1) if sc_us > 0 else None,
-                      "fd_flops": int(fd_flops), "xi_flops": int(xi_flops),
-                      "TFLOPs": round((fd_flops + xi_flops) / (sc_us * 1e-6) / 1e12, 2) if sc_us > 0 else None,
-                      "mfma_frac": round((fd_flops + xi_flops) / (sc_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 5) if sc_us > 0 else None},
-            "select": {"us": round(acc[(s, "select")], 2), "share_of_stage": round(acc[(s, "select")] / st_us, 3) if st_us > 0 else None},
-            "aggregate_compact": {"bytes": int(rw_bytes), "GBps": round(rw_bytes / (rw_us * 1e-6) / 1e9, 1) if rw_us > 0 else None,
-                                  "hbm_frac": round(rw_bytes / (rw_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if rw_us > 0 else None}}
+    # ---- the dominant kernel with caches flushed in front of every launch: the regime the fractions are quoted from
+    if want("cold"):
+        cold = _rows_roofline(wl, rows_cold_pass(wl, pipe, tensors, stream, timer, n_inst), n_ins,
+                              "cold: 1 GiB read in front of every launch")
+        traffic, src = measured_traffic(wl.name)
+        cold["traffic"] = traffic
+        cold["traffic_source"] = ("committed profile %s (not measured by this run)" % src) if src else None
+        out["roofline"] = cold
+    elif "roofline_warm" in out:
+        out["roofline"] = dict(out["roofline_warm"], traffic=None)
 
-    # ---- roofline of the dominant kernel: message passing + compaction (one kernel per stage, HBM bound)
-    rows_us = sum(acc[(s, "aggregate_compact")] for s in range(wl.stages))
-    rows_b = sum(rows_bytes(wl, n_ins[s], wl.targets[s]) for s in range(wl.stages))
-    achieved = rows_b / (rows_us * 1e-6) / 1e9 if rows_us > 0 else 0.0
-    roofline = {"kernel": "rows_kernel (lightkv_aggregate_compact)", "bound": "hbm",
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(wl.name),
-                "launches_per_step": wl.stages,
-                "avg_launch_us": round(rows_us / wl.stages, 2),
-                "algorithmic_bytes_per_launch": int(rows_b / wl.stages)}
+    # ---- the same kernel on the batched workload (does not fit the caches: the primary HBM datapoint)
+    if main_workload and want("hbm_primary"):
+        wl5 = make_workload(5)
+        pipe5, tensors5 = _pipeline(wl5, dev)
+        n_ins5 = [wl5.n_per_seq] + list(wl5.targets[:-1])
+        out["roofline_hbm_primary"] = _rows_roofline(
+            wl5, rows_cold_pass(wl5, pipe5, tensors5, stream, timer, max(5, n_inst // 2)), n_ins5,
+            "cold: 1 GiB read in front of every launch")
+        del pipe5, tensors5, wl5
 
-    # the dense-contraction case: FD half of lightkv_score on single-window stages (row norms + tiled MFMA kernel + key
-    # unpacking in one call; the profile under profiles/ isolates the MFMA kernel)
-    roofline_fd = None
-    if all(w == 0 for w in wl.windows_per_axis) and wl.dtype == "bf16":
-        fd_us = 0.0
-        with torch.cuda.stream(stream):
-            for it in range(n_inst):
-                torch.cuda._sleep(2_000_000)
-                st = pipe.stages[0]
-                a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(stream)
-                B.lightkv_score(st.problem, X, None, None, st.xi, st.best_fd, st.best_dst, pipe.ws, xi_mode=B.XI_GIVEN)
-                b2.record(stream)
-                stream.synchronize()
-                fd_us += max(a.elapsed_time(b2) * 1e3 - null_us, 0.0) / n_inst
-        nA, nB = (wl.n_per_seq + 1) // 2, wl.n_per_seq // 2
-        flops = 2.0 * wl.batch * nA * nB * wl.d
-        tf = flops / (fd_us * 1e-6) / 1e12
-        roofline_fd = {"call": "lightkv_score, FD half (row_norms + fd_big + finalize)", "bound": "mfma",
-                       "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                       "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "flops_per_call": int(flops),
-                       "avg_call_us": round(fd_us, 2)}
+    # ---- the dense contractions of the 2880-token window against the matrix-core peak
+    if (main_workload or cfg == "global") and want("similarity"):
+        out["roofline_similarity"] = similarity_pass(stream, timer, n_inst, full_pairwise=False)
+    if (main_workload or cfg == "global") and want("pairwise"):
+        out["roofline_similarity_full_pairwise"] = similarity_pass(stream, timer, n_inst, full_pairwise=True)
 
-    roofline_cold = None
-    if cold_us:
-        ach = rows_b / (cold_us * 1e-6) / 1e9
-        roofline_cold = {"achieved": round(ach, 1), "frac": round(ach / HBM_PEAK_GBS, 4), "unit": "GB/s",
-                         "avg_launch_us": round(cold_us / wl.stages, 2)}
-    value = tokens_per_step / (ms_per_step * 1e-3)
-    out = {
-        "metric": "vision tokens compressed/sec per layer",
-        "value": round(value, 1),
-        "unit": "tokens/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": wl.dtype,
-        "data": "synthetic",
-        "config": {"workload": wl.name, "description": wl.notes, "batch": wl.batch, "stages": wl.stages,
-                   "tokens_in_per_stage": [wl.batch * n for n in n_ins], "windows_per_axis": wl.windows_per_axis,
-                   "launch": args.mode},
-        "roofline": roofline,
-        "calls_us": calls_us,
-        "calls_roofline": calls_roofline,
-        "event_overhead_us": round(null_us, 2),
-    }
-    if roofline_cold:
-        out["roofline_cold"] = roofline_cold
-    if roofline_fd:
-        out["roofline_similarity"] = roofline_fd
-
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and only == "all":
         from oracle import lightkv_oracle as O
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            cores = os.cpu_count() or 1
-        t0 = time.perf_counter()
-        for _ in range(args.cpu_repeats):
-            O.compress_schedule(wl)
-        dt = (time.perf_counter() - t0) / args.cpu_repeats
-        out["cpu_baseline"] = {"value": round(tokens_per_step / dt, 1), "unit": "tokens/s", "cores": int(cores),
-                               "kind": "oracle",
-                               "sample": "%d full steps of the same workload (all %d stages), numpy fp64, %.2f s each"
-                                         % (args.cpu_repeats, wl.stages, dt)}
+        out.update(cpu_baseline(lambda: O.compress_schedule(wl), tokens_per_step, args.cpu_repeats,
+                                "full steps of the same workload (all %d stages)" % wl.stages))
     print(json.dumps(out))
 
 

@@ -102,7 +102,18 @@ typedef enum {
      full weight -- and leaves if it owns at least one, so the number of tokens that leave is known only on the
      device (cu_vis_out): between ceil(k / |B|) and min(k, |A|) per window.  Supported by lightkv_score_select for
      windows of at most LIGHTKV_EDGE_MAX_WINDOW_TOKENS tokens; see there. */
-  LIGHTKV_MATCH_EDGE_TOPK = 1
+  LIGHTKV_MATCH_EDGE_TOPK = 1,
+  /* full pairwise matching, the appendix ablation ("Bipartite vs. full pairwise matching"): no A/B split, FD between
+     every two tokens of a window (the whole v x v matrix, 4 x the bipartite block), every token offers its lowest-FD
+     neighbour (ties: the neighbour earlier in the window).  The appendix gives no merge rule; this build's reading:
+     the tokens of a window are visited in ascending order of their offer (ties: earlier in the window first), and a
+     visited token is merged into its neighbour unless a token merged earlier was merged INTO it, or its neighbour has
+     itself been merged away; the visit ends after win_remove[w] merges.  So at most win_remove[w] tokens leave a
+     window (fewer if the visit runs out: the count is known on the device, cu_vis_out), no token that leaves is a
+     destination, and best_fd / best_dst hold every token's offer (+inf / -1 for a token alone in its window).
+     lightkv_score computes the offers, lightkv_score_select offers and selection (lightkv_select alone returns
+     LIGHTKV_ERR_UNSUPPORTED); bf16, d a multiple of 64. */
+  LIGHTKV_MATCH_FULL_PAIRWISE = 2
 } lightkv_match;
 
 /* Limits of this build. */
@@ -135,7 +146,8 @@ typedef struct lightkv_problem {
                                  LIGHTKV_ERR_UNSUPPORTED                                          */
   int32_t match;              /* lightkv_match; 0 (a zeroed struct) = one edge per A node.  With
                                  LIGHTKV_MATCH_EDGE_TOPK win_remove[w] counts EDGES (0 <= k_w <= |A_w| |B_w|)
-                                 and h_win_remove is required                                     */
+                                 and h_win_remove is required; with LIGHTKV_MATCH_FULL_PAIRWISE it is
+                                 the most tokens that may leave (0 <= r_w <= ceil(v_w / 2))       */
   int32_t reserved;           /* must be 0                                                       */
   const int32_t *h_cu_vis;    /* HOST [batch+1] vision-token offsets, h_cu_vis[0] = 0            */
   const int32_t *h_cu_txt;    /* HOST [batch+1] prompt-token offsets (may be NULL for XI_GIVEN)  */

@@ -23,6 +23,8 @@ What it computes follows the paper's Sec. 3.2.1 (Steps 1-5), Sec. 3.2.2
                  `message_passing_edges` / `compress_stage_edges`: every A node
                  with at least one selected edge leaves, so the number of tokens
                  that go depends on the data.
+                 Full pairwise matching (the appendix ablation): FD between every two
+                 tokens of a window, `nearest_neighbours` / `select_full_pairwise`.
   xi             Step 3, Eq. (attention-factor): attention between a vision token
                  and the prompt tokens, summed over heads and prompt tokens.
   message pass   Eq. (message-passing): X_B <- (xi_B + M^T xi_A)^-1 (X_B*xi_B + M^T (X_A*xi_A)),
@@ -341,6 +343,59 @@ def select_edge_topk(X: np.ndarray, win_offsets, win_tokens, win_edges: np.ndarr
     return edges
 
 
+def nearest_neighbours(X: np.ndarray, win_offsets, win_tokens, metric: str = "cosine"):
+    """Full pairwise matching (appendix, "Bipartite vs. full pairwise matching"): FD between every two tokens of a
+    window (the whole v x v matrix, diagonal excluded), and for every token its lowest-FD neighbour (ties: the
+    neighbour that comes first in the window).  Returns near_fd[float64, N] (+inf for a token alone in its window)
+    and near_dst[int32, N] (token index, -1 where there is none)."""
+    n = X.shape[0]
+    near_fd = np.full(n, np.inf)
+    near_dst = np.full(n, -1, dtype=np.int32)
+    for wdx in range(len(win_offsets) - 1):
+        toks = np.asarray(win_tokens[win_offsets[wdx]:win_offsets[wdx + 1]])
+        if len(toks) < 2:
+            continue
+        fd = feature_divergence(X[toks], X[toks], metric)
+        np.fill_diagonal(fd, np.inf)
+        j = np.argmin(fd, axis=1)
+        near_fd[toks] = fd[np.arange(len(toks)), j]
+        near_dst[toks] = toks[j]
+    return near_fd, near_dst
+
+
+def select_full_pairwise(near_fd: np.ndarray, near_dst: np.ndarray, win_offsets, win_tokens, win_remove):
+    """Which tokens leave under full pairwise matching.  The appendix gives accuracy and cost of this variant but no
+    merge rule; the reading taken here: the tokens of a window are visited in ascending order of their
+    nearest-neighbour FD (ties: earlier in the window first), and a visited token is merged into its nearest
+    neighbour unless (a) a token merged earlier was merged INTO it (a token that has received others stays), or
+    (b) its nearest neighbour has itself been merged away already; the visit ends after r_w merges.  So a token
+    that leaves is never a destination, every destination stays, and at most r_w tokens leave a window -- fewer if
+    the visit runs out of tokens that may leave.  Returns dst[int32, N] (-1: stays)."""
+    n = near_fd.shape[0]
+    dst = np.full(n, -1, dtype=np.int32)
+    for wdx in range(len(win_offsets) - 1):
+        toks = np.asarray(win_tokens[win_offsets[wdx]:win_offsets[wdx + 1]])
+        r = int(win_remove[wdx])
+        if r == 0 or len(toks) < 2:
+            continue
+        order = sorted(range(len(toks)), key=lambda l: (near_fd[toks[l]], l))
+        received = set()
+        gone = set()
+        done = 0
+        for l in order:
+            if done == r:
+                break
+            t = int(toks[l])
+            b = int(near_dst[t])
+            if b < 0 or t in received or b in gone:
+                continue
+            dst[t] = b
+            gone.add(t)
+            received.add(b)
+            done += 1
+    return dst
+
+
 def kept_index(dst: np.ndarray) -> np.ndarray:
     """new_index[i]: row of token i in the compacted tensors (order preserved), -1 if merged away."""
     keep = dst < 0
@@ -493,6 +548,24 @@ def compress_stage_edges(X, K, V, Q, pos, cu_vis, cu_txt, heads, head_dim, win_o
         cu_out[b + 1] = cu_out[b] + int(keep[int(cu_vis[b]):int(cu_vis[b + 1])].sum())
     return EdgeStageResult(xi, edges, gone, new_index, go, gs, Xo, Ko, Vo,
                            np.asarray(pos)[keep].astype(np.int32), cu_out)
+
+
+def compress_stage_full_pairwise(X, K, V, Q, pos, cu_vis, cu_txt, heads, head_dim, win_offsets, win_tokens,
+                                 win_remove, scale=None, lse=None, xi=None, metric: str = "cosine") -> StageResult:
+    """One whole compression step with full pairwise matching inside every window (appendix ablation)."""
+    if xi is None:
+        xi = xi_text_query(Q, K, cu_vis, cu_txt, heads, head_dim, scale=scale, lse=lse)
+    near_fd, near_dst = nearest_neighbours(X, win_offsets, win_tokens, metric)
+    dst = select_full_pairwise(near_fd, near_dst, win_offsets, win_tokens, win_remove)
+    new_index = kept_index(dst)
+    go, gs = groups_csr(dst)
+    Xo, Ko, Vo = (compact(message_passing(Y, xi, dst), dst) for Y in (X, K, V))
+    keep = dst < 0
+    cu_out = np.zeros_like(np.asarray(cu_vis, dtype=np.int32))
+    for b in range(len(cu_vis) - 1):
+        cu_out[b + 1] = cu_out[b] + int(keep[int(cu_vis[b]):int(cu_vis[b + 1])].sum())
+    return StageResult(xi, near_fd, near_dst, dst, new_index, go, gs, Xo, Ko, Vo,
+                       np.asarray(pos)[keep].astype(np.int32), cu_out)
 
 
 def stage_removals(batch: int, n_in: int, n_out: int, windows_per_seq: int) -> np.ndarray:

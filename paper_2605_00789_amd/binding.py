@@ -136,7 +136,7 @@ def _ld(t: Optional[torch.Tensor]) -> int:
 
 
 METRICS = {"cosine": 0, "euclidean": 1, "l2sq": 2}
-MATCH_BEST_PER_A, MATCH_EDGE_TOPK = 0, 1
+MATCH_BEST_PER_A, MATCH_EDGE_TOPK, MATCH_FULL_PAIRWISE = 0, 1, 2
 EDGE_MAX_WINDOW_TOKENS = 256   # LIGHTKV_EDGE_MAX_WINDOW_TOKENS
 SELECT_STATIC_MAX_TOKENS = 65536   # LIGHTKV_SELECT_STATIC_MAX_TOKENS
 ONE_STREAM_MAX_TOKENS = 1024   # LIGHTKV_ONE_STREAM_MAX_TOKENS

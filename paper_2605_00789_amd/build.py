@@ -10,7 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "liblightkv.so")
-SOURCES = ["lk_api.hip", "lk_windows.hip", "lk_score_fd.hip", "lk_score_fd_big.hip", "lk_fd_dump.hip", "lk_score_xi.hip", "lk_xi_seq.hip", "lk_select.hip", "lk_select_edges.hip", "lk_rows.hip", "lk_fused.hip", "lk_schedule.hip"]
+SOURCES = ["lk_api.hip", "lk_windows.hip", "lk_score_fd.hip", "lk_score_fd_big.hip", "lk_fd_dump.hip", "lk_score_xi.hip", "lk_xi_seq.hip", "lk_select.hip", "lk_select_edges.hip", "lk_select_pair.hip", "lk_rows.hip", "lk_fused.hip", "lk_schedule.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 instruction forms are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -25,7 +25,10 @@ lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool n
   if (p->batch < 1 || p->d < 1 || p->heads < 1 || p->head_dim < 1 || p->n_windows < 0) return LIGHTKV_ERR_SHAPE;
   if (p->dtype != LIGHTKV_F32 && p->dtype != LIGHTKV_BF16) return LIGHTKV_ERR_UNSUPPORTED;
   if (p->metric < LIGHTKV_METRIC_COSINE || p->metric > LIGHTKV_METRIC_L2SQ) return LIGHTKV_ERR_UNSUPPORTED;
-  if (p->match < LIGHTKV_MATCH_BEST_PER_A || p->match > LIGHTKV_MATCH_EDGE_TOPK || p->reserved != 0)
+  if (p->match < LIGHTKV_MATCH_BEST_PER_A || p->match > LIGHTKV_MATCH_FULL_PAIRWISE || p->reserved != 0)
+    return LIGHTKV_ERR_UNSUPPORTED;
+  // full pairwise matching runs on the tiled matrix-core kernel only: bf16 rows of whole 64-element k-steps
+  if (p->match == LIGHTKV_MATCH_FULL_PAIRWISE && (p->dtype != LIGHTKV_BF16 || p->d % 64 != 0))
     return LIGHTKV_ERR_UNSUPPORTED;
   c.elem_bytes = p->dtype == LIGHTKV_BF16 ? 2 : 4;
   if (p->d % (16 / c.elem_bytes) != 0) return LIGHTKV_ERR_UNSUPPORTED;
@@ -99,10 +102,12 @@ struct WsLayout {
 };
 
 bool edge_topk(const lightkv_problem *p) { return p->match == LIGHTKV_MATCH_EDGE_TOPK; }
+bool full_pairwise(const lightkv_problem *p) { return p->match == LIGHTKV_MATCH_FULL_PAIRWISE; }
 // ints of scratch for the edge list (A token, B token, position among the B token's sources)
 size_t edge_ints(const lightkv_problem *p, const Checked &c) { return edge_topk(p) ? (size_t)3 * (size_t)c.sum_remove : 0; }
 
 bool use_big_fd(const lightkv_problem *p, const Checked &c) {
+  if (full_pairwise(p)) return true;   // squared norms and one packed key per position, as on the tiled bipartite path
   if (edge_topk(p)) return false;   // every pair's FD is ranked: the small tiles keep them all, the tiled kernel only row minima
   // the large-window kernel wants whole pairs of 128-element k-steps; other shapes take the small-tile path
   if (p->dtype != LIGHTKV_BF16 || p->d % 256 != 0 || c.max_window < FD_BIG_MIN_WINDOW) return false;
@@ -114,6 +119,7 @@ bool use_big_fd(const lightkv_problem *p, const Checked &c) {
 }
 
 WsLayout ws_layout(const FdPlan &fd, const FdBigPlan &big, bool use_big, const XiPlan &xi, int sum_n, size_t n_edge_ints) {
+  // (full pairwise matching needs at most what the tiled bipartite path lays out: norms and one key plane or more)
   WsLayout l;
   size_t off = 0;
   l.fd_partial = off; off = align_up(off + (use_big ? 0 : fd.partial_floats * sizeof(float)));
@@ -149,7 +155,7 @@ lightkv_status select_impl(const lightkv_problem *p, bool from_keys, float *best
   const bool have_txt = p->h_cu_txt && p->cu_txt;
   const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, have_txt ? p->h_cu_txt : nullptr, p->heads, 0);
   const FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
-  if (edge_topk(p)) return LIGHTKV_ERR_UNSUPPORTED;   // needs every pair's FD: lightkv_score_select only
+  if (edge_topk(p) || full_pairwise(p)) return LIGHTKV_ERR_UNSUPPORTED;   // scores of another kind: lightkv_score_select only
   const WsLayout l = ws_layout(fd, big, use_big_fd(p, c), xp, c.sum_n, 0);
   // only the selection scratch (and the keys) are used here; accept a workspace that covers the layout
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) != 0 || ws_bytes < l.total) return LIGHTKV_ERR_WORKSPACE;
@@ -298,7 +304,9 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
   if (fd_dump) {
     if (!need_fd) return LIGHTKV_ERR_NULL;
     if (fd_dump_floats < 0) return LIGHTKV_ERR_SHAPE;
-    if ((reinterpret_cast<uintptr_t>(fd_dump) & 3) || p->n_windows > 65535) return LIGHTKV_ERR_UNSUPPORTED;
+    // (the dump holds the bipartite |A| x |B| blocks: not defined for full pairwise matching)
+    if ((reinterpret_cast<uintptr_t>(fd_dump) & 3) || p->n_windows > 65535 || p->match == LIGHTKV_MATCH_FULL_PAIRWISE)
+      return LIGHTKV_ERR_UNSUPPORTED;
   }
   if (need_xi) {
     if (!Q || !K) return LIGHTKV_ERR_NULL;
@@ -327,6 +335,8 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
   fd.metric = big.metric = p->metric;
   const bool use_big = use_big_fd(p, c);
   const bool edge = sel && need_fd && edge_topk(p);
+  const bool pairwise = need_fd && full_pairwise(p);
+  if (pairwise && (uint64_t)c.sum_n * (uint64_t)ldx * 2u >= (1ull << 32)) return LIGHTKV_ERR_UNSUPPORTED;   // 32-bit row offsets
   const WsLayout l = ws_layout(fd, big, use_big, xp, c.sum_n, need_fd ? edge_ints(p, c) : 0);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) % ALIGN) != 0 || ws_bytes < l.total) return LIGHTKV_ERR_WORKSPACE;
   char *wsb = static_cast<char *>(ws);
@@ -337,8 +347,9 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
   // running a step of the xi chain next to a step of the FD chain (no helper stream, no fork/join).  Larger steps fill
   // the chip with either chain alone; there the shared launches take as long as the two in a row and the helper
   // stream is the better arrangement (measured: 2880 tokens 248 vs 237 us per three stages, 576 tokens 190 vs 199).
-  if (need_xi && need_fd && sel && !edge && fd.n_tiles > 0 && c.sum_n > 0 && c.sum_n <= LIGHTKV_ONE_STREAM_MAX_TOKENS &&
-      p->n_windows > 0) {
+  // (only layouts of the small-tile path hold the partial tiles these launches write: never with use_big)
+  if (need_xi && need_fd && sel && !edge && !pairwise && !use_big && fd.n_tiles > 0 && c.sum_n > 0 &&
+      c.sum_n <= LIGHTKV_ONE_STREAM_MAX_TOKENS && p->n_windows > 0) {
     const float scale = softmax_scale != 0.f ? softmax_scale : 1.0f / sqrtf((float)p->head_dim);
     int32_t *cnt = reinterpret_cast<int32_t *>(wsb + l.sel_cnt), *rank = reinterpret_cast<int32_t *>(wsb + l.sel_rank);
     const hipError_t e = launch_score_select_fused(
@@ -372,6 +383,21 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
   lightkv_status fd_status = LIGHTKV_OK;
   if (!need_fd) {
     // xi only
+  } else if (pairwise) {
+    // every two tokens of a window: nearest neighbour per token on the matrix cores, the visit in rank order, index scan
+    int32_t *cnt = reinterpret_cast<int32_t *>(wsb + l.sel_cnt), *rank = reinterpret_cast<int32_t *>(wsb + l.sel_rank);
+    unsigned long long *keys = reinterpret_cast<unsigned long long *>(wsb + l.fd_keys);
+    if (!sel) {   // scores only: every token's nearest neighbour
+      if (launch_fd_pair(X, ldx, p->d, p->n_windows, c.max_window, c.sum_n, p->metric, p->win_offsets, p->win_tokens,
+                         x_sqnorm, reinterpret_cast<float *>(wsb + l.fd_norm), keys, best_fd, best_dst, s) != hipSuccess)
+        fd_status = LIGHTKV_ERR_LAUNCH;
+    } else if (launch_fd_pair(X, ldx, p->d, p->n_windows, c.max_window, c.sum_n, p->metric, p->win_offsets, p->win_tokens,
+                       x_sqnorm, reinterpret_cast<float *>(wsb + l.fd_norm), keys, nullptr, nullptr, s) != hipSuccess ||
+        launch_pair_select(p->n_windows, c.max_window, c.sum_n, p->win_offsets, p->win_tokens, p->win_remove, keys,
+                           best_fd, best_dst, sel->dst, cnt, rank, s) != hipSuccess ||
+        launch_select_scan(p->batch, c.sum_n, p->cu_vis, sel->dst, sel->new_index, sel->grp_offsets, sel->grp_src,
+                           sel->cu_vis_out, cnt, rank, s) != hipSuccess)
+      fd_status = LIGHTKV_ERR_LAUNCH;
   } else if (edge) {
     // the k lowest edges of every window: partial tiles, ranking per window, index scan, group lists from the edge list
     int32_t *cnt = reinterpret_cast<int32_t *>(wsb + l.sel_cnt), *rank = reinterpret_cast<int32_t *>(wsb + l.sel_rank);
@@ -436,7 +462,7 @@ lightkv_status lightkv_score_select(const lightkv_problem *p, const void *X, int
   if (st != LIGHTKV_OK) return st;
   if (!p->win_remove) return LIGHTKV_ERR_NULL;
   const FdPlan small = make_fd_small_fused_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
-  if ((small.n_tiles > 0 && !use_big_fd(p, c)) || p->n_windows == 0 || edge_topk(p)) {
+  if ((small.n_tiles > 0 && !use_big_fd(p, c)) || p->n_windows == 0 || edge_topk(p) || full_pairwise(p)) {
     const SelectOut sel{dst, new_index, grp_offsets, grp_src, cu_vis_out};
     return score_impl(p, X, ldx, x_sqnorm, Q, q_tok_stride, q_head_stride, K, k_tok_stride, k_head_stride, xi_mode, lse,
                       softmax_scale, xi, best_fd, best_dst, &sel, false, nullptr, 0, ws, ws_bytes, stream);

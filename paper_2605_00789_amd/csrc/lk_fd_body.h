@@ -33,10 +33,11 @@ __device__ __forceinline__ double divergence(int metric, double dot, double a2, 
     double den;
     if (a2 >= NORM_EPS * NORM_EPS && b2 >= NORM_EPS * NORM_EPS) den = sqrt(a2 * b2);
     else den = fmax(sqrt(a2), NORM_EPS) * fmax(sqrt(b2), NORM_EPS);
-    return fmax(1.0 - dot / den, 0.0);
+    const double fd = 1.0 - dot / den;
+    return fd < 0.0 ? 0.0 : fd;   // (a NaN stays a NaN: fmax would turn it into the best possible score)
   }
-  const double d2 = fmax(a2 + b2 - 2.0 * dot, 0.0);
-  return metric == 1 ? sqrt(d2) : d2;
+  const double d2 = a2 + b2 - 2.0 * dot;
+  return metric == 1 ? sqrt(d2 < 0.0 ? 0.0 : d2) : (d2 < 0.0 ? 0.0 : d2);
 }
 
 constexpr int FD_PARTIAL_LDS = FD_WAVES * (32 * 32 + 2 * 32) * (int)sizeof(float);   // bytes of LDS fd_partial_body needs

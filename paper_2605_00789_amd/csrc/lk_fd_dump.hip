@@ -69,9 +69,11 @@ __global__ __launch_bounds__(256) void fd_dump_kernel(DumpArgs g) {
   }
   double fd;
   if (g.metric == 0) {
-    fd = fmax(1.0 - dot / (fmax(sqrt(sa), 1e-12) * fmax(sqrt(sb), 1e-12)), 0.0);
+    fd = 1.0 - dot / (fmax(sqrt(sa), 1e-12) * fmax(sqrt(sb), 1e-12));
+    fd = fd < 0.0 ? 0.0 : fd;   // (a NaN stays a NaN: fmax would drop it)
   } else {
-    const double d2 = fmax(sa + sb - 2.0 * dot, 0.0);
+    double d2 = sa + sb - 2.0 * dot;
+    d2 = d2 < 0.0 ? 0.0 : d2;
     fd = g.metric == 1 ? sqrt(d2) : d2;
   }
   g.out[idx] = (float)fd;

@@ -87,6 +87,17 @@ hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int 
                          const int32_t *win_offsets, const int32_t *win_tokens, const float *x_sqnorm, float *sq_ws,
                          unsigned long long *keys, float *best_fd, int32_t *best_dst, bool finalize,
                          hipStream_t stream);
+// Full pairwise matching (every two tokens of a window): one packed key per list position in `keys`
+// (FD bits << 32 | position of the nearest neighbour in the window list).  bf16, d a multiple of 64.
+// best_fd / best_dst: written from the keys if not NULL (every token's nearest neighbour).
+hipError_t launch_fd_pair(const void *X, int64_t ldx, int d, int n_windows, int max_window, int sum_n, int metric,
+                          const int32_t *win_offsets, const int32_t *win_tokens, const float *x_sqnorm, float *sq_ws,
+                          unsigned long long *keys, float *best_fd, int32_t *best_dst, hipStream_t stream);
+// ... and the selection on those keys (lk_select_pair.hip): dst, source counts and ranks, best_fd / best_dst
+hipError_t launch_pair_select(int n_windows, int max_window, int sum_n, const int32_t *win_offsets,
+                              const int32_t *win_tokens, const int32_t *win_remove, const unsigned long long *keys,
+                              float *best_fd, int32_t *best_dst, int32_t *dst, int32_t *cnt, int32_t *src_rank,
+                              hipStream_t stream);
 
 // ---- scores + selection in three launches on one stream (lk_fused.hip); windows of at most 64 tokens
 struct XiArgs;

@@ -44,6 +44,7 @@ struct BigArgs {
   int32_t *best_dst;
   int mt, nt;
   int metric;                    // 0: 1 - cos, 1: |a - b|, 2: |a - b|^2
+  int mt2, nt2;                  // fd_pair_kernel: 192 x 192 tiles per window along rows and columns
 };
 
 // ---- |x|^2 per token, summed in fp32 ----------------------------------------------------------------------------
@@ -257,7 +258,7 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
   unsigned long long *row_key = reinterpret_cast<unsigned long long *>(lds + 2 * BIG_TM * 8 + 2 * BIG_TM * 4);   // [96]
   if (tid < 2 * BIG_TM) {
     // the only fp64 sqrt/div of the cosine path: once per tile row and column
-    e_rnorm[tid] = g.metric == 0 ? 1.0 / fmax(sqrt((double)e_sq), 1e-12) : (double)e_sq;
+    e_rnorm[tid] = e_sq != e_sq ? (double)e_sq : (g.metric == 0 ? 1.0 / fmax(sqrt((double)e_sq), 1e-12) : (double)e_sq);   // NaN rows keep a NaN norm
     e_token[tid] = e_tok;
   }
   if (tid < BIG_TM) row_key[tid] = ~0ull;
@@ -310,9 +311,10 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
         const double dot = (double)own[3 * t + k][q];
         float fd;
         if (g.metric == 0) {
-          fd = (float)fmax(1.0 - dot * ra * rb, 0.0);
+          { const double c1 = 1.0 - dot * ra * rb; fd = (float)(c1 < 0.0 ? 0.0 : c1); }   // (a NaN stays a NaN: fmax would drop it)
         } else {   // |a - b|^2 = |a|^2 + |b|^2 - 2 <a, b>
-          const double d2 = fmax(ra + rb - 2.0 * dot, 0.0);
+          double d2 = ra + rb - 2.0 * dot;
+          d2 = d2 < 0.0 ? 0.0 : d2;   // (keeps a NaN)
           fd = (float)(g.metric == 1 ? sqrt(d2) : d2);
         }
         // key = (FD bits, B token): tokens of a window ascend with their local position, so the smaller token is the
@@ -368,6 +370,276 @@ __global__ __launch_bounds__(256) void fd_big_finalize_kernel(BigArgs g, int chu
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------------------------------
+// Full pairwise matching (appendix, "Bipartite vs. full pairwise matching"): FD between every two tokens of a window,
+// the whole v x v matrix (what the appendix FLOPs table counts: 4 x the bipartite block), and for every token its
+// lowest-FD neighbour.  For the 2880-token window that is a 2880 x 2880 x 4096 contraction, 68 GFLOP.
+//
+// What bounds these kernels is operand delivery, not the matrix pipe: every operand byte a workgroup consumes comes
+// out of L2 (nothing is reused through L1), the chip's L2s hand over about 19.5 TB/s in total (measured with the
+// loads of this very loop alone), and a T x T tile needs 2 * 2T bytes per k for 2 T^2 flop per k.  With 96 x 96 tiles
+// the loads alone take longer than the MFMAs; here the output is large enough for 192 x 192 tiles to fill the chip
+// (15 x 15 = 225 workgroups), which halves the bytes per flop.  A workgroup is 2 x 2 waves of 96 x 96 each (a 6 x 6
+// grid of 16 x 16 accumulators per wave, as in fd_big_kernel).  Per k-step of 64: 384 rows x 128 bytes staged (12
+// loads and 12 LDS stores per thread), 24 fragment reads and 72 MFMAs per wave; register ring of two k-steps, two
+// LDS stages, one LDS-only barrier per step, branch-free body.  Epilogue per wave on its own quadrant: FD in fp64
+// from the stored norms, diagonal masked, minimum over the six column blocks per lane, 16-lane reductions by
+// shuffles, one integer atomicMin per row and wave on the row's key (FD bits << 32 | position of the neighbour in
+// the window list): order independent, so bit-reproducible, and equal FDs go to the earlier neighbour.
+constexpr int T2_NB = 6;                          // 16 x 16 blocks per edge of a wave's tile
+constexpr int T2_WT = 16 * T2_NB;                 // 96
+constexpr int T2_TM = 2 * T2_WT;                  // 192: rows and columns of a workgroup tile
+constexpr int T2_BK = 64;                         // elements per k-step
+constexpr int T2_PITCH = T2_BK * 2 + 16;          // 144 bytes per staged row: 16 rows of one k-chunk fall on 16 distinct 16-byte slots
+constexpr int T2_STAGE = 2 * T2_TM * T2_PITCH;    // row panel, then column panel
+constexpr int T2_PASSES = T2_TM / 32;             // 32 rows x 8 chunks of 16 bytes are staged per pass
+
+// (window, tile) of a workgroup.  Workgroups are dealt to the 8 XCDs round robin, each XCD with an L2 of its own.  One
+// window: the tile grid is cut into 2 x 4 blocks, one per XCD, so that an XCD's tiles touch as few distinct row and
+// column panels as possible (what an XCD's L2 has to fetch from the fabric).  Several windows: every XCD takes a
+// contiguous run of (window, tile) jobs, tiles row-major.
+struct T2Job { int w, mt, nt; bool ok; };
+__device__ __forceinline__ T2Job t2_job(const BigArgs &g, int block) {
+  T2Job j{0, 0, 0, false};
+  const int xcd = block & 7, local = block >> 3;
+  if (g.n_windows == 1) {
+    const int bi = xcd >> 2, bj = xcd & 3;
+    const int r0 = bi * g.mt2 / 2, r1 = (bi + 1) * g.mt2 / 2;
+    const int c0 = bj * g.nt2 / 4, c1 = (bj + 1) * g.nt2 / 4;
+    const int wd = c1 - c0;
+    if (wd <= 0 || local >= wd * (r1 - r0)) return j;
+    j.mt = r0 + local / wd;
+    j.nt = c0 + local - (local / wd) * wd;
+    j.ok = true;
+    return j;
+  }
+  const int per = g.mt2 * g.nt2;
+  const int n_jobs = g.n_windows * per;
+  const int per_xcd = (n_jobs + 7) >> 3;
+  const int lid = xcd * per_xcd + local;
+  if (local >= per_xcd || lid >= n_jobs) return j;
+  j.w = lid / per;
+  const int rem = lid - j.w * per;
+  j.mt = rem / g.nt2;
+  j.nt = rem - j.mt * g.nt2;
+  j.ok = true;
+  return j;
+}
+// workgroups to launch so that every job of t2_job has one
+static unsigned t2_grid(int n_windows, int mt2, int nt2) {
+  if (n_windows == 1) {
+    int biggest = 0;
+    for (int x = 0; x < 8; ++x) {
+      const int bi = x >> 2, bj = x & 3;
+      const int h = (bi + 1) * mt2 / 2 - bi * mt2 / 2, wd = (bj + 1) * nt2 / 4 - bj * nt2 / 4;
+      biggest = h * wd > biggest ? h * wd : biggest;
+    }
+    return 8u * (unsigned)biggest;
+  }
+  const unsigned n_jobs = (unsigned)n_windows * (unsigned)(mt2 * nt2);
+  return (n_jobs + 7u) / 8u * 8u;
+}
+
+__global__ __launch_bounds__(BIG_THREADS) void fd_pair_kernel(BigArgs g) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const T2Job job = t2_job(g, blockIdx.x);
+  if (!job.ok) return;
+  const int off = g.win_offsets[job.w];
+  int v = g.win_offsets[job.w + 1] - off;
+  v = v < g.mt2 * T2_TM ? v : g.mt2 * T2_TM;       // a window beyond the caller's bound: its surplus tokens are not scored
+  const int row0 = job.mt * T2_TM, col0 = job.nt * T2_TM;
+  if (v < 2 || row0 >= v || col0 >= v) return;
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int l16 = lane & 15, kg = lane >> 4;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // rows this thread stages: 32 rows per pass, 8 threads per row.  32-bit offsets (checked by the launcher): every
+  // load is "uniform base + per-lane offset", the k position advances on the scalar unit.
+  const int srow = tid >> 3, schunk = tid & 7;
+  uint32_t offa[T2_PASSES], offb[T2_PASSES];
+#pragma unroll
+  for (int p = 0; p < T2_PASSES; ++p) {
+    int la = row0 + p * 32 + srow, lb = col0 + p * 32 + srow;
+    la = la < v ? la : v - 1;                   // padding rows repeat the last valid one; their results are never used
+    lb = lb < v ? lb : v - 1;
+    int ta = g.win_tokens[off + la], tb = g.win_tokens[off + lb];
+    ta = ((unsigned)ta < (unsigned)g.sum_n) ? ta : 0;
+    tb = ((unsigned)tb < (unsigned)g.sum_n) ? tb : 0;
+    offa[p] = (uint32_t)ta * (uint32_t)g.ldx * 2u + (uint32_t)schunk * 16u;
+    offb[p] = (uint32_t)tb * (uint32_t)g.ldx * 2u + (uint32_t)schunk * 16u;
+  }
+  // |x|^2 of the tile rows / columns this thread publishes for the epilogue (384 entries over 256 threads), fetched now
+  // so that the latency hides behind the k loop
+  float e_sq[2];
+  bool e_ok[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int e = tid + u * BIG_THREADS;          // 0..191: rows, 192..383: columns
+    const int l = e < T2_TM ? row0 + e : col0 + e - T2_TM;
+    const int t = g.win_tokens[off + (l < v ? l : v - 1)];
+    e_ok[u] = e < 2 * T2_TM && l < v && (unsigned)t < (unsigned)g.sum_n;
+    e_sq[u] = g.sq[e_ok[u] ? t : 0];
+  }
+
+  f32x4 acc[T2_NB][T2_NB];
+#pragma unroll
+  for (int i = 0; i < T2_NB; ++i)
+#pragma unroll
+    for (int j = 0; j < T2_NB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int n_my = g.d / T2_BK;                   // k-steps (d is a multiple of 64, at least 64: checked by the launcher)
+  const char *xbase = static_cast<const char *>(g.X);
+  uint4 ring[2][2 * T2_PASSES];
+  auto gload = [&](int ks, uint4 *r) {   // unconditional: steps past the end re-read the last one
+    const char *kb = xbase + (size_t)(ks < n_my ? ks : n_my - 1) * (T2_BK * 2);   // scalar
+#pragma unroll
+    for (int p = 0; p < T2_PASSES; ++p) {
+      r[p] = ld16(kb + offa[p]);
+      r[T2_PASSES + p] = ld16(kb + offb[p]);
+    }
+  };
+  char *lds_w = lds + srow * T2_PITCH + schunk * 16;
+  auto lstore = [&](int stage, const uint4 *r) {
+    char *base = lds_w + stage * T2_STAGE;
+#pragma unroll
+    for (int p = 0; p < T2_PASSES; ++p) {
+      *reinterpret_cast<uint4 *>(base + p * 32 * T2_PITCH) = r[p];
+      *reinterpret_cast<uint4 *>(base + T2_TM * T2_PITCH + p * 32 * T2_PITCH) = r[T2_PASSES + p];
+    }
+  };
+  const char *lds_ra = lds + (wm * T2_WT + l16) * T2_PITCH + kg * 16;
+  const char *lds_rb = lds + (T2_TM + wn * T2_WT + l16) * T2_PITCH + kg * 16;
+  // One k-step = two halves of 32 elements.  Per half: 12 fragment reads, then 36 MFMAs with 6 LDS stores (half of the
+  // next step's data, ring slot -> the other stage) and the 6 global loads that refill those ring registers slotted
+  // between them (6 MFMAs, 1 store, 1 load, ...): the matrix pipe runs while the LDS port takes the stores, and
+  // every ring register is on its way again right after its store.
+  auto step = [&](int stage, uint4 *r, int ks_refill) {
+    const char *abase = lds_ra + stage * T2_STAGE;
+    const char *bbase = lds_rb + stage * T2_STAGE;
+    char *wbase = lds_w + (stage ^ 1) * T2_STAGE;
+    const char *kb = xbase + (size_t)(ks_refill < n_my ? ks_refill : n_my - 1) * (T2_BK * 2);   // scalar
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      bf16x8 fa[T2_NB], fb[T2_NB];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < T2_NB; ++i) fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(bbase + i * 16 * T2_PITCH + h * 64));
+#pragma unroll
+      for (int i = 0; i < T2_NB; ++i) fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(abase + i * 16 * T2_PITCH + h * 64));
+#pragma unroll
+      for (int i = 0; i < T2_NB; ++i)
+#pragma unroll
+        for (int j = 0; j < T2_NB; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+      for (int p = h * (T2_PASSES / 2); p < (h + 1) * (T2_PASSES / 2); ++p) {
+        *reinterpret_cast<uint4 *>(wbase + p * 32 * T2_PITCH) = r[p];
+        *reinterpret_cast<uint4 *>(wbase + T2_TM * T2_PITCH + p * 32 * T2_PITCH) = r[T2_PASSES + p];
+      }
+#pragma unroll
+      for (int p = h * (T2_PASSES / 2); p < (h + 1) * (T2_PASSES / 2); ++p) {
+        r[p] = ld16(kb + offa[p]);
+        r[T2_PASSES + p] = ld16(kb + offb[p]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * T2_NB, 0);
+#pragma unroll
+      for (int q = 0; q < T2_PASSES; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, T2_NB * T2_NB / T2_PASSES, 0);
+        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  gload(0, ring[0]);
+  __builtin_amdgcn_sched_barrier(0);
+  gload(1, ring[1]);
+  __builtin_amdgcn_sched_barrier(0);
+  lstore(0, ring[0]);
+  __builtin_amdgcn_sched_barrier(0);
+  gload(2, ring[0]);
+  __builtin_amdgcn_sched_barrier(0);
+  lds_barrier();
+  // (an empty statement that ties every accumulator to the accumulation registers: without it the register allocator
+  // rotates the accumulators through other registers inside the k loop)
+#pragma unroll
+  for (int i = 0; i < T2_NB; ++i)
+#pragma unroll
+    for (int j = 0; j < T2_NB; ++j) asm volatile("" : "+a"(acc[i][j]));
+  // Step ks computes from LDS stage ks & 1 while the data of step ks + 1 moves from its ring slot to the other stage
+  // (after the last step that copy is a harmless repeat).  Steps come in pairs so that stage and ring slot are static.
+  int ks = 0;
+  for (; ks + 1 < n_my; ks += 2) {
+    step(0, ring[1], ks + 3);
+    lds_barrier();
+    step(1, ring[0], ks + 4);
+    lds_barrier();
+  }
+  if (ks < n_my) {   // an odd number of steps: the last one, from stage 0
+    step(0, ring[1], ks + 3);
+    lds_barrier();
+  }
+#pragma unroll
+  for (int i = 0; i < T2_NB; ++i)
+#pragma unroll
+    for (int j = 0; j < T2_NB; ++j) asm volatile("" : "+a"(acc[i][j]));
+
+  // ---- epilogue.  LDS is free now: 1/|x| (or |x|^2 for the distances) of the 192 rows, then of the 192 columns.
+  double *e_rnorm = reinterpret_cast<double *>(lds);
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int e = tid + u * BIG_THREADS;
+    if (e < 2 * T2_TM)   // a negative entry marks a row or column that does not exist (norms are never negative)
+      e_rnorm[e] = !e_ok[u] ? -1.0 : (e_sq[u] != e_sq[u] || g.metric != 0 ? (double)e_sq[u] : 1.0 / fmax(sqrt((double)e_sq[u]), 1e-12));   // NaN rows keep a NaN norm
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < T2_NB; ++i) {
+    unsigned long long kmin[4] = {~0ull, ~0ull, ~0ull, ~0ull};
+#pragma unroll
+    for (int j = 0; j < T2_NB; ++j) {
+      const int cl = wn * T2_WT + j * 16 + l16;
+      const double rb = e_rnorm[T2_TM + cl];
+      const int lb = col0 + cl;                     // position of the column token in the window list
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int rl = wm * T2_WT + i * 16 + kg * 4 + q;
+        const double ra = e_rnorm[rl];
+        const double dot = (double)acc[i][j][q];
+        float fd;
+        if (g.metric == 0) {
+          { const double c1 = 1.0 - dot * ra * rb; fd = (float)(c1 < 0.0 ? 0.0 : c1); }   // (a NaN stays a NaN: fmax would drop it)
+        } else {   // |a - b|^2 = |a|^2 + |b|^2 - 2 <a, b>
+          double d2 = ra + rb - 2.0 * dot;
+          d2 = d2 < 0.0 ? 0.0 : d2;   // (keeps a NaN)
+          fd = (float)(g.metric == 1 ? sqrt(d2) : d2);
+        }
+        unsigned long long key = ((unsigned long long)__float_as_uint(fd) << 32) | (unsigned)lb;
+        key = (ra >= 0.0 && rb >= 0.0 && row0 + rl != lb && fd == fd) ? key : ~0ull;   // no self pairs, NaN never competes
+        kmin[q] = key < kmin[q] ? key : kmin[q];
+      }
+    }
+#pragma unroll
+    for (int m = 8; m >= 1; m >>= 1) {   // the 16 lanes with the same lane / 16 hold the same rows
+      unsigned long long other[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) other[q] = __shfl_xor(kmin[q], m, 64);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) kmin[q] = other[q] < kmin[q] ? other[q] : kmin[q];
+    }
+    if (l16 == 0) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int la = row0 + wm * T2_WT + i * 16 + kg * 4 + q;
+        if (la < v && kmin[q] != ~0ull) atomicMin(&g.cand[(size_t)(off + la)], kmin[q]);
+      }
+    }
+  }
+}
+
 FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n) {
   FdBigPlan p{};
   const int maxA = (max_window_tokens + 1) / 2, maxB = max_window_tokens / 2;
@@ -380,6 +652,20 @@ FdBigPlan make_fd_big_plan(int n_windows, int max_window_tokens, int sum_n) {
   p.nt_store = p.nt <= FD_BIG_KEYS_PER_TILE_MAX_NT ? p.nt : 1;
   p.key_bytes = (size_t)sum_n * 8 * (size_t)p.nt_store;
   return p;
+}
+
+// kernels that ask for more dynamic LDS than the 64 KB default: a property of a kernel as loaded on a device, set once
+// per device (setting it twice is harmless: the flag only has to be free of data races)
+static hipError_t allow_big_lds(int which, const void *kernel, size_t lds) {
+  static std::atomic<bool> attr_set[2][64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!attr_set[which][dev].load(std::memory_order_acquire)) {
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set[which][dev].store(true, std::memory_order_release);
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
@@ -407,21 +693,63 @@ hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int 
   }
   const unsigned n_tiles = (unsigned)(n_windows * plan.mt * plan.nt);
   const unsigned grid = (n_tiles + 7u) / 8u * 8u;   // whole rounds over the XCDs; surplus workgroups exit at once
-  constexpr size_t lds = (size_t)2 * BIG_STAGE;      // 102 KB: above the 64 KB default, the attribute below allows it
-  static std::atomic<bool> attr_set[64];                     // a property of the kernel as loaded on a device, set once per device
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  if (!attr_set[dev].load(std::memory_order_acquire)) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(fd_big_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set[dev].store(true, std::memory_order_release);
-  }
+  constexpr size_t lds = (size_t)2 * BIG_STAGE;      // 102 KB: above the 64 KB default
+  e = allow_big_lds(0, reinterpret_cast<const void *>(fd_big_kernel), lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(fd_big_kernel, dim3(grid), dim3(BIG_THREADS), lds, stream, g);
   e = hipGetLastError();
   if (e != hipSuccess || !finalize) return e;   // without it the caller's selection reads the keys
   const int cpw = (plan.max_window + 255) / 256 > 0 ? (plan.max_window + 255) / 256 : 1;
   hipLaunchKernelGGL(fd_big_finalize_kernel, dim3((unsigned)(n_windows * cpw)), dim3(256), 0, stream, g, cpw);
+  return hipGetLastError();
+}
+
+// Keys of fd_pair_kernel -> best_fd / best_dst (every token's nearest neighbour), for callers of lightkv_score; the
+// selection of lightkv_score_select reads the keys itself.
+__global__ __launch_bounds__(256) void fd_pair_finalize_kernel(BigArgs g, int chunks_per_window) {
+  const int w = blockIdx.x / chunks_per_window, c = blockIdx.x - w * chunks_per_window;
+  const int off = g.win_offsets[w];
+  const int v = g.win_offsets[w + 1] - off;
+  const int scored = v < g.mt2 * T2_TM ? v : g.mt2 * T2_TM;
+  for (int l = c * 256 + (int)threadIdx.x; l < v; l += chunks_per_window * 256) {
+    const int tok = g.win_tokens[off + l];
+    if ((unsigned)tok >= (unsigned)g.sum_n) continue;
+    const unsigned long long key = l < scored ? g.cand[off + l] : ~0ull;
+    const unsigned nb = (unsigned)(key & 0xffffffffu);
+    const int nt = (key != ~0ull && nb < (unsigned)scored) ? g.win_tokens[off + (int)nb] : -1;
+    const bool has = (unsigned)nt < (unsigned)g.sum_n;
+    g.best_fd[tok] = has ? __uint_as_float((unsigned)(key >> 32)) : __uint_as_float(0x7f800000u);
+    g.best_dst[tok] = has ? nt : -1;
+  }
+}
+
+// Full pairwise matching: squared norms (unless handed in) and key reset, then the 192 x 192 tiled kernel.  Leaves one
+// packed key per list position in `keys` (FD bits << 32 | position of the nearest neighbour in the window list; all
+// ones where there is none); the selection reads them.  d must be a multiple of 64.
+hipError_t launch_fd_pair(const void *X, int64_t ldx, int d, int n_windows, int max_window, int sum_n, int metric,
+                          const int32_t *win_offsets, const int32_t *win_tokens, const float *x_sqnorm, float *sq_ws,
+                          unsigned long long *keys, float *best_fd, int32_t *best_dst, hipStream_t stream) {
+  if (n_windows == 0 || sum_n == 0) return hipSuccess;
+  BigArgs g{};
+  g.X = X; g.ldx = ldx; g.d = d; g.n_windows = n_windows; g.sum_n = sum_n;
+  g.win_offsets = win_offsets; g.win_tokens = win_tokens;
+  g.cand = keys; g.metric = metric; g.best_fd = best_fd; g.best_dst = best_dst;
+  g.sq = x_sqnorm ? x_sqnorm : sq_ws; g.sq_out = sq_ws;
+  g.reset_keys = 1;
+  g.mt2 = g.nt2 = (max_window + T2_TM - 1) / T2_TM;
+  hipError_t e;
+  if (!x_sqnorm) hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((sum_n + 3) / 4)), dim3(256), 0, stream, g);
+  else hipLaunchKernelGGL(reset_keys_kernel, dim3((unsigned)((sum_n + 255) / 256)), dim3(256), 0, stream, g);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  constexpr size_t lds = (size_t)2 * T2_STAGE;   // 108 KB
+  e = allow_big_lds(1, reinterpret_cast<const void *>(fd_pair_kernel), lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(fd_pair_kernel, dim3(t2_grid(n_windows, g.mt2, g.nt2)), dim3(BIG_THREADS), lds, stream, g);
+  e = hipGetLastError();
+  if (e != hipSuccess || !best_fd) return e;   // without outputs of its own the caller's selection reads the keys
+  const int cpw = max_window > 256 ? (max_window + 255) / 256 : 1;
+  hipLaunchKernelGGL(fd_pair_finalize_kernel, dim3((unsigned)(n_windows * cpw)), dim3(256), 0, stream, g, cpw);
   return hipGetLastError();
 }
 

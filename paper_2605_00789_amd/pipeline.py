@@ -233,19 +233,26 @@ class EdgeStepResult:
 
 
 class EdgeTopKSchedule:
-    """The hierarchical schedule with the k lowest-FD edges per window (LIGHTKV_MATCH_EDGE_TOPK, k = floor(rho v / 2)
-    as Sec. 3.2.1 counts the pairs).  How many tokens leave depends on the data, so the host reads two small arrays back
-    per stage -- the window sizes (to count k and size the edge list) and the sequence lengths after the step -- and
-    allocates the stage's buffers then; nothing here is captured in a graph."""
+    """The hierarchical schedule for the matchings whose token counts depend on the data:
+      match="edge_topk"      the k lowest-FD edges per window (LIGHTKV_MATCH_EDGE_TOPK, k = floor(rho v / 2) as
+                             Sec. 3.2.1 counts the pairs);
+      match="full_pairwise"  every token against every other token of its window (LIGHTKV_MATCH_FULL_PAIRWISE, the
+                             appendix ablation), at most floor(rho v) tokens leave a window.
+    The host reads small arrays back per stage -- for the edges the counts and window sizes (the edge list is sized from
+    them), and for both the sequence lengths after the step -- and allocates the stage's buffers then; nothing here is
+    captured in a graph."""
 
     def __init__(self, *, dtype: str, batch: int, d: int, heads: int, head_dim: int, tiles: int, grid_h: int,
                  grid_w: int, cu_txt: np.ndarray, windows_per_axis: Sequence[int], rho: Sequence[float],
-                 device="cuda:0", metric: str = "cosine"):
+                 device="cuda:0", metric: str = "cosine", match: str = "edge_topk"):
         self.dtype, self.batch, self.d, self.heads, self.head_dim = dtype, batch, d, heads, head_dim
         self.tiles, self.grid_h, self.grid_w = tiles, grid_h, grid_w
         self.windows_per_axis, self.rho = list(windows_per_axis), list(rho)
         self.device = torch.device(device)
         self.metric = metric
+        if match not in ("edge_topk", "full_pairwise"):
+            raise ValueError(match)
+        self.match = match
         self.h_cu_txt = np.ascontiguousarray(cu_txt, dtype=np.int32)
         self.cu_txt = torch.from_numpy(self.h_cu_txt).to(self.device)
 
@@ -270,33 +277,42 @@ class EdgeTopKSchedule:
         B.lightkv_build_windows(batch, h_cu_vis, cu_vis, pos, self.tiles, self.grid_h, self.grid_w, w, win_offsets,
                                 win_tokens)
         mark("end")
-        if h_win_edges is None:                              # k_w = floor(rho v_w / 2), on the device
+        pairwise = self.match == "full_pairwise"
+        if h_win_edges is None:                              # k_w = floor(rho v_w / 2) (r_w = floor(rho v_w)), on the device
             win_remove = torch.empty(max(n_windows, 1), **i32)
-            B.lightkv_window_counts(batch, n_windows, win_offsets, B.COUNT_EDGES, win_remove, rho=self.rho[s])
-            h_k = win_remove.cpu().numpy()[:n_windows]       # first read-back: the counts ...
+            B.lightkv_window_counts(batch, n_windows, win_offsets, B.COUNT_RATIO if pairwise else B.COUNT_EDGES,
+                                    win_remove, rho=self.rho[s])
+            h_k = None if pairwise else win_remove.cpu().numpy()[:n_windows]   # edges: first read-back, the counts ...
         else:
             h_k = np.ascontiguousarray(h_win_edges, dtype=np.int32)
             win_remove = torch.from_numpy(h_k).to(dev)
-        h_win_offsets = win_offsets.cpu().numpy()            # ... and the window sizes
-        prob = B.Problem(batch=batch, d=self.d, heads=self.heads, head_dim=self.head_dim, dtype=self.dtype,
-                         h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt,
-                         n_windows=n_windows, max_window_tokens=0, win_offsets=win_offsets, win_tokens=win_tokens,
-                         win_remove=win_remove, h_win_offsets=h_win_offsets, h_win_remove=h_k, metric=self.metric,
-                         match=B.MATCH_EDGE_TOPK)
+        if pairwise:                                         # needs no host copy of the windows, only a bound on their size
+            bound = min(max_window_cells(self.tiles, self.grid_h, self.grid_w, w), max(int(np.diff(h_cu_vis).max()), 1))
+            prob = B.Problem(batch=batch, d=self.d, heads=self.heads, head_dim=self.head_dim, dtype=self.dtype,
+                             h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt,
+                             n_windows=n_windows, max_window_tokens=bound, win_offsets=win_offsets, win_tokens=win_tokens,
+                             win_remove=win_remove, metric=self.metric, match=B.MATCH_FULL_PAIRWISE)
+        else:
+            h_win_offsets = win_offsets.cpu().numpy()        # ... and the window sizes
+            prob = B.Problem(batch=batch, d=self.d, heads=self.heads, head_dim=self.head_dim, dtype=self.dtype,
+                             h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt,
+                             n_windows=n_windows, max_window_tokens=0, win_offsets=win_offsets, win_tokens=win_tokens,
+                             win_remove=win_remove, h_win_offsets=h_win_offsets, h_win_remove=h_k, metric=self.metric,
+                             match=B.MATCH_EDGE_TOPK)
         ws = torch.empty(B.lightkv_workspace_size(prob), dtype=torch.uint8, device=dev)
         tdt = X.dtype
         xi = torch.empty(sum_n, dtype=torch.float32, device=dev) if xi_given is None else xi_given
         best_fd = torch.empty(sum_n, dtype=torch.float32, device=dev)
         best_dst, dst, new_index = (torch.empty(sum_n, **i32) for _ in range(3))
         grp_offsets = torch.empty(sum_n + 1, **i32)
-        grp_src = torch.empty(max(int(h_k.sum()), 1), **i32)
+        grp_src = torch.empty(max(sum_n if pairwise else int(h_k.sum()), 1), **i32)
         cu_vis_out = torch.empty(batch + 1, **i32)
         mark("score_select")
         B.lightkv_score_select(prob, X, Q, K, xi, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, ws,
                                xi_mode=B.XI_TEXT_QUERY if xi_given is None else B.XI_GIVEN)
         mark("end")
         # every window that takes an edge loses at least one token: an upper bound on the rows written
-        rows = max(sum_n - int((h_k > 0).sum()), 1)
+        rows = max(sum_n if pairwise else sum_n - int((h_k > 0).sum()), 1)
         X_out, K_out, V_out = (torch.empty(rows, self.d, dtype=tdt, device=dev) for _ in range(3))
         pos_out = torch.empty(rows, **i32)
         mark("aggregate_compact")
@@ -304,6 +320,8 @@ class EdgeTopKSchedule:
         mark("end")
         h_out = cu_vis_out.cpu().numpy()                     # second read-back: the sequence lengths after the step
         n_out = int(h_out[-1])
+        if h_k is None:
+            h_k = win_remove.cpu().numpy()[:n_windows]
         return EdgeStepResult(h_out, X_out[:n_out], K_out[:n_out], V_out[:n_out], pos_out[:n_out], xi, best_fd, best_dst,
                               dst, new_index, grp_offsets, grp_src, win_offsets, win_tokens, h_k)
 

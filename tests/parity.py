@@ -369,3 +369,144 @@ def check_edge_workload(wl, rho, stages=None, metric="cosine"):
         reports.append(rep)
         X, K, V, pos, cu = out["X"], out["K"], out["V"], out["pos"], out["cu_vis"]
     return reports
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Full pairwise matching (appendix ablation, LIGHTKV_MATCH_FULL_PAIRWISE)
+# ---------------------------------------------------------------------------------------------------------------
+@dataclass
+class PairwiseReport:
+    stage: int
+    n_in: int
+    n_out: int
+    tie_rows: int = 0           # tokens whose GPU neighbour differs from the oracle's but ties within the band
+    differs_from_oracle_selection: int = 0   # information: tokens decided differently by the all-fp64 selection
+    max_xi_rel: float = 0.0
+    max_fd_abs: float = 0.0
+    max_row_rel: float = 0.0
+
+
+def check_pairwise_step(sched, s: int, h_cu_vis, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_given=None, h_win_remove=None):
+    """One step of full pairwise matching against the oracle, which gets exactly the tensors the GPU step consumed.
+    Scores: every token's nearest-neighbour FD within the stated FD tolerance, its neighbour the oracle's or one that
+    ties with it within TIE_BAND.  Selection: the visit is sequential, so a near-tie in the scores may legitimately
+    change everything after it; it is therefore checked exactly against the oracle's rule applied to the scores the
+    GPU reported (integer work on given keys), and how far the all-fp64 selection differs is reported as information.
+    Rows: oracle message passing on the GPU's (verified) selection."""
+    batch = sched.batch
+    dX, dK, dV = to_dev(Xs, dtype), to_dev(Ks, dtype), to_dev(Vs, dtype)
+    dQ = to_dev(Qs, dtype)
+    dpos = torch.from_numpy(np.ascontiguousarray(pos, dtype=np.int32)).to(dX.device)
+    dxi = None if xi_given is None else torch.from_numpy(np.ascontiguousarray(xi_given, dtype=np.float32)).to(dX.device)
+    r = sched.run_step(s, h_cu_vis, dX, dK, dV, dQ, dpos, xi_given=dxi, h_win_edges=h_win_remove)
+    torch.cuda.synchronize()
+    g = {k: getattr(r, k).cpu().numpy() for k in ("win_offsets", "win_tokens", "best_fd", "best_dst", "dst", "new_index",
+                                                  "grp_offsets", "grp_src", "pos")}
+    g_xi = r.xi.cpu().numpy()
+    bf16 = dtype == "bf16"
+    metric = sched.metric
+    n = int(h_cu_vis[-1])
+    rep = PairwiseReport(stage=s, n_in=n, n_out=int(r.h_cu_vis_out[-1]))
+
+    wo, wt = O.build_windows(pos, h_cu_vis, sched.tiles, sched.grid_h, sched.grid_w, sched.windows_per_axis[s])
+    np.testing.assert_array_equal(g["win_offsets"], wo, err_msg="win_offsets")
+    np.testing.assert_array_equal(g["win_tokens"][:len(wt)], wt, err_msg="win_tokens")
+    rem = O.removal_counts_ratio(wo, sched.rho[s]) if h_win_remove is None else np.asarray(h_win_remove, dtype=np.int32)
+    np.testing.assert_array_equal(r.h_win_edges, rem, err_msg="win_remove")
+
+    X64, K64, V64 = O.widen(Xs, dtype), O.widen(Ks, dtype), O.widen(Vs, dtype)
+    if xi_given is None:
+        xi_ref = O.xi_text_query(O.widen(Qs, dtype), K64, h_cu_vis, sched.h_cu_txt, sched.heads, sched.head_dim)
+        rel = np.abs(g_xi - xi_ref) / np.maximum(np.abs(xi_ref), 1e-300)
+        rep.max_xi_rel = float(rel.max()) if len(rel) else 0.0
+        assert rep.max_xi_rel <= (1e-3 if bf16 else 1e-5), "xi relative error %.3g" % rep.max_xi_rel
+    else:
+        xi_ref = np.asarray(xi_given, dtype=np.float64)
+
+    # ---- scores
+    for w in range(len(wo) - 1):
+        toks = wt[wo[w]:wo[w + 1]]
+        if len(toks) < 2:
+            assert np.all(g["best_dst"][toks] == -1) and np.all(np.isinf(g["best_fd"][toks]))
+            continue
+        fd = O.feature_divergence(X64[toks], X64[toks], metric)
+        np.fill_diagonal(fd, np.inf)
+        g_fd = g["best_fd"][toks].astype(np.float64)
+        scale = 1.0
+        if metric != "cosine":
+            if metric == "euclidean":
+                fd, g_fd = fd * fd, g_fd * g_fd
+            scale = 2.0 * float((X64[toks] ** 2).sum(axis=1).max())
+        band = TIE_BAND * scale
+        j_ref = np.argmin(fd, axis=1)
+        f_ref = fd[np.arange(len(toks)), j_ref]
+        local = {int(t): k for k, t in enumerate(toks)}
+        b_gpu = g["best_dst"][toks]
+        for l in np.nonzero(b_gpu != toks[j_ref])[0]:
+            assert int(b_gpu[l]) in local and int(b_gpu[l]) != int(toks[l]), "neighbour of token %d is not another token of its window" % toks[l]
+            f_g = fd[l, local[int(b_gpu[l])]]
+            assert f_g <= f_ref[l] + band, "window %d token %d: neighbour FD %.9g vs best %.9g" % (w, toks[l], f_g, f_ref[l])
+            rep.tie_rows += 1
+        rep.max_fd_abs = max(rep.max_fd_abs, float((np.abs(g_fd - f_ref) / scale).max()))
+    assert rep.max_fd_abs <= (1e-5 if bf16 else 1e-6), "nearest-neighbour FD abs error %.3g" % rep.max_fd_abs
+
+    # ---- selection: the oracle's visit on the scores the GPU reported -> exact
+    dst = g["dst"]
+    want = O.select_full_pairwise(g["best_fd"].astype(np.float64), g["best_dst"], wo, wt, rem)
+    np.testing.assert_array_equal(dst, want, err_msg="dst")
+    nf, nd = O.nearest_neighbours(X64, wo, wt, metric)
+    rep.differs_from_oracle_selection = int((O.select_full_pairwise(nf, nd, wo, wt, rem) != dst).sum())
+    gone = dst >= 0
+    assert not gone[dst[gone]].any(), "a destination was merged away"
+    for w in range(len(wo) - 1):
+        toks = wt[wo[w]:wo[w + 1]]
+        assert int(gone[toks].sum()) <= int(rem[w])
+
+    # ---- index structures follow from dst: exact
+    np.testing.assert_array_equal(g["new_index"], O.kept_index(dst), err_msg="new_index")
+    go, gs = O.groups_csr(dst)
+    np.testing.assert_array_equal(g["grp_offsets"][:n + 1], go, err_msg="grp_offsets")
+    np.testing.assert_array_equal(g["grp_src"][:len(gs)], gs, err_msg="grp_src")
+    keep = ~gone
+    cu_out = np.zeros(batch + 1, dtype=np.int32)
+    for b in range(batch):
+        cu_out[b + 1] = cu_out[b] + int(keep[h_cu_vis[b]:h_cu_vis[b + 1]].sum())
+    np.testing.assert_array_equal(r.h_cu_vis_out, cu_out, err_msg="cu_vis_out")
+    n_out = int(keep.sum())
+    np.testing.assert_array_equal(g["pos"], np.asarray(pos)[keep], err_msg="pos_out")
+
+    outs = {}
+    tol = 2e-2 if bf16 else 1e-5
+    for name, Y64, dev_out, src_store in (("X", X64, r.X, Xs), ("K", K64, r.K, Ks), ("V", V64, r.V, Vs)):
+        ref = O.compact(O.message_passing(Y64, xi_ref, dst), dst)
+        got_store = from_dev(dev_out, dtype)
+        got = O.widen(got_store, dtype)
+        assert got.shape[0] == n_out
+        num = np.linalg.norm(got - ref, axis=1)
+        den = np.maximum(np.linalg.norm(ref, axis=1), 1e-300)
+        row_rel = float((num / den).max()) if n_out else 0.0
+        elem_rel = float((np.abs(got - ref).max(axis=1) / np.maximum(np.abs(ref).max(axis=1), 1e-300)).max()) if n_out else 0.0
+        rep.max_row_rel = max(rep.max_row_rel, row_rel)
+        assert row_rel <= tol and elem_rel <= tol, "%s rows: rel %.3g / %.3g" % (name, row_rel, elem_rel)
+        untouched = (go[1:] - go[:-1])[keep] == 0
+        np.testing.assert_array_equal(got_store[untouched], np.asarray(src_store)[keep][untouched], err_msg=name + " copied rows")
+        outs[name] = got_store
+    outs["pos"] = g["pos"].copy()
+    outs["cu_vis"] = cu_out
+    return rep, outs
+
+
+def check_pairwise_workload(wl, rho, stages=None, metric="cosine"):
+    from paper_2605_00789_amd import EdgeTopKSchedule
+    n_st = wl.stages if stages is None else stages
+    sched = EdgeTopKSchedule(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, tiles=wl.tiles,
+                             grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                             windows_per_axis=wl.windows_per_axis[:n_st], rho=list(rho)[:n_st], metric=metric,
+                             match="full_pairwise")
+    X, K, V, pos, cu = wl.X, wl.K, wl.V, wl.pos, wl.cu_vis
+    reports = []
+    for s in range(n_st):
+        rep, out = check_pairwise_step(sched, s, cu, X, K, V, wl.Q, pos, wl.dtype)
+        reports.append(rep)
+        X, K, V, pos, cu = out["X"], out["K"], out["V"], out["pos"], out["cu_vis"]
+    return reports

@@ -72,7 +72,11 @@ def test_workspace_size_and_descriptor_validation(B):
     assert _ws_size(B, _problem(B, metric=2))[0] == 0 and _ws_size(B, _problem(B, metric=3))[0] == 5   # lightkv_metric
     assert _ws_size(B, _problem(B, metric=-1))[0] == 5
     # lightkv_match: the k lowest edges need the host's counts, count pairs instead of A nodes, and bound the window
-    assert _ws_size(B, _problem(B, match=2))[0] == 5 and _ws_size(B, _problem(B, match=-1))[0] == 5
+    assert _ws_size(B, _problem(B, match=3))[0] == 5 and _ws_size(B, _problem(B, match=-1))[0] == 5
+    # full pairwise matching: bf16 rows of whole 64-element k-steps only
+    assert _ws_size(B, _problem(B, match=2))[0] == 0
+    assert _ws_size(B, _problem(B, match=2, dtype=0))[0] == 5
+    assert _ws_size(B, _problem(B, match=2, d=96, heads=3))[0] == 5
     assert _ws_size(B, _problem(B, reserved=1))[0] == 5
     st_e, n_e = _ws_size(B, _problem(B, match=1, h_win_remove=np.array([4, 3], dtype=np.int32)))   # 2 x 2 pairs per window
     assert st_e == 0 and n_e >= _ws_size(B, _problem(B))[1]

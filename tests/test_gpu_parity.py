@@ -1079,3 +1079,108 @@ def test_rows_behind_the_vision_span_are_shifted(fused):
     for got, src in zip(small, full):
         assert torch.equal(got[n_out:n_out + 10], src[n:n + 10]) and torch.all(got[n_out + 10:] == 7.0)
     assert torch.all(small_pos[n_out + 10:] == -7)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Full pairwise matching (appendix ablation)
+# ---------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg,rho,stages", [(2, (0.3, 0.3, 0.3), 3), ("global", (0.18,), 1), (3, (0.25, 0.25), 2),
+                                            (5, (0.3, 0.2), 2), (4, (0.45,), 1)])
+def test_full_pairwise_matching_matches_oracle(cfg, rho, stages):
+    """Every token against every other token of its window at the measured configurations' sizes: windows of 36 to 387
+    tokens (config 2: one tile holds a window, then several), the single 2880-token window (15 x 15 tiles of 192:
+    the 68 GFLOP contraction), 180 windows of 16 tokens (config 3), a ragged batch (5)."""
+    from workloads import make_workload
+    from parity import check_pairwise_workload
+    wl = make_workload(cfg)
+    print("[full pairwise] config %s" % cfg, flush=True)
+    reps = check_pairwise_workload(wl, rho, stages=stages)
+    for r in reps:
+        print("  stage %d: %d -> %d tokens, %d tied neighbours, fd abs %.2e, xi rel %.2e, rows rel %.2e, "
+              "%d tokens decided differently by the all-fp64 visit" % (r.stage, r.n_in, r.n_out, r.tie_rows, r.max_fd_abs,
+                                                                      r.max_xi_rel, r.max_row_rel, r.differs_from_oracle_selection), flush=True)
+        assert r.n_out < r.n_in
+
+
+def test_full_pairwise_edge_cases():
+    """Hand-set counts (none, one, half a window), windows of one and two tokens, identical tokens (every FD ties at
+    zero: positions decide the neighbours and the visit), the largest window (4096 tokens), the distance metrics, NaN rows."""
+    from workloads import make_custom
+    from parity import check_pairwise_step, to_dev
+    from oracle import lightkv_oracle as O
+    from paper_2605_00789_amd import EdgeTopKSchedule
+
+    def sched_for(wl, w, metric="cosine", rho=0.4):
+        return EdgeTopKSchedule(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                                tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                                windows_per_axis=[w], rho=[rho], metric=metric, match="full_pairwise")
+
+    wl = make_custom(name="pair_a", seed=41, dtype="bf16", batch=2, grid_h=10, grid_w=7, text_lens=(9, 20), d=128, heads=1,
+                     head_dim=128, windows_per_axis=(3,), n_final=40)
+    wo, _ = O.build_windows(wl.pos, wl.cu_vis, wl.tiles, wl.grid_h, wl.grid_w, 3)
+    v = np.diff(wo)
+    k = np.array([[0, 1, (x + 1) // 2, min(3, x // 2)][i % 4] if x >= 2 else 0 for i, x in enumerate(v)], dtype=np.int32)
+    rep, _ = check_pairwise_step(sched_for(wl, 3), 0, wl.cu_vis, wl.X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype, h_win_remove=k)
+    print("[pairwise cases] (a) %d -> %d tokens" % (rep.n_in, rep.n_out), flush=True)
+    wl = make_custom(name="pair_b", seed=42, dtype="bf16", batch=1, grid_h=6, grid_w=6, text_lens=(5,), d=256, heads=2,
+                     head_dim=128, windows_per_axis=(5,), n_final=30)
+    rep, _ = check_pairwise_step(sched_for(wl, 5), 0, wl.cu_vis, wl.X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
+    print("[pairwise cases] (b) %d -> %d tokens" % (rep.n_in, rep.n_out), flush=True)
+    wl = make_custom(name="pair_c", seed=43, dtype="bf16", batch=1, grid_h=12, grid_w=12, text_lens=(7,), d=256, heads=2,
+                     head_dim=128, windows_per_axis=(2,), n_final=100)
+    X = wl.X.copy()
+    X[:] = X[0]
+    rep, _ = check_pairwise_step(sched_for(wl, 2), 0, wl.cu_vis, X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
+    assert rep.tie_rows == 0 and rep.differs_from_oracle_selection == 0
+    print("[pairwise cases] (c) %d -> %d tokens" % (rep.n_in, rep.n_out), flush=True)
+    for metric in ("cosine", "euclidean", "l2sq"):
+        wl = make_custom(name="pair_d", seed=44, dtype="bf16", batch=1, grid_h=64, grid_w=64, text_lens=(33,), d=128,
+                         heads=1, head_dim=128, windows_per_axis=(0,), n_final=3000, structure="grid", n_c=50)
+        rep, _ = check_pairwise_step(sched_for(wl, 0, metric, rho=0.3), 0, wl.cu_vis, wl.X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
+        print("[pairwise cases] (d) %s %d -> %d tokens, %d tied, %d differ from the all-fp64 visit"
+              % (metric, rep.n_in, rep.n_out, rep.tie_rows, rep.differs_from_oracle_selection), flush=True)
+    # NaN rows never take part: they neither leave nor receive
+    wl = make_custom(name="pair_nan", seed=45, dtype="bf16", batch=1, grid_h=8, grid_w=8, text_lens=(8,), d=256, heads=2,
+                     head_dim=128, n_c=8, structure="iid", windows_per_axis=(2,), n_final=40)
+    X = wl.X.copy()
+    X[[0, 3, 17, 40]] = 0x7FC0
+    sch = sched_for(wl, 2, rho=0.5)
+    r = sch.run_step(0, wl.cu_vis, to_dev(X, "bf16"), to_dev(wl.K, "bf16"), to_dev(wl.V, "bf16"), to_dev(wl.Q, "bf16"),
+                     torch.from_numpy(wl.pos).cuda())
+    torch.cuda.synchronize()
+    dst = r.dst.cpu().numpy()
+    assert np.all(dst[[0, 3, 17, 40]] == -1) and not np.isin(dst, [0, 3, 17, 40]).any()
+    np.testing.assert_array_equal(r.new_index.cpu().numpy(), O.kept_index(dst))
+
+
+def test_full_pairwise_scores_alone_equal_those_of_the_fused_call():
+    """lightkv_score with LIGHTKV_MATCH_FULL_PAIRWISE leaves every token's nearest neighbour in best_fd / best_dst:
+    the same values lightkv_score_select reports (bit for bit), +inf / -1 for a token alone in its window."""
+    from workloads import make_custom
+    from parity import to_dev
+    from paper_2605_00789_amd import EdgeTopKSchedule
+    from paper_2605_00789_amd import binding as B
+    wl = make_custom(name="pair_scores", seed=46, dtype="bf16", batch=2, grid_h=9, grid_w=9, text_lens=(8, 30), d=192, heads=3,
+                     head_dim=64, n_c=10, structure="grid", windows_per_axis=(7,), n_final=60)   # 49 windows per sequence, some of one token
+    sched = EdgeTopKSchedule(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, tiles=wl.tiles,
+                             grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt, windows_per_axis=[7], rho=[0.4],
+                             match="full_pairwise")
+    X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+    pos = torch.from_numpy(wl.pos).cuda()
+    r = sched.run_step(0, wl.cu_vis, X, K, V, Q, pos)
+    torch.cuda.synchronize()
+    n = int(wl.cu_vis[-1])
+    cu = torch.from_numpy(wl.cu_vis.astype(np.int32)).cuda()
+    prob = B.Problem(batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, dtype=wl.dtype,
+                     h_cu_vis=wl.cu_vis.astype(np.int32), cu_vis=cu, n_windows=r.win_offsets.numel() - 1, max_window_tokens=4,
+                     win_offsets=r.win_offsets, win_tokens=r.win_tokens, match=B.MATCH_FULL_PAIRWISE)
+    ws = torch.empty(B.lightkv_workspace_size(prob), dtype=torch.uint8, device="cuda")
+    fd = torch.full((n,), -1.0, dtype=torch.float32, device="cuda")
+    nb = torch.full((n,), -9, dtype=torch.int32, device="cuda")
+    B.lightkv_score(prob, X, None, None, torch.ones(n, device="cuda"), fd, nb, ws, xi_mode=B.XI_GIVEN)
+    torch.cuda.synchronize()
+    assert torch.equal(fd, r.best_fd) and torch.equal(nb, r.best_dst)
+    sizes = np.diff(r.win_offsets.cpu().numpy())
+    assert (sizes == 1).any()
+    lone = r.win_tokens.cpu().numpy()[r.win_offsets.cpu().numpy()[:-1][sizes == 1]]
+    assert np.all(nb.cpu().numpy()[lone] == -1) and np.all(np.isinf(fd.cpu().numpy()[lone]))

@@ -599,3 +599,99 @@ def test_edge_counts_follow_step_2_as_printed():
     assert O.edge_counts_ratio(offs, 1.0).tolist() == [18, 0, 0, 1, 72, 8]
     assert O.edge_counts_ratio(np.array([0, 2, 5], dtype=np.int32), 40.0).tolist() == [1, 2]
     assert O.edge_counts_ratio(offs, 0.0).tolist() == [0] * 6
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# full pairwise matching (appendix ablation)
+# ---------------------------------------------------------------------------------------------------------------
+def test_nearest_neighbours_against_a_library_distance_matrix():
+    from scipy.spatial.distance import cdist
+    rng = np.random.default_rng(31)
+    X = rng.standard_normal((23, 7))
+    offs = np.array([0, 9, 10, 23], dtype=np.int32)                  # windows of 9, 1 and 13 tokens
+    toks = rng.permutation(23).astype(np.int32)
+    toks[0:9].sort(); toks[10:23].sort()
+    fd, nb = O.nearest_neighbours(X, offs, toks)
+    for lo, hi in ((0, 9), (10, 23)):
+        t = toks[lo:hi]
+        D = cdist(X[t], X[t], "cosine")
+        np.fill_diagonal(D, np.inf)
+        np.testing.assert_allclose(fd[t], D.min(axis=1), rtol=0, atol=1e-12)
+        np.testing.assert_array_equal(nb[t], t[D.argmin(axis=1)])
+    assert np.isinf(fd[toks[9]]) and nb[toks[9]] == -1               # a token alone in its window has no neighbour
+    # the whole v x v matrix is what the appendix FLOPs table counts: exactly 4 x the bipartite block of an even window
+    assert O.fd_flops(512, 1024, False) == 4 * O.fd_flops(512, 1024, True)
+    # Euclidean: 3-4-5
+    Y = np.array([[0.0, 0.0], [3.0, 4.0], [3.0, 0.0]])
+    fd, nb = O.nearest_neighbours(Y, np.array([0, 3]), np.arange(3, dtype=np.int32), "euclidean")
+    assert fd.tolist() == [3.0, 4.0, 3.0] and nb.tolist() == [2, 2, 0]
+
+
+def test_full_pairwise_selection_by_hand():
+    """Unit rows at chosen angles, so the FD order is known: tokens 0..5 at 0, 1, 10, 12, 40 and 41.5 degrees.
+    Nearest neighbours: 0<->1 (1 degree), 2<->3 (2 degrees), 4<->5 (1.5 degrees).  Visit order by FD: 0, 1 (1 deg),
+    4, 5 (1.5 deg), 2, 3 (2 deg).  r = 2: token 0 leaves into 1; token 1 has received a token and stays; token 4
+    leaves into 5.  r = 3 adds 2 -> 3 (5 stays as a destination).  r = 6: only three can leave."""
+    ang = np.deg2rad([0.0, 1.0, 10.0, 12.0, 40.0, 41.5])
+    X = np.stack([np.cos(ang), np.sin(ang)], axis=1)
+    offs, toks = np.array([0, 6], dtype=np.int32), np.arange(6, dtype=np.int32)
+    fd, nb = O.nearest_neighbours(X, offs, toks)
+    assert nb.tolist() == [1, 0, 3, 2, 5, 4]
+    assert O.select_full_pairwise(fd, nb, offs, toks, [2]).tolist() == [1, -1, -1, -1, 5, -1]
+    assert O.select_full_pairwise(fd, nb, offs, toks, [3]).tolist() == [1, -1, 3, -1, 5, -1]
+    assert O.select_full_pairwise(fd, nb, offs, toks, [6]).tolist() == [1, -1, 3, -1, 5, -1]
+    assert O.select_full_pairwise(fd, nb, offs, toks, [0]).tolist() == [-1] * 6
+    # a chain: tokens at 0, 3, 5, 6 degrees -> nearest: 0->1, 1->2, 2->3, 3->2; order by FD: 2, 3 (1 deg), 1 (2 deg), 0 (3 deg)
+    ang = np.deg2rad([0.0, 3.0, 5.0, 6.0])
+    X = np.stack([np.cos(ang), np.sin(ang)], axis=1)
+    offs, toks = np.array([0, 4], dtype=np.int32), np.arange(4, dtype=np.int32)
+    fd, nb = O.nearest_neighbours(X, offs, toks)
+    assert nb.tolist() == [1, 2, 3, 2]
+    # 2 leaves into 3; 3 has received and stays; 1's neighbour (2) is gone, so 1 stays; 0 leaves into 1
+    assert O.select_full_pairwise(fd, nb, offs, toks, [3]).tolist() == [1, -1, 3, -1]
+    # a hub: three tokens whose nearest neighbour is token 3, which itself is nearest to token 2
+    ang = np.deg2rad([0.0, 20.0, 11.0, 10.0])
+    X = np.stack([np.cos(ang), np.sin(ang)], axis=1)
+    fd, nb = O.nearest_neighbours(X, offs, toks)
+    assert nb.tolist() == [3, 2, 3, 2]
+    # order: 2, 3 (1 deg), 1 (9 deg), 0 (10 deg): 2 -> 3; 3 stays; 1's neighbour 2 is gone; 0 -> 3 (a second source)
+    assert O.select_full_pairwise(fd, nb, offs, toks, [4]).tolist() == [3, -1, 3, -1]
+
+
+def test_full_pairwise_selection_invariants_and_the_conflict_free_optimum():
+    rng = np.random.default_rng(77)
+    for trial in range(60):
+        n = int(rng.integers(2, 40))
+        X = rng.standard_normal((n, 5))
+        offs, toks = np.array([0, n], dtype=np.int32), np.arange(n, dtype=np.int32)
+        fd, nb = O.nearest_neighbours(X, offs, toks)
+        r = int(rng.integers(0, n // 2 + 2))
+        dst = O.select_full_pairwise(fd, nb, offs, toks, [r])
+        gone = dst >= 0
+        assert gone.sum() <= r
+        assert np.all(dst[gone] == nb[gone])                         # every merge goes to the nearest neighbour
+        assert not gone[dst[gone]].any()                             # a destination stays
+        if gone.sum() < r:                                           # the visit ran out: every stayer is blocked
+            for t in np.nonzero(~gone)[0]:
+                assert (dst == t).any() or gone[nb[t]]
+        elif r > 0:                                                  # ... else everything before the last merge was visited
+            last = max((fd[t], t) for t in np.nonzero(gone)[0])
+            for t in np.nonzero(~gone)[0]:
+                if (fd[t], t) < last:
+                    assert (dst == t).any() or gone[nb[t]]
+    # well separated mutual pairs: no conflict ever arises, and the r merges are the r lowest-FD pairs -- the choice
+    # that minimises the summed FD over all ways of merging r tokens into distinct partners (brute force)
+    ang = np.deg2rad([0.0, 2.0, 30.0, 33.0, 60.0, 61.0, 90.0, 94.0])
+    X = np.stack([np.cos(ang), np.sin(ang)], axis=1)
+    offs, toks = np.array([0, 8], dtype=np.int32), np.arange(8, dtype=np.int32)
+    fd, nb = O.nearest_neighbours(X, offs, toks)
+    full = O.feature_divergence(X, X)
+    for r in (1, 2, 3, 4):
+        dst = O.select_full_pairwise(fd, nb, offs, toks, [r])
+        got = sum(full[a, dst[a]] for a in range(8) if dst[a] >= 0)
+        best = np.inf
+        for S in itertools.combinations(range(8), r):
+            rest = [t for t in range(8) if t not in S]
+            cost = sum(min(full[a, b] for b in rest) for a in S)     # each leaver to its best staying partner
+            best = min(best, cost)
+        assert abs(got - best) < 1e-12 and (dst >= 0).sum() == r
