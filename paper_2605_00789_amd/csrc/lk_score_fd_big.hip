@@ -380,15 +380,21 @@ __global__ __launch_bounds__(256) void fd_big_finalize_kernel(BigArgs g, int chu
 // out of L2 (nothing is reused through L1), the chip's L2s hand over about 19.5 TB/s in total (measured with the
 // loads of this very loop alone), and a T x T tile needs 2 * 2T bytes per k for 2 T^2 flop per k.  With 96 x 96 tiles
 // the loads alone take longer than the MFMAs; here the output is large enough for 192 x 192 tiles to fill the chip
-// (15 x 15 = 225 workgroups), which halves the bytes per flop.  A workgroup is 2 x 2 waves of 96 x 96 each (a 6 x 6
-// grid of 16 x 16 accumulators per wave, as in fd_big_kernel).  Per k-step of 64: 384 rows x 128 bytes staged (12
-// loads and 12 LDS stores per thread), 24 fragment reads and 72 MFMAs per wave; register ring of two k-steps, two
-// LDS stages, one LDS-only barrier per step, branch-free body.  Epilogue per wave on its own quadrant: FD in fp64
-// from the stored norms, diagonal masked, minimum over the six column blocks per lane, 16-lane reductions by
-// shuffles, one integer atomicMin per row and wave on the row's key (FD bits << 32 | position of the neighbour in
-// the window list): order independent, so bit-reproducible, and equal FDs go to the earlier neighbour.
-constexpr int T2_NB = 6;                          // 16 x 16 blocks per edge of a wave's tile
-constexpr int T2_WT = 16 * T2_NB;                 // 96
+// (15 x 15 = 225 workgroups), which halves the bytes per flop.  A workgroup is 2 x 2 waves of 96 x 96 each, a wave's
+// tile a 3 x 3 grid of 32 x 32 accumulators.  (Bare loops of independent MFMAs on this chip: v_mfma_f32_32x32x16_bf16
+// sustains 2.0-2.1 PFLOP/s on constant operands and 1.33-1.5 PFLOP/s on random bf16 operands -- the clocks drop
+// with the switching activity -- and v_mfma_f32_16x16x32_bf16 1.4-1.5 even on constant ones.  So about 1.5 PFLOP/s,
+// 60 % of the nominal 2.5, is what the matrix pipes give on real data.  Measured on this kernel, 2880 x 2880 x 4096:
+// 89 us in all; without its LDS stores 75; MFMAs and barriers alone 66, of which about 10 are launch, the dependent
+// index loads in front of the loop and the epilogue; the global loads cost nothing on top.)  Per
+// k-step of 64: 384 rows x 128 bytes staged (12 loads and 12 LDS stores per thread), 24 fragment reads and 36 MFMAs
+// per wave; register ring of two k-steps, two LDS stages, one LDS-only barrier per step, branch-free body.
+// Epilogue per wave on its own quadrant: FD in fp64 from the stored norms, diagonal masked, minimum over the three
+// column blocks per lane, 32-lane reductions by shuffles, one integer atomicMin per row and wave on the row's key
+// (FD bits << 32 | position of the neighbour in the window list): order independent, so bit-reproducible, and equal
+// FDs go to the earlier neighbour.
+constexpr int T2_NB = 3;                          // 32 x 32 blocks per edge of a wave's tile
+constexpr int T2_WT = 32 * T2_NB;                 // 96
 constexpr int T2_TM = 2 * T2_WT;                  // 192: rows and columns of a workgroup tile
 constexpr int T2_BK = 64;                         // elements per k-step
 constexpr int T2_PITCH = T2_BK * 2 + 16;          // 144 bytes per staged row: 16 rows of one k-chunk fall on 16 distinct 16-byte slots
@@ -453,12 +459,16 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_pair_kernel(BigArgs g) {
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
-  const int l16 = lane & 15, kg = lane >> 4;
+  const int l32 = lane & 31, kg = lane >> 5;    // MFMA operand layout: row (column) l32, k-slice kg of a 16-element sub-step
   const int wm = wave >> 1, wn = wave & 1;
 
-  // rows this thread stages: 32 rows per pass, 8 threads per row.  32-bit offsets (checked by the launcher): every
-  // load is "uniform base + per-lane offset", the k position advances on the scalar unit.
-  const int srow = tid >> 3, schunk = tid & 7;
+  // rows this thread stages: 32 rows per pass, 8 threads per row (128 bytes).  Inside a wave the row order is
+  // 0, 8, 1, 9, ...: two rows that are 8 apart lie 8 * 144 = 128 (mod 256) bytes apart, so the 16 lanes of a quarter
+  // wave store to 256 distinct bytes of a 256-byte bank row (in natural order neighbouring rows overlap by 16 bytes).
+  // 32-bit offsets (checked by the launcher): every load is "uniform base + per-lane offset", the k position
+  // advances on the scalar unit.
+  const int sg = tid >> 3, schunk = tid & 7;
+  const int srow = (sg & ~15) | ((sg & 1) << 3) | ((sg & 15) >> 1);
   uint32_t offa[T2_PASSES], offb[T2_PASSES];
 #pragma unroll
   for (int p = 0; p < T2_PASSES; ++p) {
@@ -484,11 +494,13 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_pair_kernel(BigArgs g) {
     e_sq[u] = g.sq[e_ok[u] ? t : 0];
   }
 
-  f32x4 acc[T2_NB][T2_NB];
+  f32x16 acc[T2_NB][T2_NB];
 #pragma unroll
   for (int i = 0; i < T2_NB; ++i)
 #pragma unroll
-    for (int j = 0; j < T2_NB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < T2_NB; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int n_my = g.d / T2_BK;                   // k-steps (d is a multiple of 64, at least 64: checked by the launcher)
   const char *xbase = static_cast<const char *>(g.X);
@@ -510,49 +522,85 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_pair_kernel(BigArgs g) {
       *reinterpret_cast<uint4 *>(base + T2_TM * T2_PITCH + p * 32 * T2_PITCH) = r[T2_PASSES + p];
     }
   };
-  const char *lds_ra = lds + (wm * T2_WT + l16) * T2_PITCH + kg * 16;
-  const char *lds_rb = lds + (T2_TM + wn * T2_WT + l16) * T2_PITCH + kg * 16;
-  // One k-step = two halves of 32 elements.  Per half: 12 fragment reads, then 36 MFMAs with 6 LDS stores (half of the
-  // next step's data, ring slot -> the other stage) and the 6 global loads that refill those ring registers slotted
-  // between them (6 MFMAs, 1 store, 1 load, ...): the matrix pipe runs while the LDS port takes the stores, and
-  // every ring register is on its way again right after its store.
-  auto step = [&](int stage, uint4 *r, int ks_refill) {
-    const char *abase = lds_ra + stage * T2_STAGE;
-    const char *bbase = lds_rb + stage * T2_STAGE;
-    char *wbase = lds_w + (stage ^ 1) * T2_STAGE;
-    const char *kb = xbase + (size_t)(ks_refill < n_my ? ks_refill : n_my - 1) * (T2_BK * 2);   // scalar
+  const char *lds_ra = lds + (wm * T2_WT + l32) * T2_PITCH + kg * 16;
+  const char *lds_rb = lds + (T2_TM + wn * T2_WT + l32) * T2_PITCH + kg * 16;
+  // operand fragments of one 32-element half of a k-step: two 16-element sub-steps x (3 row blocks + 3 column blocks)
+  struct Frag { bf16x8 a[2][T2_NB], b[2][T2_NB]; };
+  auto fread = [&](int stage, int h, Frag &f) {
+    const char *abase = lds_ra + stage * T2_STAGE + h * 64;
+    const char *bbase = lds_rb + stage * T2_STAGE + h * 64;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      bf16x8 fa[T2_NB], fb[T2_NB];
-      __builtin_amdgcn_sched_barrier(0);
+    for (int u = 0; u < 2; ++u) {
 #pragma unroll
-      for (int i = 0; i < T2_NB; ++i) fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(bbase + i * 16 * T2_PITCH + h * 64));
+      for (int i = 0; i < T2_NB; ++i) f.b[u][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(bbase + i * 32 * T2_PITCH + u * 32));
 #pragma unroll
-      for (int i = 0; i < T2_NB; ++i) fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(abase + i * 16 * T2_PITCH + h * 64));
+      for (int i = 0; i < T2_NB; ++i) f.a[u][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(abase + i * 32 * T2_PITCH + u * 32));
+    }
+  };
+  auto mma = [&](const Frag &f) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int i = 0; i < T2_NB; ++i)
 #pragma unroll
         for (int j = 0; j < T2_NB; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[u][i], f.b[u][j], acc[i][j], 0, 0, 0);
+  };
+  // One k-step = two halves of 32 elements, and the operand fragments of a half are fetched from LDS while the
+  // MFMAs of the half before it run, so that (with one wave per SIMD) the matrix pipe never waits for an LDS round trip:
+  //   first half : 18 MFMAs on f0 | 12 fragment reads (second half of this stage -> f1) | the 12 LDS stores that move
+  //                the next step's data from its ring slot into the other stage | 6 of the 12 global loads that refill
+  //                the ring slot
+  //   barrier    : the other stage is complete (LDS traffic only; global loads stay in flight)
+  //   second half: 18 MFMAs on f1 | 12 fragment reads (first half of the other stage -> f0) | the other 6 refills
+  // Issue order is pinned with sched_group_barrier: one MFMA, then one LDS or memory instruction, and so on.
+  Frag f0, f1;
+  auto step = [&](int stage, uint4 *r, int ks_refill) {
+    char *wbase = lds_w + (stage ^ 1) * T2_STAGE;
+    const char *kb = xbase + (size_t)(ks_refill < n_my ? ks_refill : n_my - 1) * (T2_BK * 2);   // scalar
+    __builtin_amdgcn_sched_barrier(0);
+    fread(stage, 1, f1);
+    mma(f0);
 #pragma unroll
-      for (int p = h * (T2_PASSES / 2); p < (h + 1) * (T2_PASSES / 2); ++p) {
-        *reinterpret_cast<uint4 *>(wbase + p * 32 * T2_PITCH) = r[p];
-        *reinterpret_cast<uint4 *>(wbase + T2_TM * T2_PITCH + p * 32 * T2_PITCH) = r[T2_PASSES + p];
-      }
-#pragma unroll
-      for (int p = h * (T2_PASSES / 2); p < (h + 1) * (T2_PASSES / 2); ++p) {
-        r[p] = ld16(kb + offa[p]);
-        r[T2_PASSES + p] = ld16(kb + offb[p]);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 * T2_NB, 0);
-#pragma unroll
-      for (int q = 0; q < T2_PASSES; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, T2_NB * T2_NB / T2_PASSES, 0);
-        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+    for (int p = 0; p < T2_PASSES; ++p) {
+      *reinterpret_cast<uint4 *>(wbase + p * 32 * T2_PITCH) = r[p];
+      *reinterpret_cast<uint4 *>(wbase + T2_TM * T2_PITCH + p * 32 * T2_PITCH) = r[T2_PASSES + p];
     }
+#pragma unroll
+    for (int p = 0; p < T2_PASSES / 2; ++p) {
+      r[p] = ld16(kb + offa[p]);
+      r[T2_PASSES + p] = ld16(kb + offb[p]);
+    }
+    // 12 reads first (they feed the second half and have the whole first half to arrive), then 12 x (1 MFMA, 1 store),
+    // then 6 x (1 MFMA, 1 load)
+    __builtin_amdgcn_sched_group_barrier(0x100, 4 * T2_NB, 0);
+#pragma unroll
+    for (int q = 0; q < 2 * T2_PASSES; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+    }
+#pragma unroll
+    for (int q = 0; q < T2_PASSES; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    lds_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    fread(stage ^ 1, 0, f0);
+    mma(f1);
+#pragma unroll
+    for (int p = T2_PASSES / 2; p < T2_PASSES; ++p) {
+      r[p] = ld16(kb + offa[p]);
+      r[T2_PASSES + p] = ld16(kb + offb[p]);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 4 * T2_NB, 0);
+#pragma unroll
+    for (int q = 0; q < T2_PASSES; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   };
   gload(0, ring[0]);
   __builtin_amdgcn_sched_barrier(0);
@@ -563,6 +611,7 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_pair_kernel(BigArgs g) {
   gload(2, ring[0]);
   __builtin_amdgcn_sched_barrier(0);
   lds_barrier();
+  fread(0, 0, f0);
   // (an empty statement that ties every accumulator to the accumulation registers: without it the register allocator
   // rotates the accumulators through other registers inside the k loop)
 #pragma unroll
@@ -570,22 +619,20 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_pair_kernel(BigArgs g) {
 #pragma unroll
     for (int j = 0; j < T2_NB; ++j) asm volatile("" : "+a"(acc[i][j]));
   // Step ks computes from LDS stage ks & 1 while the data of step ks + 1 moves from its ring slot to the other stage
-  // (after the last step that copy is a harmless repeat).  Steps come in pairs so that stage and ring slot are static.
+  // (after the last step that copy is a harmless repeat, and so is the fragment fetch at its end).  Steps come in
+  // pairs so that stage and ring slot are static.  No barrier is needed between two steps: a step only stores to the
+  // stage whose last reads (this wave's and, through the mid-step barrier of the step before, everybody's) are complete.
   int ks = 0;
   for (; ks + 1 < n_my; ks += 2) {
     step(0, ring[1], ks + 3);
-    lds_barrier();
     step(1, ring[0], ks + 4);
-    lds_barrier();
   }
-  if (ks < n_my) {   // an odd number of steps: the last one, from stage 0
-    step(0, ring[1], ks + 3);
-    lds_barrier();
-  }
+  if (ks < n_my) step(0, ring[1], ks + 3);   // an odd number of steps: the last one, from stage 0
 #pragma unroll
   for (int i = 0; i < T2_NB; ++i)
 #pragma unroll
     for (int j = 0; j < T2_NB; ++j) asm volatile("" : "+a"(acc[i][j]));
+  __syncthreads();   // every wave is through with the operand stages before the epilogue reuses LDS
 
   // ---- epilogue.  LDS is free now: 1/|x| (or |x|^2 for the distances) of the 192 rows, then of the 192 columns.
   double *e_rnorm = reinterpret_cast<double *>(lds);
@@ -596,19 +643,22 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_pair_kernel(BigArgs g) {
       e_rnorm[e] = !e_ok[u] ? -1.0 : (e_sq[u] != e_sq[u] || g.metric != 0 ? (double)e_sq[u] : 1.0 / fmax(sqrt((double)e_sq[u]), 1e-12));   // NaN rows keep a NaN norm
   }
   __syncthreads();
+  // Accumulator layout of a 32 x 32 block: a lane holds column lane % 32 and the 16 rows acc_row(e, lane).
 #pragma unroll
   for (int i = 0; i < T2_NB; ++i) {
-    unsigned long long kmin[4] = {~0ull, ~0ull, ~0ull, ~0ull};
+    unsigned long long kmin[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) kmin[e] = ~0ull;
 #pragma unroll
     for (int j = 0; j < T2_NB; ++j) {
-      const int cl = wn * T2_WT + j * 16 + l16;
+      const int cl = wn * T2_WT + j * 32 + l32;
       const double rb = e_rnorm[T2_TM + cl];
       const int lb = col0 + cl;                     // position of the column token in the window list
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int rl = wm * T2_WT + i * 16 + kg * 4 + q;
+      for (int e = 0; e < 16; ++e) {
+        const int rl = wm * T2_WT + i * 32 + acc_row(e, lane);
         const double ra = e_rnorm[rl];
-        const double dot = (double)acc[i][j][q];
+        const double dot = (double)acc[i][j][e];
         float fd;
         if (g.metric == 0) {
           { const double c1 = 1.0 - dot * ra * rb; fd = (float)(c1 < 0.0 ? 0.0 : c1); }   // (a NaN stays a NaN: fmax would drop it)
@@ -619,22 +669,22 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_pair_kernel(BigArgs g) {
         }
         unsigned long long key = ((unsigned long long)__float_as_uint(fd) << 32) | (unsigned)lb;
         key = (ra >= 0.0 && rb >= 0.0 && row0 + rl != lb && fd == fd) ? key : ~0ull;   // no self pairs, NaN never competes
-        kmin[q] = key < kmin[q] ? key : kmin[q];
+        kmin[e] = key < kmin[e] ? key : kmin[e];
       }
     }
 #pragma unroll
-    for (int m = 8; m >= 1; m >>= 1) {   // the 16 lanes with the same lane / 16 hold the same rows
-      unsigned long long other[4];
+    for (int m = 16; m >= 1; m >>= 1) {   // the 32 lanes with the same lane / 32 hold the same rows
+      unsigned long long other[16];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) other[q] = __shfl_xor(kmin[q], m, 64);
+      for (int e = 0; e < 16; ++e) other[e] = __shfl_xor(kmin[e], m, 64);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) kmin[q] = other[q] < kmin[q] ? other[q] : kmin[q];
+      for (int e = 0; e < 16; ++e) kmin[e] = other[e] < kmin[e] ? other[e] : kmin[e];
     }
-    if (l16 == 0) {
+    if (l32 == 0) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int la = row0 + wm * T2_WT + i * 16 + kg * 4 + q;
-        if (la < v && kmin[q] != ~0ull) atomicMin(&g.cand[(size_t)(off + la)], kmin[q]);
+      for (int e = 0; e < 16; ++e) {
+        const int la = row0 + wm * T2_WT + i * 32 + acc_row(e, lane);
+        if (la < v && kmin[e] != ~0ull) atomicMin(&g.cand[(size_t)(off + la)], kmin[e]);
       }
     }
   }
