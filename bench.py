@@ -34,7 +34,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
-PASSES = ("all", "step", "cold", "hbm_primary", "similarity", "pairwise")
+PASSES = ("all", "step", "cold", "hbm_primary", "similarity", "pairwise", "ceilings")
 
 
 def _parse():
@@ -237,6 +237,55 @@ def similarity_pass(stream, timer, n_inst, full_pairwise):
             "bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "flops_per_call": int(flops), "avg_call_us": round(us, 2),
             "workload": wl.name}
+
+
+def ceilings_pass(stream):
+    """What the chip delivers to the dense contractions, measured with the probe library (no method arithmetic): the
+    operand loads of the tiled FD kernels alone (every byte comes out of L2: nothing is reused through L1), and bare
+    loops of independent 32x32x16 bf16 MFMAs on constant and on random operands (the sustained clocks depend on the
+    switching activity of the operands)."""
+    import ctypes as C
+    import numpy as np
+    import torch
+    from workloads import make_workload
+    from paper_2605_00789_amd import to_device as to_dev
+    path = os.path.join(ROOT, "paper_2605_00789_amd", "liblightkv_probe.so")
+    lib = C.CDLL(path)
+    lib.lightkv_probe_operand_delivery.restype = C.c_int
+    lib.lightkv_probe_operand_delivery.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                                   C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_double), C.c_void_p]
+    lib.lightkv_probe_mfma.restype = C.c_int
+    lib.lightkv_probe_mfma.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.c_void_p]
+    wl = make_workload("global")
+    X = to_dev(wl.X, wl.dtype)
+    n, row_bytes = X.shape[0], X.shape[1] * 2
+    sp = C.c_void_p(stream.cuda_stream)
+    out = {"operand_delivery": [], "mfma_bare_loop": []}
+    for name, pairwise, tile, splits, piece in (("bipartite 1440 x 1440, 96 x 96 tiles (fd_big_kernel's loads)", 0, 96, 1, 256),
+                                                ("bipartite, 96 x 96 tiles, 128-byte pieces", 0, 96, 1, 128),
+                                                ("bipartite, 192 x 192 tiles, hidden axis split 4 ways", 0, 192, 4, 128),
+                                                ("full pairwise 2880 x 2880, 192 x 192 tiles (fd_pair_kernel's loads)", 1, 192, 1, 128),
+                                                ("full pairwise, 96 x 96 tiles", 1, 96, 1, 256)):
+        us, nbytes = C.c_float(0), C.c_double(0)
+        rc = lib.lightkv_probe_operand_delivery(C.c_void_p(X.data_ptr()), n, row_bytes, pairwise, tile, splits, piece, 20,
+                                                C.byref(us), C.byref(nbytes), sp)
+        if rc != 0:
+            raise RuntimeError("lightkv_probe_operand_delivery failed: %d" % rc)
+        out["operand_delivery"].append({"case": name, "us": round(us.value, 2), "MB_to_CUs": round(nbytes.value / 1e6, 1),
+                                        "TBps": round(nbytes.value / (us.value * 1e-6) / 1e12, 2)})
+    iters_mfma = 500
+    for name, data in (("constant operands (all lanes 1.0)", torch.ones(1024 * 6 * 256 * 8, dtype=torch.bfloat16, device=X.device)),
+                       ("random operands (N(0,1) bf16)", torch.randn(1024 * 6 * 256 * 8, device=X.device).to(torch.bfloat16))):
+        for wgs in (225, 256, 1024):
+            us = C.c_float(0)
+            rc = lib.lightkv_probe_mfma(C.c_void_p(data.data_ptr()), wgs, iters_mfma, 5, C.byref(us), sp)
+            if rc != 0:
+                raise RuntimeError("lightkv_probe_mfma failed: %d" % rc)
+            flops = wgs * 4 * 9 * iters_mfma * 32768.0
+            out["mfma_bare_loop"].append({"case": name, "workgroups": wgs, "us": round(us.value, 2),
+                                          "TFLOPs": round(flops / (us.value * 1e-6) / 1e12, 1),
+                                          "frac_of_published_peak": round(flops / (us.value * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 3)})
+    return out
 
 
 def cpu_baseline(run_once, tokens_per_step, repeats, sample):
@@ -515,6 +564,10 @@ def main():
         out["roofline_similarity"] = similarity_pass(stream, timer, n_inst, full_pairwise=False)
     if (main_workload or cfg == "global") and want("pairwise"):
         out["roofline_similarity_full_pairwise"] = similarity_pass(stream, timer, n_inst, full_pairwise=True)
+
+    if only == "ceilings":
+        with torch.cuda.stream(stream):
+            out["ceilings"] = ceilings_pass(stream)
 
     if not args.no_cpu_baseline and only == "all":
         from oracle import lightkv_oracle as O

@@ -10,6 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "liblightkv.so")
+PROBE_LIB_PATH = os.path.join(HERE, "liblightkv_probe.so")   # measurement kernels for bench.py --pass ceilings, nothing of the method
 SOURCES = ["lk_api.hip", "lk_windows.hip", "lk_score_fd.hip", "lk_score_fd_big.hip", "lk_fd_dump.hip", "lk_score_xi.hip", "lk_xi_seq.hip", "lk_select.hip", "lk_select_edges.hip", "lk_select_pair.hip", "lk_rows.hip", "lk_fused.hip", "lk_schedule.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 instruction forms are kept out of the generated code on purpose
@@ -49,6 +50,14 @@ def build(verbose: bool = True, jobs: int = 6) -> str:
     os.replace(tmp, LIB_PATH)
     if verbose:
         print("built", LIB_PATH)
+    probe_obj = compile_one("lk_probe.hip")
+    tmp = PROBE_LIB_PATH + ".tmp"
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, probe_obj], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stderr)
+    os.replace(tmp, PROBE_LIB_PATH)
+    if verbose:
+        print("built", PROBE_LIB_PATH)
     return LIB_PATH
 
 

@@ -226,6 +226,7 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_sort_kernel(WinArgs
 // that can give more than q give one more until the budget is met.  Integer work throughout; rho is a double so that
 // the floor is taken in the precision a host program would use.
 constexpr int CNT_THREADS = 256;
+constexpr int CNT_CACHE = 8192;   // window caps kept in LDS (16 KB)
 
 struct CountArgs {
   const int32_t *win_offsets, *cu_vis, *cu_target;
@@ -260,10 +261,17 @@ __global__ __launch_bounds__(CNT_THREADS) void window_counts_kernel(CountArgs g)
     return;
   }
   const int budget = (g.cu_vis[b + 1] - g.cu_vis[b]) - (g.cu_target[b + 1] - g.cu_target[b]);
-  auto cap_of = [&](int w) {
+  // the caps are looked at a dozen times: the first CNT_CACHE of them are kept in LDS (one trip to memory instead of
+  // one per pass, which is what this small kernel's time consists of); longer lists re-read the rest
+  __shared__ uint16_t cap_lds[CNT_CACHE];
+  auto cap_mem = [&](int w) {
     const int v = g.win_offsets[w0 + w + 1] - g.win_offsets[w0 + w];
-    return v >= 2 ? (v + 1) >> 1 : 0;
+    const int c = v >= 2 ? (v + 1) >> 1 : 0;
+    return c < 65535 ? c : 65535;
   };
+  for (int w = tid; w < W && w < CNT_CACHE; w += CNT_THREADS) cap_lds[w] = (uint16_t)cap_mem(w);
+  __syncthreads();
+  auto cap_of = [&](int w) { return w < CNT_CACHE ? (int)cap_lds[w] : cap_mem(w); };
   int total = 0, maxcap = 0;
   for (int w = tid; w < W; w += CNT_THREADS) { const int c = cap_of(w); total += c; maxcap = c > maxcap ? c : maxcap; }
   total = block_sum_256(total, red);

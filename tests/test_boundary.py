@@ -219,3 +219,16 @@ def test_window_counts_rejects_bad_arguments_before_any_launch(B):
     assert f(1, 4, fake, 0, float("nan"), None, None, fake, None, None) == 2
     assert f(1, 4, fake, 1, -0.1, None, None, fake, None, None) == 2
     assert f(2, 0, fake, 0, 0.5, None, None, fake, None, None) == 0          # nothing to do
+
+
+def test_probe_library_exports_what_its_header_declares():
+    """The measurement library behind bench.py --pass ceilings (no method arithmetic) loads and exports its two calls."""
+    header = open(os.path.join(ROOT, "include", "lightkv_probe.h")).read()
+    declared = set(re.findall(r"^int (lightkv_probe_[a-z_]+)\(", header, re.M))
+    assert declared == {"lightkv_probe_operand_delivery", "lightkv_probe_mfma"}
+    lib = C.CDLL(os.path.join(ROOT, "paper_2605_00789_amd", "liblightkv_probe.so"))
+    for name in declared:
+        assert hasattr(lib, name), name
+    # arguments are checked before anything is launched (no device needed)
+    lib.lightkv_probe_mfma.restype = C.c_int
+    assert lib.lightkv_probe_mfma(None, 4, 10, 1, None, None) != 0
