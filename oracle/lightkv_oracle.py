@@ -147,19 +147,29 @@ def removal_counts_even(n_remove: int, n_windows: int) -> np.ndarray:
     return np.array([q + (1 if k < rem else 0) for k in range(n_windows)], dtype=np.int32)
 
 
-def removal_counts_ratio(win_offsets: np.ndarray, rho: float) -> np.ndarray:
+def proposing_count(v, direction: str = "a_to_b"):
+    """Tokens of a v-token window on the side that proposes: |A| = ceil(v/2) in the paper's direction, |B| =
+    floor(v/2) in the reverse one (Sec. 3.2.1, message-passing paragraph)."""
+    if direction not in ("a_to_b", "b_to_a"):
+        raise ValueError("unknown direction %r" % (direction,))
+    return (v + 1) // 2 if direction == "a_to_b" else v // 2
+
+
+def removal_counts_ratio(win_offsets: np.ndarray, rho: float, direction: str = "a_to_b") -> np.ndarray:
     """Paper-style count: a fraction rho of every window's tokens leaves
-    (Sec. 3.2.2: a fraction 1-rho remains), capped by |A| (the 50 % limit
+    (Sec. 3.2.2: a fraction 1-rho remains), capped by the proposing set (|A|: the 50 % limit
     named in the limitations paragraph)."""
     v = np.diff(np.asarray(win_offsets, dtype=np.int64))
-    return np.minimum(np.floor(rho * v + 1e-9).astype(np.int64), (v + 1) // 2).astype(np.int32)
+    return np.minimum(np.floor(rho * v + 1e-9).astype(np.int64), proposing_count(v, direction)).astype(np.int32)
 
 
-def removal_counts_target(win_offsets: np.ndarray, batch: int, n_remove: Sequence[int]) -> Tuple[np.ndarray, np.ndarray]:
+def removal_counts_target(win_offsets: np.ndarray, batch: int, n_remove: Sequence[int],
+                          direction: str = "a_to_b") -> Tuple[np.ndarray, np.ndarray]:
     """Removal counts that take n_remove[b] tokens out of sequence b, whatever sizes its windows have
     (later stages: the windows no longer hold equal numbers of tokens).  Reading of Step 2 / Sec. 3.2.2 when a stage
     is given a token budget instead of a ratio: the budget is spread as evenly as the windows allow.  A window of v
-    tokens can give up at most its set A, cap = ceil(v/2) (0 if v < 2: nothing to merge into).  With q the largest
+    tokens can give up at most its proposing set, cap = ceil(v/2) (floor(v/2) in the reverse direction; 0 if v < 2:
+    nothing to merge into).  With q the largest
     level for which sum_w min(cap_w, q) does not exceed the budget, window w gives min(cap_w, q), and what is then
     still missing comes one token each from the first windows (in window order) that can give more than q.  Where no
     cap binds this is floor(R/W) per window and one more for the first R mod W windows.
@@ -171,7 +181,7 @@ def removal_counts_target(win_offsets: np.ndarray, batch: int, n_remove: Sequenc
     bad = np.zeros(batch, dtype=bool)
     for b in range(batch):
         vs = v[b * per_seq:(b + 1) * per_seq]
-        cap = [int((x + 1) // 2) if x >= 2 else 0 for x in vs]
+        cap = [int(proposing_count(int(x), direction)) if x >= 2 else 0 for x in vs]
         R = int(n_remove[b])
         if R < 0:
             raise ValueError("a stage cannot add tokens")
@@ -205,10 +215,16 @@ def edge_counts_ratio(win_offsets: np.ndarray, rho: float) -> np.ndarray:
     return np.minimum(k, ((v + 1) // 2) * (v // 2)).astype(np.int32)
 
 
-def split_window(tokens: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
-    """Step 1: local positions 0,2,4,.. -> A ; 1,3,5,.. -> B."""
+def split_window(tokens: np.ndarray, direction: str = "a_to_b") -> Tuple[np.ndarray, np.ndarray]:
+    """Step 1: local positions 0,2,4,.. -> A ; 1,3,5,.. -> B.  Returns (proposing set, receiving set): (A, B) in the
+    paper's direction; in the reverse direction (Sec. 3.2.1, message-passing paragraph: defined analogously) the
+    nodes of B propose and those of A receive, so (B, A)."""
     tokens = np.asarray(tokens)
-    return tokens[0::2], tokens[1::2]
+    if direction == "a_to_b":
+        return tokens[0::2], tokens[1::2]
+    if direction == "b_to_a":
+        return tokens[1::2], tokens[0::2]
+    raise ValueError("unknown direction %r" % (direction,))
 
 
 # ---------------------------------------------------------------------------
@@ -283,8 +299,10 @@ def feature_divergence(XA: np.ndarray, XB: np.ndarray, metric: str = "cosine") -
     return np.sqrt(d2) if metric == "euclidean" else d2
 
 
-def best_edges(X: np.ndarray, win_offsets: np.ndarray, win_tokens: np.ndarray, metric: str = "cosine"):
-    """For every A node its lowest-FD B node of the same window.
+def best_edges(X: np.ndarray, win_offsets: np.ndarray, win_tokens: np.ndarray, metric: str = "cosine",
+               direction: str = "a_to_b"):
+    """For every A node its lowest-FD B node of the same window (direction "b_to_a": read A as the proposing set B and
+    B as the receiving set A throughout).
     Returns best_fd[float64, N] (+inf on B rows and on A rows of windows without a
     B node) and best_dst[int32, N] (token index, -1 where there is none).
     Ties go to the B node that comes first in the window."""
@@ -293,8 +311,8 @@ def best_edges(X: np.ndarray, win_offsets: np.ndarray, win_tokens: np.ndarray, m
     best_dst = np.full(n, -1, dtype=np.int32)
     for wdx in range(len(win_offsets) - 1):
         toks = win_tokens[win_offsets[wdx]:win_offsets[wdx + 1]]
-        A, B = split_window(toks)
-        if len(B) == 0:
+        A, B = split_window(toks, direction)
+        if len(B) == 0 or len(A) == 0:
             continue
         fd = feature_divergence(X[A], X[B], metric)
         j = np.argmin(fd, axis=1)                # first minimum = lowest local B position
@@ -304,7 +322,7 @@ def best_edges(X: np.ndarray, win_offsets: np.ndarray, win_tokens: np.ndarray, m
 
 
 def select(best_fd: np.ndarray, best_dst: np.ndarray, win_offsets: np.ndarray,
-           win_tokens: np.ndarray, win_remove: np.ndarray):
+           win_tokens: np.ndarray, win_remove: np.ndarray, direction: str = "a_to_b"):
     """Step 2 under the one-edge-per-A-node reading: in every window the r A nodes
     with the lowest proposal (ties: earlier in the window first) are merged.
     Returns dst[int32, N]: the B token an A token is merged into, -1 for every
@@ -313,7 +331,7 @@ def select(best_fd: np.ndarray, best_dst: np.ndarray, win_offsets: np.ndarray,
     dst = np.full(n, -1, dtype=np.int32)
     for wdx in range(len(win_offsets) - 1):
         toks = win_tokens[win_offsets[wdx]:win_offsets[wdx + 1]]
-        A, B = split_window(toks)
+        A, B = split_window(toks, direction)
         r = int(win_remove[wdx])
         if r == 0 or len(B) == 0:
             continue
@@ -497,12 +515,13 @@ class StageResult:
 
 
 def compress_stage(X, K, V, Q, pos, cu_vis, cu_txt, heads, head_dim, win_offsets, win_tokens,
-                   win_remove, scale=None, lse=None, xi=None, metric: str = "cosine") -> StageResult:
+                   win_remove, scale=None, lse=None, xi=None, metric: str = "cosine",
+                   direction: str = "a_to_b") -> StageResult:
     """One whole compression step on float64 inputs (already widened from storage)."""
     if xi is None:
         xi = xi_text_query(Q, K, cu_vis, cu_txt, heads, head_dim, scale=scale, lse=lse)
-    best_fd, best_dst = best_edges(X, win_offsets, win_tokens, metric)
-    dst = select(best_fd, best_dst, win_offsets, win_tokens, win_remove)
+    best_fd, best_dst = best_edges(X, win_offsets, win_tokens, metric, direction)
+    dst = select(best_fd, best_dst, win_offsets, win_tokens, win_remove, direction)
     new_index = kept_index(dst)
     go, gs = groups_csr(dst)
     Xo = compact(message_passing(X, xi, dst), dst)
@@ -575,7 +594,8 @@ def stage_removals(batch: int, n_in: int, n_out: int, windows_per_seq: int) -> n
     return np.tile(one, batch)
 
 
-def compress_schedule(wl, stages: Optional[int] = None, metric: str = "cosine") -> List[StageResult]:
+def compress_schedule(wl, stages: Optional[int] = None, metric: str = "cosine",
+                      direction: str = "a_to_b") -> List[StageResult]:
     """Runs the hierarchical schedule (Sec. 3.2.2) of a workload: after every stage the
     outputs are rounded to the storage dtype, as a KV cache would hold them."""
     X, K, V = wl.X, wl.K, wl.V
@@ -587,11 +607,11 @@ def compress_schedule(wl, stages: Optional[int] = None, metric: str = "cosine") 
         w = wl.windows_per_axis[s]
         wo, wt = build_windows(pos, cu_vis, wl.tiles, wl.grid_h, wl.grid_w, w)
         n_seq = np.diff(np.asarray(cu_vis, dtype=np.int64))
-        rem, bad = removal_counts_target(wo, wl.batch, n_seq - wl.targets[s])
+        rem, bad = removal_counts_target(wo, wl.batch, n_seq - wl.targets[s], direction)
         if bad.any():
             raise ValueError("stage %d: the windows cannot give up %s tokens" % (s, (n_seq - wl.targets[s]).tolist()))
         res = compress_stage(widen(X, wl.dtype), widen(K, wl.dtype), widen(V, wl.dtype), Q, pos, cu_vis,
-                             wl.cu_txt, wl.heads, wl.head_dim, wo, wt, rem, metric=metric)
+                             wl.cu_txt, wl.heads, wl.head_dim, wo, wt, rem, metric=metric, direction=direction)
         out.append(res)
         X, K, V = (round_to_storage(t, wl.dtype) for t in (res.X, res.K, res.V))
         pos, cu_vis, n_in = res.pos, res.cu_vis, wl.targets[s]

@@ -695,3 +695,90 @@ def test_full_pairwise_selection_invariants_and_the_conflict_free_optimum():
             cost = sum(min(full[a, b] for b in rest) for a in S)     # each leaver to its best staying partner
             best = min(best, cost)
         assert abs(got - best) < 1e-12 and (dst >= 0).sum() == r
+
+
+# ---------------------------------------------------------------- reverse direction (Sec. 3.2.1, message-passing paragraph)
+def test_reverse_direction_by_hand_on_an_odd_window():
+    """Five tokens (A = 10, 12, 14 at local positions 0, 2, 4; B = 11, 13): in the reverse direction the two B nodes
+    propose and the three A nodes receive, the last A node included."""
+    X = np.zeros((16, 2))
+    ang = {10: 0.0, 11: 80.0, 12: 40.0, 13: 5.0, 14: 90.0}           # degrees; FD = 1 - cos(difference)
+    for t, a in ang.items():
+        X[t] = [math.cos(math.radians(a)), math.sin(math.radians(a))]
+    toks = np.array([10, 11, 12, 13, 14], dtype=np.int32)
+    offs = np.array([0, 5], dtype=np.int32)
+    P, R = O.split_window(toks, "b_to_a")
+    assert P.tolist() == [11, 13] and R.tolist() == [10, 12, 14]
+    bf, bd = O.best_edges(X, offs, toks, direction="b_to_a")
+    assert bd[11] == 14 and bd[13] == 10                              # 80 -> 90 (10 degrees), 5 -> 0 (5 degrees)
+    assert bf[11] == pytest.approx(1 - math.cos(math.radians(10)), abs=1e-15)
+    assert bf[13] == pytest.approx(1 - math.cos(math.radians(5)), abs=1e-15)
+    assert np.all(np.isinf(bf[[10, 12, 14]])) and np.all(bd[[10, 12, 14]] == -1)   # the receiving side offers nothing
+    dst1 = O.select(bf, bd, offs, toks, np.array([1]), "b_to_a")
+    assert {t: int(dst1[t]) for t in toks} == {10: -1, 11: -1, 12: -1, 13: 10, 14: -1}   # the closer pair goes first
+    dst2 = O.select(bf, bd, offs, toks, np.array([2]), "b_to_a")
+    assert {t: int(dst2[t]) for t in toks} == {10: -1, 11: 14, 12: -1, 13: 10, 14: -1}
+    with pytest.raises(ValueError):
+        O.select(bf, bd, offs, toks, np.array([3]), "b_to_a")        # |B| = 2 nodes can leave, not 3
+    # the paper's direction on the same window: A proposes (three offers), B receives
+    bf0, bd0 = O.best_edges(X, offs, toks)
+    assert bd0[[10, 12, 14]].tolist() == [13, 13, 11] and np.all(bd0[[11, 13]] == -1)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_reverse_direction_is_the_forward_step_with_the_labels_exchanged(seed):
+    """Windows of even size: exchanging the two tokens of every (A, B) position pair in the window list and running the
+    paper's direction is the reverse direction on the original list (same offers, same merges, token by token)."""
+    rng = np.random.default_rng(100 + seed)
+    sizes = rng.choice([2, 4, 6, 8, 12], size=4)
+    n = int(sizes.sum())
+    X = rng.standard_normal((n, 5))
+    toks = rng.permutation(n).astype(np.int32)
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    for k in range(4):
+        toks[offs[k]:offs[k + 1]].sort()
+    swapped = toks.copy()
+    swapped[0::2], swapped[1::2] = toks[1::2], toks[0::2]            # all windows start at even offsets
+    rem = np.array([int(rng.integers(0, s // 2 + 1)) for s in sizes], dtype=np.int32)
+    bf_r, bd_r = O.best_edges(X, offs, toks, direction="b_to_a")
+    bf_f, bd_f = O.best_edges(X, offs, swapped)
+    np.testing.assert_array_equal(bf_r, bf_f)
+    np.testing.assert_array_equal(bd_r, bd_f)
+    np.testing.assert_array_equal(O.select(bf_r, bd_r, offs, toks, rem, "b_to_a"), O.select(bf_f, bd_f, offs, swapped, rem))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_reverse_direction_is_the_brute_force_minimiser(seed):
+    """As for the paper's direction: among all ways of choosing r proposing nodes (now of B) and one receiving node (of
+    A) for each, the selected edge set has the smallest total FD; windows of odd size included."""
+    rng = np.random.default_rng(200 + seed)
+    v = int(rng.integers(4, 10))
+    X = rng.standard_normal((v + 2, 6))
+    toks = np.sort(rng.choice(v + 2, size=v, replace=False)).astype(np.int32)
+    offs = np.array([0, v], dtype=np.int32)
+    A, B = toks[0::2], toks[1::2]
+    r = int(rng.integers(1, min(3, len(B)) + 1))
+    bf, bd = O.best_edges(X, offs, toks, direction="b_to_a")
+    dst = O.select(bf, bd, offs, toks, np.array([r]), "b_to_a")
+    got = sorted((int(t), int(dst[t])) for t in range(len(dst)) if dst[t] >= 0)
+    best, best_cost = None, float("inf")
+    for S in itertools.combinations(B.tolist(), r):
+        for g in itertools.product(A.tolist(), repeat=r):
+            cost = sum(_explicit_fd(X, b, a) for b, a in zip(S, g))
+            if cost < best_cost - 1e-14:
+                best, best_cost = sorted(zip(S, g)), cost
+    assert got == best and all(b in B.tolist() and a in A.tolist() for b, a in got)
+
+
+def test_reverse_direction_counts():
+    offs = np.array([0, 5, 6, 6, 14, 17], dtype=np.int32)              # sizes 5, 1, 0, 8, 3
+    assert O.removal_counts_ratio(offs, 0.5, "b_to_a").tolist() == [2, 0, 0, 4, 1]
+    assert O.removal_counts_ratio(offs, 0.5).tolist() == [2, 0, 0, 4, 1]
+    assert O.removal_counts_ratio(offs, 0.9, "b_to_a").tolist() == [2, 0, 0, 4, 1]   # |B| = floor(v/2) at most
+    assert O.removal_counts_ratio(offs, 0.9).tolist() == [3, 0, 0, 4, 2]             # |A| = ceil(v/2) at most (v = 1: its A)
+    rem, bad = O.removal_counts_target(offs, 1, [7], "b_to_a")
+    assert rem.tolist() == [2, 0, 0, 4, 1] and not bad[0]              # caps 2, 0, 0, 4, 1: every one binds
+    rem, bad = O.removal_counts_target(offs, 1, [8], "b_to_a")
+    assert bad[0] and rem.tolist() == [2, 0, 0, 4, 1]
+    rem, bad = O.removal_counts_target(offs, 1, [8])
+    assert not bad[0] and rem.tolist() == [3, 0, 0, 3, 2]              # caps 3, 0, 0, 4, 2: level 3 meets the budget exactly
