@@ -116,6 +116,18 @@ typedef enum {
   LIGHTKV_MATCH_FULL_PAIRWISE = 2
 } lightkv_match;
 
+/* Which side of a window's bipartite split proposes (Sec. 3.2.1, message-passing paragraph: messages go from A to B,
+   and the reverse direction is defined analogously).  With B_TO_A the tokens at the odd local positions (set B) each
+   offer their lowest-FD edge into set A (ties: the A node earlier in the window), the r_w of them with the lowest FD
+   are merged into their A node, and set A stays: every statement of this header about "A" and "B" then holds with
+   the two sets exchanged (0 <= r_w <= |B_w| = floor(v_w / 2); best_fd / best_dst are written for the B nodes and are
+   +inf / -1 for the A nodes).  Defined for LIGHTKV_MATCH_BEST_PER_A only; with another lightkv_match the calls return
+   LIGHTKV_ERR_UNSUPPORTED. */
+typedef enum {
+  LIGHTKV_DIRECTION_A_TO_B = 0,   /* a zeroed struct: the paper's direction */
+  LIGHTKV_DIRECTION_B_TO_A = 1
+} lightkv_direction;
+
 /* Limits of this build. */
 #define LIGHTKV_MAX_WINDOW_TOKENS 4096   /* tokens in one window                    */
 #define LIGHTKV_MAX_SEQ_TOKENS    16384  /* vision tokens in one sequence           */
@@ -148,7 +160,7 @@ typedef struct lightkv_problem {
                                  LIGHTKV_MATCH_EDGE_TOPK win_remove[w] counts EDGES (0 <= k_w <= |A_w| |B_w|)
                                  and h_win_remove is required; with LIGHTKV_MATCH_FULL_PAIRWISE it is
                                  the most tokens that may leave (0 <= r_w <= ceil(v_w / 2))       */
-  int32_t reserved;           /* must be 0                                                       */
+  int32_t direction;          /* lightkv_direction; 0 (a zeroed struct) = A proposes, B receives    */
   const int32_t *h_cu_vis;    /* HOST [batch+1] vision-token offsets, h_cu_vis[0] = 0            */
   const int32_t *h_cu_txt;    /* HOST [batch+1] prompt-token offsets (may be NULL for XI_GIVEN)  */
   const int32_t *cu_vis;      /* device copy of h_cu_vis                                         */
@@ -219,6 +231,7 @@ typedef enum {
  * Per-window counts r_w (or k_w) on the device, from the window sizes as they are (after earlier stages the windows
  * of a sequence no longer hold equal numbers of tokens).  Every sequence owns n_windows / batch windows.
  *   win_offsets[n_windows+1]  device, from lightkv_build_windows
+ *   direction                 lightkv_direction: which set counts as "A" below (RATIO and TARGET; EDGES: A_TO_B only)
  *   rho                       RATIO / EDGES; a double, so that the floor is the one a host program computes
  *   cu_vis, cu_vis_target     TARGET: device [batch+1] offsets of the sequences now and after the step
  *   win_remove[n_windows]     device, out
@@ -226,7 +239,7 @@ typedef enum {
  *                             than its sets A hold: then every window gives its whole set A), else 0
  */
 lightkv_status lightkv_window_counts(int32_t batch, int32_t n_windows, const int32_t *win_offsets, int32_t mode,
-                                     double rho, const int32_t *cu_vis, const int32_t *cu_vis_target,
+                                     int32_t direction, double rho, const int32_t *cu_vis, const int32_t *cu_vis_target,
                                      int32_t *win_remove, int32_t *status, void *stream);
 
 /*

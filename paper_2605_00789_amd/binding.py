@@ -29,7 +29,7 @@ class _CProblem(C.Structure):
     _fields_ = [
         ("batch", C.c_int32), ("d", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32),
         ("dtype", C.c_int32), ("n_windows", C.c_int32), ("max_window_tokens", C.c_int32), ("metric", C.c_int32),
-        ("match", C.c_int32), ("reserved", C.c_int32),
+        ("match", C.c_int32), ("direction", C.c_int32),
         ("h_cu_vis", C.c_void_p), ("h_cu_txt", C.c_void_p), ("cu_vis", C.c_void_p), ("cu_txt", C.c_void_p),
         ("win_offsets", C.c_void_p), ("win_tokens", C.c_void_p), ("win_remove", C.c_void_p),
         ("h_win_offsets", C.c_void_p), ("h_win_remove", C.c_void_p),
@@ -78,7 +78,7 @@ def _load():
     lib.lightkv_max_window_cells.restype = C.c_int32
     lib.lightkv_max_window_cells.argtypes = [i32, i32, i32, i32]
     lib.lightkv_window_counts.restype = C.c_int
-    lib.lightkv_window_counts.argtypes = [i32, i32, vp, i32, C.c_double, vp, vp, vp, vp, vp]
+    lib.lightkv_window_counts.argtypes = [i32, i32, vp, i32, i32, C.c_double, vp, vp, vp, vp, vp]
     lib.lightkv_select_static.restype = C.c_int
     lib.lightkv_select_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.lightkv_aggregate.restype = C.c_int
@@ -137,6 +137,7 @@ def _ld(t: Optional[torch.Tensor]) -> int:
 
 METRICS = {"cosine": 0, "euclidean": 1, "l2sq": 2}
 MATCH_BEST_PER_A, MATCH_EDGE_TOPK, MATCH_FULL_PAIRWISE = 0, 1, 2
+DIRECTION_A_TO_B, DIRECTION_B_TO_A = 0, 1   # lightkv_direction
 EDGE_MAX_WINDOW_TOKENS = 256   # LIGHTKV_EDGE_MAX_WINDOW_TOKENS
 SELECT_STATIC_MAX_TOKENS = 65536   # LIGHTKV_SELECT_STATIC_MAX_TOKENS
 ONE_STREAM_MAX_TOKENS = 1024   # LIGHTKV_ONE_STREAM_MAX_TOKENS
@@ -147,7 +148,8 @@ class Problem:
 
     def __init__(self, *, batch, d, heads, head_dim, dtype, h_cu_vis, cu_vis, h_cu_txt=None, cu_txt=None,
                  n_windows=0, max_window_tokens=0, win_offsets=None, win_tokens=None, win_remove=None,
-                 h_win_offsets=None, h_win_remove=None, metric="cosine", match=MATCH_BEST_PER_A):
+                 h_win_offsets=None, h_win_remove=None, metric="cosine", match=MATCH_BEST_PER_A,
+                 direction=DIRECTION_A_TO_B):
         self.refs = dict(h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=h_cu_txt, cu_txt=cu_txt,
                          win_offsets=win_offsets, win_tokens=win_tokens, win_remove=win_remove,
                          h_win_offsets=h_win_offsets, h_win_remove=h_win_remove)
@@ -156,7 +158,7 @@ class Problem:
         self.c.dtype = {"f32": F32, "bf16": BF16, F32: F32, BF16: BF16}[dtype]
         self.c.n_windows, self.c.max_window_tokens = n_windows, max_window_tokens
         self.c.metric = METRICS[metric] if isinstance(metric, str) else int(metric)
-        self.c.match, self.c.reserved = int(match), 0
+        self.c.match, self.c.direction = int(match), int(direction)
         for name in ("h_cu_vis", "h_cu_txt", "h_win_offsets", "h_win_remove"):
             setattr(self.c, name, _hptr(self.refs[name]))
         for name in ("cu_vis", "cu_txt", "win_offsets", "win_tokens", "win_remove"):
@@ -211,9 +213,9 @@ def lightkv_max_window_cells(tiles: int, grid_h: int, grid_w: int, w: int) -> in
     return n
 
 
-def lightkv_window_counts(batch, n_windows, win_offsets, mode, win_remove, *, rho=0.0, cu_vis=None, cu_vis_target=None,
-                          status=None, stream=None):
-    _check(_lib.lightkv_window_counts(batch, n_windows, _dptr(win_offsets), int(mode), float(rho), _dptr(cu_vis),
+def lightkv_window_counts(batch, n_windows, win_offsets, mode, win_remove, *, direction=DIRECTION_A_TO_B, rho=0.0,
+                          cu_vis=None, cu_vis_target=None, status=None, stream=None):
+    _check(_lib.lightkv_window_counts(batch, n_windows, _dptr(win_offsets), int(mode), int(direction), float(rho), _dptr(cu_vis),
                                       _dptr(cu_vis_target), _dptr(win_remove), _dptr(status), _stream(stream)),
            "lightkv_window_counts")
 

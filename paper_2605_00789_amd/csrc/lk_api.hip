@@ -20,13 +20,23 @@ struct Checked {
   int64_t sum_remove = 0;   // sum of h_win_remove (when given)
 };
 
+// The window bound the launch plans are made with.  In the reverse direction the receiving side of an odd window is
+// the larger one; planning with the bound rounded up to even makes room for either side (the library's largest
+// window, 4096 tokens, is even).
+int plan_bound(const lightkv_problem *p, int max_window) {
+  return p->direction == LIGHTKV_DIRECTION_B_TO_A ? ((max_window + 1) & ~1) : max_window;
+}
+
 lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool need_txt, Checked &c) {
   if (!p || !p->h_cu_vis || !p->cu_vis) return LIGHTKV_ERR_NULL;
   if (p->batch < 1 || p->d < 1 || p->heads < 1 || p->head_dim < 1 || p->n_windows < 0) return LIGHTKV_ERR_SHAPE;
   if (p->dtype != LIGHTKV_F32 && p->dtype != LIGHTKV_BF16) return LIGHTKV_ERR_UNSUPPORTED;
   if (p->metric < LIGHTKV_METRIC_COSINE || p->metric > LIGHTKV_METRIC_L2SQ) return LIGHTKV_ERR_UNSUPPORTED;
-  if (p->match < LIGHTKV_MATCH_BEST_PER_A || p->match > LIGHTKV_MATCH_FULL_PAIRWISE || p->reserved != 0)
-    return LIGHTKV_ERR_UNSUPPORTED;
+  if (p->match < LIGHTKV_MATCH_BEST_PER_A || p->match > LIGHTKV_MATCH_FULL_PAIRWISE) return LIGHTKV_ERR_UNSUPPORTED;
+  if (p->direction != LIGHTKV_DIRECTION_A_TO_B && p->direction != LIGHTKV_DIRECTION_B_TO_A) return LIGHTKV_ERR_UNSUPPORTED;
+  // the reverse direction is defined for the best edge of every proposing node; an edge list and the full pairwise
+  // visit have no proposing side
+  if (p->direction != LIGHTKV_DIRECTION_A_TO_B && p->match != LIGHTKV_MATCH_BEST_PER_A) return LIGHTKV_ERR_UNSUPPORTED;
   // full pairwise matching runs on the tiled matrix-core kernel only: bf16 rows of whole 64-element k-steps
   if (p->match == LIGHTKV_MATCH_FULL_PAIRWISE && (p->dtype != LIGHTKV_BF16 || p->d % 64 != 0))
     return LIGHTKV_ERR_UNSUPPORTED;
@@ -70,7 +80,7 @@ lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool n
           const int v = p->h_win_offsets[w + 1] - p->h_win_offsets[w];
           const int r = p->h_win_remove[w];
           // tokens of A at most; with the k lowest edges, pairs of the window at most
-          const int cap = (v < 2) ? 0 : (p->match == LIGHTKV_MATCH_EDGE_TOPK ? ((v + 1) / 2) * (v / 2) : (v + 1) / 2);
+          const int cap = (v < 2) ? 0 : (p->match == LIGHTKV_MATCH_EDGE_TOPK ? ((v + 1) / 2) * (v / 2) : side_a(v, p->direction));
           if (r < 0 || r > cap) return LIGHTKV_ERR_REMOVE_COUNT;
           c.sum_remove += r;
         }
@@ -81,6 +91,7 @@ lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool n
       c.max_window = p->max_window_tokens;
     }
     if (c.max_window > LIGHTKV_MAX_WINDOW_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;
+    c.max_window = plan_bound(p, c.max_window);
     if (p->match == LIGHTKV_MATCH_EDGE_TOPK) {
       // the edge list is sized from the host's counts, and the whole |A| x |B| block of a window is ranked in LDS
       if (!p->h_win_offsets || !p->h_win_remove) return LIGHTKV_ERR_NULL;
@@ -164,7 +175,7 @@ lightkv_status select_impl(const lightkv_problem *p, bool from_keys, float *best
   if (launch_select(p->n_windows, c.max_window, p->batch, c.sum_n, p->cu_vis, p->win_offsets, p->win_tokens,
                     p->win_remove, keys, big.mt, big.nt_store, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out,
                     reinterpret_cast<int32_t *>(wsb + l.sel_cnt), reinterpret_cast<int32_t *>(wsb + l.sel_rank),
-                    static_cast<hipStream_t>(stream)) != hipSuccess)
+                    p->direction, static_cast<hipStream_t>(stream)) != hipSuccess)
     return LIGHTKV_ERR_LAUNCH;
   return LIGHTKV_OK;
 }
@@ -261,16 +272,18 @@ int32_t lightkv_max_window_cells(int32_t tiles, int32_t grid_h, int32_t grid_w, 
 }
 
 lightkv_status lightkv_window_counts(int32_t batch, int32_t n_windows, const int32_t *win_offsets, int32_t mode,
-                                     double rho, const int32_t *cu_vis, const int32_t *cu_vis_target,
+                                     int32_t direction, double rho, const int32_t *cu_vis, const int32_t *cu_vis_target,
                                      int32_t *win_remove, int32_t *status, void *stream) {
+  if (direction != LIGHTKV_DIRECTION_A_TO_B && direction != LIGHTKV_DIRECTION_B_TO_A) return LIGHTKV_ERR_UNSUPPORTED;
+  if (direction != LIGHTKV_DIRECTION_A_TO_B && mode == LIGHTKV_COUNT_EDGES) return LIGHTKV_ERR_UNSUPPORTED;
   if (!win_offsets || !win_remove) return LIGHTKV_ERR_NULL;
   if (batch < 1 || n_windows < 0 || n_windows % batch != 0) return LIGHTKV_ERR_SHAPE;
   if (mode < LIGHTKV_COUNT_RATIO || mode > LIGHTKV_COUNT_TARGET) return LIGHTKV_ERR_UNSUPPORTED;
   if (mode == LIGHTKV_COUNT_TARGET && (!cu_vis || !cu_vis_target)) return LIGHTKV_ERR_NULL;
   if (mode != LIGHTKV_COUNT_TARGET && !(rho >= 0.0 && rho <= 1e6)) return LIGHTKV_ERR_SHAPE;   // also refuses NaN
   if (n_windows == 0) return LIGHTKV_OK;
-  if (launch_window_counts(batch, n_windows / batch, win_offsets, mode, rho, cu_vis, cu_vis_target, win_remove, status,
-                           static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (launch_window_counts(batch, n_windows / batch, win_offsets, mode, direction, rho, cu_vis, cu_vis_target, win_remove,
+                           status, static_cast<hipStream_t>(stream)) != hipSuccess)
     return LIGHTKV_ERR_LAUNCH;
   return LIGHTKV_OK;
 }
@@ -327,12 +340,13 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
         const int v = p->h_win_offsets[w + 1] - p->h_win_offsets[w];
         max_window = v > max_window ? v : max_window;
       }
-    c.max_window = max_window;
+    c.max_window = plan_bound(p, max_window);
   }
   FdPlan fd = make_fd_plan(p->n_windows, c.max_window, p->d, c.elem_bytes);
   const XiPlan xp = make_xi_plan(p->batch, p->h_cu_vis, p->h_cu_txt && p->cu_txt ? p->h_cu_txt : nullptr, p->heads, 0);
   FdBigPlan big = make_fd_big_plan(p->n_windows, c.max_window, c.sum_n);
   fd.metric = big.metric = p->metric;
+  fd.dir = big.dir = p->direction;
   const bool use_big = use_big_fd(p, c);
   const bool edge = sel && need_fd && edge_topk(p);
   const bool pairwise = need_fd && full_pairwise(p);
@@ -429,7 +443,7 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
     fd_status = LIGHTKV_ERR_LAUNCH;
   }
   if (fd_dump && fd_status == LIGHTKV_OK &&
-      launch_fd_dump(p->dtype, X, ldx, p->d, p->n_windows, c.max_window, c.sum_n, p->metric, p->win_offsets,
+      launch_fd_dump(p->dtype, X, ldx, p->d, p->n_windows, c.max_window, c.sum_n, p->metric, p->direction, p->win_offsets,
                      p->win_tokens, fd_dump, (long long)fd_dump_floats, s) != hipSuccess)
     fd_status = LIGHTKV_ERR_LAUNCH;
   if (fk && hipStreamWaitEvent(s, fk->event[1], 0) != hipSuccess) return LIGHTKV_ERR_LAUNCH;   // join
@@ -599,7 +613,7 @@ extern "C" lightkv_status lightkv_select_static(const lightkv_problem *p, const 
   if (st != LIGHTKV_OK) return st;
   if (!p->win_remove || !best_fd || !best_dst || !dst || !new_index || !grp_offsets || !grp_src || !cu_vis_out)
     return LIGHTKV_ERR_NULL;
-  if (edge_topk(p)) return LIGHTKV_ERR_UNSUPPORTED;
+  if (edge_topk(p) || full_pairwise(p)) return LIGHTKV_ERR_UNSUPPORTED;
   if (c.sum_n > STATIC_SELECT_MAX_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;   // beyond the static array
   int32_t *base = static_scratch_for_current_device();
   if (!base) return LIGHTKV_ERR_LAUNCH;
@@ -613,7 +627,7 @@ extern "C" lightkv_status lightkv_select_static(const lightkv_problem *p, const 
   }
   if (launch_select(p->n_windows, c.max_window, p->batch, c.sum_n, p->cu_vis, p->win_offsets, p->win_tokens,
                     p->win_remove, nullptr, 0, 0, const_cast<float *>(best_fd), const_cast<int32_t *>(best_dst), dst,
-                    new_index, grp_offsets, grp_src, cu_vis_out, cnt, rank, s) != hipSuccess)
+                    new_index, grp_offsets, grp_src, cu_vis_out, cnt, rank, p->direction, s) != hipSuccess)
     return LIGHTKV_ERR_LAUNCH;
   return LIGHTKV_OK;
 }

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "lk_launch.h"
+
 namespace lk {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;

@@ -23,6 +23,7 @@ struct FdArgs {
   int32_t *best_dst;
   int slot, group, mt, nt, n_tiles, ksplit, n_spans, spans_per_wg;
   int metric;   // 0: 1 - cos, 1: |a - b|, 2: |a - b|^2
+  int dir;      // 0: even list positions propose, 1: odd ones (side_a / pos_a)
 };
 
 // Divergence of a pair from its inner product and squared norms (fp64).  The distances use
@@ -49,8 +50,8 @@ __device__ __forceinline__ WinInfo win_info(const FdArgs &g, int w) {
   if (w < g.n_windows) {
     wi.off = g.win_offsets[w];
     const int v = g.win_offsets[w + 1] - wi.off;
-    wi.nA = (v + 1) >> 1;
-    wi.nB = v >> 1;
+    wi.nA = side_a(v, g.dir);
+    wi.nB = side_b(v, g.dir);
   }
   return wi;
 }
@@ -81,16 +82,16 @@ __device__ __forceinline__ void fd_partial_body(const FdArgs &g, int block_id, c
   if (g.group > 1) {
     const int s = r / g.slot, l = r - s * g.slot;
     const WinInfo wi = win_info(g, tile * g.group + s);
-    if (l < wi.nA) a_tok = checked_token(g, wi.off + 2 * l);
-    if (l < wi.nB) b_tok = checked_token(g, wi.off + 2 * l + 1);
+    if (l < wi.nA) a_tok = checked_token(g, wi.off + pos_a(l, g.dir));
+    if (l < wi.nB) b_tok = checked_token(g, wi.off + pos_b(l, g.dir));
   } else {
     const int per = g.mt * g.nt;
     const int w = tile / per, rem = tile - w * per;
     const int mt = rem / g.nt, nt = rem - mt * g.nt;
     const WinInfo wi = win_info(g, w);
     const int la = mt * 32 + r, lb = nt * 32 + r;
-    if (la < wi.nA) a_tok = checked_token(g, wi.off + 2 * la);
-    if (lb < wi.nB) b_tok = checked_token(g, wi.off + 2 * lb + 1);
+    if (la < wi.nA) a_tok = checked_token(g, wi.off + pos_a(la, g.dir));
+    if (lb < wi.nB) b_tok = checked_token(g, wi.off + pos_b(lb, g.dir));
     need_na = (nt == 0);
     need_nb = (mt == 0);
   }
@@ -237,10 +238,10 @@ __device__ __forceinline__ void fd_tail_select_body(const FdArgs &g, const Small
     if (tid < 32 && (tid & ((1 << shift) - 1)) == 0) {   // first row of a window slot: its removal count
       const int v = m_end - m_off;
       const int cap = (g.group > 1) ? g.slot : 32;
-      int nA = (v + 1) >> 1;
+      int nA = side_a(v, g.dir);
       nA = nA < cap ? nA : cap;
       int rr = m_rem < 0 ? 0 : (m_rem > nA ? nA : m_rem);
-      if ((v >> 1) == 0) rr = 0;
+      if (side_b(v, g.dir) == 0) rr = 0;
       L.slot_r[tid >> shift] = rr;
     }
   }
@@ -345,7 +346,7 @@ inline FdArgs make_fd_args(const FdPlan &plan, int dtype, const void *X, int64_t
   g.win_offsets = win_offsets; g.win_tokens = win_tokens;
   g.partial = partial; g.best_fd = best_fd; g.best_dst = best_dst;
   g.slot = plan.slot; g.group = plan.group; g.mt = plan.mt; g.nt = plan.nt;
-  g.n_tiles = plan.n_tiles; g.ksplit = plan.ksplit; g.metric = plan.metric;
+  g.n_tiles = plan.n_tiles; g.ksplit = plan.ksplit; g.metric = plan.metric; g.dir = plan.dir;
   const int span = (dtype == 1) ? 64 : 32;
   g.n_spans = (d + span - 1) / span;
   g.spans_per_wg = (g.n_spans + plan.ksplit - 1) / plan.ksplit;

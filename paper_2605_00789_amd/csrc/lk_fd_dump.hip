@@ -13,7 +13,7 @@ namespace lk {
 struct DumpArgs {
   const void *X;
   int64_t ldx;
-  int d, n_windows, sum_n, metric, tiles_b;
+  int d, n_windows, sum_n, metric, dir, tiles_b;
   const int32_t *win_offsets, *win_tokens;
   float *out;
   long long capacity;   // floats the caller's buffer holds
@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void fd_dump_kernel(DumpArgs g) {
   const int w = blockIdx.z;
   const int off = g.win_offsets[w];
   const int v = g.win_offsets[w + 1] - off;
-  const int nA = (v + 1) >> 1, nB = v >> 1;
+  const int nA = side_a(v, g.dir), nB = side_b(v, g.dir);
   const int a0 = blockIdx.y * 16, b0 = blockIdx.x * 16;
   if (a0 >= nA || b0 >= nB) return;   // uniform
   // where this window's block starts: the pairs of the windows before it
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void fd_dump_kernel(DumpArgs g) {
   const long long base = part[0];
   const int la = a0 + (int)(threadIdx.x >> 4), lb = b0 + (int)(threadIdx.x & 15);
   if (la >= nA || lb >= nB) return;
-  const int ta = g.win_tokens[off + 2 * la], tb = g.win_tokens[off + 2 * lb + 1];
+  const int ta = g.win_tokens[off + pos_a(la, g.dir)], tb = g.win_tokens[off + pos_b(lb, g.dir)];
   const long long idx = base + (long long)la * nB + lb;
   if (idx >= g.capacity) return;
   if ((unsigned)ta >= (unsigned)g.sum_n || (unsigned)tb >= (unsigned)g.sum_n) { g.out[idx] = __uint_as_float(0x7fc00000u); return; }
@@ -80,11 +80,11 @@ __global__ __launch_bounds__(256) void fd_dump_kernel(DumpArgs g) {
 }
 
 hipError_t launch_fd_dump(int dtype, const void *X, int64_t ldx, int d, int n_windows, int max_window, int sum_n,
-                          int metric, const int32_t *win_offsets, const int32_t *win_tokens, float *out,
+                          int metric, int dir, const int32_t *win_offsets, const int32_t *win_tokens, float *out,
                           long long capacity, hipStream_t stream) {
   if (n_windows == 0 || sum_n == 0 || max_window < 2) return hipSuccess;
   DumpArgs g{};
-  g.X = X; g.ldx = ldx; g.d = d; g.n_windows = n_windows; g.sum_n = sum_n; g.metric = metric;
+  g.X = X; g.ldx = ldx; g.d = d; g.n_windows = n_windows; g.sum_n = sum_n; g.metric = metric; g.dir = dir;
   g.win_offsets = win_offsets; g.win_tokens = win_tokens; g.out = out; g.capacity = capacity;
   const int ta = ((max_window + 1) / 2 + 15) / 16, tb = (max_window / 2 + 15) / 16;
   if (n_windows > 65535) return hipErrorInvalidValue;   // windows ride in the z dimension of the grid

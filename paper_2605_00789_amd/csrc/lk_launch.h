@@ -6,6 +6,15 @@
 
 namespace lk {
 
+// The bipartite split of a window's list (Sec. 3.2.1 Step 1) and the direction of the merge (message-passing
+// paragraph: the reverse direction is defined analogously).  dir 0: the tokens at list positions 0, 2, 4, ... propose
+// and merge into the tokens at positions 1, 3, 5, ...; dir 1: the odd positions propose, the even ones receive.  In
+// the kernels "A" is always the proposing side and "B" the receiving side.
+__host__ __device__ __forceinline__ int side_a(int v, int dir) { return (v + 1 - dir) >> 1; }
+__host__ __device__ __forceinline__ int side_b(int v, int dir) { return (v + dir) >> 1; }
+__host__ __device__ __forceinline__ int pos_a(int i, int dir) { return 2 * i + dir; }
+__host__ __device__ __forceinline__ int pos_b(int j, int dir) { return 2 * j + 1 - dir; }
+
 // ---- feature divergence (Steps 1-2) ------------------------------------------------------
 // The |A_w| x |B_w| cosine blocks are cut into 32x32 tiles.  Small windows are packed several to
 // a tile (block diagonal): `slot` rows/cols per window, `group` windows per tile.  Large windows
@@ -20,6 +29,8 @@ struct FdPlan {
   int ksplit;
   size_t partial_floats;   // n_tiles * ksplit * FD_TILE_FLOATS
   int metric;              // 0 cosine FD, 1 Euclidean, 2 squared L2 (set by the caller after planning)
+  int dir;                 // 0: even list positions propose, 1: odd ones (set by the caller after planning; a plan for
+                           // dir 1 is made with the window bound rounded up to even, so that both sides fit)
 };
 constexpr int FD_TOK_OFFSET = 32 * 32 + 32 + 32;    // dots, |a|^2 partials, |b|^2 partials ...
 constexpr int FD_TILE_FLOATS = FD_TOK_OFFSET + 64;  // ... then (slice 0 only) the tokens of the 32 rows and 32 columns
@@ -33,7 +44,7 @@ hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, const
                                 hipStream_t stream);
 
 // per-window counts from a ratio (mode 0: tokens, 1: edges) or from per-sequence target lengths (mode 2)
-hipError_t launch_window_counts(int batch, int win_per_seq, const int32_t *win_offsets, int mode, double rho,
+hipError_t launch_window_counts(int batch, int win_per_seq, const int32_t *win_offsets, int mode, int dir, double rho,
                                 const int32_t *cu_vis, const int32_t *cu_target, int32_t *win_remove, int32_t *status,
                                 hipStream_t stream);
 
@@ -64,7 +75,7 @@ hipError_t launch_edge_fill(int sum_k, int sum_n, const int32_t *edges, const in
 
 // Debug dump of the FD of every pair (lk_fd_dump.hip); at most 65535 windows.
 hipError_t launch_fd_dump(int dtype, const void *X, int64_t ldx, int d, int n_windows, int max_window, int sum_n,
-                          int metric, const int32_t *win_offsets, const int32_t *win_tokens, float *out,
+                          int metric, int dir, const int32_t *win_offsets, const int32_t *win_tokens, float *out,
                           long long capacity, hipStream_t stream);
 
 // Large windows (compute bound): LDS-tiled MFMA GEMM with the row arg-min fused into its epilogue.
@@ -77,6 +88,7 @@ struct FdBigPlan {
   size_t key_bytes;  // [nt_store][sum_n] packed keys (FD bits << 32 | B token): per column tile, the best key of the A
                      // row at every position of the window lists; all-ones where nothing was offered
   int metric;        // as in FdPlan
+  int dir;           // as in FdPlan
 };
 constexpr int FD_BIG_TILE = 96;            // rows and columns of a workgroup tile
 constexpr int FD_BIG_KEYS_PER_TILE_MAX_NT = 4;   // up to this many column tiles per window, each keeps keys of its own
@@ -144,7 +156,7 @@ hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int su
                          const int32_t *win_offsets, const int32_t *win_tokens, const int32_t *win_remove,
                          const unsigned long long *keys, int key_mt, int key_nt, float *best_fd, int32_t *best_dst, int32_t *dst,
                          int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out, int32_t *cnt,
-                         int32_t *src_rank, hipStream_t stream);
+                         int32_t *src_rank, int dir, hipStream_t stream);
 
 // the scan half of lightkv_select alone (dst, cnt, src_rank already written)
 hipError_t launch_select_scan(int batch, int sum_n, const int32_t *cu_vis, const int32_t *dst, int32_t *new_index,

@@ -86,7 +86,7 @@ extern "C" lightkv_status lightkv_compress_schedule(const lightkv_stage *stages,
       rc = lightkv_build_windows(p->batch, p->h_cu_vis, p->cu_vis, posi, tiles, grid_h, grid_w, st.w, st.win_offsets,
                                  st.win_tokens, main);
       if (rc == LIGHTKV_OK && st.cu_vis_target)
-        rc = lightkv_window_counts(p->batch, p->n_windows, st.win_offsets, LIGHTKV_COUNT_TARGET, 0.0, p->cu_vis,
+        rc = lightkv_window_counts(p->batch, p->n_windows, st.win_offsets, LIGHTKV_COUNT_TARGET, p->direction, 0.0, p->cu_vis,
                                    st.cu_vis_target, st.win_remove, st.status, main);
     }
     windows_pending = false;
@@ -113,7 +113,8 @@ extern "C" lightkv_status lightkv_compress_schedule(const lightkv_stage *stages,
       // ... and their counts: the next stage's budget over the windows as they now are (cu_vis_out of this stage is
       // the next stage's cu_vis)
       if (rc == LIGHTKV_OK && nx.cu_vis_target)
-        rc = lightkv_window_counts(nx.problem.batch, nx.problem.n_windows, nx.win_offsets, LIGHTKV_COUNT_TARGET, 0.0,
+        rc = lightkv_window_counts(nx.problem.batch, nx.problem.n_windows, nx.win_offsets, LIGHTKV_COUNT_TARGET,
+                                   nx.problem.direction, 0.0,
                                    st.cu_vis_out, nx.cu_vis_target, nx.win_remove, nx.status, wsx);
       if (win_forked && hipEventRecord(h->event[EV_JOIN_WIN], h->stream[1]) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
       windows_pending = true;

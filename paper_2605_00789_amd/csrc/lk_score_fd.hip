@@ -108,16 +108,16 @@ __global__ __launch_bounds__(FD_THREADS) void fd_epilogue_kernel(FdArgs g) {
     if (ob < best || (ob == best && oc < best_c)) { best = ob; best_c = oc; }
   }
   if (sub == 0 && a_valid) {
-    const int a_tok = checked_token(g, wi.off + 2 * l);
+    const int a_tok = checked_token(g, wi.off + pos_a(l, g.dir));
     if (a_tok >= 0) {
       // no finite score at all (NaN rows): propose the first B node with FD = +inf, so that counts stay exact
       const bool has = best_c != 0x7fffffff;
       g.best_fd[a_tok] = has ? (float)best : __uint_as_float(0x7f800000u);
-      g.best_dst[a_tok] = (wi.nB > 0) ? checked_token(g, wi.off + 2 * (has ? best_c : 0) + 1) : -1;
+      g.best_dst[a_tok] = (wi.nB > 0) ? checked_token(g, wi.off + pos_b(has ? best_c : 0, g.dir)) : -1;
     }
   }
   if (sub == 1 && l < wi.nB) {   // B rows carry no proposal
-    const int b_tok = checked_token(g, wi.off + 2 * l + 1);
+    const int b_tok = checked_token(g, wi.off + pos_b(l, g.dir));
     if (b_tok >= 0) {
       g.best_fd[b_tok] = __uint_as_float(0x7f800000u);
       g.best_dst[b_tok] = -1;

@@ -45,6 +45,7 @@ struct BigArgs {
   int mt, nt;
   int metric;                    // 0: 1 - cos, 1: |a - b|, 2: |a - b|^2
   int mt2, nt2;                  // fd_pair_kernel: 192 x 192 tiles per window along rows and columns
+  int dir;                       // bipartite kernels: 0 even list positions propose, 1 odd ones (side_a / pos_a)
 };
 
 // ---- |x|^2 per token, summed in fp32 ----------------------------------------------------------------------------
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
   const int mt = in_panel / pw, nt = panel * PW + (in_panel - mt * pw);
   const int off = g.win_offsets[w];
   const int v = g.win_offsets[w + 1] - off;
-  const int nA = (v + 1) >> 1, nB = v >> 1;
+  const int nA = side_a(v, g.dir), nB = side_b(v, g.dir);
   const int row0 = mt * BIG_TM, col0 = nt * BIG_TM;
   if (row0 >= nA || col0 >= nB) return;
 
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
     int la = row0 + p * 16 + srow, lb = col0 + p * 16 + srow;
     la = la < nA ? la : nA - 1;                 // padding rows repeat the last valid one; never read back
     lb = lb < nB ? lb : nB - 1;
-    int ta = g.win_tokens[off + 2 * la], tb = g.win_tokens[off + 2 * lb + 1];
+    int ta = g.win_tokens[off + pos_a(la, g.dir)], tb = g.win_tokens[off + pos_b(lb, g.dir)];
     ta = ((unsigned)ta < (unsigned)g.sum_n) ? ta : 0;
     tb = ((unsigned)tb < (unsigned)g.sum_n) ? tb : 0;
     offa[p] = (uint32_t)ta * (uint32_t)g.ldx * 2u + (uint32_t)schunk * 16u;
@@ -142,7 +143,8 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
     const bool is_b = tid >= BIG_TM;
     const int l = (is_b ? col0 : row0) + (is_b ? tid - BIG_TM : tid);
     const int lim = is_b ? nB : nA;
-    const int t = g.win_tokens[off + 2 * (l < lim ? l : lim - 1) + (is_b ? 1 : 0)];
+    const int lc = l < lim ? l : lim - 1;
+    const int t = g.win_tokens[off + (is_b ? pos_b(lc, g.dir) : pos_a(lc, g.dir))];
     const bool ok = l < lim && (unsigned)t < (unsigned)g.sum_n;
     e_sq = g.sq[ok ? t : 0];
     e_tok = ok ? t : -1;
@@ -346,7 +348,7 @@ __global__ __launch_bounds__(BIG_THREADS) void fd_big_kernel(BigArgs g) {
   // With many column tiles per window that minimum is taken here instead, by one integer atomicMin per row and tile
   // on a single key per position (order independent, so still bit-reproducible).
   if (tid < BIG_TM && row0 + tid < nA) {
-    const size_t pos = (size_t)(off + 2 * (row0 + tid));
+    const size_t pos = (size_t)(off + pos_a(row0 + tid, g.dir));
     if (g.nt_store > 1 || g.nt == 1) g.cand[(size_t)nt * (size_t)g.sum_n + pos] = row_key[tid];
     else if (row_key[tid] != ~0ull) atomicMin(&g.cand[pos], row_key[tid]);
   }
@@ -359,11 +361,11 @@ __global__ __launch_bounds__(256) void fd_big_finalize_kernel(BigArgs g, int chu
   const int w = blockIdx.x / chunks_per_window, c = blockIdx.x - w * chunks_per_window;
   const int off = g.win_offsets[w];
   const int v = g.win_offsets[w + 1] - off;
-  const int n_col = fd_big_col_tiles(v >> 1, g.nt_store);
+  const int n_col = fd_big_col_tiles(side_b(v, g.dir), g.nt_store);
   for (int t = c * 256 + (int)threadIdx.x; t < v; t += chunks_per_window * 256) {
     const int tok = g.win_tokens[off + t];
     if ((unsigned)tok >= (unsigned)g.sum_n) continue;
-    const bool scored = !(t & 1) && (t >> 1) < g.mt * FD_BIG_TILE;
+    const bool scored = (t & 1) == g.dir && (t >> 1) < g.mt * FD_BIG_TILE;
     const unsigned long long key = scored ? fd_big_best_key(g.cand, g.sum_n, off + t, n_col) : ~0ull;
     g.best_fd[tok] = key == ~0ull ? __uint_as_float(0x7f800000u) : __uint_as_float((unsigned)(key >> 32));
     g.best_dst[tok] = key == ~0ull ? -1 : (int)(key & 0xffffffffu);
@@ -727,7 +729,7 @@ hipError_t launch_fd_big(const FdBigPlan &plan, const void *X, int64_t ldx, int 
   g.X = X; g.ldx = ldx; g.d = d; g.n_windows = n_windows; g.sum_n = sum_n;
   g.win_offsets = win_offsets; g.win_tokens = win_tokens;
   g.cand = keys; g.best_fd = best_fd; g.best_dst = best_dst;
-  g.mt = plan.mt; g.nt = plan.nt; g.metric = plan.metric;
+  g.mt = plan.mt; g.nt = plan.nt; g.metric = plan.metric; g.dir = plan.dir;
   g.sq = x_sqnorm ? x_sqnorm : sq_ws; g.sq_out = sq_ws;
   g.nt_store = plan.nt_store;
   g.reset_keys = plan.nt_store == 1 && plan.nt > 1;   // one key per position, reached by atomicMin: start from all-ones

@@ -24,7 +24,8 @@ struct SelArgs {
   const unsigned long long *best_key;   // optional: packed keys of the tiled FD kernel, [column tile][list position]
   int key_mt, key_nt;                   // tiles per window that kernel was planned with
   int32_t *dst, *new_index, *grp_offsets, *grp_src, *cu_vis_out, *cnt, *src_rank;
-  int cap;   // power of two >= the largest |A|
+  int cap;   // power of two >= the larger side of the largest window
+  int dir;   // 0: even list positions propose, 1: odd ones (side_a / pos_a)
 };
 
 
@@ -64,30 +65,30 @@ __global__ __launch_bounds__(COUNT_MAX_A * SEGS) void select_window_kernel(SelAr
   const int w = blockIdx.x;
   const int off = g.win_offsets[w];
   const int v = g.win_offsets[w + 1] - off;
-  int nA = (v + 1) >> 1;
-  const int nB = v >> 1;
   const int cap = g.cap < COUNT_MAX_A ? g.cap : COUNT_MAX_A;
-  if (nA > cap) nA = cap;                     // window larger than the caller's bound: surplus rows stay
+  const int v_in = v < 2 * cap ? v : 2 * cap;   // window larger than the caller's bound: the surplus tokens stay
+  const int nA = side_a(v_in, g.dir), nB = side_b(v_in, g.dir);
   int r = g.win_remove[w];
   r = r < 0 ? 0 : (r > nA ? nA : r);
   if (nB == 0) r = 0;
   const int la = threadIdx.x % COUNT_MAX_A, seg = threadIdx.x / COUNT_MAX_A;
-  for (int t = 2 * nA + (int)threadIdx.x; t < v; t += COUNT_MAX_A * SEGS) {
+  for (int t = v_in + (int)threadIdx.x; t < v; t += COUNT_MAX_A * SEGS) {
     const int tok = g.win_tokens[off + t];
     if ((unsigned)tok < (unsigned)g.sum_n) {
       g.dst[tok] = -1; g.cnt[tok] = 0; g.src_rank[tok] = 0;
       publish(g, tok, __uint_as_float(0x7f800000u), -1);
     }
   }
-  const bool has_a = la < nA, has_b = la < nB && 2 * la + 1 < 2 * nA;
-  int a_tok = g.win_tokens[off + 2 * (has_a ? la : 0)];
-  int b_tok = g.win_tokens[off + (has_b ? 2 * la + 1 : 0)];
-  const int first_b = g.win_tokens[off + (nB > 0 ? 1 : 0)];
+  const bool has_a = la < nA, has_b = la < nB;
+  const int a_pos = has_a ? pos_a(la, g.dir) : 0;
+  int a_tok = g.win_tokens[off + a_pos];
+  int b_tok = g.win_tokens[off + (has_b ? pos_b(la, g.dir) : 0)];
+  const int first_b = g.win_tokens[off + (nB > 0 ? pos_b(0, g.dir) : 0)];
   if (!has_a || (unsigned)a_tok >= (unsigned)g.sum_n) a_tok = -1;
   if (!has_b || (unsigned)b_tok >= (unsigned)g.sum_n) b_tok = -1;
   float fd;
   int prop;   // the proposal of this A node, or the first B node of the window
-  proposal_of(g, a_tok >= 0 ? a_tok : 0, off + 2 * (has_a ? la : 0), has_a ? la : 0, fd_big_col_tiles(nB, g.key_nt), fd, prop);
+  proposal_of(g, a_tok >= 0 ? a_tok : 0, off + a_pos, has_a ? la : 0, fd_big_col_tiles(nB, g.key_nt), fd, prop);
   if (seg == 0) {
     publish(g, a_tok, fd, prop);
     publish(g, b_tok, __uint_as_float(0x7f800000u), -1);
@@ -177,12 +178,11 @@ __global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelA
   const int w = blockIdx.x / blocks_per_window, rb = blockIdx.x - w * blocks_per_window;
   const int off = g.win_offsets[w];
   const int v = g.win_offsets[w + 1] - off;
-  int nA = (v + 1) >> 1;
-  const int nB = v >> 1;
-  if (nA > g.cap) nA = g.cap;
-  if (rb * RANK_ROWS >= nA) return;
+  const int v_in = v < 2 * g.cap ? v : 2 * g.cap;
+  const int nA = side_a(v_in, g.dir), nB = side_b(v_in, g.dir);
+  if (rb * RANK_ROWS >= (nA > nB ? nA : nB)) return;
   if (MODE == 0 && rb == 0) {   // tokens of a window beyond the caller's bound stay
-    for (int t = 2 * nA + (int)threadIdx.x; t < v; t += RANK_ROWS * RANK_SEGS) {
+    for (int t = v_in + (int)threadIdx.x; t < v; t += RANK_ROWS * RANK_SEGS) {
       const int tok = g.win_tokens[off + t];
       if ((unsigned)tok < (unsigned)g.sum_n) {
         g.dst[tok] = -1; g.cnt[tok] = 0; g.src_rank[tok] = 0;
@@ -199,14 +199,15 @@ __global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelA
   const int seg_len = ((nA + RANK_SEGS - 1) / RANK_SEGS + 3) & ~3;   // entries per segment, a multiple of 4
   for (int la0 = 0; la0 < seg_len * RANK_SEGS; la0 += RANK_ROWS * RANK_SEGS) {
     const int la = la0 + tid;
-    const int tok = g.win_tokens[off + 2 * (la < nA ? la : nA - 1)];
+    const int lc = la < nA ? la : (nA > 0 ? nA - 1 : 0);
+    const int lpos = nA > 0 ? pos_a(lc, g.dir) : 0;   // (a window without a proposing node: position 0, value unused)
+    const int tok = g.win_tokens[off + lpos];
     const bool ok = (unsigned)tok < (unsigned)g.sum_n;
     uint32_t val;
     if (MODE == 0) {
       float fd;
       int unused;
-      const int lc = la < nA ? la : nA - 1;
-      proposal_of(g, ok ? tok : 0, off + 2 * lc, lc, fd_big_col_tiles(nB, g.key_nt), fd, unused);
+      proposal_of(g, ok ? tok : 0, off + lpos, lc, fd_big_col_tiles(nB, g.key_nt), fd, unused);
       if (!ok || !(fd >= 0.f)) fd = __uint_as_float(0x7f800000u);   // NaN or negative never wins
       val = f32_order_key(fd);
     } else {
@@ -219,17 +220,18 @@ __global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelA
   const int row = tid & (RANK_ROWS - 1), seg = tid / RANK_ROWS;
   const int la = rb * RANK_ROWS + row;
   const bool has_a = la < nA, has_b = la < nB;
-  int a_tok = g.win_tokens[off + 2 * (has_a ? la : 0)];
-  int b_tok = g.win_tokens[off + (has_b ? 2 * la + 1 : 0)];
+  const int a_pos = has_a ? pos_a(la, g.dir) : 0;
+  int a_tok = g.win_tokens[off + a_pos];
+  int b_tok = g.win_tokens[off + (has_b ? pos_b(la, g.dir) : 0)];
   if (!has_a || (unsigned)a_tok >= (unsigned)g.sum_n) a_tok = -1;
   if (!has_b || (unsigned)b_tok >= (unsigned)g.sum_n) b_tok = -1;
   int prop = -1;
   if (MODE == 0 && seg == 0) {   // the proposal of this A node, or the first B node of the window
     float fd;
-    proposal_of(g, a_tok >= 0 ? a_tok : 0, off + 2 * (has_a ? la : 0), has_a ? la : 0, fd_big_col_tiles(nB, g.key_nt), fd, prop);
+    proposal_of(g, a_tok >= 0 ? a_tok : 0, off + a_pos, has_a ? la : 0, fd_big_col_tiles(nB, g.key_nt), fd, prop);
     publish(g, a_tok, fd, prop);
     publish(g, b_tok, __uint_as_float(0x7f800000u), -1);
-    const int first_b = g.win_tokens[off + (nB > 0 ? 1 : 0)];
+    const int first_b = g.win_tokens[off + (nB > 0 ? pos_b(0, g.dir) : 0)];
     if (a_tok < 0) prop = -1;
     else if ((unsigned)prop >= (unsigned)g.sum_n) prop = (nB > 0 && (unsigned)first_b < (unsigned)g.sum_n) ? first_b : -1;
   }
@@ -470,15 +472,15 @@ hipError_t launch_select(int n_windows, int max_window_tokens, int batch, int su
                          const int32_t *win_offsets, const int32_t *win_tokens, const int32_t *win_remove,
                          const unsigned long long *keys, int key_mt, int key_nt, float *best_fd, int32_t *best_dst,
                          int32_t *dst, int32_t *new_index, int32_t *grp_offsets, int32_t *grp_src, int32_t *cu_vis_out,
-                         int32_t *cnt, int32_t *src_rank, hipStream_t stream) {
+                         int32_t *cnt, int32_t *src_rank, int dir, hipStream_t stream) {
   SelArgs g{};
-  g.best_key = keys; g.key_mt = key_mt; g.key_nt = key_nt;
+  g.best_key = keys; g.key_mt = key_mt; g.key_nt = key_nt; g.dir = dir;
   g.n_windows = n_windows; g.batch = batch; g.sum_n = sum_n;
   g.cu_vis = cu_vis; g.win_offsets = win_offsets; g.win_tokens = win_tokens; g.win_remove = win_remove;
   g.best_fd = best_fd; g.best_dst = best_dst;
   g.dst = dst; g.new_index = new_index; g.grp_offsets = grp_offsets; g.grp_src = grp_src;
   g.cu_vis_out = cu_vis_out; g.cnt = cnt; g.src_rank = src_rank;
-  const int maxA = (max_window_tokens + 1) / 2;
+  const int maxA = (max_window_tokens + 1) / 2;   // (dir 1: the caller hands in an even bound, so this covers both sides)
   g.cap = maxA > 1 ? maxA : 1;
   if (n_windows > 0) {
     hipError_t e;

@@ -231,7 +231,7 @@ constexpr int CNT_CACHE = 8192;   // window caps kept in LDS (16 KB)
 struct CountArgs {
   const int32_t *win_offsets, *cu_vis, *cu_target;
   int32_t *win_remove, *status;
-  int win_per_seq, mode;
+  int win_per_seq, mode, dir;
   double rho;
 };
 
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(CNT_THREADS) void window_counts_kernel(CountArgs g)
     for (int w = tid; w < W; w += CNT_THREADS) {
       const long long v = g.win_offsets[w0 + w + 1] - g.win_offsets[w0 + w];
       long long r, cap;
-      if (g.mode == 0) { r = (long long)floor(g.rho * (double)v + 1e-9); cap = (v + 1) / 2; }
+      if (g.mode == 0) { r = (long long)floor(g.rho * (double)v + 1e-9); cap = side_a((int)v, g.dir); }
       else             { r = (long long)floor(g.rho * (double)v / 2.0 + 1e-9); cap = ((v + 1) / 2) * (v / 2); }
       r = r < 0 ? 0 : (r > cap ? cap : r);
       g.win_remove[w0 + w] = (int)r;
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(CNT_THREADS) void window_counts_kernel(CountArgs g)
   __shared__ uint16_t cap_lds[CNT_CACHE];
   auto cap_mem = [&](int w) {
     const int v = g.win_offsets[w0 + w + 1] - g.win_offsets[w0 + w];
-    const int c = v >= 2 ? (v + 1) >> 1 : 0;
+    const int c = v >= 2 ? side_a(v, g.dir) : 0;   // the proposing side; a single token has nobody to merge into
     return c < 65535 ? c : 65535;
   };
   for (int w = tid; w < W && w < CNT_CACHE; w += CNT_THREADS) cap_lds[w] = (uint16_t)cap_mem(w);
@@ -319,12 +319,12 @@ __global__ __launch_bounds__(CNT_THREADS) void window_counts_kernel(CountArgs g)
   }
 }
 
-hipError_t launch_window_counts(int batch, int win_per_seq, const int32_t *win_offsets, int mode, double rho,
+hipError_t launch_window_counts(int batch, int win_per_seq, const int32_t *win_offsets, int mode, int dir, double rho,
                                 const int32_t *cu_vis, const int32_t *cu_target, int32_t *win_remove, int32_t *status,
                                 hipStream_t stream) {
   CountArgs g{};
   g.win_offsets = win_offsets; g.cu_vis = cu_vis; g.cu_target = cu_target; g.win_remove = win_remove; g.status = status;
-  g.win_per_seq = win_per_seq; g.mode = mode; g.rho = rho;
+  g.win_per_seq = win_per_seq; g.mode = mode; g.dir = dir; g.rho = rho;
   hipLaunchKernelGGL(window_counts_kernel, dim3(batch), dim3(CNT_THREADS), 0, stream, g);
   return hipGetLastError();
 }

@@ -60,8 +60,10 @@ class StageBuffers:
 class CompressionPipeline:
     def __init__(self, *, dtype: str, batch: int, d: int, heads: int, head_dim: int, tiles: int, grid_h: int,
                  grid_w: int, cu_txt: np.ndarray, windows_per_axis: Sequence[int], targets: Sequence[int],
-                 device="cuda:0", fused: bool = True, metric: str = "cosine"):
+                 device="cuda:0", fused: bool = True, metric: str = "cosine", direction: str = "a_to_b"):
         self.dtype, self.batch, self.d, self.heads, self.head_dim = dtype, batch, d, heads, head_dim
+        self.direction = direction   # "b_to_a": the reverse direction (LIGHTKV_DIRECTION_B_TO_A)
+        self._dir = {"a_to_b": B.DIRECTION_A_TO_B, "b_to_a": B.DIRECTION_B_TO_A}[direction]
         self.tiles, self.grid_h, self.grid_w = tiles, grid_h, grid_w
         self.device = torch.device(device)
         self.fused = fused
@@ -91,7 +93,7 @@ class CompressionPipeline:
             prob = B.Problem(batch=batch, d=d, heads=heads, head_dim=head_dim, dtype=dtype, h_cu_vis=h_cu,
                              cu_vis=cu, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt, n_windows=n_windows,
                              max_window_tokens=bound, win_offsets=win_offsets, win_tokens=win_tokens,
-                             win_remove=win_remove, h_win_remove=None, metric=metric)
+                             win_remove=win_remove, h_win_remove=None, metric=metric, direction=self._dir)
             ws_bytes = max(ws_bytes, B.lightkv_workspace_size(prob))
             st = StageBuffers(
                 n_in=n_in, n_out=n_out, w=w, problem=prob, h_cu_vis=h_cu, cu_vis=cu, win_offsets=win_offsets,
@@ -156,7 +158,7 @@ class CompressionPipeline:
             B.lightkv_build_windows(self.batch, st.h_cu_vis, st.cu_vis, pos, self.tiles, self.grid_h, self.grid_w, st.w,
                                     st.win_offsets, st.win_tokens, stream=main)
             B.lightkv_window_counts(self.batch, p.c.n_windows, st.win_offsets, B.COUNT_TARGET, st.win_remove,
-                                    cu_vis=st.cu_vis, cu_vis_target=st.cu_target, status=st.status, stream=main)
+                                    direction=self._dir, cu_vis=st.cu_vis, cu_vis_target=st.cu_target, status=st.status, stream=main)
         if one_stream:
             B.lightkv_score_select(p, X, Q, K if score_K is None else score_K, xi, st.best_fd, st.best_dst, st.dst,
                                    st.new_index, st.grp_offsets, st.grp_src, st.cu_vis_out, self.ws, xi_mode=xi_mode,
@@ -178,7 +180,7 @@ class CompressionPipeline:
                                          self.grid_h, self.grid_w, nx.w, nx.win_offsets, nx.win_tokens,
                                          stream=self.side2)
             B.lightkv_window_counts(self.batch, nx.problem.c.n_windows, nx.win_offsets, B.COUNT_TARGET, nx.win_remove,
-                                    cu_vis=st.cu_vis_out, cu_vis_target=nx.cu_target, status=nx.status, stream=self.side2)
+                                    direction=self._dir, cu_vis=st.cu_vis_out, cu_vis_target=nx.cu_target, status=nx.status, stream=self.side2)
         if xi_given is None and not one_stream:
             main.wait_stream(self.side)                                   # join: the merge needs xi
         stream = main

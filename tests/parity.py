@@ -75,6 +75,7 @@ def check_stage(pipe, s: int, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_mode=0, lse
     rep = StageReport(stage=s, n_in=st_cfg.n_in, n_out=st_cfg.n_out)
     bf16 = dtype == "bf16"
     metric = getattr(pipe, "metric", "cosine")
+    direction = getattr(pipe, "direction", "a_to_b")   # "b_to_a": A below is the proposing set B, Bn the receiving set A
 
     # ---- windows: exact
     cu_vis = st_cfg.h_cu_vis
@@ -83,7 +84,7 @@ def check_stage(pipe, s: int, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_mode=0, lse
     np.testing.assert_array_equal(g["win_tokens"][:len(wt)], wt, err_msg="win_tokens")
     # per-window counts: the stage's token budget spread over the windows as they are (exact)
     n_seq = np.diff(np.asarray(cu_vis, dtype=np.int64))
-    rem, infeasible = O.removal_counts_target(wo, batch, n_seq - st_cfg.n_out)
+    rem, infeasible = O.removal_counts_target(wo, batch, n_seq - st_cfg.n_out, direction)
     assert not infeasible.any(), "the stage's budget cannot be met by these windows"
     np.testing.assert_array_equal(st.win_remove.cpu().numpy()[:len(rem)], rem, err_msg="win_remove")
     np.testing.assert_array_equal(st.status.cpu().numpy(), np.zeros(batch, dtype=np.int32), err_msg="status")
@@ -110,9 +111,9 @@ def check_stage(pipe, s: int, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_mode=0, lse
     exp_new_removed = 0
     for w in range(len(wo) - 1):
         toks = wt[wo[w]:wo[w + 1]]
-        A, Bn = O.split_window(toks)
-        if len(Bn) == 0:
-            assert np.all(g["best_dst"][A] == -1) and np.all(np.isinf(g["best_fd"][A]))
+        A, Bn = O.split_window(toks, direction)
+        if len(Bn) == 0 or len(A) == 0:
+            assert np.all(g["best_dst"][toks] == -1) and np.all(np.isinf(g["best_fd"][toks]))
             assert np.all(g["dst"][toks] == -1)
             continue
         fd = O.feature_divergence(X64[A], X64[Bn], metric)        # oracle's dense FD block (fp64)
@@ -199,13 +200,14 @@ def check_stage(pipe, s: int, Xs, Ks, Vs, Qs, pos, dtype: str, *, xi_mode=0, lse
     return rep, outs
 
 
-def check_workload(wl, pipe=None, stages=None, fused=True, metric="cosine"):
+def check_workload(wl, pipe=None, stages=None, fused=True, metric="cosine", direction="a_to_b"):
     """Runs all stages of a workload teacher-forced; returns the per-stage reports."""
     from paper_2605_00789_amd import CompressionPipeline
     if pipe is None:
         pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
                                    tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
-                                   windows_per_axis=wl.windows_per_axis, targets=wl.targets, fused=fused, metric=metric)
+                                   windows_per_axis=wl.windows_per_axis, targets=wl.targets, fused=fused, metric=metric,
+                                   direction=direction)
     X, K, V, pos = wl.X, wl.K, wl.V, wl.pos
     reports = []
     for s in range(wl.stages if stages is None else stages):

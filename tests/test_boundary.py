@@ -77,7 +77,11 @@ def test_workspace_size_and_descriptor_validation(B):
     assert _ws_size(B, _problem(B, match=2))[0] == 0
     assert _ws_size(B, _problem(B, match=2, dtype=0))[0] == 5
     assert _ws_size(B, _problem(B, match=2, d=96, heads=3))[0] == 5
-    assert _ws_size(B, _problem(B, reserved=1))[0] == 5
+    # lightkv_direction: the reverse direction exists for one proposal per node only
+    assert _ws_size(B, _problem(B, direction=1))[0] == 0
+    assert _ws_size(B, _problem(B, direction=2))[0] == 5 and _ws_size(B, _problem(B, direction=-1))[0] == 5
+    assert _ws_size(B, _problem(B, direction=1, match=2))[0] == 5
+    assert _ws_size(B, _problem(B, direction=1, match=1, h_win_remove=np.array([1, 1], dtype=np.int32)))[0] == 5
     st_e, n_e = _ws_size(B, _problem(B, match=1, h_win_remove=np.array([4, 3], dtype=np.int32)))   # 2 x 2 pairs per window
     assert st_e == 0 and n_e >= _ws_size(B, _problem(B))[1]
     assert _ws_size(B, _problem(B, match=0, h_win_remove=np.array([4, 3], dtype=np.int32)))[0] == 4   # more than |A| = 2
@@ -211,14 +215,16 @@ def test_window_counts_rejects_bad_arguments_before_any_launch(B):
     lib = B._lib
     fake = C.c_void_p(0x1000)
     f = lib.lightkv_window_counts
-    assert f(1, 4, None, 0, 0.5, None, None, fake, None, None) == 1
-    assert f(1, 4, fake, 0, 0.5, None, None, None, None, None) == 1
-    assert f(3, 4, fake, 0, 0.5, None, None, fake, None, None) == 2          # windows do not divide over the sequences
-    assert f(1, 4, fake, 7, 0.5, None, None, fake, None, None) == 5          # unknown mode
-    assert f(1, 4, fake, 2, 0.0, None, fake, fake, None, None) == 1          # target mode without the current offsets
-    assert f(1, 4, fake, 0, float("nan"), None, None, fake, None, None) == 2
-    assert f(1, 4, fake, 1, -0.1, None, None, fake, None, None) == 2
-    assert f(2, 0, fake, 0, 0.5, None, None, fake, None, None) == 0          # nothing to do
+    assert f(1, 4, None, 0, 0, 0.5, None, None, fake, None, None) == 1
+    assert f(1, 4, fake, 0, 0, 0.5, None, None, None, None, None) == 1
+    assert f(3, 4, fake, 0, 0, 0.5, None, None, fake, None, None) == 2          # windows do not divide over the sequences
+    assert f(1, 4, fake, 7, 0, 0.5, None, None, fake, None, None) == 5          # unknown mode
+    assert f(1, 4, fake, 0, 2, 0.5, None, None, fake, None, None) == 5          # unknown direction
+    assert f(1, 4, fake, 1, 1, 0.5, None, None, fake, None, None) == 5          # edge counts have no direction
+    assert f(1, 4, fake, 2, 0, 0.0, None, fake, fake, None, None) == 1          # target mode without the current offsets
+    assert f(1, 4, fake, 0, 0, float("nan"), None, None, fake, None, None) == 2
+    assert f(1, 4, fake, 1, 0, -0.1, None, None, fake, None, None) == 2
+    assert f(2, 0, fake, 0, 0, 0.5, None, None, fake, None, None) == 0          # nothing to do
 
 
 def test_probe_library_exports_what_its_header_declares():

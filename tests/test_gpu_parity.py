@@ -141,6 +141,90 @@ def test_shapes_and_edge_cases(case):
     _report(wl, reps)
 
 
+_REVERSE_CASES = [
+    # windows of odd size on every FD / selection path: the receiving side is then the larger one
+    dict(name="odd_windows_bf16", dtype="bf16", batch=2, grid_h=7, grid_w=9, text_lens=(5, 33), d=256, heads=2,
+         head_dim=128, n_c=6, structure="iid", windows_per_axis=(2, 1), n_final=40),
+    dict(name="odd_windows_f32", dtype="f32", batch=3, grid_h=5, grid_w=5, text_lens=(1, 32, 47), d=192, heads=6,
+         head_dim=32, n_c=5, structure="iid", windows_per_axis=(2, 0), n_final=15),
+    dict(name="odd_one_tile_windows_bf16", dtype="bf16", batch=2, grid_h=21, grid_w=21, text_lens=(12, 30), d=256, heads=2,
+         head_dim=128, n_c=20, structure="grid", windows_per_axis=(3, 3), n_final=260),   # 49-token windows: 24 propose, 25 receive
+    dict(name="odd_mid_window_f32", dtype="f32", batch=1, grid_h=21, grid_w=21, text_lens=(17,), d=64, heads=2,
+         head_dim=32, n_c=25, structure="grid", windows_per_axis=(1, 0), n_final=250),     # 441 tokens: several small tiles per window
+    dict(name="odd_big_window_bf16", dtype="bf16", batch=2, grid_h=37, grid_w=39, text_lens=(9, 21), d=256, heads=2,
+         head_dim=128, n_c=40, structure="grid", windows_per_axis=(1, 1), n_final=800),    # 1443 tokens: tiled kernel, 721 x 722
+    dict(name="window_of_385_bf16", dtype="bf16", batch=8, grid_h=35, grid_w=11, text_lens=(9,) * 8, d=256, heads=2,
+         head_dim=128, n_c=40, structure="grid", windows_per_axis=(1,), n_final=250),      # 192 propose, 193 receive: one row past a tile edge
+    dict(name="max_window_bf16", dtype="bf16", batch=1, grid_h=64, grid_w=64, text_lens=(24,), d=256, heads=2,
+         head_dim=128, n_c=50, structure="grid", windows_per_axis=(0,), n_final=2500),
+    dict(name="all_of_B_leaves", dtype="bf16", batch=2, grid_h=8, grid_w=8, text_lens=(8, 9), d=128, heads=1,
+         head_dim=128, n_c=4, structure="iid", windows_per_axis=(4,), n_final=32),
+    dict(name="single_token_windows", dtype="f32", batch=1, grid_h=3, grid_w=3, text_lens=(4,), d=64, heads=2,
+         head_dim=32, n_c=3, structure="iid", windows_per_axis=(3,), n_final=9),
+    dict(name="three_token_windows", dtype="bf16", batch=2, grid_h=9, grid_w=3, text_lens=(4, 6), d=128, heads=1,
+         head_dim=128, n_c=3, structure="iid", windows_per_axis=(3,), n_final=20),          # packed tiles: one proposes, two receive
+]
+
+
+@pytest.mark.parametrize("case", _REVERSE_CASES, ids=[c["name"] for c in _REVERSE_CASES])
+def test_reverse_direction_shapes_match_oracle(case):
+    """The reverse direction of Sec. 3.2.1's message-passing paragraph (set B proposes, set A receives) on every FD and
+    selection path, windows of odd size included, every output against the oracle run in the same direction."""
+    from workloads import make_custom
+    from parity import check_workload
+    print("[parity] reverse direction, case", case["name"], flush=True)
+    wl = make_custom(seed=4321, **case)
+    reps = check_workload(wl, direction="b_to_a")
+    _report(wl, reps)
+    assert [r.n_out for r in reps] == wl.targets
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, "global"])
+def test_reverse_direction_on_the_measured_configs(cfg):
+    from workloads import make_workload
+    from parity import check_workload
+    print("[parity] reverse direction, workload", cfg, flush=True)
+    wl = make_workload(cfg)
+    reps = check_workload(wl, direction="b_to_a")
+    _report(wl, reps)
+    assert [r.n_out for r in reps] == wl.targets
+
+
+def test_reverse_direction_run_equals_its_stages_and_differs_from_the_forward_one():
+    """lightkv_compress_schedule in the reverse direction: bit-identical to the stage-by-stage calls; and the direction
+    is not a no-op (the merged tokens sit at odd local positions, the forward run merges even ones)."""
+    from workloads import make_workload
+    from paper_2605_00789_amd import CompressionPipeline, to_device as to_dev
+    wl = make_workload(2)
+    outs = {}
+    for direction in ("a_to_b", "b_to_a"):
+        pipe = CompressionPipeline(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                                   tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                                   windows_per_axis=wl.windows_per_axis, targets=wl.targets, direction=direction)
+        X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+        pos = torch.from_numpy(wl.pos).to(X.device)
+        last = pipe.run(X, K, V, Q, pos)
+        torch.cuda.synchronize()
+        n_out = wl.batch * wl.targets[-1]
+        whole = [t[:n_out].clone() for t in (last.X_out, last.K_out, last.V_out, last.pos_out)]
+        dst0 = pipe.stages[0].dst.cpu().numpy().copy()
+        x, k, v, p = X, K, V, pos
+        for s in range(len(pipe.stages)):
+            st = pipe.run_stage(s, x, k, v, Q, p)
+            x, k, v, p = st.X_out, st.K_out, st.V_out, st.pos_out
+        torch.cuda.synchronize()
+        for a, b in zip(whole, (x, k, v, p)):
+            assert torch.equal(a, b[:n_out])
+        outs[direction] = dst0
+    wo = pipe.stages[0].win_offsets.cpu().numpy()
+    wt = pipe.stages[0].win_tokens.cpu().numpy()
+    local = np.empty(len(wt), dtype=np.int64)
+    for w in range(len(wo) - 1):
+        local[wt[wo[w]:wo[w + 1]]] = np.arange(wo[w + 1] - wo[w])
+    assert np.all(local[outs["a_to_b"] >= 0] % 2 == 0) and np.all(local[outs["b_to_a"] >= 0] % 2 == 1)
+    assert (outs["a_to_b"] >= 0).sum() == (outs["b_to_a"] >= 0).sum() > 0
+
+
 @pytest.mark.parametrize("metric", ["euclidean", "l2sq"])
 @pytest.mark.parametrize("cfg", [1, 2, "global"])
 def test_distance_metrics_match_oracle(cfg, metric):
@@ -882,9 +966,20 @@ def test_window_counts_match_oracle():
         want, bad = O.removal_counts_target(wo, batch, budget)
         np.testing.assert_array_equal(out.cpu().numpy(), want, err_msg="target counts, trial %d" % trial)
         np.testing.assert_array_equal(status.cpu().numpy(), bad.astype(np.int32), err_msg="status, trial %d" % trial)
+        # the reverse direction: the caps are the B sets
+        cap_r = np.where(sizes >= 2, sizes // 2, 0).reshape(batch, per).sum(axis=1)
+        budget_r = [min(int(b), int(c)) + (1 if kind == 1 else 0) for b, c in zip(budget, cap_r)]
+        target_r = np.concatenate([[0], np.cumsum(n_seq - np.asarray(budget_r))]).astype(np.int32)
+        B.lightkv_window_counts(batch, batch * per, d_wo, B.COUNT_TARGET, out, direction=B.DIRECTION_B_TO_A, cu_vis=d_cu,
+                                cu_vis_target=torch.from_numpy(target_r).to(dev), status=status)
+        want, bad = O.removal_counts_target(wo, batch, budget_r, "b_to_a")
+        np.testing.assert_array_equal(out.cpu().numpy(), want, err_msg="target counts, reverse, trial %d" % trial)
+        np.testing.assert_array_equal(status.cpu().numpy(), bad.astype(np.int32), err_msg="status, reverse, trial %d" % trial)
         for rho in (0.5, 0.36, 0.7, 1.0, 0.1, 0.0, 0.45):
             B.lightkv_window_counts(batch, batch * per, d_wo, B.COUNT_RATIO, out, rho=rho)
             np.testing.assert_array_equal(out.cpu().numpy(), O.removal_counts_ratio(wo, rho), err_msg="ratio %g" % rho)
+            B.lightkv_window_counts(batch, batch * per, d_wo, B.COUNT_RATIO, out, direction=B.DIRECTION_B_TO_A, rho=rho)
+            np.testing.assert_array_equal(out.cpu().numpy(), O.removal_counts_ratio(wo, rho, "b_to_a"), err_msg="ratio %g, reverse" % rho)
             B.lightkv_window_counts(batch, batch * per, d_wo, B.COUNT_EDGES, out, rho=rho)
             np.testing.assert_array_equal(out.cpu().numpy(), O.edge_counts_ratio(wo, rho), err_msg="edges %g" % rho)
 
