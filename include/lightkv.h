@@ -132,7 +132,8 @@ typedef enum {
 #define LIGHTKV_MAX_WINDOW_TOKENS 4096   /* tokens in one window                    */
 #define LIGHTKV_MAX_SEQ_TOKENS    16384  /* vision tokens in one sequence           */
 #define LIGHTKV_MAX_TEXT_TOKENS   4096   /* prompt tokens in one sequence           */
-#define LIGHTKV_EDGE_MAX_WINDOW_TOKENS 256  /* tokens in one window with LIGHTKV_MATCH_EDGE_TOPK */
+#define LIGHTKV_EDGE_MAX_WINDOW_TOKENS 4096 /* tokens in one window with LIGHTKV_MATCH_EDGE_TOPK; windows bounded by more than
+                                               256 tokens are ranked through a matrix of all their FD values in the workspace */
 #define LIGHTKV_SELECT_STATIC_MAX_TOKENS 65536  /* vision tokens of a batch in lightkv_select_static */
 /* Steps of at most this many vision tokens whose windows hold at most 64 tokens: lightkv_score_select runs the xi
    passes inside the launches of the FD chain, on the caller's stream alone (see there). */
@@ -157,8 +158,8 @@ typedef struct lightkv_problem {
   int32_t metric;             /* lightkv_metric; 0 (a zeroed struct) = cosine FD; other values ->
                                  LIGHTKV_ERR_UNSUPPORTED                                          */
   int32_t match;              /* lightkv_match; 0 (a zeroed struct) = one edge per A node.  With
-                                 LIGHTKV_MATCH_EDGE_TOPK win_remove[w] counts EDGES (0 <= k_w <= |A_w| |B_w|)
-                                 and h_win_remove is required; with LIGHTKV_MATCH_FULL_PAIRWISE it is
+                                 LIGHTKV_MATCH_EDGE_TOPK win_remove[w] counts EDGES (0 <= k_w <= |A_w| |B_w|;
+                                 h_win_remove optional, see lightkv_score_select); with LIGHTKV_MATCH_FULL_PAIRWISE it is
                                  the most tokens that may leave (0 <= r_w <= ceil(v_w / 2))       */
   int32_t direction;          /* lightkv_direction; 0 (a zeroed struct) = A proposes, B receives    */
   const int32_t *h_cu_vis;    /* HOST [batch+1] vision-token offsets, h_cu_vis[0] = 0            */
@@ -315,9 +316,15 @@ lightkv_status lightkv_select_static(const lightkv_problem *p, const float *best
  *
  * With p->match == LIGHTKV_MATCH_EDGE_TOPK (this call only; lightkv_select alone returns LIGHTKV_ERR_UNSUPPORTED,
  * because the selection needs the FD of every pair, which never leaves the workspace):
- *   win_remove[w] = k_w, the number of EDGES taken in window w (device values above |A_w| |B_w| are clamped);
+ *   win_remove[w] = k_w, the number of EDGES taken in window w (device values above |A_w| |B_w| are clamped).
+ *                 With h_win_remove (and h_win_offsets, against which it is validated) the edge list is sized from
+ *                 the host's counts, which must equal the device's.  Without h_win_remove the counts are read on
+ *                 the device only -- e.g. straight from lightkv_window_counts(LIGHTKV_COUNT_EDGES), no read-back --,
+ *                 the list gets one slot per token of the batch, and k_w is in addition clamped to v_w, the tokens of
+ *                 the window (never binding for rho <= 2);
  *   dst[a]        the B token of a's lowest selected edge, -1 if a owns none (a stays)
  *   grp_offsets / grp_src   sources of every B token over ALL selected edges, ascending; grp_src needs sum k_w ints
+ *                           (sumN ints without h_win_remove)
  *   new_index, cu_vis_out   as above; the number of staying tokens is data dependent -- a caller that needs it on the
  *                           host reads cu_vis_out back.  lightkv_aggregate_compact / lightkv_compact then write that
  *                           many rows; size their outputs for sumN - (number of windows with k_w > 0) rows or more.

@@ -138,7 +138,7 @@ def _ld(t: Optional[torch.Tensor]) -> int:
 METRICS = {"cosine": 0, "euclidean": 1, "l2sq": 2}
 MATCH_BEST_PER_A, MATCH_EDGE_TOPK, MATCH_FULL_PAIRWISE = 0, 1, 2
 DIRECTION_A_TO_B, DIRECTION_B_TO_A = 0, 1   # lightkv_direction
-EDGE_MAX_WINDOW_TOKENS = 256   # LIGHTKV_EDGE_MAX_WINDOW_TOKENS
+EDGE_MAX_WINDOW_TOKENS = 4096   # LIGHTKV_EDGE_MAX_WINDOW_TOKENS
 SELECT_STATIC_MAX_TOKENS = 65536   # LIGHTKV_SELECT_STATIC_MAX_TOKENS
 ONE_STREAM_MAX_TOKENS = 1024   # LIGHTKV_ONE_STREAM_MAX_TOKENS
 
@@ -255,6 +255,13 @@ def lightkv_score_select(p: Problem, X, Q, K, xi, best_fd, best_dst, dst, new_in
 
     qts, qhs = strides(Q)
     kts, khs = strides(K)
+    if p.c.match == MATCH_EDGE_TOPK:
+        # the C call takes plain pointers: the one size the library cannot check is checked here.  With the host's
+        # counts the group list holds one entry per edge, without them at most one per token of the batch.
+        h_k, h_cu = p.refs.get("h_win_remove"), p.refs["h_cu_vis"]
+        need = int(np.asarray(h_k, dtype=np.int64).sum()) if h_k is not None else int(h_cu[-1])
+        if grp_src.numel() < need:
+            raise ValueError("grp_src holds %d entries, this step may write %d" % (grp_src.numel(), need))
     _check(_lib.lightkv_score_select(p.ref(), _dptr(X), _ld(X), _dptr(x_sqnorm), _dptr(Q), qts, qhs, _dptr(K), kts, khs, xi_mode,
                                      _dptr(lse), float(softmax_scale), _dptr(xi), _dptr(best_fd), _dptr(best_dst),
                                      _dptr(dst), _dptr(new_index), _dptr(grp_offsets), _dptr(grp_src),

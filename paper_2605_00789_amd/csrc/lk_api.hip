@@ -17,7 +17,8 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 struct Checked {
   int sum_n = 0, sum_t = 0, max_seq = 0, max_window = 0, elem_bytes = 0;
-  int64_t sum_remove = 0;   // sum of h_win_remove (when given)
+  int64_t sum_remove = 0;   // sum of h_win_remove (when given); edge lists without host counts: the slots reserved
+  bool edge_device_counts = false;   // LIGHTKV_MATCH_EDGE_TOPK without h_win_remove: the counts are on the device only
 };
 
 // The window bound the launch plans are made with.  In the reverse direction the receiving side of an odd window is
@@ -93,9 +94,13 @@ lightkv_status check_problem(const lightkv_problem *p, bool need_windows, bool n
     if (c.max_window > LIGHTKV_MAX_WINDOW_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;
     c.max_window = plan_bound(p, c.max_window);
     if (p->match == LIGHTKV_MATCH_EDGE_TOPK) {
-      // the edge list is sized from the host's counts, and the whole |A| x |B| block of a window is ranked in LDS
-      if (!p->h_win_offsets || !p->h_win_remove) return LIGHTKV_ERR_NULL;
+      // the edge list is sized from the host's counts (validated against the host's window sizes) or, without them,
+      // for one slot per token: a window's k is then bounded by its tokens as well as by its pairs
+      if (p->h_win_remove && !p->h_win_offsets) return LIGHTKV_ERR_NULL;
+      if (!p->h_win_remove) { c.sum_remove = c.sum_n; c.edge_device_counts = true; }
       if (c.max_window > LIGHTKV_EDGE_MAX_WINDOW_TOKENS || c.sum_remove >= (1ll << 28)) return LIGHTKV_ERR_UNSUPPORTED;
+      // windows beyond the one-kernel path keep the keys of all their pairs in the workspace
+      if (edge_big_key_count(p->n_windows, c.max_window) >= (1ull << 31)) return LIGHTKV_ERR_UNSUPPORTED;
     }
   }
   return LIGHTKV_OK;
@@ -115,7 +120,10 @@ struct WsLayout {
 bool edge_topk(const lightkv_problem *p) { return p->match == LIGHTKV_MATCH_EDGE_TOPK; }
 bool full_pairwise(const lightkv_problem *p) { return p->match == LIGHTKV_MATCH_FULL_PAIRWISE; }
 // ints of scratch for the edge list (A token, B token, position among the B token's sources)
-size_t edge_ints(const lightkv_problem *p, const Checked &c) { return edge_topk(p) ? (size_t)3 * (size_t)c.sum_remove : 0; }
+// ... followed by the key matrices of windows beyond the one-kernel path
+size_t edge_ints(const lightkv_problem *p, const Checked &c) {
+  return edge_topk(p) ? (size_t)3 * (size_t)c.sum_remove + edge_big_key_count(p->n_windows, c.max_window) : 0;
+}
 
 bool use_big_fd(const lightkv_problem *p, const Checked &c) {
   if (full_pairwise(p)) return true;   // squared norms and one packed key per position, as on the tiled bipartite path
@@ -419,7 +427,8 @@ lightkv_status score_impl(const lightkv_problem *p, const void *X, int64_t ldx, 
     const int sum_k = (int)c.sum_remove;
     if (launch_edge_select(fd, p->dtype, X, ldx, p->d, p->n_windows, c.max_window, c.sum_n, sum_k, p->win_offsets,
                            p->win_tokens, p->win_remove, reinterpret_cast<float *>(wsb + l.fd_partial), best_fd,
-                           best_dst, sel->dst, cnt, rank, edges, s) != hipSuccess ||
+                           best_dst, sel->dst, cnt, rank, edges, c.edge_device_counts,
+                           reinterpret_cast<uint32_t *>(edges + (size_t)3 * (size_t)sum_k), s) != hipSuccess ||
         launch_select_scan(p->batch, c.sum_n, p->cu_vis, sel->dst, sel->new_index, sel->grp_offsets, sel->grp_src,
                            sel->cu_vis_out, cnt, rank, s) != hipSuccess ||
         launch_edge_fill(sum_k, c.sum_n, edges, sel->grp_offsets, sel->grp_src, s) != hipSuccess)

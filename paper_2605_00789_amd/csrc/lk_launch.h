@@ -61,7 +61,9 @@ hipError_t launch_fd_select_small(const FdPlan &plan, int dtype, const void *X, 
                                   int32_t *dst, int32_t *cnt, int32_t *src_rank, hipStream_t stream);
 
 // Step 2 read literally (lk_select_edges.hip): the k lowest-FD edges of every window.  Windows of at most
-// 2 * EDGE_MAX_SIDE tokens; `edges` is scratch of 3 * sum_k ints (sum_k = the k of all windows).
+// 2 * EDGE_MAX_SIDE tokens are ranked in LDS by one kernel; larger ones through a key matrix in `big_keys`.
+// `edges` is scratch of 3 * sum_k ints (sum_k = the k of all windows, or a bound on it with device_counts, where a
+// window's k is also bounded by its tokens).
 constexpr int EDGE_MAX_SIDE = 128;
 hipError_t launch_fd_partial(const FdPlan &plan, int dtype, const void *X, int64_t ldx, int d, int n_windows, int sum_n,
                              const int32_t *win_offsets, const int32_t *win_tokens, float *partial, hipStream_t stream);
@@ -69,7 +71,9 @@ hipError_t launch_edge_select(const FdPlan &plan, int dtype, const void *X, int6
                               int max_window, int sum_n, int sum_k, const int32_t *win_offsets,
                               const int32_t *win_tokens, const int32_t *win_remove, float *partial, float *best_fd,
                               int32_t *best_dst, int32_t *dst, int32_t *cnt, int32_t *src_rank, int32_t *edges,
-                              hipStream_t stream);
+                              bool device_counts, uint32_t *big_keys, hipStream_t stream);
+// the FD keys of every pair of every window, for windows beyond the one-kernel path: 32-bit keys (0 if not needed)
+size_t edge_big_key_count(int n_windows, int max_window);
 hipError_t launch_edge_fill(int sum_k, int sum_n, const int32_t *edges, const int32_t *grp_offsets, int32_t *grp_src,
                             hipStream_t stream);
 

@@ -216,7 +216,9 @@ class CompressionPipeline:
 
 @dataclass
 class EdgeStepResult:
-    """Outputs of one step with Step 2 read literally; every tensor is cut to the rows the step really wrote."""
+    """Outputs of one step whose token count depends on the data; every tensor is cut to the rows the step really wrote.
+    The tensors are views of buffers the schedule owns: those of a step stay valid until the step after next runs (X, K,
+    V, pos: two sets in turn) or until the next step runs (everything else)."""
     h_cu_vis_out: np.ndarray
     X: torch.Tensor
     K: torch.Tensor
@@ -231,18 +233,25 @@ class EdgeStepResult:
     grp_src: torch.Tensor
     win_offsets: torch.Tensor
     win_tokens: torch.Tensor
-    h_win_edges: np.ndarray
+    win_remove: torch.Tensor     # per-window counts as the step used them (device)
+    cu_vis_out: torch.Tensor     # device copy of h_cu_vis_out
+
+    @property
+    def h_win_edges(self) -> np.ndarray:
+        """The per-window counts on the host (a read-back: call it outside timed regions)."""
+        return self.win_remove.cpu().numpy()
 
 
 class EdgeTopKSchedule:
     """The hierarchical schedule for the matchings whose token counts depend on the data:
       match="edge_topk"      the k lowest-FD edges per window (LIGHTKV_MATCH_EDGE_TOPK, k = floor(rho v / 2) as
-                             Sec. 3.2.1 counts the pairs);
+                             Sec. 3.2.1 counts the pairs), windows of any size the library takes;
       match="full_pairwise"  every token against every other token of its window (LIGHTKV_MATCH_FULL_PAIRWISE, the
                              appendix ablation), at most floor(rho v) tokens leave a window.
-    The host reads small arrays back per stage -- for the edges the counts and window sizes (the edge list is sized from
-    them), and for both the sequence lengths after the step -- and allocates the stage's buffers then; nothing here is
-    captured in a graph."""
+    Every buffer is allocated once, here, for the largest step (the first); the per-window counts are computed and
+    consumed on the device.  The one thing the host reads back per step is cu_vis_out, the batch + 1 sequence offsets
+    after the step: the next step's descriptor needs them.  Nothing here is captured in a graph (the sizes of a step
+    depend on the data of the one before)."""
 
     def __init__(self, *, dtype: str, batch: int, d: int, heads: int, head_dim: int, tiles: int, grid_h: int,
                  grid_w: int, cu_txt: np.ndarray, windows_per_axis: Sequence[int], rho: Sequence[float],
@@ -257,80 +266,107 @@ class EdgeTopKSchedule:
         self.match = match
         self.h_cu_txt = np.ascontiguousarray(cu_txt, dtype=np.int32)
         self.cu_txt = torch.from_numpy(self.h_cu_txt).to(self.device)
+        dev, i32 = self.device, dict(dtype=torch.int32, device=self.device)
+        n0 = tiles * grid_h * grid_w
+        cap = max(batch * n0, 1)
+        self.capacity = cap
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        f32 = dict(dtype=torch.float32, device=dev)
+        self._win_tokens = torch.empty(cap, **i32)
+        self._xi, self._best_fd = torch.empty(cap, **f32), torch.empty(cap, **f32)
+        self._best_dst, self._dst, self._new_index = (torch.empty(cap, **i32) for _ in range(3))
+        self._grp_offsets, self._grp_src = torch.empty(cap + 1, **i32), torch.empty(cap, **i32)
+        self._cu = [torch.empty(batch + 1, **i32) for _ in range(2)]          # in turn: a step's cu_vis and cu_vis_out
+        self._out = [tuple(torch.empty(cap, d, dtype=tdt, device=dev) for _ in range(3)) + (torch.empty(cap, **i32),)
+                     for _ in range(2)]
+        self._win_offsets, self._win_remove, self._bound = [], [], []
+        h_full = (np.arange(batch + 1, dtype=np.int32) * n0).astype(np.int32)
+        ws_bytes = 0
+        for w in self.windows_per_axis:
+            n_windows = batch * windows_per_sequence(tiles, w)
+            self._win_offsets.append(torch.empty(n_windows + 1, **i32))
+            self._win_remove.append(torch.empty(max(n_windows, 1), **i32))
+            self._bound.append(min(max_window_cells(tiles, grid_h, grid_w, w), max(n0, 1)))
+            ws_bytes = max(ws_bytes, B.lightkv_workspace_size(self._problem(len(self._bound) - 1, h_full, self._cu[0])))
+        self._ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def _problem(self, s, h_cu_vis, cu_vis, h_win_offsets=None, h_k=None):
+        n_windows = self.batch * windows_per_sequence(self.tiles, self.windows_per_axis[s])
+        pairwise = self.match == "full_pairwise"
+        bound = min(self._bound[s], max(int(np.diff(h_cu_vis).max()), 1))
+        return B.Problem(batch=self.batch, d=self.d, heads=self.heads, head_dim=self.head_dim, dtype=self.dtype,
+                         h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt, n_windows=n_windows,
+                         max_window_tokens=0 if h_win_offsets is not None else bound, win_offsets=self._win_offsets[s],
+                         win_tokens=self._win_tokens, win_remove=self._win_remove[s], h_win_offsets=h_win_offsets,
+                         h_win_remove=h_k, metric=self.metric,
+                         match=B.MATCH_FULL_PAIRWISE if pairwise else B.MATCH_EDGE_TOPK)
 
     def run_step(self, s: int, h_cu_vis: np.ndarray, X, K, V, Q, pos, *, xi_given=None, h_win_edges=None,
-                 marks: Optional[list] = None) -> EdgeStepResult:
-        """marks: if a list, (name, event) pairs are appended around the three library calls (current stream)."""
+                 marks: Optional[list] = None, cu_vis=None, host_mirror: bool = True) -> EdgeStepResult:
+        """marks: if a list, (name, event) pairs are appended around the three library calls (current stream).
+        cu_vis: the device copy of h_cu_vis if the caller has one (run() hands on the previous step's cu_vis_out).
+        h_win_edges: per-window counts given by the caller instead of the ratio (then they and the window sizes are
+        validated on the host, which costs a read-back of the window offsets; host_mirror=False hands them to the
+        device only, as the ratio's counts are)."""
         def mark(name):
             if marks is not None:
                 ev = torch.cuda.Event(enable_timing=True)
                 ev.record()
                 marks.append((name, ev))
 
-        dev, i32 = self.device, dict(dtype=torch.int32, device=self.device)
         batch, w = self.batch, self.windows_per_axis[s]
         h_cu_vis = np.ascontiguousarray(h_cu_vis, dtype=np.int32)
-        cu_vis = torch.from_numpy(h_cu_vis).to(dev)
         sum_n = int(h_cu_vis[-1])
+        if sum_n > self.capacity:
+            raise ValueError("more tokens than the schedule was built for")
+        if cu_vis is None:
+            cu_vis = self._cu[0]
+            cu_vis.copy_(torch.from_numpy(h_cu_vis))
+        cu_vis_out = self._cu[1] if cu_vis is self._cu[0] else self._cu[0]
         n_windows = batch * windows_per_sequence(self.tiles, w)
-        win_offsets = torch.empty(n_windows + 1, **i32)
-        win_tokens = torch.empty(max(sum_n, 1), **i32)
+        win_offsets, win_tokens, win_remove = self._win_offsets[s], self._win_tokens, self._win_remove[s]
         mark("build_windows")
         B.lightkv_build_windows(batch, h_cu_vis, cu_vis, pos, self.tiles, self.grid_h, self.grid_w, w, win_offsets,
                                 win_tokens)
         mark("end")
         pairwise = self.match == "full_pairwise"
         if h_win_edges is None:                              # k_w = floor(rho v_w / 2) (r_w = floor(rho v_w)), on the device
-            win_remove = torch.empty(max(n_windows, 1), **i32)
             B.lightkv_window_counts(batch, n_windows, win_offsets, B.COUNT_RATIO if pairwise else B.COUNT_EDGES,
                                     win_remove, rho=self.rho[s])
-            h_k = None if pairwise else win_remove.cpu().numpy()[:n_windows]   # edges: first read-back, the counts ...
+            prob = self._problem(s, h_cu_vis, cu_vis)
         else:
             h_k = np.ascontiguousarray(h_win_edges, dtype=np.int32)
-            win_remove = torch.from_numpy(h_k).to(dev)
-        if pairwise:                                         # needs no host copy of the windows, only a bound on their size
-            bound = min(max_window_cells(self.tiles, self.grid_h, self.grid_w, w), max(int(np.diff(h_cu_vis).max()), 1))
-            prob = B.Problem(batch=batch, d=self.d, heads=self.heads, head_dim=self.head_dim, dtype=self.dtype,
-                             h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt,
-                             n_windows=n_windows, max_window_tokens=bound, win_offsets=win_offsets, win_tokens=win_tokens,
-                             win_remove=win_remove, metric=self.metric, match=B.MATCH_FULL_PAIRWISE)
-        else:
-            h_win_offsets = win_offsets.cpu().numpy()        # ... and the window sizes
-            prob = B.Problem(batch=batch, d=self.d, heads=self.heads, head_dim=self.head_dim, dtype=self.dtype,
-                             h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt,
-                             n_windows=n_windows, max_window_tokens=0, win_offsets=win_offsets, win_tokens=win_tokens,
-                             win_remove=win_remove, h_win_offsets=h_win_offsets, h_win_remove=h_k, metric=self.metric,
-                             match=B.MATCH_EDGE_TOPK)
-        ws = torch.empty(B.lightkv_workspace_size(prob), dtype=torch.uint8, device=dev)
-        tdt = X.dtype
-        xi = torch.empty(sum_n, dtype=torch.float32, device=dev) if xi_given is None else xi_given
-        best_fd = torch.empty(sum_n, dtype=torch.float32, device=dev)
-        best_dst, dst, new_index = (torch.empty(sum_n, **i32) for _ in range(3))
-        grp_offsets = torch.empty(sum_n + 1, **i32)
-        grp_src = torch.empty(max(sum_n if pairwise else int(h_k.sum()), 1), **i32)
-        cu_vis_out = torch.empty(batch + 1, **i32)
+            win_remove[:n_windows].copy_(torch.from_numpy(h_k))
+            mirror = host_mirror and not pairwise
+            prob = self._problem(s, h_cu_vis, cu_vis, win_offsets.cpu().numpy() if mirror else None, h_k if mirror else None)
+            # with the host's counts the library sizes the edge list from them -- up to every pair of a window -- and
+            # writes that many group entries; counts known to the device only are clamped to one per token
+            if mirror and int(h_k.sum()) > self._grp_src.numel():
+                self._grp_src = torch.empty(int(h_k.sum()), dtype=torch.int32, device=self.device)
+        need = B.lightkv_workspace_size(prob)
+        if need > self._ws.numel():                          # (the plans are not monotone in the sizes: a rare regrow)
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        xi = self._xi[:sum_n] if xi_given is None else xi_given
+        best_fd, best_dst, dst, new_index = (t[:max(sum_n, 1)] for t in (self._best_fd, self._best_dst, self._dst, self._new_index))
+        grp_offsets, grp_src = self._grp_offsets[:sum_n + 1], self._grp_src
         mark("score_select")
-        B.lightkv_score_select(prob, X, Q, K, xi, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out, ws,
-                               xi_mode=B.XI_TEXT_QUERY if xi_given is None else B.XI_GIVEN)
+        B.lightkv_score_select(prob, X, Q, K, xi, best_fd, best_dst, dst, new_index, grp_offsets, grp_src, cu_vis_out,
+                               self._ws, xi_mode=B.XI_TEXT_QUERY if xi_given is None else B.XI_GIVEN)
         mark("end")
-        # every window that takes an edge loses at least one token: an upper bound on the rows written
-        rows = max(sum_n if pairwise else sum_n - int((h_k > 0).sum()), 1)
-        X_out, K_out, V_out = (torch.empty(rows, self.d, dtype=tdt, device=dev) for _ in range(3))
-        pos_out = torch.empty(rows, **i32)
+        X_out, K_out, V_out, pos_out = self._out[0] if X.data_ptr() != self._out[0][0].data_ptr() else self._out[1]
         mark("aggregate_compact")
         B.lightkv_aggregate_compact(prob, new_index, grp_offsets, grp_src, xi, X, K, V, pos, X_out, K_out, V_out, pos_out)
         mark("end")
-        h_out = cu_vis_out.cpu().numpy()                     # second read-back: the sequence lengths after the step
+        h_out = cu_vis_out.cpu().numpy()                     # the one read-back: the sequence lengths after the step
         n_out = int(h_out[-1])
-        if h_k is None:
-            h_k = win_remove.cpu().numpy()[:n_windows]
-        return EdgeStepResult(h_out, X_out[:n_out], K_out[:n_out], V_out[:n_out], pos_out[:n_out], xi, best_fd, best_dst,
-                              dst, new_index, grp_offsets, grp_src, win_offsets, win_tokens, h_k)
+        res = EdgeStepResult(h_out, X_out[:n_out], K_out[:n_out], V_out[:n_out], pos_out[:n_out], xi, best_fd, best_dst,
+                             dst, new_index, grp_offsets, grp_src, win_offsets, win_tokens, win_remove[:n_windows], cu_vis_out)
+        return res
 
     def run(self, h_cu_vis: np.ndarray, X, K, V, Q, pos, marks: Optional[list] = None) -> List[EdgeStepResult]:
-        out = []
+        out, cu_vis = [], None
         for s in range(len(self.windows_per_axis)):
-            r = self.run_step(s, h_cu_vis, X, K, V, Q, pos, marks=marks)
+            r = self.run_step(s, h_cu_vis, X, K, V, Q, pos, marks=marks, cu_vis=cu_vis)
             out.append(r)
-            h_cu_vis, X, K, V, pos = r.h_cu_vis_out, r.X, r.K, r.V, r.pos
+            h_cu_vis, X, K, V, pos, cu_vis = r.h_cu_vis_out, r.X, r.K, r.V, r.pos, r.cu_vis_out
         return out

@@ -86,12 +86,15 @@ def test_workspace_size_and_descriptor_validation(B):
     assert st_e == 0 and n_e >= _ws_size(B, _problem(B))[1]
     assert _ws_size(B, _problem(B, match=0, h_win_remove=np.array([4, 3], dtype=np.int32)))[0] == 4   # more than |A| = 2
     assert _ws_size(B, _problem(B, match=1, h_win_remove=np.array([5, 0], dtype=np.int32)))[0] == 4   # more than 4 pairs
-    p_nohost = _problem(B, match=1)
+    p_nohost = _problem(B, match=1)                          # counts on the device only: one slot per token instead
     p_nohost.h_win_remove = None
-    assert _ws_size(B, p_nohost)[0] == 1
-    big = np.array([0, 300], dtype=np.int32)
-    assert _ws_size(B, _problem(B, match=1, n_windows=1, h_cu_vis=big, h_win_offsets=big,
-                                h_win_remove=np.array([1], dtype=np.int32)))[0] == 5                  # 300-token window
+    assert _ws_size(B, p_nohost)[0] == 0
+    p_half = _problem(B, match=1, max_window_tokens=4)       # host counts cannot be validated without host window sizes
+    p_half.h_win_offsets = None
+    assert _ws_size(B, p_half)[0] == 1
+    big = np.array([0, 300], dtype=np.int32)                 # a 300-token window: the keys of its 150 x 150 pairs are in the workspace
+    st_b, n_b = _ws_size(B, _problem(B, match=1, n_windows=1, h_cu_vis=big, h_win_offsets=big, h_win_remove=np.array([1], dtype=np.int32)))
+    assert st_b == 0 and n_b > 150 * 150 * 4
     assert _ws_size(B, _problem(B, batch=0))[0] == 2
     assert _ws_size(B, _problem(B, h_cu_vis=np.array([1, 8], dtype=np.int32)))[0] == 2
     assert _ws_size(B, _problem(B, h_cu_vis=np.array([0, 20000], dtype=np.int32),

@@ -836,11 +836,13 @@ def test_nan_rows_keep_the_counts_exact():
 # Step 2 read literally: the k lowest-FD edges per window
 # ---------------------------------------------------------------------------------------------------------------
 @pytest.mark.gpu
-@pytest.mark.parametrize("cfg,rho,stages", [(1, (0.5,), 1), (2, (0.5, 0.5), 2), (4, (0.6,), 1), (3, (0.5, 0.5), 2),
-                                            (5, (0.5, 0.3), 2)])
+@pytest.mark.parametrize("cfg,rho,stages", [(1, (0.5,), 1), (2, (0.5, 0.5, 0.5), 3), (4, (0.6,), 1), (3, (0.5, 0.5, 0.4), 3),
+                                            (5, (0.5, 0.3, 0.3), 3), ("global", (0.36,), 1)])
 def test_edge_topk_matching_matches_oracle(cfg, rho, stages):
-    """floor(rho v / 2) lowest-FD edges per window at the measured configurations' sizes: packed 16-token windows
-    (configs 1, 3), single-tile and multi-tile windows (2, 4, 5), a ragged batch after the first stage (5)."""
+    """floor(rho v / 2) lowest-FD edges per window at the measured configurations' sizes, every stage of their schedules:
+    packed 16-token windows (configs 1, 3), single-tile and multi-tile windows (2, 4, 5), a ragged batch after the first
+    stage (5), the whole-tile windows of the last stage of W = [4, 2, 1] (2, 5: about 390 tokens, ranked through the key
+    matrix in the workspace) and one window of 2880 tokens (global)."""
     from workloads import make_workload
     from parity import check_edge_workload
     wl = make_workload(cfg)
@@ -890,12 +892,45 @@ def test_edge_topk_edge_cases():
     rep, _ = check_edge_step(sched_for(wl, 2), 0, wl.cu_vis, X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
     assert rep.window_ties == 0
     print("[edge cases] (c) %d -> %d tokens, %d edges" % (rep.n_in, rep.n_out, rep.edges), flush=True)
-    # (d) the largest supported window (256 tokens: a 16 x 16 grid as one window), distances
+    # (d) the largest window the one-kernel path takes (256 tokens: a 16 x 16 grid as one window), distances
     for metric in ("cosine", "euclidean", "l2sq"):
         wl = make_custom(name="edge_d", seed=34, dtype="bf16", batch=1, grid_h=16, grid_w=16, text_lens=(33,), d=512,
                          heads=4, head_dim=128, windows_per_axis=(1,), n_final=200, structure="grid")
         rep, _ = check_edge_step(sched_for(wl, 1, metric), 0, wl.cu_vis, wl.X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
         print("[edge cases] (d) %s %d -> %d tokens, %d edges, %d tied" % (metric, rep.n_in, rep.n_out, rep.edges, rep.window_ties), flush=True)
+    # (e) windows beyond the one-kernel path (key matrix in the workspace): 17 x 18 = 306 tokens next to smaller windows of
+    # the same launch, hand-set counts (none, one, every pair, a few), host mirror and device-only counts; fp32 and bf16
+    for dtype, d_, hd in (("f32", 64, 32), ("bf16", 256, 128)):
+        wl = make_custom(name="edge_e", seed=35, dtype=dtype, batch=3, grid_h=17, grid_w=18, text_lens=(9, 20, 3), d=d_, heads=2,
+                         head_dim=hd, windows_per_axis=(1,), n_final=200, structure="grid")
+        pairs = 153 * 153
+        for k, mirror in (([0, 1, pairs], True), ([40, pairs - 1, 7], True), ([5, 100000, 306], False)):
+            rep, _ = check_edge_step(sched_for(wl, 1), 0, wl.cu_vis, wl.X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype,
+                                     h_win_edges=np.array(k, dtype=np.int32), host_mirror=mirror)
+            print("[edge cases] (e) %s k=%s mirror=%s: %d -> %d tokens, %d edges" % (dtype, k, mirror, rep.n_in, rep.n_out, rep.edges), flush=True)
+    # (f) identical tokens in a large window: every FD is exactly zero, the pair index decides (the two extra radix passes)
+    wl = make_custom(name="edge_f", seed=36, dtype="bf16", batch=1, grid_h=20, grid_w=21, text_lens=(7,), d=256, heads=2,
+                     head_dim=128, windows_per_axis=(1,), n_final=300)
+    X = wl.X.copy()
+    X[:] = X[0]
+    rep, _ = check_edge_step(sched_for(wl, 1), 0, wl.cu_vis, X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
+    assert rep.window_ties == 0
+    print("[edge cases] (f) %d -> %d tokens, %d edges" % (rep.n_in, rep.n_out, rep.edges), flush=True)
+    # ... and half of the rows identical: a block of exact zeros below the threshold or across it
+    X = wl.X.copy()
+    X[::2] = X[0]
+    for rho in (0.2, 0.9):
+        s1 = EdgeTopKSchedule(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, tiles=wl.tiles,
+                              grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt, windows_per_axis=[1], rho=[rho])
+        rep, _ = check_edge_step(s1, 0, wl.cu_vis, X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
+        print("[edge cases] (f) rho %.1f: %d -> %d tokens, %d edges, %d tied" % (rho, rep.n_in, rep.n_out, rep.edges, rep.window_ties), flush=True)
+    # (g) the largest window of the library: 4096 tokens
+    wl = make_custom(name="edge_g", seed=37, dtype="bf16", batch=1, grid_h=64, grid_w=64, text_lens=(24,), d=256, heads=2,
+                     head_dim=128, n_c=50, structure="grid", windows_per_axis=(0,), n_final=3000)
+    s1 = EdgeTopKSchedule(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, tiles=wl.tiles,
+                          grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt, windows_per_axis=[0], rho=[0.5])
+    rep, _ = check_edge_step(s1, 0, wl.cu_vis, wl.X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
+    print("[edge cases] (g) %d -> %d tokens, %d edges, %d tied" % (rep.n_in, rep.n_out, rep.edges, rep.window_ties), flush=True)
 
 
 @pytest.mark.gpu
@@ -904,7 +939,7 @@ def test_edge_topk_refusals():
     import paper_2605_00789_amd as L
     from paper_2605_00789_amd import binding as B
     dev = "cuda:0"
-    n, d = 600, 64
+    n, d = 4097, 64
     h_cu = np.array([0, n], dtype=np.int32)
     cu = torch.from_numpy(h_cu).to(dev)
     offs = np.array([0, n], dtype=np.int32)
@@ -919,12 +954,20 @@ def test_edge_topk_refusals():
         a.update(kw)
         return B.Problem(**a)
 
-    with pytest.raises(L.LightKVError) as e:      # a window of 600 tokens
+    with pytest.raises(L.LightKVError) as e:      # a window of 4097 tokens
         B.lightkv_workspace_size(prob())
     assert e.value.status == 5
-    with pytest.raises(L.LightKVError) as e:      # the host's counts are required
-        B.lightkv_workspace_size(prob(h_win_remove=None))
-    assert e.value.status in (1, 5)
+    two = np.array([0, 2000, n], dtype=np.int32)
+    ok = dict(n_windows=2, h_win_offsets=two, win_offsets=torch.from_numpy(two).to(dev), h_win_remove=np.array([3, 3], dtype=np.int32),
+              win_remove=torch.zeros(2, dtype=torch.int32, device=dev))
+    assert B.lightkv_workspace_size(prob(**ok)) > 2 * 1049 * 1048 * 4   # the keys of every pair of both windows, at their bound
+    with pytest.raises(L.LightKVError) as e:      # host counts are validated against host window sizes: both or neither
+        B.lightkv_workspace_size(prob(**dict(ok, h_win_offsets=None, max_window_tokens=2100)))
+    assert e.value.status == 1
+    assert B.lightkv_workspace_size(prob(**dict(ok, h_win_offsets=None, h_win_remove=None, max_window_tokens=2100))) > 0
+    with pytest.raises(L.LightKVError) as e:      # the reverse direction has no edge list
+        B.lightkv_workspace_size(prob(**dict(ok, direction=B.DIRECTION_B_TO_A)))
+    assert e.value.status == 5
     small = np.array([0, 200, n], dtype=np.int32)
     with pytest.raises(L.LightKVError) as e:      # more edges than the window has pairs
         B.lightkv_workspace_size(prob(n_windows=2, h_win_offsets=small, win_offsets=torch.from_numpy(small).to(dev),
