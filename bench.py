@@ -112,8 +112,21 @@ def calibrate_counters():
     print(json.dumps({"calibration": "copies of 64 MiB and 512 MiB, four each"}))
 
 
+def _probe_lib():
+    import ctypes as C
+    lib = C.CDLL(os.path.join(ROOT, "paper_2605_00789_amd", "liblightkv_probe.so"))
+    lib.lightkv_probe_operand_delivery.restype = C.c_int
+    lib.lightkv_probe_operand_delivery.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                                   C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_double), C.c_void_p]
+    lib.lightkv_probe_mfma.restype = C.c_int
+    lib.lightkv_probe_mfma.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.c_void_p]
+    return lib
+
+
 class _Timer:
-    """HIP events on the launch stream; the interval of an empty event pair is measured the same way and removed."""
+    """HIP events on the launch stream; the interval of an empty event pair is measured the same way and removed.  What
+    is left of an interval around one kernel is its dispatch latency plus its execution: an upper bound of the duration a
+    kernel trace reports for it."""
 
     def __init__(self, stream):
         import torch
@@ -249,13 +262,7 @@ def ceilings_pass(stream):
     import torch
     from workloads import make_workload
     from paper_2605_00789_amd import to_device as to_dev
-    path = os.path.join(ROOT, "paper_2605_00789_amd", "liblightkv_probe.so")
-    lib = C.CDLL(path)
-    lib.lightkv_probe_operand_delivery.restype = C.c_int
-    lib.lightkv_probe_operand_delivery.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
-                                                   C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_double), C.c_void_p]
-    lib.lightkv_probe_mfma.restype = C.c_int
-    lib.lightkv_probe_mfma.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.c_void_p]
+    lib = _probe_lib()
     wl = make_workload("global")
     X = to_dev(wl.X, wl.dtype)
     n, row_bytes = X.shape[0], X.shape[1] * 2

@@ -224,7 +224,9 @@ lightkv_status lightkv_workspace_size(const lightkv_problem *p, size_t *bytes) {
 static lightkv_status build_windows_impl(int32_t batch, const int32_t *h_cu_vis, const int32_t *cu_vis,
                                          const int32_t *pos, const int32_t *new_index, const int32_t *cu_vis_out,
                                          int32_t tiles, int32_t grid_h, int32_t grid_w, int32_t w,
-                                         int32_t *win_offsets, int32_t *win_tokens, void *stream) {
+                                         int32_t *win_offsets, int32_t *win_tokens, void *stream,
+                                         const int32_t *cu_target = nullptr, int32_t *win_remove = nullptr,
+                                         int32_t *status = nullptr, int dir = 0, bool *counts_done = nullptr) {
   if (!h_cu_vis || !cu_vis || !pos || !win_offsets || !win_tokens) return LIGHTKV_ERR_NULL;
   if (batch < 1 || tiles < 1 || grid_h < 1 || grid_w < 1 || w < 0 || h_cu_vis[0] != 0) return LIGHTKV_ERR_SHAPE;
   int max_seq = 0;
@@ -236,7 +238,8 @@ static lightkv_status build_windows_impl(int32_t batch, const int32_t *h_cu_vis,
   if (max_seq > LIGHTKV_MAX_SEQ_TOKENS) return LIGHTKV_ERR_UNSUPPORTED;
   if ((int64_t)tiles * w * w > (1 << 17) || (int64_t)tiles * grid_h * grid_w > (1ll << 30)) return LIGHTKV_ERR_UNSUPPORTED;
   if (launch_build_windows(cu_vis, pos, new_index, cu_vis_out, batch, max_seq, tiles, grid_h, grid_w, w, win_offsets,
-                           win_tokens, static_cast<hipStream_t>(stream)) != hipSuccess)
+                           win_tokens, cu_target, win_remove, status, dir, counts_done,
+                           static_cast<hipStream_t>(stream)) != hipSuccess)
     return LIGHTKV_ERR_LAUNCH;
   return LIGHTKV_OK;
 }
@@ -297,6 +300,28 @@ lightkv_status lightkv_window_counts(int32_t batch, int32_t n_windows, const int
 }
 
 }  // extern "C"
+
+// Windows and their counts for lightkv_compress_schedule: lightkv_build_windows (or _next) followed by
+// lightkv_window_counts(LIGHTKV_COUNT_TARGET) on the windows just built -- in ONE launch where the partition kernel
+// allows it (the window sizes are in its LDS at the end), in two otherwise.  Same validation, same results.
+int lk::build_windows_with_counts(int32_t batch, const int32_t *h_cu_vis, const int32_t *cu_vis, const int32_t *pos,
+                                  const int32_t *new_index, const int32_t *cu_vis_out, int32_t tiles, int32_t grid_h,
+                                  int32_t grid_w, int32_t w, int32_t *win_offsets, int32_t *win_tokens, int32_t n_windows,
+                                  int32_t direction, const int32_t *cu_target, int32_t *win_remove, int32_t *status,
+                                  void *stream) {
+  if ((new_index == nullptr) != (cu_vis_out == nullptr)) return LIGHTKV_ERR_NULL;
+  if (!cu_target || !win_remove) return LIGHTKV_ERR_NULL;
+  if (direction != LIGHTKV_DIRECTION_A_TO_B && direction != LIGHTKV_DIRECTION_B_TO_A) return LIGHTKV_ERR_UNSUPPORTED;
+  const int32_t wps = lightkv_windows_per_sequence(tiles, w);
+  if (batch < 1 || wps < 0 || (int64_t)wps * batch != n_windows) return LIGHTKV_ERR_SHAPE;
+  bool done = false;
+  const lightkv_status st = build_windows_impl(batch, h_cu_vis, cu_vis, pos, new_index, cu_vis_out, tiles, grid_h, grid_w, w,
+                                               win_offsets, win_tokens, stream, cu_target, win_remove, status, direction, &done);
+  if (st != LIGHTKV_OK || done) return st;
+  // the current lengths of the sequences: after the previous stage's compaction in the "next" form
+  return lightkv_window_counts(batch, n_windows, win_offsets, LIGHTKV_COUNT_TARGET, direction, 0.0,
+                               cu_vis_out ? cu_vis_out : cu_vis, cu_target, win_remove, status, stream);
+}
 
 namespace {
 struct SelectOut {   // outputs of lightkv_select, present when selection is to be fused behind the scores

@@ -38,10 +38,20 @@ constexpr int FD_MAX_COLS = 2048;                   // |B| of the largest suppor
 
 FdPlan make_fd_plan(int n_windows, int max_window_tokens, int d, int dtype_bytes);
 
+// cu_target / win_remove / status / dir / counts_done (all optional): the per-window counts of a token budget
+// (launch_window_counts, mode 2) in the same launch where the kernel allows it; *counts_done says whether it did.
 hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, const int32_t *new_index,
                                 const int32_t *cu_out, int batch, int max_seq, int tiles,
                                 int grid_h, int grid_w, int w, int32_t *win_offsets, int32_t *win_tokens,
+                                const int32_t *cu_target, int32_t *win_remove, int32_t *status, int dir, bool *counts_done,
                                 hipStream_t stream);
+
+// windows + their counts from per-sequence target lengths, in one launch where possible (lk_api.hip); a lightkv_status
+int build_windows_with_counts(int32_t batch, const int32_t *h_cu_vis, const int32_t *cu_vis, const int32_t *pos,
+                              const int32_t *new_index, const int32_t *cu_vis_out, int32_t tiles, int32_t grid_h,
+                              int32_t grid_w, int32_t w, int32_t *win_offsets, int32_t *win_tokens, int32_t n_windows,
+                              int32_t direction, const int32_t *cu_target, int32_t *win_remove, int32_t *status,
+                              void *stream);
 
 // per-window counts from a ratio (mode 0: tokens, 1: edges) or from per-sequence target lengths (mode 2)
 hipError_t launch_window_counts(int batch, int win_per_seq, const int32_t *win_offsets, int mode, int dir, double rho,

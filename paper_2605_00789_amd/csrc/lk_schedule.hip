@@ -6,6 +6,7 @@
 #include "../../include/lightkv.h"
 
 #include "lk_helpers.h"
+#include "lk_launch.h"
 
 #include <hip/hip_runtime.h>
 #include <mutex>
@@ -83,11 +84,13 @@ extern "C" lightkv_status lightkv_compress_schedule(const lightkv_stage *stages,
     if (windows_pending) {
       if (win_forked && hipStreamWaitEvent(main, h->event[EV_JOIN_WIN], 0) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
     } else if (rc == LIGHTKV_OK) {
-      rc = lightkv_build_windows(p->batch, p->h_cu_vis, p->cu_vis, posi, tiles, grid_h, grid_w, st.w, st.win_offsets,
-                                 st.win_tokens, main);
-      if (rc == LIGHTKV_OK && st.cu_vis_target)
-        rc = lightkv_window_counts(p->batch, p->n_windows, st.win_offsets, LIGHTKV_COUNT_TARGET, p->direction, 0.0, p->cu_vis,
-                                   st.cu_vis_target, st.win_remove, st.status, main);
+      if (st.cu_vis_target)   // windows and their counts (one launch where the partition kernel allows it)
+        rc = (lightkv_status)lk::build_windows_with_counts(p->batch, p->h_cu_vis, p->cu_vis, posi, nullptr, nullptr, tiles,
+                                                           grid_h, grid_w, st.w, st.win_offsets, st.win_tokens, p->n_windows,
+                                                           p->direction, st.cu_vis_target, st.win_remove, st.status, main);
+      else
+        rc = lightkv_build_windows(p->batch, p->h_cu_vis, p->cu_vis, posi, tiles, grid_h, grid_w, st.w, st.win_offsets,
+                                   st.win_tokens, main);
     }
     windows_pending = false;
     // ---- feature divergence + selection
@@ -108,14 +111,16 @@ extern "C" lightkv_status lightkv_compress_schedule(const lightkv_stage *stages,
       hipStream_t wsx = main;
       if (h && order_after(h->stream[1], main, h->event[EV_FORK_WIN])) { wsx = h->stream[1]; win_forked = true; }
       else if (h) (void)hipGetLastError();
-      rc = lightkv_build_windows_next(p->batch, p->h_cu_vis, p->cu_vis, posi, st.new_index, st.cu_vis_out, tiles, grid_h,
-                                      grid_w, nx.w, nx.win_offsets, nx.win_tokens, wsx);
-      // ... and their counts: the next stage's budget over the windows as they now are (cu_vis_out of this stage is
+      // ... with their counts: the next stage's budget over the windows as they now are (cu_vis_out of this stage is
       // the next stage's cu_vis)
-      if (rc == LIGHTKV_OK && nx.cu_vis_target)
-        rc = lightkv_window_counts(nx.problem.batch, nx.problem.n_windows, nx.win_offsets, LIGHTKV_COUNT_TARGET,
-                                   nx.problem.direction, 0.0,
-                                   st.cu_vis_out, nx.cu_vis_target, nx.win_remove, nx.status, wsx);
+      if (nx.cu_vis_target)
+        rc = (lightkv_status)lk::build_windows_with_counts(p->batch, p->h_cu_vis, p->cu_vis, posi, st.new_index, st.cu_vis_out,
+                                                           tiles, grid_h, grid_w, nx.w, nx.win_offsets, nx.win_tokens,
+                                                           nx.problem.n_windows, nx.problem.direction, nx.cu_vis_target,
+                                                           nx.win_remove, nx.status, wsx);
+      else
+        rc = lightkv_build_windows_next(p->batch, p->h_cu_vis, p->cu_vis, posi, st.new_index, st.cu_vis_out, tiles, grid_h,
+                                        grid_w, nx.w, nx.win_offsets, nx.win_tokens, wsx);
       if (win_forked && hipEventRecord(h->event[EV_JOIN_WIN], h->stream[1]) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
       windows_pending = true;
     }

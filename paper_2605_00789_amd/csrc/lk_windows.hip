@@ -25,6 +25,11 @@ struct WinArgs {
   const int32_t *new_index, *cu_out;
   int batch, tiles, grid_h, grid_w, w, win_per_seq;
   int32_t *win_offsets, *win_tokens;
+  // optional (table kernel only): the per-window counts of the sequences' token budgets in the same launch -- the
+  // window sizes are in LDS at the end of the kernel anyway.  cu_target NULL: no counts.
+  const int32_t *cu_target;   // [batch + 1] offsets of the sequences after the step the windows are built for
+  int32_t *win_remove, *status;
+  int dir;
 };
 
 // index under which token i is listed, or -1 if it does not take part
@@ -57,6 +62,78 @@ __device__ __forceinline__ void wave_bin_rank(int wid, bool valid, int lane, int
       is_leader = (lane == leader);
     }
     remaining &= ~m;
+  }
+}
+
+// ---- the token budget of a sequence spread over its windows (Sec. 3.2.2: the ratios P given as target lengths) ----
+// With cap_w the most a window can give and q the largest level for which sum_w min(cap_w, q) stays within the budget,
+// window w gives min(cap_w, q), and the first windows (in order) that can give more than q give one more until the
+// budget is met.  A budget that cannot be met (negative, or above sum_w cap_w): every window gives its cap (nothing for
+// a negative budget) and the status word is set.  Integer work; run by all NT threads of a workgroup.
+// red, wave_tot: NT / 64 ints of LDS each.
+template <int NT>
+__device__ __forceinline__ int block_sum(int v, int *red) {
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();                              // red may still be read from the previous call
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  int t = 0;
+#pragma unroll
+  for (int i = 0; i < NT / 64; ++i) t += red[i];
+  return t;
+}
+
+template <int NT, typename CapFn>
+__device__ __forceinline__ void counts_target_body(int W, int budget, CapFn cap_of, int32_t *win_remove, int32_t *status,
+                                                   int *red, int *wave_tot) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int total = 0, maxcap = 0;
+  for (int w = tid; w < W; w += NT) { const int c = cap_of(w); total += c; maxcap = c > maxcap ? c : maxcap; }
+  total = block_sum<NT>(total, red);
+  for (int o = 32; o >= 1; o >>= 1) { const int t = __shfl_xor(maxcap, o, 64); maxcap = t > maxcap ? t : maxcap; }
+  __syncthreads();
+  if (lane == 0) red[wave] = maxcap;
+  __syncthreads();
+  maxcap = 0;
+#pragma unroll
+  for (int i = 0; i < NT / 64; ++i) maxcap = red[i] > maxcap ? red[i] : maxcap;
+  const bool infeasible = budget < 0 || budget > total;
+  if (status && tid == 0) *status = infeasible ? 1 : 0;
+  if (infeasible) {   // more than every set A holds: all of them go; a negative budget: nothing goes
+    for (int w = tid; w < W; w += NT) win_remove[w] = budget < 0 ? 0 : cap_of(w);
+    return;
+  }
+  // largest level q in [0, maxcap + 1] with sum_w min(cap_w, q) <= budget
+  int lo = 0, hi = maxcap + 1;
+  while (lo < hi) {   // uniform
+    const int mid = (lo + hi + 1) >> 1;
+    int f = 0;
+    for (int w = tid; w < W; w += NT) { const int c = cap_of(w); f += c < mid ? c : mid; }
+    f = block_sum<NT>(f, red);
+    if (f <= budget) lo = mid; else hi = mid - 1;
+  }
+  const int q = lo;
+  int given = 0;
+  for (int w = tid; w < W; w += NT) { const int c = cap_of(w); given += c < q ? c : q; }
+  given = block_sum<NT>(given, red);
+  const int missing = budget - given;
+  // one more from the first `missing` windows (in order) whose cap exceeds q
+  int carry = 0;
+  for (int wb = 0; wb < W; wb += NT) {   // uniform
+    const int w = wb + tid;
+    const int c = w < W ? cap_of(w) : 0;
+    const int more = (w < W && c > q) ? 1 : 0;
+    int inc = more;
+    for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(inc, o, 64); if (lane >= o) inc += t; }
+    __syncthreads();
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    int before = carry, all = 0;
+#pragma unroll
+    for (int k = 0; k < NT / 64; ++k) { before += (k < wave) ? wave_tot[k] : 0; all += wave_tot[k]; }
+    const int excl = before + inc - more;
+    if (w < W) win_remove[w] = (c < q ? c : q) + ((more && excl < missing) ? 1 : 0);
+    carry += all;
   }
 }
 
@@ -188,6 +265,17 @@ __global__ __launch_bounds__(WIN_THREADS) void build_windows_table_kernel(WinArg
     wave_bin_rank(wid, valid, lane, rank, gs, leader);
     if (valid) g.win_tokens[out_base + winbase[wid] + table[(i >> 6) * wps + wid] + rank] = id;
   }
+  if (g.cu_target) {
+    // the sizes of this sequence's windows are the differences of winbase[] (LDS; the end of the last window is out_n)
+    auto cap_of = [&](int w) {
+      const int v = (w + 1 < wps ? winbase[w + 1] : out_n) - winbase[w];
+      const int c = v >= 2 ? side_a(v, g.dir) : 0;   // the proposing side; a single token has nobody to merge into
+      return c < 65535 ? c : 65535;
+    };
+    const int budget = out_n - (g.cu_target[b + 1] - g.cu_target[b]);
+    counts_target_body<WIN_THREADS>(wps, budget, cap_of, g.win_remove + wbase, g.status ? g.status + b : nullptr, scan_lds,
+                                    scan_lds + 32);
+  }
 }
 
 __global__ __launch_bounds__(WIN_THREADS) void build_windows_sort_kernel(WinArgs g) {
@@ -235,19 +323,11 @@ struct CountArgs {
   double rho;
 };
 
-__device__ __forceinline__ int block_sum_256(int v, int *lds4) {
-  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-  __syncthreads();                              // lds4 may still be read from the previous call
-  if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return lds4[0] + lds4[1] + lds4[2] + lds4[3];
-}
-
 __global__ __launch_bounds__(CNT_THREADS) void window_counts_kernel(CountArgs g) {
   __shared__ int red[4];
   __shared__ int wave_tot[4];
   const int b = blockIdx.x, W = g.win_per_seq, w0 = b * W;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x;
   if (g.mode != 2) {
     for (int w = tid; w < W; w += CNT_THREADS) {
       const long long v = g.win_offsets[w0 + w + 1] - g.win_offsets[w0 + w];
@@ -272,51 +352,7 @@ __global__ __launch_bounds__(CNT_THREADS) void window_counts_kernel(CountArgs g)
   for (int w = tid; w < W && w < CNT_CACHE; w += CNT_THREADS) cap_lds[w] = (uint16_t)cap_mem(w);
   __syncthreads();
   auto cap_of = [&](int w) { return w < CNT_CACHE ? (int)cap_lds[w] : cap_mem(w); };
-  int total = 0, maxcap = 0;
-  for (int w = tid; w < W; w += CNT_THREADS) { const int c = cap_of(w); total += c; maxcap = c > maxcap ? c : maxcap; }
-  total = block_sum_256(total, red);
-  for (int o = 32; o >= 1; o >>= 1) { const int t = __shfl_xor(maxcap, o, 64); maxcap = t > maxcap ? t : maxcap; }
-  __syncthreads();
-  if (lane == 0) red[wave] = maxcap;
-  __syncthreads();
-  maxcap = max(max(red[0], red[1]), max(red[2], red[3]));
-  const bool infeasible = budget < 0 || budget > total;
-  if (g.status && tid == 0) g.status[b] = infeasible ? 1 : 0;
-  if (infeasible) {   // more than every set A holds: all of them go; a negative budget: nothing goes
-    for (int w = tid; w < W; w += CNT_THREADS) g.win_remove[w0 + w] = budget < 0 ? 0 : cap_of(w);
-    return;
-  }
-  // largest level q in [0, maxcap + 1] with sum_w min(cap_w, q) <= budget
-  int lo = 0, hi = maxcap + 1;
-  while (lo < hi) {   // uniform
-    const int mid = (lo + hi + 1) >> 1;
-    int f = 0;
-    for (int w = tid; w < W; w += CNT_THREADS) { const int c = cap_of(w); f += c < mid ? c : mid; }
-    f = block_sum_256(f, red);
-    if (f <= budget) lo = mid; else hi = mid - 1;
-  }
-  const int q = lo;
-  int given = 0;
-  for (int w = tid; w < W; w += CNT_THREADS) { const int c = cap_of(w); given += c < q ? c : q; }
-  given = block_sum_256(given, red);
-  const int missing = budget - given;
-  // one more from the first `missing` windows (in order) whose cap exceeds q
-  int carry = 0;
-  for (int wb = 0; wb < W; wb += CNT_THREADS) {   // uniform
-    const int w = wb + tid;
-    const int c = w < W ? cap_of(w) : 0;
-    const int more = (w < W && c > q) ? 1 : 0;
-    int inc = more;
-    for (int o = 1; o < 64; o <<= 1) { const int t = __shfl_up(inc, o, 64); if (lane >= o) inc += t; }
-    __syncthreads();
-    if (lane == 63) wave_tot[wave] = inc;
-    __syncthreads();
-    int before = carry;
-    for (int k = 0; k < wave; ++k) before += wave_tot[k];
-    const int excl = before + inc - more;
-    if (w < W) g.win_remove[w0 + w] = (c < q ? c : q) + ((more && excl < missing) ? 1 : 0);
-    carry += wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
-  }
+  counts_target_body<CNT_THREADS>(W, budget, cap_of, g.win_remove + w0, g.status ? g.status + b : nullptr, red, wave_tot);
 }
 
 hipError_t launch_window_counts(int batch, int win_per_seq, const int32_t *win_offsets, int mode, int dir, double rho,
@@ -332,7 +368,9 @@ hipError_t launch_window_counts(int batch, int win_per_seq, const int32_t *win_o
 hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, const int32_t *new_index,
                                 const int32_t *cu_out, int batch, int max_seq, int tiles,
                                 int grid_h, int grid_w, int w, int32_t *win_offsets, int32_t *win_tokens,
+                                const int32_t *cu_target, int32_t *win_remove, int32_t *status, int dir, bool *counts_done,
                                 hipStream_t stream) {
+  if (counts_done) *counts_done = false;
   WinArgs g{};
   g.cu_vis = cu_vis; g.pos = pos; g.new_index = new_index; g.cu_out = cu_out; g.batch = batch; g.tiles = tiles; g.grid_h = grid_h; g.grid_w = grid_w; g.w = w;
   g.win_per_seq = (w == 0) ? 1 : tiles * w * w;
@@ -341,6 +379,10 @@ hipError_t launch_build_windows(const int32_t *cu_vis, const int32_t *pos, const
   const int64_t entries = (int64_t)runs * g.win_per_seq;
   const size_t lds = (size_t)(entries + (entries & 1)) * sizeof(uint16_t) + (size_t)g.win_per_seq * sizeof(int);
   if (lds <= WIN_TABLE_LDS_MAX) {
+    if (cu_target && win_remove && counts_done) {   // the counts ride along (the sort fallback leaves them to the caller)
+      g.cu_target = cu_target; g.win_remove = win_remove; g.status = status; g.dir = dir;
+      *counts_done = true;
+    }
     hipLaunchKernelGGL(build_windows_table_kernel, dim3(batch), dim3(WIN_THREADS), lds, stream, g);
   } else {
     const int p2 = next_pow2(max_seq > 1 ? max_seq : 1);
