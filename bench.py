@@ -252,6 +252,39 @@ def similarity_pass(stream, timer, n_inst, full_pairwise):
             "workload": wl.name}
 
 
+def copy_ceiling(stream, timer, total_mb_list=(107, 342, 824), n_inst=20):
+    """A plain device-to-device copy (torch's copy kernel) whose read + write traffic equals that of a launch of the merge
+    kernel, timed the same way as the cold pass: 1 GiB read in front of every launch, HIP events around the one kernel.
+    What a copy reaches is what "HBM bound" can mean at that size on this chip."""
+    import torch
+    dev = torch.device("cuda:0")
+    flush = torch.zeros(1 << 27, dtype=torch.int64, device=dev)
+    sink = torch.zeros((), dtype=torch.int64, device=dev)
+    out = []
+    with torch.cuda.stream(stream):
+        for mb in total_mb_list:
+            n = mb * 1000 * 1000 // 2 // 2          # bf16 elements per side: read n, write n
+            a = torch.empty(n, dtype=torch.bfloat16, device=dev).normal_()
+            b = torch.empty_like(a)
+            b.copy_(a)
+            stream.synchronize()
+            us = 0.0
+            for _ in range(n_inst):
+                torch.sum(flush, dim=(0,), out=sink)
+                e0, e1 = timer.pair()
+                e0.record(stream)
+                b.copy_(a)
+                e1.record(stream)
+                stream.synchronize()
+                us += timer.us(e0, e1) / n_inst
+            gbs = 4.0 * n / (us * 1e-6) / 1e9
+            out.append({"traffic_MB": round(4.0 * n / 1e6, 1), "us": round(us, 2), "GBps": round(gbs, 1),
+                        "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)})
+            del a, b
+    del flush, sink
+    return out
+
+
 def ceilings_pass(stream):
     """What the chip delivers to the dense contractions, measured with the probe library (no method arithmetic): the
     operand loads of the tiled FD kernels alone (every byte comes out of L2: nothing is reused through L1), and bare
@@ -573,6 +606,7 @@ def main():
     if only == "ceilings":
         with torch.cuda.stream(stream):
             out["ceilings"] = ceilings_pass(stream)
+        out["ceilings"]["plain_copy_cold"] = copy_ceiling(stream, timer)
 
     if not args.no_cpu_baseline and only == "all":
         from oracle import lightkv_oracle as O
