@@ -79,6 +79,33 @@ __device__ __forceinline__ void stage_prompt_rows(const XiArgs &g, char *q_lds, 
   }
 }
 
+// The same copy in two halves, so that other loads can be issued between the global loads and the LDS stores that wait
+// for them.
+template <typename T, int DH, int RW>
+__device__ __forceinline__ void load_prompt_rows(const XiArgs &g, int t0, int nT, int j0, int64_t txt_ho,
+                                                 uint4 (&v)[XiStage<T, DH, RW>::ROWS / (XI_THREADS / XiStage<T, DH, RW>::CPR)]) {
+  using S = XiStage<T, DH, RW>;
+  constexpr int BYTES = Elem<T>::BYTES;
+  constexpr int PER_PASS = XI_THREADS / S::CPR;
+  const int c = threadIdx.x % S::CPR, r0 = threadIdx.x / S::CPR;
+#pragma unroll
+  for (int p = 0; p < S::ROWS / PER_PASS; ++p) {
+    const int j = j0 + p * PER_PASS + r0;
+    const int tok = t0 + (j < nT ? j : nT - 1);
+    v[p] = ld16(static_cast<const char *>(g.txt) + ((int64_t)tok * g.txt_ts + txt_ho) * BYTES + c * 16);
+  }
+}
+template <typename T, int DH, int RW>
+__device__ __forceinline__ void store_prompt_rows(char *q_lds,
+                                                  const uint4 (&v)[XiStage<T, DH, RW>::ROWS / (XI_THREADS / XiStage<T, DH, RW>::CPR)]) {
+  using S = XiStage<T, DH, RW>;
+  constexpr int PER_PASS = XI_THREADS / S::CPR;
+  const int c = threadIdx.x % S::CPR, r0 = threadIdx.x / S::CPR;
+#pragma unroll
+  for (int p = 0; p < S::ROWS / PER_PASS; ++p)
+    *reinterpret_cast<uint4 *>(q_lds + (p * PER_PASS + r0) * S::PITCH + c * 16) = v[p];
+}
+
 template <typename T, int DH>
 __device__ __forceinline__ void read_prompt_frag(const char *q_lds, int row, int half, uint4 *v) {
   using S = XiStage<T, DH, 64>;   // pitch and row size do not depend on the chunk length
@@ -207,7 +234,11 @@ __device__ __forceinline__ void xi_colsum_body(const XiArgs &g, int block_id, ch
   float colsum = 0.f;
   for (int j0 = 0; j0 < nT; j0 += S::ROWS) {
     __syncthreads();   // the previous chunk has been consumed
-    stage_prompt_rows<T, DH, RW>(g, q_lds, t0, nT, j0, txt_ho);
+    // the prompt rows' loads go out first; the row statistics below issue their own loads behind them, and the LDS
+    // stores that have to wait for the prompt rows come after both (one trip to memory instead of two in a row)
+    uint4 staged[S::ROWS / (XI_THREADS / S::CPR)];
+    load_prompt_rows<T, DH, RW>(g, t0, nT, j0, txt_ho, staged);
+    if (VISION_LSE) store_prompt_rows<T, DH, RW>(q_lds, staged);
     if (!VISION_LSE) {
       // (max, 1/sum) of every prompt row of the chunk.  TPR threads share a row: each merges every TPR-th
       // per-block pair of pass 1 (its loads in flight together), then the partial results are merged by
@@ -254,6 +285,7 @@ __device__ __forceinline__ void xi_colsum_body(const XiArgs &g, int block_id, ch
         }
         if (j < nT) { m = pm; inv = 1.f / psum; }
       }
+      store_prompt_rows<T, DH, RW>(q_lds, staged);
       if (part == 0) rowstat[idx] = make_float2(m, inv);   // rows past nT get weight 0
     }
     __syncthreads();
