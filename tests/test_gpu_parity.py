@@ -908,6 +908,10 @@ def test_edge_topk_edge_cases():
             rep, _ = check_edge_step(sched_for(wl, 1), 0, wl.cu_vis, wl.X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype,
                                      h_win_edges=np.array(k, dtype=np.int32), host_mirror=mirror)
             print("[edge cases] (e) %s k=%s mirror=%s: %d -> %d tokens, %d edges" % (dtype, k, mirror, rep.n_in, rep.n_out, rep.edges), flush=True)
+    # ... and the distance metrics on such windows
+    for metric in ("euclidean", "l2sq"):
+        rep, _ = check_edge_step(sched_for(wl, 1, metric), 0, wl.cu_vis, wl.X, wl.K, wl.V, wl.Q, wl.pos, wl.dtype)
+        print("[edge cases] (e) %s: %d -> %d tokens, %d edges, %d tied" % (metric, rep.n_in, rep.n_out, rep.edges, rep.window_ties), flush=True)
     # (f) identical tokens in a large window: every FD is exactly zero, the pair index decides (the two extra radix passes)
     wl = make_custom(name="edge_f", seed=36, dtype="bf16", batch=1, grid_h=20, grid_w=21, text_lens=(7,), d=256, heads=2,
                      head_dim=128, windows_per_axis=(1,), n_final=300)
