@@ -162,7 +162,8 @@ def rows_cold_pass(wl, pipe, tensors, stream, timer, n_inst):
     """The merge kernel of every stage with L2 and Infinity Cache holding none of its inputs: a 1 GiB buffer is READ in
     front of every launch (clean lines: a flush by writing would leave the caches full of dirty lines whose write-back
     then competes with the kernel).  Stage inputs and index structures are those a run of the schedule left behind.
-    Returns microseconds per stage (mean over n_inst launches)."""
+    Returns microseconds per stage (mean over n_inst launches); the single launches are kept in `rows_cold_pass.samples`
+    (a list per stage) for the spread that goes into the line."""
     import torch
     from paper_2605_00789_amd import binding as B
     X, K, V, Q, pos = tensors
@@ -170,6 +171,7 @@ def rows_cold_pass(wl, pipe, tensors, stream, timer, n_inst):
     flush = torch.zeros(1 << 27, dtype=torch.int64, device=dev)
     sink = torch.zeros((), dtype=torch.int64, device=dev)
     per_stage = [0.0] * wl.stages
+    samples = [[] for _ in range(wl.stages)]
     with torch.cuda.stream(stream):
         pipe.run(X, K, V, Q, pos)
         stream.synchronize()
@@ -188,15 +190,28 @@ def rows_cold_pass(wl, pipe, tensors, stream, timer, n_inst):
                 Xi, Ki, Vi, pi = st.X_out, st.K_out, st.V_out, st.pos_out
             stream.synchronize()
             for s, (a, b) in enumerate(evs):
-                per_stage[s] += timer.us(a, b) / n_inst
+                us = timer.us(a, b)
+                per_stage[s] += us / n_inst
+                samples[s].append(us)
     del flush, sink
+    rows_cold_pass.samples = samples
     return per_stage
 
 
-def _rows_roofline(wl, per_stage_us, n_ins, regime):
+def _rows_roofline(wl, per_stage_us, n_ins, regime, samples=None):
     rows_b = [rows_bytes(wl, n_ins[s], wl.targets[s]) for s in range(wl.stages)]
     tot_us, tot_b = sum(per_stage_us), sum(rows_b)
     ach = tot_b / (tot_us * 1e-6) / 1e9 if tot_us > 0 else 0.0
+    spread = {}
+    if samples:   # per stage: 10th percentile, median, 90th percentile of the single launches
+        def pct(v, q):
+            v = sorted(v)
+            return round(v[min(len(v) - 1, int(q * len(v)))], 2)
+        spread = {"launch_us_p10_p50_p90_per_stage": [[pct(v, 0.1), pct(v, 0.5), pct(v, 0.9)] for v in samples]}
+    return {**_rows_roofline_core(wl, regime, ach, tot_us, per_stage_us, tot_b), **spread}
+
+
+def _rows_roofline_core(wl, regime, ach, tot_us, per_stage_us, tot_b):
     return {"kernel": "rows_kernel (lightkv_aggregate_compact)", "bound": "hbm", "regime": regime,
             "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
             "launches_per_step": wl.stages, "avg_launch_us": round(tot_us / wl.stages, 2),
@@ -578,8 +593,8 @@ def main():
 
     # ---- the dominant kernel with caches flushed in front of every launch: the regime the fractions are quoted from
     if want("cold"):
-        cold = _rows_roofline(wl, rows_cold_pass(wl, pipe, tensors, stream, timer, n_inst), n_ins,
-                              "cold: 1 GiB read in front of every launch")
+        cold_us = rows_cold_pass(wl, pipe, tensors, stream, timer, n_inst)
+        cold = _rows_roofline(wl, cold_us, n_ins, "cold: 1 GiB read in front of every launch", samples=rows_cold_pass.samples)
         traffic, src = measured_traffic(wl.name)
         cold["traffic"] = traffic
         cold["traffic_source"] = ("committed profile %s (not measured by this run)" % src) if src else None
@@ -592,9 +607,9 @@ def main():
         wl5 = make_workload(5)
         pipe5, tensors5 = _pipeline(wl5, dev)
         n_ins5 = [wl5.n_per_seq] + list(wl5.targets[:-1])
-        out["roofline_hbm_primary"] = _rows_roofline(
-            wl5, rows_cold_pass(wl5, pipe5, tensors5, stream, timer, max(5, n_inst // 2)), n_ins5,
-            "cold: 1 GiB read in front of every launch")
+        cold5_us = rows_cold_pass(wl5, pipe5, tensors5, stream, timer, max(5, n_inst // 2))
+        out["roofline_hbm_primary"] = _rows_roofline(wl5, cold5_us, n_ins5, "cold: 1 GiB read in front of every launch",
+                                                     samples=rows_cold_pass.samples)
         del pipe5, tensors5, wl5
 
     # ---- the dense contractions of the 2880-token window against the matrix-core peak
