@@ -19,7 +19,6 @@ struct RowArgs {
   float *x_sqnorm_out;   // optional: |x|^2 of every output row of tensor 0 (as stored), fp32
   const float *xi;
   int d, sum_n, mode;
-  int look_first;     // 1: read new_index before fetching the row (see rows_kernel)
   int64_t out_rows;   // capacity of the compacted outputs; rows beyond it are dropped
 };
 
@@ -56,15 +55,11 @@ template <> struct RowIO<float> {
 // unconditional (clamped addresses) so that the compiler never has to wait inside a branch.
 constexpr int ROWS_PER_WG = ROW_THREADS / WAVE;
 constexpr int ROW_UNROLL = 8;   // 16-byte chunks per lane and pass
-// Inputs up to this size sit in the Infinity Cache when the kernel runs (the score kernels have just read them); above
-// it the rows stream from HBM.
-constexpr int64_t ROWS_CACHED_BYTES = 160ll << 20;
 constexpr int64_t ROWS_STREAM_OUT_BYTES = 128ll << 20;   // inputs beyond this: nontemporal output stores
 
 // MODE 0: aggregate in place   1: compact   2: aggregate + compact
 //
 // Dependent loads are what this kernel waits for, so they are arranged in as few rounds as possible:
-//   (round 0  new_index alone, when the inputs are cache resident: see look_first below)
 //   round 1  the row itself, xi of the row, new_index and the group bounds (all depend on the row number only)
 //   round 2  the source list of the group
 //   round 3  xi of the sources and the rows of the first two sources, together
@@ -93,17 +88,12 @@ __global__ __launch_bounds__(ROW_THREADS) void rows_kernel(RowArgs g) {
   uint4 v[ROW_UNROLL];
   const char *row_in = in ? in + (int64_t)b * ld_in : nullptr;
   if (MODE == 0 && g.grp_offsets[b + 1] == g.grp_offsets[b]) return;
-  // A row that is merged away need not be fetched by its own wave at all (its target's wave reads it): looking at
-  // new_index first saves those bytes (8-11 % of the reads) but puts one more dependent load in front of every row.
-  // That pays while the loads are served by the Infinity Cache; when the rows stream from HBM the longer life of every
-  // wave costs more than the bytes saved, and the row is fetched together with its indices instead.  Large outputs are
-  // also stored nontemporally: they cannot stay cached until the next stage reads them, and kept out of the caches
-  // they leave them to the kernels that run next (batch of 16: step -3.6 %; on the cache-resident sizes the same stores
-  // cost +2.4 %: the next stage's kernels then find their inputs in HBM).
-  if (MODE != 0 && g.look_first) {
-    const int o = g.new_index[b];
-    if (o < 0 || o >= g.out_rows) return;
-  }
+  // A row that is merged away is fetched by its own wave as well as by its target's (8-11 % more bytes read): looking
+  // at new_index first would save those bytes but puts one more dependent load in front of every row, and the longer
+  // life of every wave costs more than the bytes (single launch on 2880 tokens: 26.8 -> 23.9 us without the look).
+  // Large outputs are stored nontemporally: they cannot stay cached until the next stage reads them, and kept out of
+  // the caches they leave them to the kernels that run next (batch of 16: step -3.6 %; on the cache-resident sizes the
+  // same stores cost +2.4 %: the next stage's kernels then find their inputs in HBM).
   if (in != nullptr) {
 #pragma unroll
     for (int u = 0; u < ROW_UNROLL; ++u) {
@@ -311,7 +301,6 @@ hipError_t launch_rows(int mode, int dtype, int d, int sum_n, const RowTensors &
   g.pos_out = pos_out; g.xi = xi; g.d = d; g.sum_n = sum_n; g.mode = mode; g.out_rows = out_rows;
   int n_tensors = 0;
   for (int i = 0; i < 3; ++i) n_tensors += t.in[i] != nullptr;
-  g.look_first = (int64_t)sum_n * d * (dtype == 1 ? 2 : 4) * n_tensors <= ROWS_CACHED_BYTES;
   // nontemporal output stores once the tensors are far beyond what stays cached until the next stage reads them
   const bool stream_out = mode != 0 && (int64_t)sum_n * d * (dtype == 1 ? 2 : 4) * n_tensors > ROWS_STREAM_OUT_BYTES;
   const dim3 grid((unsigned)((sum_n + ROWS_PER_WG - 1) / ROWS_PER_WG), 3);
