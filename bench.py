@@ -421,7 +421,7 @@ def bench_variant(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "match": args.match, "rho": rho, "batch": wl.batch, "stages": len(ws_axis),
                    "windows_per_axis": ws_axis, "tokens_in_per_stage": n_in, "tokens_out_per_stage": n_out,
-                   "counts_per_stage": [int(r.h_win_edges.sum()) for r in res], "launch": "eager; buffers allocated once, counts on the device, one read-back per stage (the batch + 1 sequence offsets)"},
+                   "counts_per_stage": [int(r.h_win_edges.sum()) for r in res], "launch": "one library call (lightkv_compress_schedule_ratio): eager, buffers allocated once, counts on the device, one read-back per stage (the batch + 1 sequence offsets); calls_us from the same stages driven call by call"},
         "roofline": {"kernel": "rows_kernel (lightkv_aggregate_compact)", "bound": "hbm", "regime": "in the step",
                      "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
                      "traffic": None, "launches_per_step": len(ws_axis), "avg_launch_us": round(rows_us / len(ws_axis), 2),

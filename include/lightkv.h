@@ -25,13 +25,14 @@
  *   - state the library keeps between calls (per device, host-side handles only,
  *     created on first use outside stream capture, default priority, never
  *     destroyed): one helper stream with two events for lightkv_score, two helper
- *     streams with four events for lightkv_compress_schedule, and the "large LDS"
+ *     streams with four events for the two schedule calls, and the "large LDS"
  *     attribute of three kernels.  Calls whose `stream` is being captured never
  *     touch the helper streams: they enqueue everything on `stream` in order, so
  *     a capture only ever contains the caller's stream.
  *   - all work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) or on helper streams that fork from and rejoin it before the
- *     call returns; no call synchronises or reads device memory on the host.
+ *     call returns; no call synchronises or reads device memory on the host, with
+ *     one exception that says so: lightkv_compress_schedule_ratio.
  *   - tensors are token-major: row i holds the `d` contiguous elements of token i;
  *     `ld*` are row strides in elements.  Sequences of a batch are packed one after
  *     the other; cu_vis / cu_txt are their [batch+1] offsets.
@@ -430,7 +431,7 @@ typedef struct lightkv_stage {
  * LIGHTKV_ONE_STREAM_MAX_TOKENS tokens whose windows hold at most 64 tokens use the one-stream form of
  * lightkv_score_select instead.  One workspace serves all stages: ws_bytes must cover lightkv_workspace_size of every
  * stage.  Host threads calling this on one device take turns enqueueing.  Only LIGHTKV_MATCH_BEST_PER_A (fixed token
- * counts) is supported here.
+ * counts) is supported here; lightkv_compress_schedule_ratio below takes the others.
  * Errors: the first failing call's status; stages before it have been enqueued.
  */
 lightkv_status lightkv_compress_schedule(const lightkv_stage *stages, int32_t n_stages,
@@ -439,6 +440,37 @@ lightkv_status lightkv_compress_schedule(const lightkv_stage *stages, int32_t n_
                                          const void *V, int64_t ldv, const int32_t *pos,
                                          const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
                                          float softmax_scale, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The schedule when the token count a stage leaves depends on the data: LIGHTKV_MATCH_EDGE_TOPK (Step 2 of Sec. 3.2.1
+ * read literally: the k lowest edges of a window), LIGHTKV_MATCH_FULL_PAIRWISE (appendix "Bipartite vs. full pairwise
+ * matching"), or LIGHTKV_MATCH_BEST_PER_A driven by the ratio of Sec. 3.2.2 instead of fixed budgets.  rho[n_stages]
+ * (host) is the ratio of every stage; the per-window counts are computed on the device from the windows as they are
+ * (lightkv_window_counts: LIGHTKV_COUNT_EDGES for EDGE_TOPK, LIGHTKV_COUNT_RATIO otherwise) and consumed there.
+ * Per stage the call enqueues lightkv_build_windows + lightkv_window_counts (stage 0; later stages' windows and counts
+ * are built by lightkv_build_windows_next next to the previous stage's merge, on a helper stream as in
+ * lightkv_compress_schedule), lightkv_score_select (xi from Q and the stage's K rows, TEXT_QUERY) and
+ * lightkv_aggregate_compact -- with the same results as those calls, bit for bit -- then copies the stage's cu_vis_out
+ * to h_cu_vis_out[s * (batch+1) ...] (host, [n_stages * (batch+1)], out) and WAITS for `stream`: the next stage's launch
+ * plans need those offsets.  One synchronisation per stage; the call cannot be captured into a graph (a capturing
+ * stream -> LIGHTKV_ERR_UNSUPPORTED, nothing enqueued).  When it returns LIGHTKV_OK every stage has finished.
+ * Of the descriptors: stages[0].problem carries the input's h_cu_vis / cu_vis; for s > 0 those two fields are ignored
+ * (the library uses what stage s-1 left).  problem.max_window_tokens is required for every stage (a bound from the cell
+ * geometry, lightkv_max_window_cells, holds whatever the earlier stages removed); h_win_offsets, h_win_remove and
+ * cu_vis_target must be NULL; win_remove is required and must be the array problem.win_remove points to; status is not
+ * used.  Every per-token array of a stage must hold the tokens of stage 0's input (no stage has more), grp_src as
+ * lightkv_score_select states, out_rows at least the rows the stage leaves (checked after the stage ->
+ * LIGHTKV_ERR_SHAPE).  ws_bytes should cover lightkv_workspace_size of every stage's descriptor laid over stage 0's
+ * offsets; each stage's real need is checked when it is reached (-> LIGHTKV_ERR_WORKSPACE).
+ * Errors: the first failing call's status; stages before it have run.
+ */
+lightkv_status lightkv_compress_schedule_ratio(const lightkv_stage *stages, int32_t n_stages, const double *rho,
+                                               int32_t tiles, int32_t grid_h, int32_t grid_w,
+                                               const void *X, int64_t ldx, const void *K, int64_t ldk,
+                                               const void *V, int64_t ldv, const int32_t *pos,
+                                               const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
+                                               float softmax_scale, void *ws, size_t ws_bytes,
+                                               int32_t *h_cu_vis_out, void *stream);
 
 #ifdef __cplusplus
 }

@@ -90,12 +90,16 @@ def _load():
     lib.lightkv_compress_schedule.restype = C.c_int
     lib.lightkv_compress_schedule.argtypes = [C.POINTER(_CStage), i32, i32, i32, i32, vp, i64, vp, i64, vp, i64, vp,
                                               vp, i64, i64, f32, vp, sz, vp]
+    lib.lightkv_compress_schedule_ratio.restype = C.c_int
+    lib.lightkv_compress_schedule_ratio.argtypes = [C.POINTER(_CStage), i32, C.POINTER(C.c_double), i32, i32, i32, vp, i64,
+                                                    vp, i64, vp, i64, vp, vp, i64, i64, f32, vp, sz, vp, vp]
     return lib
 
 
 _lib = _load()
 
 EXPORTS = ("lightkv_status_string", "lightkv_version", "lightkv_workspace_size", "lightkv_build_windows", "lightkv_compress_schedule",
+           "lightkv_compress_schedule_ratio",
            "lightkv_build_windows_next", "lightkv_windows_per_sequence", "lightkv_max_window_cells", "lightkv_window_counts",
            "lightkv_score", "lightkv_score_select", "lightkv_select", "lightkv_select_static", "lightkv_aggregate", "lightkv_compact", "lightkv_aggregate_compact")
 
@@ -333,3 +337,20 @@ def lightkv_compress_schedule(stages: StageArray, tiles, grid_h, grid_w, X, K, V
                                           _dptr(V), _ld(V), _dptr(pos), _dptr(Q), int(Q.stride(0)), hd,
                                           float(softmax_scale), _dptr(ws), ws.numel() * ws.element_size(),
                                           _stream(stream)), "lightkv_compress_schedule")
+
+
+def lightkv_compress_schedule_ratio(stages: StageArray, rho, tiles, grid_h, grid_w, X, K, V, pos, Q, ws, *,
+                                    softmax_scale=0.0, stream=None) -> np.ndarray:
+    """All stages of a schedule whose token counts depend on the data, in one call (it waits for the stream once per
+    stage).  rho: one ratio per stage.  Returns the [n_stages, batch + 1] sequence offsets the stages left (host)."""
+    prob = stages.keep[0]["problem"].c
+    if len(rho) != stages.n:
+        raise ValueError("one ratio per stage")
+    rho_c = (C.c_double * stages.n)(*[float(r) for r in rho])
+    h_out = np.zeros((stages.n, prob.batch + 1), dtype=np.int32)
+    _check(_lib.lightkv_compress_schedule_ratio(stages.c, stages.n, rho_c, tiles, grid_h, grid_w, _dptr(X), _ld(X),
+                                                _dptr(K), _ld(K), _dptr(V), _ld(V), _dptr(pos), _dptr(Q),
+                                                int(Q.stride(0)), prob.head_dim, float(softmax_scale), _dptr(ws),
+                                                ws.numel() * ws.element_size(), h_out.ctypes.data_as(C.c_void_p),
+                                                _stream(stream)), "lightkv_compress_schedule_ratio")
+    return h_out

@@ -2,7 +2,9 @@
 // enqueued through the library's own entry points, arranged over the caller's stream and two helper streams so that
 //   - xi (needs only Q and the stage's K rows) runs next to the feature-divergence chain and the selection,
 //   - the next stage's windows (need only pos and the selection) are built next to the merge of the rows.
-// Nothing here launches a kernel itself, allocates device memory or synchronises.
+// Nothing here launches a kernel itself or allocates device memory.  lightkv_compress_schedule never synchronises;
+// lightkv_compress_schedule_ratio (token counts that depend on the data) waits for the stream once per stage, to read
+// the sequence offsets the stage left.
 #include "../../include/lightkv.h"
 
 #include "lk_helpers.h"
@@ -10,6 +12,7 @@
 
 #include <hip/hip_runtime.h>
 #include <mutex>
+#include <algorithm>
 
 namespace {
 
@@ -138,5 +141,136 @@ extern "C" lightkv_status lightkv_compress_schedule(const lightkv_stage *stages,
   // whatever happened, nothing stays forked: the helper streams rejoin the caller's
   if (xi_forked) (void)hipStreamWaitEvent(main, h->event[EV_JOIN_XI], 0);
   if (win_forked) (void)hipStreamWaitEvent(main, h->event[EV_JOIN_WIN], 0);
+  return rc;
+}
+
+// The schedule when a stage's token count depends on the data (the k lowest edges of a window, the full pairwise
+// visit, or any matching driven by the ratio of Sec. 3.2.2 instead of fixed budgets): per-window counts come from the
+// window sizes on the device, and the batch + 1 sequence offsets a stage leaves are read back before the next stage is
+// laid out -- the one synchronisation per stage.
+extern "C" lightkv_status lightkv_compress_schedule_ratio(const lightkv_stage *stages, int32_t n_stages, const double *rho,
+                                                          int32_t tiles, int32_t grid_h, int32_t grid_w,
+                                                          const void *X, int64_t ldx, const void *K, int64_t ldk,
+                                                          const void *V, int64_t ldv, const int32_t *pos,
+                                                          const void *Q, int64_t q_tok_stride, int64_t q_head_stride,
+                                                          float softmax_scale, void *ws, size_t ws_bytes,
+                                                          int32_t *h_cu_vis_out, void *stream) {
+  if (!stages || !rho || !X || !K || !V || !pos || !Q || !h_cu_vis_out) return LIGHTKV_ERR_NULL;
+  if (n_stages < 1) return LIGHTKV_ERR_SHAPE;
+  const int batch = stages[0].problem.batch;
+  if (batch < 1) return LIGHTKV_ERR_SHAPE;
+  for (int s = 0; s < n_stages; ++s) {
+    const lightkv_stage &st = stages[s];
+    if (st.reserved != 0 || st.cu_vis_target) return LIGHTKV_ERR_UNSUPPORTED;
+    if (!st.win_offsets || !st.win_tokens || !st.win_remove || !st.xi || !st.best_fd || !st.best_dst || !st.dst ||
+        !st.new_index || !st.grp_offsets || !st.grp_src || !st.cu_vis_out || !st.X_out || !st.K_out || !st.V_out ||
+        !st.pos_out)
+      return LIGHTKV_ERR_NULL;
+    if (st.problem.win_offsets != st.win_offsets || st.problem.win_tokens != st.win_tokens ||
+        st.problem.win_remove != st.win_remove)
+      return LIGHTKV_ERR_SHAPE;
+    // counts and window sizes are the device's alone here
+    if (st.problem.h_win_offsets || st.problem.h_win_remove) return LIGHTKV_ERR_UNSUPPORTED;
+    if (st.problem.batch != batch || st.problem.d != stages[0].problem.d || st.problem.max_window_tokens <= 0 ||
+        st.problem.n_windows % batch != 0)
+      return LIGHTKV_ERR_SHAPE;
+    if (!(rho[s] >= 0.0 && rho[s] <= 1e6)) return LIGHTKV_ERR_SHAPE;
+  }
+  if (!stages[0].problem.h_cu_vis || !stages[0].problem.cu_vis) return LIGHTKV_ERR_NULL;
+  hipStream_t main = static_cast<hipStream_t>(stream);
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(main, &cs) != hipSuccess) { (void)hipGetLastError(); return LIGHTKV_ERR_LAUNCH; }
+  if (cs != hipStreamCaptureStatusNone) return LIGHTKV_ERR_UNSUPPORTED;   // the call waits for the stream: not capturable
+  std::unique_lock<std::mutex> guard;
+  Helpers *h = lk::acquire_helpers<2, 4>(main, guard);
+
+  const int d = stages[0].problem.d, head_dim = stages[0].problem.head_dim;
+  const void *Xi = X, *Ki = K, *Vi = V;
+  int64_t ldxi = ldx, ldki = ldk, ldvi = ldv;
+  const int32_t *posi = pos;
+  const float *sq = nullptr;
+  const int32_t *h_cu = stages[0].problem.h_cu_vis;   // offsets of the stage's input: on the host ...
+  const int32_t *d_cu = stages[0].problem.cu_vis;     // ... and on the device
+  bool windows_pending = false, win_forked = false;
+  lightkv_status rc = LIGHTKV_OK;
+  for (int s = 0; s < n_stages && rc == LIGHTKV_OK; ++s) {
+    const lightkv_stage &st = stages[s];
+    lightkv_problem q = st.problem;
+    q.h_cu_vis = h_cu;
+    q.cu_vis = d_cu;
+    int max_seq = 0;
+    for (int b = 0; b < batch; ++b) max_seq = std::max(max_seq, h_cu[b + 1] - h_cu[b]);
+    // a window holds no more tokens than its sequence: the tighter bound picks the cheaper launch plans; the plans are
+    // not monotone in it, so if that one wants more workspace than there is, the stage's own bound is used
+    const int bound = st.problem.max_window_tokens;
+    q.max_window_tokens = std::max(1, std::min(bound, max_seq));
+    size_t need = 0;
+    rc = lightkv_workspace_size(&q, &need);
+    if (rc == LIGHTKV_OK && (!ws || ws_bytes < need) && q.max_window_tokens != bound) {
+      q.max_window_tokens = bound;
+      rc = lightkv_workspace_size(&q, &need);
+    }
+    if (rc == LIGHTKV_OK && (!ws || ws_bytes < need)) rc = LIGHTKV_ERR_WORKSPACE;
+    const int count_mode = q.match == LIGHTKV_MATCH_EDGE_TOPK ? LIGHTKV_COUNT_EDGES : LIGHTKV_COUNT_RATIO;
+    // ---- windows and their counts: built next to the previous stage's merge, or here
+    if (windows_pending) {
+      if (win_forked && hipStreamWaitEvent(main, h->event[EV_JOIN_WIN], 0) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
+      win_forked = false;
+    } else if (rc == LIGHTKV_OK) {
+      rc = lightkv_build_windows(batch, h_cu, d_cu, posi, tiles, grid_h, grid_w, st.w, st.win_offsets, st.win_tokens, main);
+      if (rc == LIGHTKV_OK)
+        rc = lightkv_window_counts(batch, q.n_windows, st.win_offsets, count_mode, q.direction, rho[s], nullptr, nullptr,
+                                   st.win_remove, nullptr, main);
+    }
+    windows_pending = false;
+    // ---- scores (xi and feature divergence) and selection
+    if (rc == LIGHTKV_OK)
+      rc = lightkv_score_select(&q, Xi, ldxi, sq, Q, q_tok_stride, q_head_stride, Ki, ldki, head_dim, LIGHTKV_XI_TEXT_QUERY,
+                                nullptr, softmax_scale, st.xi, st.best_fd, st.best_dst, st.dst, st.new_index, st.grp_offsets,
+                                st.grp_src, st.cu_vis_out, ws, ws_bytes, main);
+    // ---- the next stage's windows and counts follow from the selection alone: next to the merge
+    if (rc == LIGHTKV_OK && s + 1 < n_stages) {
+      const lightkv_stage &nx = stages[s + 1];
+      const int nx_mode = nx.problem.match == LIGHTKV_MATCH_EDGE_TOPK ? LIGHTKV_COUNT_EDGES : LIGHTKV_COUNT_RATIO;
+      hipStream_t wsx = main;
+      if (h && order_after(h->stream[1], main, h->event[EV_FORK_WIN])) { wsx = h->stream[1]; win_forked = true; }
+      else if (h) (void)hipGetLastError();
+      rc = lightkv_build_windows_next(batch, h_cu, d_cu, posi, st.new_index, st.cu_vis_out, tiles, grid_h, grid_w, nx.w,
+                                      nx.win_offsets, nx.win_tokens, wsx);
+      if (rc == LIGHTKV_OK)
+        rc = lightkv_window_counts(batch, nx.problem.n_windows, nx.win_offsets, nx_mode, nx.problem.direction, rho[s + 1],
+                                   nullptr, nullptr, nx.win_remove, nullptr, wsx);
+      if (win_forked && hipEventRecord(h->event[EV_JOIN_WIN], h->stream[1]) != hipSuccess) rc = rc == LIGHTKV_OK ? LIGHTKV_ERR_LAUNCH : rc;
+      windows_pending = true;
+    }
+    // ---- merge and compact
+    if (rc == LIGHTKV_OK)
+      rc = lightkv_aggregate_compact(&q, st.new_index, st.grp_offsets, st.grp_src, st.xi, Xi, ldxi, Ki, ldki, Vi, ldvi, posi,
+                                     st.X_out, st.K_out, st.V_out, st.pos_out, st.x_sqnorm_out, st.out_rows, 0, nullptr, main);
+    // ---- the offsets the stage left: the next stage's descriptor
+    int32_t *h_out = h_cu_vis_out + (size_t)s * (batch + 1);
+    if (rc == LIGHTKV_OK &&
+        (hipMemcpyAsync(h_out, st.cu_vis_out, sizeof(int32_t) * (batch + 1), hipMemcpyDeviceToHost, main) != hipSuccess ||
+         hipStreamSynchronize(main) != hipSuccess)) {
+      (void)hipGetLastError();
+      rc = LIGHTKV_ERR_LAUNCH;
+    }
+    if (rc == LIGHTKV_OK) {
+      // a sequence never grows, and everything that stays must have found room in the stage's outputs
+      bool ok = h_out[0] == 0;
+      for (int b = 0; ok && b < batch; ++b) {
+        const int n = h_out[b + 1] - h_out[b];
+        ok = n >= 0 && n <= h_cu[b + 1] - h_cu[b];
+      }
+      if (!ok || h_out[batch] > st.out_rows) rc = LIGHTKV_ERR_SHAPE;
+    }
+    Xi = st.X_out; Ki = st.K_out; Vi = st.V_out;
+    ldxi = ldki = ldvi = d;
+    posi = st.pos_out;
+    sq = st.x_sqnorm_out;
+    h_cu = h_out;
+    d_cu = st.cu_vis_out;
+  }
+  if (win_forked) (void)hipStreamWaitEvent(main, h->event[EV_JOIN_WIN], 0);   // nothing stays forked
   return rc;
 }

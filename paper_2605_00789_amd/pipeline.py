@@ -247,11 +247,14 @@ class EdgeTopKSchedule:
       match="edge_topk"      the k lowest-FD edges per window (LIGHTKV_MATCH_EDGE_TOPK, k = floor(rho v / 2) as
                              Sec. 3.2.1 counts the pairs), windows of any size the library takes;
       match="full_pairwise"  every token against every other token of its window (LIGHTKV_MATCH_FULL_PAIRWISE, the
-                             appendix ablation), at most floor(rho v) tokens leave a window.
+                             appendix ablation), at most floor(rho v) tokens leave a window;
+      match="best_per_a"     the default matching with r_w = floor(rho v_w) taken from the windows as they are
+                             (Sec. 3.2.2's ratio instead of fixed token budgets).
     Every buffer is allocated once, here, for the largest step (the first); the per-window counts are computed and
     consumed on the device.  The one thing the host reads back per step is cu_vis_out, the batch + 1 sequence offsets
     after the step: the next step's descriptor needs them.  Nothing here is captured in a graph (the sizes of a step
-    depend on the data of the one before)."""
+    depend on the data of the one before).  run() is one library call (lightkv_compress_schedule_ratio); run_step() and
+    run_steps() drive the same stages call by call."""
 
     def __init__(self, *, dtype: str, batch: int, d: int, heads: int, head_dim: int, tiles: int, grid_h: int,
                  grid_w: int, cu_txt: np.ndarray, windows_per_axis: Sequence[int], rho: Sequence[float],
@@ -261,7 +264,7 @@ class EdgeTopKSchedule:
         self.windows_per_axis, self.rho = list(windows_per_axis), list(rho)
         self.device = torch.device(device)
         self.metric = metric
-        if match not in ("edge_topk", "full_pairwise"):
+        if match not in ("edge_topk", "full_pairwise", "best_per_a"):
             raise ValueError(match)
         self.match = match
         self.h_cu_txt = np.ascontiguousarray(cu_txt, dtype=np.int32)
@@ -289,17 +292,22 @@ class EdgeTopKSchedule:
             self._bound.append(min(max_window_cells(tiles, grid_h, grid_w, w), max(n0, 1)))
             ws_bytes = max(ws_bytes, B.lightkv_workspace_size(self._problem(len(self._bound) - 1, h_full, self._cu[0])))
         self._ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self._call = None        # buffers and descriptors of the one-call form, made on first use
+
+    def _match_code(self):
+        return {"edge_topk": B.MATCH_EDGE_TOPK, "full_pairwise": B.MATCH_FULL_PAIRWISE, "best_per_a": B.MATCH_BEST_PER_A}[self.match]
+
+    def _count_mode(self):
+        return B.COUNT_EDGES if self.match == "edge_topk" else B.COUNT_RATIO
 
     def _problem(self, s, h_cu_vis, cu_vis, h_win_offsets=None, h_k=None):
         n_windows = self.batch * windows_per_sequence(self.tiles, self.windows_per_axis[s])
-        pairwise = self.match == "full_pairwise"
         bound = min(self._bound[s], max(int(np.diff(h_cu_vis).max()), 1))
         return B.Problem(batch=self.batch, d=self.d, heads=self.heads, head_dim=self.head_dim, dtype=self.dtype,
                          h_cu_vis=h_cu_vis, cu_vis=cu_vis, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt, n_windows=n_windows,
                          max_window_tokens=0 if h_win_offsets is not None else bound, win_offsets=self._win_offsets[s],
                          win_tokens=self._win_tokens, win_remove=self._win_remove[s], h_win_offsets=h_win_offsets,
-                         h_win_remove=h_k, metric=self.metric,
-                         match=B.MATCH_FULL_PAIRWISE if pairwise else B.MATCH_EDGE_TOPK)
+                         h_win_remove=h_k, metric=self.metric, match=self._match_code())
 
     def run_step(self, s: int, h_cu_vis: np.ndarray, X, K, V, Q, pos, *, xi_given=None, h_win_edges=None,
                  marks: Optional[list] = None, cu_vis=None, host_mirror: bool = True) -> EdgeStepResult:
@@ -329,15 +337,13 @@ class EdgeTopKSchedule:
         B.lightkv_build_windows(batch, h_cu_vis, cu_vis, pos, self.tiles, self.grid_h, self.grid_w, w, win_offsets,
                                 win_tokens)
         mark("end")
-        pairwise = self.match == "full_pairwise"
         if h_win_edges is None:                              # k_w = floor(rho v_w / 2) (r_w = floor(rho v_w)), on the device
-            B.lightkv_window_counts(batch, n_windows, win_offsets, B.COUNT_RATIO if pairwise else B.COUNT_EDGES,
-                                    win_remove, rho=self.rho[s])
+            B.lightkv_window_counts(batch, n_windows, win_offsets, self._count_mode(), win_remove, rho=self.rho[s])
             prob = self._problem(s, h_cu_vis, cu_vis)
         else:
             h_k = np.ascontiguousarray(h_win_edges, dtype=np.int32)
             win_remove[:n_windows].copy_(torch.from_numpy(h_k))
-            mirror = host_mirror and not pairwise
+            mirror = host_mirror and self.match == "edge_topk"
             prob = self._problem(s, h_cu_vis, cu_vis, win_offsets.cpu().numpy() if mirror else None, h_k if mirror else None)
             # with the host's counts the library sizes the edge list from them -- up to every pair of a window -- and
             # writes that many group entries; counts known to the device only are clamped to one per token
@@ -363,7 +369,60 @@ class EdgeTopKSchedule:
                              dst, new_index, grp_offsets, grp_src, win_offsets, win_tokens, win_remove[:n_windows], cu_vis_out)
         return res
 
+    def _call_buffers(self, h_cu_vis):
+        """Per-stage index buffers and descriptors for lightkv_compress_schedule_ratio (the row tensors are the two sets
+        the steps use in turn)."""
+        i32, f32 = dict(dtype=torch.int32, device=self.device), dict(dtype=torch.float32, device=self.device)
+        cap, batch = self.capacity, self.batch
+        cu_in = torch.from_numpy(h_cu_vis).to(self.device)
+        stages, bufs = [], []
+        for s, w in enumerate(self.windows_per_axis):
+            n_windows = batch * windows_per_sequence(self.tiles, w)
+            b = dict(win_offsets=self._win_offsets[s], win_tokens=torch.empty(cap, **i32), win_remove=self._win_remove[s],
+                     xi=torch.empty(cap, **f32), best_fd=torch.empty(cap, **f32), best_dst=torch.empty(cap, **i32),
+                     dst=torch.empty(cap, **i32), new_index=torch.empty(cap, **i32), grp_offsets=torch.empty(cap + 1, **i32),
+                     grp_src=torch.empty(cap, **i32), cu_vis_out=torch.empty(batch + 1, **i32))
+            X_out, K_out, V_out, pos_out = self._out[s % 2]
+            prob = B.Problem(batch=batch, d=self.d, heads=self.heads, head_dim=self.head_dim, dtype=self.dtype,
+                             h_cu_vis=h_cu_vis, cu_vis=cu_in, h_cu_txt=self.h_cu_txt, cu_txt=self.cu_txt,
+                             n_windows=n_windows, max_window_tokens=self._bound[s], win_offsets=b["win_offsets"],
+                             win_tokens=b["win_tokens"], win_remove=b["win_remove"], metric=self.metric,
+                             match=self._match_code())
+            need = B.lightkv_workspace_size(prob)
+            if need > self._ws.numel():
+                self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+            stages.append(dict(problem=prob, w=w, X_out=X_out, K_out=K_out, V_out=V_out, pos_out=pos_out, **b))
+            bufs.append(b)
+        return dict(h_cu_vis=h_cu_vis.copy(), cu_in=cu_in, bufs=bufs, stages=B.StageArray(stages))
+
     def run(self, h_cu_vis: np.ndarray, X, K, V, Q, pos, marks: Optional[list] = None) -> List[EdgeStepResult]:
+        """Every stage in one library call.  X, K, V, pos must not be the schedule's own output sets.  With marks the
+        stages are driven call by call instead (run_steps), so that every call can be timed."""
+        if marks is not None:
+            return self.run_steps(h_cu_vis, X, K, V, Q, pos, marks=marks)
+        h_cu_vis = np.ascontiguousarray(h_cu_vis, dtype=np.int32)
+        if int(h_cu_vis[-1]) > self.capacity:
+            raise ValueError("more tokens than the schedule was built for")
+        c = self._call
+        if c is None or not np.array_equal(c["h_cu_vis"], h_cu_vis):
+            c = self._call = self._call_buffers(h_cu_vis)
+        h_out = B.lightkv_compress_schedule_ratio(c["stages"], self.rho, self.tiles, self.grid_h, self.grid_w, X, K, V,
+                                                  pos, Q, self._ws)
+        out, n_in = [], int(h_cu_vis[-1])
+        for s, b in enumerate(c["bufs"]):
+            X_out, K_out, V_out, pos_out = self._out[s % 2]
+            n_out = int(h_out[s, -1])
+            n_windows = self.batch * windows_per_sequence(self.tiles, self.windows_per_axis[s])
+            out.append(EdgeStepResult(h_out[s], X_out[:n_out], K_out[:n_out], V_out[:n_out], pos_out[:n_out],
+                                      b["xi"][:n_in], b["best_fd"][:max(n_in, 1)], b["best_dst"][:max(n_in, 1)],
+                                      b["dst"][:max(n_in, 1)], b["new_index"][:max(n_in, 1)], b["grp_offsets"][:n_in + 1],
+                                      b["grp_src"], b["win_offsets"], b["win_tokens"], b["win_remove"][:n_windows],
+                                      b["cu_vis_out"]))
+            n_in = n_out
+        return out
+
+    def run_steps(self, h_cu_vis: np.ndarray, X, K, V, Q, pos, marks: Optional[list] = None) -> List[EdgeStepResult]:
+        """The same stages call by call (one read-back per stage, here on the host side of the binding)."""
         out, cu_vis = [], None
         for s in range(len(self.windows_per_axis)):
             r = self.run_step(s, h_cu_vis, X, K, V, Q, pos, marks=marks, cu_vis=cu_vis)

@@ -177,6 +177,35 @@ def test_entry_points_reject_bad_arguments_before_launch(B):
     stage.reserved = 3
     assert sc() == 5
     stage.reserved = 0
+    # the ratio-driven schedule: same validation before anything is enqueued; counts and window sizes are the device's
+    ratio = lib.lightkv_compress_schedule_ratio
+    rho = (C.c_double * 1)(0.5)
+    h_out = np.zeros(2, dtype=np.int32)
+    h_out_p = C.c_void_p(h_out.ctypes.data)
+
+    def sr(n=1, rho_=rho, X=fake, out=h_out_p):
+        return ratio((B._CStage * 1)(stage), n, rho_, 1, 2, 4, X, 64, fake, 64, fake, 64, fake, fake, 64, 32, 0.0, fake,
+                     1 << 30, out, None)
+
+    stage.win_remove = 0x1000
+    stage.problem.win_remove = 0x1000
+    stage.problem.max_window_tokens = 4
+    assert sr() == 5                               # host window sizes in the descriptor: not here
+    stage.problem.h_win_offsets = None
+    assert sr() == 5                               # ... nor host counts
+    stage.problem.h_win_remove = None
+    assert sr(n=0) == 2 and sr(X=None) == 1 and sr(rho_=None) == 1 and sr(out=None) == 1
+    assert sr(rho_=(C.c_double * 1)(-0.1)) == 2 and sr(rho_=(C.c_double * 1)(float("nan"))) == 2
+    stage.win_remove = None
+    assert sr() == 1                               # the counts need a place
+    stage.win_remove = 0x2000
+    assert sr() == 2                               # ... the one the descriptor points to
+    stage.win_remove = 0x1000
+    stage.cu_vis_target = 0x1000
+    assert sr() == 5                               # token budgets belong to lightkv_compress_schedule
+    stage.cu_vis_target = None
+    stage.problem.max_window_tokens = 0
+    assert sr() == 2                               # the bound is mandatory
     # aggregate / compact
     assert lib.lightkv_aggregate(C.byref(p), None, fake, fake, fake, 64, fake, 64, fake, 64, None) == 1
     assert lib.lightkv_aggregate(C.byref(p), fake, fake, fake, fake, 8, fake, 64, fake, 64, None) == 2

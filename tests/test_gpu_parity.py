@@ -1326,3 +1326,106 @@ def test_full_pairwise_scores_alone_equal_those_of_the_fused_call():
     assert (sizes == 1).any()
     lone = r.win_tokens.cpu().numpy()[r.win_offsets.cpu().numpy()[:-1][sizes == 1]]
     assert np.all(nb.cpu().numpy()[lone] == -1) and np.all(np.isinf(fd.cpu().numpy()[lone]))
+
+
+@pytest.mark.parametrize("cfg,match,rho", [(2, "edge_topk", 0.36), (5, "edge_topk", 0.5), (3, "edge_topk", 0.36),
+                                            (2, "full_pairwise", 0.18), (5, "full_pairwise", 0.2),
+                                            (2, "best_per_a", 0.3), (5, "best_per_a", 0.45), ("global", "edge_topk", 0.36)])
+def test_ratio_schedule_in_one_call_equals_its_steps(cfg, match, rho):
+    """lightkv_compress_schedule_ratio (every stage in one library call, the next stage's windows and counts built next
+    to the merge) against the same stages driven call by call: every index array, the offsets and the row tensors of
+    every stage agree bit for bit; a second call gives the same again (the buffers carry nothing over)."""
+    from workloads import make_workload
+    from parity import to_dev
+    from paper_2605_00789_amd import EdgeTopKSchedule
+    wl = make_workload(cfg)
+    axis = list(wl.windows_per_axis)
+
+    def sched():
+        return EdgeTopKSchedule(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim,
+                                tiles=wl.tiles, grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt,
+                                windows_per_axis=axis, rho=[rho] * len(axis), match=match)
+
+    X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+    pos = torch.from_numpy(wl.pos).cuda()
+    print("[ratio schedule] %s %s: call by call" % (wl.name, match), flush=True)
+    ref, keep = sched(), []
+    cu, Xs, Ks, Vs, ps, cu_dev = wl.cu_vis, X, K, V, pos, None
+    for s in range(len(axis)):
+        r = ref.run_step(s, cu, Xs, Ks, Vs, Q, ps, cu_vis=cu_dev)
+        torch.cuda.synchronize()
+        n_in = int(np.asarray(cu)[-1])
+        keep.append(dict(h_out=r.h_cu_vis_out.copy(), X=r.X.clone(), K=r.K.clone(), V=r.V.clone(), pos=r.pos.clone(),
+                         xi=r.xi[:n_in].clone(), dst=r.dst[:n_in].clone(), new_index=r.new_index[:n_in].clone(),
+                         best_fd=r.best_fd[:n_in].clone(), best_dst=r.best_dst[:n_in].clone(),
+                         grp_offsets=r.grp_offsets[:n_in + 1].clone(), win_offsets=r.win_offsets.clone(),
+                         win_tokens=r.win_tokens[:n_in].clone(), win_remove=r.win_remove.clone()))
+        keep[-1]["grp_src"] = r.grp_src[:int(keep[-1]["grp_offsets"][-1])].clone()
+        cu, Xs, Ks, Vs, ps, cu_dev = r.h_cu_vis_out, r.X, r.K, r.V, r.pos, r.cu_vis_out
+    one = sched()
+    for attempt in range(2):
+        print("[ratio schedule] %s %s: one call (%d)" % (wl.name, match, attempt), flush=True)
+        res = one.run(wl.cu_vis, X, K, V, Q, pos)
+        n_in = int(wl.cu_vis[-1])
+        for s, (r, k) in enumerate(zip(res, keep)):
+            np.testing.assert_array_equal(r.h_cu_vis_out, k["h_out"], err_msg="stage %d offsets" % s)
+            assert torch.equal(r.cu_vis_out.cpu(), torch.from_numpy(k["h_out"]))
+            for name in ("xi", "dst", "new_index", "best_fd", "best_dst", "grp_offsets", "win_offsets", "win_remove"):
+                got = getattr(r, name)
+                assert torch.equal(got[:k[name].numel()], k[name]), "stage %d %s" % (s, name)
+            assert torch.equal(r.win_tokens[:n_in], k["win_tokens"]), "stage %d win_tokens" % s
+            assert torch.equal(r.grp_src[:k["grp_src"].numel()], k["grp_src"]), "stage %d grp_src" % s
+            if s >= len(res) - 2:   # the row tensors are two sets used in turn: the last two stages' are still there
+                for name in ("X", "K", "V", "pos"):
+                    assert torch.equal(getattr(r, name), k[name]), "stage %d %s" % (s, name)
+            n_in = int(k["h_out"][-1])
+        assert res[-1].h_cu_vis_out[-1] < wl.cu_vis[-1]
+    if match == "best_per_a":   # the counts are the oracle's floor(rho v), capped by |A|, on the windows of every stage
+        from oracle import lightkv_oracle as O
+        n_in = int(wl.cu_vis[-1])
+        for s, r in enumerate(res):
+            want = O.removal_counts_ratio(r.win_offsets.cpu().numpy(), rho)
+            np.testing.assert_array_equal(r.win_remove.cpu().numpy(), want, err_msg="stage %d counts" % s)
+            assert int(r.h_cu_vis_out[-1]) == n_in - int(want.sum())
+            n_in = int(r.h_cu_vis_out[-1])
+
+
+def test_ratio_schedule_refusals_on_device():
+    """A capturing stream is refused before anything is enqueued; outputs too small for what a stage leaves are reported
+    after that stage."""
+    from workloads import make_workload
+    from parity import to_dev
+    from paper_2605_00789_amd import EdgeTopKSchedule
+    from paper_2605_00789_amd import binding as B
+    wl = make_workload(2)
+    axis = list(wl.windows_per_axis)
+    sch = EdgeTopKSchedule(dtype=wl.dtype, batch=wl.batch, d=wl.d, heads=wl.heads, head_dim=wl.head_dim, tiles=wl.tiles,
+                           grid_h=wl.grid_h, grid_w=wl.grid_w, cu_txt=wl.cu_txt, windows_per_axis=axis,
+                           rho=[0.3] * len(axis), match="edge_topk")
+    X, K, V, Q = (to_dev(t, wl.dtype) for t in (wl.X, wl.K, wl.V, wl.Q))
+    pos = torch.from_numpy(wl.pos).cuda()
+    sch.run(wl.cu_vis, X, K, V, Q, pos)              # eager first: helper streams and descriptors exist
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    marker = torch.zeros(64, device="cuda")
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side, capture_error_mode="thread_local"):
+        marker.add_(1.0)                             # (so that the capture is not empty)
+        with pytest.raises(B.LightKVError) as e:
+            B.lightkv_compress_schedule_ratio(sch._call["stages"], sch.rho, sch.tiles, sch.grid_h, sch.grid_w, X, K, V,
+                                              pos, Q, sch._ws)
+        assert e.value.status == 5                   # LIGHTKV_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    # outputs with room for fewer rows than the first stage leaves
+    st = sch._call["stages"]
+    full = st.c[0].out_rows
+    st.c[0].out_rows = 10
+    try:
+        with pytest.raises(B.LightKVError) as e:
+            sch.run(wl.cu_vis, X, K, V, Q, pos)
+        assert e.value.status == 2                   # LIGHTKV_ERR_SHAPE
+    finally:
+        st.c[0].out_rows = full
+    torch.cuda.synchronize()
+    res = sch.run(wl.cu_vis, X, K, V, Q, pos)        # and the schedule still works afterwards
+    assert res[-1].h_cu_vis_out[-1] < wl.cu_vis[-1]
