@@ -205,8 +205,9 @@ const char *lightkv_status_string(int status) {
   }
 }
 
-int lightkv_version(void) { return 310; }   // 0.3.1: lightkv_problem.direction (was reserved), direction argument of
-                                            // lightkv_window_counts, edge lists for windows of up to 4096 tokens
+int lightkv_version(void) { return 320; }   // 0.3.2: lightkv_compress_schedule_ratio (0.3.1: lightkv_problem.direction,
+                                            // direction argument of lightkv_window_counts, edge lists for windows of
+                                            // up to 4096 tokens)
 
 lightkv_status lightkv_workspace_size(const lightkv_problem *p, size_t *bytes) {
   if (!bytes) return LIGHTKV_ERR_NULL;
