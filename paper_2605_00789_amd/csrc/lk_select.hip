@@ -10,7 +10,8 @@
 //   select_window_kernel : per window -> dst[], per-token source counts, per-source ranks (up to 256 A nodes), by
 //                          counting smaller keys inside one workgroup
 //   select_rank_kernel   : the same results for larger windows, the counting spread over several workgroups
-//   select_scan_kernel   : one workgroup -> exclusive scans (new_index, grp_offsets), cu_vis_out, grp_src
+//   select_scan_kernel   : one workgroup (per sequence, for larger batches) -> exclusive scans (new_index, grp_offsets),
+//                          cu_vis_out, grp_src
 #include <atomic>
 #include "lk_xi_body.h"
 
@@ -26,6 +27,7 @@ struct SelArgs {
   int32_t *dst, *new_index, *grp_offsets, *grp_src, *cu_vis_out, *cnt, *src_rank;
   int cap;   // power of two >= the larger side of the largest window
   int dir;   // 0: even list positions propose, 1: odd ones (side_a / pos_a)
+  int per_seq;   // scan: one workgroup per sequence (0: one workgroup for the whole batch)
 };
 
 
@@ -289,12 +291,17 @@ __global__ __launch_bounds__(RANK_ROWS * RANK_SEGS) void select_rank_kernel(SelA
   }
 }
 
-// Single workgroup: scans over all tokens of the batch.  Every thread owns a run of consecutive tokens, so one
-// pass needs a single workgroup scan (two values at once) instead of one per 1024 tokens; all loads of a pass are
-// issued together.
+// Scans over all tokens of the batch.  Every thread owns a run of consecutive tokens, so one pass needs a single
+// workgroup scan (two values at once) instead of one per 1024 tokens; all loads of a pass are issued together.
+// One workgroup does the whole batch, or (per_seq, for batches of some size) one workgroup per sequence: it first
+// counts what stays and what is merged in the sequences before its own -- re-reading a few KB is cheaper than any
+// exchange between workgroups -- and then scans its own tokens from those bases.  A token's target lies in its own
+// window, hence in its own sequence, so the inverse map needs nothing from another workgroup either.
 constexpr int SCAN_THREADS = 1024;
 constexpr int SCAN_ITEMS = 10;     // tokens per thread and pass (10240 tokens per pass)
 constexpr int FILL_UNROLL = 4;
+constexpr int SCAN_PER_SEQ_MIN_TOKENS = 2048;   // batches with fewer tokens: one workgroup for all (a single short pass)
+constexpr int SCAN_PER_SEQ_MAX_BATCH = 256;
 constexpr size_t SCAN_LDS_BYTES = (size_t)2 * SCAN_THREADS * SCAN_ITEMS * sizeof(int);   // 80 KB: above the 64 KB default
 
 // WITH_HEADS: the first n_head_blocks workgroups of the launch do something else entirely -- they sum the per-head xi
@@ -313,18 +320,53 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
   __shared__ int2 wsum[SCAN_THREADS / 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int s_first = g.cu_vis[tid <= g.batch ? tid : g.batch];   // sequence start handled by this thread (first round)
-  int per = (g.sum_n + SCAN_THREADS - 1) / SCAN_THREADS;
+  // the tokens of this workgroup: [t0, t1)
+  const int seq = (int)blockIdx.x - (WITH_HEADS ? n_head_blocks : 0);
+  int t0 = 0, t1 = g.sum_n;
+  if (g.per_seq) {
+    t0 = g.cu_vis[seq]; t1 = g.cu_vis[seq + 1];
+    t0 = t0 < 0 ? 0 : (t0 > g.sum_n ? g.sum_n : t0);
+    t1 = t1 < t0 ? t0 : (t1 > g.sum_n ? g.sum_n : t1);
+  }
+  int keep_base = 0, cnt_base = 0;
+  if (g.per_seq) {   // staying tokens and sources before this sequence
+    int ks = 0, cs = 0;
+    for (int i = tid; i < t0; i += 4 * SCAN_THREADS) {   // uniform trip count per wave is not needed: plain loads
+      int dv[4], cv[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int ii = i + j * SCAN_THREADS;
+        const int ic = ii < t0 ? ii : 0;
+        dv[j] = g.dst[ic]; cv[j] = g.cnt[ic];
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bool ok = i + j * SCAN_THREADS < t0;
+        ks += (ok && dv[j] < 0) ? 1 : 0;
+        cs += ok ? cv[j] : 0;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) { ks += __shfl_xor(ks, o, 64); cs += __shfl_xor(cs, o, 64); }
+    if (lane == 0) wsum[wave] = make_int2(ks, cs);
+    __syncthreads();
+#pragma unroll
+    for (int w2 = 0; w2 < SCAN_THREADS / 64; ++w2) { keep_base += wsum[w2].x; cnt_base += wsum[w2].y; }
+    __syncthreads();   // wsum is written again by the first pass
+  }
+  const int keep_first = keep_base;
+  const int n_loc = t1 - t0;
+  int per = (n_loc + SCAN_THREADS - 1) / SCAN_THREADS;
   per = per < 1 ? 1 : (per > SCAN_ITEMS ? SCAN_ITEMS : per);
   if (per < SCAN_ITEMS && per > 1 && !(per & 1)) ++per;   // an odd run length: thread t's slots in kb[] start at bank t * per
   const int pass_tokens = per * SCAN_THREADS;
-  const bool one_pass = g.sum_n <= pass_tokens;   // then dst / src_rank stay in registers for the inverse map below
-  int keep_base = 0, cnt_base = 0;
+  const bool one_pass = n_loc <= pass_tokens;   // then dst / src_rank stay in registers for the inverse map below
   int d[SCAN_ITEMS], c[SCAN_ITEMS], sr[SCAN_ITEMS];
-  for (int pass_base = 0; pass_base < g.sum_n; pass_base += pass_tokens) {
+  for (int pass_base = t0; pass_base < t1; pass_base += pass_tokens) {
     const int i0 = pass_base + tid * per;
 #pragma unroll
     for (int k = 0; k < SCAN_ITEMS; ++k) {
-      const bool ok = k < per && i0 + k < g.sum_n;
+      const bool ok = k < per && i0 + k < t1;
       const int ic = ok ? i0 + k : 0;            // unconditional loads from a clamped index
       const int dv = g.dst[ic], cv = g.cnt[ic], sv = g.src_rank[ic];
       d[k] = ok ? dv : 0;
@@ -334,7 +376,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
     int ks = 0, cs = 0;
 #pragma unroll
     for (int k = 0; k < SCAN_ITEMS; ++k) {
-      const bool ok = k < per && i0 + k < g.sum_n;
+      const bool ok = k < per && i0 + k < t1;
       ks += (ok && d[k] < 0) ? 1 : 0;
       cs += c[k];
     }
@@ -358,7 +400,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
     int ek = keep_base + wk + ik - ks, ec = cnt_base + wc + ic2 - cs;
 #pragma unroll
     for (int k = 0; k < SCAN_ITEMS; ++k) {
-      const bool ok = k < per && i0 + k < g.sum_n;
+      const bool ok = k < per && i0 + k < t1;
       if (ok) {
         const int keep = d[k] < 0 ? 1 : 0;
         kb[tid * per + k] = ek;
@@ -373,8 +415,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
     // not wait for the stores above
     if (one_pass) lds_barrier(); else __syncthreads();
     // vision offsets after the step: staying tokens before each sequence start that falls into this pass
-    const int pass_end = min(pass_base + pass_tokens, g.sum_n);
-    for (int b = tid; b <= g.batch; b += SCAN_THREADS) {
+    const int pass_end = min(pass_base + pass_tokens, t1);
+    for (int b = tid; b <= (g.per_seq ? -1 : g.batch); b += SCAN_THREADS) {
       const int s = (b == tid) ? s_first : g.cu_vis[b];
       if (s >= pass_base && s < pass_end) g.cu_vis_out[b] = kb[s - pass_base];
     }
@@ -382,20 +424,25 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
     cnt_base += tot_c;
     if (!one_pass) __syncthreads();
   }
-  for (int b = tid; b <= g.batch; b += SCAN_THREADS) {
+  for (int b = tid; b <= (g.per_seq ? -1 : g.batch); b += SCAN_THREADS) {
     const int s = (b == tid) ? s_first : g.cu_vis[b];
     if (s >= g.sum_n) g.cu_vis_out[b] = keep_base;
   }
-  if (tid == 0) g.grp_offsets[g.sum_n] = cnt_base;
+  if (g.per_seq && tid == 0) {   // the offset of the own sequence; the last workgroup also closes both arrays
+    g.cu_vis_out[seq] = keep_first;
+    if (seq == g.batch - 1) g.cu_vis_out[g.batch] = keep_base;
+  }
+  if (tid == 0 && (!g.per_seq || seq == g.batch - 1)) g.grp_offsets[g.sum_n] = cnt_base;
   // inverse map: source a goes to slot grp_offsets[dst[a]] + (its rank among the sources of that target).  In a single
   // pass the group starts of all tokens are in LDS (written before the barrier above); otherwise they are read back
   // from global memory after the barrier below.
+  // (a target outside [t0, t1) cannot come from the selection kernels; it is dropped rather than followed)
   if (one_pass) {
-    const int i0 = tid * per;
+    const int i0 = t0 + tid * per;
 #pragma unroll
     for (int k = 0; k < SCAN_ITEMS; ++k) {   // c[] is free now: it takes the group starts
-      const bool ok = k < per && i0 + k < g.sum_n && d[k] >= 0 && d[k] < g.sum_n;
-      c[k] = gb[ok ? d[k] : 0];
+      const bool ok = k < per && i0 + k < t1 && d[k] >= t0 && d[k] < t1;
+      c[k] = gb[ok ? d[k] - t0 : 0];
       d[k] = ok ? d[k] : -1;
     }
 #pragma unroll
@@ -403,14 +450,14 @@ __global__ __launch_bounds__(SCAN_THREADS) void select_scan_kernel(SelArgs g, Xi
       if (d[k] >= 0) g.grp_src[c[k] + sr[k]] = i0 + k;
   }
   __syncthreads();
-  for (int a0 = 0; a0 < (one_pass ? 0 : g.sum_n); a0 += FILL_UNROLL * SCAN_THREADS) {
+  for (int a0 = t0; a0 < (one_pass ? t0 : t1); a0 += FILL_UNROLL * SCAN_THREADS) {
     int b[FILL_UNROLL], r2[FILL_UNROLL], go[FILL_UNROLL];
 #pragma unroll
     for (int j = 0; j < FILL_UNROLL; ++j) {
       const int a = a0 + j * SCAN_THREADS + tid;
-      const int ac = a < g.sum_n ? a : 0;
+      const int ac = a < t1 ? a : 0;
       const int bv = g.dst[ac], sv = g.src_rank[ac];
-      b[j] = a < g.sum_n ? bv : -1;
+      b[j] = (a < t1 && bv >= t0 && bv < t1) ? bv : -1;
       r2[j] = sv;
     }
 #pragma unroll
@@ -447,9 +494,13 @@ hipError_t launch_select_scan(int batch, int sum_n, const int32_t *cu_vis, const
   g.batch = batch; g.sum_n = sum_n; g.cu_vis = cu_vis;
   g.dst = const_cast<int32_t *>(dst); g.new_index = new_index; g.grp_offsets = grp_offsets; g.grp_src = grp_src;
   g.cu_vis_out = cu_vis_out; g.cnt = const_cast<int32_t *>(cnt); g.src_rank = const_cast<int32_t *>(src_rank);
+  // one workgroup per sequence once a batch is large enough for the single workgroup's serial passes to show, as long
+  // as all of them fit the chip at once (one workgroup of this kernel fills a CU)
+  g.per_seq = (batch > 1 && batch <= SCAN_PER_SEQ_MAX_BATCH && sum_n >= SCAN_PER_SEQ_MIN_TOKENS) ? 1 : 0;
   hipError_t e = allow_scan_lds();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(select_scan_kernel<false>, dim3(1), dim3(SCAN_THREADS), SCAN_LDS_BYTES, stream, g, XiArgs{}, 0);
+  hipLaunchKernelGGL(select_scan_kernel<false>, dim3(g.per_seq ? (unsigned)batch : 1u), dim3(SCAN_THREADS), SCAN_LDS_BYTES,
+                     stream, g, XiArgs{}, 0);
   return hipGetLastError();
 }
 

@@ -1429,3 +1429,59 @@ def test_ratio_schedule_refusals_on_device():
     torch.cuda.synchronize()
     res = sch.run(wl.cu_vis, X, K, V, Q, pos)        # and the schedule still works afterwards
     assert res[-1].h_cu_vis_out[-1] < wl.cu_vis[-1]
+
+
+@pytest.mark.parametrize("name,lens,grid,w", [
+    ("ragged_with_empty_sequences", (0, 700, 0, 1500, 300, 0), (40, 40), 4),      # one workgroup per sequence, some with nothing to do
+    ("a_sequence_longer_than_one_pass", (12000, 3000, 1), (128, 128), 8),         # 12000 tokens: two passes inside its workgroup
+    ("two_sequences_of_one_pass_each", (9000, 10240), (128, 128), 6),
+    ("many_short_sequences", tuple([16] * 300), (4, 4), 2),                       # more sequences than get a workgroup each: one for all
+    ("small_batch", (500, 400), (32, 32), 4),                                     # below the token threshold: one workgroup
+])
+def test_index_scans_of_ragged_batches_match_oracle(name, lens, grid, w):
+    """lightkv_select on batches of uneven sequences (random scores with many ties, random proposals inside every
+    window): dst, new_index, grp_offsets, grp_src and cu_vis_out against the oracle's selection and its index
+    identities, exactly.  Covers the scan with one workgroup per sequence, sequences of several passes, empty ones."""
+    from oracle import lightkv_oracle as O
+    from paper_2605_00789_amd import binding as B
+    rng = np.random.default_rng(len(lens) * 1000 + sum(lens))
+    gh, gw = grid
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    pos = np.concatenate([np.sort(rng.choice(gh * gw, size=L, replace=False)) for L in lens] + [np.zeros(0, dtype=np.int64)]).astype(np.int32)
+    wo, wt = O.build_windows(pos, cu, 1, gh, gw, w)
+    n = int(cu[-1])
+    best_fd = np.full(n, np.inf, dtype=np.float32)
+    best_dst = np.full(n, -1, dtype=np.int32)
+    rem = np.zeros(len(wo) - 1, dtype=np.int32)
+    for k in range(len(wo) - 1):
+        toks = wt[wo[k]:wo[k + 1]]
+        A, Bn = toks[0::2], toks[1::2]
+        if len(Bn) == 0:
+            continue
+        best_fd[A] = rng.integers(0, 12, size=len(A)).astype(np.float32) / 8.0
+        best_dst[A] = rng.choice(Bn, size=len(A))
+        rem[k] = int(rng.uniform(0.0, 1.0) * len(A))
+    want_dst = O.select(best_fd.astype(np.float64), best_dst, wo, wt, rem)
+    want_new = O.kept_index(want_dst)
+    want_go, want_gs = O.groups_csr(want_dst)
+    keep = (want_dst < 0).astype(np.int64)
+    want_cu = np.concatenate([[0], np.cumsum(keep)])[cu].astype(np.int32)
+    dev = "cuda:0"
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    wo32, wt32 = wo.astype(np.int32), wt.astype(np.int32)
+    prob = B.Problem(batch=len(lens), d=64, heads=2, head_dim=32, dtype="f32", h_cu_vis=cu, cu_vis=t(cu),
+                     n_windows=len(wo) - 1, max_window_tokens=0, win_offsets=t(wo32), win_tokens=t(wt32), win_remove=t(rem),
+                     h_win_offsets=wo32, h_win_remove=rem)
+    i32 = dict(dtype=torch.int32, device=dev)
+    outs = [torch.full((n,), -9, **i32), torch.full((n,), -9, **i32), torch.full((n + 1,), -9, **i32),
+            torch.full((max(int(rem.sum()), 1),), -9, **i32), torch.full((len(cu),), -9, **i32)]
+    ws = torch.empty(B.lightkv_workspace_size(prob), dtype=torch.uint8, device=dev)
+    print("[ragged scan] %s: %d tokens in %d sequences, %d leave" % (name, n, len(lens), int(rem.sum())), flush=True)
+    B.lightkv_select(prob, t(best_fd), t(best_dst), *outs, ws)
+    torch.cuda.synchronize()
+    dst, new_index, grp_offsets, grp_src, cu_out = (o.cpu().numpy() for o in outs)
+    np.testing.assert_array_equal(dst, want_dst)
+    np.testing.assert_array_equal(new_index, want_new)
+    np.testing.assert_array_equal(grp_offsets, want_go)
+    np.testing.assert_array_equal(grp_src[:len(want_gs)], want_gs)
+    np.testing.assert_array_equal(cu_out, want_cu)
