@@ -300,6 +300,15 @@ def copy_ceiling(stream, timer, total_mb_list=(107, 342, 824), n_inst=20):
     return out
 
 
+def _copy_reference(stream, timer, roof, n_inst):
+    """The achievable ceiling beside a cold roofline object: a plain device-to-device copy with the kernel's algorithmic
+    bytes per launch as its traffic, flushed and timed exactly like the kernel; frac_of_copy = copy time / kernel time."""
+    mb = int(round(roof["algorithmic_bytes_per_launch"] / 1e6))
+    c = copy_ceiling(stream, timer, total_mb_list=(mb,), n_inst=max(5, min(n_inst, 20)))[0]
+    c["kernel_frac_of_copy"] = round(c["us"] / roof["avg_launch_us"], 4)
+    return c
+
+
 def ceilings_pass(stream):
     """What the chip delivers to the dense contractions, measured with the probe library (no method arithmetic): the
     operand loads of the tiled FD kernels alone (every byte comes out of L2: nothing is reused through L1), and bare
@@ -598,6 +607,7 @@ def main():
         traffic, src = measured_traffic(wl.name)
         cold["traffic"] = traffic
         cold["traffic_source"] = ("committed profile %s (not measured by this run)" % src) if src else None
+        cold["copy_reference"] = _copy_reference(stream, timer, cold, n_inst)
         out["roofline"] = cold
     elif "roofline_warm" in out:
         out["roofline"] = dict(out["roofline_warm"], traffic=None)
@@ -610,6 +620,7 @@ def main():
         cold5_us = rows_cold_pass(wl5, pipe5, tensors5, stream, timer, max(5, n_inst // 2))
         out["roofline_hbm_primary"] = _rows_roofline(wl5, cold5_us, n_ins5, "cold: 1 GiB read in front of every launch",
                                                      samples=rows_cold_pass.samples)
+        out["roofline_hbm_primary"]["copy_reference"] = _copy_reference(stream, timer, out["roofline_hbm_primary"], n_inst)
         del pipe5, tensors5, wl5
 
     # ---- the dense contractions of the 2880-token window against the matrix-core peak
