@@ -782,3 +782,52 @@ def test_reverse_direction_counts():
     assert bad[0] and rem.tolist() == [2, 0, 0, 4, 1]
     rem, bad = O.removal_counts_target(offs, 1, [8])
     assert not bad[0] and rem.tolist() == [3, 0, 0, 3, 2]              # caps 3, 0, 0, 4, 2: level 3 meets the budget exactly
+
+
+def test_whole_stage_by_hand_on_four_tokens():
+    """One window of four tokens worked by hand (Sec. 3.2.1 Steps 1-5, Eq. similarity and message-passing):
+    A = {t0, t2}, B = {t1, t3}; t0 is identical to t1 (FD 0) and t2 is closest to t3 (FD 1 - 1/sqrt 2); with r = 1 the
+    one merge is t0 -> t1, weighted 1 : 3 by the given xi; the sequence is then t1', t2, t3 in the old order."""
+    s = 1.0 / math.sqrt(2.0)
+    X = np.array([[1.0, 0.0], [1.0, 0.0], [0.0, 1.0], [s, s]])
+    K = np.array([[4.0, 0.0], [0.0, 4.0], [5.0, 6.0], [7.0, 8.0]])
+    V = np.array([[8.0, 8.0], [0.0, 4.0], [1.0, 2.0], [3.0, 4.0]])
+    xi = np.array([1.0, 3.0, 1.0, 1.0])
+    pos = np.arange(4, dtype=np.int32)
+    cu = np.array([0, 4], dtype=np.int32)
+    wo, wt = np.array([0, 4]), np.arange(4)
+    r = O.compress_stage(X, K, V, None, pos, cu, np.array([0, 0]), 1, 2, wo, wt, np.array([1]), xi=xi)
+    np.testing.assert_allclose(r.best_fd[[0, 2]], [0.0, 1.0 - s], atol=1e-15)
+    np.testing.assert_array_equal(r.best_dst[[0, 2]], [1, 3])
+    np.testing.assert_array_equal(r.dst, [1, -1, -1, -1])
+    np.testing.assert_array_equal(r.new_index, [-1, 0, 1, 2])
+    np.testing.assert_array_equal(r.grp_offsets, [0, 0, 1, 1, 1])
+    np.testing.assert_array_equal(r.grp_src, [0])
+    np.testing.assert_allclose(r.X, [[1.0, 0.0], [0.0, 1.0], [s, s]], atol=1e-15)
+    np.testing.assert_allclose(r.K, [[1.0, 3.0], [5.0, 6.0], [7.0, 8.0]], atol=1e-15)      # (1*K0 + 3*K1) / 4
+    np.testing.assert_allclose(r.V, [[2.0, 5.0], [1.0, 2.0], [3.0, 4.0]], atol=1e-15)
+    np.testing.assert_array_equal(r.pos, [1, 2, 3])
+    np.testing.assert_array_equal(r.cu_vis, [0, 3])
+    # r = 2: both A nodes leave, the sequence is t1', t3'
+    r2 = O.compress_stage(X, K, V, None, pos, cu, np.array([0, 0]), 1, 2, wo, wt, np.array([2]), xi=xi)
+    np.testing.assert_array_equal(r2.dst, [1, -1, 3, -1])
+    np.testing.assert_allclose(r2.K, [[1.0, 3.0], [6.0, 7.0]], atol=1e-15)                  # (K2 + K3) / 2
+    np.testing.assert_array_equal(r2.pos, [1, 3])
+    # the full pairwise visit on the same tokens: t0 and t1 are each other's neighbours at FD 0 and t0 comes first, so
+    # t0 -> t1; t1 has received and stays; next in order is t2 (its neighbour t3 is still there): t2 -> t3
+    p1 = O.compress_stage_full_pairwise(X, K, V, None, pos, cu, np.array([0, 0]), 1, 2, wo, wt, np.array([1]), xi=xi)
+    np.testing.assert_array_equal(p1.dst, [1, -1, -1, -1])
+    np.testing.assert_allclose(p1.K, r.K, atol=1e-15)
+    p2 = O.compress_stage_full_pairwise(X, K, V, None, pos, cu, np.array([0, 0]), 1, 2, wo, wt, np.array([2]), xi=xi)
+    np.testing.assert_array_equal(p2.dst, [1, -1, 3, -1])
+    np.testing.assert_allclose(p2.X[1], [s / 2, (1 + s) / 2], atol=1e-15)                   # (X2 + X3) / 2
+    np.testing.assert_array_equal(p2.cu_vis, [0, 2])
+
+
+def test_proposing_side_and_even_spread_closed_forms():
+    """The proposing set of a window of v tokens has ceil(v/2) nodes (floor(v/2) in the reverse direction); equal windows
+    that all lose the same budget give floor(R/W) each and one more from the first R mod W (Sec. 3.2.2)."""
+    for v in range(0, 12):
+        assert O.proposing_count(v) == (v + 1) // 2 and O.proposing_count(v, "b_to_a") == v // 2
+    np.testing.assert_array_equal(O.stage_removals(2, 576, 472, 16), np.tile([7] * 8 + [6] * 8, 2))   # 104 = 16*6 + 8
+    np.testing.assert_array_equal(O.stage_removals(1, 64, 36, 4), [7, 7, 7, 7])
