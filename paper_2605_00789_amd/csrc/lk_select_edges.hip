@@ -397,6 +397,8 @@ __global__ __launch_bounds__(256) void edge_keys_kernel(FdArgs g, EdgeArgs q) {
   }
 }
 
+constexpr int EB_LOADS = 16;   // keys a thread keeps in flight per step of the radix and column passes
+constexpr int EB_ROWS = 4;     // rows a wave takes at a time in the row pass
 __global__ __launch_bounds__(EB_THREADS) void edge_select_big_kernel(FdArgs g, EdgeArgs q) {
   __shared__ int hist[EB_BINS];
   __shared__ int tok[2 * EB_MAX_SIDE];
@@ -444,12 +446,12 @@ __global__ __launch_bounds__(EB_THREADS) void edge_select_big_kernel(FdArgs g, E
     for (int i = tid; i < EB_BINS; i += EB_THREADS) hist[i] = 0;
     __syncthreads();
     int run_digit = -1, run = 0;   // FD lies in a narrow range: a thread adds a run of equal digits once
-    for (int e0 = tid; e0 < E; e0 += 4 * EB_THREADS) {
-      uint32_t key[4];
+    for (int e0 = tid; e0 < E; e0 += EB_LOADS * EB_THREADS) {
+      uint32_t key[EB_LOADS];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { const int e = e0 + u * EB_THREADS; key[u] = M[e < E ? e : E - 1]; }
+      for (int u = 0; u < EB_LOADS; ++u) { const int e = e0 + u * EB_THREADS; key[u] = M[e < E ? e : E - 1]; }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < EB_LOADS; ++u) {
         const uint32_t e = (uint32_t)(e0 + u * EB_THREADS);
         const bool in = e < (uint32_t)E && (key[u] & kmask) == kprefix && (e & emask) == eprefix;
         int digit;
@@ -499,42 +501,56 @@ __global__ __launch_bounds__(EB_THREADS) void edge_select_big_kernel(FdArgs g, E
   const uint32_t Te = emask ? eprefix : 0xffffffffu;   // at the threshold value: the pairs up to this index are taken
   auto selected = [&](uint32_t key, uint32_t e) { return any && (key < T || (key == T && e <= Te)); };
 
-  // ---- by rows: best edge and lowest selected edge of every A node (a wave per row, lanes stride the columns)
-  for (int la = wave; la < nA; la += EB_WAVES) {
-    unsigned long long best = ~0ull, best_sel = ~0ull;   // (key << 32 | column): the minimum is the first minimum
-    const uint32_t *row = M + (size_t)la * nB;
+  // ---- by rows: best edge and lowest selected edge of every A node (a wave takes EB_ROWS rows at a time, so that
+  // their loads are in flight together; lanes stride the columns)
+  for (int la0 = wave * EB_ROWS; la0 < nA; la0 += EB_WAVES * EB_ROWS) {
+    unsigned long long best_r[EB_ROWS], best_sel_r[EB_ROWS];   // (key << 32 | column): the minimum is the first minimum
+#pragma unroll
+    for (int r = 0; r < EB_ROWS; ++r) { best_r[r] = ~0ull; best_sel_r[r] = ~0ull; }
     for (int lb0 = lane; lb0 < nB; lb0 += 4 * 64) {
-      uint32_t key[4];
+      uint32_t key[EB_ROWS][4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { const int lb = lb0 + u * 64; key[u] = row[lb < nB ? lb : nB - 1]; }
+      for (int r = 0; r < EB_ROWS; ++r) {
+        const uint32_t *row = M + (size_t)(la0 + r < nA ? la0 + r : nA - 1) * nB;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int lb = lb0 + u * 64;
-        if (lb < nB) {
-          const unsigned long long c = ((unsigned long long)key[u] << 32) | (unsigned)lb;
-          best = c < best ? c : best;
-          if (selected(key[u], (uint32_t)(la * nB + lb))) best_sel = c < best_sel ? c : best_sel;
+        for (int u = 0; u < 4; ++u) { const int lb = lb0 + u * 64; key[r][u] = row[lb < nB ? lb : nB - 1]; }
+      }
+#pragma unroll
+      for (int r = 0; r < EB_ROWS; ++r) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int lb = lb0 + u * 64;
+          if (lb < nB && la0 + r < nA) {
+            const unsigned long long c = ((unsigned long long)key[r][u] << 32) | (unsigned)lb;
+            best_r[r] = c < best_r[r] ? c : best_r[r];
+            if (selected(key[r][u], (uint32_t)((la0 + r) * nB + lb))) best_sel_r[r] = c < best_sel_r[r] ? c : best_sel_r[r];
+          }
         }
       }
     }
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      const unsigned long long ob = __shfl_xor(best, o, 64), os = __shfl_xor(best_sel, o, 64);
-      best = ob < best ? ob : best;
-      best_sel = os < best_sel ? os : best_sel;
-    }
-    if (lane == 0) {
-      const int sel_c = best_sel == ~0ull ? -1 : (int)(best_sel & 0xffffffffu);
-      selcol[la] = sel_c < 0 ? (uint16_t)0xffffu : (uint16_t)sel_c;
-      const int a_tok = tok[2 * la];
-      if (a_tok >= 0) {
-        const uint32_t bk = (uint32_t)(best >> 32);
-        const uint32_t u = (bk & 0x80000000u) ? (bk & 0x7fffffffu) : ~bk;   // order key back to the float it came from
-        g.best_fd[a_tok] = __uint_as_float(u);
-        g.best_dst[a_tok] = tok[2 * (int)(best & 0xffffffffu) + 1];
-        q.dst[a_tok] = sel_c >= 0 ? tok[2 * sel_c + 1] : -1;
-        q.cnt[a_tok] = 0;
-        if (sel_c < 0) q.src_rank[a_tok] = 0;   // (a node that leaves gets its rank from the column pass below)
+    for (int r = 0; r < EB_ROWS; ++r) {
+      unsigned long long best = best_r[r], best_sel = best_sel_r[r];
+      const int la = la0 + r;
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) {
+        const unsigned long long ob = __shfl_xor(best, o, 64), os = __shfl_xor(best_sel, o, 64);
+        best = ob < best ? ob : best;
+        best_sel = os < best_sel ? os : best_sel;
+      }
+      if (lane == 0 && la < nA) {
+        const int sel_c = best_sel == ~0ull ? -1 : (int)(best_sel & 0xffffffffu);
+        selcol[la] = sel_c < 0 ? (uint16_t)0xffffu : (uint16_t)sel_c;
+        const int a_tok = tok[2 * la];
+        if (a_tok >= 0) {
+          const uint32_t bk = (uint32_t)(best >> 32);
+          const uint32_t u = (bk & 0x80000000u) ? (bk & 0x7fffffffu) : ~bk;   // order key back to the float it came from
+          g.best_fd[a_tok] = __uint_as_float(u);
+          g.best_dst[a_tok] = tok[2 * (int)(best & 0xffffffffu) + 1];
+          q.dst[a_tok] = sel_c >= 0 ? tok[2 * sel_c + 1] : -1;
+          q.cnt[a_tok] = 0;
+          if (sel_c < 0) q.src_rank[a_tok] = 0;   // (a node that leaves gets its rank from the column pass below)
+        }
       }
     }
   }
@@ -543,12 +559,12 @@ __global__ __launch_bounds__(EB_THREADS) void edge_select_big_kernel(FdArgs g, E
   for (int lb = tid; lb < nB; lb += EB_THREADS) {
     const int b_tok = tok[2 * lb + 1];
     int pos = 0;
-    for (int la0 = 0; la0 < nA; la0 += 4) {
-      uint32_t key[4];
+    for (int la0 = 0; la0 < nA; la0 += EB_LOADS) {
+      uint32_t key[EB_LOADS];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { const int la = la0 + u; key[u] = M[(size_t)(la < nA ? la : nA - 1) * nB + lb]; }
+      for (int u = 0; u < EB_LOADS; ++u) { const int la = la0 + u; key[u] = M[(size_t)(la < nA ? la : nA - 1) * nB + lb]; }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < EB_LOADS; ++u) {
         const int la = la0 + u;
         if (la < nA && selected(key[u], (uint32_t)(la * nB + lb))) {
           const int a_tok = tok[2 * la];
